@@ -1,0 +1,182 @@
+"""Seeded synthetic inputs for the pooled decoder step.
+
+This module only *draws numbers*: decoder dimensions, random weights, random
+encoder outputs, request lengths, step counts and arrival times.  It contains
+none of the decoder's arithmetic and imports neither the HIP binding nor the
+CPU oracle, so both can be fed from it.
+
+The paper's own workload (a model trained on a Mandarin corpus, texts of three
+length classes with mean durations 2.64 / 4.08 / 7.00 / 4.54 s, Sec. 3.1) is
+not available; the workloads below stand in for it with the same shapes:
+encoder outputs of a few tens to a few hundred tokens and a few hundred mel
+frames per request.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import Dict, List, Optional
+
+import numpy as np
+
+# Tacotron-2 decoder dimensions ("same model parameters as the original",
+# Sec. 3.1); the concrete numbers are this build's workload definition.
+DIMS: Dict[str, int] = dict(
+    n_mel=80,
+    prenet_dim=256,
+    enc_dim=512,
+    att_rnn_dim=1024,
+    dec_rnn_dim=1024,
+    att_dim=128,
+    loc_filters=32,
+    loc_kernel=31,
+    loc_in_channels=2,
+)
+
+WEIGHT_SEED = 1234
+WEIGHT_STD = 0.05
+
+# Field order of the weight struct at the C boundary; tensors are drawn in
+# this order from one generator.
+WEIGHT_FIELDS = (
+    "prenet1", "prenet2",
+    "att_w_ih", "att_w_hh", "att_b",
+    "q_w", "mem_w", "loc_conv", "loc_w", "v",
+    "dec_w_ih", "dec_w_hh", "dec_b",
+    "mel_w", "mel_b", "stop_w", "stop_b",
+)
+
+
+def weight_shapes(dims: Dict[str, int] = DIMS) -> Dict[str, tuple]:
+    d = dims
+    att_in = d["prenet_dim"] + d["enc_dim"]
+    dec_in = d["att_rnn_dim"] + d["enc_dim"]
+    proj_in = d["dec_rnn_dim"] + d["enc_dim"]
+    return {
+        "prenet1": (d["prenet_dim"], d["n_mel"]),
+        "prenet2": (d["prenet_dim"], d["prenet_dim"]),
+        "att_w_ih": (4 * d["att_rnn_dim"], att_in),
+        "att_w_hh": (4 * d["att_rnn_dim"], d["att_rnn_dim"]),
+        "att_b": (4 * d["att_rnn_dim"],),
+        "q_w": (d["att_dim"], d["att_rnn_dim"]),
+        "mem_w": (d["att_dim"], d["enc_dim"]),
+        "loc_conv": (d["loc_filters"], d["loc_in_channels"], d["loc_kernel"]),
+        "loc_w": (d["att_dim"], d["loc_filters"]),
+        "v": (d["att_dim"],),
+        "dec_w_ih": (4 * d["dec_rnn_dim"], dec_in),
+        "dec_w_hh": (4 * d["dec_rnn_dim"], d["dec_rnn_dim"]),
+        "dec_b": (4 * d["dec_rnn_dim"],),
+        "mel_w": (d["n_mel"], proj_in),
+        "mel_b": (d["n_mel"],),
+        "stop_w": (1, proj_in),
+        "stop_b": (1,),
+    }
+
+
+def round_to_bf16(x: np.ndarray) -> np.ndarray:
+    """Round fp32 values to the nearest bfloat16 (ties to even); result is fp32."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    bits = x.view(np.uint32).astype(np.uint64)
+    lsb = (bits >> 16) & 1
+    rounded = ((bits + 0x7FFF + lsb) >> 16) << 16
+    out = rounded.astype(np.uint32).view(np.float32)
+    # NaN/Inf are never drawn here; keep them unchanged if they appear.
+    bad = ~np.isfinite(x)
+    if bad.any():
+        out = out.copy()
+        out[bad] = x[bad]
+    return out.reshape(x.shape)
+
+
+def make_weights(seed: int = WEIGHT_SEED, dims: Dict[str, int] = DIMS,
+                 bf16: bool = False, std: float = WEIGHT_STD) -> Dict[str, np.ndarray]:
+    """Every tensor ~ N(0, std^2) in fp32, drawn in WEIGHT_FIELDS order.
+
+    With ``bf16`` the matrices are then rounded to bfloat16 values (still held
+    in fp32 arrays); the bias vectors stay fp32.
+    """
+    rng = np.random.default_rng(seed)
+    shapes = weight_shapes(dims)
+    w = {}
+    for name in WEIGHT_FIELDS:
+        t = (rng.standard_normal(shapes[name]) * std).astype(np.float32)
+        if bf16 and not name.endswith("_b"):
+            t = round_to_bf16(t)
+        w[name] = np.ascontiguousarray(t)
+    return w
+
+
+@dataclass
+class Workload:
+    """One synthetic job: per-request encoder lengths, step counts and outputs."""
+    name: str
+    bf16: bool
+    enc_len: np.ndarray            # [n] int32
+    n_steps: np.ndarray            # [n] int32
+    seed: int
+    arrival_s: Optional[np.ndarray] = None   # [n] float64, streaming load only
+    chunk_frames: int = 40
+    dims: Dict[str, int] = field(default_factory=lambda: dict(DIMS))
+    _enc_cache: Dict[int, np.ndarray] = field(default_factory=dict, repr=False)
+
+    @property
+    def n_requests(self) -> int:
+        return int(self.enc_len.shape[0])
+
+    def encoder_outputs(self, i: int) -> np.ndarray:
+        """F_enc of request i, [L_i, enc_dim] ~ N(0,1) fp32 (bf16 values if bf16)."""
+        if i not in self._enc_cache:
+            rng = np.random.default_rng([self.seed, 7919, int(i)])
+            f = rng.standard_normal((int(self.enc_len[i]), self.dims["enc_dim"])).astype(np.float32)
+            if self.bf16:
+                f = round_to_bf16(f)
+            self._enc_cache[i] = np.ascontiguousarray(f)
+        return self._enc_cache[i]
+
+    def drop_cache(self) -> None:
+        self._enc_cache.clear()
+
+
+def workload(name: str) -> Workload:
+    """The five workloads of this build.
+
+    c1  1 request, fp32, L = 20, 10 steps
+    c2  16 requests, fp32, L ~ U{20..100}, 200 steps each, all join at step 0
+    c3  64 requests, bf16, L ~ U{30..300}, steps ~ U{100..600}, pool shrinks
+    c4  256 requests, bf16, L ~ U{50..400}, 400 steps each
+    c5  Poisson arrivals at 100/s over 10 s, bf16, L ~ U{30..300}, steps = 4 L,
+        mel drained in 40-frame chunks
+    """
+    if name == "c1":
+        return Workload("c1", False, np.array([20], np.int32), np.array([10], np.int32), 101)
+    if name == "c2":
+        rng = np.random.default_rng(102)
+        L = rng.integers(20, 101, size=16).astype(np.int32)
+        return Workload("c2", False, L, np.full(16, 200, np.int32), 102)
+    if name == "c3":
+        rng = np.random.default_rng(103)
+        L = rng.integers(30, 301, size=64).astype(np.int32)
+        n = rng.integers(100, 601, size=64).astype(np.int32)
+        return Workload("c3", True, L, n, 103)
+    if name == "c4":
+        rng = np.random.default_rng(104)
+        L = rng.integers(50, 401, size=256).astype(np.int32)
+        return Workload("c4", True, L, np.full(256, 400, np.int32), 104)
+    if name == "c5":
+        rng = np.random.default_rng(105)
+        rate, horizon = 100.0, 10.0
+        gaps = rng.exponential(1.0 / rate, size=int(rate * horizon * 2))
+        t = np.cumsum(gaps)
+        t = t[t < horizon]
+        n = t.shape[0]
+        L = rng.integers(30, 301, size=n).astype(np.int32)
+        return Workload("c5", True, L, (4 * L).astype(np.int32), 105, arrival_s=t, chunk_frames=40)
+    raise KeyError(name)
+
+
+def small_workload(n_requests: int, lo: int, hi: int, steps_lo: int, steps_hi: int,
+                   seed: int, bf16: bool = False) -> Workload:
+    """A free-form job for tests: L ~ U{lo..hi}, steps ~ U{steps_lo..steps_hi}."""
+    rng = np.random.default_rng(seed)
+    L = rng.integers(lo, hi + 1, size=n_requests).astype(np.int32)
+    n = rng.integers(steps_lo, steps_hi + 1, size=n_requests).astype(np.int32)
+    return Workload(f"small{seed}", bf16, L, n, seed)
