@@ -1,0 +1,294 @@
+"""Thin ctypes binding of the C-ABI library declared in include/tts_pool.h.
+
+Argument marshalling only: every step of the decoder path runs in the HIP
+kernels of libtts_pool.so.  PyTorch is used for the device arena and the
+stream, nothing else.  If the library has not been built this module raises;
+there is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Dict, Optional, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libtts_pool.so")
+
+TTS_OK = 0
+TTS_E_INVAL, TTS_E_FULL, TTS_E_NOTFOUND, TTS_E_HIP, TTS_E_ARENA, TTS_E_UNSUPPORTED = -1, -2, -3, -4, -5, -6
+DTYPE_F32, DTYPE_BF16 = 0, 1
+STATE = dict(m=0, a=1, w_last=2, w_acc=3, h_att=4, c_att=5, h_dec=6, c_dec=7)
+
+_CFG_INT_FIELDS = ("n_mel", "prenet_dim", "enc_dim", "att_rnn_dim", "dec_rnn_dim", "att_dim",
+                   "loc_filters", "loc_kernel", "loc_in_channels",
+                   "max_pool", "max_enc_len", "max_steps", "chunk_frames",
+                   "weight_dtype", "memory_dtype", "use_graph")
+WEIGHT_FIELDS = ("prenet1", "prenet2", "att_w_ih", "att_w_hh", "att_b", "q_w", "mem_w", "loc_conv",
+                 "loc_w", "v", "dec_w_ih", "dec_w_hh", "dec_b", "mel_w", "mel_b", "stop_w", "stop_b")
+
+# every symbol include/tts_pool.h declares
+EXPORTS = (
+    "tts_pool_workspace_bytes", "tts_pool_create", "tts_pool_add_request", "tts_pool_step",
+    "tts_pool_step_n", "tts_pool_drain_chunk", "tts_pool_get_stop_logits", "tts_pool_retire",
+    "tts_pool_get_state", "tts_pool_set_state", "tts_pool_frames", "tts_pool_size", "tts_pool_n_active",
+    "tts_pool_sync", "tts_pool_timing", "tts_pool_elapsed_ms", "tts_pool_destroy", "tts_last_error",
+    "tts_book_create", "tts_book_add", "tts_book_step", "tts_book_drain", "tts_book_retire",
+    "tts_book_destroy",
+)
+
+_fp = C.POINTER(C.c_float)
+_ip = C.POINTER(C.c_int)
+_i64p = C.POINTER(C.c_int64)
+
+
+class TtsConfig(C.Structure):
+    _fields_ = [(n, C.c_int) for n in _CFG_INT_FIELDS] + [("stop_threshold", C.c_float)]
+
+
+class TtsWeights(C.Structure):
+    _fields_ = [(n, _fp) for n in WEIGHT_FIELDS]
+
+
+class TtsError(RuntimeError):
+    def __init__(self, code: int, text: str):
+        super().__init__(f"tts_pool error {code}: {text}")
+        self.code = code
+        self.text = text
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Load libtts_pool.so (built beforehand by paper_2211_13939_amd/build.py)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2211_13939_amd.build` "
+                           "(there is no fallback path)")
+    L = C.CDLL(LIB_PATH)
+    vp = C.c_void_p
+    L.tts_pool_workspace_bytes.restype = C.c_size_t
+    L.tts_pool_workspace_bytes.argtypes = [C.POINTER(TtsConfig)]
+    L.tts_pool_create.argtypes = [C.POINTER(TtsConfig), C.POINTER(TtsWeights), vp, C.c_size_t, vp, C.POINTER(vp)]
+    L.tts_pool_add_request.argtypes = [vp, vp, C.c_int, C.c_int, _i64p]
+    L.tts_pool_step.argtypes = [vp, _ip]
+    L.tts_pool_step_n.argtypes = [vp, C.c_int, _i64p]
+    L.tts_pool_drain_chunk.argtypes = [vp, C.c_int64, _fp, _ip, _ip]
+    L.tts_pool_get_stop_logits.argtypes = [vp, C.c_int64, C.c_int, C.c_int, _fp]
+    L.tts_pool_retire.argtypes = [vp, C.c_int64]
+    L.tts_pool_get_state.argtypes = [vp, C.c_int64, C.c_int, _fp, C.c_int, _ip]
+    L.tts_pool_set_state.argtypes = [vp, C.c_int64, C.c_int, _fp, C.c_int]
+    L.tts_pool_frames.argtypes = [vp, C.c_int64, _ip, _ip]
+    L.tts_pool_size.argtypes = [vp]
+    L.tts_pool_n_active.argtypes = [vp]
+    L.tts_pool_sync.argtypes = [vp]
+    L.tts_pool_timing.argtypes = [vp, C.c_int]
+    L.tts_pool_elapsed_ms.argtypes = [vp, _fp]
+    L.tts_pool_destroy.restype = None
+    L.tts_pool_destroy.argtypes = [vp]
+    L.tts_last_error.restype = C.c_char_p
+    L.tts_last_error.argtypes = []
+    L.tts_book_create.restype = vp
+    L.tts_book_create.argtypes = [C.c_int, C.c_int, C.c_int, C.c_int]
+    L.tts_book_add.argtypes = [vp, C.c_int, C.c_int, _i64p]
+    L.tts_book_step.argtypes = [vp, _i64p, _ip]
+    L.tts_book_drain.argtypes = [vp, C.c_int64, _ip, _ip, _ip]
+    L.tts_book_retire.argtypes = [vp, C.c_int64]
+    L.tts_book_destroy.restype = None
+    L.tts_book_destroy.argtypes = [vp]
+    _lib = L
+    return L
+
+
+def _check(rc: int) -> None:
+    if rc != TTS_OK:
+        raise TtsError(rc, lib().tts_last_error().decode("utf-8", "replace"))
+
+
+def make_config(dims: Dict[str, int], max_pool: int, max_enc_len: int, max_steps: int, chunk_frames: int = 40,
+                bf16: bool = False, memory_bf16: Optional[bool] = None, use_graph: bool = True,
+                stop_threshold: float = -1.0) -> TtsConfig:
+    if memory_bf16 is None:
+        memory_bf16 = bf16
+    c = TtsConfig()
+    for k, v in dims.items():
+        setattr(c, k, int(v))
+    c.max_pool, c.max_enc_len, c.max_steps, c.chunk_frames = int(max_pool), int(max_enc_len), int(max_steps), int(chunk_frames)
+    c.weight_dtype = DTYPE_BF16 if bf16 else DTYPE_F32
+    c.memory_dtype = DTYPE_BF16 if memory_bf16 else DTYPE_F32
+    c.use_graph = int(bool(use_graph))
+    c.stop_threshold = float(stop_threshold)
+    return c
+
+
+def workspace_bytes(cfg: TtsConfig) -> int:
+    return int(lib().tts_pool_workspace_bytes(C.byref(cfg)))
+
+
+class Pool:
+    """tts_pool_* calls on one pool; owns the torch arena and stream."""
+
+    def __init__(self, cfg: TtsConfig, weights: Dict[str, np.ndarray], device: str = "cuda:0"):
+        import torch
+        if not torch.cuda.is_available():
+            raise RuntimeError("no GPU visible: the decoder step has no CPU path")
+        self._torch = torch
+        self.cfg = cfg
+        self.device = torch.device(device)
+        nbytes = workspace_bytes(cfg)
+        if nbytes == 0:
+            _check(TTS_E_INVAL)
+        with torch.cuda.device(self.device):
+            self.arena = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+            self.stream = torch.cuda.Stream(device=self.device)
+        self._warr = {n: np.ascontiguousarray(weights[n], dtype=np.float32) for n in WEIGHT_FIELDS}
+        w = TtsWeights(*[self._warr[n].ctypes.data_as(_fp) for n in WEIGHT_FIELDS])
+        h = C.c_void_p()
+        with torch.cuda.device(self.device):
+            _check(lib().tts_pool_create(C.byref(cfg), C.byref(w), C.c_void_p(self.arena.data_ptr()), nbytes,
+                                         C.c_void_p(self.stream.cuda_stream), C.byref(h)))
+        self._h = h
+        self.n_mel = cfg.n_mel
+        self.chunk = cfg.chunk_frames
+
+    # -- the five pool calls
+    def add_request(self, enc_out, n_steps: int) -> int:
+        """enc_out: numpy fp32 [L, enc_dim] (host) or a torch CUDA fp32 tensor (device)."""
+        rid = C.c_int64()
+        if isinstance(enc_out, np.ndarray):
+            a = np.ascontiguousarray(enc_out, dtype=np.float32)
+            ptr, L = a.ctypes.data, a.shape[0]
+        else:
+            a = enc_out.contiguous()
+            assert a.is_cuda and a.dtype == self._torch.float32
+            ptr, L = a.data_ptr(), a.shape[0]
+        _check(lib().tts_pool_add_request(self._h, C.c_void_p(ptr), int(L), int(n_steps), C.byref(rid)))
+        return rid.value
+
+    def add_request_raw(self, ptr: int, L: int, n_steps: int) -> int:
+        rid = C.c_int64()
+        _check(lib().tts_pool_add_request(self._h, C.c_void_p(ptr), int(L), int(n_steps), C.byref(rid)))
+        return rid.value
+
+    def step(self) -> int:
+        n = C.c_int()
+        _check(lib().tts_pool_step(self._h, C.byref(n)))
+        return n.value
+
+    def step_n(self, n: int) -> int:
+        frames = C.c_int64()
+        _check(lib().tts_pool_step_n(self._h, int(n), C.byref(frames)))
+        return frames.value
+
+    def drain_chunk(self, rid: int) -> Tuple[np.ndarray, bool]:
+        buf = np.empty((self.chunk, self.n_mel), np.float32)
+        n, fin = C.c_int(), C.c_int()
+        _check(lib().tts_pool_drain_chunk(self._h, rid, buf.ctypes.data_as(_fp), C.byref(n), C.byref(fin)))
+        return buf[: n.value], bool(fin.value)
+
+    def retire(self, rid: int) -> None:
+        _check(lib().tts_pool_retire(self._h, rid))
+
+    # -- helpers
+    def stop_logits(self, rid: int, first: int, count: int) -> np.ndarray:
+        buf = np.empty(count, np.float32)
+        _check(lib().tts_pool_get_stop_logits(self._h, rid, first, count, buf.ctypes.data_as(_fp)))
+        return buf
+
+    def get_state(self, rid: int, name: str) -> np.ndarray:
+        buf = np.empty(max(self.cfg.max_enc_len, 1024), np.float32)
+        n = C.c_int()
+        _check(lib().tts_pool_get_state(self._h, rid, STATE[name], buf.ctypes.data_as(_fp), buf.shape[0], C.byref(n)))
+        return buf[: n.value].copy()
+
+    def set_state(self, rid: int, name: str, value) -> None:
+        v = np.ascontiguousarray(value, np.float32).ravel()
+        _check(lib().tts_pool_set_state(self._h, rid, STATE[name], v.ctypes.data_as(_fp), v.shape[0]))
+
+    def frames(self, rid: int) -> Tuple[int, bool]:
+        n, fin = C.c_int(), C.c_int()
+        _check(lib().tts_pool_frames(self._h, rid, C.byref(n), C.byref(fin)))
+        return n.value, bool(fin.value)
+
+    def size(self) -> int:
+        return lib().tts_pool_size(self._h)
+
+    def n_active(self) -> int:
+        return lib().tts_pool_n_active(self._h)
+
+    def sync(self) -> None:
+        _check(lib().tts_pool_sync(self._h))
+
+    def timing(self, on: bool) -> None:
+        _check(lib().tts_pool_timing(self._h, int(on)))
+
+    def elapsed_ms(self) -> float:
+        ms = C.c_float()
+        _check(lib().tts_pool_elapsed_ms(self._h, C.byref(ms)))
+        return ms.value
+
+    def drain_all(self, rid: int) -> np.ndarray:
+        """Every remaining frame of a finished request (host convenience loop over drain_chunk)."""
+        out = []
+        while True:
+            chunk, fin = self.drain_chunk(rid)
+            if chunk.shape[0]:
+                out.append(chunk.copy())
+            if fin or chunk.shape[0] == 0:
+                break
+        return np.concatenate(out, axis=0) if out else np.zeros((0, self.n_mel), np.float32)
+
+    def close(self) -> None:
+        if getattr(self, "_h", None):
+            lib().tts_pool_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class Book:
+    """Host-only bookkeeping model (tts_book_*): pooling semantics without a device."""
+
+    def __init__(self, max_pool: int, max_enc_len: int, max_steps: int, chunk_frames: int):
+        self._h = lib().tts_book_create(max_pool, max_enc_len, max_steps, chunk_frames)
+        if not self._h:
+            raise ValueError("tts_book_create rejected its arguments")
+        self.max_pool = max_pool
+
+    def add(self, L: int, n_steps: int) -> int:
+        rid = C.c_int64()
+        _check(lib().tts_book_add(self._h, L, n_steps, C.byref(rid)))
+        return rid.value
+
+    def step(self):
+        ids = (C.c_int64 * self.max_pool)()
+        n = C.c_int()
+        _check(lib().tts_book_step(self._h, ids, C.byref(n)))
+        return [ids[i] for i in range(n.value)]
+
+    def drain(self, rid: int):
+        first, n, fin = C.c_int(), C.c_int(), C.c_int()
+        _check(lib().tts_book_drain(self._h, rid, C.byref(first), C.byref(n), C.byref(fin)))
+        return first.value, n.value, bool(fin.value)
+
+    def retire(self, rid: int) -> None:
+        _check(lib().tts_book_retire(self._h, rid))
+
+    def close(self):
+        if self._h:
+            lib().tts_book_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

@@ -1,0 +1,25 @@
+// Launch wrappers of the decoder-step kernels (definitions in kernels.hip).
+#pragma once
+#include "dev.h"
+
+namespace tts {
+
+// dtype codes as in the public header: 0 = fp32, 1 = bf16
+struct StepLaunch {
+    int wdtype;     // weights / activations
+    int mdtype;     // encoder memory
+    int n_blocks;   // per-request grids are launched with this many blocks (>= n_active)
+};
+
+// One decoder step (paper Eq. 2) for every request listed in d.table.
+// `cur` selects which half of the double-buffered activations is read.
+hipError_t launch_step(const DevPtrs& d, const StepLaunch& cfg, int cur, hipStream_t s);
+
+hipError_t launch_set_table(const DevPtrs& d, const TableArgs& args, hipStream_t s);
+hipError_t launch_slot_init(const DevPtrs& d, int wdtype, int slot, int L, int n_steps, hipStream_t s);
+// F_enc (fp32, device) -> slot memory, and processed memory PM = F W_mem^T
+hipError_t launch_join_memory(const DevPtrs& d, int mdtype, const float* F_dev, int slot, int L, hipStream_t s);
+// p = Pre(m_last) into both activation buffers of one slot (after a state overwrite)
+hipError_t launch_prenet_slot(const DevPtrs& d, int wdtype, int slot, hipStream_t s);
+
+}  // namespace tts

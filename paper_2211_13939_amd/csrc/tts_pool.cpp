@@ -1,0 +1,708 @@
+// Host side of the tts_pool C ABI: argument checks, arena carve-up, weight
+// re-layout, pool bookkeeping, kernel / graph launches.  All arithmetic of the
+// decoder step lives in kernels.hip.
+#include "../../include/tts_pool.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <map>
+#include <memory>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "book.h"
+#include "dev.h"
+#include "kernels.h"
+
+using namespace tts;
+
+// ------------------------------------------------------------------ errors
+static thread_local std::string g_err;
+
+static int fail(int code, const char* fmt, ...)
+{
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    g_err = buf;
+    return code;
+}
+
+#define HIP_TRY(expr)                                                                         \
+    do {                                                                                      \
+        hipError_t e_ = (expr);                                                               \
+        if (e_ != hipSuccess) return fail(TTS_E_HIP, "%s: %s", #expr, hipGetErrorString(e_)); \
+    } while (0)
+
+extern "C" const char* tts_last_error(void) { return g_err.c_str(); }
+
+// ------------------------------------------------------------------ config
+static int check_config(const tts_config* c)
+{
+    if (!c) return fail(TTS_E_INVAL, "config is null");
+    if (c->n_mel != N_MEL || c->prenet_dim != PRENET || c->enc_dim != ENC || c->att_rnn_dim != HID ||
+        c->dec_rnn_dim != HID || c->att_dim != ATT || c->loc_filters != LOC_F || c->loc_kernel != LOC_K ||
+        (c->loc_in_channels != 1 && c->loc_in_channels != 2))
+        return fail(TTS_E_UNSUPPORTED,
+                    "kernels are built for dims 80/256/512/1024/1024/128, 32 filters, kernel 31, 1 or 2 channels");
+    if (c->max_pool < 1 || c->max_pool > MAX_POOL) return fail(TTS_E_INVAL, "max_pool must be in 1..%d", MAX_POOL);
+    if (c->max_enc_len < 1 || c->max_enc_len > MAX_ENC_LEN)
+        return fail(TTS_E_INVAL, "max_enc_len must be in 1..%d", MAX_ENC_LEN);
+    if (c->max_steps < 1 || c->max_steps > (1 << 20)) return fail(TTS_E_INVAL, "max_steps must be in 1..2^20");
+    if (c->chunk_frames < 1) return fail(TTS_E_INVAL, "chunk_frames must be >= 1");
+    if (c->weight_dtype != TTS_DTYPE_F32 && c->weight_dtype != TTS_DTYPE_BF16)
+        return fail(TTS_E_INVAL, "weight_dtype must be 0 (fp32) or 1 (bf16)");
+    if (c->memory_dtype != TTS_DTYPE_F32 && c->memory_dtype != TTS_DTYPE_BF16)
+        return fail(TTS_E_INVAL, "memory_dtype must be 0 (fp32) or 1 (bf16)");
+    if (c->memory_dtype == TTS_DTYPE_BF16 && c->weight_dtype != TTS_DTYPE_BF16)
+        return fail(TTS_E_INVAL, "bf16 memory requires bf16 weights");
+    return TTS_OK;
+}
+
+// ------------------------------------------------------------------ arena
+namespace {
+
+struct Carver {
+    size_t off = 0;
+    size_t take(size_t bytes)
+    {
+        size_t o = off;
+        off += (bytes + 255) & ~size_t(255);
+        return o;
+    }
+};
+
+struct Layout {
+    size_t Wa, Wd, ba, bd, Wq, WmemT, KcT, Wloc, v, Wmel, bmel, Wp1T, Wp2T;
+    size_t xatt[2], xdec[2], c_att, c_dec, m_last, w_last, w_acc, Fmem, PM, mel_ring, stop_ring;
+    size_t L, t, n_steps, done, table, stage;
+    size_t total;
+};
+
+Layout make_layout(const tts_config& c)
+{
+    const size_t ws = c.weight_dtype == TTS_DTYPE_BF16 ? 2 : 4;
+    const size_t ms = c.memory_dtype == TTS_DTYPE_BF16 ? 2 : 4;
+    const size_t S = c.max_pool, ML = c.max_enc_len;
+    Carver a;
+    Layout l;
+    l.Wa = a.take((size_t)4 * HID * K_ATT * ws);
+    l.Wd = a.take((size_t)4 * HID * K_DEC * ws);
+    l.ba = a.take((size_t)4 * HID * 4);
+    l.bd = a.take((size_t)4 * HID * 4);
+    l.Wq = a.take((size_t)ATT * HID * ws);
+    l.WmemT = a.take((size_t)ENC * ATT * 4);
+    l.KcT = a.take((size_t)2 * LOC_K * LOC_F * 4);
+    l.Wloc = a.take((size_t)ATT * LOC_F * 4);
+    l.v = a.take((size_t)ATT * 4);
+    l.Wmel = a.take((size_t)N_PROJ * K_PROJ * ws);
+    l.bmel = a.take((size_t)N_PROJ * 4);
+    l.Wp1T = a.take((size_t)N_MEL * PRENET * ws);
+    l.Wp2T = a.take((size_t)PRENET * PRENET * ws);
+    for (int b = 0; b < 2; ++b) {
+        l.xatt[b] = a.take(S * K_ATT * ws);
+        l.xdec[b] = a.take(S * K_DEC * ws);
+    }
+    l.c_att = a.take(S * HID * 4);
+    l.c_dec = a.take(S * HID * 4);
+    l.m_last = a.take(S * N_MEL * 4);
+    l.w_last = a.take(S * ML * 4);
+    l.w_acc = a.take(S * ML * 4);
+    l.Fmem = a.take(S * ML * ENC * ms);
+    l.PM = a.take(S * ML * ATT * ms);
+    l.mel_ring = a.take(S * (size_t)c.max_steps * N_MEL * 4);
+    l.stop_ring = a.take(S * (size_t)c.max_steps * 4);
+    l.L = a.take(S * 4);
+    l.t = a.take(S * 4);
+    l.n_steps = a.take(S * 4);
+    l.done = a.take(S * 4);
+    l.table = a.take((TABLE_HDR + MAX_POOL) * 4);
+    l.stage = a.take(ML * ENC * 4);
+    l.total = a.off;
+    return l;
+}
+
+uint16_t host_f2bf(float f)
+{
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+float host_bf2f(uint16_t b)
+{
+    uint32_t u = (uint32_t)b << 16;
+    float f;
+    memcpy(&f, &u, 4);
+    return f;
+}
+
+// fp32 host values -> device array of the weight dtype
+int upload(void* dst, const std::vector<float>& src, bool bf16)
+{
+    if (!bf16) {
+        HIP_TRY(hipMemcpy(dst, src.data(), src.size() * 4, hipMemcpyHostToDevice));
+    } else {
+        std::vector<uint16_t> h(src.size());
+        for (size_t i = 0; i < src.size(); ++i) h[i] = host_f2bf(src[i]);
+        HIP_TRY(hipMemcpy(dst, h.data(), h.size() * 2, hipMemcpyHostToDevice));
+    }
+    return TTS_OK;
+}
+
+// Gate matrix [W_ih | W_hh] (rows i,f,g,o blocks of HID) -> MFMA fragment order:
+// rows re-ordered unit-major/gate-minor, tiles of 16 rows x (64 bytes of k);
+// within a tile lane l holds row l%16, 16 bytes at byte offset 16*(l/16).
+std::vector<float> gate_fragments(const float* w_ih, int in_dim, const float* w_hh, bool bf16)
+{
+    const int K = in_dim + HID;
+    const int KB = bf16 ? 32 : 16;   // k elements per 64-byte fragment row
+    const int EPL = KB / 4;          // elements per lane
+    const int NK = K / KB;
+    std::vector<float> out((size_t)4 * HID * K);
+    for (int rt = 0; rt < HID / 4; ++rt)
+        for (int ks = 0; ks < NK; ++ks)
+            for (int lane = 0; lane < 64; ++lane) {
+                const int r = rt * 16 + (lane & 15);      // re-ordered row
+                const int unit = r >> 2, gate = r & 3;
+                const int src_row = gate * HID + unit;
+                for (int i = 0; i < EPL; ++i) {
+                    const int k = ks * KB + (lane >> 4) * EPL + i;
+                    const float val = k < in_dim ? w_ih[(size_t)src_row * in_dim + k]
+                                                 : w_hh[(size_t)src_row * HID + (k - in_dim)];
+                    out[(((size_t)rt * NK + ks) * 64 + lane) * EPL + i] = val;
+                }
+            }
+    return out;
+}
+
+}  // namespace
+
+extern "C" size_t tts_pool_workspace_bytes(const tts_config* cfg)
+{
+    if (check_config(cfg) != TTS_OK) return 0;
+    return make_layout(*cfg).total;
+}
+
+// ------------------------------------------------------------------ pool
+struct tts_pool {
+    tts_config cfg;
+    DevPtrs d;
+    hipStream_t stream = nullptr;
+    std::unique_ptr<PoolBook> book;
+    int parity = 0;               // activation buffer half the next step reads
+    bool stop_enabled = false;
+    bool timing = false;
+    hipEvent_t ev0 = nullptr, ev1 = nullptr;
+    bool ev_valid = false;
+    std::map<int, hipGraphExec_t> graphs;   // key = bucket * 2 + parity
+    std::vector<hipGraph_t> graph_defs;
+};
+
+static int upload_weights(tts_pool* p, const tts_weights* w, char* base, const Layout& l)
+{
+    const bool bf = p->cfg.weight_dtype == TTS_DTYPE_BF16;
+    const int C = p->cfg.loc_in_channels;
+    int rc;
+    // LSTM gate matrices: attention LSTM sees [Pre(M_last); A] then H_att, decoder LSTM [H_att; A] then H_dec
+    if ((rc = upload(base + l.Wa, gate_fragments(w->att_w_ih, PRENET + ENC, w->att_w_hh, bf), bf))) return rc;
+    if ((rc = upload(base + l.Wd, gate_fragments(w->dec_w_ih, HID + ENC, w->dec_w_hh, bf), bf))) return rc;
+    std::vector<float> ba(4 * HID), bd(4 * HID);
+    for (int u = 0; u < HID; ++u)
+        for (int g = 0; g < 4; ++g) {
+            ba[u * 4 + g] = w->att_b[g * HID + u];
+            bd[u * 4 + g] = w->dec_b[g * HID + u];
+        }
+    if ((rc = upload(base + l.ba, ba, false))) return rc;
+    if ((rc = upload(base + l.bd, bd, false))) return rc;
+    if ((rc = upload(base + l.Wq, std::vector<float>(w->q_w, w->q_w + ATT * HID), bf))) return rc;
+    std::vector<float> memT((size_t)ENC * ATT);
+    for (int a = 0; a < ATT; ++a)
+        for (int k = 0; k < ENC; ++k) memT[(size_t)k * ATT + a] = w->mem_w[(size_t)a * ENC + k];
+    if ((rc = upload(base + l.WmemT, memT, false))) return rc;
+    // location filters [f][c][k] -> [c'][k][f] with c' = 0 for W_last, 1 for W_acc;
+    // a one-channel model convolves W_acc only
+    std::vector<float> kc((size_t)2 * LOC_K * LOC_F, 0.f);
+    for (int f = 0; f < LOC_F; ++f)
+        for (int c = 0; c < C; ++c)
+            for (int k = 0; k < LOC_K; ++k) {
+                const int cd = (C == 2) ? c : 1;
+                kc[((size_t)cd * LOC_K + k) * LOC_F + f] = w->loc_conv[((size_t)f * C + c) * LOC_K + k];
+            }
+    if ((rc = upload(base + l.KcT, kc, false))) return rc;
+    if ((rc = upload(base + l.Wloc, std::vector<float>(w->loc_w, w->loc_w + ATT * LOC_F), false))) return rc;
+    if ((rc = upload(base + l.v, std::vector<float>(w->v, w->v + ATT), false))) return rc;
+    std::vector<float> proj((size_t)N_PROJ * K_PROJ), bproj(N_PROJ);
+    memcpy(proj.data(), w->mel_w, (size_t)N_MEL * K_PROJ * 4);
+    memcpy(proj.data() + (size_t)N_MEL * K_PROJ, w->stop_w, (size_t)K_PROJ * 4);
+    memcpy(bproj.data(), w->mel_b, N_MEL * 4);
+    bproj[N_MEL] = w->stop_b[0];
+    if ((rc = upload(base + l.Wmel, proj, bf))) return rc;
+    if ((rc = upload(base + l.bmel, bproj, false))) return rc;
+    std::vector<float> p1T((size_t)N_MEL * PRENET), p2T((size_t)PRENET * PRENET);
+    for (int o = 0; o < PRENET; ++o) {
+        for (int k = 0; k < N_MEL; ++k) p1T[(size_t)k * PRENET + o] = w->prenet1[(size_t)o * N_MEL + k];
+        for (int k = 0; k < PRENET; ++k) p2T[(size_t)k * PRENET + o] = w->prenet2[(size_t)o * PRENET + k];
+    }
+    if ((rc = upload(base + l.Wp1T, p1T, bf))) return rc;
+    if ((rc = upload(base + l.Wp2T, p2T, bf))) return rc;
+    return TTS_OK;
+}
+
+extern "C" int tts_pool_create(const tts_config* cfg, const tts_weights* w, void* dev_arena, size_t arena_bytes,
+                               void* hip_stream, tts_pool** out)
+{
+    int rc = check_config(cfg);
+    if (rc) return rc;
+    if (!w || !out) return fail(TTS_E_INVAL, "weights / out is null");
+    const float* const* wp = reinterpret_cast<const float* const*>(w);
+    for (size_t i = 0; i < sizeof(tts_weights) / sizeof(float*); ++i)
+        if (!wp[i]) return fail(TTS_E_INVAL, "weight tensor %zu is null", i);
+    const Layout l = make_layout(*cfg);
+    if (!dev_arena || ((uintptr_t)dev_arena & 255)) return fail(TTS_E_ARENA, "arena is null or not 256-byte aligned");
+    if (arena_bytes < l.total) return fail(TTS_E_ARENA, "arena has %zu bytes, %zu needed", arena_bytes, l.total);
+    if (cfg->use_graph && !hip_stream)
+        return fail(TTS_E_INVAL, "graph capture needs a stream other than the default (null) stream");
+    hipPointerAttribute_t attr;
+    if (hipPointerGetAttributes(&attr, dev_arena) != hipSuccess || attr.type != hipMemoryTypeDevice) {
+        (void)hipGetLastError();
+        return fail(TTS_E_ARENA, "arena is not device memory");
+    }
+
+    tts_pool* p = new (std::nothrow) tts_pool();
+    if (!p) return fail(TTS_E_INVAL, "out of host memory");
+    p->cfg = *cfg;
+    p->stream = (hipStream_t)hip_stream;
+    p->stop_enabled = cfg->stop_threshold >= 0.f && cfg->stop_threshold <= 1.f;
+    p->book.reset(new PoolBook(cfg->max_pool, cfg->max_enc_len, cfg->max_steps, cfg->chunk_frames));
+
+    char* base = (char*)dev_arena;
+    DevPtrs& d = p->d;
+    d.Wa = (const uint4*)(base + l.Wa);
+    d.Wd = (const uint4*)(base + l.Wd);
+    d.ba = (const float*)(base + l.ba);
+    d.bd = (const float*)(base + l.bd);
+    d.Wq = base + l.Wq;
+    d.WmemT = (const float*)(base + l.WmemT);
+    d.KcT = (const float*)(base + l.KcT);
+    d.Wloc = (const float*)(base + l.Wloc);
+    d.v = (const float*)(base + l.v);
+    d.Wmel = base + l.Wmel;
+    d.bmel = (const float*)(base + l.bmel);
+    d.Wp1T = base + l.Wp1T;
+    d.Wp2T = base + l.Wp2T;
+    for (int b = 0; b < 2; ++b) {
+        d.xatt[b] = base + l.xatt[b];
+        d.xdec[b] = base + l.xdec[b];
+    }
+    d.c_att = (float*)(base + l.c_att);
+    d.c_dec = (float*)(base + l.c_dec);
+    d.m_last = (float*)(base + l.m_last);
+    d.w_last = (float*)(base + l.w_last);
+    d.w_acc = (float*)(base + l.w_acc);
+    d.Fmem = base + l.Fmem;
+    d.PM = base + l.PM;
+    d.mel_ring = (float*)(base + l.mel_ring);
+    d.stop_ring = (float*)(base + l.stop_ring);
+    d.L = (int*)(base + l.L);
+    d.t = (int*)(base + l.t);
+    d.n_steps = (int*)(base + l.n_steps);
+    d.done = (int*)(base + l.done);
+    d.table = (int*)(base + l.table);
+    d.stage = (float*)(base + l.stage);
+    d.max_enc_len = cfg->max_enc_len;
+    d.max_steps = cfg->max_steps;
+    d.stop_threshold = p->stop_enabled ? cfg->stop_threshold : -1.f;
+
+    rc = upload_weights(p, w, base, l);
+    if (rc == TTS_OK) {
+        // slot counters and the table start defined: nothing active, everything "done"
+        hipError_t e = hipMemset(base + l.L, 0, l.stage - l.L);
+        if (e == hipSuccess) e = hipEventCreate(&p->ev0);
+        if (e == hipSuccess) e = hipEventCreate(&p->ev1);
+        if (e == hipSuccess) e = hipDeviceSynchronize();
+        if (e != hipSuccess) rc = fail(TTS_E_HIP, "pool setup: %s", hipGetErrorString(e));
+    }
+    if (rc) {
+        tts_pool_destroy(p);
+        return rc;
+    }
+    *out = p;
+    return TTS_OK;
+}
+
+extern "C" void tts_pool_destroy(tts_pool* p)
+{
+    if (!p) return;
+    (void)hipStreamSynchronize(p->stream);
+    for (auto& kv : p->graphs) (void)hipGraphExecDestroy(kv.second);
+    for (auto g : p->graph_defs) (void)hipGraphDestroy(g);
+    if (p->ev0) (void)hipEventDestroy(p->ev0);
+    if (p->ev1) (void)hipEventDestroy(p->ev1);
+    delete p;
+}
+
+extern "C" int tts_pool_add_request(tts_pool* p, const float* enc_out, int L, int n_steps, int64_t* out_id)
+{
+    if (!p || !enc_out || !out_id) return fail(TTS_E_INVAL, "null argument");
+    if (L < 1 || L > p->cfg.max_enc_len) return fail(TTS_E_INVAL, "L = %d outside 1..%d", L, p->cfg.max_enc_len);
+    if (n_steps < 1 || n_steps > p->cfg.max_steps)
+        return fail(TTS_E_INVAL, "n_steps = %d outside 1..%d", n_steps, p->cfg.max_steps);
+    if (p->book->size() >= p->cfg.max_pool) return fail(TTS_E_FULL, "pool holds max_pool = %d requests", p->cfg.max_pool);
+
+    hipPointerAttribute_t attr;
+    bool on_device = false;
+    if (hipPointerGetAttributes(&attr, enc_out) == hipSuccess) on_device = attr.type == hipMemoryTypeDevice;
+    else (void)hipGetLastError();
+
+    const float* F_dev = enc_out;
+    if (!on_device) {
+        // the caller may free a host buffer on return: finish the copy before returning
+        HIP_TRY(hipMemcpyAsync(p->d.stage, enc_out, (size_t)L * ENC * 4, hipMemcpyHostToDevice, p->stream));
+        HIP_TRY(hipStreamSynchronize(p->stream));
+        F_dev = p->d.stage;
+    }
+    int64_t id;
+    int slot;
+    int rc = p->book->add(L, n_steps, &id, &slot);
+    if (rc) return fail(rc == -2 ? TTS_E_FULL : TTS_E_INVAL, "request rejected");
+    HIP_TRY(launch_slot_init(p->d, p->cfg.weight_dtype, slot, L, n_steps, p->stream));
+    HIP_TRY(launch_join_memory(p->d, p->cfg.memory_dtype, F_dev, slot, L, p->stream));
+    *out_id = id;
+    return TTS_OK;
+}
+
+static int bucket_for(int n)
+{
+    int b = 1;
+    while (b < n) b <<= 1;
+    return b;
+}
+
+static int push_table(tts_pool* p)
+{
+    if (!p->book->dirty()) return TTS_OK;
+    TableArgs a;
+    const std::vector<int>& act = p->book->active();
+    a.n_active = (int)act.size();
+    for (size_t i = 0; i < act.size(); ++i) a.slot[i] = (uint16_t)act[i];
+    HIP_TRY(launch_set_table(p->d, a, p->stream));
+    p->book->clear_dirty();
+    return TTS_OK;
+}
+
+static int launch_one_step(tts_pool* p, int n_active)
+{
+    StepLaunch sl;
+    sl.wdtype = p->cfg.weight_dtype;
+    sl.mdtype = p->cfg.memory_dtype;
+    if (!p->cfg.use_graph) {
+        sl.n_blocks = n_active;
+        HIP_TRY(launch_step(p->d, sl, p->parity, p->stream));
+        return TTS_OK;
+    }
+    const int bucket = bucket_for(n_active);
+    const int key = bucket * 2 + p->parity;
+    auto it = p->graphs.find(key);
+    if (it == p->graphs.end()) {
+        sl.n_blocks = bucket;
+        hipGraph_t g = nullptr;
+        hipGraphExec_t ge = nullptr;
+        HIP_TRY(hipStreamBeginCapture(p->stream, hipStreamCaptureModeThreadLocal));
+        hipError_t le = launch_step(p->d, sl, p->parity, p->stream);
+        hipError_t ce = hipStreamEndCapture(p->stream, &g);
+        if (le != hipSuccess) return fail(TTS_E_HIP, "capture of the step failed: %s", hipGetErrorString(le));
+        if (ce != hipSuccess) return fail(TTS_E_HIP, "hipStreamEndCapture: %s", hipGetErrorString(ce));
+        HIP_TRY(hipGraphInstantiate(&ge, g, nullptr, nullptr, 0));
+        p->graph_defs.push_back(g);
+        it = p->graphs.emplace(key, ge).first;
+    }
+    HIP_TRY(hipGraphLaunch(it->second, p->stream));
+    return TTS_OK;
+}
+
+static int step_impl(tts_pool* p, int n, int64_t* out_frames, int* out_last_active)
+{
+    int64_t frames = 0;
+    int last = 0;
+    if (p->timing) HIP_TRY(hipEventRecord(p->ev0, p->stream));
+    for (int i = 0; i < n; ++i) {
+        const int n_active = (int)p->book->active().size();
+        last = n_active;
+        if (n_active == 0) break;
+        int rc = push_table(p);
+        if (rc) return rc;
+        rc = launch_one_step(p, n_active);
+        if (rc) return rc;
+        p->parity ^= 1;
+        p->book->step(p->parity);
+        frames += n_active;
+    }
+    if (p->timing) {
+        HIP_TRY(hipEventRecord(p->ev1, p->stream));
+        p->ev_valid = true;
+    }
+    if (out_frames) *out_frames = frames;
+    if (out_last_active) *out_last_active = last;
+    return TTS_OK;
+}
+
+extern "C" int tts_pool_step(tts_pool* p, int* out_n_active)
+{
+    if (!p) return fail(TTS_E_INVAL, "pool is null");
+    return step_impl(p, 1, nullptr, out_n_active);
+}
+
+extern "C" int tts_pool_step_n(tts_pool* p, int n, int64_t* out_frames)
+{
+    if (!p || n < 0) return fail(TTS_E_INVAL, "bad argument");
+    return step_impl(p, n, out_frames, nullptr);
+}
+
+// with a stop threshold the device may have ended a request before its cap
+static int refresh_slot(tts_pool* p, int slot)
+{
+    if (!p->stop_enabled) return TTS_OK;
+    int td[2] = {0, 0};
+    HIP_TRY(hipMemcpyAsync(&td[0], p->d.t + slot, 4, hipMemcpyDeviceToHost, p->stream));
+    HIP_TRY(hipMemcpyAsync(&td[1], p->d.done + slot, 4, hipMemcpyDeviceToHost, p->stream));
+    HIP_TRY(hipStreamSynchronize(p->stream));
+    if (td[1] && td[0] <= p->book->slot(slot).t) p->book->finish_early(slot, td[0]);
+    return TTS_OK;
+}
+
+extern "C" int tts_pool_drain_chunk(tts_pool* p, int64_t id, float* dst, int* out_frames, int* out_finished)
+{
+    if (!p || !dst || !out_frames || !out_finished) return fail(TTS_E_INVAL, "null argument");
+    const int slot = p->book->find(id);
+    if (slot < 0) return fail(TTS_E_NOTFOUND, "no request with id %lld", (long long)id);
+    int rc = refresh_slot(p, slot);
+    if (rc) return rc;
+    int first, count, fin;
+    p->book->drain_plan(slot, &first, &count, &fin);
+    if (count > 0) {
+        const float* src = p->d.mel_ring + ((size_t)slot * p->cfg.max_steps + first) * N_MEL;
+        HIP_TRY(hipMemcpyAsync(dst, src, (size_t)count * N_MEL * 4, hipMemcpyDeviceToHost, p->stream));
+        HIP_TRY(hipStreamSynchronize(p->stream));
+        p->book->drain_commit(slot, count);
+    }
+    *out_frames = count;
+    *out_finished = fin;
+    return TTS_OK;
+}
+
+extern "C" int tts_pool_get_stop_logits(tts_pool* p, int64_t id, int first, int count, float* dst)
+{
+    if (!p || !dst) return fail(TTS_E_INVAL, "null argument");
+    const int slot = p->book->find(id);
+    if (slot < 0) return fail(TTS_E_NOTFOUND, "no request with id %lld", (long long)id);
+    int rc = refresh_slot(p, slot);
+    if (rc) return rc;
+    if (first < 0 || count < 0 || first + count > p->book->slot(slot).t)
+        return fail(TTS_E_INVAL, "frames [%d, %d) not produced yet", first, first + count);
+    if (count == 0) return TTS_OK;
+    HIP_TRY(hipMemcpyAsync(dst, p->d.stop_ring + (size_t)slot * p->cfg.max_steps + first, (size_t)count * 4,
+                           hipMemcpyDeviceToHost, p->stream));
+    HIP_TRY(hipStreamSynchronize(p->stream));
+    return TTS_OK;
+}
+
+extern "C" int tts_pool_retire(tts_pool* p, int64_t id)
+{
+    if (!p) return fail(TTS_E_INVAL, "pool is null");
+    if (p->book->retire(id)) return fail(TTS_E_NOTFOUND, "no request with id %lld", (long long)id);
+    return TTS_OK;
+}
+
+extern "C" int tts_pool_frames(tts_pool* p, int64_t id, int* out_frames, int* out_finished)
+{
+    if (!p) return fail(TTS_E_INVAL, "pool is null");
+    const int slot = p->book->find(id);
+    if (slot < 0) return fail(TTS_E_NOTFOUND, "no request with id %lld", (long long)id);
+    int rc = refresh_slot(p, slot);
+    if (rc) return rc;
+    if (out_frames) *out_frames = p->book->slot(slot).t;
+    if (out_finished) *out_finished = p->book->slot(slot).state == SlotState::Finished;
+    return TTS_OK;
+}
+
+extern "C" int tts_pool_size(const tts_pool* p) { return p ? p->book->size() : 0; }
+extern "C" int tts_pool_n_active(const tts_pool* p) { return p ? (int)p->book->active().size() : 0; }
+
+extern "C" int tts_pool_sync(tts_pool* p)
+{
+    if (!p) return fail(TTS_E_INVAL, "pool is null");
+    HIP_TRY(hipStreamSynchronize(p->stream));
+    return TTS_OK;
+}
+
+extern "C" int tts_pool_timing(tts_pool* p, int enable)
+{
+    if (!p) return fail(TTS_E_INVAL, "pool is null");
+    p->timing = enable != 0;
+    p->ev_valid = false;
+    return TTS_OK;
+}
+
+extern "C" int tts_pool_elapsed_ms(tts_pool* p, float* out_ms)
+{
+    if (!p || !out_ms) return fail(TTS_E_INVAL, "null argument");
+    if (!p->ev_valid) return fail(TTS_E_INVAL, "no timed step yet (enable tts_pool_timing first)");
+    HIP_TRY(hipEventSynchronize(p->ev1));
+    HIP_TRY(hipEventElapsedTime(out_ms, p->ev0, p->ev1));
+    return TTS_OK;
+}
+
+// ------------------------------------------------------------------ state access
+namespace {
+struct StateLoc {
+    bool wt;           // stored in the weight/activation dtype (else fp32)
+    int n;
+    // up to 4 device locations holding a copy (all written on set, first read on get)
+    char* loc[4];
+    int n_loc;
+};
+}  // namespace
+
+static int locate_state(tts_pool* p, int slot, int which, StateLoc* s)
+{
+    const DevPtrs& d = p->d;
+    const size_t ws = p->cfg.weight_dtype == TTS_DTYPE_BF16 ? 2 : 4;
+    const int rd = p->book->slot(slot).parity;   // buffer half holding the newest activations of this request
+    auto xa = [&](int b, int off) { return (char*)d.xatt[b] + ((size_t)slot * K_ATT + off) * ws; };
+    auto xd = [&](int b, int off) { return (char*)d.xdec[b] + ((size_t)slot * K_DEC + off) * ws; };
+    s->n_loc = 0;
+    switch (which) {
+    case TTS_STATE_M_LAST: s->wt = false; s->n = N_MEL; s->loc[s->n_loc++] = (char*)(d.m_last + (size_t)slot * N_MEL); break;
+    case TTS_STATE_A:
+        s->wt = true; s->n = ENC;
+        s->loc[s->n_loc++] = xa(rd, XA_A); s->loc[s->n_loc++] = xa(rd ^ 1, XA_A);
+        s->loc[s->n_loc++] = xd(rd, XD_A); s->loc[s->n_loc++] = xd(rd ^ 1, XD_A);
+        break;
+    case TTS_STATE_W_LAST: s->wt = false; s->n = p->book->slot(slot).L; s->loc[s->n_loc++] = (char*)(d.w_last + (size_t)slot * d.max_enc_len); break;
+    case TTS_STATE_W_ACC: s->wt = false; s->n = p->book->slot(slot).L; s->loc[s->n_loc++] = (char*)(d.w_acc + (size_t)slot * d.max_enc_len); break;
+    case TTS_STATE_H_ATT:
+        s->wt = true; s->n = HID;
+        s->loc[s->n_loc++] = xa(rd, XA_H); s->loc[s->n_loc++] = xa(rd ^ 1, XA_H);
+        s->loc[s->n_loc++] = xd(rd, XD_HA); s->loc[s->n_loc++] = xd(rd ^ 1, XD_HA);
+        break;
+    case TTS_STATE_C_ATT: s->wt = false; s->n = HID; s->loc[s->n_loc++] = (char*)(d.c_att + (size_t)slot * HID); break;
+    case TTS_STATE_H_DEC:
+        s->wt = true; s->n = HID;
+        s->loc[s->n_loc++] = xd(rd, XD_HD); s->loc[s->n_loc++] = xd(rd ^ 1, XD_HD);
+        break;
+    case TTS_STATE_C_DEC: s->wt = false; s->n = HID; s->loc[s->n_loc++] = (char*)(d.c_dec + (size_t)slot * HID); break;
+    default: return fail(TTS_E_INVAL, "unknown state %d", which);
+    }
+    return TTS_OK;
+}
+
+extern "C" int tts_pool_get_state(tts_pool* p, int64_t id, int which, float* dst, int cap, int* out_n)
+{
+    if (!p || !dst) return fail(TTS_E_INVAL, "null argument");
+    const int slot = p->book->find(id);
+    if (slot < 0) return fail(TTS_E_NOTFOUND, "no request with id %lld", (long long)id);
+    StateLoc s;
+    int rc = locate_state(p, slot, which, &s);
+    if (rc) return rc;
+    if (out_n) *out_n = s.n;
+    if (cap < s.n) return fail(TTS_E_INVAL, "room for %d elements, %d needed", cap, s.n);
+    const bool bf = s.wt && p->cfg.weight_dtype == TTS_DTYPE_BF16;
+    if (!bf) {
+        HIP_TRY(hipMemcpyAsync(dst, s.loc[0], (size_t)s.n * 4, hipMemcpyDeviceToHost, p->stream));
+        HIP_TRY(hipStreamSynchronize(p->stream));
+    } else {
+        std::vector<uint16_t> h(s.n);
+        HIP_TRY(hipMemcpyAsync(h.data(), s.loc[0], (size_t)s.n * 2, hipMemcpyDeviceToHost, p->stream));
+        HIP_TRY(hipStreamSynchronize(p->stream));
+        for (int i = 0; i < s.n; ++i) dst[i] = host_bf2f(h[i]);
+    }
+    return TTS_OK;
+}
+
+extern "C" int tts_pool_set_state(tts_pool* p, int64_t id, int which, const float* src, int n)
+{
+    if (!p || !src) return fail(TTS_E_INVAL, "null argument");
+    const int slot = p->book->find(id);
+    if (slot < 0) return fail(TTS_E_NOTFOUND, "no request with id %lld", (long long)id);
+    StateLoc s;
+    int rc = locate_state(p, slot, which, &s);
+    if (rc) return rc;
+    if (n != s.n) return fail(TTS_E_INVAL, "state %d has %d elements, %d given", which, s.n, n);
+    const bool bf = s.wt && p->cfg.weight_dtype == TTS_DTYPE_BF16;
+    std::vector<uint16_t> h;
+    const void* hsrc = src;
+    size_t bytes = (size_t)n * 4;
+    if (bf) {
+        h.resize(n);
+        for (int i = 0; i < n; ++i) h[i] = host_f2bf(src[i]);
+        hsrc = h.data();
+        bytes = (size_t)n * 2;
+    }
+    for (int i = 0; i < s.n_loc; ++i) HIP_TRY(hipMemcpyAsync(s.loc[i], hsrc, bytes, hipMemcpyHostToDevice, p->stream));
+    if (which == TTS_STATE_M_LAST) HIP_TRY(launch_prenet_slot(p->d, p->cfg.weight_dtype, slot, p->stream));
+    HIP_TRY(hipStreamSynchronize(p->stream));
+    return TTS_OK;
+}
+
+// ------------------------------------------------------------------ host-only bookkeeping model
+struct tts_book {
+    PoolBook book;
+    tts_book(int a, int b, int c, int d) : book(a, b, c, d) {}
+};
+
+extern "C" tts_book* tts_book_create(int max_pool, int max_enc_len, int max_steps, int chunk_frames)
+{
+    if (max_pool < 1 || max_enc_len < 1 || max_steps < 1 || chunk_frames < 1) return nullptr;
+    return new (std::nothrow) tts_book(max_pool, max_enc_len, max_steps, chunk_frames);
+}
+
+extern "C" int tts_book_add(tts_book* b, int L, int n_steps, int64_t* out_id)
+{
+    if (!b || !out_id) return fail(TTS_E_INVAL, "null argument");
+    int rc = b->book.add(L, n_steps, out_id, nullptr);
+    if (rc == -1) return fail(TTS_E_INVAL, "L or n_steps out of range");
+    if (rc == -2) return fail(TTS_E_FULL, "pool is full");
+    return TTS_OK;
+}
+
+extern "C" int tts_book_step(tts_book* b, int64_t* out_ids, int* out_n_active)
+{
+    if (!b) return fail(TTS_E_INVAL, "null argument");
+    std::vector<int> adv;
+    int n = b->book.step(0, &adv);
+    // ids must be read before a finished slot could be reused; slots keep their info until retired
+    if (out_ids)
+        for (int i = 0; i < n; ++i) out_ids[i] = b->book.slot(adv[i]).id;
+    if (out_n_active) *out_n_active = n;
+    return TTS_OK;
+}
+
+extern "C" int tts_book_drain(tts_book* b, int64_t id, int* out_first, int* out_frames, int* out_finished)
+{
+    if (!b) return fail(TTS_E_INVAL, "null argument");
+    int slot = b->book.find(id);
+    if (slot < 0) return fail(TTS_E_NOTFOUND, "no request with id %lld", (long long)id);
+    int first, count, fin;
+    b->book.drain_plan(slot, &first, &count, &fin);
+    b->book.drain_commit(slot, count);
+    if (out_first) *out_first = first;
+    if (out_frames) *out_frames = count;
+    if (out_finished) *out_finished = fin;
+    return TTS_OK;
+}
+
+extern "C" int tts_book_retire(tts_book* b, int64_t id)
+{
+    if (!b) return fail(TTS_E_INVAL, "null argument");
+    if (b->book.retire(id)) return fail(TTS_E_NOTFOUND, "no request with id %lld", (long long)id);
+    return TTS_OK;
+}
+
+extern "C" void tts_book_destroy(tts_book* b) { delete b; }

@@ -1,0 +1,101 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every symbol the
+header declares, validates configurations, and its host-side pool bookkeeping
+follows the pooling semantics of Sec. 2.2.2 / the timeline of Sec. 2.2.3.
+No compute call is made here."""
+import os
+import re
+
+import pytest
+
+from paper_2211_13939_amd import binding, synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "tts_pool.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(tts_(?:pool|book|last)_\w+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = binding.lib()
+    names = _declared_symbols()
+    assert len(names) >= 20
+    for n in names:
+        assert hasattr(L, n), n
+    assert sorted(binding.EXPORTS) == names
+
+
+def test_config_validation_without_gpu():
+    good = binding.make_config(synth.DIMS, max_pool=16, max_enc_len=100, max_steps=200)
+    assert binding.workspace_bytes(good) > 72_000_000          # fp32 weights alone are 72.7 MB
+    bf = binding.make_config(synth.DIMS, max_pool=16, max_enc_len=100, max_steps=200, bf16=True)
+    assert 36_000_000 < binding.workspace_bytes(bf) < binding.workspace_bytes(good)
+    for field, bad in (("max_pool", 0), ("max_pool", 257), ("max_enc_len", 0), ("max_enc_len", 1025),
+                       ("max_steps", 0), ("chunk_frames", 0), ("n_mel", 81), ("att_dim", 64),
+                       ("loc_in_channels", 3), ("weight_dtype", 2)):
+        c = binding.make_config(synth.DIMS, max_pool=16, max_enc_len=100, max_steps=200)
+        setattr(c, field, bad)
+        assert binding.workspace_bytes(c) == 0, field
+        assert binding.lib().tts_last_error()
+    c = binding.make_config(synth.DIMS, max_pool=16, max_enc_len=100, max_steps=200, bf16=False, memory_bf16=True)
+    assert binding.workspace_bytes(c) == 0
+
+
+def test_timeline_membership_trace():
+    """The timeline of Sec. 2.2.3: request 1 arrives before step 0; 2 and 3 arrive
+    during step 1 and are first processed in step 2; 1 completes in step 3; 2 in
+    step 5; 4 arrives at the end of step 5 and is batched with 3 in step 6, where
+    3 completes."""
+    b = binding.Book(8, 100, 100, 4)
+    r1 = b.add(10, 4)                      # steps 0..3
+    trace = [b.step(), b.step()]           # steps 0, 1
+    r2 = b.add(10, 4)                      # arrived during step 1 -> steps 2..5
+    r3 = b.add(10, 5)                      # steps 2..6
+    trace += [b.step(), b.step()]          # steps 2, 3 (request 1 completes in 3)
+    b.retire(r1)
+    trace += [b.step(), b.step()]          # steps 4, 5 (request 2 completes in 5)
+    b.retire(r2)
+    r4 = b.add(10, 9)
+    trace += [b.step()]                    # step 6
+    assert trace == [[r1], [r1], [r1, r2, r3], [r1, r2, r3], [r2, r3], [r2, r3], [r3, r4]]
+    first, n, fin = b.drain(r3)
+    assert (first, n, fin) == (0, 4, False)
+    first, n, fin = b.drain(r3)
+    assert (first, n, fin) == (4, 1, True)          # short last chunk of a finished request
+    assert b.drain(r4) == (0, 0, False)             # chunk not full yet, still running
+
+
+def test_book_errors_and_slot_reuse():
+    b = binding.Book(2, 50, 20, 5)
+    with pytest.raises(binding.TtsError) as e:
+        b.add(0, 5)
+    assert e.value.code == binding.TTS_E_INVAL
+    with pytest.raises(binding.TtsError):
+        b.add(51, 5)
+    with pytest.raises(binding.TtsError):
+        b.add(5, 21)
+    a = b.add(5, 3)
+    c = b.add(6, 20)
+    with pytest.raises(binding.TtsError) as e:
+        b.add(5, 5)
+    assert e.value.code == binding.TTS_E_FULL
+    assert b.step() == [a, c] and b.step() == [a, c] and b.step() == [a, c]
+    assert b.step() == [c]                 # a reached its cap: holds its slot but no longer advances
+    with pytest.raises(binding.TtsError) as e:
+        b.add(5, 5)                        # still full until retired
+    assert e.value.code == binding.TTS_E_FULL
+    assert b.drain(a) == (0, 3, True)
+    b.retire(a)
+    with pytest.raises(binding.TtsError) as e:
+        b.retire(a)
+    assert e.value.code == binding.TTS_E_NOTFOUND
+    with pytest.raises(binding.TtsError):
+        b.drain(a)
+    d = b.add(7, 2)
+    assert d not in (a, c)                 # ids are never reused
+    assert b.step() == [c, d]
+    b.retire(c)                            # retiring an unfinished request is allowed
+    assert b.step() == [d]
+    assert b.step() == []                  # empty step is a no-op
