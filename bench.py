@@ -1,0 +1,232 @@
+#!/usr/bin/env python3
+"""Benchmark of the pooled decoder step on one MI355X.
+
+Workload (config.workload = "c3"): 64 requests, bf16 weights with fp32
+accumulation, encoder lengths U{30..300}, per-request frame counts U{100..600};
+all join at step 0 from encoder outputs already resident in HBM, each retires
+at its own end and the pool shrinks.  A "step" is one tts_pool_step: every
+request still in the pool produces one mel frame (prenet, attention LSTM,
+location-sensitive attention, decoder LSTM, projection).  --steps K times
+exactly K steps of that job (replayed from the start when it runs out);
+value = frames produced / wall time.
+
+One JSON line is printed, with
+  roofline      the dominant kernel of the step at pool = 64, HIP-event timed
+  cpu_baseline  the CPU oracle on the first 100 steps of the same 64 requests
+  stream        first-chunk latency under the 100-QPS Poisson arrival load (c5)
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+
+
+def algorithmic_bytes(P, sum_L, s_w, s_m):
+    """Bytes one step must move, per kernel, for P requests with sum_L encoder
+    positions: every step weight once, each request's processed memory and
+    encoder output once, carried state read and written, mel written."""
+    gates_att = 4096 * 1792 * s_w + 4096 * 4
+    gates_dec = 4096 * 2560 * s_w + 4096 * 4
+    lsa_w = 128 * 1024 * s_w + (32 * 2 * 31 + 128 * 32 + 128) * 4
+    proj_w = (81 * 1536 + 80 * 256 + 256 * 256) * s_w + 81 * 4
+    st = 4  # carried state counted in fp32: read + write
+    return {
+        # x = [p; a; h_att] read, c_att read+write, h_att written
+        "k_lstm_att": gates_att + P * (1792 * st + 2 * 1024 * st + 1024 * st),
+        # h_att read, PM + F_enc streamed, W_last/W_acc read+write, a written
+        "k_lsa": lsa_w + sum_L * ((128 + 512) * s_m + 16) + P * (1024 * st + 512 * st),
+        "k_lstm_dec": gates_dec + P * (2560 * st + 2 * 1024 * st + 1024 * st),
+        # [h_dec; a] read, mel ring + m_last + stop written, p written
+        "k_proj": proj_w + P * (1536 * st + 80 * 4 * 2 + 4 + 256 * st),
+    }
+
+
+def run_job(pool, wl, enc_dev, n_steps_total, pos=0):
+    """Run `n_steps_total` steps of the job, continuing at step `pos` of the
+    current pass (requests are re-admitted when a pass ends).  Returns
+    (frames, new_pos).  Retires every request as soon as it has finished."""
+    n = wl.n_steps
+    horizon = int(n.max())
+    order = np.argsort(n, kind="stable")
+    frames = 0
+    done = 0
+    state = run_job.state
+    while done < n_steps_total:
+        if pos == 0:
+            state["ids"] = [pool.add_request(enc_dev[i], int(n[i])) for i in range(wl.n_requests)]
+            state["next_fin"] = 0
+        ids, k = state["ids"], state["next_fin"]
+        # next moment a request finishes
+        nxt = int(n[order[k]]) if k < wl.n_requests else horizon
+        seg = min(nxt - pos, n_steps_total - done)
+        if seg > 0:
+            frames += pool.step_n(seg)
+            pos += seg
+            done += seg
+        while k < wl.n_requests and n[order[k]] <= pos:
+            pool.retire(ids[order[k]])
+            k += 1
+        state["next_fin"] = k
+        if pos >= horizon:
+            pos = 0
+    return frames, pos
+
+
+run_job.state = {}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3000)
+    ap.add_argument("--warmup", type=int, default=600)
+    ap.add_argument("--workload", default="c3", choices=["c2", "c3", "c4"])
+    ap.add_argument("--no-graph", action="store_true")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-stream", action="store_true")
+    ap.add_argument("--profile-only", action="store_true",
+                    help="only the timed steps (for rocprofv3 runs): no cpu baseline, no stream load")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (requests are independent; more GPUs would each "
+              "hold their own pool). Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+    if args.profile_only:
+        args.no_cpu_baseline = args.no_stream = True
+
+    import torch
+    from paper_2211_13939_amd import binding, synth
+
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    wl = synth.workload(args.workload)
+    weights = synth.make_weights(bf16=wl.bf16)
+    cfg = binding.make_config(wl.dims, max_pool=wl.n_requests, max_enc_len=int(wl.enc_len.max()),
+                              max_steps=int(wl.n_steps.max()), chunk_frames=wl.chunk_frames, bf16=wl.bf16,
+                              use_graph=not args.no_graph)
+    pool = binding.Pool(cfg, weights)
+    dev = pool.device
+    enc_dev = [torch.from_numpy(wl.encoder_outputs(i)).to(dev) for i in range(wl.n_requests)]
+    torch.cuda.synchronize()
+
+    # ---- warmup, then exactly K timed steps
+    run_job.state = {}
+    _, pos = run_job(pool, wl, enc_dev, args.warmup, 0)
+    # finish the warmup pass so that the timed region starts with a fresh job
+    if pos:
+        _, pos = run_job(pool, wl, enc_dev, int(wl.n_steps.max()) - pos, pos)
+    pool.sync()
+    torch.cuda.synchronize()
+    pool.timing(False)
+    t0 = time.perf_counter()
+    frames, _ = run_job(pool, wl, enc_dev, args.steps, 0)
+    pool.sync()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    for rid in list(run_job.state.get("ids", [])):
+        try:
+            pool.retire(rid)
+        except binding.TtsError:
+            pass
+    fps = frames / wall
+
+    # ---- full-pool steady state and per-kernel device times (HIP events on the pool's stream)
+    ids = [pool.add_request(enc_dev[i], int(wl.n_steps[i])) for i in range(wl.n_requests)]
+    full_steps = int(wl.n_steps.min()) - 1
+    pool.step_n(20)
+    pool.sync()
+    pool.timing(True)
+    pool.step_n(full_steps - 20 - 30)
+    full_ms = pool.elapsed_ms()
+    pool.timing(False)
+    kernel_us = pool.kernel_times_us(30)      # still the full pool: 30 event-bracketed steps
+    for rid in ids:
+        pool.retire(rid)
+    P = wl.n_requests
+    sum_L = int(wl.enc_len.sum())
+    s_w = 2 if wl.bf16 else 4
+    per_kernel = algorithmic_bytes(P, sum_L, s_w, s_w)
+    step_bytes = sum(per_kernel.values())
+    step_us = full_ms * 1e3 / (full_steps - 50)
+
+    out = {
+        "metric": "decoder frames/sec at pool=64 (bf16); p50 first-chunk latency at 100 QPS",
+        "value": fps,
+        "unit": "frames/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": wall * 1e3 / args.steps,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16" if wl.bf16 else "f32",
+        "data": "synthetic",
+        "config": {"workload": args.workload, "requests": P, "enc_len": "U{30..300}" if args.workload == "c3" else "see synth.py",
+                   "frames_per_request": "U{100..600}" if args.workload == "c3" else "see synth.py",
+                   "weights": "bf16, fp32 accumulate" if wl.bf16 else "fp32", "graph": not args.no_graph,
+                   "frames_timed": int(frames)},
+        "full_pool": {"pool": P, "us_per_step": step_us, "frames_per_s": P / (step_us * 1e-6)},
+    }
+    if kernel_us:
+        dom = max(kernel_us, key=kernel_us.get)
+        out["roofline"] = {"bound": "hbm", "kernel": dom, "achieved": per_kernel[dom] / (kernel_us[dom] * 1e-6) / 1e9,
+                           "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                           "frac": per_kernel[dom] / (kernel_us[dom] * 1e-6) / 1e9 / HBM_PEAK_GBS, "traffic": None,
+                           "kernel_us": kernel_us, "algorithmic_bytes": per_kernel}
+    else:
+        out["roofline"] = {"bound": "hbm", "kernel": "step (4 kernels, one graph launch)",
+                           "achieved": step_bytes / (step_us * 1e-6) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                           "frac": step_bytes / (step_us * 1e-6) / 1e9 / HBM_PEAK_GBS, "traffic": None,
+                           "algorithmic_bytes": per_kernel}
+    out["step_roofline"] = {"bytes": step_bytes, "us": step_us,
+                            "frac_of_hbm_peak": step_bytes / (step_us * 1e-6) / 1e9 / HBM_PEAK_GBS}
+
+    if not args.no_stream:
+        from paper_2211_13939_amd import stream
+        w5 = synth.workload("c5")
+        cfg5 = binding.make_config(w5.dims, max_pool=64, max_enc_len=int(w5.enc_len.max()),
+                                   max_steps=int(w5.n_steps.max()), chunk_frames=w5.chunk_frames, bf16=True,
+                                   use_graph=not args.no_graph)
+        pool.close()
+        pool5 = binding.Pool(cfg5, synth.make_weights(bf16=True))
+        res = {}
+        for name, je in (("per_step_join", 1), ("per_chunk_join", w5.chunk_frames)):
+            be = stream.GpuBackend(pool5, w5.encoder_outputs, w5.n_steps, w5.chunk_frames)
+            r = stream.simulate(be, w5.arrival_s, w5.n_steps, w5.chunk_frames, join_every=je, max_pool=64)
+            pc = r.percentiles("first")
+            res[name] = {"p50_ms": pc["p50"] * 1e3, "p95_ms": pc["p95"] * 1e3, "p99_ms": pc["p99"] * 1e3,
+                         "last_chunk_p50_ms": r.percentiles("last")["p50"] * 1e3,
+                         "mean_pool": sum(k * v for k, v in r.pool_size_hist.items()) / max(1, r.n_steps),
+                         "busy_s": r.busy_s, "requests": int(w5.n_requests)}
+        out["stream"] = {"workload": "c5: Poisson 100 QPS x 10 s, L~U{30..300}, frames=4L, 40-frame chunks",
+                         **res, "paper_context": "first-chunk latency < 80 ms at 100 QPS, full pipeline, one A10"}
+        pool5.close()
+    else:
+        pool.close()
+
+    if not args.no_cpu_baseline:
+        from oracle import oracle as orc
+        cores = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "0") or (os.cpu_count() or 1)))
+        W = orc.Weights(weights)
+        n_req, window = (wl.n_requests, 40) if wl.n_requests >= 64 else (wl.n_requests, 100)
+        Fs = [wl.encoder_outputs(i) for i in range(n_req)]
+        t0 = time.perf_counter()
+        _, _, fr, used = orc.pool_decode(wl.dims, W, Fs, [window] * n_req, window, pm_round_bf16=wl.bf16,
+                                         n_threads=cores)
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": float(fr.sum()) / dt, "unit": "frames/s", "cores": int(used), "kind": "oracle",
+                               "sample": f"first {window} steps of the same {n_req} requests "
+                                         f"({int(fr.sum())} frames, {dt:.1f} s incl. join)"}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -33,7 +33,8 @@ EXPORTS = (
     "tts_pool_workspace_bytes", "tts_pool_create", "tts_pool_add_request", "tts_pool_step",
     "tts_pool_step_n", "tts_pool_drain_chunk", "tts_pool_get_stop_logits", "tts_pool_retire",
     "tts_pool_get_state", "tts_pool_set_state", "tts_pool_frames", "tts_pool_size", "tts_pool_n_active",
-    "tts_pool_sync", "tts_pool_timing", "tts_pool_elapsed_ms", "tts_pool_destroy", "tts_last_error",
+    "tts_pool_sync", "tts_pool_timing", "tts_pool_elapsed_ms", "tts_pool_kernel_times", "tts_pool_destroy",
+    "tts_last_error",
     "tts_book_create", "tts_book_add", "tts_book_step", "tts_book_drain", "tts_book_retire",
     "tts_book_destroy",
 )
@@ -88,6 +89,7 @@ def lib() -> C.CDLL:
     L.tts_pool_sync.argtypes = [vp]
     L.tts_pool_timing.argtypes = [vp, C.c_int]
     L.tts_pool_elapsed_ms.argtypes = [vp, _fp]
+    L.tts_pool_kernel_times.argtypes = [vp, C.c_int, _fp, C.c_int, _ip]
     L.tts_pool_destroy.restype = None
     L.tts_pool_destroy.argtypes = [vp]
     L.tts_last_error.restype = C.c_char_p
@@ -230,6 +232,15 @@ class Pool:
         ms = C.c_float()
         _check(lib().tts_pool_elapsed_ms(self._h, C.byref(ms)))
         return ms.value
+
+    KERNEL_NAMES = ("k_lstm_att", "k_lsa", "k_lstm_dec", "k_proj")
+
+    def kernel_times_us(self, n_steps: int) -> Dict[str, float]:
+        """Average device time of each kernel over n un-graphed, event-bracketed steps."""
+        buf = (C.c_float * 8)()
+        nk = C.c_int()
+        _check(lib().tts_pool_kernel_times(self._h, int(n_steps), buf, 8, C.byref(nk)))
+        return {self.KERNEL_NAMES[i]: float(buf[i]) for i in range(nk.value)}
 
     def drain_all(self, rid: int) -> np.ndarray:
         """Every remaining frame of a finished request (host convenience loop over drain_chunk)."""

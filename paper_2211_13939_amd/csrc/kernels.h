@@ -13,7 +13,10 @@ struct StepLaunch {
 
 // One decoder step (paper Eq. 2) for every request listed in d.table.
 // `cur` selects which half of the double-buffered activations is read.
-hipError_t launch_step(const DevPtrs& d, const StepLaunch& cfg, int cur, hipStream_t s);
+// If `ev` is given it holds N_STEP_KERNELS + 1 events: ev[0] is recorded before the
+// first kernel and ev[i + 1] after kernel i (per-kernel device times).
+constexpr int N_STEP_KERNELS = 4;
+hipError_t launch_step(const DevPtrs& d, const StepLaunch& cfg, int cur, hipStream_t s, hipEvent_t* ev = nullptr);
 
 hipError_t launch_set_table(const DevPtrs& d, const TableArgs& args, hipStream_t s);
 hipError_t launch_slot_init(const DevPtrs& d, int wdtype, int slot, int L, int n_steps, hipStream_t s);

@@ -478,8 +478,10 @@ __global__ __launch_bounds__(ATT) void k_join_memory(DevPtrs d, const float* __r
 // launch wrappers
 // ---------------------------------------------------------------------------
 template <typename XT, typename MT>
-static hipError_t step_typed(const DevPtrs& d, int nb, int cur, hipStream_t s)
+static hipError_t step_typed(const DevPtrs& d, int nb, int cur, hipStream_t s, hipEvent_t* ev)
 {
+    auto mark = [&](int i) { if (ev) (void)hipEventRecord(ev[i], s); };
+    mark(0);
     XT* xatt_cur = reinterpret_cast<XT*>(d.xatt[cur]);
     XT* xatt_nxt = reinterpret_cast<XT*>(d.xatt[cur ^ 1]);
     XT* xdec_cur = reinterpret_cast<XT*>(d.xdec[cur]);
@@ -488,21 +490,25 @@ static hipError_t step_typed(const DevPtrs& d, int nb, int cur, hipStream_t s)
     hipLaunchKernelGGL((k_lstm<XT, K_ATT>), dim3(HID / 4), dim3(LSTM_WAVES * 64), 0, s,
                        d.Wa, d.ba, xatt_cur, d.c_att, xdec_cur, K_DEC, XD_HA, xatt_nxt, K_ATT, XA_H,
                        d.table, d.done);
+    mark(1);
     hipLaunchKernelGGL((k_lsa<XT, MT>), dim3(nb), dim3(256), 0, s, d, cur);
+    mark(2);
     // H_dec(t): consumed by this step's projection and the next step's decoder LSTM (same buffer)
     hipLaunchKernelGGL((k_lstm<XT, K_DEC>), dim3(HID / 4), dim3(LSTM_WAVES * 64), 0, s,
                        d.Wd, d.bd, xdec_cur, d.c_dec, xdec_nxt, K_DEC, XD_HD, xdec_nxt, K_DEC, XD_HD,
                        d.table, d.done);
+    mark(3);
     hipLaunchKernelGGL((k_proj<XT>), dim3(nb), dim3(256), 0, s, d, cur);
+    mark(4);
     return hipGetLastError();
 }
 
-hipError_t launch_step(const DevPtrs& d, const StepLaunch& cfg, int cur, hipStream_t s)
+hipError_t launch_step(const DevPtrs& d, const StepLaunch& cfg, int cur, hipStream_t s, hipEvent_t* ev)
 {
     if (cfg.n_blocks < 1) return hipSuccess;
-    if (cfg.wdtype == 0 && cfg.mdtype == 0) return step_typed<float, float>(d, cfg.n_blocks, cur, s);
-    if (cfg.wdtype == 1 && cfg.mdtype == 1) return step_typed<bf16_t, bf16_t>(d, cfg.n_blocks, cur, s);
-    if (cfg.wdtype == 1 && cfg.mdtype == 0) return step_typed<bf16_t, float>(d, cfg.n_blocks, cur, s);
+    if (cfg.wdtype == 0 && cfg.mdtype == 0) return step_typed<float, float>(d, cfg.n_blocks, cur, s, ev);
+    if (cfg.wdtype == 1 && cfg.mdtype == 1) return step_typed<bf16_t, bf16_t>(d, cfg.n_blocks, cur, s, ev);
+    if (cfg.wdtype == 1 && cfg.mdtype == 0) return step_typed<bf16_t, float>(d, cfg.n_blocks, cur, s, ev);
     return hipErrorInvalidValue;
 }
 

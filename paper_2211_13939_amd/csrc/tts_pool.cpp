@@ -465,6 +465,41 @@ extern "C" int tts_pool_step_n(tts_pool* p, int n, int64_t* out_frames)
     return step_impl(p, n, out_frames, nullptr);
 }
 
+// n un-graphed steps with an event between consecutive kernels; average device
+// time of each kernel in microseconds
+extern "C" int tts_pool_kernel_times(tts_pool* p, int n, float* out_us, int cap, int* out_n_kernels)
+{
+    if (!p || !out_us || n < 1) return fail(TTS_E_INVAL, "bad argument");
+    if (out_n_kernels) *out_n_kernels = N_STEP_KERNELS;
+    if (cap < N_STEP_KERNELS) return fail(TTS_E_INVAL, "room for %d kernels, %d needed", cap, N_STEP_KERNELS);
+    hipEvent_t ev[N_STEP_KERNELS + 1];
+    for (auto& e : ev) HIP_TRY(hipEventCreate(&e));
+    double acc[N_STEP_KERNELS] = {0};
+    int done = 0, rc = TTS_OK;
+    for (int i = 0; i < n && rc == TTS_OK; ++i) {
+        const int n_active = (int)p->book->active().size();
+        if (n_active == 0) break;
+        if ((rc = push_table(p))) break;
+        StepLaunch sl{p->cfg.weight_dtype, p->cfg.memory_dtype, n_active};
+        hipError_t e = launch_step(p->d, sl, p->parity, p->stream, ev);
+        if (e == hipSuccess) e = hipEventSynchronize(ev[N_STEP_KERNELS]);
+        for (int k = 0; k < N_STEP_KERNELS && e == hipSuccess; ++k) {
+            float ms = 0.f;
+            e = hipEventElapsedTime(&ms, ev[k], ev[k + 1]);
+            acc[k] += ms;
+        }
+        if (e != hipSuccess) rc = fail(TTS_E_HIP, "timed step: %s", hipGetErrorString(e));
+        p->parity ^= 1;
+        p->book->step(p->parity);
+        ++done;
+    }
+    for (auto& e : ev) (void)hipEventDestroy(e);
+    if (rc) return rc;
+    if (done == 0) return fail(TTS_E_INVAL, "the pool is empty");
+    for (int k = 0; k < N_STEP_KERNELS; ++k) out_us[k] = (float)(acc[k] * 1e3 / done);
+    return TTS_OK;
+}
+
 // with a stop threshold the device may have ended a request before its cap
 static int refresh_slot(tts_pool* p, int slot)
 {

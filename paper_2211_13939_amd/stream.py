@@ -1,0 +1,159 @@
+"""Arrival-driven serving loop over a request pool (Sec. 2.2.2, 2.2.3).
+
+The loop is the paper's "infinite loop": requests that have arrived join the
+pool, every pooled request is advanced, full chunks are handed out, finished
+requests leave.  Time is simulated: the clock advances by the *measured* wall
+time of each segment of work, and jumps to the next arrival when the pool is
+empty, so a 10 s arrival trace does not need 10 s of wall time.
+
+Two join policies:
+  join_every = chunk   the paper's iteration: module D produces one chunk for
+                       every pooled request per iteration, arrivals wait for
+                       the next iteration (first-chunk latency between T and
+                       2T for constant iteration time T, mean 1.5 T).
+  join_every = 1       a request joins before the next decoder step.
+
+This module is host logic only; the backend does the work.
+"""
+from __future__ import annotations
+
+import time
+from dataclasses import dataclass, field
+from typing import Dict, List, Optional, Sequence
+
+import numpy as np
+
+
+class PoolBackend:
+    """What the loop needs from a pool.  `run(k)` advances every pooled request
+    by k steps, hands out every chunk that became ready and returns
+    (elapsed seconds, ids whose chunk was handed out, ids that finished)."""
+
+    def add(self, index: int) -> int:
+        raise NotImplementedError
+
+    def run(self, k: int):
+        raise NotImplementedError
+
+    def retire(self, rid: int) -> None:
+        raise NotImplementedError
+
+
+@dataclass
+class StreamResult:
+    first_chunk_latency_s: np.ndarray
+    last_chunk_latency_s: np.ndarray
+    pool_size_hist: Dict[int, int]
+    n_segments: int
+    n_steps: int
+    busy_s: float
+    end_clock_s: float
+
+    def percentiles(self, which="first"):
+        x = self.first_chunk_latency_s if which == "first" else self.last_chunk_latency_s
+        return {f"p{p}": float(np.percentile(x, p)) for p in (50, 95, 99)}
+
+
+def simulate(backend: PoolBackend, arrival_s: Sequence[float], n_steps: Sequence[int], chunk: int,
+             join_every: int = 1, step_time_guess_s: float = 30e-6, max_pool: Optional[int] = None) -> StreamResult:
+    arrival_s = np.asarray(arrival_s, np.float64)
+    n_steps = np.asarray(n_steps, np.int64)
+    n = arrival_s.shape[0]
+    order = np.argsort(arrival_s, kind="stable")
+    nxt = 0                                  # next arrival (position in `order`) not yet admitted
+    clock = 0.0
+    live: Dict[int, dict] = {}               # rid -> {index, done_steps, first_seen}
+    fcl = np.full(n, np.nan)
+    lcl = np.full(n, np.nan)
+    hist: Dict[int, int] = {}
+    n_seg = 0
+    total_steps = 0
+    busy = 0.0
+    step_est = step_time_guess_s
+
+    while nxt < n or live:
+        if not live and nxt < n and arrival_s[order[nxt]] > clock:
+            clock = float(arrival_s[order[nxt]])          # idle until the next arrival
+        # admit everything that has arrived (bounded by the pool's capacity)
+        t0 = time.perf_counter()
+        while nxt < n and arrival_s[order[nxt]] <= clock and (max_pool is None or len(live) < max_pool):
+            i = int(order[nxt])
+            rid = backend.add(i)
+            live[rid] = dict(index=i, done=0, total=int(n_steps[i]), first=False)
+            nxt += 1
+        # how many steps until something must happen on the host
+        if join_every > 1:
+            k = join_every
+        else:
+            k = min(_steps_to_event(s, chunk) for s in live.values())
+            if nxt < n and (max_pool is None or len(live) < max_pool):
+                gap = arrival_s[order[nxt]] - clock
+                k = max(1, min(k, int(np.ceil(gap / max(step_est, 1e-9)))))
+        hist[len(live)] = hist.get(len(live), 0) + k
+        elapsed, chunk_ids, fin_ids = backend.run(k)
+        # a real backend is timed here (joins, steps, drains); a model backend reports its own time
+        dt = (time.perf_counter() - t0) if elapsed is None else float(elapsed)
+        clock += dt
+        busy += dt
+        n_seg += 1
+        total_steps += k
+        step_est = 0.8 * step_est + 0.2 * (dt / k)
+        for s in live.values():
+            s["done"] = min(s["total"], s["done"] + k)
+        for rid in chunk_ids:
+            s = live[rid]
+            if not s["first"]:
+                s["first"] = True
+                fcl[s["index"]] = clock - arrival_s[s["index"]]
+        for rid in fin_ids:
+            s = live.pop(rid)
+            if not s["first"]:
+                fcl[s["index"]] = clock - arrival_s[s["index"]]
+            lcl[s["index"]] = clock - arrival_s[s["index"]]
+            backend.retire(rid)
+    return StreamResult(fcl, lcl, hist, n_seg, total_steps, busy, clock)
+
+
+def _steps_to_event(s: dict, chunk: int) -> int:
+    """Steps until this request completes its next chunk or finishes."""
+    to_chunk = chunk - (s["done"] % chunk)
+    to_end = s["total"] - s["done"]
+    return max(1, min(to_chunk, to_end))
+
+
+class GpuBackend(PoolBackend):
+    """Drives a binding.Pool; encoder outputs are taken from `enc(i)` (host
+    numpy or device tensor)."""
+
+    def __init__(self, pool, enc, n_steps, chunk: int):
+        self.pool, self.enc, self.n_steps, self.chunk = pool, enc, n_steps, chunk
+        self.live: Dict[int, dict] = {}
+
+    def add(self, index: int) -> int:
+        rid = self.pool.add_request(self.enc(index), int(self.n_steps[index]))
+        self.live[rid] = dict(done=0, total=int(self.n_steps[index]), drained=0)
+        return rid
+
+    def run(self, k: int):
+        self.pool.step_n(k)
+        chunk_ids, fin_ids = [], []
+        for rid, s in self.live.items():
+            s["done"] = min(s["total"], s["done"] + k)
+            ready = s["done"] - s["drained"] >= self.chunk or s["done"] == s["total"]
+            if ready:
+                while True:
+                    frames, fin = self.pool.drain_chunk(rid)
+                    s["drained"] += frames.shape[0]
+                    if frames.shape[0]:
+                        chunk_ids.append(rid)
+                    if fin:
+                        fin_ids.append(rid)
+                    if fin or frames.shape[0] == 0 or s["done"] - s["drained"] < self.chunk:
+                        break
+        if not chunk_ids and not fin_ids:
+            self.pool.sync()
+        return None, chunk_ids, fin_ids
+
+    def retire(self, rid: int) -> None:
+        self.pool.retire(rid)
+        self.live.pop(rid, None)
