@@ -52,7 +52,9 @@ def algorithmic_bytes(P, sum_L, s_w, s_m):
 def run_job(pool, wl, enc_dev, n_steps_total, pos=0):
     """Run `n_steps_total` steps of the job, continuing at step `pos` of the
     current pass (requests are re-admitted when a pass ends).  Returns
-    (frames, new_pos).  Retires every request as soon as it has finished."""
+    (frames, new_pos).  The loop is the paper's iteration: up to one chunk of
+    decoder steps for every pooled request, then every request that has
+    completed is removed from the pool."""
     n = wl.n_steps
     horizon = int(n.max())
     order = np.argsort(n, kind="stable")
@@ -64,13 +66,10 @@ def run_job(pool, wl, enc_dev, n_steps_total, pos=0):
             state["ids"] = [pool.add_request(enc_dev[i], int(n[i])) for i in range(wl.n_requests)]
             state["next_fin"] = 0
         ids, k = state["ids"], state["next_fin"]
-        # next moment a request finishes
-        nxt = int(n[order[k]]) if k < wl.n_requests else horizon
-        seg = min(nxt - pos, n_steps_total - done)
-        if seg > 0:
-            frames += pool.step_n(seg)
-            pos += seg
-            done += seg
+        seg = min(wl.chunk_frames, horizon - pos, n_steps_total - done)
+        frames += pool.step_n(seg)
+        pos += seg
+        done += seg
         while k < wl.n_requests and n[order[k]] <= pos:
             pool.retire(ids[order[k]])
             k += 1

@@ -4,6 +4,7 @@
 // code and no HIP calls in here.
 #pragma once
 #include <cstdint>
+#include <set>
 #include <unordered_map>
 #include <vector>
 
@@ -26,8 +27,7 @@ public:
     PoolBook(int max_pool, int max_enc_len, int max_steps, int chunk_frames)
         : max_pool_(max_pool), max_enc_len_(max_enc_len), max_steps_(max_steps),
           chunk_(chunk_frames), slots_(max_pool) {
-        free_.reserve(max_pool);
-        for (int s = max_pool - 1; s >= 0; --s) free_.push_back(s);
+        for (int s = 0; s < max_pool; ++s) free_.insert(s);
         active_.reserve(max_pool);
     }
 
@@ -35,8 +35,9 @@ public:
     int add(int L, int n_steps, int64_t* out_id, int* out_slot) {
         if (L < 1 || L > max_enc_len_ || n_steps < 1 || n_steps > max_steps_) return -1;
         if (free_.empty()) return -2;
-        int s = free_.back();
-        free_.pop_back();
+        // lowest free slot first: keeps the occupied slots packed into few 16-slot tiles
+        int s = *free_.begin();
+        free_.erase(free_.begin());
         SlotInfo& si = slots_[s];
         si = SlotInfo();
         si.id = next_id_++;
@@ -111,7 +112,7 @@ public:
         if (slots_[s].state == SlotState::Active) remove_active(s);
         slots_[s].state = SlotState::Free;
         by_id_.erase(id);
-        free_.push_back(s);
+        free_.insert(s);
         return 0;
     }
 
@@ -136,7 +137,7 @@ private:
 
     int max_pool_, max_enc_len_, max_steps_, chunk_;
     std::vector<SlotInfo> slots_;
-    std::vector<int> free_;
+    std::set<int> free_;
     std::vector<int> active_;
     std::unordered_map<int64_t, int> by_id_;
     int64_t next_id_ = 1;

@@ -23,7 +23,12 @@ constexpr int K_PROJ = HID + ENC;           // 1536: [H_dec; A]
 constexpr int N_PROJ = N_MEL + 1;           // mel rows + stop row
 constexpr int MAX_POOL = 256;
 constexpr int MAX_ENC_LEN = 1024;
-constexpr int TABLE_HDR = 4;                // table[0] = n_active, slots follow at [4..]
+constexpr int MAX_TILES = MAX_POOL / 16;     // a pool tile = 16 consecutive slots = the 16 columns of one MFMA
+// device table: [0] = number of active requests, [1] = number of active tiles,
+// [TABLE_SLOTS + i] = slot of active request i, [TABLE_TILES + i] = i-th active tile
+constexpr int TABLE_SLOTS = 4;
+constexpr int TABLE_TILES = TABLE_SLOTS + MAX_POOL;
+constexpr int TABLE_INTS = TABLE_TILES + MAX_TILES;
 
 // offsets inside the activation rows
 constexpr int XA_P = 0, XA_A = PRENET, XA_H = PRENET + ENC;       // x_att = [p | a | h_att]
@@ -35,23 +40,23 @@ struct DevPtrs {
     const uint4* Wd;      // decoder-LSTM gate matrix, MFMA fragment order
     const float* ba;      // [HID][4] gate-interleaved merged bias
     const float* bd;
-    const void* Wq;       // [ATT][HID] WT
+    const void* Wq;       // [ATT][HID] WT, MFMA fragment order (8 row tiles)
+    const void* lsa_kfrag; // location filters as per-lane MFMA A operands (layout depends on WT)
+    const void* lsa_wfrag; // W_loc as per-lane MFMA A operands (layout depends on WT)
     const float* WmemT;   // [ENC][ATT] fp32 (join time only)
-    const float* KcT;     // [2][LOC_K][LOC_F] fp32, channel 0 = W_last, 1 = W_acc
-    const float* Wloc;    // [ATT][LOC_F] fp32
     const float* v;       // [ATT] fp32
-    const void* Wmel;     // [N_PROJ][K_PROJ] WT, last row = stop
+    const void* Wmel;     // [96][K_PROJ] WT in MFMA fragment order: 80 mel rows, the stop row, zero rows
     const float* bmel;    // [N_PROJ]
-    const void* Wp1T;     // [N_MEL][PRENET] WT (transposed)
-    const void* Wp2T;     // [PRENET][PRENET] WT (transposed)
+    const void* Wp1;      // [PRENET][80 (fp32) or 96 (bf16, zero padded)] WT in MFMA fragment order
+    const void* Wp2;      // [PRENET][PRENET] WT in MFMA fragment order
     // per-slot state
-    void* xatt[2];        // [slots][K_ATT] WT, double buffered
-    void* xdec[2];        // [slots][K_DEC] WT, double buffered
+    void* xatt[2];        // [tiles][K_ATT / KB fragments][64 lanes][16 B] WT: slot-tiled MFMA B-operand order, double buffered
+    void* xdec[2];        // same for K_DEC
     float* c_att;         // [slots][HID]
     float* c_dec;         // [slots][HID]
     float* m_last;        // [slots][N_MEL]
-    float* w_last;        // [slots][max_enc_len]
-    float* w_acc;         // [slots][max_enc_len]
+    float* w_last[2];     // [slots][max_enc_len], double buffered like the activations
+    float* w_acc[2];      // [slots][max_enc_len]
     void* Fmem;           // [slots][max_enc_len][ENC] MT
     void* PM;             // [slots][max_enc_len][ATT] MT
     float* mel_ring;      // [slots][max_steps][N_MEL]
@@ -59,8 +64,9 @@ struct DevPtrs {
     int* L;               // [slots]
     int* t;               // [slots] frames produced
     int* n_steps;         // [slots]
-    int* done;            // [slots]
-    int* table;           // [TABLE_HDR + MAX_POOL]
+    int* done;            // [slots] reached its last frame (or tripped the stop threshold)
+    int* live;            // [MAX_POOL] listed in the table (advanced by the next step)
+    int* table;           // [TABLE_INTS]
     float* stage;         // [max_enc_len][ENC] fp32 staging for host-side encoder outputs
     int max_enc_len;
     int max_steps;
@@ -69,7 +75,9 @@ struct DevPtrs {
 
 struct TableArgs {
     int n_active;
+    int n_tiles;
     uint16_t slot[MAX_POOL];
+    uint8_t tile[MAX_TILES];
 };
 
 }  // namespace tts

@@ -9,6 +9,7 @@ struct StepLaunch {
     int wdtype;     // weights / activations
     int mdtype;     // encoder memory
     int n_blocks;   // per-request grids are launched with this many blocks (>= n_active)
+    int n_tiles;    // per-tile grids are launched with this many blocks (>= active tiles)
 };
 
 // One decoder step (paper Eq. 2) for every request listed in d.table.
@@ -24,5 +25,9 @@ hipError_t launch_slot_init(const DevPtrs& d, int wdtype, int slot, int L, int n
 hipError_t launch_join_memory(const DevPtrs& d, int mdtype, const float* F_dev, int slot, int L, hipStream_t s);
 // p = Pre(m_last) into both activation buffers of one slot (after a state overwrite)
 hipError_t launch_prenet_slot(const DevPtrs& d, int wdtype, int slot, hipStream_t s);
+
+// one slot's piece [off, off+n) of a slot-tiled activation array with K elements per slot <-> fp32 device buffer
+hipError_t launch_x_get(int wdtype, const void* X, int K, int slot, int off, int n, float* out, hipStream_t s);
+hipError_t launch_x_set(int wdtype, void* X, int K, int slot, int off, int n, const float* in, hipStream_t s);
 
 }  // namespace tts

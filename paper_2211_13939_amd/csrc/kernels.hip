@@ -6,6 +6,13 @@
 //   k_lstm<dec>   gates GEMM on MFMA + fused cell        (Eq. 2 line 3)
 //   k_proj        mel + stop projection, ring write, prenet of the new frame
 //                                                         (Eq. 2 line 5, Pre() of line 1)
+//
+// Activations (the vectors multiplied by weight matrices) live in HBM in MFMA
+// B-operand order, tiled by pool slot: 16 slots form a tile, and a tile's
+// [K x 16] block is stored fragment by fragment (64 bytes of k per column),
+// lane l = column l%16, 16-byte piece l/16.  One wave-wide 16-byte load is then
+// one contiguous kilobyte, for the weights (A operand) and the activations (B
+// operand) alike, and building / splitting the dynamic batch is pure indexing.
 #include "kernels.h"
 
 namespace tts {
@@ -27,13 +34,17 @@ __device__ __forceinline__ uint16_t f2bf_bits(float f)
     u += 0x7FFFu + ((u >> 16) & 1u);
     return (uint16_t)(u >> 16);
 }
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
+{
+    return (uint32_t)f2bf_bits(lo) | ((uint32_t)f2bf_bits(hi) << 16);
+}
 template <typename T> __device__ __forceinline__ T from_float(float x);
 template <> __device__ __forceinline__ float from_float<float>(float x) { return x; }
 template <> __device__ __forceinline__ bf16_t from_float<bf16_t>(float x) { bf16_t r; r.bits = f2bf_bits(x); return r; }
 
-__device__ __forceinline__ float sigmoidf_(float x) { return 1.0f / (1.0f + __expf(-x)); }
-// 1 - 2/(1+e^{2x}): absolute error ~1e-7, saturates cleanly at +-1
-__device__ __forceinline__ float tanhf_(float x) { return 1.0f - 2.0f / (1.0f + __expf(2.0f * x)); }
+__device__ __forceinline__ float sigmoidf_(float x) { return __builtin_amdgcn_rcpf(1.0f + __expf(-x)); }
+// 1 - 2/(1+e^{2x}) with the hardware reciprocal (1 ulp): absolute error ~1e-7, saturates cleanly at +-1
+__device__ __forceinline__ float tanhf_(float x) { return 1.0f - 2.0f * __builtin_amdgcn_rcpf(1.0f + __expf(2.0f * x)); }
 
 __device__ __forceinline__ float wave_sum(float x)
 {
@@ -67,7 +78,26 @@ template <> struct Vec16<bf16_t> {
     }
 };
 
-// D(16x16) += A(16 x 64B of k) * B(64B of k x 16): one fragment pair.
+// Fragment geometry for element type T: a fragment is 64 bytes of k per row / column.
+template <typename T> struct Frag {
+    static constexpr int KB = 64 / (int)sizeof(T);    // k elements per fragment
+    static constexpr int EPL = 16 / (int)sizeof(T);   // k elements per lane
+};
+
+// element offset of (slot, k) in a slot-tiled activation array with NK fragments per tile
+template <typename T>
+__device__ __forceinline__ size_t xoff(int NK, int slot, int k)
+{
+    constexpr int KB = Frag<T>::KB, EPL = Frag<T>::EPL;
+    return ((((size_t)(slot >> 4) * NK + k / KB) * 64) + (slot & 15) + 16 * ((k % KB) / EPL)) * EPL + (k % EPL);
+}
+// uint4 index of fragment `frag` of tile `tile`, lane `lane`
+__device__ __forceinline__ size_t xfrag(int NK, int tile, int frag, int lane)
+{
+    return ((size_t)tile * NK + frag) * 64 + lane;
+}
+
+// D(16x16) += A(16 x 64B of k) * B(64B of k x 16): one fragment each.
 // Lane l of A holds row l%16, bytes [16*(l/16), +16) of that row's 64-byte k chunk;
 // lane l of B the same for column l%16.  A and B use the same k <-> (lane group,
 // element) map, so the contraction is over the whole chunk whatever order the
@@ -88,366 +118,659 @@ template <> __device__ __forceinline__ floatx4 mfma_frag<float>(const uint4& a, 
 
 // ---------------------------------------------------------------------------
 // LSTM gates + cell.  Workgroup b owns hidden units 4b..4b+3 (16 gate rows in
-// unit-major, gate-minor order) for the whole pool; its waves split K.
+// unit-major, gate-minor order) for every pool tile; its waves split K.
 //   gates = W [x] + b;  c <- sig(f) c + sig(i) tanh(g);  h <- sig(o) tanh(c)
+// The accumulator of lane l is (column l%16, gates i,f,g,o of unit l/16): the
+// cell update needs no data movement beyond the cross-wave reduction.
 // ---------------------------------------------------------------------------
 constexpr int LSTM_WAVES = 8;
 
 template <typename XT, int K>
 __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm(
-    const uint4* __restrict__ Wfrag, const float* __restrict__ bias, const XT* __restrict__ X,
-    float* __restrict__ c_state, XT* __restrict__ hout0, int stride0, int off0,
-    XT* __restrict__ hout1, int stride1, int off1,
-    const int* __restrict__ table, const int* __restrict__ done)
+    const uint4* __restrict__ Wfrag, const float* __restrict__ bias, const uint4* __restrict__ X,
+    float* __restrict__ c_state, XT* __restrict__ hout0, int nk0, int off0,
+    XT* __restrict__ hout1, int nk1, int off1,
+    const int* __restrict__ table, const int* __restrict__ live, const int* __restrict__ done)
 {
     constexpr int NW = LSTM_WAVES;
-    constexpr int KB = 64 / (int)sizeof(XT);   // k elements per fragment
-    constexpr int NK = K / KB;
-    constexpr int NF = NK / NW;
+    constexpr int NK = K / Frag<XT>::KB;      // fragments per row tile / per pool tile
+    constexpr int NF = NK / NW;               // fragments per wave
     static_assert(NK % NW == 0, "K must split evenly over the waves");
-    constexpr int EPL = 16 / (int)sizeof(XT);  // elements per lane per fragment
+    constexpr int TIF = sizeof(XT) == 2 ? 4 : 1;   // pool tiles whose activations are in flight together
 
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int rt = blockIdx.x;
-    const int P = table[0];
-    if (P <= 0) return;
 
+    // this workgroup's slice of the gate matrix: the only HBM stream, requested first
     uint4 a[NF];
 #pragma unroll
-    for (int f = 0; f < NF; ++f) a[f] = Wfrag[((size_t)rt * NK + (wave + f * NW)) * 64 + lane];
+    for (int f = 0; f < NF; ++f) a[f] = Wfrag[xfrag(NK, rt, wave + f * NW, lane)];
+
+    const int n_tiles = table[1];
+    // the first four waves also own the cell update of (pool tile in flight = wave, lane)
+    const int unit = rt * 4 + (lane >> 4);
+    floatx4 bias4 = {0.f, 0.f, 0.f, 0.f};
+    if (wave < 4) bias4 = *reinterpret_cast<const floatx4*>(bias + unit * 4);
 
     __shared__ floatx4 red[NW][4][64];
 
-    for (int pc = 0; pc < P; pc += 64) {
+    for (int tg = 0; tg < n_tiles; tg += 4) {
+        int slotE = -1;
+        float c_old = 0.f;
+        if (wave < 4 && tg + wave < n_tiles) {
+            const int sl = table[TABLE_TILES + tg + wave] * 16 + (lane & 15);
+            if (live[sl] && !done[sl]) {
+                slotE = sl;
+                c_old = c_state[(size_t)sl * HID + unit];
+            }
+        }
 #pragma unroll
-        for (int nt = 0; nt < 4; ++nt) {
-            const int p0 = pc + nt * 16;
-            if (p0 < P) {
-                const int pi = p0 + (lane & 15);
-                const bool valid = pi < P;
-                const int slot = valid ? table[TABLE_HDR + pi] : 0;
-                const XT* xrow = X + (size_t)slot * K + (lane >> 4) * EPL;
-                uint4 b[NF];
+        for (int t0 = 0; t0 < 4; t0 += TIF) {
+            uint4 b[TIF][NF];
 #pragma unroll
-                for (int f = 0; f < NF; ++f) {
-                    b[f] = make_uint4(0, 0, 0, 0);
-                    if (valid) b[f] = *reinterpret_cast<const uint4*>(xrow + (wave + f * NW) * KB);
+            for (int t = 0; t < TIF; ++t) {
+                if (tg + t0 + t < n_tiles) {
+                    const int tile = table[TABLE_TILES + tg + t0 + t];
+#pragma unroll
+                    for (int f = 0; f < NF; ++f) b[t][f] = X[xfrag(NK, tile, wave + f * NW, lane)];
                 }
-                floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+            }
 #pragma unroll
-                for (int f = 0; f < NF; ++f) acc = mfma_frag<XT>(a[f], b[f], acc);
-                red[wave][nt][lane] = acc;
+            for (int t = 0; t < TIF; ++t) {
+                if (tg + t0 + t < n_tiles) {
+                    floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int f = 0; f < NF; ++f) acc = mfma_frag<XT>(a[f], b[t][f], acc);
+                    red[wave][t0 + t][lane] = acc;
+                }
             }
         }
         __syncthreads();
-        if (threadIdx.x < 256) {
-            const int nt = threadIdx.x >> 6;
-            const int pi = pc + nt * 16 + (lane & 15);
-            if (pi < P) {
-                const int slot = table[TABLE_HDR + pi];
-                if (!done[slot]) {
-                    const int unit = rt * 4 + (lane >> 4);
-                    floatx4 g = *reinterpret_cast<const floatx4*>(bias + unit * 4);
+        if (slotE >= 0) {
+            floatx4 g = bias4;
 #pragma unroll
-                    for (int w = 0; w < NW; ++w) g += red[w][nt][lane];
-                    const float gi = sigmoidf_(g[0]), gf = sigmoidf_(g[1]);
-                    const float gg = tanhf_(g[2]), go = sigmoidf_(g[3]);
-                    const size_t ci = (size_t)slot * HID + unit;
-                    const float c = gf * c_state[ci] + gi * gg;
-                    c_state[ci] = c;
-                    const XT h = from_float<XT>(go * tanhf_(c));
-                    hout0[(size_t)slot * stride0 + off0 + unit] = h;
-                    hout1[(size_t)slot * stride1 + off1 + unit] = h;
-                }
-            }
+            for (int w = 0; w < NW; ++w) g += red[w][wave][lane];
+            const float gi = sigmoidf_(g[0]), gf = sigmoidf_(g[1]);
+            const float gg = tanhf_(g[2]), go = sigmoidf_(g[3]);
+            const float c = gf * c_old + gi * gg;
+            c_state[(size_t)slotE * HID + unit] = c;
+            const XT h = from_float<XT>(go * tanhf_(c));
+            hout0[xoff<XT>(nk0, slotE, off0 + unit)] = h;
+            hout1[xoff<XT>(nk1, slotE, off1 + unit)] = h;
         }
         __syncthreads();
     }
 }
 
 // ---------------------------------------------------------------------------
-// Location-sensitive attention, one workgroup per request.
+// Location-sensitive attention, one workgroup (8 waves) per request:
 //   q = W_q h_att
-//   loc[j][f] = sum_c sum_k Kc[f][c][k] u_c[j+k-15]      (u = W_last, W_acc; zero outside [0,L))
+//   loc[j][f] = sum_c sum_k Kc[f][c][k] u_c[j+k-15]         (u = W_last, W_acc; zero outside [0,L))
 //   e_j = v . tanh(q + W_loc loc[j] + PM[j])
 //   w = softmax_{j<L}(e);  A = sum_j w_j F[j];  W_last <- w;  W_acc <- W_acc + w
+// All three contractions run on MFMA with 16 positions (or, for q, 16 copies
+// of h_att) as the columns:
+//   q      (128 x 16, K split over the waves) = W_q * h_att
+//   loc^T  (32 x 16)          = Kc (32 x 64 taps) * U^T (64 taps x 16 positions)
+//   pl^T   (128 x 16)         = W_loc (128 x 32)  * loc^T
+// The accumulator layout of loc^T is exactly the B-operand layout of the next
+// product once the filter index is walked in the order the lanes hold it, so
+// nothing moves between the two.  The rows of W_loc are permuted so that lane
+// group g ends up with attention dims 32g..32g+31: its slice of PM[j] is one
+// contiguous run.  The constant A operands come pre-arranged per lane.
 // ---------------------------------------------------------------------------
+constexpr int LSA_THREADS = 512;
+constexpr int LSA_WAVES = LSA_THREADS / 64;
+constexpr int LSA_UPAD = MAX_ENC_LEN + 48;
+
+template <typename XT> struct LsaTile;
+
+// fp32: v_mfma_f32_16x16x4_f32, lane group g supplies k = g of each 4-wide step
+template <> struct LsaTile<float> {
+    float kA[2][16];   // [mt][c*8+s]: filter 16 mt + jl, tap 4 s + g of channel c
+    float4 wA[8][2];   // [at][mt]: W_loc row 32 (jl/4) + 4 at + jl%4, filters 16 mt + 4 g .. +3
+    __device__ __forceinline__ void load(const DevPtrs& d, int lane)
+    {
+        const float* kf = reinterpret_cast<const float*>(d.lsa_kfrag);
+        const float4* wf = reinterpret_cast<const float4*>(d.lsa_wfrag);
+#pragma unroll
+        for (int i = 0; i < 32; ++i) kA[i >> 4][i & 15] = kf[i * 64 + lane];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) wA[i >> 1][i & 1] = wf[i * 64 + lane];
+    }
+    // x0 = index into s_u of this lane's position at tap 0
+    __device__ __forceinline__ void run(const float* u0, const float* u1, int x0, int g, floatx4* pl) const
+    {
+        floatx4 loc0 = {0.f, 0.f, 0.f, 0.f}, loc1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int cs = 0; cs < 16; ++cs) {
+            const float b = (cs < 8 ? u0 : u1)[x0 + g + 4 * (cs & 7)];
+            loc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(kA[0][cs], b, loc0, 0, 0, 0);
+            loc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(kA[1][cs], b, loc1, 0, 0, 0);
+        }
+#pragma unroll
+        for (int at = 0; at < 8; ++at) {
+            floatx4 p = {0.f, 0.f, 0.f, 0.f};
+            p = __builtin_amdgcn_mfma_f32_16x16x4f32(wA[at][0].x, loc0[0], p, 0, 0, 0);
+            p = __builtin_amdgcn_mfma_f32_16x16x4f32(wA[at][0].y, loc0[1], p, 0, 0, 0);
+            p = __builtin_amdgcn_mfma_f32_16x16x4f32(wA[at][0].z, loc0[2], p, 0, 0, 0);
+            p = __builtin_amdgcn_mfma_f32_16x16x4f32(wA[at][0].w, loc0[3], p, 0, 0, 0);
+            p = __builtin_amdgcn_mfma_f32_16x16x4f32(wA[at][1].x, loc1[0], p, 0, 0, 0);
+            p = __builtin_amdgcn_mfma_f32_16x16x4f32(wA[at][1].y, loc1[1], p, 0, 0, 0);
+            p = __builtin_amdgcn_mfma_f32_16x16x4f32(wA[at][1].z, loc1[2], p, 0, 0, 0);
+            p = __builtin_amdgcn_mfma_f32_16x16x4f32(wA[at][1].w, loc1[3], p, 0, 0, 0);
+            pl[at] = p;
+        }
+    }
+};
+
+// bf16: v_mfma_f32_16x16x32_bf16, lane group g supplies 8 k values per step
+template <> struct LsaTile<bf16_t> {
+    uint4 kA[2][2];    // [mt][c]: filter 16 mt + jl, taps 8 g .. 8 g + 7 of channel c
+    uint4 wA[8];       // [at]: W_loc row 32 (jl/4) + 4 at + jl%4, filters {4g..4g+3, 16+4g..16+4g+3}
+    __device__ __forceinline__ void load(const DevPtrs& d, int lane)
+    {
+        const uint4* kf = reinterpret_cast<const uint4*>(d.lsa_kfrag);
+        const uint4* wf = reinterpret_cast<const uint4*>(d.lsa_wfrag);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) kA[i >> 1][i & 1] = kf[i * 64 + lane];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) wA[i] = wf[i * 64 + lane];
+    }
+    __device__ __forceinline__ void run(const float* u0, const float* u1, int x0, int g, floatx4* pl) const
+    {
+        floatx4 loc0 = {0.f, 0.f, 0.f, 0.f}, loc1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+            const float* u = (c == 0 ? u0 : u1) + x0 + 8 * g;
+            uint4 b;
+            b.x = pack_bf16x2(u[0], u[1]); b.y = pack_bf16x2(u[2], u[3]);
+            b.z = pack_bf16x2(u[4], u[5]); b.w = pack_bf16x2(u[6], u[7]);
+            loc0 = mfma_frag<bf16_t>(kA[0][c], b, loc0);
+            loc1 = mfma_frag<bf16_t>(kA[1][c], b, loc1);
+        }
+        uint4 bl;
+        bl.x = pack_bf16x2(loc0[0], loc0[1]); bl.y = pack_bf16x2(loc0[2], loc0[3]);
+        bl.z = pack_bf16x2(loc1[0], loc1[1]); bl.w = pack_bf16x2(loc1[2], loc1[3]);
+#pragma unroll
+        for (int at = 0; at < 8; ++at) {
+            floatx4 z = {0.f, 0.f, 0.f, 0.f};
+            pl[at] = mfma_frag<bf16_t>(wA[at], bl, z);
+        }
+    }
+};
+
 template <typename XT, typename MT>
-__global__ __launch_bounds__(256) void k_lsa(DevPtrs d, int cur)
+__global__ __launch_bounds__(LSA_THREADS) void k_lsa(DevPtrs d, int cur)
 {
     const int pi = blockIdx.x;
     if (pi >= d.table[0]) return;
-    const int slot = d.table[TABLE_HDR + pi];
+    const int slot = d.table[TABLE_SLOTS + pi];
     if (d.done[slot]) return;
     const int L = d.L[slot];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int jl = lane & 15, g = lane >> 4;
+    const int ntile = (L + 15) >> 4;
 
-    __shared__ float s_q[ATT];
-    __shared__ float s_v[ATT];
-    __shared__ __attribute__((aligned(16))) float s_K[2 * LOC_K * LOC_F];
-    __shared__ __attribute__((aligned(16))) float s_Wl[ATT * LOC_F];
-    __shared__ float s_u[2][MAX_ENC_LEN + 2 * LOC_PAD + 2];
+    __shared__ __attribute__((aligned(16))) float s_q[ATT];
+    __shared__ __attribute__((aligned(16))) float s_v[ATT];
+    __shared__ float s_u[2][LSA_UPAD];            // s_u[c][x] = u_c[x - 15]
     __shared__ float s_e[MAX_ENC_LEN];
-    __shared__ float s_red[8];
-    __shared__ __attribute__((aligned(16))) float s_ctx[4][ENC];
+    __shared__ float s_red[2 * LSA_WAVES];
+    __shared__ __attribute__((aligned(16))) float s_ctx[LSA_WAVES][ENC];   // also the partial q sums
 
-    // ---- stage small weights and the two weight histories
-    for (int i = tid; i < 2 * LOC_K * LOC_F; i += 256) s_K[i] = d.KcT[i];
-    for (int i = tid; i < ATT * LOC_F; i += 256) s_Wl[i] = d.Wloc[i];
-    if (tid < ATT) s_v[tid] = d.v[tid];
-    const float* wl = d.w_last + (size_t)slot * d.max_enc_len;
-    const float* wa = d.w_acc + (size_t)slot * d.max_enc_len;
-    for (int i = tid; i < L + 2 * LOC_PAD; i += 256) {
-        const int j = i - LOC_PAD;
+    constexpr int KB = Frag<XT>::KB;
+    constexpr int NPM = Vec16<MT>::N;
+    constexpr int NV = 32 / NPM;                  // 16-byte pieces of a lane's 32 attention dims of PM[j]
+    const MT* PMs = reinterpret_cast<const MT*>(d.PM) + (size_t)slot * d.max_enc_len * ATT + 32 * g;
+    const float* wl = d.w_last[cur] + (size_t)slot * d.max_enc_len;
+    const float* wa = d.w_acc[cur] + (size_t)slot * d.max_enc_len;
+
+    // ---- everything the prologue needs is requested before anything is consumed
+    // q = W_q h_att: wave w contracts k in [128 w, 128 w + 128) for all 128 outputs
+    constexpr int NKQ = HID / KB;                 // fragments per row tile of W_q
+    constexpr int NKW = NKQ / LSA_WAVES;          // fragments per wave
+    constexpr int MG = sizeof(XT) == 2 ? 8 : 2;   // row tiles whose fragments are in flight together
+    const uint4* Wq = reinterpret_cast<const uint4*>(d.Wq) + (size_t)(wave * NKW) * 64 + lane;
+    // B operand: every column is this request's h_att (column slot%16 of its tile)
+    const uint4* hx = reinterpret_cast<const uint4*>(d.xdec[cur]) +
+                      xfrag(K_DEC / KB, slot >> 4, XD_HA / KB + wave * NKW, (slot & 15) + 16 * g);
+    uint4 hb[NKW];
+#pragma unroll
+    for (int f = 0; f < NKW; ++f) hb[f] = hx[(size_t)f * 64];
+    uint4 qa[MG][NKW];
+#pragma unroll
+    for (int m = 0; m < MG; ++m)
+#pragma unroll
+        for (int f = 0; f < NKW; ++f) qa[m][f] = Wq[((size_t)m * NKQ + f) * 64];
+
+    constexpr int UPT = (LSA_UPAD + LSA_THREADS - 1) / LSA_THREADS;
+    float ul[UPT], ua[UPT];
+#pragma unroll
+    for (int i = 0; i < UPT; ++i) {
+        const int j = tid + i * LSA_THREADS - LOC_PAD;
         const bool in = (j >= 0 && j < L);
-        s_u[0][i] = in ? wl[j] : 0.f;
-        s_u[1][i] = in ? wa[j] : 0.f;
+        ul[i] = in ? wl[j] : 0.f;
+        ua[i] = in ? wa[j] : 0.f;
+    }
+    const float vreg = tid < ATT ? d.v[tid] : 0.f;
+    LsaTile<XT> tile;
+    if constexpr (sizeof(XT) == 2) tile.load(d, lane);   // the fp32 operands are too many registers to hold this early
+    constexpr bool PM_AHEAD = sizeof(XT) == 2;    // fp32 operands leave no registers for a second PM row
+    uint4 pmv[NV];
+    if constexpr (PM_AHEAD) {
+        const MT* pm = PMs + (size_t)min(wave * 16 + jl, L - 1) * ATT;
+#pragma unroll
+        for (int i = 0; i < NV; ++i) pmv[i] = *reinterpret_cast<const uint4*>(pm + i * NPM);
     }
 
-    // ---- q = W_q h_att: each wave 32 outputs, lanes stride k in 16-byte pieces
-    {
-        constexpr int N = Vec16<XT>::N;
-        constexpr int CH = HID / N / 64;     // 16-byte chunks per lane
-        const XT* h = reinterpret_cast<const XT*>(d.xdec[cur]) + (size_t)slot * K_DEC + XD_HA;
-        float hv[CH][N];
+    // ---- q partial sums
 #pragma unroll
-        for (int c = 0; c < CH; ++c)
-            Vec16<XT>::unpack(*reinterpret_cast<const uint4*>(h + (lane + 64 * c) * N), hv[c]);
-        const XT* Wq = reinterpret_cast<const XT*>(d.Wq);
-        for (int o = wave * 32; o < wave * 32 + 32; ++o) {
-            float acc = 0.f;
+    for (int m0 = 0; m0 < 8; m0 += MG) {
+        if (m0 > 0) {
 #pragma unroll
-            for (int c = 0; c < CH; ++c) {
-                float wv[N];
-                Vec16<XT>::unpack(*reinterpret_cast<const uint4*>(Wq + (size_t)o * HID + (lane + 64 * c) * N), wv);
+            for (int m = 0; m < MG; ++m)
 #pragma unroll
-                for (int i = 0; i < N; ++i) acc += wv[i] * hv[c][i];
-            }
-            acc = wave_sum(acc);
-            if (lane == 0) s_q[o] = acc;
+                for (int f = 0; f < NKW; ++f) qa[m][f] = Wq[((size_t)(m0 + m) * NKQ + f) * 64];
         }
+#pragma unroll
+        for (int m = 0; m < MG; ++m) {
+            floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int f = 0; f < NKW; ++f) acc = mfma_frag<XT>(qa[m][f], hb[f], acc);
+            // every column holds the same h: take column 0
+            if (jl == 0) *reinterpret_cast<floatx4*>(&s_ctx[wave][16 * (m0 + m) + 4 * g]) = acc;
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < UPT; ++i) {
+        const int x = tid + i * LSA_THREADS;
+        if (x < ntile * 16 + 32) {
+            s_u[0][x] = ul[i];
+            s_u[1][x] = ua[i];
+        }
+    }
+    if (tid < ATT) s_v[tid] = vreg;
+    if constexpr (sizeof(XT) == 4) tile.load(d, lane);
+    __syncthreads();
+    if (tid < ATT) {
+        float q = 0.f;
+#pragma unroll
+        for (int w = 0; w < LSA_WAVES; ++w) q += s_ctx[w][tid];
+        s_q[tid] = q;
     }
     __syncthreads();
 
-    // ---- energies, one position per thread
-    const MT* PMs = reinterpret_cast<const MT*>(d.PM) + (size_t)slot * d.max_enc_len * ATT;
-    for (int j = tid; j < L; j += 256) {
-        float loc[LOC_F];
+    // ---- energies, one 16-position tile per wave at a time; PM of the next tile is already in flight
+    for (int tt = wave; tt < ntile; tt += LSA_WAVES) {
+        const int j = tt * 16 + jl;
+        uint4 pmc[NV];
+        if constexpr (PM_AHEAD) {
 #pragma unroll
-        for (int f = 0; f < LOC_F; ++f) loc[f] = 0.f;
-        for (int c = 0; c < 2; ++c)
-            for (int k = 0; k < LOC_K; ++k) {
-                const float u = s_u[c][j + k];
-                const float4* kk = reinterpret_cast<const float4*>(&s_K[(c * LOC_K + k) * LOC_F]);
+            for (int i = 0; i < NV; ++i) pmc[i] = pmv[i];
+            // unconditional: past the end it re-reads the last row, which is never used
+            const MT* pm = PMs + (size_t)min(j + LSA_WAVES * 16, L - 1) * ATT;
 #pragma unroll
-                for (int f4 = 0; f4 < LOC_F / 4; ++f4) {
-                    const float4 kv = kk[f4];
-                    loc[4 * f4 + 0] += kv.x * u; loc[4 * f4 + 1] += kv.y * u;
-                    loc[4 * f4 + 2] += kv.z * u; loc[4 * f4 + 3] += kv.w * u;
-                }
-            }
-        constexpr int N = Vec16<MT>::N;
-        const MT* pm = PMs + (size_t)j * ATT;
-        float e = 0.f;
-        for (int a0 = 0; a0 < ATT; a0 += N) {
-            float pv[N];
-            Vec16<MT>::unpack(*reinterpret_cast<const uint4*>(pm + a0), pv);
+            for (int i = 0; i < NV; ++i) pmv[i] = *reinterpret_cast<const uint4*>(pm + i * NPM);
+        } else {
+            const MT* pm = PMs + (size_t)min(j, L - 1) * ATT;
 #pragma unroll
-            for (int i = 0; i < N; ++i) {
-                const int a = a0 + i;
-                const float4* wr = reinterpret_cast<const float4*>(&s_Wl[a * LOC_F]);
-                float pl = 0.f;
-#pragma unroll
-                for (int f4 = 0; f4 < LOC_F / 4; ++f4) {
-                    const float4 wv = wr[f4];
-                    pl += wv.x * loc[4 * f4 + 0] + wv.y * loc[4 * f4 + 1] + wv.z * loc[4 * f4 + 2] + wv.w * loc[4 * f4 + 3];
-                }
-                e += s_v[a] * tanhf_(s_q[a] + pl + pv[i]);
-            }
+            for (int i = 0; i < NV; ++i) pmc[i] = *reinterpret_cast<const uint4*>(pm + i * NPM);
         }
-        s_e[j] = e;
+        floatx4 pl[8];
+        tile.run(s_u[0], s_u[1], tt * 16 + jl, g, pl);
+        float e = 0.f;
+#pragma unroll
+        for (int at = 0; at < 8; ++at) {
+            // rows 4g..4g+3 of tile `at` are attention dims 32 g + 4 at + i
+            const float4 qv = *reinterpret_cast<const float4*>(&s_q[32 * g + 4 * at]);
+            const float4 vv = *reinterpret_cast<const float4*>(&s_v[32 * g + 4 * at]);
+            float pv[4];
+            if constexpr (sizeof(MT) == 2) {
+                const uint4& u = pmc[at >> 1];
+                const uint32_t w0 = (at & 1) ? u.z : u.x, w1 = (at & 1) ? u.w : u.y;
+                pv[0] = bf16_lo(w0); pv[1] = bf16_hi(w0); pv[2] = bf16_lo(w1); pv[3] = bf16_hi(w1);
+            } else {
+                Vec16<float>::unpack(pmc[at], pv);
+            }
+            e += vv.x * tanhf_(qv.x + pl[at][0] + pv[0]);
+            e += vv.y * tanhf_(qv.y + pl[at][1] + pv[1]);
+            e += vv.z * tanhf_(qv.z + pl[at][2] + pv[2]);
+            e += vv.w * tanhf_(qv.w + pl[at][3] + pv[3]);
+        }
+        e += __shfl_xor(e, 16, 64);
+        e += __shfl_xor(e, 32, 64);
+        if (g == 0 && j < L) s_e[j] = e;
+    }
+
+    // ---- context: wave w takes positions w, w+8, ...; lane takes 8 columns; NR rows in flight.
+    // The first batch of encoder rows is requested before the softmax needs its barriers.
+    constexpr int NR = sizeof(MT) == 2 ? 16 : 8;
+    constexpr int VPR = 8 * (int)sizeof(MT) / 16;   // 16-byte loads per row per lane
+    const MT* Fm = reinterpret_cast<const MT*>(d.Fmem) + (size_t)slot * d.max_enc_len * ENC + lane * 8;
+    uint4 rows[NR][VPR];
+#pragma unroll
+    for (int r = 0; r < NR; ++r) {
+        const MT* row = Fm + (size_t)min(wave + r * LSA_WAVES, L - 1) * ENC;
+#pragma unroll
+        for (int v = 0; v < VPR; ++v) rows[r][v] = *reinterpret_cast<const uint4*>(row + v * NPM);
     }
     __syncthreads();
 
     // ---- ragged softmax over j < L
     float mx = -INFINITY;
-    for (int j = tid; j < L; j += 256) mx = fmaxf(mx, s_e[j]);
+    for (int x = tid; x < L; x += LSA_THREADS) mx = fmaxf(mx, s_e[x]);
     mx = wave_max(mx);
     if (lane == 0) s_red[wave] = mx;
     __syncthreads();
-    mx = fmaxf(fmaxf(s_red[0], s_red[1]), fmaxf(s_red[2], s_red[3]));
+    mx = s_red[0];
+#pragma unroll
+    for (int w = 1; w < LSA_WAVES; ++w) mx = fmaxf(mx, s_red[w]);
     float sum = 0.f;
-    for (int j = tid; j < L; j += 256) {
-        const float p = __expf(s_e[j] - mx);
-        s_e[j] = p;
+    for (int x = tid; x < L; x += LSA_THREADS) {
+        const float p = __expf(s_e[x] - mx);
+        s_e[x] = p;
         sum += p;
     }
     sum = wave_sum(sum);
-    if (lane == 0) s_red[4 + wave] = sum;
+    if (lane == 0) s_red[LSA_WAVES + wave] = sum;
     __syncthreads();
-    const float inv = 1.0f / (s_red[4] + s_red[5] + s_red[6] + s_red[7]);
-    float* wl_out = d.w_last + (size_t)slot * d.max_enc_len;
-    float* wa_out = d.w_acc + (size_t)slot * d.max_enc_len;
-    for (int j = tid; j < L; j += 256) {
-        const float w = s_e[j] * inv;
-        s_e[j] = w;
-        wl_out[j] = w;
-        wa_out[j] = s_u[1][j + LOC_PAD] + w;
-    }
-    __syncthreads();
+    sum = 0.f;
+#pragma unroll
+    for (int w = 0; w < LSA_WAVES; ++w) sum += s_red[LSA_WAVES + w];
+    const float inv = 1.0f / sum;
 
-    // ---- context: wave w takes rows j = w, w+4, ...; lane takes 8 columns
     {
-        const MT* Fm = reinterpret_cast<const MT*>(d.Fmem) + (size_t)slot * d.max_enc_len * ENC;
         float acc[8];
 #pragma unroll
         for (int i = 0; i < 8; ++i) acc[i] = 0.f;
-        for (int j = wave; j < L; j += 4) {
-            const float w = s_e[j];
-            const MT* row = Fm + (size_t)j * ENC + lane * 8;
-            float fv[8];
-            if constexpr (sizeof(MT) == 2) {
-                Vec16<MT>::unpack(*reinterpret_cast<const uint4*>(row), fv);
-            } else {
-                Vec16<MT>::unpack(*reinterpret_cast<const uint4*>(row), fv);
-                Vec16<MT>::unpack(*reinterpret_cast<const uint4*>(row + 4), fv + 4);
-            }
+        for (int x0 = wave; x0 < L; x0 += LSA_WAVES * NR) {
 #pragma unroll
-            for (int i = 0; i < 8; ++i) acc[i] += w * fv[i];
+            for (int r = 0; r < NR; ++r) {
+                const int x = x0 + r * LSA_WAVES;
+                const float w = x < L ? s_e[x] : 0.f;
+                float fv[8];
+#pragma unroll
+                for (int v = 0; v < VPR; ++v) Vec16<MT>::unpack(rows[r][v], fv + v * NPM);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) acc[i] += w * fv[i];
+                // refill this register row with the row NR rounds ahead (unconditional: past
+                // the end it re-reads the last row with weight zero)
+                const MT* row = Fm + (size_t)min(x + NR * LSA_WAVES, L - 1) * ENC;
+#pragma unroll
+                for (int v = 0; v < VPR; ++v) rows[r][v] = *reinterpret_cast<const uint4*>(row + v * NPM);
+            }
         }
 #pragma unroll
         for (int i = 0; i < 8; ++i) s_ctx[wave][lane * 8 + i] = acc[i];
     }
     __syncthreads();
-    XT* xa = reinterpret_cast<XT*>(d.xatt[cur ^ 1]) + (size_t)slot * K_ATT + XA_A;
-    XT* xd = reinterpret_cast<XT*>(d.xdec[cur]) + (size_t)slot * K_DEC + XD_A;
-    for (int k = tid; k < ENC; k += 256) {
-        const XT a = from_float<XT>(s_ctx[0][k] + s_ctx[1][k] + s_ctx[2][k] + s_ctx[3][k]);
-        xa[k] = a;
-        xd[k] = a;
+
+    XT* xa = reinterpret_cast<XT*>(d.xatt[cur ^ 1]);
+    XT* xd = reinterpret_cast<XT*>(d.xdec[cur]);
+    float* wl_out = d.w_last[cur ^ 1] + (size_t)slot * d.max_enc_len;
+    float* wa_out = d.w_acc[cur ^ 1] + (size_t)slot * d.max_enc_len;
+    for (int k = tid; k < ENC; k += LSA_THREADS) {
+        float c = 0.f;
+#pragma unroll
+        for (int w = 0; w < LSA_WAVES; ++w) c += s_ctx[w][k];
+        const XT a = from_float<XT>(c * inv);
+        xa[xoff<XT>(K_ATT / KB, slot, XA_A + k)] = a;
+        xd[xoff<XT>(K_DEC / KB, slot, XD_A + k)] = a;
+    }
+    for (int x = tid; x < L; x += LSA_THREADS) {
+        const float w = s_e[x] * inv;
+        wl_out[x] = w;
+        wa_out[x] = s_u[1][x + LOC_PAD] + w;
     }
 }
 
 // ---------------------------------------------------------------------------
-// Prenet of one frame held in LDS: p = relu(W2 relu(W1 m)), thread o < 256
-// computes output o.  Both matrices are stored transposed so lanes read
-// consecutive addresses.
+// Mel + stop projection of [H_dec; A] (Eq. 2 line 5), ring write, frame counter
+// and the prenet of the new frame (the Pre(M_last) of the next step), one
+// workgroup per pool tile (16 slots).  Three chained MFMA products with the
+// slots as the 16 columns:
+//   mel^T (96 x 16)  = W_proj (81 rows padded to 96, K = 1536, split over the waves) * Y^T
+//   hid^T (256 x 16) = relu(W_p1 (K = 80, zero padded) * mel^T)
+//   p^T   (256 x 16) = relu(W_p2 * hid^T)
 // ---------------------------------------------------------------------------
-template <typename XT>
-__device__ __forceinline__ float prenet_thread(const DevPtrs& d, const float* s_mel, float* s_hid, int o)
+constexpr int PROJ_THREADS = 512;
+constexpr int PROJ_WAVES = PROJ_THREADS / 64;
+constexpr int PROJ_ROWS = 96;
+
+template <typename XT> struct PrenetK1 { static constexpr int value = 80; };
+template <> struct PrenetK1<bf16_t> { static constexpr int value = 96; };
+
+// B fragment (16 bytes of XT) from 16/sizeof(XT) consecutive fp32 values in LDS
+template <typename XT> __device__ __forceinline__ uint4 frag_from_f32(const float* p);
+template <> __device__ __forceinline__ uint4 frag_from_f32<float>(const float* p)
 {
-    const XT* W1 = reinterpret_cast<const XT*>(d.Wp1T);
-    const XT* W2 = reinterpret_cast<const XT*>(d.Wp2T);
-    float acc = 0.f;
-    for (int k = 0; k < N_MEL; ++k) acc += to_float(W1[k * PRENET + o]) * s_mel[k];
-    s_hid[o] = fmaxf(acc, 0.f);
-    __syncthreads();
-    acc = 0.f;
-    for (int k = 0; k < PRENET; ++k) acc += to_float(W2[k * PRENET + o]) * s_hid[k];
-    return fmaxf(acc, 0.f);
+    return make_uint4(__float_as_uint(p[0]), __float_as_uint(p[1]), __float_as_uint(p[2]), __float_as_uint(p[3]));
+}
+template <> __device__ __forceinline__ uint4 frag_from_f32<bf16_t>(const float* p)
+{
+    return make_uint4(pack_bf16x2(p[0], p[1]), pack_bf16x2(p[2], p[3]), pack_bf16x2(p[4], p[5]), pack_bf16x2(p[6], p[7]));
 }
 
-// mel/stop projection of [H_dec; A], ring write, frame counter, prenet of the new frame
 template <typename XT>
-__global__ __launch_bounds__(256) void k_proj(DevPtrs d, int cur)
+__global__ __launch_bounds__(PROJ_THREADS) void k_proj(DevPtrs d, int cur)
 {
-    const int pi = blockIdx.x;
-    if (pi >= d.table[0]) return;
-    const int slot = d.table[TABLE_HDR + pi];
-    if (d.done[slot]) return;
+    if ((int)blockIdx.x >= d.table[1]) return;
+    const int tile = d.table[TABLE_TILES + blockIdx.x];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int jl = lane & 15, g = lane >> 4;
+    constexpr int KB = Frag<XT>::KB;
+    constexpr int EPL = Frag<XT>::EPL;
+    constexpr int NKD = K_DEC / KB;
 
-    __shared__ float s_mel[N_PROJ + 3];
-    __shared__ float s_hid[PRENET];
+    __shared__ __attribute__((aligned(16))) float s_big[PROJ_WAVES * PROJ_ROWS * 16];   // partial sums, later hid
+    __shared__ __attribute__((aligned(16))) float s_mel[16][PROJ_ROWS];
+    __shared__ int s_slot[16], s_t[16];
+    float (*s_part)[PROJ_ROWS][16] = reinterpret_cast<float (*)[PROJ_ROWS][16]>(s_big);
+    float (*s_hid)[PRENET] = reinterpret_cast<float (*)[PRENET]>(s_big);
 
-    constexpr int N = Vec16<XT>::N;
-    constexpr int CH = K_PROJ / N / 64;   // 16-byte chunks per lane: 3 (bf16) or 6 (fp32)
-    const XT* hd = reinterpret_cast<const XT*>(d.xdec[cur ^ 1]) + (size_t)slot * K_DEC + XD_HD;
-    const XT* av = reinterpret_cast<const XT*>(d.xdec[cur]) + (size_t)slot * K_DEC + XD_A;
-    float yv[CH][N];
-#pragma unroll
-    for (int c = 0; c < CH; ++c) {
-        const int k = (lane + 64 * c) * N;
-        const XT* src = (k < HID) ? (hd + k) : (av + (k - HID));
-        Vec16<XT>::unpack(*reinterpret_cast<const uint4*>(src), yv[c]);
+    if (tid < 16) {
+        int sl = tile * 16 + tid, t = 0;
+        if (d.live[sl] && !d.done[sl]) t = d.t[sl]; else sl = -1;
+        s_slot[tid] = sl;
+        s_t[tid] = t;
     }
-    const XT* W = reinterpret_cast<const XT*>(d.Wmel);
-    for (int o = wave; o < N_PROJ; o += 4) {
-        float acc = 0.f;
+
+    // weights of the two prenet layers for this wave's row tiles: requested now, used at the end
+    constexpr int NK3 = PrenetK1<XT>::value / KB;
+    constexpr int NK4 = PRENET / KB;
+    uint4 a3[2][NK3], a4[2][NK4];
+    {
+        const uint4* W1 = reinterpret_cast<const uint4*>(d.Wp1) + lane;
+        const uint4* W2 = reinterpret_cast<const uint4*>(d.Wp2) + lane;
 #pragma unroll
-        for (int c = 0; c < CH; ++c) {
-            float wv[N];
-            Vec16<XT>::unpack(*reinterpret_cast<const uint4*>(W + (size_t)o * K_PROJ + (lane + 64 * c) * N), wv);
+        for (int m = 0; m < 2; ++m) {
+            const int mt = wave + m * PROJ_WAVES;
 #pragma unroll
-            for (int i = 0; i < N; ++i) acc += wv[i] * yv[c][i];
+            for (int f = 0; f < NK3; ++f) a3[m][f] = W1[((size_t)mt * NK3 + f) * 64];
+#pragma unroll
+            for (int f = 0; f < NK4; ++f) a4[m][f] = W2[((size_t)mt * NK4 + f) * 64];
         }
-        acc = wave_sum(acc);
-        if (lane == 0) s_mel[o] = acc + d.bmel[o];
+    }
+
+    // ---- phase 1: projection of [h_dec; a], K split over the waves
+    {
+        constexpr int NK = K_PROJ / KB;
+        constexpr int NKW = NK / PROJ_WAVES;
+        static_assert(NK % PROJ_WAVES == 0, "K must split evenly over the waves");
+        constexpr int MH = sizeof(XT) == 2 ? 3 : 1;   // row tiles whose fragments are in flight together
+        const uint4* xnew = reinterpret_cast<const uint4*>(d.xdec[cur ^ 1]);   // h_dec of this step
+        const uint4* xcur = reinterpret_cast<const uint4*>(d.xdec[cur]);       // a of this step
+        uint4 b[NKW];
+#pragma unroll
+        for (int f = 0; f < NKW; ++f) {
+            const int ks = wave * NKW + f;
+            b[f] = ks < HID / KB ? xnew[xfrag(NKD, tile, XD_HD / KB + ks, lane)]
+                                 : xcur[xfrag(NKD, tile, XD_A / KB + ks - HID / KB, lane)];
+        }
+        const uint4* W = reinterpret_cast<const uint4*>(d.Wmel) + lane;
+#pragma unroll
+        for (int m0 = 0; m0 < PROJ_ROWS / 16; m0 += MH) {
+            uint4 a[MH][NKW];
+#pragma unroll
+            for (int m = 0; m < MH; ++m)
+#pragma unroll
+                for (int f = 0; f < NKW; ++f) a[m][f] = W[((size_t)(m0 + m) * NK + wave * NKW + f) * 64];
+#pragma unroll
+            for (int m = 0; m < MH; ++m) {
+                floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int f = 0; f < NKW; ++f) acc = mfma_frag<XT>(a[m][f], b[f], acc);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) s_part[wave][16 * (m0 + m) + 4 * g + i][jl] = acc[i];
+            }
+        }
     }
     __syncthreads();
 
-    const int t = d.t[slot];
-    if (tid < N_MEL) {
-        d.mel_ring[((size_t)slot * d.max_steps + t) * N_MEL + tid] = s_mel[tid];
-        d.m_last[(size_t)slot * N_MEL + tid] = s_mel[tid];
+    // ---- phase 2: reduce, bias, hand the frame out
+    for (int idx = tid; idx < 16 * PROJ_ROWS; idx += PROJ_THREADS) {
+        const int o = idx >> 4, r = idx & 15;
+        float v = 0.f;
+        if (o < N_PROJ) {
+            v = d.bmel[o];
+#pragma unroll
+            for (int w = 0; w < PROJ_WAVES; ++w) v += s_part[w][o][r];
+        }
+        s_mel[r][o] = v;
     }
-    if (tid == N_MEL) d.stop_ring[(size_t)slot * d.max_steps + t] = s_mel[N_MEL];
+    __syncthreads();
+    for (int idx = tid; idx < 16 * N_PROJ; idx += PROJ_THREADS) {
+        const int r = idx / N_PROJ, o = idx - r * N_PROJ;
+        const int sl = s_slot[r];
+        if (sl >= 0) {
+            const float v = s_mel[r][o];
+            if (o < N_MEL) {
+                d.mel_ring[((size_t)sl * d.max_steps + s_t[r]) * N_MEL + o] = v;
+                d.m_last[(size_t)sl * N_MEL + o] = v;
+            } else {
+                d.stop_ring[(size_t)sl * d.max_steps + s_t[r]] = v;
+            }
+        }
+    }
 
-    const float p = prenet_thread<XT>(d, s_mel, s_hid, tid);
-    reinterpret_cast<XT*>(d.xatt[cur ^ 1])[(size_t)slot * K_ATT + XA_P + tid] = from_float<XT>(p);
+    // ---- phase 3: hid^T = relu(W_p1 mel^T); wave w owns row tiles w and w + 8
+    {
+        uint4 b[NK3];
+#pragma unroll
+        for (int f = 0; f < NK3; ++f) b[f] = frag_from_f32<XT>(&s_mel[jl][f * KB + g * EPL]);
+        floatx4 acc[2];
+#pragma unroll
+        for (int m = 0; m < 2; ++m) {
+            acc[m] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int f = 0; f < NK3; ++f) acc[m] = mfma_frag<XT>(a3[m][f], b[f], acc[m]);
+        }
+        // s_hid aliases the partial sums: every read of those finished before the last barrier
+#pragma unroll
+        for (int m = 0; m < 2; ++m)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) s_hid[jl][16 * (wave + m * PROJ_WAVES) + 4 * g + i] = fmaxf(acc[m][i], 0.f);
+    }
+    __syncthreads();
 
-    if (tid == 0) {
-        const int tn = t + 1;
-        d.t[slot] = tn;
-        bool fin = tn >= d.n_steps[slot];
-        if (d.stop_threshold >= 0.f && sigmoidf_(s_mel[N_MEL]) > d.stop_threshold) fin = true;
-        if (fin) d.done[slot] = 1;
+    // ---- phase 4: p^T = relu(W_p2 hid^T)
+    {
+        uint4 b[NK4];
+#pragma unroll
+        for (int f = 0; f < NK4; ++f) b[f] = frag_from_f32<XT>(&s_hid[jl][f * KB + g * EPL]);
+        const int sl = s_slot[jl];
+        XT* xa = reinterpret_cast<XT*>(d.xatt[cur ^ 1]);
+#pragma unroll
+        for (int m = 0; m < 2; ++m) {
+            const int mt = wave + m * PROJ_WAVES;
+            floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int f = 0; f < NK4; ++f) acc = mfma_frag<XT>(a4[m][f], b[f], acc);
+            if (sl >= 0) {
+                // four consecutive k inside one 16-byte piece
+                XT* dst = xa + xoff<XT>(K_ATT / KB, sl, XA_P + 16 * mt + 4 * g);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) dst[i] = from_float<XT>(fmaxf(acc[i], 0.f));
+            }
+        }
+    }
+
+    if (tid < 16 && s_slot[tid] >= 0) {
+        const int sl = s_slot[tid];
+        const int tn = s_t[tid] + 1;
+        d.t[sl] = tn;
+        bool fin = tn >= d.n_steps[sl];
+        if (d.stop_threshold >= 0.f && sigmoidf_(s_mel[tid][N_MEL]) > d.stop_threshold) fin = true;
+        if (fin) d.done[sl] = 1;
     }
 }
 
-// p = Pre(m_last) of one slot into both activation buffers
+// element (row, k) of a matrix stored in MFMA A-fragment order with NK fragments per row tile
+template <typename XT>
+__device__ __forceinline__ float frag_elem(const void* base, int NK, int row, int k)
+{
+    return to_float(reinterpret_cast<const XT*>(base)[xoff<XT>(NK, row, k)]);
+}
+
+// p = Pre(m_last) of one slot into both activation buffers (after a state overwrite; not on the step path)
 template <typename XT>
 __global__ __launch_bounds__(256) void k_prenet_slot(DevPtrs d, int slot)
 {
+    constexpr int KB = Frag<XT>::KB;
     __shared__ float s_mel[N_MEL];
     __shared__ float s_hid[PRENET];
-    if (threadIdx.x < N_MEL) s_mel[threadIdx.x] = d.m_last[(size_t)slot * N_MEL + threadIdx.x];
+    const int o = threadIdx.x;
+    if (o < N_MEL) s_mel[o] = d.m_last[(size_t)slot * N_MEL + o];
     __syncthreads();
-    const XT p = from_float<XT>(prenet_thread<XT>(d, s_mel, s_hid, threadIdx.x));
-    reinterpret_cast<XT*>(d.xatt[0])[(size_t)slot * K_ATT + XA_P + threadIdx.x] = p;
-    reinterpret_cast<XT*>(d.xatt[1])[(size_t)slot * K_ATT + XA_P + threadIdx.x] = p;
+    float acc = 0.f;
+    for (int k = 0; k < N_MEL; ++k) acc += frag_elem<XT>(d.Wp1, PrenetK1<XT>::value / KB, o, k) * to_float(from_float<XT>(s_mel[k]));
+    s_hid[o] = fmaxf(acc, 0.f);
+    __syncthreads();
+    acc = 0.f;
+    for (int k = 0; k < PRENET; ++k) acc += frag_elem<XT>(d.Wp2, PRENET / KB, o, k) * to_float(from_float<XT>(s_hid[k]));
+    const XT p = from_float<XT>(fmaxf(acc, 0.f));
+    for (int b = 0; b < 2; ++b) reinterpret_cast<XT*>(d.xatt[b])[xoff<XT>(K_ATT / KB, slot, XA_P + o)] = p;
 }
 
 // ---------------------------------------------------------------------------
 // Pool bookkeeping on the device
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void k_set_table(TableArgs a, int* table)
+__global__ __launch_bounds__(MAX_POOL) void k_set_table(TableArgs a, int* table, int* live)
 {
-    if (threadIdx.x == 0) table[0] = a.n_active;
-    if ((int)threadIdx.x < a.n_active) table[TABLE_HDR + threadIdx.x] = a.slot[threadIdx.x];
+    const int tid = threadIdx.x;
+    live[tid] = 0;
+    __syncthreads();
+    if (tid == 0) { table[0] = a.n_active; table[1] = a.n_tiles; }
+    if (tid < a.n_active) {
+        table[TABLE_SLOTS + tid] = a.slot[tid];
+        live[a.slot[tid]] = 1;
+    }
+    if (tid < a.n_tiles) table[TABLE_TILES + tid] = a.tile[tid];
 }
 
 // a joining request starts from all-zero state
 template <typename XT>
 __global__ __launch_bounds__(256) void k_slot_init(DevPtrs d, int slot, int L, int n_steps)
 {
+    constexpr int KB = Frag<XT>::KB;
     const int tid = threadIdx.x;
     const XT z = from_float<XT>(0.f);
     for (int b = 0; b < 2; ++b) {
-        XT* xa = reinterpret_cast<XT*>(d.xatt[b]) + (size_t)slot * K_ATT;
-        XT* xd = reinterpret_cast<XT*>(d.xdec[b]) + (size_t)slot * K_DEC;
-        for (int i = tid; i < K_ATT; i += 256) xa[i] = z;
-        for (int i = tid; i < K_DEC; i += 256) xd[i] = z;
+        XT* xa = reinterpret_cast<XT*>(d.xatt[b]);
+        XT* xd = reinterpret_cast<XT*>(d.xdec[b]);
+        for (int k = tid; k < K_ATT; k += 256) xa[xoff<XT>(K_ATT / KB, slot, k)] = z;
+        for (int k = tid; k < K_DEC; k += 256) xd[xoff<XT>(K_DEC / KB, slot, k)] = z;
+        for (int i = tid; i < d.max_enc_len; i += 256) {
+            d.w_last[b][(size_t)slot * d.max_enc_len + i] = 0.f;
+            d.w_acc[b][(size_t)slot * d.max_enc_len + i] = 0.f;
+        }
     }
     for (int i = tid; i < HID; i += 256) {
         d.c_att[(size_t)slot * HID + i] = 0.f;
         d.c_dec[(size_t)slot * HID + i] = 0.f;
     }
     if (tid < N_MEL) d.m_last[(size_t)slot * N_MEL + tid] = 0.f;
-    for (int i = tid; i < d.max_enc_len; i += 256) {
-        d.w_last[(size_t)slot * d.max_enc_len + i] = 0.f;
-        d.w_acc[(size_t)slot * d.max_enc_len + i] = 0.f;
-    }
     if (tid == 0) {
         d.L[slot] = L;
         d.t[slot] = 0;
@@ -474,47 +797,60 @@ __global__ __launch_bounds__(ATT) void k_join_memory(DevPtrs d, const float* __r
     reinterpret_cast<MT*>(d.PM)[((size_t)slot * d.max_enc_len + j) * ATT + tid] = from_float<MT>(acc);
 }
 
+// gather / scatter of one slot's piece of a slot-tiled activation array (state access, not on the step path)
+template <typename XT>
+__global__ __launch_bounds__(256) void k_x_get(const XT* X, int NK, int slot, int off, int n, float* out)
+{
+    for (int k = threadIdx.x; k < n; k += 256) out[k] = to_float(X[xoff<XT>(NK, slot, off + k)]);
+}
+template <typename XT>
+__global__ __launch_bounds__(256) void k_x_set(XT* X, int NK, int slot, int off, int n, const float* in)
+{
+    for (int k = threadIdx.x; k < n; k += 256) X[xoff<XT>(NK, slot, off + k)] = from_float<XT>(in[k]);
+}
+
 // ---------------------------------------------------------------------------
 // launch wrappers
 // ---------------------------------------------------------------------------
 template <typename XT, typename MT>
-static hipError_t step_typed(const DevPtrs& d, int nb, int cur, hipStream_t s, hipEvent_t* ev)
+static hipError_t step_typed(const DevPtrs& d, int n_req, int n_tiles, int cur, hipStream_t s, hipEvent_t* ev)
 {
+    constexpr int KB = Frag<XT>::KB;
     auto mark = [&](int i) { if (ev) (void)hipEventRecord(ev[i], s); };
-    mark(0);
-    XT* xatt_cur = reinterpret_cast<XT*>(d.xatt[cur]);
+    const uint4* xatt_cur = reinterpret_cast<const uint4*>(d.xatt[cur]);
     XT* xatt_nxt = reinterpret_cast<XT*>(d.xatt[cur ^ 1]);
     XT* xdec_cur = reinterpret_cast<XT*>(d.xdec[cur]);
     XT* xdec_nxt = reinterpret_cast<XT*>(d.xdec[cur ^ 1]);
+    mark(0);
     // H_att(t): consumed by this step's decoder LSTM / LSA and by the next step's attention LSTM
     hipLaunchKernelGGL((k_lstm<XT, K_ATT>), dim3(HID / 4), dim3(LSTM_WAVES * 64), 0, s,
-                       d.Wa, d.ba, xatt_cur, d.c_att, xdec_cur, K_DEC, XD_HA, xatt_nxt, K_ATT, XA_H,
-                       d.table, d.done);
+                       d.Wa, d.ba, xatt_cur, d.c_att, xdec_cur, K_DEC / KB, XD_HA, xatt_nxt, K_ATT / KB, XA_H,
+                       d.table, d.live, d.done);
     mark(1);
-    hipLaunchKernelGGL((k_lsa<XT, MT>), dim3(nb), dim3(256), 0, s, d, cur);
+    hipLaunchKernelGGL((k_lsa<XT, MT>), dim3(n_req), dim3(LSA_THREADS), 0, s, d, cur);
     mark(2);
     // H_dec(t): consumed by this step's projection and the next step's decoder LSTM (same buffer)
     hipLaunchKernelGGL((k_lstm<XT, K_DEC>), dim3(HID / 4), dim3(LSTM_WAVES * 64), 0, s,
-                       d.Wd, d.bd, xdec_cur, d.c_dec, xdec_nxt, K_DEC, XD_HD, xdec_nxt, K_DEC, XD_HD,
-                       d.table, d.done);
+                       d.Wd, d.bd, reinterpret_cast<const uint4*>(d.xdec[cur]), d.c_dec, xdec_nxt, K_DEC / KB, XD_HD,
+                       xdec_nxt, K_DEC / KB, XD_HD, d.table, d.live, d.done);
     mark(3);
-    hipLaunchKernelGGL((k_proj<XT>), dim3(nb), dim3(256), 0, s, d, cur);
+    hipLaunchKernelGGL((k_proj<XT>), dim3(n_tiles), dim3(PROJ_THREADS), 0, s, d, cur);
     mark(4);
     return hipGetLastError();
 }
 
 hipError_t launch_step(const DevPtrs& d, const StepLaunch& cfg, int cur, hipStream_t s, hipEvent_t* ev)
 {
-    if (cfg.n_blocks < 1) return hipSuccess;
-    if (cfg.wdtype == 0 && cfg.mdtype == 0) return step_typed<float, float>(d, cfg.n_blocks, cur, s, ev);
-    if (cfg.wdtype == 1 && cfg.mdtype == 1) return step_typed<bf16_t, bf16_t>(d, cfg.n_blocks, cur, s, ev);
-    if (cfg.wdtype == 1 && cfg.mdtype == 0) return step_typed<bf16_t, float>(d, cfg.n_blocks, cur, s, ev);
+    if (cfg.n_blocks < 1 || cfg.n_tiles < 1) return hipSuccess;
+    if (cfg.wdtype == 0 && cfg.mdtype == 0) return step_typed<float, float>(d, cfg.n_blocks, cfg.n_tiles, cur, s, ev);
+    if (cfg.wdtype == 1 && cfg.mdtype == 1) return step_typed<bf16_t, bf16_t>(d, cfg.n_blocks, cfg.n_tiles, cur, s, ev);
+    if (cfg.wdtype == 1 && cfg.mdtype == 0) return step_typed<bf16_t, float>(d, cfg.n_blocks, cfg.n_tiles, cur, s, ev);
     return hipErrorInvalidValue;
 }
 
 hipError_t launch_set_table(const DevPtrs& d, const TableArgs& args, hipStream_t s)
 {
-    hipLaunchKernelGGL(k_set_table, dim3(1), dim3(256), 0, s, args, d.table);
+    hipLaunchKernelGGL(k_set_table, dim3(1), dim3(MAX_POOL), 0, s, args, d.table, d.live);
     return hipGetLastError();
 }
 
@@ -536,6 +872,24 @@ hipError_t launch_prenet_slot(const DevPtrs& d, int wdtype, int slot, hipStream_
 {
     if (wdtype == 0) hipLaunchKernelGGL((k_prenet_slot<float>), dim3(1), dim3(256), 0, s, d, slot);
     else hipLaunchKernelGGL((k_prenet_slot<bf16_t>), dim3(1), dim3(256), 0, s, d, slot);
+    return hipGetLastError();
+}
+
+hipError_t launch_x_get(int wdtype, const void* X, int K, int slot, int off, int n, float* out, hipStream_t s)
+{
+    if (wdtype == 0)
+        hipLaunchKernelGGL((k_x_get<float>), dim3(1), dim3(256), 0, s, reinterpret_cast<const float*>(X), K / Frag<float>::KB, slot, off, n, out);
+    else
+        hipLaunchKernelGGL((k_x_get<bf16_t>), dim3(1), dim3(256), 0, s, reinterpret_cast<const bf16_t*>(X), K / Frag<bf16_t>::KB, slot, off, n, out);
+    return hipGetLastError();
+}
+
+hipError_t launch_x_set(int wdtype, void* X, int K, int slot, int off, int n, const float* in, hipStream_t s)
+{
+    if (wdtype == 0)
+        hipLaunchKernelGGL((k_x_set<float>), dim3(1), dim3(256), 0, s, reinterpret_cast<float*>(X), K / Frag<float>::KB, slot, off, n, in);
+    else
+        hipLaunchKernelGGL((k_x_set<bf16_t>), dim3(1), dim3(256), 0, s, reinterpret_cast<bf16_t*>(X), K / Frag<bf16_t>::KB, slot, off, n, in);
     return hipGetLastError();
 }
 

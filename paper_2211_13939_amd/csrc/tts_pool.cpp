@@ -7,6 +7,7 @@
 
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <map>
 #include <memory>
@@ -79,9 +80,9 @@ struct Carver {
 };
 
 struct Layout {
-    size_t Wa, Wd, ba, bd, Wq, WmemT, KcT, Wloc, v, Wmel, bmel, Wp1T, Wp2T;
-    size_t xatt[2], xdec[2], c_att, c_dec, m_last, w_last, w_acc, Fmem, PM, mel_ring, stop_ring;
-    size_t L, t, n_steps, done, table, stage;
+    size_t Wa, Wd, ba, bd, Wq, WmemT, lsa_kfrag, lsa_wfrag, v, Wmel, bmel, Wp1, Wp2;
+    size_t xatt[2], xdec[2], c_att, c_dec, m_last, w_last[2], w_acc[2], Fmem, PM, mel_ring, stop_ring;
+    size_t L, t, n_steps, done, live, table, stage;
     size_t total;
 };
 
@@ -89,7 +90,7 @@ Layout make_layout(const tts_config& c)
 {
     const size_t ws = c.weight_dtype == TTS_DTYPE_BF16 ? 2 : 4;
     const size_t ms = c.memory_dtype == TTS_DTYPE_BF16 ? 2 : 4;
-    const size_t S = c.max_pool, ML = c.max_enc_len;
+    const size_t S = (size_t)((c.max_pool + 15) / 16) * 16, ML = c.max_enc_len;   // slots padded to whole 16-slot tiles
     Carver a;
     Layout l;
     l.Wa = a.take((size_t)4 * HID * K_ATT * ws);
@@ -98,13 +99,13 @@ Layout make_layout(const tts_config& c)
     l.bd = a.take((size_t)4 * HID * 4);
     l.Wq = a.take((size_t)ATT * HID * ws);
     l.WmemT = a.take((size_t)ENC * ATT * 4);
-    l.KcT = a.take((size_t)2 * LOC_K * LOC_F * 4);
-    l.Wloc = a.take((size_t)ATT * LOC_F * 4);
+    l.lsa_kfrag = a.take((size_t)2 * 16 * 64 * 4);
+    l.lsa_wfrag = a.take((size_t)16 * 64 * 16);
     l.v = a.take((size_t)ATT * 4);
-    l.Wmel = a.take((size_t)N_PROJ * K_PROJ * ws);
+    l.Wmel = a.take((size_t)96 * K_PROJ * ws);
     l.bmel = a.take((size_t)N_PROJ * 4);
-    l.Wp1T = a.take((size_t)N_MEL * PRENET * ws);
-    l.Wp2T = a.take((size_t)PRENET * PRENET * ws);
+    l.Wp1 = a.take((size_t)PRENET * 96 * ws);
+    l.Wp2 = a.take((size_t)PRENET * PRENET * ws);
     for (int b = 0; b < 2; ++b) {
         l.xatt[b] = a.take(S * K_ATT * ws);
         l.xdec[b] = a.take(S * K_DEC * ws);
@@ -112,8 +113,10 @@ Layout make_layout(const tts_config& c)
     l.c_att = a.take(S * HID * 4);
     l.c_dec = a.take(S * HID * 4);
     l.m_last = a.take(S * N_MEL * 4);
-    l.w_last = a.take(S * ML * 4);
-    l.w_acc = a.take(S * ML * 4);
+    for (int b = 0; b < 2; ++b) {
+        l.w_last[b] = a.take(S * ML * 4);
+        l.w_acc[b] = a.take(S * ML * 4);
+    }
     l.Fmem = a.take(S * ML * ENC * ms);
     l.PM = a.take(S * ML * ATT * ms);
     l.mel_ring = a.take(S * (size_t)c.max_steps * N_MEL * 4);
@@ -122,7 +125,8 @@ Layout make_layout(const tts_config& c)
     l.t = a.take(S * 4);
     l.n_steps = a.take(S * 4);
     l.done = a.take(S * 4);
-    l.table = a.take((TABLE_HDR + MAX_POOL) * 4);
+    l.live = a.take(MAX_POOL * 4);
+    l.table = a.take(TABLE_INTS * 4);
     l.stage = a.take(ML * ENC * 4);
     l.total = a.off;
     return l;
@@ -135,14 +139,6 @@ uint16_t host_f2bf(float f)
     u += 0x7FFFu + ((u >> 16) & 1u);
     return (uint16_t)(u >> 16);
 }
-float host_bf2f(uint16_t b)
-{
-    uint32_t u = (uint32_t)b << 16;
-    float f;
-    memcpy(&f, &u, 4);
-    return f;
-}
-
 // fp32 host values -> device array of the weight dtype
 int upload(void* dst, const std::vector<float>& src, bool bf16)
 {
@@ -156,30 +152,84 @@ int upload(void* dst, const std::vector<float>& src, bool bf16)
     return TTS_OK;
 }
 
-// Gate matrix [W_ih | W_hh] (rows i,f,g,o blocks of HID) -> MFMA fragment order:
-// rows re-ordered unit-major/gate-minor, tiles of 16 rows x (64 bytes of k);
-// within a tile lane l holds row l%16, 16 bytes at byte offset 16*(l/16).
-std::vector<float> gate_fragments(const float* w_ih, int in_dim, const float* w_hh, bool bf16)
+// A [rows][K] matrix given by an element accessor -> MFMA A-operand fragment
+// order: tiles of 16 rows x (64 bytes of k); within a tile lane l holds row
+// l%16, 16 bytes at byte offset 16*(l/16).
+template <typename Get>
+std::vector<float> pack_fragments(int rows, int K, bool bf16, Get get)
 {
-    const int K = in_dim + HID;
     const int KB = bf16 ? 32 : 16;   // k elements per 64-byte fragment row
     const int EPL = KB / 4;          // elements per lane
     const int NK = K / KB;
-    std::vector<float> out((size_t)4 * HID * K);
-    for (int rt = 0; rt < HID / 4; ++rt)
+    std::vector<float> out((size_t)rows * K);
+    for (int rt = 0; rt < rows / 16; ++rt)
         for (int ks = 0; ks < NK; ++ks)
-            for (int lane = 0; lane < 64; ++lane) {
-                const int r = rt * 16 + (lane & 15);      // re-ordered row
-                const int unit = r >> 2, gate = r & 3;
-                const int src_row = gate * HID + unit;
-                for (int i = 0; i < EPL; ++i) {
-                    const int k = ks * KB + (lane >> 4) * EPL + i;
-                    const float val = k < in_dim ? w_ih[(size_t)src_row * in_dim + k]
-                                                 : w_hh[(size_t)src_row * HID + (k - in_dim)];
-                    out[(((size_t)rt * NK + ks) * 64 + lane) * EPL + i] = val;
-                }
-            }
+            for (int lane = 0; lane < 64; ++lane)
+                for (int i = 0; i < EPL; ++i)
+                    out[(((size_t)rt * NK + ks) * 64 + lane) * EPL + i] =
+                        get(rt * 16 + (lane & 15), ks * KB + (lane >> 4) * EPL + i);
     return out;
+}
+
+// Gate matrix [W_ih | W_hh] (rows i,f,g,o blocks of HID): rows re-ordered
+// unit-major/gate-minor so that one 16-row tile is the four gates of four units.
+std::vector<float> gate_fragments(const float* w_ih, int in_dim, const float* w_hh, bool bf16)
+{
+    return pack_fragments(4 * HID, in_dim + HID, bf16, [&](int r, int k) {
+        const int unit = r >> 2, gate = r & 3;
+        const int src_row = gate * HID + unit;
+        return k < in_dim ? w_ih[(size_t)src_row * in_dim + k] : w_hh[(size_t)src_row * HID + (k - in_dim)];
+    });
+}
+
+// Location filters and W_loc as the per-lane constant A operands of the
+// attention kernel.  Channel 0 of the kernel is W_last, channel 1 W_acc (a
+// one-channel model convolves W_acc only); taps are padded from 31 to 32.
+// Lane = (jl = lane%16, g = lane/16).
+void lsa_fragments(const float* loc_conv, int C, const float* loc_w, bool bf16,
+                   std::vector<float>* kfrag, std::vector<float>* wfrag)
+{
+    auto tap = [&](int f, int cd, int k) -> float {
+        if (k >= LOC_K) return 0.f;
+        if (C == 2) return loc_conv[((size_t)f * 2 + cd) * LOC_K + k];
+        return cd == 1 ? loc_conv[(size_t)f * LOC_K + k] : 0.f;
+    };
+    auto wrow = [&](int at, int jl) { return 32 * (jl >> 2) + 4 * at + (jl & 3); };
+    if (!bf16) {
+        // kfrag[(mt*16 + c*8 + s)*64 + lane] = tap 4s+g of channel c, filter 16mt+jl
+        kfrag->assign((size_t)32 * 64, 0.f);
+        for (int mt = 0; mt < 2; ++mt)
+            for (int cs = 0; cs < 16; ++cs)
+                for (int lane = 0; lane < 64; ++lane)
+                    (*kfrag)[((size_t)mt * 16 + cs) * 64 + lane] =
+                        tap(16 * mt + (lane & 15), cs >> 3, 4 * (cs & 7) + (lane >> 4));
+        // wfrag[((at*2 + mt)*64 + lane)*4 + i] = W_loc[row(at,jl)][16mt + 4g + i]
+        wfrag->assign((size_t)16 * 64 * 4, 0.f);
+        for (int at = 0; at < 8; ++at)
+            for (int mt = 0; mt < 2; ++mt)
+                for (int lane = 0; lane < 64; ++lane)
+                    for (int i = 0; i < 4; ++i)
+                        (*wfrag)[(((size_t)at * 2 + mt) * 64 + lane) * 4 + i] =
+                            loc_w[(size_t)wrow(at, lane & 15) * LOC_F + 16 * mt + 4 * (lane >> 4) + i];
+    } else {
+        // kfrag[((mt*2 + c)*64 + lane)*8 + e] = tap 8g+e of channel c, filter 16mt+jl
+        kfrag->assign((size_t)4 * 64 * 8, 0.f);
+        for (int mt = 0; mt < 2; ++mt)
+            for (int c = 0; c < 2; ++c)
+                for (int lane = 0; lane < 64; ++lane)
+                    for (int e = 0; e < 8; ++e)
+                        (*kfrag)[(((size_t)mt * 2 + c) * 64 + lane) * 8 + e] =
+                            tap(16 * mt + (lane & 15), c, 8 * (lane >> 4) + e);
+        // wfrag[(at*64 + lane)*8 + e] = W_loc[row(at,jl)][e < 4 ? 4g+e : 16+4g+e-4]
+        wfrag->assign((size_t)8 * 64 * 8, 0.f);
+        for (int at = 0; at < 8; ++at)
+            for (int lane = 0; lane < 64; ++lane)
+                for (int e = 0; e < 8; ++e) {
+                    const int g = lane >> 4;
+                    const int f = e < 4 ? 4 * g + e : 16 + 4 * g + (e - 4);
+                    (*wfrag)[((size_t)at * 64 + lane) * 8 + e] = loc_w[(size_t)wrow(at, lane & 15) * LOC_F + f];
+                }
+    }
 }
 
 }  // namespace
@@ -197,11 +247,12 @@ struct tts_pool {
     hipStream_t stream = nullptr;
     std::unique_ptr<PoolBook> book;
     int parity = 0;               // activation buffer half the next step reads
+    int n_tiles = 0;              // 16-slot tiles with at least one active request (as last uploaded)
     bool stop_enabled = false;
     bool timing = false;
     hipEvent_t ev0 = nullptr, ev1 = nullptr;
     bool ev_valid = false;
-    std::map<int, hipGraphExec_t> graphs;   // key = bucket * 2 + parity
+    std::map<int, hipGraphExec_t> graphs;   // key = ((steps * 1024 + bucket) * 2 + parity
     std::vector<hipGraph_t> graph_defs;
 };
 
@@ -221,37 +272,35 @@ static int upload_weights(tts_pool* p, const tts_weights* w, char* base, const L
         }
     if ((rc = upload(base + l.ba, ba, false))) return rc;
     if ((rc = upload(base + l.bd, bd, false))) return rc;
-    if ((rc = upload(base + l.Wq, std::vector<float>(w->q_w, w->q_w + ATT * HID), bf))) return rc;
+    if ((rc = upload(base + l.Wq, pack_fragments(ATT, HID, bf, [&](int r, int k) { return w->q_w[(size_t)r * HID + k]; }), bf)))
+        return rc;
     std::vector<float> memT((size_t)ENC * ATT);
     for (int a = 0; a < ATT; ++a)
         for (int k = 0; k < ENC; ++k) memT[(size_t)k * ATT + a] = w->mem_w[(size_t)a * ENC + k];
     if ((rc = upload(base + l.WmemT, memT, false))) return rc;
-    // location filters [f][c][k] -> [c'][k][f] with c' = 0 for W_last, 1 for W_acc;
-    // a one-channel model convolves W_acc only
-    std::vector<float> kc((size_t)2 * LOC_K * LOC_F, 0.f);
-    for (int f = 0; f < LOC_F; ++f)
-        for (int c = 0; c < C; ++c)
-            for (int k = 0; k < LOC_K; ++k) {
-                const int cd = (C == 2) ? c : 1;
-                kc[((size_t)cd * LOC_K + k) * LOC_F + f] = w->loc_conv[((size_t)f * C + c) * LOC_K + k];
-            }
-    if ((rc = upload(base + l.KcT, kc, false))) return rc;
-    if ((rc = upload(base + l.Wloc, std::vector<float>(w->loc_w, w->loc_w + ATT * LOC_F), false))) return rc;
+    std::vector<float> kfrag, wfrag;
+    lsa_fragments(w->loc_conv, C, w->loc_w, bf, &kfrag, &wfrag);
+    if ((rc = upload(base + l.lsa_kfrag, kfrag, bf))) return rc;
+    if ((rc = upload(base + l.lsa_wfrag, wfrag, bf))) return rc;
     if ((rc = upload(base + l.v, std::vector<float>(w->v, w->v + ATT), false))) return rc;
-    std::vector<float> proj((size_t)N_PROJ * K_PROJ), bproj(N_PROJ);
-    memcpy(proj.data(), w->mel_w, (size_t)N_MEL * K_PROJ * 4);
-    memcpy(proj.data() + (size_t)N_MEL * K_PROJ, w->stop_w, (size_t)K_PROJ * 4);
+    // projection rows: 80 mel rows, the stop row, zero rows up to 96
+    if ((rc = upload(base + l.Wmel, pack_fragments(96, K_PROJ, bf, [&](int r, int k) {
+             return r < N_MEL ? w->mel_w[(size_t)r * K_PROJ + k] : (r == N_MEL ? w->stop_w[k] : 0.f);
+         }), bf)))
+        return rc;
+    std::vector<float> bproj(N_PROJ);
     memcpy(bproj.data(), w->mel_b, N_MEL * 4);
     bproj[N_MEL] = w->stop_b[0];
-    if ((rc = upload(base + l.Wmel, proj, bf))) return rc;
     if ((rc = upload(base + l.bmel, bproj, false))) return rc;
-    std::vector<float> p1T((size_t)N_MEL * PRENET), p2T((size_t)PRENET * PRENET);
-    for (int o = 0; o < PRENET; ++o) {
-        for (int k = 0; k < N_MEL; ++k) p1T[(size_t)k * PRENET + o] = w->prenet1[(size_t)o * N_MEL + k];
-        for (int k = 0; k < PRENET; ++k) p2T[(size_t)k * PRENET + o] = w->prenet2[(size_t)o * PRENET + k];
-    }
-    if ((rc = upload(base + l.Wp1T, p1T, bf))) return rc;
-    if ((rc = upload(base + l.Wp2T, p2T, bf))) return rc;
+    const int k1 = bf ? 96 : 80;   // the first prenet layer's K padded to whole fragments
+    if ((rc = upload(base + l.Wp1, pack_fragments(PRENET, k1, bf, [&](int r, int k) {
+             return k < N_MEL ? w->prenet1[(size_t)r * N_MEL + k] : 0.f;
+         }), bf)))
+        return rc;
+    if ((rc = upload(base + l.Wp2, pack_fragments(PRENET, PRENET, bf, [&](int r, int k) {
+             return w->prenet2[(size_t)r * PRENET + k];
+         }), bf)))
+        return rc;
     return TTS_OK;
 }
 
@@ -290,13 +339,13 @@ extern "C" int tts_pool_create(const tts_config* cfg, const tts_weights* w, void
     d.bd = (const float*)(base + l.bd);
     d.Wq = base + l.Wq;
     d.WmemT = (const float*)(base + l.WmemT);
-    d.KcT = (const float*)(base + l.KcT);
-    d.Wloc = (const float*)(base + l.Wloc);
+    d.lsa_kfrag = base + l.lsa_kfrag;
+    d.lsa_wfrag = base + l.lsa_wfrag;
     d.v = (const float*)(base + l.v);
     d.Wmel = base + l.Wmel;
     d.bmel = (const float*)(base + l.bmel);
-    d.Wp1T = base + l.Wp1T;
-    d.Wp2T = base + l.Wp2T;
+    d.Wp1 = base + l.Wp1;
+    d.Wp2 = base + l.Wp2;
     for (int b = 0; b < 2; ++b) {
         d.xatt[b] = base + l.xatt[b];
         d.xdec[b] = base + l.xdec[b];
@@ -304,8 +353,10 @@ extern "C" int tts_pool_create(const tts_config* cfg, const tts_weights* w, void
     d.c_att = (float*)(base + l.c_att);
     d.c_dec = (float*)(base + l.c_dec);
     d.m_last = (float*)(base + l.m_last);
-    d.w_last = (float*)(base + l.w_last);
-    d.w_acc = (float*)(base + l.w_acc);
+    for (int b = 0; b < 2; ++b) {
+        d.w_last[b] = (float*)(base + l.w_last[b]);
+        d.w_acc[b] = (float*)(base + l.w_acc[b]);
+    }
     d.Fmem = base + l.Fmem;
     d.PM = base + l.PM;
     d.mel_ring = (float*)(base + l.mel_ring);
@@ -314,6 +365,7 @@ extern "C" int tts_pool_create(const tts_config* cfg, const tts_weights* w, void
     d.t = (int*)(base + l.t);
     d.n_steps = (int*)(base + l.n_steps);
     d.done = (int*)(base + l.done);
+    d.live = (int*)(base + l.live);
     d.table = (int*)(base + l.table);
     d.stage = (float*)(base + l.stage);
     d.max_enc_len = cfg->max_enc_len;
@@ -378,6 +430,9 @@ extern "C" int tts_pool_add_request(tts_pool* p, const float* enc_out, int L, in
     return TTS_OK;
 }
 
+// most steps captured into one graph
+static const int MAX_GRAPH_STEPS = 32;
+
 static int bucket_for(int n)
 {
     int b = 1;
@@ -389,33 +444,48 @@ static int push_table(tts_pool* p)
 {
     if (!p->book->dirty()) return TTS_OK;
     TableArgs a;
+    memset(&a, 0, sizeof a);
     const std::vector<int>& act = p->book->active();
     a.n_active = (int)act.size();
-    for (size_t i = 0; i < act.size(); ++i) a.slot[i] = (uint16_t)act[i];
+    bool used[MAX_TILES] = {false};
+    for (size_t i = 0; i < act.size(); ++i) {
+        a.slot[i] = (uint16_t)act[i];
+        used[act[i] >> 4] = true;
+    }
+    for (int t = 0; t < MAX_TILES; ++t)
+        if (used[t]) a.tile[a.n_tiles++] = (uint8_t)t;
+    p->n_tiles = a.n_tiles;
     HIP_TRY(launch_set_table(p->d, a, p->stream));
     p->book->clear_dirty();
     return TTS_OK;
 }
 
-static int launch_one_step(tts_pool* p, int n_active)
+// Queue `nsteps` consecutive steps for the current membership.  With graphs the
+// steps are one hipGraph launch (captured once per (nsteps, pool bucket,
+// parity)); requests that reach their end inside the graph are skipped by the
+// kernels through their device-side done flag.
+static int launch_steps(tts_pool* p, int n_active, int nsteps)
 {
     StepLaunch sl;
     sl.wdtype = p->cfg.weight_dtype;
     sl.mdtype = p->cfg.memory_dtype;
     if (!p->cfg.use_graph) {
         sl.n_blocks = n_active;
-        HIP_TRY(launch_step(p->d, sl, p->parity, p->stream));
+        sl.n_tiles = p->n_tiles;
+        for (int i = 0; i < nsteps; ++i) HIP_TRY(launch_step(p->d, sl, p->parity ^ (i & 1), p->stream));
         return TTS_OK;
     }
     const int bucket = bucket_for(n_active);
-    const int key = bucket * 2 + p->parity;
+    const int key = (nsteps * 1024 + bucket) * 2 + p->parity;
     auto it = p->graphs.find(key);
     if (it == p->graphs.end()) {
         sl.n_blocks = bucket;
+        sl.n_tiles = (p->cfg.max_pool + 15) / 16;   // per-tile workgroups beyond the active tiles exit at once
         hipGraph_t g = nullptr;
         hipGraphExec_t ge = nullptr;
         HIP_TRY(hipStreamBeginCapture(p->stream, hipStreamCaptureModeThreadLocal));
-        hipError_t le = launch_step(p->d, sl, p->parity, p->stream);
+        hipError_t le = hipSuccess;
+        for (int i = 0; i < nsteps && le == hipSuccess; ++i) le = launch_step(p->d, sl, p->parity ^ (i & 1), p->stream);
         hipError_t ce = hipStreamEndCapture(p->stream, &g);
         if (le != hipSuccess) return fail(TTS_E_HIP, "capture of the step failed: %s", hipGetErrorString(le));
         if (ce != hipSuccess) return fail(TTS_E_HIP, "hipStreamEndCapture: %s", hipGetErrorString(ce));
@@ -432,17 +502,23 @@ static int step_impl(tts_pool* p, int n, int64_t* out_frames, int* out_last_acti
     int64_t frames = 0;
     int last = 0;
     if (p->timing) HIP_TRY(hipEventRecord(p->ev0, p->stream));
-    for (int i = 0; i < n; ++i) {
+    int i = 0;
+    while (i < n) {
         const int n_active = (int)p->book->active().size();
         last = n_active;
         if (n_active == 0) break;
         int rc = push_table(p);
         if (rc) return rc;
-        rc = launch_one_step(p, n_active);
+        int g = 1;
+        if (p->cfg.use_graph)
+            while (g * 2 <= n - i && g * 2 <= MAX_GRAPH_STEPS) g *= 2;
+        rc = launch_steps(p, n_active, g);
         if (rc) return rc;
-        p->parity ^= 1;
-        p->book->step(p->parity);
-        frames += n_active;
+        for (int k = 0; k < g; ++k) {
+            p->parity ^= 1;
+            frames += p->book->step(p->parity);
+        }
+        i += g;
     }
     if (p->timing) {
         HIP_TRY(hipEventRecord(p->ev1, p->stream));
@@ -480,7 +556,7 @@ extern "C" int tts_pool_kernel_times(tts_pool* p, int n, float* out_us, int cap,
         const int n_active = (int)p->book->active().size();
         if (n_active == 0) break;
         if ((rc = push_table(p))) break;
-        StepLaunch sl{p->cfg.weight_dtype, p->cfg.memory_dtype, n_active};
+        StepLaunch sl{p->cfg.weight_dtype, p->cfg.memory_dtype, n_active, p->n_tiles};
         hipError_t e = launch_step(p->d, sl, p->parity, p->stream, ev);
         if (e == hipSuccess) e = hipEventSynchronize(ev[N_STEP_KERNELS]);
         for (int k = 0; k < N_STEP_KERNELS && e == hipSuccess; ++k) {
@@ -596,43 +672,51 @@ extern "C" int tts_pool_elapsed_ms(tts_pool* p, float* out_ms)
 
 // ------------------------------------------------------------------ state access
 namespace {
+// where one carried state lives: either plain fp32 arrays (up to two copies) or
+// pieces of the slot-tiled activation arrays (up to four copies)
 struct StateLoc {
-    bool wt;           // stored in the weight/activation dtype (else fp32)
-    int n;
-    // up to 4 device locations holding a copy (all written on set, first read on get)
-    char* loc[4];
-    int n_loc;
+    int n = 0;
+    int n_plain = 0;
+    float* plain[2];
+    int n_x = 0;
+    void* x[4];
+    int xK[4];
+    int xoff[4];
 };
 }  // namespace
 
 static int locate_state(tts_pool* p, int slot, int which, StateLoc* s)
 {
     const DevPtrs& d = p->d;
-    const size_t ws = p->cfg.weight_dtype == TTS_DTYPE_BF16 ? 2 : 4;
-    const int rd = p->book->slot(slot).parity;   // buffer half holding the newest activations of this request
-    auto xa = [&](int b, int off) { return (char*)d.xatt[b] + ((size_t)slot * K_ATT + off) * ws; };
-    auto xd = [&](int b, int off) { return (char*)d.xdec[b] + ((size_t)slot * K_DEC + off) * ws; };
-    s->n_loc = 0;
+    const int rd = p->book->slot(slot).parity;   // buffer half holding the newest state of this request
+    const size_t ml = d.max_enc_len;
+    auto addx = [&](void* X, int K, int off) { s->x[s->n_x] = X; s->xK[s->n_x] = K; s->xoff[s->n_x] = off; ++s->n_x; };
     switch (which) {
-    case TTS_STATE_M_LAST: s->wt = false; s->n = N_MEL; s->loc[s->n_loc++] = (char*)(d.m_last + (size_t)slot * N_MEL); break;
+    case TTS_STATE_M_LAST: s->n = N_MEL; s->plain[s->n_plain++] = d.m_last + (size_t)slot * N_MEL; break;
     case TTS_STATE_A:
-        s->wt = true; s->n = ENC;
-        s->loc[s->n_loc++] = xa(rd, XA_A); s->loc[s->n_loc++] = xa(rd ^ 1, XA_A);
-        s->loc[s->n_loc++] = xd(rd, XD_A); s->loc[s->n_loc++] = xd(rd ^ 1, XD_A);
+        s->n = ENC;
+        addx(d.xatt[rd], K_ATT, XA_A); addx(d.xatt[rd ^ 1], K_ATT, XA_A);
+        addx(d.xdec[rd], K_DEC, XD_A); addx(d.xdec[rd ^ 1], K_DEC, XD_A);
         break;
-    case TTS_STATE_W_LAST: s->wt = false; s->n = p->book->slot(slot).L; s->loc[s->n_loc++] = (char*)(d.w_last + (size_t)slot * d.max_enc_len); break;
-    case TTS_STATE_W_ACC: s->wt = false; s->n = p->book->slot(slot).L; s->loc[s->n_loc++] = (char*)(d.w_acc + (size_t)slot * d.max_enc_len); break;
+    case TTS_STATE_W_LAST:
+        s->n = p->book->slot(slot).L;
+        s->plain[s->n_plain++] = d.w_last[rd] + slot * ml; s->plain[s->n_plain++] = d.w_last[rd ^ 1] + slot * ml;
+        break;
+    case TTS_STATE_W_ACC:
+        s->n = p->book->slot(slot).L;
+        s->plain[s->n_plain++] = d.w_acc[rd] + slot * ml; s->plain[s->n_plain++] = d.w_acc[rd ^ 1] + slot * ml;
+        break;
     case TTS_STATE_H_ATT:
-        s->wt = true; s->n = HID;
-        s->loc[s->n_loc++] = xa(rd, XA_H); s->loc[s->n_loc++] = xa(rd ^ 1, XA_H);
-        s->loc[s->n_loc++] = xd(rd, XD_HA); s->loc[s->n_loc++] = xd(rd ^ 1, XD_HA);
+        s->n = HID;
+        addx(d.xatt[rd], K_ATT, XA_H); addx(d.xatt[rd ^ 1], K_ATT, XA_H);
+        addx(d.xdec[rd], K_DEC, XD_HA); addx(d.xdec[rd ^ 1], K_DEC, XD_HA);
         break;
-    case TTS_STATE_C_ATT: s->wt = false; s->n = HID; s->loc[s->n_loc++] = (char*)(d.c_att + (size_t)slot * HID); break;
+    case TTS_STATE_C_ATT: s->n = HID; s->plain[s->n_plain++] = d.c_att + (size_t)slot * HID; break;
     case TTS_STATE_H_DEC:
-        s->wt = true; s->n = HID;
-        s->loc[s->n_loc++] = xd(rd, XD_HD); s->loc[s->n_loc++] = xd(rd ^ 1, XD_HD);
+        s->n = HID;
+        addx(d.xdec[rd], K_DEC, XD_HD); addx(d.xdec[rd ^ 1], K_DEC, XD_HD);
         break;
-    case TTS_STATE_C_DEC: s->wt = false; s->n = HID; s->loc[s->n_loc++] = (char*)(d.c_dec + (size_t)slot * HID); break;
+    case TTS_STATE_C_DEC: s->n = HID; s->plain[s->n_plain++] = d.c_dec + (size_t)slot * HID; break;
     default: return fail(TTS_E_INVAL, "unknown state %d", which);
     }
     return TTS_OK;
@@ -648,16 +732,10 @@ extern "C" int tts_pool_get_state(tts_pool* p, int64_t id, int which, float* dst
     if (rc) return rc;
     if (out_n) *out_n = s.n;
     if (cap < s.n) return fail(TTS_E_INVAL, "room for %d elements, %d needed", cap, s.n);
-    const bool bf = s.wt && p->cfg.weight_dtype == TTS_DTYPE_BF16;
-    if (!bf) {
-        HIP_TRY(hipMemcpyAsync(dst, s.loc[0], (size_t)s.n * 4, hipMemcpyDeviceToHost, p->stream));
-        HIP_TRY(hipStreamSynchronize(p->stream));
-    } else {
-        std::vector<uint16_t> h(s.n);
-        HIP_TRY(hipMemcpyAsync(h.data(), s.loc[0], (size_t)s.n * 2, hipMemcpyDeviceToHost, p->stream));
-        HIP_TRY(hipStreamSynchronize(p->stream));
-        for (int i = 0; i < s.n; ++i) dst[i] = host_bf2f(h[i]);
-    }
+    const float* src = s.n_plain ? s.plain[0] : p->d.stage;
+    if (!s.n_plain) HIP_TRY(launch_x_get(p->cfg.weight_dtype, s.x[0], s.xK[0], slot, s.xoff[0], s.n, p->d.stage, p->stream));
+    HIP_TRY(hipMemcpyAsync(dst, src, (size_t)s.n * 4, hipMemcpyDeviceToHost, p->stream));
+    HIP_TRY(hipStreamSynchronize(p->stream));
     return TTS_OK;
 }
 
@@ -670,17 +748,13 @@ extern "C" int tts_pool_set_state(tts_pool* p, int64_t id, int which, const floa
     int rc = locate_state(p, slot, which, &s);
     if (rc) return rc;
     if (n != s.n) return fail(TTS_E_INVAL, "state %d has %d elements, %d given", which, s.n, n);
-    const bool bf = s.wt && p->cfg.weight_dtype == TTS_DTYPE_BF16;
-    std::vector<uint16_t> h;
-    const void* hsrc = src;
-    size_t bytes = (size_t)n * 4;
-    if (bf) {
-        h.resize(n);
-        for (int i = 0; i < n; ++i) h[i] = host_f2bf(src[i]);
-        hsrc = h.data();
-        bytes = (size_t)n * 2;
+    for (int i = 0; i < s.n_plain; ++i)
+        HIP_TRY(hipMemcpyAsync(s.plain[i], src, (size_t)n * 4, hipMemcpyHostToDevice, p->stream));
+    if (s.n_x) {
+        HIP_TRY(hipMemcpyAsync(p->d.stage, src, (size_t)n * 4, hipMemcpyHostToDevice, p->stream));
+        for (int i = 0; i < s.n_x; ++i)
+            HIP_TRY(launch_x_set(p->cfg.weight_dtype, s.x[i], s.xK[i], slot, s.xoff[i], n, p->d.stage, p->stream));
     }
-    for (int i = 0; i < s.n_loc; ++i) HIP_TRY(hipMemcpyAsync(s.loc[i], hsrc, bytes, hipMemcpyHostToDevice, p->stream));
     if (which == TTS_STATE_M_LAST) HIP_TRY(launch_prenet_slot(p->d, p->cfg.weight_dtype, slot, p->stream));
     HIP_TRY(hipStreamSynchronize(p->stream));
     return TTS_OK;
