@@ -215,14 +215,15 @@ def main():
         from oracle import oracle as orc
         cores = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "0") or (os.cpu_count() or 1)))
         W = orc.Weights(weights)
-        n_req, window = (wl.n_requests, 40) if wl.n_requests >= 64 else (wl.n_requests, 100)
+        # about 10-30 s of oracle work on 8-16 cores
+        n_req, window = (wl.n_requests, 300) if wl.n_requests <= 64 else (64, 300)
         Fs = [wl.encoder_outputs(i) for i in range(n_req)]
         t0 = time.perf_counter()
         _, _, fr, used = orc.pool_decode(wl.dims, W, Fs, [window] * n_req, window, pm_round_bf16=wl.bf16,
                                          n_threads=cores)
         dt = time.perf_counter() - t0
         out["cpu_baseline"] = {"value": float(fr.sum()) / dt, "unit": "frames/s", "cores": int(used), "kind": "oracle",
-                               "sample": f"first {window} steps of the same {n_req} requests "
+                               "sample": f"first {window} frames of each of the first {n_req} requests of the same job "
                                          f"({int(fr.sum())} frames, {dt:.1f} s incl. join)"}
     print(json.dumps(out))
 

@@ -1,0 +1,304 @@
+"""Pool semantics of the HIP library (Sec. 2.2.2 / 2.2.3) and edge cases, through
+the C ABI on a real GPU.  Eq. 2 never mixes two requests, so a request's frames
+must not depend on who shares the pool, when it joined, or which slot it got:
+those comparisons are bit-exact (same kernels, same per-column arithmetic).
+Comparisons with the CPU oracle use the fp32 / bf16 bars."""
+import numpy as np
+import pytest
+
+from paper_2211_13939_amd import binding, synth
+from tests.helpers import TOL_BF16, TOL_F32, gpu_decode, make_pool, max_err, oracle_decode, say
+
+pytestmark = pytest.mark.gpu
+
+
+def _drain(pool, rid):
+    return pool.drain_all(rid)
+
+
+@pytest.fixture(scope="module")
+def wl8():
+    return synth.small_workload(8, 5, 90, 24, 24, seed=11)
+
+
+@pytest.fixture(scope="module")
+def solo_frames(wl8, weights_fp32):
+    """Every request of wl8 decoded alone in a pool of one (24 frames)."""
+    say("reference: 8 requests decoded alone, fp32")
+    out = []
+    for i in range(8):
+        out.append(gpu_decode(wl8, weights_fp32, [i], 24)[0])
+    return out
+
+
+def test_pool_equals_solo_and_oracle(wl8, weights_fp32, solo_frames):
+    say("case: pool of 8 vs each alone vs oracle")
+    pooled = gpu_decode(wl8, weights_fp32, list(range(8)), 24)
+    for i in range(8):
+        np.testing.assert_array_equal(pooled[i], solo_frames[i])
+    ref, _, _ = oracle_decode(wl8, weights_fp32, list(range(8)), 24)
+    assert max_err(pooled, ref) <= TOL_F32
+
+
+def test_slot_permutation(wl8, weights_fp32, solo_frames):
+    say("case: join order permuted")
+    order = [5, 2, 7, 0, 3, 6, 1, 4]
+    pooled = gpu_decode(wl8, weights_fp32, order, 24)
+    for k, i in enumerate(order):
+        np.testing.assert_array_equal(pooled[k], solo_frames[i])
+
+
+def test_late_join_retire_and_slot_reuse(wl8, weights_fp32, solo_frames):
+    """Requests join at different steps, one is retired unfinished, its slot is
+    reused by a shorter request (stale encoder rows beyond its length must not
+    matter), survivors are not perturbed."""
+    say("case: late join / neighbour retire / slot reuse")
+    pool = make_pool(wl8, weights_fp32, max_pool=4, max_enc_len=90, max_steps=24, chunk_frames=8)
+    enc = wl8.encoder_outputs
+    long_i = int(np.argmax(wl8.enc_len))
+    short_i = int(np.argmin(wl8.enc_len))
+    others = [i for i in range(8) if i not in (long_i, short_i)][:2]
+    r_long = pool.add_request(enc(long_i), 24)
+    r_a = pool.add_request(enc(others[0]), 24)
+    assert pool.step_n(7) == 14
+    r_b = pool.add_request(enc(others[1]), 24)          # joins 7 steps late
+    assert pool.step_n(5) == 15
+    pool.retire(r_long)                                  # leaves unfinished after 12 frames
+    r_short = pool.add_request(enc(short_i), 24)         # takes the freed slot
+    assert pool.n_active() == 3 and pool.size() == 3
+    total = 0
+    while pool.n_active():
+        total += pool.step()
+    got = {others[0]: _drain(pool, r_a), others[1]: _drain(pool, r_b), short_i: _drain(pool, r_short)}
+    for i, frames in got.items():
+        assert frames.shape == (24, 80)
+        np.testing.assert_array_equal(frames, solo_frames[i])
+    assert total == (24 - 12) + (24 - 5) + 24
+    pool.close()
+
+
+def test_timeline_of_the_paper(wl8, weights_fp32, solo_frames):
+    """The narrative of Sec. 2.2.3 with a 'step' = one chunk iteration of the
+    decoder: request 1 from step 0; requests 2, 3 from step 2; request 1 done
+    in step 3; request 2 done in step 5; request 4 joins for step 6 with 3."""
+    say("case: timeline of Sec. 2.2.3")
+    chunk = 3
+    pool = make_pool(wl8, weights_fp32, max_pool=4, max_enc_len=90, max_steps=24, chunk_frames=chunk)
+    enc = wl8.encoder_outputs
+    frames = {}
+    members = []
+
+    def iteration(ids):
+        members.append(sorted(k for k in ids))
+        advanced = pool.step_n(chunk)
+        assert advanced == chunk * len(ids)
+        for k, rid in ids.items():
+            c, fin = pool.drain_chunk(rid)
+            assert c.shape[0] == chunk
+            frames.setdefault(k, []).append(c.copy())
+
+    r = {1: pool.add_request(enc(0), 4 * chunk)}
+    iteration(r); iteration(r)                           # steps 0, 1
+    r[2] = pool.add_request(enc(1), 4 * chunk)           # arrived during step 1
+    r[3] = pool.add_request(enc(2), 5 * chunk)
+    iteration(r); iteration(r)                           # steps 2, 3
+    assert pool.frames(r[1]) == (4 * chunk, True)
+    pool.retire(r.pop(1))
+    iteration(r); iteration(r)                           # steps 4, 5
+    pool.retire(r.pop(2))
+    r[4] = pool.add_request(enc(3), 2 * chunk)           # arrived at the end of step 5
+    iteration(r)                                         # step 6
+    assert members == [[1], [1], [1, 2, 3], [1, 2, 3], [2, 3], [2, 3], [3, 4]]
+    assert pool.frames(r[3]) == (5 * chunk, True)
+    for k, i in ((1, 0), (2, 1), (3, 2), (4, 3)):
+        got = np.concatenate(frames[k])
+        np.testing.assert_array_equal(got, solo_frames[i][: got.shape[0]])
+    pool.close()
+
+
+def test_drain_chunks_and_errors(wl8, weights_fp32):
+    say("case: drain semantics and error codes")
+    pool = make_pool(wl8, weights_fp32, max_pool=2, max_enc_len=90, max_steps=24, chunk_frames=10)
+    assert pool.step() == 0                               # empty pool: a no-op
+    enc = wl8.encoder_outputs
+    a = pool.add_request(enc(0), 23)
+    b = pool.add_request(enc(1), 5)
+    with pytest.raises(binding.TtsError) as e:
+        pool.add_request(enc(2), 5)
+    assert e.value.code == binding.TTS_E_FULL
+    for bad_L, bad_n in ((0, 5), (91, 5), (10, 0), (10, 25)):
+        with pytest.raises(binding.TtsError) as e:
+            pool.add_request_raw(enc(2).ctypes.data, bad_L, bad_n)
+        assert e.value.code == binding.TTS_E_INVAL
+    assert pool.step_n(9) == 5 + 9                        # b stops after its 5 frames
+    c, fin = pool.drain_chunk(a)
+    assert c.shape[0] == 0 and not fin                    # 9 < 10: chunk not ready
+    c, fin = pool.drain_chunk(b)
+    assert c.shape[0] == 5 and fin                        # finished: short last chunk
+    c, fin = pool.drain_chunk(b)
+    assert c.shape[0] == 0 and fin
+    pool.retire(b)
+    with pytest.raises(binding.TtsError) as e:
+        pool.drain_chunk(b)
+    assert e.value.code == binding.TTS_E_NOTFOUND
+    with pytest.raises(binding.TtsError) as e:
+        pool.retire(b)
+    assert e.value.code == binding.TTS_E_NOTFOUND
+    assert pool.step_n(100) == 14                         # a runs to its cap, then nothing advances
+    sizes = []
+    while True:
+        c, fin = pool.drain_chunk(a)
+        sizes.append(c.shape[0])
+        if fin:
+            break
+    assert sizes == [10, 10, 3]
+    assert pool.frames(a) == (23, True)
+    pool.close()
+
+
+def test_snapshot_resume(wl8, weights_fp32, solo_frames):
+    """The carried state set of Sec. 2.1.3 is complete: a fresh request restored
+    from get_state continues on the same trajectory.  (Not bit-exact: restoring
+    M_last recomputes its prenet with another summation order than the step.)"""
+    say("case: snapshot / resume through get_state, set_state")
+    pool = make_pool(wl8, weights_fp32, max_pool=2, max_enc_len=90, max_steps=24, chunk_frames=24)
+    enc = wl8.encoder_outputs
+    a = pool.add_request(enc(4), 24)
+    pool.step_n(9)
+    snap = {k: pool.get_state(a, k) for k in binding.STATE}
+    assert snap["w_last"].shape[0] == wl8.enc_len[4] and abs(snap["w_last"].sum() - 1) < 1e-5
+    assert abs(snap["w_acc"].sum() - 9) < 1e-4
+    b = pool.add_request(enc(4), 15)
+    for k, v in snap.items():
+        pool.set_state(b, k, v)
+    pool.retire(a)
+    pool.step_n(15)
+    got = _drain(pool, b)
+    assert got.shape == (15, 80)
+    assert np.abs(got - solo_frames[4][9:24]).max() <= 1e-5
+    pool.close()
+
+
+def test_stop_threshold(wl8):
+    """sigmoid(stop logit) > threshold ends a request; the tripping frame is kept."""
+    say("case: stop threshold")
+    from oracle import oracle as orc
+    w = synth.make_weights()
+    w["stop_b"] = w["stop_b"].copy()
+    w["stop_b"][:] = 0.2
+    thr = 0.62          # request 0 trips at its 4th frame; every other margin is >= 5e-3
+    pool = make_pool(wl8, w, max_pool=8, max_enc_len=90, max_steps=24, chunk_frames=24, stop_threshold=thr)
+    ids = [pool.add_request(wl8.encoder_outputs(i), 24) for i in range(8)]
+    pool.step_n(24)
+    W = orc.Weights(w)
+    n_early = 0
+    for i, rid in enumerate(ids):
+        r = orc.Request(wl8.dims, W, wl8.encoder_outputs(i), 24, stop_threshold=thr)
+        ref, stops = [], []
+        while True:
+            o = r.step()
+            if o is None:
+                break
+            ref.append(o[0]); stops.append(o[1])
+        # the decision is only checked where the oracle's margin is clear of rounding
+        margin = min(abs(1 / (1 + np.exp(-s)) - thr) for s in stops)
+        n, fin = pool.frames(rid)
+        assert fin
+        if margin > 1e-4:
+            assert n == len(ref)
+            got = _drain(pool, rid)
+            assert np.abs(got - np.array(ref)).max() <= TOL_F32
+            assert np.abs(pool.stop_logits(rid, 0, n) - np.array(stops)).max() <= TOL_F32
+            n_early += n < 24
+    assert n_early >= 1
+    pool.close()
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+def test_graph_equals_plain_launches_and_is_deterministic(wl8, bf16):
+    say(f"case: graph vs plain launches, repeatability (bf16={bf16})")
+    wl = synth.small_workload(8, 5, 90, 24, 24, seed=11, bf16=bf16)
+    w = synth.make_weights(bf16=bf16)
+    a = gpu_decode(wl, w, list(range(8)), 24, use_graph=True)
+    b = gpu_decode(wl, w, list(range(8)), 24, use_graph=False)
+    c = gpu_decode(wl, w, list(range(8)), 24, use_graph=True)
+    np.testing.assert_array_equal(a, b)
+    np.testing.assert_array_equal(a, c)
+
+
+def test_device_pointer_input(wl8, weights_fp32, solo_frames):
+    import torch
+    say("case: encoder outputs handed over in device memory")
+    pool = make_pool(wl8, weights_fp32, max_pool=2, max_enc_len=90, max_steps=24, chunk_frames=24)
+    t = torch.from_numpy(wl8.encoder_outputs(6)).to(pool.device)
+    rid = pool.add_request(t, 24)
+    pool.step_n(24)
+    np.testing.assert_array_equal(_drain(pool, rid), solo_frames[6])
+    pool.close()
+
+
+@pytest.mark.parametrize("L,n_steps,max_pool", [(1, 1, 1), (1, 6, 5), (16, 3, 17), (17, 3, 33), (1024, 3, 2)])
+def test_edge_sizes_fp32(L, n_steps, max_pool, weights_fp32):
+    say(f"case: edge sizes L={L} n_steps={n_steps} max_pool={max_pool}")
+    wl = synth.small_workload(1, L, L, n_steps, n_steps, seed=100 + L)
+    pool = make_pool(wl, weights_fp32, max_pool=max_pool, max_enc_len=max(L, 1), max_steps=n_steps, chunk_frames=4)
+    rid = pool.add_request(wl.encoder_outputs(0), n_steps)
+    pool.step_n(n_steps + 2)
+    got = _drain(pool, rid)[None]
+    pool.close()
+    ref, _, _ = oracle_decode(wl, weights_fp32, [0], n_steps)
+    assert got.shape == (1, n_steps, 80)
+    assert max_err(got, ref) <= TOL_F32
+
+
+def test_single_location_channel():
+    say("case: location conv with one input channel (W_acc only)")
+    dims = dict(synth.DIMS, loc_in_channels=1)
+    w = synth.make_weights(dims=dims)
+    wl = synth.small_workload(3, 20, 60, 12, 12, seed=21)
+    wl.dims = dims
+    got = gpu_decode(wl, w, [0, 1, 2], 12)
+    ref, _, _ = oracle_decode(wl, w, [0, 1, 2], 12)
+    assert max_err(got, ref) <= TOL_F32
+
+
+def test_c4_full_pool_bf16(weights_bf16):
+    """256 requests at the full c4 shape (bench launch configuration: graphs,
+    bf16 memory): oracle on a 16-request sample over 50 steps; the other
+    requests are covered by the pool-composition invariance."""
+    wl = synth.workload("c4")
+    say("case c4: 256 requests L in [50,400], first 50 steps, bf16; oracle on 16 of them")
+    gpu = gpu_decode(wl, weights_bf16, list(range(256)), 50)
+    assert np.isfinite(gpu).all()
+    sample = list(range(0, 256, 16))
+    ref, _, _ = oracle_decode(wl, weights_bf16, sample, 50, n_threads=16)
+    err = max_err(gpu[sample], ref)
+    say(f"  max abs err {err:.3e}")
+    assert err <= TOL_BF16
+    solo = gpu_decode(wl, weights_bf16, [37], 50)
+    np.testing.assert_array_equal(solo[0], gpu[37])
+
+
+def test_c3_shrinking_pool_full_job(weights_bf16):
+    """The whole c3 job as the benchmark runs it (requests retire at their own
+    end): every request produces exactly its frame count, sampled requests match
+    the oracle over their first 50 frames and stay finite to the end."""
+    wl = synth.workload("c3")
+    say("case c3: full job, 64 requests, pool shrinks")
+    pool = make_pool(wl, weights_bf16)
+    ids = [pool.add_request(wl.encoder_outputs(i), int(wl.n_steps[i])) for i in range(64)]
+    total = 0
+    while pool.n_active():
+        total += pool.step_n(40)
+        for i, rid in enumerate(ids):
+            if rid is not None and pool.frames(rid)[1] and i not in (3, 30, 59):
+                pool.retire(rid)
+                ids[i] = None
+    assert total == int(wl.n_steps.sum())
+    sample = [3, 30, 59]
+    ref, _, _ = oracle_decode(wl, weights_bf16, sample, 50, n_threads=3)
+    for k, i in enumerate(sample):
+        got = _drain(pool, ids[i])
+        assert got.shape[0] == wl.n_steps[i] and np.isfinite(got).all()
+        assert np.abs(got[:50] - ref[k]).max() <= TOL_BF16
+    pool.close()
