@@ -1,5 +1,6 @@
 // Decoder-step kernels for gfx950 (MI355X).  One step of paper Eq. 2 for a pool
-// of requests is four kernels:
+// of requests is four kernels (every extra kernel costs a launch gap plus a chain
+// of dependent memory round trips, about 4-6 us on this machine):
 //   k_lstm<att>   gates GEMM on MFMA + fused cell        (Eq. 2 line 1)
 //   k_lsa         query, location features, energies, ragged softmax, context,
 //                 W_acc update                            (Eq. 2 lines 2 and 4)
@@ -300,10 +301,10 @@ template <> struct LsaTile<bf16_t> {
     }
 };
 
-template <typename XT, typename MT>
+template <typename XT, typename MT, int S>
 __global__ __launch_bounds__(LSA_THREADS) void k_lsa(DevPtrs d, int cur)
 {
-    const int pi = blockIdx.x;
+    const int pi = blockIdx.x / S, sp = blockIdx.x % S;
     if (pi >= d.table[0]) return;
     const int slot = d.table[TABLE_SLOTS + pi];
     if (d.done[slot]) return;
@@ -317,7 +318,7 @@ __global__ __launch_bounds__(LSA_THREADS) void k_lsa(DevPtrs d, int cur)
     __shared__ float s_u[2][LSA_UPAD];            // s_u[c][x] = u_c[x - 15]
     __shared__ float s_e[MAX_ENC_LEN];
     __shared__ float s_red[2 * LSA_WAVES];
-    __shared__ __attribute__((aligned(16))) float s_ctx[LSA_WAVES][ENC];   // also the partial q sums
+    __shared__ __attribute__((aligned(16))) float s_ctx[LSA_WAVES][ENC];
 
     constexpr int KB = Frag<XT>::KB;
     constexpr int NPM = Vec16<MT>::N;
@@ -327,23 +328,6 @@ __global__ __launch_bounds__(LSA_THREADS) void k_lsa(DevPtrs d, int cur)
     const float* wa = d.w_acc[cur] + (size_t)slot * d.max_enc_len;
 
     // ---- everything the prologue needs is requested before anything is consumed
-    // q = W_q h_att: wave w contracts k in [128 w, 128 w + 128) for all 128 outputs
-    constexpr int NKQ = HID / KB;                 // fragments per row tile of W_q
-    constexpr int NKW = NKQ / LSA_WAVES;          // fragments per wave
-    constexpr int MG = sizeof(XT) == 2 ? 8 : 2;   // row tiles whose fragments are in flight together
-    const uint4* Wq = reinterpret_cast<const uint4*>(d.Wq) + (size_t)(wave * NKW) * 64 + lane;
-    // B operand: every column is this request's h_att (column slot%16 of its tile)
-    const uint4* hx = reinterpret_cast<const uint4*>(d.xdec[cur]) +
-                      xfrag(K_DEC / KB, slot >> 4, XD_HA / KB + wave * NKW, (slot & 15) + 16 * g);
-    uint4 hb[NKW];
-#pragma unroll
-    for (int f = 0; f < NKW; ++f) hb[f] = hx[(size_t)f * 64];
-    uint4 qa[MG][NKW];
-#pragma unroll
-    for (int m = 0; m < MG; ++m)
-#pragma unroll
-        for (int f = 0; f < NKW; ++f) qa[m][f] = Wq[((size_t)m * NKQ + f) * 64];
-
     constexpr int UPT = (LSA_UPAD + LSA_THREADS - 1) / LSA_THREADS;
     float ul[UPT], ua[UPT];
 #pragma unroll
@@ -354,6 +338,22 @@ __global__ __launch_bounds__(LSA_THREADS) void k_lsa(DevPtrs d, int cur)
         ua[i] = in ? wa[j] : 0.f;
     }
     const float vreg = tid < ATT ? d.v[tid] : 0.f;
+    // q = W_q h_att: wave w contracts k in [128 w, 128 w + 128) for all 128 outputs; every column
+    // of the B operand is this request's h_att (column slot%16 of its tile)
+    constexpr int NKQ = HID / KB;                 // fragments per row tile of W_q
+    constexpr int NKW = NKQ / LSA_WAVES;          // fragments per wave
+    constexpr int MG = sizeof(XT) == 2 ? 8 : 2;   // row tiles whose fragments are in flight together
+    const uint4* Wq = reinterpret_cast<const uint4*>(d.Wq) + (size_t)(wave * NKW) * 64 + lane;
+    const uint4* hx = reinterpret_cast<const uint4*>(d.xdec[cur]) +
+                      xfrag(K_DEC / KB, slot >> 4, XD_HA / KB + wave * NKW, (slot & 15) + 16 * g);
+    uint4 hb[NKW];
+#pragma unroll
+    for (int f = 0; f < NKW; ++f) hb[f] = hx[(size_t)f * 64];
+    uint4 qa[MG][NKW];
+#pragma unroll
+    for (int m = 0; m < MG; ++m)
+#pragma unroll
+        for (int f = 0; f < NKW; ++f) qa[m][f] = Wq[((size_t)m * NKQ + f) * 64];
     LsaTile<XT> tile;
     if constexpr (sizeof(XT) == 2) tile.load(d, lane);   // the fp32 operands are too many registers to hold this early
     constexpr bool PM_AHEAD = sizeof(XT) == 2;    // fp32 operands leave no registers for a second PM row
@@ -363,8 +363,6 @@ __global__ __launch_bounds__(LSA_THREADS) void k_lsa(DevPtrs d, int cur)
 #pragma unroll
         for (int i = 0; i < NV; ++i) pmv[i] = *reinterpret_cast<const uint4*>(pm + i * NPM);
     }
-
-    // ---- q partial sums
 #pragma unroll
     for (int m0 = 0; m0 < 8; m0 += MG) {
         if (m0 > 0) {
@@ -378,7 +376,7 @@ __global__ __launch_bounds__(LSA_THREADS) void k_lsa(DevPtrs d, int cur)
             floatx4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int f = 0; f < NKW; ++f) acc = mfma_frag<XT>(qa[m][f], hb[f], acc);
-            // every column holds the same h: take column 0
+            // every column holds the same h: take column 0 (s_ctx doubles as the partial-q buffer)
             if (jl == 0) *reinterpret_cast<floatx4*>(&s_ctx[wave][16 * (m0 + m) + 4 * g]) = acc;
         }
     }
@@ -401,7 +399,9 @@ __global__ __launch_bounds__(LSA_THREADS) void k_lsa(DevPtrs d, int cur)
     }
     __syncthreads();
 
-    // ---- energies, one 16-position tile per wave at a time; PM of the next tile is already in flight
+    // ---- energies, one 16-position tile per wave at a time; PM of the next tile is already in flight.
+    // With S > 1 every workgroup of the request computes all energies: they are cheap next to the
+    // encoder-row stream, and it keeps the softmax exact and local.
     for (int tt = wave; tt < ntile; tt += LSA_WAVES) {
         const int j = tt * 16 + jl;
         uint4 pmc[NV];
@@ -443,18 +443,30 @@ __global__ __launch_bounds__(LSA_THREADS) void k_lsa(DevPtrs d, int cur)
         if (g == 0 && j < L) s_e[j] = e;
     }
 
-    // ---- context: wave w takes positions w, w+8, ...; lane takes 8 columns; NR rows in flight.
-    // The first batch of encoder rows is requested before the softmax needs its barriers.
-    constexpr int NR = sizeof(MT) == 2 ? 16 : 8;
+    // ---- context over this workgroup's ENC / S columns: a wave-wide load covers S encoder rows
+    // (64 / S lanes x 8 columns each), NR loads in flight per wave.  The first batch is requested
+    // before the softmax needs its barriers.
+    // The sum over positions is taken in an order that does not depend on S: position x belongs to
+    // class x % 32 = 4 * wave + r, each class is summed in increasing x, then
+    // a = sum_{wave = 0..7} ((c[0] + c[1]) + (c[2] + c[3])), so that a request's result is bit-identical
+    // whatever the pool size (and hence S) happens to be.
+    constexpr int FS = ENC / S;                     // columns of this workgroup
+    constexpr int LPR = 64 / S;                     // lanes per encoder row
+    constexpr int NA = 4 / S;                       // position classes per lane
+    constexpr int NR = sizeof(MT) == 2 ? 16 : 8;    // rows in flight per lane
+    constexpr int NP = NR / NA;                     // 32-position passes in flight
     constexpr int VPR = 8 * (int)sizeof(MT) / 16;   // 16-byte loads per row per lane
-    const MT* Fm = reinterpret_cast<const MT*>(d.Fmem) + (size_t)slot * d.max_enc_len * ENC + lane * 8;
-    uint4 rows[NR][VPR];
+    const int xw = wave * 4 + (lane / LPR) * NA;    // this lane's first class
+    const MT* Fm = reinterpret_cast<const MT*>(d.Fmem) + (size_t)slot * d.max_enc_len * ENC + sp * FS + (lane % LPR) * 8;
+    uint4 rows[NP][NA][VPR];
 #pragma unroll
-    for (int r = 0; r < NR; ++r) {
-        const MT* row = Fm + (size_t)min(wave + r * LSA_WAVES, L - 1) * ENC;
+    for (int pp = 0; pp < NP; ++pp)
 #pragma unroll
-        for (int v = 0; v < VPR; ++v) rows[r][v] = *reinterpret_cast<const uint4*>(row + v * NPM);
-    }
+        for (int c = 0; c < NA; ++c) {
+            const MT* row = Fm + (size_t)min(pp * 32 + xw + c, L - 1) * ENC;
+#pragma unroll
+            for (int v = 0; v < VPR; ++v) rows[pp][c][v] = *reinterpret_cast<const uint4*>(row + v * NPM);
+        }
     __syncthreads();
 
     // ---- ragged softmax over j < L
@@ -481,44 +493,64 @@ __global__ __launch_bounds__(LSA_THREADS) void k_lsa(DevPtrs d, int cur)
     const float inv = 1.0f / sum;
 
     {
-        float acc[8];
+        float acc[NA][8];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) acc[i] = 0.f;
-        for (int x0 = wave; x0 < L; x0 += LSA_WAVES * NR) {
+        for (int c = 0; c < NA; ++c)
 #pragma unroll
-            for (int r = 0; r < NR; ++r) {
-                const int x = x0 + r * LSA_WAVES;
-                const float w = x < L ? s_e[x] : 0.f;
-                float fv[8];
+            for (int i = 0; i < 8; ++i) acc[c][i] = 0.f;
+        for (int x0 = 0; x0 < L; x0 += 32 * NP) {
 #pragma unroll
-                for (int v = 0; v < VPR; ++v) Vec16<MT>::unpack(rows[r][v], fv + v * NPM);
+            for (int pp = 0; pp < NP; ++pp)
 #pragma unroll
-                for (int i = 0; i < 8; ++i) acc[i] += w * fv[i];
-                // refill this register row with the row NR rounds ahead (unconditional: past
-                // the end it re-reads the last row with weight zero)
-                const MT* row = Fm + (size_t)min(x + NR * LSA_WAVES, L - 1) * ENC;
+                for (int c = 0; c < NA; ++c) {
+                    const int x = x0 + pp * 32 + xw + c;
+                    const float w = x < L ? s_e[x] : 0.f;
+                    float fv[8];
 #pragma unroll
-                for (int v = 0; v < VPR; ++v) rows[r][v] = *reinterpret_cast<const uint4*>(row + v * NPM);
-            }
+                    for (int v = 0; v < VPR; ++v) Vec16<MT>::unpack(rows[pp][c][v], fv + v * NPM);
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) acc[c][i] = fmaf(w, fv[i], acc[c][i]);
+                    // refill this register row with the row NP passes ahead (unconditional: past
+                    // the end it re-reads the last row with weight zero)
+                    const MT* row = Fm + (size_t)min(x + 32 * NP, L - 1) * ENC;
+#pragma unroll
+                    for (int v = 0; v < VPR; ++v) rows[pp][c][v] = *reinterpret_cast<const uint4*>(row + v * NPM);
+                }
         }
+        // classes held by one lane are paired here: (c0 + c1) [+ (c2 + c3)]
 #pragma unroll
-        for (int i = 0; i < 8; ++i) s_ctx[wave][lane * 8 + i] = acc[i];
+        for (int i = 0; i < 8; ++i) {
+            float t = acc[0][i];
+            if constexpr (NA >= 2) t = acc[0][i] + acc[1][i];
+            if constexpr (NA == 4) t = t + (acc[2][i] + acc[3][i]);
+            s_ctx[wave][lane * 8 + i] = t;
+        }
     }
     __syncthreads();
 
     XT* xa = reinterpret_cast<XT*>(d.xatt[cur ^ 1]);
     XT* xd = reinterpret_cast<XT*>(d.xdec[cur]);
-    float* wl_out = d.w_last[cur ^ 1] + (size_t)slot * d.max_enc_len;
-    float* wa_out = d.w_acc[cur ^ 1] + (size_t)slot * d.max_enc_len;
-    for (int k = tid; k < ENC; k += LSA_THREADS) {
+    for (int f = tid; f < FS; f += LSA_THREADS) {
+        // column f of this workgroup: lane f/8 of each row group, element f%8
+        const int e0 = (f / 8) * 8 + (f & 7);
         float c = 0.f;
 #pragma unroll
-        for (int w = 0; w < LSA_WAVES; ++w) c += s_ctx[w][k];
+        for (int w = 0; w < LSA_WAVES; ++w) {
+            float t;
+            if constexpr (S == 1) t = s_ctx[w][e0];
+            else if constexpr (S == 2) t = s_ctx[w][e0] + s_ctx[w][LPR * 8 + e0];
+            else t = (s_ctx[w][e0] + s_ctx[w][LPR * 8 + e0]) + (s_ctx[w][2 * LPR * 8 + e0] + s_ctx[w][3 * LPR * 8 + e0]);
+            c += t;
+        }
         const XT a = from_float<XT>(c * inv);
+        const int k = sp * FS + f;
         xa[xoff<XT>(K_ATT / KB, slot, XA_A + k)] = a;
         xd[xoff<XT>(K_DEC / KB, slot, XD_A + k)] = a;
     }
-    for (int x = tid; x < L; x += LSA_THREADS) {
+    // the new weights: every workgroup of the request holds all of them, each writes its share
+    float* wl_out = d.w_last[cur ^ 1] + (size_t)slot * d.max_enc_len;
+    float* wa_out = d.w_acc[cur ^ 1] + (size_t)slot * d.max_enc_len;
+    for (int x = sp + S * tid; x < L; x += S * LSA_THREADS) {
         const float w = s_e[x] * inv;
         wl_out[x] = w;
         wa_out[x] = s_u[1][x + LOC_PAD] + w;
@@ -813,7 +845,7 @@ __global__ __launch_bounds__(256) void k_x_set(XT* X, int NK, int slot, int off,
 // launch wrappers
 // ---------------------------------------------------------------------------
 template <typename XT, typename MT>
-static hipError_t step_typed(const DevPtrs& d, int n_req, int n_tiles, int cur, hipStream_t s, hipEvent_t* ev)
+static hipError_t step_typed(const DevPtrs& d, int n_req, int n_tiles, int lsa_split, int cur, hipStream_t s, hipEvent_t* ev)
 {
     constexpr int KB = Frag<XT>::KB;
     auto mark = [&](int i) { if (ev) (void)hipEventRecord(ev[i], s); };
@@ -822,12 +854,14 @@ static hipError_t step_typed(const DevPtrs& d, int n_req, int n_tiles, int cur, 
     XT* xdec_cur = reinterpret_cast<XT*>(d.xdec[cur]);
     XT* xdec_nxt = reinterpret_cast<XT*>(d.xdec[cur ^ 1]);
     mark(0);
-    // H_att(t): consumed by this step's decoder LSTM / LSA and by the next step's attention LSTM
+    // H_att(t): consumed by this step's decoder LSTM / attention and by the next step's attention LSTM
     hipLaunchKernelGGL((k_lstm<XT, K_ATT>), dim3(HID / 4), dim3(LSTM_WAVES * 64), 0, s,
                        d.Wa, d.ba, xatt_cur, d.c_att, xdec_cur, K_DEC / KB, XD_HA, xatt_nxt, K_ATT / KB, XA_H,
                        d.table, d.live, d.done);
     mark(1);
-    hipLaunchKernelGGL((k_lsa<XT, MT>), dim3(n_req), dim3(LSA_THREADS), 0, s, d, cur);
+    if (lsa_split == 4) hipLaunchKernelGGL((k_lsa<XT, MT, 4>), dim3(n_req * 4), dim3(LSA_THREADS), 0, s, d, cur);
+    else if (lsa_split == 2) hipLaunchKernelGGL((k_lsa<XT, MT, 2>), dim3(n_req * 2), dim3(LSA_THREADS), 0, s, d, cur);
+    else hipLaunchKernelGGL((k_lsa<XT, MT, 1>), dim3(n_req), dim3(LSA_THREADS), 0, s, d, cur);
     mark(2);
     // H_dec(t): consumed by this step's projection and the next step's decoder LSTM (same buffer)
     hipLaunchKernelGGL((k_lstm<XT, K_DEC>), dim3(HID / 4), dim3(LSTM_WAVES * 64), 0, s,
@@ -842,9 +876,9 @@ static hipError_t step_typed(const DevPtrs& d, int n_req, int n_tiles, int cur, 
 hipError_t launch_step(const DevPtrs& d, const StepLaunch& cfg, int cur, hipStream_t s, hipEvent_t* ev)
 {
     if (cfg.n_blocks < 1 || cfg.n_tiles < 1) return hipSuccess;
-    if (cfg.wdtype == 0 && cfg.mdtype == 0) return step_typed<float, float>(d, cfg.n_blocks, cfg.n_tiles, cur, s, ev);
-    if (cfg.wdtype == 1 && cfg.mdtype == 1) return step_typed<bf16_t, bf16_t>(d, cfg.n_blocks, cfg.n_tiles, cur, s, ev);
-    if (cfg.wdtype == 1 && cfg.mdtype == 0) return step_typed<bf16_t, float>(d, cfg.n_blocks, cfg.n_tiles, cur, s, ev);
+    if (cfg.wdtype == 0 && cfg.mdtype == 0) return step_typed<float, float>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cur, s, ev);
+    if (cfg.wdtype == 1 && cfg.mdtype == 1) return step_typed<bf16_t, bf16_t>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cur, s, ev);
+    if (cfg.wdtype == 1 && cfg.mdtype == 0) return step_typed<bf16_t, float>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cur, s, ev);
     return hipErrorInvalidValue;
 }
 

@@ -430,6 +430,9 @@ extern "C" int tts_pool_add_request(tts_pool* p, const float* enc_out, int L, in
     return TTS_OK;
 }
 
+// workgroups per request in the attention kernel: more when the pool alone cannot fill the chip
+static int lsa_split_for(int n_blocks) { return n_blocks <= 64 ? 4 : (n_blocks <= 128 ? 2 : 1); }
+
 // most steps captured into one graph
 static const int MAX_GRAPH_STEPS = 32;
 
@@ -472,6 +475,7 @@ static int launch_steps(tts_pool* p, int n_active, int nsteps)
     if (!p->cfg.use_graph) {
         sl.n_blocks = n_active;
         sl.n_tiles = p->n_tiles;
+        sl.lsa_split = lsa_split_for(n_active);
         for (int i = 0; i < nsteps; ++i) HIP_TRY(launch_step(p->d, sl, p->parity ^ (i & 1), p->stream));
         return TTS_OK;
     }
@@ -481,6 +485,7 @@ static int launch_steps(tts_pool* p, int n_active, int nsteps)
     if (it == p->graphs.end()) {
         sl.n_blocks = bucket;
         sl.n_tiles = (p->cfg.max_pool + 15) / 16;   // per-tile workgroups beyond the active tiles exit at once
+        sl.lsa_split = lsa_split_for(bucket);
         hipGraph_t g = nullptr;
         hipGraphExec_t ge = nullptr;
         HIP_TRY(hipStreamBeginCapture(p->stream, hipStreamCaptureModeThreadLocal));
@@ -556,7 +561,7 @@ extern "C" int tts_pool_kernel_times(tts_pool* p, int n, float* out_us, int cap,
         const int n_active = (int)p->book->active().size();
         if (n_active == 0) break;
         if ((rc = push_table(p))) break;
-        StepLaunch sl{p->cfg.weight_dtype, p->cfg.memory_dtype, n_active, p->n_tiles};
+        StepLaunch sl{p->cfg.weight_dtype, p->cfg.memory_dtype, n_active, p->n_tiles, lsa_split_for(n_active)};
         hipError_t e = launch_step(p->d, sl, p->parity, p->stream, ev);
         if (e == hipSuccess) e = hipEventSynchronize(ev[N_STEP_KERNELS]);
         for (int k = 0; k < N_STEP_KERNELS && e == hipSuccess; ++k) {
