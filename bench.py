@@ -91,6 +91,9 @@ def main():
     ap.add_argument("--no-graph", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-stream", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run ten plain device copies of 256 MiB: a kernel of known traffic to scale "
+                         "rocprofv3's FETCH_SIZE / WRITE_SIZE readings with")
     ap.add_argument("--profile-only", action="store_true",
                     help="only the timed steps (for rocprofv3 runs): no cpu baseline, no stream load")
     args = ap.parse_args()
@@ -105,6 +108,15 @@ def main():
     from paper_2211_13939_amd import binding, synth
 
     assert torch.cuda.is_available(), "bench.py needs the GPU"
+    if args.copy_calibration:
+        n = 256 << 20
+        src = torch.full((n,), 7, dtype=torch.uint8, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(10):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration": {"bytes_read": n, "bytes_written": n, "copies": 10}}))
+        return
     wl = synth.workload(args.workload)
     weights = synth.make_weights(bf16=wl.bf16)
     cfg = binding.make_config(wl.dims, max_pool=wl.n_requests, max_enc_len=int(wl.enc_len.max()),
@@ -174,12 +186,21 @@ def main():
                    "frames_timed": int(frames)},
         "full_pool": {"pool": P, "us_per_step": step_us, "frames_per_s": P / (step_us * 1e-6)},
     }
+    event_cost_us = kernel_us.pop("event_cost", None)
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", f"{args.workload}_bf16_traffic.json")
+    if os.path.exists(tpath):
+        traffic = json.load(open(tpath))
     if kernel_us:
         dom = max(kernel_us, key=kernel_us.get)
         out["roofline"] = {"bound": "hbm", "kernel": dom, "achieved": per_kernel[dom] / (kernel_us[dom] * 1e-6) / 1e9,
                            "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                           "frac": per_kernel[dom] / (kernel_us[dom] * 1e-6) / 1e9 / HBM_PEAK_GBS, "traffic": None,
-                           "kernel_us": kernel_us, "algorithmic_bytes": per_kernel}
+                           "frac": per_kernel[dom] / (kernel_us[dom] * 1e-6) / 1e9 / HBM_PEAK_GBS,
+                           "traffic": traffic.get(dom) if traffic else None,
+                           "kernel_us": kernel_us, "event_cost_us": event_cost_us, "algorithmic_bytes": per_kernel,
+                           "note": "kernel_us: HIP-event intervals around each kernel of 30 un-graphed full-pool steps "
+                                   "queued back to back, minus the measured cost of an event; traffic: rocprofv3 "
+                                   "FETCH_SIZE + WRITE_SIZE per launch (profiles/)"}
     else:
         out["roofline"] = {"bound": "hbm", "kernel": "step (4 kernels, one graph launch)",
                            "achieved": step_bytes / (step_us * 1e-6) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",

@@ -174,11 +174,15 @@ int tts_pool_sync(tts_pool *pool);
 int tts_pool_timing(tts_pool *pool, int enable);
 int tts_pool_elapsed_ms(tts_pool *pool, float *out_ms);
 
-/* Profiling aid: run `n` steps WITHOUT the graph, with a HIP event between
- * consecutive kernels, and return the average device time of each kernel of
- * the step in microseconds in out_us (room for `cap` values; *out_n_kernels
- * receives how many there are: attention LSTM, attention, decoder LSTM,
- * projection + prenet).  The steps are real: requests advance.  Waits for the stream. */
+/* Profiling aid: run `n` steps WITHOUT the graph, queued back to back with a
+ * HIP event between consecutive kernels, and return the average device time of
+ * each kernel of the step in microseconds in out_us (room for `cap` values;
+ * *out_n_kernels receives how many there are: attention LSTM, attention,
+ * decoder LSTM, projection + prenet).  The device cost of an event itself is
+ * measured with adjacent events and subtracted; if cap > *out_n_kernels it is
+ * stored after the kernel times.  The intervals still contain the launch gap,
+ * so they are upper bounds of the kernels' own durations.  The steps are real:
+ * requests advance.  Waits for the stream. */
 int tts_pool_kernel_times(tts_pool *pool, int n, float *out_us, int cap, int *out_n_kernels);
 
 void tts_pool_destroy(tts_pool *pool);

@@ -240,7 +240,9 @@ class Pool:
         buf = (C.c_float * 8)()
         nk = C.c_int()
         _check(lib().tts_pool_kernel_times(self._h, int(n_steps), buf, 8, C.byref(nk)))
-        return {self.KERNEL_NAMES[i]: float(buf[i]) for i in range(nk.value)}
+        out = {self.KERNEL_NAMES[i]: float(buf[i]) for i in range(nk.value)}
+        out["event_cost"] = float(buf[nk.value])
+        return out
 
     def drain_all(self, rid: int) -> np.ndarray:
         """Every remaining frame of a finished request (host convenience loop over drain_chunk)."""

@@ -25,10 +25,11 @@ constexpr int MAX_POOL = 256;
 constexpr int MAX_ENC_LEN = 1024;
 constexpr int MAX_TILES = MAX_POOL / 16;     // a pool tile = 16 consecutive slots = the 16 columns of one MFMA
 // device table: [0] = number of active requests, [1] = number of active tiles,
-// [TABLE_SLOTS + i] = slot of active request i, [TABLE_TILES + i] = i-th active tile
-constexpr int TABLE_SLOTS = 4;
-constexpr int TABLE_TILES = TABLE_SLOTS + MAX_POOL;
-constexpr int TABLE_INTS = TABLE_TILES + MAX_TILES;
+// [TABLE_TILES + i] = i-th active tile (header and tile list share the first 128 bytes, so a
+// kernel gets both with one round trip), [TABLE_SLOTS + i] = slot of active request i
+constexpr int TABLE_TILES = 2;
+constexpr int TABLE_SLOTS = 32;
+constexpr int TABLE_INTS = TABLE_SLOTS + MAX_POOL;
 
 // offsets inside the activation rows
 constexpr int XA_P = 0, XA_A = PRENET, XA_H = PRENET + ENC;       // x_att = [p | a | h_att]

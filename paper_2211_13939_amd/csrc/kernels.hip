@@ -147,7 +147,11 @@ __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm(
 #pragma unroll
     for (int f = 0; f < NF; ++f) a[f] = Wfrag[xfrag(NK, rt, wave + f * NW, lane)];
 
-    const int n_tiles = table[1];
+    // header and the whole tile list at once (one round trip; the activation loads below depend on it)
+    int hdr[TABLE_TILES + MAX_TILES];
+#pragma unroll
+    for (int i = 0; i < TABLE_TILES + MAX_TILES; ++i) hdr[i] = table[i];
+    const int n_tiles = hdr[1];
     // the first four waves also own the cell update of (pool tile in flight = wave, lane)
     const int unit = rt * 4 + (lane >> 4);
     floatx4 bias4 = {0.f, 0.f, 0.f, 0.f};
@@ -155,11 +159,15 @@ __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm(
 
     __shared__ floatx4 red[NW][4][64];
 
-    for (int tg = 0; tg < n_tiles; tg += 4) {
+#pragma unroll
+    for (int tg = 0; tg < MAX_TILES; tg += 4) {
+        if (tg >= n_tiles) break;
         int slotE = -1;
         float c_old = 0.f;
         if (wave < 4 && tg + wave < n_tiles) {
-            const int sl = table[TABLE_TILES + tg + wave] * 16 + (lane & 15);
+            const int my_tile = wave == 0 ? hdr[TABLE_TILES + tg] : wave == 1 ? hdr[TABLE_TILES + tg + 1]
+                              : wave == 2 ? hdr[TABLE_TILES + tg + 2] : hdr[TABLE_TILES + tg + 3];
+            const int sl = my_tile * 16 + (lane & 15);
             if (live[sl] && !done[sl]) {
                 slotE = sl;
                 c_old = c_state[(size_t)sl * HID + unit];
@@ -171,7 +179,7 @@ __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm(
 #pragma unroll
             for (int t = 0; t < TIF; ++t) {
                 if (tg + t0 + t < n_tiles) {
-                    const int tile = table[TABLE_TILES + tg + t0 + t];
+                    const int tile = hdr[TABLE_TILES + tg + t0 + t];
 #pragma unroll
                     for (int f = 0; f < NF; ++f) b[t][f] = X[xfrag(NK, tile, wave + f * NW, lane)];
                 }

@@ -546,38 +546,56 @@ extern "C" int tts_pool_step_n(tts_pool* p, int n, int64_t* out_frames)
     return step_impl(p, n, out_frames, nullptr);
 }
 
-// n un-graphed steps with an event between consecutive kernels; average device
-// time of each kernel in microseconds
+// n un-graphed steps with an event between consecutive kernels, queued back to
+// back (one wait at the end); average device time of each kernel in
+// microseconds.  An event costs device time of its own: that cost is measured
+// with pairs of adjacent events and subtracted.
 extern "C" int tts_pool_kernel_times(tts_pool* p, int n, float* out_us, int cap, int* out_n_kernels)
 {
-    if (!p || !out_us || n < 1) return fail(TTS_E_INVAL, "bad argument");
+    if (!p || !out_us || n < 1 || n > 4096) return fail(TTS_E_INVAL, "bad argument");
     if (out_n_kernels) *out_n_kernels = N_STEP_KERNELS;
     if (cap < N_STEP_KERNELS) return fail(TTS_E_INVAL, "room for %d kernels, %d needed", cap, N_STEP_KERNELS);
-    hipEvent_t ev[N_STEP_KERNELS + 1];
-    for (auto& e : ev) HIP_TRY(hipEventCreate(&e));
-    double acc[N_STEP_KERNELS] = {0};
-    int done = 0, rc = TTS_OK;
+    const int per = N_STEP_KERNELS + 2;          // events per step: one before, one after each kernel, one more for calibration
+    std::vector<hipEvent_t> ev((size_t)n * per, nullptr);
+    int rc = TTS_OK;
+    for (auto& e : ev)
+        if (hipEventCreate(&e) != hipSuccess) { rc = fail(TTS_E_HIP, "hipEventCreate failed"); break; }
+    int done = 0;
     for (int i = 0; i < n && rc == TTS_OK; ++i) {
         const int n_active = (int)p->book->active().size();
         if (n_active == 0) break;
         if ((rc = push_table(p))) break;
         StepLaunch sl{p->cfg.weight_dtype, p->cfg.memory_dtype, n_active, p->n_tiles, lsa_split_for(n_active)};
-        hipError_t e = launch_step(p->d, sl, p->parity, p->stream, ev);
-        if (e == hipSuccess) e = hipEventSynchronize(ev[N_STEP_KERNELS]);
-        for (int k = 0; k < N_STEP_KERNELS && e == hipSuccess; ++k) {
-            float ms = 0.f;
-            e = hipEventElapsedTime(&ms, ev[k], ev[k + 1]);
-            acc[k] += ms;
-        }
-        if (e != hipSuccess) rc = fail(TTS_E_HIP, "timed step: %s", hipGetErrorString(e));
+        hipEvent_t* e = &ev[(size_t)i * per];
+        hipError_t he = launch_step(p->d, sl, p->parity, p->stream, e);
+        // an empty interval right after the step: the cost of the event itself
+        if (he == hipSuccess) he = hipEventRecord(e[N_STEP_KERNELS + 1], p->stream);
+        if (he != hipSuccess) { rc = fail(TTS_E_HIP, "timed step: %s", hipGetErrorString(he)); break; }
         p->parity ^= 1;
         p->book->step(p->parity);
         ++done;
     }
-    for (auto& e : ev) (void)hipEventDestroy(e);
+    double acc[N_STEP_KERNELS + 1] = {0};
+    if (rc == TTS_OK && done > 0) {
+        hipError_t he = hipStreamSynchronize(p->stream);
+        for (int i = 0; i < done && he == hipSuccess; ++i)
+            for (int k = 0; k <= N_STEP_KERNELS && he == hipSuccess; ++k) {
+                float ms = 0.f;
+                he = hipEventElapsedTime(&ms, ev[(size_t)i * per + k], ev[(size_t)i * per + k + 1]);
+                acc[k] += ms;
+            }
+        if (he != hipSuccess) rc = fail(TTS_E_HIP, "timed step: %s", hipGetErrorString(he));
+    }
+    for (auto& e : ev)
+        if (e) (void)hipEventDestroy(e);
     if (rc) return rc;
     if (done == 0) return fail(TTS_E_INVAL, "the pool is empty");
-    for (int k = 0; k < N_STEP_KERNELS; ++k) out_us[k] = (float)(acc[k] * 1e3 / done);
+    const double ev_cost = acc[N_STEP_KERNELS] / done;
+    for (int k = 0; k < N_STEP_KERNELS; ++k) {
+        const double us = (acc[k] / done - ev_cost) * 1e3;
+        out_us[k] = (float)(us > 0 ? us : 0);
+    }
+    if (cap > N_STEP_KERNELS) out_us[N_STEP_KERNELS] = (float)(ev_cost * 1e3);
     return TTS_OK;
 }
 
