@@ -35,34 +35,51 @@ class OrcWeights(C.Structure):
 _lib = None
 
 
+def load(path: str) -> C.CDLL:
+    """Load one build of the oracle and declare its entry points."""
+    L = C.CDLL(path)
+    _declare(L)
+    return L
+
+
+def use_library(L: Optional[C.CDLL]) -> Optional[C.CDLL]:
+    """Swap the library every function below calls (tests of the pins themselves
+    point them at deliberately broken builds); returns the previous one."""
+    global _lib
+    prev, _lib = _lib, L
+    return prev
+
+
 def lib() -> C.CDLL:
     global _lib
     if _lib is None:
         path = _build.OUT
         if not os.path.exists(path) or os.path.getmtime(path) < os.path.getmtime(_build.SRC):
             _build.build(force=True)
-        L = C.CDLL(path)
-        L.orc_prenet.argtypes = [C.POINTER(OrcDims), _fp, _fp, _dp, _dp]
-        L.orc_lstm_cell.argtypes = [C.c_int, C.c_int, _fp, _fp, _fp, _dp, _dp, _dp]
-        L.orc_memory_projection.argtypes = [C.POINTER(OrcDims), _fp, _fp, C.c_int, C.c_int, _dp]
-        L.orc_location_features.argtypes = [C.c_int, C.c_int, C.c_int, C.c_int, _fp, _dp, _dp]
-        L.orc_lsa.argtypes = [C.POINTER(OrcDims), C.POINTER(OrcWeights), C.c_int, _fp, _dp, _dp, _dp, _dp,
-                              _dp, _dp, _dp]
-        L.orc_projection.argtypes = [C.POINTER(OrcDims), C.POINTER(OrcWeights), _dp, _dp, _dp, _dp]
-        L.orc_request_new.restype = C.c_void_p
-        L.orc_request_new.argtypes = [C.POINTER(OrcDims), C.POINTER(OrcWeights), _fp, C.c_int, C.c_int,
-                                      C.c_int, C.c_double]
-        L.orc_request_free.argtypes = [C.c_void_p]
-        L.orc_request_step.argtypes = [C.c_void_p, _dp, _dp]
-        L.orc_request_get.argtypes = [C.c_void_p, C.c_int, _dp]
-        L.orc_request_set.argtypes = [C.c_void_p, C.c_int, _dp]
-        L.orc_request_frames.argtypes = [C.c_void_p]
-        L.orc_request_finished.argtypes = [C.c_void_p]
-        L.orc_pool_decode.argtypes = [C.POINTER(OrcDims), C.POINTER(OrcWeights), C.c_int,
-                                      C.POINTER(_fp), _ip, _ip, C.c_int, C.c_int, C.c_double, C.c_int,
-                                      _dp, _dp, _ip]
-        _lib = L
+        _lib = load(path)
     return _lib
+
+
+def _declare(L: C.CDLL) -> None:
+    L.orc_prenet.argtypes = [C.POINTER(OrcDims), _fp, _fp, _dp, _dp]
+    L.orc_lstm_cell.argtypes = [C.c_int, C.c_int, _fp, _fp, _fp, _dp, _dp, _dp]
+    L.orc_memory_projection.argtypes = [C.POINTER(OrcDims), _fp, _fp, C.c_int, C.c_int, _dp]
+    L.orc_location_features.argtypes = [C.c_int, C.c_int, C.c_int, C.c_int, _fp, _dp, _dp]
+    L.orc_lsa.argtypes = [C.POINTER(OrcDims), C.POINTER(OrcWeights), C.c_int, _fp, _dp, _dp, _dp, _dp,
+                          _dp, _dp, _dp]
+    L.orc_projection.argtypes = [C.POINTER(OrcDims), C.POINTER(OrcWeights), _dp, _dp, _dp, _dp]
+    L.orc_request_new.restype = C.c_void_p
+    L.orc_request_new.argtypes = [C.POINTER(OrcDims), C.POINTER(OrcWeights), _fp, C.c_int, C.c_int,
+                                  C.c_int, C.c_double]
+    L.orc_request_free.argtypes = [C.c_void_p]
+    L.orc_request_step.argtypes = [C.c_void_p, _dp, _dp]
+    L.orc_request_get.argtypes = [C.c_void_p, C.c_int, _dp]
+    L.orc_request_set.argtypes = [C.c_void_p, C.c_int, _dp]
+    L.orc_request_frames.argtypes = [C.c_void_p]
+    L.orc_request_finished.argtypes = [C.c_void_p]
+    L.orc_pool_decode.argtypes = [C.POINTER(OrcDims), C.POINTER(OrcWeights), C.c_int,
+                                  C.POINTER(_fp), _ip, _ip, C.c_int, C.c_int, C.c_double, C.c_int,
+                                  _dp, _dp, _ip]
 
 
 def _f(a: np.ndarray):

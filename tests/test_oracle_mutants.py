@@ -1,0 +1,137 @@
+"""The pins must be able to tell a wrong oracle from the right one: each case
+plants one plausible mistake in a copy of the oracle's C source (on the CPU, in a
+temporary build), points the pin tests at that build and expects at least one of
+them to fail.  The unmodified source, built the same way, must pass them all."""
+import os
+import subprocess
+import tempfile
+
+import pytest
+
+from oracle import build as obuild
+from oracle import oracle as orc
+from tests import test_oracle_pins as pins
+
+MUTANTS = {
+    "lstm gates f and g swapped":
+        ("double gf = sigmoid(g[hid + u]);\n        double gg = tanh(g[2 * hid + u]);",
+         "double gf = sigmoid(g[2 * hid + u]);\n        double gg = tanh(g[hid + u]);"),
+    "lstm recurrent term dropped":
+        ("for (int k = 0; k < hid; ++k) s += (double)W_hh[(size_t)r * hid + k] * h[k];", ""),
+    "lstm bias dropped":
+        ("double s = (double)b[r];", "double s = 0.0;"),
+    "lstm h uses old cell":
+        ("c[u] = gf * c[u] + gi * gg;\n        h[u] = go * tanh(c[u]);",
+         "h[u] = go * tanh(c[u]);\n        c[u] = gf * c[u] + gi * gg;"),
+    "convolution flipped":
+        ("int jj = j + k - pad;", "int jj = j - k + pad;"),
+    "convolution padding off by one":
+        ("int pad = (ksz - 1) / 2;", "int pad = (ksz - 1) / 2 + 1;"),
+    "location channels swapped":
+        ("memcpy(u, w_last, sizeof(double) * L);\n        memcpy(u + L, w_acc, sizeof(double) * L);",
+         "memcpy(u, w_acc, sizeof(double) * L);\n        memcpy(u + L, w_last, sizeof(double) * L);"),
+    "energy without query":
+        ("tanh(q[a] + pl + PM[(size_t)j * A + a])", "tanh(pl + PM[(size_t)j * A + a])"),
+    "energy without location term":
+        ("tanh(q[a] + pl + PM[(size_t)j * A + a])", "tanh(q[a] + PM[(size_t)j * A + a])"),
+    "softmax not normalised":
+        ("for (int j = 0; j < L; ++j) w[j] /= den;", ""),
+    "memory projection transposed":
+        ("s += (double)mem_w[a * d->enc_dim + k] * (double)F[(size_t)j * d->enc_dim + k];",
+         "s += (double)mem_w[(k * d->att_dim + a) % (d->att_dim * d->enc_dim)] * (double)F[(size_t)j * d->enc_dim + k];"),
+    "context uses transposed weights index":
+        ("for (int j = 0; j < L; ++j) s += w[j] * (double)F[(size_t)j * d->enc_dim + k];",
+         "for (int j = 0; j < L; ++j) s += w[L - 1 - j] * (double)F[(size_t)j * d->enc_dim + k];"),
+    "prenet second relu missing":
+        ("p[o] = s > 0.0 ? s : 0.0;", "p[o] = s;"),
+    "prenet first layer transposed":
+        ("s += (double)W1[o * d->n_mel + i] * m[i];", "s += (double)W1[(i * d->prenet_dim + o) % (d->prenet_dim * d->n_mel)] * m[i];"),
+    "projection concatenation swapped":
+        ("for (int k = 0; k < H; ++k) s += (double)W->mel_w[(size_t)o * IN + k] * h_dec[k];\n"
+         "        for (int k = 0; k < E; ++k) s += (double)W->mel_w[(size_t)o * IN + H + k] * ctx[k];",
+         "for (int k = 0; k < E; ++k) s += (double)W->mel_w[(size_t)o * IN + k] * ctx[k];\n"
+         "        for (int k = 0; k < H; ++k) s += (double)W->mel_w[(size_t)o * IN + E + k] * h_dec[k];"),
+    "attention lstm input order swapped":
+        ("orc_prenet(d, r->W.prenet1, r->W.prenet2, r->m, x);\n    memcpy(x + d->prenet_dim, r->a, sizeof(double) * d->enc_dim);",
+         "orc_prenet(d, r->W.prenet1, r->W.prenet2, r->m, x + d->enc_dim);\n    memcpy(x, r->a, sizeof(double) * d->enc_dim);"),
+    "decoder lstm sees previous context":
+        ("memcpy(x, r->h_att, sizeof(double) * d->att_rnn_dim);\n    memcpy(x + d->att_rnn_dim, r->a, sizeof(double) * d->enc_dim);\n    orc_lstm_cell(dec_in",
+         "orc_lstm_cell(dec_in"),
+    "accumulated weights updated before attention":
+        ("    /* A, W_last = LSA(H_att, F_enc, W_acc) */\n", "    for (int j = 0; j < r->L; ++j) r->w_acc[j] += r->w_last[j];\n"),
+    "accumulated weights not updated":
+        ("r->w_acc[j] += w[j];", ""),
+    "last weights not carried":
+        ("r->w_last[j] = w[j];", ""),
+    "mel not fed back":
+        ("orc_projection(d, &r->W, r->h_dec, r->a, r->m, &stop);",
+         "{ double tmp[512]; orc_projection(d, &r->W, r->h_dec, r->a, tmp, &stop); if (mel_out) memcpy(mel_out, tmp, sizeof(double) * d->n_mel); mel_out = NULL; }"),
+    "stop rule inverted":
+        ("sigmoid(stop) > r->stop_threshold", "sigmoid(stop) < r->stop_threshold"),
+    "bf16 rounding truncates":
+        ("u = (u + 0x7FFFu + lsb) & 0xFFFF0000u;", "u = u & 0xFFFF0000u;"),
+}
+
+# every pin except the two slow full-size ones
+PIN_TESTS = [
+    lambda: pins.test_lstm_zero_weights_closed_form(),
+    lambda: pins.test_lstm_matches_library_cell(1),
+    lambda: [pins.test_location_delta_kernel_shifts(s, c) for s in (-15, -3, 0, 4, 15) for c in (0, 1)],
+    lambda: [pins.test_location_matches_library_conv(L, n) for L in (1, 5, 31, 32, 67) for n in (1, 2)],
+    lambda: pins.test_location_brute_force_tiny(),
+    lambda: pins.test_lsa_softmax_invariants_and_convexity(),
+    lambda: pins.test_lsa_v_zero_gives_uniform_weights_and_column_mean(),
+    lambda: pins.test_lsa_without_query_and_location_is_softmax_of_v_tanh_pm(),
+    lambda: pins.test_lsa_energy_formula_against_numpy_and_library(),
+    lambda: pins.test_lsa_channel_order_last_then_acc(),
+    lambda: pins.test_memory_projection_and_bf16_rounding(),
+    lambda: pins.test_prenet_identity_like_weights_relu(),
+    lambda: pins.test_projection_one_hot_rows_pick_h_then_ctx(),
+    lambda: [pins.test_request_matches_library_composition(n) for n in (1, 2)],
+    lambda: pins.test_concatenation_orders_with_one_hot_probes(),
+    lambda: pins.test_step_order_acc_updated_after_attention(),
+    lambda: pins.test_snapshot_resume(),
+    lambda: pins.test_stop_threshold_ends_request_and_keeps_tripping_frame(),
+    lambda: pins.test_pool_decode_is_each_request_alone_and_thread_invariant(),
+]
+
+
+def _build_variant(src_text: str, workdir: str, name: str):
+    c = os.path.join(workdir, name + ".c")
+    so = os.path.join(workdir, name + ".so")
+    with open(c, "w") as f:
+        f.write(src_text)
+    subprocess.run(["gcc", "-O1", "-std=c99", "-fPIC", "-shared", "-fopenmp", "-w", "-o", so, c, "-lm"], check=True)
+    return orc.load(so)
+
+
+def _pins_fail(lib) -> bool:
+    prev = orc.use_library(lib)
+    try:
+        for t in PIN_TESTS:
+            try:
+                t()
+            except (AssertionError, ValueError):
+                return True
+        return False
+    finally:
+        orc.use_library(prev)
+
+
+@pytest.fixture(scope="module")
+def source():
+    return open(obuild.SRC).read()
+
+
+def test_unmodified_source_passes_every_pin(source):
+    with tempfile.TemporaryDirectory() as tmp:
+        assert not _pins_fail(_build_variant(source, tmp, "clean"))
+
+
+@pytest.mark.parametrize("name", sorted(MUTANTS))
+def test_pins_catch_planted_mistake(name, source):
+    old, new = MUTANTS[name]
+    assert source.count(old) == 1, f"mutation site for '{name}' not found exactly once"
+    with tempfile.TemporaryDirectory() as tmp:
+        lib = _build_variant(source.replace(old, new), tmp, "mutant")
+        assert _pins_fail(lib), f"no pin noticed: {name}"
