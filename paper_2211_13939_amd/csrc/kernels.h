@@ -11,6 +11,7 @@ struct StepLaunch {
     int n_blocks;   // per-request grids are launched with this many blocks (>= n_active)
     int n_tiles;    // per-tile grids are launched with this many blocks (>= active tiles)
     int lsa_split;  // workgroups per request in the attention kernel (1, 2 or 4; they split the context columns)
+    int wide_lstm;  // non-zero: LSTM workgroups own two row tiles and half of the pool tiles (pools of many tiles)
 };
 
 // One decoder step (paper Eq. 2) for every request listed in d.table.

@@ -211,6 +211,97 @@ __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm(
     }
 }
 
+// Variant for pools of more than two tiles: a workgroup owns TWO row tiles
+// (8 hidden units) and half of the pool tiles, grid = 128 row pairs x 2 pool
+// halves.  Every workgroup then pulls 2/16 of the weights' rows and half of the
+// activations through its CU instead of 1/16 and all of them, which is what
+// bounds the kernel once the pool is large (the activations come from L2, and
+// a CU's L2 port, not HBM, is the bottleneck).  The two workgroups that share
+// a row pair sit on the same XCD (blockIdx differs by 128), so the second
+// read of the weights hits that XCD's L2.
+template <typename XT, int K>
+__global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm2(
+    const uint4* __restrict__ Wfrag, const float* __restrict__ bias, const uint4* __restrict__ X,
+    float* __restrict__ c_state, XT* __restrict__ hout0, int nk0, int off0,
+    XT* __restrict__ hout1, int nk1, int off1,
+    const int* __restrict__ table, const int* __restrict__ live, const int* __restrict__ done)
+{
+    constexpr int NW = LSTM_WAVES;
+    constexpr int NK = K / Frag<XT>::KB;
+    constexpr int NF = NK / NW;
+    constexpr int TP = sizeof(XT) == 2 ? 2 : 1;    // pool tiles per round
+
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int rg = blockIdx.x & 127, cg = blockIdx.x >> 7;
+
+    uint4 a[2][NF];
+#pragma unroll
+    for (int r = 0; r < 2; ++r)
+#pragma unroll
+        for (int f = 0; f < NF; ++f) a[r][f] = Wfrag[xfrag(NK, 2 * rg + r, wave + f * NW, lane)];
+
+    __shared__ int s_hdr[TABLE_TILES + MAX_TILES];
+    __shared__ floatx4 red[NW][2 * TP][64];
+    if (threadIdx.x < TABLE_TILES + MAX_TILES) s_hdr[threadIdx.x] = table[threadIdx.x];
+    __syncthreads();
+    const int n_tiles = s_hdr[1];
+    const int half = (n_tiles + 1) >> 1;
+    const int c0 = cg == 0 ? 0 : half, c1 = cg == 0 ? half : n_tiles;
+
+    // waves 0 .. 2 TP - 1 also own a cell update: (pool tile of the round = wave / 2, row tile = wave % 2)
+    const int er = wave & 1, et = wave >> 1;
+    const int unit = (2 * rg + er) * 4 + (lane >> 4);
+    floatx4 bias4 = {0.f, 0.f, 0.f, 0.f};
+    if (wave < 2 * TP) bias4 = *reinterpret_cast<const floatx4*>(bias + unit * 4);
+
+    for (int tp = c0; tp < c1; tp += TP) {
+        int slotE = -1;
+        float c_old = 0.f;
+        if (wave < 2 * TP && tp + et < c1) {
+            const int sl = s_hdr[TABLE_TILES + tp + et] * 16 + (lane & 15);
+            if (live[sl] && !done[sl]) {
+                slotE = sl;
+                c_old = c_state[(size_t)sl * HID + unit];
+            }
+        }
+        uint4 b[TP][NF];
+#pragma unroll
+        for (int t = 0; t < TP; ++t) {
+            if (tp + t < c1) {
+                const int tile = s_hdr[TABLE_TILES + tp + t];
+#pragma unroll
+                for (int f = 0; f < NF; ++f) b[t][f] = X[xfrag(NK, tile, wave + f * NW, lane)];
+            }
+        }
+#pragma unroll
+        for (int t = 0; t < TP; ++t) {
+            if (tp + t < c1) {
+#pragma unroll
+                for (int r = 0; r < 2; ++r) {
+                    floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int f = 0; f < NF; ++f) acc = mfma_frag<XT>(a[r][f], b[t][f], acc);
+                    red[wave][2 * t + r][lane] = acc;
+                }
+            }
+        }
+        __syncthreads();
+        if (slotE >= 0) {
+            floatx4 g = bias4;
+#pragma unroll
+            for (int w = 0; w < NW; ++w) g += red[w][wave][lane];
+            const float gi = sigmoidf_(g[0]), gf = sigmoidf_(g[1]);
+            const float gg = tanhf_(g[2]), go = sigmoidf_(g[3]);
+            const float c = gf * c_old + gi * gg;
+            c_state[(size_t)slotE * HID + unit] = c;
+            const XT h = from_float<XT>(go * tanhf_(c));
+            hout0[xoff<XT>(nk0, slotE, off0 + unit)] = h;
+            hout1[xoff<XT>(nk1, slotE, off1 + unit)] = h;
+        }
+        __syncthreads();
+    }
+}
+
 // ---------------------------------------------------------------------------
 // Location-sensitive attention, one workgroup (8 waves) per request:
 //   q = W_q h_att
@@ -312,13 +403,26 @@ template <> struct LsaTile<bf16_t> {
 template <typename XT, typename MT, int S>
 __global__ __launch_bounds__(LSA_THREADS) void k_lsa(DevPtrs d, int cur)
 {
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int jl = lane & 15, g = lane >> 4;
+    // The query weights do not depend on which request this workgroup serves: their loads go out
+    // before the table is even read.  q = W_q h_att: wave w contracts k in [128 w, 128 w + 128)
+    // for all 128 outputs.
+    constexpr int NKQ = HID / Frag<XT>::KB;       // fragments per row tile of W_q
+    constexpr int NKW = NKQ / LSA_WAVES;          // fragments per wave
+    constexpr int MG = sizeof(XT) == 2 ? 8 : 2;   // row tiles whose fragments are in flight together
+    const uint4* Wq = reinterpret_cast<const uint4*>(d.Wq) + (size_t)(wave * NKW) * 64 + lane;
+    uint4 qa[MG][NKW];
+#pragma unroll
+    for (int m = 0; m < MG; ++m)
+#pragma unroll
+        for (int f = 0; f < NKW; ++f) qa[m][f] = Wq[((size_t)m * NKQ + f) * 64];
+
     const int pi = blockIdx.x / S, sp = blockIdx.x % S;
     if (pi >= d.table[0]) return;
     const int slot = d.table[TABLE_SLOTS + pi];
     if (d.done[slot]) return;
     const int L = d.L[slot];
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    const int jl = lane & 15, g = lane >> 4;
     const int ntile = (L + 15) >> 4;
 
     __shared__ __attribute__((aligned(16))) float s_q[ATT];
@@ -346,22 +450,12 @@ __global__ __launch_bounds__(LSA_THREADS) void k_lsa(DevPtrs d, int cur)
         ua[i] = in ? wa[j] : 0.f;
     }
     const float vreg = tid < ATT ? d.v[tid] : 0.f;
-    // q = W_q h_att: wave w contracts k in [128 w, 128 w + 128) for all 128 outputs; every column
-    // of the B operand is this request's h_att (column slot%16 of its tile)
-    constexpr int NKQ = HID / KB;                 // fragments per row tile of W_q
-    constexpr int NKW = NKQ / LSA_WAVES;          // fragments per wave
-    constexpr int MG = sizeof(XT) == 2 ? 8 : 2;   // row tiles whose fragments are in flight together
-    const uint4* Wq = reinterpret_cast<const uint4*>(d.Wq) + (size_t)(wave * NKW) * 64 + lane;
+    // every column of the B operand of the query product is this request's h_att (column slot%16 of its tile)
     const uint4* hx = reinterpret_cast<const uint4*>(d.xdec[cur]) +
                       xfrag(K_DEC / KB, slot >> 4, XD_HA / KB + wave * NKW, (slot & 15) + 16 * g);
     uint4 hb[NKW];
 #pragma unroll
     for (int f = 0; f < NKW; ++f) hb[f] = hx[(size_t)f * 64];
-    uint4 qa[MG][NKW];
-#pragma unroll
-    for (int m = 0; m < MG; ++m)
-#pragma unroll
-        for (int f = 0; f < NKW; ++f) qa[m][f] = Wq[((size_t)m * NKQ + f) * 64];
     LsaTile<XT> tile;
     if constexpr (sizeof(XT) == 2) tile.load(d, lane);   // the fp32 operands are too many registers to hold this early
     constexpr bool PM_AHEAD = sizeof(XT) == 2;    // fp32 operands leave no registers for a second PM row
@@ -595,13 +689,34 @@ template <> __device__ __forceinline__ uint4 frag_from_f32<bf16_t>(const float* 
 template <typename XT>
 __global__ __launch_bounds__(PROJ_THREADS) void k_proj(DevPtrs d, int cur)
 {
-    if ((int)blockIdx.x >= d.table[1]) return;
-    const int tile = d.table[TABLE_TILES + blockIdx.x];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int jl = lane & 15, g = lane >> 4;
     constexpr int KB = Frag<XT>::KB;
     constexpr int EPL = Frag<XT>::EPL;
     constexpr int NKD = K_DEC / KB;
+
+    // weights of the two prenet layers for this wave's row tiles: requested first (they do not
+    // depend on the tile), used at the end
+    constexpr int NK3 = PrenetK1<XT>::value / KB;
+    constexpr int NK4 = PRENET / KB;
+    uint4 a3[2][NK3], a4[2][NK4];
+    auto load_prenet_weights = [&]() {
+        const uint4* W1 = reinterpret_cast<const uint4*>(d.Wp1) + lane;
+        const uint4* W2 = reinterpret_cast<const uint4*>(d.Wp2) + lane;
+#pragma unroll
+        for (int m = 0; m < 2; ++m) {
+            const int mt = wave + m * PROJ_WAVES;
+#pragma unroll
+            for (int f = 0; f < NK3; ++f) a3[m][f] = W1[((size_t)mt * NK3 + f) * 64];
+#pragma unroll
+            for (int f = 0; f < NK4; ++f) a4[m][f] = W2[((size_t)mt * NK4 + f) * 64];
+        }
+    };
+    constexpr bool PRENET_EARLY = sizeof(XT) == 2;   // the fp32 fragments are too many registers to hold through phase 1
+    if constexpr (PRENET_EARLY) load_prenet_weights();
+
+    if ((int)blockIdx.x >= d.table[1]) return;
+    const int tile = d.table[TABLE_TILES + blockIdx.x];
 
     __shared__ __attribute__((aligned(16))) float s_big[PROJ_WAVES * PROJ_ROWS * 16];   // partial sums, later hid
     __shared__ __attribute__((aligned(16))) float s_mel[16][PROJ_ROWS];
@@ -614,23 +729,6 @@ __global__ __launch_bounds__(PROJ_THREADS) void k_proj(DevPtrs d, int cur)
         if (d.live[sl] && !d.done[sl]) t = d.t[sl]; else sl = -1;
         s_slot[tid] = sl;
         s_t[tid] = t;
-    }
-
-    // weights of the two prenet layers for this wave's row tiles: requested now, used at the end
-    constexpr int NK3 = PrenetK1<XT>::value / KB;
-    constexpr int NK4 = PRENET / KB;
-    uint4 a3[2][NK3], a4[2][NK4];
-    {
-        const uint4* W1 = reinterpret_cast<const uint4*>(d.Wp1) + lane;
-        const uint4* W2 = reinterpret_cast<const uint4*>(d.Wp2) + lane;
-#pragma unroll
-        for (int m = 0; m < 2; ++m) {
-            const int mt = wave + m * PROJ_WAVES;
-#pragma unroll
-            for (int f = 0; f < NK3; ++f) a3[m][f] = W1[((size_t)mt * NK3 + f) * 64];
-#pragma unroll
-            for (int f = 0; f < NK4; ++f) a4[m][f] = W2[((size_t)mt * NK4 + f) * 64];
-        }
     }
 
     // ---- phase 1: projection of [h_dec; a], K split over the waves
@@ -655,7 +753,11 @@ __global__ __launch_bounds__(PROJ_THREADS) void k_proj(DevPtrs d, int cur)
 #pragma unroll
             for (int m = 0; m < MH; ++m)
 #pragma unroll
-                for (int f = 0; f < NKW; ++f) a[m][f] = W[((size_t)(m0 + m) * NK + wave * NKW + f) * 64];
+                for (int f = 0; f < NKW; ++f) {
+                    // the last row tile holds the stop row and 15 rows of zeros: do not fetch the zeros
+                    a[m][f] = make_uint4(0, 0, 0, 0);
+                    if (m0 + m < PROJ_ROWS / 16 - 1 || jl == 0) a[m][f] = W[((size_t)(m0 + m) * NK + wave * NKW + f) * 64];
+                }
 #pragma unroll
             for (int m = 0; m < MH; ++m) {
                 floatx4 acc = {0.f, 0.f, 0.f, 0.f};
@@ -667,6 +769,8 @@ __global__ __launch_bounds__(PROJ_THREADS) void k_proj(DevPtrs d, int cur)
         }
     }
     __syncthreads();
+
+    if constexpr (!PRENET_EARLY) load_prenet_weights();
 
     // ---- phase 2: reduce, bias, hand the frame out
     for (int idx = tid; idx < 16 * PROJ_ROWS; idx += PROJ_THREADS) {
@@ -853,7 +957,7 @@ __global__ __launch_bounds__(256) void k_x_set(XT* X, int NK, int slot, int off,
 // launch wrappers
 // ---------------------------------------------------------------------------
 template <typename XT, typename MT>
-static hipError_t step_typed(const DevPtrs& d, int n_req, int n_tiles, int lsa_split, int cur, hipStream_t s, hipEvent_t* ev)
+static hipError_t step_typed(const DevPtrs& d, int n_req, int n_tiles, int lsa_split, bool wide, int cur, hipStream_t s, hipEvent_t* ev)
 {
     constexpr int KB = Frag<XT>::KB;
     auto mark = [&](int i) { if (ev) (void)hipEventRecord(ev[i], s); };
@@ -863,18 +967,29 @@ static hipError_t step_typed(const DevPtrs& d, int n_req, int n_tiles, int lsa_s
     XT* xdec_nxt = reinterpret_cast<XT*>(d.xdec[cur ^ 1]);
     mark(0);
     // H_att(t): consumed by this step's decoder LSTM / attention and by the next step's attention LSTM
-    hipLaunchKernelGGL((k_lstm<XT, K_ATT>), dim3(HID / 4), dim3(LSTM_WAVES * 64), 0, s,
-                       d.Wa, d.ba, xatt_cur, d.c_att, xdec_cur, K_DEC / KB, XD_HA, xatt_nxt, K_ATT / KB, XA_H,
-                       d.table, d.live, d.done);
+    if constexpr (sizeof(XT) != 2) wide = false;   // the fp32 fragments of two row tiles do not fit the register file
+    if (wide)
+        hipLaunchKernelGGL((k_lstm2<XT, K_ATT>), dim3(HID / 4), dim3(LSTM_WAVES * 64), 0, s,
+                           d.Wa, d.ba, xatt_cur, d.c_att, xdec_cur, K_DEC / KB, XD_HA, xatt_nxt, K_ATT / KB, XA_H,
+                           d.table, d.live, d.done);
+    else
+        hipLaunchKernelGGL((k_lstm<XT, K_ATT>), dim3(HID / 4), dim3(LSTM_WAVES * 64), 0, s,
+                           d.Wa, d.ba, xatt_cur, d.c_att, xdec_cur, K_DEC / KB, XD_HA, xatt_nxt, K_ATT / KB, XA_H,
+                           d.table, d.live, d.done);
     mark(1);
     if (lsa_split == 4) hipLaunchKernelGGL((k_lsa<XT, MT, 4>), dim3(n_req * 4), dim3(LSA_THREADS), 0, s, d, cur);
     else if (lsa_split == 2) hipLaunchKernelGGL((k_lsa<XT, MT, 2>), dim3(n_req * 2), dim3(LSA_THREADS), 0, s, d, cur);
     else hipLaunchKernelGGL((k_lsa<XT, MT, 1>), dim3(n_req), dim3(LSA_THREADS), 0, s, d, cur);
     mark(2);
     // H_dec(t): consumed by this step's projection and the next step's decoder LSTM (same buffer)
-    hipLaunchKernelGGL((k_lstm<XT, K_DEC>), dim3(HID / 4), dim3(LSTM_WAVES * 64), 0, s,
-                       d.Wd, d.bd, reinterpret_cast<const uint4*>(d.xdec[cur]), d.c_dec, xdec_nxt, K_DEC / KB, XD_HD,
-                       xdec_nxt, K_DEC / KB, XD_HD, d.table, d.live, d.done);
+    if (wide)
+        hipLaunchKernelGGL((k_lstm2<XT, K_DEC>), dim3(HID / 4), dim3(LSTM_WAVES * 64), 0, s,
+                           d.Wd, d.bd, reinterpret_cast<const uint4*>(d.xdec[cur]), d.c_dec, xdec_nxt, K_DEC / KB, XD_HD,
+                           xdec_nxt, K_DEC / KB, XD_HD, d.table, d.live, d.done);
+    else
+        hipLaunchKernelGGL((k_lstm<XT, K_DEC>), dim3(HID / 4), dim3(LSTM_WAVES * 64), 0, s,
+                           d.Wd, d.bd, reinterpret_cast<const uint4*>(d.xdec[cur]), d.c_dec, xdec_nxt, K_DEC / KB, XD_HD,
+                           xdec_nxt, K_DEC / KB, XD_HD, d.table, d.live, d.done);
     mark(3);
     hipLaunchKernelGGL((k_proj<XT>), dim3(n_tiles), dim3(PROJ_THREADS), 0, s, d, cur);
     mark(4);
@@ -884,9 +999,9 @@ static hipError_t step_typed(const DevPtrs& d, int n_req, int n_tiles, int lsa_s
 hipError_t launch_step(const DevPtrs& d, const StepLaunch& cfg, int cur, hipStream_t s, hipEvent_t* ev)
 {
     if (cfg.n_blocks < 1 || cfg.n_tiles < 1) return hipSuccess;
-    if (cfg.wdtype == 0 && cfg.mdtype == 0) return step_typed<float, float>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cur, s, ev);
-    if (cfg.wdtype == 1 && cfg.mdtype == 1) return step_typed<bf16_t, bf16_t>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cur, s, ev);
-    if (cfg.wdtype == 1 && cfg.mdtype == 0) return step_typed<bf16_t, float>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cur, s, ev);
+    if (cfg.wdtype == 0 && cfg.mdtype == 0) return step_typed<float, float>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cfg.wide_lstm != 0, cur, s, ev);
+    if (cfg.wdtype == 1 && cfg.mdtype == 1) return step_typed<bf16_t, bf16_t>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cfg.wide_lstm != 0, cur, s, ev);
+    if (cfg.wdtype == 1 && cfg.mdtype == 0) return step_typed<bf16_t, float>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cfg.wide_lstm != 0, cur, s, ev);
     return hipErrorInvalidValue;
 }
 

@@ -433,6 +433,9 @@ extern "C" int tts_pool_add_request(tts_pool* p, const float* enc_out, int L, in
 // workgroups per request in the attention kernel: more when the pool alone cannot fill the chip
 static int lsa_split_for(int n_blocks) { return n_blocks <= 64 ? 4 : (n_blocks <= 128 ? 2 : 1); }
 
+// LSTM tiling: above two pool tiles a workgroup takes two row tiles and half of the pool tiles
+static int wide_lstm_for(int n_blocks) { return n_blocks > 32 ? 1 : 0; }
+
 // most steps captured into one graph
 static const int MAX_GRAPH_STEPS = 32;
 
@@ -476,6 +479,7 @@ static int launch_steps(tts_pool* p, int n_active, int nsteps)
         sl.n_blocks = n_active;
         sl.n_tiles = p->n_tiles;
         sl.lsa_split = lsa_split_for(n_active);
+        sl.wide_lstm = wide_lstm_for(n_active);
         for (int i = 0; i < nsteps; ++i) HIP_TRY(launch_step(p->d, sl, p->parity ^ (i & 1), p->stream));
         return TTS_OK;
     }
@@ -486,6 +490,7 @@ static int launch_steps(tts_pool* p, int n_active, int nsteps)
         sl.n_blocks = bucket;
         sl.n_tiles = (p->cfg.max_pool + 15) / 16;   // per-tile workgroups beyond the active tiles exit at once
         sl.lsa_split = lsa_split_for(bucket);
+        sl.wide_lstm = wide_lstm_for(bucket);
         hipGraph_t g = nullptr;
         hipGraphExec_t ge = nullptr;
         HIP_TRY(hipStreamBeginCapture(p->stream, hipStreamCaptureModeThreadLocal));
@@ -565,7 +570,7 @@ extern "C" int tts_pool_kernel_times(tts_pool* p, int n, float* out_us, int cap,
         const int n_active = (int)p->book->active().size();
         if (n_active == 0) break;
         if ((rc = push_table(p))) break;
-        StepLaunch sl{p->cfg.weight_dtype, p->cfg.memory_dtype, n_active, p->n_tiles, lsa_split_for(n_active)};
+        StepLaunch sl{p->cfg.weight_dtype, p->cfg.memory_dtype, n_active, p->n_tiles, lsa_split_for(n_active), wide_lstm_for(n_active)};
         hipEvent_t* e = &ev[(size_t)i * per];
         hipError_t he = launch_step(p->d, sl, p->parity, p->stream, e);
         // an empty interval right after the step: the cost of the event itself
