@@ -26,7 +26,9 @@ constexpr int MAX_ENC_LEN = 1024;
 constexpr int MAX_TILES = MAX_POOL / 16;     // a pool tile = 16 consecutive slots = the 16 columns of one MFMA
 // device table: [0] = number of active requests, [1] = number of active tiles,
 // [TABLE_TILES + i] = i-th active tile (header and tile list share the first 128 bytes, so a
-// kernel gets both with one round trip), [TABLE_SLOTS + i] = slot of active request i
+// kernel gets both with one round trip), [TABLE_SLOTS + i] = slot of active request i.
+// Only the LSTM kernels walk the tile list; the attention and projection kernels are laid over
+// slots / tiles directly and look at live[] and done[].
 constexpr int TABLE_TILES = 2;
 constexpr int TABLE_SLOTS = 32;
 constexpr int TABLE_INTS = TABLE_SLOTS + MAX_POOL;

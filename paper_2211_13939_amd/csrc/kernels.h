@@ -8,8 +8,8 @@ namespace tts {
 struct StepLaunch {
     int wdtype;     // weights / activations
     int mdtype;     // encoder memory
-    int n_blocks;   // per-request grids are launched with this many blocks (>= n_active)
-    int n_tiles;    // per-tile grids are launched with this many blocks (>= active tiles)
+    int n_blocks;   // the attention grid covers slots 0 .. n_blocks - 1 (all active slots lie below)
+    int n_tiles;    // the projection grid covers 16-slot tiles 0 .. n_tiles - 1
     int lsa_split;  // workgroups per request in the attention kernel (1, 2 or 4; they split the context columns)
     int wide_lstm;  // non-zero: LSTM workgroups own two row tiles and half of the pool tiles (pools of many tiles)
 };

@@ -47,6 +47,12 @@ __device__ __forceinline__ float sigmoidf_(float x) { return __builtin_amdgcn_rc
 // 1 - 2/(1+e^{2x}) with the hardware reciprocal (1 ulp): absolute error ~1e-7, saturates cleanly at +-1
 __device__ __forceinline__ float tanhf_(float x) { return 1.0f - 2.0f * __builtin_amdgcn_rcpf(1.0f + __expf(2.0f * x)); }
 
+// (1 - tanh(x)) / 2 = 1 / (1 + e^{2x})
+__device__ __forceinline__ float half_one_minus_tanh(float x)
+{
+    return __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(2.8853900817779268f * x));
+}
+
 __device__ __forceinline__ float wave_sum(float x)
 {
 #pragma unroll
@@ -142,15 +148,16 @@ __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm(
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int rt = blockIdx.x;
 
-    // this workgroup's slice of the gate matrix: the only HBM stream, requested first
-    uint4 a[NF];
-#pragma unroll
-    for (int f = 0; f < NF; ++f) a[f] = Wfrag[xfrag(NK, rt, wave + f * NW, lane)];
-
-    // header and the whole tile list at once (one round trip; the activation loads below depend on it)
+    // Loads come back in the order they were issued, and waiting for one waits for everything
+    // issued before it.  So the header and tile list go out FIRST (one round trip; the activation
+    // loads depend on it), then this workgroup's slice of the gate matrix, the only HBM stream:
+    // the activations are then requested while the weights are still on their way.
     int hdr[TABLE_TILES + MAX_TILES];
 #pragma unroll
     for (int i = 0; i < TABLE_TILES + MAX_TILES; ++i) hdr[i] = table[i];
+    uint4 a[NF];
+#pragma unroll
+    for (int f = 0; f < NF; ++f) a[f] = Wfrag[xfrag(NK, rt, wave + f * NW, lane)];
     const int n_tiles = hdr[1];
     // the first four waves also own the cell update of (pool tile in flight = wave, lane)
     const int unit = rt * 4 + (lane >> 4);
@@ -162,17 +169,16 @@ __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm(
 #pragma unroll
     for (int tg = 0; tg < MAX_TILES; tg += 4) {
         if (tg >= n_tiles) break;
-        int slotE = -1;
-        float c_old = 0.f;
-        if (wave < 4 && tg + wave < n_tiles) {
-            const int my_tile = wave == 0 ? hdr[TABLE_TILES + tg] : wave == 1 ? hdr[TABLE_TILES + tg + 1]
-                              : wave == 2 ? hdr[TABLE_TILES + tg + 2] : hdr[TABLE_TILES + tg + 3];
-            const int sl = my_tile * 16 + (lane & 15);
-            if (live[sl] && !done[sl]) {
-                slotE = sl;
-                c_old = c_state[(size_t)sl * HID + unit];
-            }
-        }
+        // The cell update's inputs: three independent, unconditional loads (a load inside a branch
+        // makes the compiler wait for every load in flight, the weights included, where the branch
+        // rejoins).  Waves without a cell update load the same words as wave % 4 and drop them.
+        const int wsel = wave & 3;
+        const int my_tile = wsel == 0 ? hdr[TABLE_TILES + tg] : wsel == 1 ? hdr[TABLE_TILES + tg + 1]
+                          : wsel == 2 ? hdr[TABLE_TILES + tg + 2] : hdr[TABLE_TILES + tg + 3];
+        const int sl = (my_tile & (MAX_TILES - 1)) * 16 + (lane & 15);   // entries past n_tiles are stale: keep them in bounds
+        const int lv = live[sl], dn = done[sl];
+        const float c_old = c_state[(size_t)sl * HID + unit];
+        __builtin_amdgcn_sched_barrier(0);   // issued here, looked at after the products
 #pragma unroll
         for (int t0 = 0; t0 < 4; t0 += TIF) {
             uint4 b[TIF][NF];
@@ -195,6 +201,7 @@ __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm(
             }
         }
         __syncthreads();
+        const int slotE = (wave < 4 && tg + wave < n_tiles && lv && !dn) ? sl : -1;
         if (slotE >= 0) {
             floatx4 g = bias4;
 #pragma unroll
@@ -234,15 +241,17 @@ __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm2(
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int rg = blockIdx.x & 127, cg = blockIdx.x >> 7;
 
+    // table first, weights second (see k_lstm): the wait for the table must not wait for the weights
+    __shared__ int s_hdr[TABLE_TILES + MAX_TILES];
+    __shared__ floatx4 red[NW][2 * TP][64];
+    int hdr_mine = 0;
+    if (threadIdx.x < TABLE_TILES + MAX_TILES) hdr_mine = table[threadIdx.x];
     uint4 a[2][NF];
 #pragma unroll
     for (int r = 0; r < 2; ++r)
 #pragma unroll
         for (int f = 0; f < NF; ++f) a[r][f] = Wfrag[xfrag(NK, 2 * rg + r, wave + f * NW, lane)];
-
-    __shared__ int s_hdr[TABLE_TILES + MAX_TILES];
-    __shared__ floatx4 red[NW][2 * TP][64];
-    if (threadIdx.x < TABLE_TILES + MAX_TILES) s_hdr[threadIdx.x] = table[threadIdx.x];
+    if (threadIdx.x < TABLE_TILES + MAX_TILES) s_hdr[threadIdx.x] = hdr_mine;
     __syncthreads();
     const int n_tiles = s_hdr[1];
     const int half = (n_tiles + 1) >> 1;
@@ -255,15 +264,12 @@ __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm2(
     if (wave < 2 * TP) bias4 = *reinterpret_cast<const floatx4*>(bias + unit * 4);
 
     for (int tp = c0; tp < c1; tp += TP) {
-        int slotE = -1;
-        float c_old = 0.f;
-        if (wave < 2 * TP && tp + et < c1) {
-            const int sl = s_hdr[TABLE_TILES + tp + et] * 16 + (lane & 15);
-            if (live[sl] && !done[sl]) {
-                slotE = sl;
-                c_old = c_state[(size_t)sl * HID + unit];
-            }
-        }
+        // cell update inputs: independent, unconditional loads (see k_lstm)
+        const int tq = min(tp + (et & (TP - 1)), c1 - 1);
+        const int sl = (s_hdr[TABLE_TILES + tq] & (MAX_TILES - 1)) * 16 + (lane & 15);
+        const int lv = live[sl], dn = done[sl];
+        const float c_old = c_state[(size_t)sl * HID + unit];
+        __builtin_amdgcn_sched_barrier(0);
         uint4 b[TP][NF];
 #pragma unroll
         for (int t = 0; t < TP; ++t) {
@@ -286,6 +292,7 @@ __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm2(
             }
         }
         __syncthreads();
+        const int slotE = (wave < 2 * TP && tp + et < c1 && lv && !dn) ? sl : -1;
         if (slotE >= 0) {
             floatx4 g = bias4;
 #pragma unroll
@@ -339,7 +346,8 @@ template <> struct LsaTile<float> {
         for (int i = 0; i < 16; ++i) wA[i >> 1][i & 1] = wf[i * 64 + lane];
     }
     // x0 = index into s_u of this lane's position at tap 0
-    __device__ __forceinline__ void run(const float* u0, const float* u1, int x0, int g, floatx4* pl) const
+    // pl[at] = q[at] + W_loc loc: the query rides in as the accumulator's start value
+    __device__ __forceinline__ void run(const float* u0, const float* u1, int x0, int g, const floatx4* q, floatx4* pl) const
     {
         floatx4 loc0 = {0.f, 0.f, 0.f, 0.f}, loc1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -350,7 +358,7 @@ template <> struct LsaTile<float> {
         }
 #pragma unroll
         for (int at = 0; at < 8; ++at) {
-            floatx4 p = {0.f, 0.f, 0.f, 0.f};
+            floatx4 p = q[at];
             p = __builtin_amdgcn_mfma_f32_16x16x4f32(wA[at][0].x, loc0[0], p, 0, 0, 0);
             p = __builtin_amdgcn_mfma_f32_16x16x4f32(wA[at][0].y, loc0[1], p, 0, 0, 0);
             p = __builtin_amdgcn_mfma_f32_16x16x4f32(wA[at][0].z, loc0[2], p, 0, 0, 0);
@@ -377,7 +385,7 @@ template <> struct LsaTile<bf16_t> {
 #pragma unroll
         for (int i = 0; i < 8; ++i) wA[i] = wf[i * 64 + lane];
     }
-    __device__ __forceinline__ void run(const float* u0, const float* u1, int x0, int g, floatx4* pl) const
+    __device__ __forceinline__ void run(const float* u0, const float* u1, int x0, int g, const floatx4* q, floatx4* pl) const
     {
         floatx4 loc0 = {0.f, 0.f, 0.f, 0.f}, loc1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -393,10 +401,7 @@ template <> struct LsaTile<bf16_t> {
         bl.x = pack_bf16x2(loc0[0], loc0[1]); bl.y = pack_bf16x2(loc0[2], loc0[3]);
         bl.z = pack_bf16x2(loc1[0], loc1[1]); bl.w = pack_bf16x2(loc1[2], loc1[3]);
 #pragma unroll
-        for (int at = 0; at < 8; ++at) {
-            floatx4 z = {0.f, 0.f, 0.f, 0.f};
-            pl[at] = mfma_frag<bf16_t>(wA[at], bl, z);
-        }
+        for (int at = 0; at < 8; ++at) pl[at] = mfma_frag<bf16_t>(wA[at], bl, q[at]);
     }
 };
 
@@ -405,9 +410,17 @@ __global__ __launch_bounds__(LSA_THREADS) void k_lsa(DevPtrs d, int cur)
 {
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int jl = lane & 15, g = lane >> 4;
-    // The query weights do not depend on which request this workgroup serves: their loads go out
-    // before the table is even read.  q = W_q h_att: wave w contracts k in [128 w, 128 w + 128)
-    // for all 128 outputs.
+    // Workgroups are laid over the pool's SLOTS, not over a list of active requests: a list would
+    // cost a dependent round trip (about a microsecond from a cold L2) before anything else could be
+    // requested.  Whether the slot holds a running request, and its encoder length, arrive with the
+    // rest of the prologue's loads.  There is deliberately no early exit in this kernel either: the
+    // compiler moves loads below a branch that may leave the kernel, which would serialise them
+    // behind that branch's condition.  A workgroup with nothing to do computes on whatever its
+    // slot holds (all reads stay inside the slot's arrays) and writes nothing.
+    const int slot = blockIdx.x / S, sp = blockIdx.x % S;
+    const int live_w = d.live[slot], done_w = d.done[slot], L_w = d.L[slot];
+    // The query weights do not depend on which request this workgroup serves.  q = W_q h_att:
+    // wave w contracts k in [128 w, 128 w + 128) for all 128 outputs.
     constexpr int NKQ = HID / Frag<XT>::KB;       // fragments per row tile of W_q
     constexpr int NKW = NKQ / LSA_WAVES;          // fragments per wave
     constexpr int MG = sizeof(XT) == 2 ? 8 : 2;   // row tiles whose fragments are in flight together
@@ -418,12 +431,6 @@ __global__ __launch_bounds__(LSA_THREADS) void k_lsa(DevPtrs d, int cur)
 #pragma unroll
         for (int f = 0; f < NKW; ++f) qa[m][f] = Wq[((size_t)m * NKQ + f) * 64];
 
-    const int pi = blockIdx.x / S, sp = blockIdx.x % S;
-    if (pi >= d.table[0]) return;
-    const int slot = d.table[TABLE_SLOTS + pi];
-    if (d.done[slot]) return;
-    const int L = d.L[slot];
-    const int ntile = (L + 15) >> 4;
 
     __shared__ __attribute__((aligned(16))) float s_q[ATT];
     __shared__ __attribute__((aligned(16))) float s_v[ATT];
@@ -435,21 +442,24 @@ __global__ __launch_bounds__(LSA_THREADS) void k_lsa(DevPtrs d, int cur)
     constexpr int KB = Frag<XT>::KB;
     constexpr int NPM = Vec16<MT>::N;
     constexpr int NV = 32 / NPM;                  // 16-byte pieces of a lane's 32 attention dims of PM[j]
-    const MT* PMs = reinterpret_cast<const MT*>(d.PM) + (size_t)slot * d.max_enc_len * ATT + 32 * g;
-    const float* wl = d.w_last[cur] + (size_t)slot * d.max_enc_len;
-    const float* wa = d.w_acc[cur] + (size_t)slot * d.max_enc_len;
+    const int ML = d.max_enc_len;
+    const MT* PMs = reinterpret_cast<const MT*>(d.PM) + (size_t)slot * ML * ATT + 32 * g;
+    const float* wl = d.w_last[cur] + (size_t)slot * ML;
+    const float* wa = d.w_acc[cur] + (size_t)slot * ML;
 
     // ---- everything the prologue needs is requested before anything is consumed
     constexpr int UPT = (LSA_UPAD + LSA_THREADS - 1) / LSA_THREADS;
     float ul[UPT], ua[UPT];
 #pragma unroll
     for (int i = 0; i < UPT; ++i) {
-        const int j = tid + i * LSA_THREADS - LOC_PAD;
-        const bool in = (j >= 0 && j < L);
-        ul[i] = in ? wl[j] : 0.f;
-        ua[i] = in ? wa[j] : 0.f;
+        // unconditional loads from a clamped index (a load inside a branch makes the compiler wait
+        // for every outstanding load where the branch rejoins)
+        // (the index is clamped to the slot's array, not to the length, which is still on its way)
+        const int jc = min(max(tid + i * LSA_THREADS - LOC_PAD, 0), ML - 1);
+        ul[i] = wl[jc];
+        ua[i] = wa[jc];
     }
-    const float vreg = tid < ATT ? d.v[tid] : 0.f;
+    const float vreg = d.v[tid & (ATT - 1)];
     // every column of the B operand of the query product is this request's h_att (column slot%16 of its tile)
     const uint4* hx = reinterpret_cast<const uint4*>(d.xdec[cur]) +
                       xfrag(K_DEC / KB, slot >> 4, XD_HA / KB + wave * NKW, (slot & 15) + 16 * g);
@@ -461,10 +471,14 @@ __global__ __launch_bounds__(LSA_THREADS) void k_lsa(DevPtrs d, int cur)
     constexpr bool PM_AHEAD = sizeof(XT) == 2;    // fp32 operands leave no registers for a second PM row
     uint4 pmv[NV];
     if constexpr (PM_AHEAD) {
-        const MT* pm = PMs + (size_t)min(wave * 16 + jl, L - 1) * ATT;
+        const MT* pm = PMs + (size_t)min(wave * 16 + jl, ML - 1) * ATT;
 #pragma unroll
         for (int i = 0; i < NV; ++i) pmv[i] = *reinterpret_cast<const uint4*>(pm + i * NPM);
     }
+    __builtin_amdgcn_sched_barrier(0);            // everything above is in flight before anything below waits
+    const bool active = live_w && !done_w;
+    const int L = active ? L_w : 1;
+    const int ntile = (L + 15) >> 4;
 #pragma unroll
     for (int m0 = 0; m0 < 8; m0 += MG) {
         if (m0 > 0) {
@@ -486,11 +500,12 @@ __global__ __launch_bounds__(LSA_THREADS) void k_lsa(DevPtrs d, int cur)
     for (int i = 0; i < UPT; ++i) {
         const int x = tid + i * LSA_THREADS;
         if (x < ntile * 16 + 32) {
-            s_u[0][x] = ul[i];
-            s_u[1][x] = ua[i];
+            const bool in = (x >= LOC_PAD && x < L + LOC_PAD);
+            s_u[0][x] = in ? ul[i] : 0.f;
+            s_u[1][x] = in ? ua[i] : 0.f;
         }
     }
-    if (tid < ATT) s_v[tid] = vreg;
+    if (tid < ATT) s_v[tid] = -2.0f * vreg;       // v . tanh(x) = sum(v) - 2 sum(v / (1 + e^{2x}))
     if constexpr (sizeof(XT) == 4) tile.load(d, lane);
     __syncthreads();
     if (tid < ATT) {
@@ -501,6 +516,14 @@ __global__ __launch_bounds__(LSA_THREADS) void k_lsa(DevPtrs d, int cur)
     }
     __syncthreads();
 
+    // this lane's share of sum(v): its 32 attention dims (s_v holds -2 v)
+    float vsum = 0.f;
+#pragma unroll
+    for (int at = 0; at < 8; ++at) {
+        const float4 vv = *reinterpret_cast<const float4*>(&s_v[32 * g + 4 * at]);
+        vsum += (vv.x + vv.y) + (vv.z + vv.w);
+    }
+    vsum *= -0.5f;
     // ---- energies, one 16-position tile per wave at a time; PM of the next tile is already in flight.
     // With S > 1 every workgroup of the request computes all energies: they are cheap next to the
     // encoder-row stream, and it keeps the softmax exact and local.
@@ -519,13 +542,14 @@ __global__ __launch_bounds__(LSA_THREADS) void k_lsa(DevPtrs d, int cur)
 #pragma unroll
             for (int i = 0; i < NV; ++i) pmc[i] = *reinterpret_cast<const uint4*>(pm + i * NPM);
         }
-        floatx4 pl[8];
-        tile.run(s_u[0], s_u[1], tt * 16 + jl, g, pl);
-        float e = 0.f;
+        // rows 4g..4g+3 of tile `at` are attention dims 32 g + 4 at + i
+        floatx4 pl[8], qv[8];
+#pragma unroll
+        for (int at = 0; at < 8; ++at) qv[at] = *reinterpret_cast<const floatx4*>(&s_q[32 * g + 4 * at]);
+        tile.run(s_u[0], s_u[1], tt * 16 + jl, g, qv, pl);
+        float e = vsum;
 #pragma unroll
         for (int at = 0; at < 8; ++at) {
-            // rows 4g..4g+3 of tile `at` are attention dims 32 g + 4 at + i
-            const float4 qv = *reinterpret_cast<const float4*>(&s_q[32 * g + 4 * at]);
             const float4 vv = *reinterpret_cast<const float4*>(&s_v[32 * g + 4 * at]);
             float pv[4];
             if constexpr (sizeof(MT) == 2) {
@@ -535,10 +559,10 @@ __global__ __launch_bounds__(LSA_THREADS) void k_lsa(DevPtrs d, int cur)
             } else {
                 Vec16<float>::unpack(pmc[at], pv);
             }
-            e += vv.x * tanhf_(qv.x + pl[at][0] + pv[0]);
-            e += vv.y * tanhf_(qv.y + pl[at][1] + pv[1]);
-            e += vv.z * tanhf_(qv.z + pl[at][2] + pv[2]);
-            e += vv.w * tanhf_(qv.w + pl[at][3] + pv[3]);
+            e = fmaf(vv.x, half_one_minus_tanh(pl[at][0] + pv[0]), e);
+            e = fmaf(vv.y, half_one_minus_tanh(pl[at][1] + pv[1]), e);
+            e = fmaf(vv.z, half_one_minus_tanh(pl[at][2] + pv[2]), e);
+            e = fmaf(vv.w, half_one_minus_tanh(pl[at][3] + pv[3]), e);
         }
         e += __shfl_xor(e, 16, 64);
         e += __shfl_xor(e, 32, 64);
@@ -646,16 +670,20 @@ __global__ __launch_bounds__(LSA_THREADS) void k_lsa(DevPtrs d, int cur)
         }
         const XT a = from_float<XT>(c * inv);
         const int k = sp * FS + f;
-        xa[xoff<XT>(K_ATT / KB, slot, XA_A + k)] = a;
-        xd[xoff<XT>(K_DEC / KB, slot, XD_A + k)] = a;
+        if (active) {
+            xa[xoff<XT>(K_ATT / KB, slot, XA_A + k)] = a;
+            xd[xoff<XT>(K_DEC / KB, slot, XD_A + k)] = a;
+        }
     }
     // the new weights: every workgroup of the request holds all of them, each writes its share
     float* wl_out = d.w_last[cur ^ 1] + (size_t)slot * d.max_enc_len;
     float* wa_out = d.w_acc[cur ^ 1] + (size_t)slot * d.max_enc_len;
     for (int x = sp + S * tid; x < L; x += S * LSA_THREADS) {
         const float w = s_e[x] * inv;
-        wl_out[x] = w;
-        wa_out[x] = s_u[1][x + LOC_PAD] + w;
+        if (active) {
+            wl_out[x] = w;
+            wa_out[x] = s_u[1][x + LOC_PAD] + w;
+        }
     }
 }
 
@@ -694,49 +722,49 @@ __global__ __launch_bounds__(PROJ_THREADS) void k_proj(DevPtrs d, int cur)
     constexpr int KB = Frag<XT>::KB;
     constexpr int EPL = Frag<XT>::EPL;
     constexpr int NKD = K_DEC / KB;
-
-    // weights of the two prenet layers for this wave's row tiles: requested first (they do not
-    // depend on the tile), used at the end
-    constexpr int NK3 = PrenetK1<XT>::value / KB;
-    constexpr int NK4 = PRENET / KB;
-    uint4 a3[2][NK3], a4[2][NK4];
-    auto load_prenet_weights = [&]() {
-        const uint4* W1 = reinterpret_cast<const uint4*>(d.Wp1) + lane;
-        const uint4* W2 = reinterpret_cast<const uint4*>(d.Wp2) + lane;
+    constexpr int NK = K_PROJ / KB;
+    constexpr int NKW = NK / PROJ_WAVES;
+    static_assert(NK % PROJ_WAVES == 0, "K must split evenly over the waves");
+    constexpr int NM = PROJ_ROWS / 16;
+    // The projection weights do not depend on which tile this workgroup serves, and one CU pulling
+    // them is what bounds the kernel: with bf16 weights the wave's whole share (all row tiles of its
+    // K range) is requested before the table is even read.  fp32 fragments are twice the registers:
+    // there the row tiles go MH at a time.
+    constexpr bool W_EARLY = sizeof(XT) == 2;
+    constexpr int MH = W_EARLY ? NM : 1;          // row tiles whose fragments are in flight together
+    const uint4* W = reinterpret_cast<const uint4*>(d.Wmel) + lane;
+    uint4 a[MH][NKW];
+    auto load_proj_weights = [&](int m0) {
 #pragma unroll
-        for (int m = 0; m < 2; ++m) {
-            const int mt = wave + m * PROJ_WAVES;
+        for (int m = 0; m < MH; ++m)
 #pragma unroll
-            for (int f = 0; f < NK3; ++f) a3[m][f] = W1[((size_t)mt * NK3 + f) * 64];
-#pragma unroll
-            for (int f = 0; f < NK4; ++f) a4[m][f] = W2[((size_t)mt * NK4 + f) * 64];
-        }
+            for (int f = 0; f < NKW; ++f) {
+                // the last row tile holds the stop row and 15 rows of zeros: do not fetch the zeros
+                a[m][f] = make_uint4(0, 0, 0, 0);
+                if (m0 + m < NM - 1 || jl == 0) a[m][f] = W[((size_t)(m0 + m) * NK + wave * NKW + f) * 64];
+            }
     };
-    constexpr bool PRENET_EARLY = sizeof(XT) == 2;   // the fp32 fragments are too many registers to hold through phase 1
-    if constexpr (PRENET_EARLY) load_prenet_weights();
-
-    if ((int)blockIdx.x >= d.table[1]) return;
-    const int tile = d.table[TABLE_TILES + blockIdx.x];
+    // (loads return in issue order: the two table words go out before the weights, so that the wait
+    // for them does not wait for the weights)
+    // A workgroup serves the 16 slots blockIdx.x * 16 ..: no list of active tiles to wait for, so the
+    // activations and the slots' bookkeeping words are requested together with the weights.  A tile
+    // without a running request is computed and dropped (there is no early exit: the compiler would
+    // move the loads below it).
+    const int tile = blockIdx.x;
+    if constexpr (W_EARLY) load_proj_weights(0);
 
     __shared__ __attribute__((aligned(16))) float s_big[PROJ_WAVES * PROJ_ROWS * 16];   // partial sums, later hid
     __shared__ __attribute__((aligned(16))) float s_mel[16][PROJ_ROWS];
-    __shared__ int s_slot[16], s_t[16];
+    __shared__ int s_slot[16], s_t[16], s_cap[16];
     float (*s_part)[PROJ_ROWS][16] = reinterpret_cast<float (*)[PROJ_ROWS][16]>(s_big);
     float (*s_hid)[PRENET] = reinterpret_cast<float (*)[PRENET]>(s_big);
 
-    if (tid < 16) {
-        int sl = tile * 16 + tid, t = 0;
-        if (d.live[sl] && !d.done[sl]) t = d.t[sl]; else sl = -1;
-        s_slot[tid] = sl;
-        s_t[tid] = t;
-    }
+    // slot bookkeeping of the 16 columns: four independent loads, consumed after phase 1
+    int my_sl = tile * 16 + (tid & 15);
+    const int my_live = d.live[my_sl], my_done = d.done[my_sl], my_t = d.t[my_sl], my_cap = d.n_steps[my_sl];
 
     // ---- phase 1: projection of [h_dec; a], K split over the waves
     {
-        constexpr int NK = K_PROJ / KB;
-        constexpr int NKW = NK / PROJ_WAVES;
-        static_assert(NK % PROJ_WAVES == 0, "K must split evenly over the waves");
-        constexpr int MH = sizeof(XT) == 2 ? 3 : 1;   // row tiles whose fragments are in flight together
         const uint4* xnew = reinterpret_cast<const uint4*>(d.xdec[cur ^ 1]);   // h_dec of this step
         const uint4* xcur = reinterpret_cast<const uint4*>(d.xdec[cur]);       // a of this step
         uint4 b[NKW];
@@ -746,18 +774,12 @@ __global__ __launch_bounds__(PROJ_THREADS) void k_proj(DevPtrs d, int cur)
             b[f] = ks < HID / KB ? xnew[xfrag(NKD, tile, XD_HD / KB + ks, lane)]
                                  : xcur[xfrag(NKD, tile, XD_A / KB + ks - HID / KB, lane)];
         }
-        const uint4* W = reinterpret_cast<const uint4*>(d.Wmel) + lane;
+        // keep these loads (and the bookkeeping loads above) here: left alone, the scheduler issues
+        // them one at a time between the MFMAs, each a full round trip
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int m0 = 0; m0 < PROJ_ROWS / 16; m0 += MH) {
-            uint4 a[MH][NKW];
-#pragma unroll
-            for (int m = 0; m < MH; ++m)
-#pragma unroll
-                for (int f = 0; f < NKW; ++f) {
-                    // the last row tile holds the stop row and 15 rows of zeros: do not fetch the zeros
-                    a[m][f] = make_uint4(0, 0, 0, 0);
-                    if (m0 + m < PROJ_ROWS / 16 - 1 || jl == 0) a[m][f] = W[((size_t)(m0 + m) * NK + wave * NKW + f) * 64];
-                }
+        for (int m0 = 0; m0 < NM; m0 += MH) {
+            if constexpr (!W_EARLY) load_proj_weights(m0);
 #pragma unroll
             for (int m = 0; m < MH; ++m) {
                 floatx4 acc = {0.f, 0.f, 0.f, 0.f};
@@ -768,9 +790,32 @@ __global__ __launch_bounds__(PROJ_THREADS) void k_proj(DevPtrs d, int cur)
             }
         }
     }
-    __syncthreads();
 
-    if constexpr (!PRENET_EARLY) load_prenet_weights();
+    if (tid < 16) {
+        const bool on = my_live && !my_done;
+        s_slot[tid] = on ? my_sl : -1;
+        s_t[tid] = on ? my_t : 0;
+        s_cap[tid] = on ? my_cap : 0;
+    }
+
+    // weights of the two prenet layers for this wave's row tiles (w and w + 8): requested now that the
+    // projection fragments have left the registers, used after the two reduction phases below
+    constexpr int NK3 = PrenetK1<XT>::value / KB;
+    constexpr int NK4 = PRENET / KB;
+    uint4 a3[2][NK3], a4[2][NK4];
+    {
+        const uint4* W1 = reinterpret_cast<const uint4*>(d.Wp1) + lane;
+        const uint4* W2 = reinterpret_cast<const uint4*>(d.Wp2) + lane;
+#pragma unroll
+        for (int m = 0; m < 2; ++m) {
+            const int mt = wave + m * PROJ_WAVES;
+#pragma unroll
+            for (int f = 0; f < NK3; ++f) a3[m][f] = W1[((size_t)mt * NK3 + f) * 64];
+#pragma unroll
+            for (int f = 0; f < NK4; ++f) a4[m][f] = W2[((size_t)mt * NK4 + f) * 64];
+        }
+    }
+    __syncthreads();
 
     // ---- phase 2: reduce, bias, hand the frame out
     for (int idx = tid; idx < 16 * PROJ_ROWS; idx += PROJ_THREADS) {
@@ -832,10 +877,11 @@ __global__ __launch_bounds__(PROJ_THREADS) void k_proj(DevPtrs d, int cur)
 #pragma unroll
             for (int f = 0; f < NK4; ++f) acc = mfma_frag<XT>(a4[m][f], b[f], acc);
             if (sl >= 0) {
-                // four consecutive k inside one 16-byte piece
+                // four consecutive k inside one 16-byte piece: one store
                 XT* dst = xa + xoff<XT>(K_ATT / KB, sl, XA_P + 16 * mt + 4 * g);
-#pragma unroll
-                for (int i = 0; i < 4; ++i) dst[i] = from_float<XT>(fmaxf(acc[i], 0.f));
+                const float p0 = fmaxf(acc[0], 0.f), p1 = fmaxf(acc[1], 0.f), p2 = fmaxf(acc[2], 0.f), p3 = fmaxf(acc[3], 0.f);
+                if constexpr (sizeof(XT) == 2) *reinterpret_cast<uint2*>(dst) = make_uint2(pack_bf16x2(p0, p1), pack_bf16x2(p2, p3));
+                else *reinterpret_cast<float4*>(dst) = make_float4(p0, p1, p2, p3);
             }
         }
     }
@@ -844,7 +890,7 @@ __global__ __launch_bounds__(PROJ_THREADS) void k_proj(DevPtrs d, int cur)
         const int sl = s_slot[tid];
         const int tn = s_t[tid] + 1;
         d.t[sl] = tn;
-        bool fin = tn >= d.n_steps[sl];
+        bool fin = tn >= s_cap[tid];
         if (d.stop_threshold >= 0.f && sigmoidf_(s_mel[tid][N_MEL]) > d.stop_threshold) fin = true;
         if (fin) d.done[sl] = 1;
     }
@@ -967,12 +1013,14 @@ static hipError_t step_typed(const DevPtrs& d, int n_req, int n_tiles, int lsa_s
     XT* xdec_nxt = reinterpret_cast<XT*>(d.xdec[cur ^ 1]);
     mark(0);
     // H_att(t): consumed by this step's decoder LSTM / attention and by the next step's attention LSTM
-    if constexpr (sizeof(XT) != 2) wide = false;   // the fp32 fragments of two row tiles do not fit the register file
-    if (wide)
-        hipLaunchKernelGGL((k_lstm2<XT, K_ATT>), dim3(HID / 4), dim3(LSTM_WAVES * 64), 0, s,
-                           d.Wa, d.ba, xatt_cur, d.c_att, xdec_cur, K_DEC / KB, XD_HA, xatt_nxt, K_ATT / KB, XA_H,
-                           d.table, d.live, d.done);
-    else
+    constexpr bool HAS_WIDE = sizeof(XT) == 2;     // the fp32 fragments of two row tiles do not fit the register file
+    if (!HAS_WIDE) wide = false;
+    if (wide) {
+        if constexpr (HAS_WIDE)
+            hipLaunchKernelGGL((k_lstm2<XT, K_ATT>), dim3(HID / 4), dim3(LSTM_WAVES * 64), 0, s,
+                               d.Wa, d.ba, xatt_cur, d.c_att, xdec_cur, K_DEC / KB, XD_HA, xatt_nxt, K_ATT / KB, XA_H,
+                               d.table, d.live, d.done);
+    } else
         hipLaunchKernelGGL((k_lstm<XT, K_ATT>), dim3(HID / 4), dim3(LSTM_WAVES * 64), 0, s,
                            d.Wa, d.ba, xatt_cur, d.c_att, xdec_cur, K_DEC / KB, XD_HA, xatt_nxt, K_ATT / KB, XA_H,
                            d.table, d.live, d.done);
@@ -982,11 +1030,12 @@ static hipError_t step_typed(const DevPtrs& d, int n_req, int n_tiles, int lsa_s
     else hipLaunchKernelGGL((k_lsa<XT, MT, 1>), dim3(n_req), dim3(LSA_THREADS), 0, s, d, cur);
     mark(2);
     // H_dec(t): consumed by this step's projection and the next step's decoder LSTM (same buffer)
-    if (wide)
-        hipLaunchKernelGGL((k_lstm2<XT, K_DEC>), dim3(HID / 4), dim3(LSTM_WAVES * 64), 0, s,
-                           d.Wd, d.bd, reinterpret_cast<const uint4*>(d.xdec[cur]), d.c_dec, xdec_nxt, K_DEC / KB, XD_HD,
-                           xdec_nxt, K_DEC / KB, XD_HD, d.table, d.live, d.done);
-    else
+    if (wide) {
+        if constexpr (HAS_WIDE)
+            hipLaunchKernelGGL((k_lstm2<XT, K_DEC>), dim3(HID / 4), dim3(LSTM_WAVES * 64), 0, s,
+                               d.Wd, d.bd, reinterpret_cast<const uint4*>(d.xdec[cur]), d.c_dec, xdec_nxt, K_DEC / KB, XD_HD,
+                               xdec_nxt, K_DEC / KB, XD_HD, d.table, d.live, d.done);
+    } else
         hipLaunchKernelGGL((k_lstm<XT, K_DEC>), dim3(HID / 4), dim3(LSTM_WAVES * 64), 0, s,
                            d.Wd, d.bd, reinterpret_cast<const uint4*>(d.xdec[cur]), d.c_dec, xdec_nxt, K_DEC / KB, XD_HD,
                            xdec_nxt, K_DEC / KB, XD_HD, d.table, d.live, d.done);

@@ -248,6 +248,7 @@ struct tts_pool {
     std::unique_ptr<PoolBook> book;
     int parity = 0;               // activation buffer half the next step reads
     int n_tiles = 0;              // 16-slot tiles with at least one active request (as last uploaded)
+    int slot_span = 0;            // highest active slot + 1 (as last uploaded): what the per-slot grids must cover
     bool stop_enabled = false;
     bool timing = false;
     hipEvent_t ev0 = nullptr, ev1 = nullptr;
@@ -454,16 +455,34 @@ static int push_table(tts_pool* p)
     const std::vector<int>& act = p->book->active();
     a.n_active = (int)act.size();
     bool used[MAX_TILES] = {false};
+    int span = 0;
     for (size_t i = 0; i < act.size(); ++i) {
         a.slot[i] = (uint16_t)act[i];
         used[act[i] >> 4] = true;
+        if (act[i] + 1 > span) span = act[i] + 1;
     }
+    p->slot_span = span;
     for (int t = 0; t < MAX_TILES; ++t)
         if (used[t]) a.tile[a.n_tiles++] = (uint8_t)t;
     p->n_tiles = a.n_tiles;
     HIP_TRY(launch_set_table(p->d, a, p->stream));
     p->book->clear_dirty();
     return TTS_OK;
+}
+
+// Launch shape for a pool whose active slots lie below `span`: the attention kernel gets `lsa_split`
+// workgroups per slot, the projection kernel one per 16-slot tile; slots and tiles without a running
+// request are computed and dropped, so the grids may cover more than is active but never more than
+// the arena holds.
+static void shape_for(const tts_pool* p, int span, StepLaunch* sl)
+{
+    const int padded = (p->cfg.max_pool + 15) / 16 * 16;
+    if (span > padded) span = padded;
+    if (span < 1) span = 1;
+    sl->n_blocks = span;
+    sl->n_tiles = (span + 15) / 16;
+    sl->lsa_split = lsa_split_for(span);
+    sl->wide_lstm = wide_lstm_for(span);
 }
 
 // Queue `nsteps` consecutive steps for the current membership.  With graphs the
@@ -475,22 +494,17 @@ static int launch_steps(tts_pool* p, int n_active, int nsteps)
     StepLaunch sl;
     sl.wdtype = p->cfg.weight_dtype;
     sl.mdtype = p->cfg.memory_dtype;
+    (void)n_active;
     if (!p->cfg.use_graph) {
-        sl.n_blocks = n_active;
-        sl.n_tiles = p->n_tiles;
-        sl.lsa_split = lsa_split_for(n_active);
-        sl.wide_lstm = wide_lstm_for(n_active);
+        shape_for(p, p->slot_span, &sl);
         for (int i = 0; i < nsteps; ++i) HIP_TRY(launch_step(p->d, sl, p->parity ^ (i & 1), p->stream));
         return TTS_OK;
     }
-    const int bucket = bucket_for(n_active);
+    const int bucket = bucket_for(p->slot_span);
     const int key = (nsteps * 1024 + bucket) * 2 + p->parity;
     auto it = p->graphs.find(key);
     if (it == p->graphs.end()) {
-        sl.n_blocks = bucket;
-        sl.n_tiles = (p->cfg.max_pool + 15) / 16;   // per-tile workgroups beyond the active tiles exit at once
-        sl.lsa_split = lsa_split_for(bucket);
-        sl.wide_lstm = wide_lstm_for(bucket);
+        shape_for(p, bucket, &sl);
         hipGraph_t g = nullptr;
         hipGraphExec_t ge = nullptr;
         HIP_TRY(hipStreamBeginCapture(p->stream, hipStreamCaptureModeThreadLocal));
@@ -570,7 +584,10 @@ extern "C" int tts_pool_kernel_times(tts_pool* p, int n, float* out_us, int cap,
         const int n_active = (int)p->book->active().size();
         if (n_active == 0) break;
         if ((rc = push_table(p))) break;
-        StepLaunch sl{p->cfg.weight_dtype, p->cfg.memory_dtype, n_active, p->n_tiles, lsa_split_for(n_active), wide_lstm_for(n_active)};
+        StepLaunch sl;
+        sl.wdtype = p->cfg.weight_dtype;
+        sl.mdtype = p->cfg.memory_dtype;
+        shape_for(p, p->slot_span, &sl);
         hipEvent_t* e = &ev[(size_t)i * per];
         hipError_t he = launch_step(p->d, sl, p->parity, p->stream, e);
         // an empty interval right after the step: the cost of the event itself
