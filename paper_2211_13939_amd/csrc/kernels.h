@@ -12,6 +12,7 @@ struct StepLaunch {
     int n_tiles;    // the projection grid covers 16-slot tiles 0 .. n_tiles - 1
     int lsa_split;  // workgroups per request in the attention kernel (1, 2 or 4; they split the context columns)
     int wide_lstm;  // non-zero: LSTM workgroups own two row tiles and half of the pool tiles (pools of many tiles)
+    int q_partials; // non-zero: the attention LSTM hands the query over as partial products (pools of <= 32 slots)
 };
 
 // One decoder step (paper Eq. 2) for every request listed in d.table.

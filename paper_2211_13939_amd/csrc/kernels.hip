@@ -129,15 +129,28 @@ template <> __device__ __forceinline__ floatx4 mfma_frag<float>(const uint4& a, 
 //   gates = W [x] + b;  c <- sig(f) c + sig(i) tanh(g);  h <- sig(o) tanh(c)
 // The accumulator of lane l is (column l%16, gates i,f,g,o of unit l/16): the
 // cell update needs no data movement beyond the cross-wave reduction.
+//
+// With QP (the attention LSTM) the epilogue also starts the attention query
+// q = W_q h of the same step: the wave that has just produced four units of h
+// for 16 slots multiplies them by the matching four columns of W_q (one
+// 16x16x4 fp32 MFMA per 16 attention dims) and stores that rank-4 partial.
+// The attention kernel then adds up a request's 256 partials (128 KB) instead
+// of pulling all of W_q (256 KB in bf16, 512 KB in fp32) through its CU, which
+// bounds its prologue.  The partials cost this kernel 128 KB of stores per
+// request, so the scheme is used by pools of at most 32 slots only (where a
+// step is latency-bound); larger pools compute q in the attention kernel.
+// qpart[slot][row tile][a].
 // ---------------------------------------------------------------------------
 constexpr int LSTM_WAVES = 8;
+constexpr int QP_STRIDE = HID / 4;   // partial rows per slot in qpart
 
-template <typename XT, int K>
+template <typename XT, int K, bool QP>
 __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm(
     const uint4* __restrict__ Wfrag, const float* __restrict__ bias, const uint4* __restrict__ X,
     float* __restrict__ c_state, XT* __restrict__ hout0, int nk0, int off0,
     XT* __restrict__ hout1, int nk1, int off1,
-    const int* __restrict__ table, const int* __restrict__ live, const int* __restrict__ done)
+    const int* __restrict__ table, const int* __restrict__ live, const int* __restrict__ done,
+    const float* __restrict__ wq_epi, float* __restrict__ qpart)
 {
     constexpr int NW = LSTM_WAVES;
     constexpr int NK = K / Frag<XT>::KB;      // fragments per row tile / per pool tile
@@ -163,6 +176,12 @@ __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm(
     const int unit = rt * 4 + (lane >> 4);
     floatx4 bias4 = {0.f, 0.f, 0.f, 0.f};
     if (wave < 4) bias4 = *reinterpret_cast<const floatx4*>(bias + unit * 4);
+    // W_q[16 at + lane%16][4 rt + lane/16]: the A operands of the query partial
+    float wq[QP ? 8 : 1];
+    if constexpr (QP) {
+#pragma unroll
+        for (int at = 0; at < 8; ++at) wq[at] = wq_epi[((size_t)rt * 8 + at) * 64 + lane];
+    }
 
     __shared__ floatx4 red[NW][4][64];
 
@@ -202,6 +221,7 @@ __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm(
         }
         __syncthreads();
         const int slotE = (wave < 4 && tg + wave < n_tiles && lv && !dn) ? sl : -1;
+        float hq = 0.f;
         if (slotE >= 0) {
             floatx4 g = bias4;
 #pragma unroll
@@ -213,6 +233,18 @@ __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm(
             const XT h = from_float<XT>(go * tanhf_(c));
             hout0[xoff<XT>(nk0, slotE, off0 + unit)] = h;
             hout1[xoff<XT>(nk1, slotE, off1 + unit)] = h;
+            hq = to_float(h);
+        }
+        if constexpr (QP) {
+            if (wave < 4 && tg + wave < n_tiles) {   // whole waves: the MFMA runs outside the per-lane branch
+#pragma unroll
+                for (int at = 0; at < 8; ++at) {
+                    const floatx4 z = {0.f, 0.f, 0.f, 0.f};
+                    const floatx4 part = __builtin_amdgcn_mfma_f32_16x16x4f32(wq[at], hq, z, 0, 0, 0);
+                    if (slotE >= 0)
+                        *reinterpret_cast<floatx4*>(qpart + ((size_t)slotE * QP_STRIDE + rt) * ATT + 16 * at + 4 * (lane >> 4)) = part;
+                }
+            }
         }
         __syncthreads();
     }
@@ -315,8 +347,9 @@ __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm2(
 //   loc[j][f] = sum_c sum_k Kc[f][c][k] u_c[j+k-15]         (u = W_last, W_acc; zero outside [0,L))
 //   e_j = v . tanh(q + W_loc loc[j] + PM[j])
 //   w = softmax_{j<L}(e);  A = sum_j w_j F[j];  W_last <- w;  W_acc <- W_acc + w
-// All three contractions run on MFMA with 16 positions (or, for q, 16 copies
-// of h_att) as the columns:
+// The contractions run on MFMA with 16 positions (or, for q, 16 copies of h_att)
+// as the columns (pools of at most 32 slots get q as partial sums from the
+// attention LSTM's epilogue instead):
 //   q      (128 x 16, K split over the waves) = W_q * h_att
 //   loc^T  (32 x 16)          = Kc (32 x 64 taps) * U^T (64 taps x 16 positions)
 //   pl^T   (128 x 16)         = W_loc (128 x 32)  * loc^T
@@ -376,14 +409,21 @@ template <> struct LsaTile<float> {
 template <> struct LsaTile<bf16_t> {
     uint4 kA[2][2];    // [mt][c]: filter 16 mt + jl, taps 8 g .. 8 g + 7 of channel c
     uint4 wA[8];       // [at]: W_loc row 32 (jl/4) + 4 at + jl%4, filters {4g..4g+3, 16+4g..16+4g+3}
-    __device__ __forceinline__ void load(const DevPtrs& d, int lane)
+    static constexpr int LDS_VECS = 12 * 64;   // the operands of all 64 lanes, as 16-byte pieces
+    // the operands are the same for every wave: the workgroup fetches them once into LDS ...
+    __device__ static __forceinline__ uint4 fetch(const DevPtrs& d, int i)
     {
         const uint4* kf = reinterpret_cast<const uint4*>(d.lsa_kfrag);
         const uint4* wf = reinterpret_cast<const uint4*>(d.lsa_wfrag);
+        return i < 4 * 64 ? kf[i] : wf[i - 4 * 64];
+    }
+    // ... and every wave takes its lanes' share from there
+    __device__ __forceinline__ void load(const uint4* lds, int lane)
+    {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) kA[i >> 1][i & 1] = kf[i * 64 + lane];
+        for (int i = 0; i < 4; ++i) kA[i >> 1][i & 1] = lds[i * 64 + lane];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) wA[i] = wf[i * 64 + lane];
+        for (int i = 0; i < 8; ++i) wA[i] = lds[(4 + i) * 64 + lane];
     }
     __device__ __forceinline__ void run(const float* u0, const float* u1, int x0, int g, const floatx4* q, floatx4* pl) const
     {
@@ -405,7 +445,7 @@ template <> struct LsaTile<bf16_t> {
     }
 };
 
-template <typename XT, typename MT, int S>
+template <typename XT, typename MT, int S, bool QP>
 __global__ __launch_bounds__(LSA_THREADS) void k_lsa(DevPtrs d, int cur)
 {
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
@@ -419,18 +459,29 @@ __global__ __launch_bounds__(LSA_THREADS) void k_lsa(DevPtrs d, int cur)
     // slot holds (all reads stay inside the slot's arrays) and writes nothing.
     const int slot = blockIdx.x / S, sp = blockIdx.x % S;
     const int live_w = d.live[slot], done_w = d.done[slot], L_w = d.L[slot];
-    // The query weights do not depend on which request this workgroup serves.  q = W_q h_att:
-    // wave w contracts k in [128 w, 128 w + 128) for all 128 outputs.
+    // q = W_q h_att, one of two ways.
+    // QP: it arrives as 256 rank-4 partial products written by this step's attention LSTM.  Thread
+    // (a = tid % 128, quarter = tid / 128) adds up its quarter's 32 pair sums P[2i] + P[2i+1] in
+    // increasing i; then q[a] = (s0 + s1) + (s2 + s3).
+    // Otherwise: on MFMA here, wave w contracting k in [128 w, 128 w + 128) for all 128 outputs
+    // with 16 copies of h_att as the columns; the weights do not depend on the request.
+    constexpr int QN = QP ? 64 : 1;
     constexpr int NKQ = HID / Frag<XT>::KB;       // fragments per row tile of W_q
     constexpr int NKW = NKQ / LSA_WAVES;          // fragments per wave
-    constexpr int MG = sizeof(XT) == 2 ? 8 : 2;   // row tiles whose fragments are in flight together
+    constexpr int MG = QP ? 1 : (sizeof(XT) == 2 ? 8 : 2);   // row tiles whose fragments are in flight together
+    float qv[QN];
+    uint4 qa[MG][QP ? 1 : NKW];
     const uint4* Wq = reinterpret_cast<const uint4*>(d.Wq) + (size_t)(wave * NKW) * 64 + lane;
-    uint4 qa[MG][NKW];
+    if constexpr (QP) {
+        const float* qp = d.qpart + ((size_t)slot * QP_STRIDE + (tid >> 7) * QN) * ATT + (tid & (ATT - 1));
 #pragma unroll
-    for (int m = 0; m < MG; ++m)
+        for (int i = 0; i < QN; ++i) qv[i] = qp[(size_t)i * ATT];
+    } else {
 #pragma unroll
-        for (int f = 0; f < NKW; ++f) qa[m][f] = Wq[((size_t)m * NKQ + f) * 64];
-
+        for (int m = 0; m < MG; ++m)
+#pragma unroll
+            for (int f = 0; f < NKW; ++f) qa[m][f] = Wq[((size_t)m * NKQ + f) * 64];
+    }
 
     __shared__ __attribute__((aligned(16))) float s_q[ATT];
     __shared__ __attribute__((aligned(16))) float s_v[ATT];
@@ -461,13 +512,24 @@ __global__ __launch_bounds__(LSA_THREADS) void k_lsa(DevPtrs d, int cur)
     }
     const float vreg = d.v[tid & (ATT - 1)];
     // every column of the B operand of the query product is this request's h_att (column slot%16 of its tile)
-    const uint4* hx = reinterpret_cast<const uint4*>(d.xdec[cur]) +
-                      xfrag(K_DEC / KB, slot >> 4, XD_HA / KB + wave * NKW, (slot & 15) + 16 * g);
-    uint4 hb[NKW];
+    uint4 hb[QP ? 1 : NKW];
+    if constexpr (!QP) {
+        const uint4* hx = reinterpret_cast<const uint4*>(d.xdec[cur]) +
+                          xfrag(K_DEC / KB, slot >> 4, XD_HA / KB + wave * NKW, (slot & 15) + 16 * g);
 #pragma unroll
-    for (int f = 0; f < NKW; ++f) hb[f] = hx[(size_t)f * 64];
+        for (int f = 0; f < NKW; ++f) hb[f] = hx[(size_t)f * 64];
+    }
     LsaTile<XT> tile;
-    if constexpr (sizeof(XT) == 2) tile.load(d, lane);   // the fp32 operands are too many registers to hold this early
+    // bf16: the constant MFMA operands go through LDS once per workgroup (straight from global every
+    // wave would pull its own 12 KB copy through the CU's one load path)
+    constexpr bool TILE_LDS = sizeof(XT) == 2;
+    constexpr int TILE_VECS = TILE_LDS ? 12 * 64 : 1;
+    __shared__ uint4 s_tile[TILE_VECS];
+    uint4 tv0 = make_uint4(0, 0, 0, 0), tv1 = make_uint4(0, 0, 0, 0);
+    if constexpr (TILE_LDS) {
+        tv0 = LsaTile<XT>::fetch(d, tid);
+        tv1 = LsaTile<XT>::fetch(d, LSA_THREADS + (tid & 255));   // 768 pieces: the upper half of the threads repeats the lower's
+    }
     constexpr bool PM_AHEAD = sizeof(XT) == 2;    // fp32 operands leave no registers for a second PM row
     uint4 pmv[NV];
     if constexpr (PM_AHEAD) {
@@ -479,21 +541,28 @@ __global__ __launch_bounds__(LSA_THREADS) void k_lsa(DevPtrs d, int cur)
     const bool active = live_w && !done_w;
     const int L = active ? L_w : 1;
     const int ntile = (L + 15) >> 4;
+    if constexpr (QP) {
+        float sq = qv[0] + qv[1];
 #pragma unroll
-    for (int m0 = 0; m0 < 8; m0 += MG) {
-        if (m0 > 0) {
+        for (int i = 2; i < QN; i += 2) sq += qv[i] + qv[i + 1];
+        s_ctx[tid >> 7][tid & (ATT - 1)] = sq;    // s_ctx doubles as the partial-q buffer
+    } else {
 #pragma unroll
-            for (int m = 0; m < MG; ++m)
+        for (int m0 = 0; m0 < 8; m0 += MG) {
+            if (m0 > 0) {
 #pragma unroll
-                for (int f = 0; f < NKW; ++f) qa[m][f] = Wq[((size_t)(m0 + m) * NKQ + f) * 64];
-        }
+                for (int m = 0; m < MG; ++m)
 #pragma unroll
-        for (int m = 0; m < MG; ++m) {
-            floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+                    for (int f = 0; f < NKW; ++f) qa[m][f] = Wq[((size_t)(m0 + m) * NKQ + f) * 64];
+            }
 #pragma unroll
-            for (int f = 0; f < NKW; ++f) acc = mfma_frag<XT>(qa[m][f], hb[f], acc);
-            // every column holds the same h: take column 0 (s_ctx doubles as the partial-q buffer)
-            if (jl == 0) *reinterpret_cast<floatx4*>(&s_ctx[wave][16 * (m0 + m) + 4 * g]) = acc;
+            for (int m = 0; m < MG; ++m) {
+                floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int f = 0; f < NKW; ++f) acc = mfma_frag<XT>(qa[m][f], hb[f], acc);
+                // every column holds the same h: take column 0
+                if (jl == 0) *reinterpret_cast<floatx4*>(&s_ctx[wave][16 * (m0 + m) + 4 * g]) = acc;
+            }
         }
     }
 #pragma unroll
@@ -506,15 +575,26 @@ __global__ __launch_bounds__(LSA_THREADS) void k_lsa(DevPtrs d, int cur)
         }
     }
     if (tid < ATT) s_v[tid] = -2.0f * vreg;       // v . tanh(x) = sum(v) - 2 sum(v / (1 + e^{2x}))
-    if constexpr (sizeof(XT) == 4) tile.load(d, lane);
+    if constexpr (TILE_LDS) {
+        s_tile[tid] = tv0;
+        if (tid < 256) s_tile[LSA_THREADS + tid] = tv1;
+    } else {
+        tile.load(d, lane);                      // fp32: too many registers to hold through the prologue
+    }
     __syncthreads();
     if (tid < ATT) {
-        float q = 0.f;
+        float q;
+        if constexpr (QP) {
+            q = (s_ctx[0][tid] + s_ctx[1][tid]) + (s_ctx[2][tid] + s_ctx[3][tid]);
+        } else {
+            q = 0.f;
 #pragma unroll
-        for (int w = 0; w < LSA_WAVES; ++w) q += s_ctx[w][tid];
+            for (int w = 0; w < LSA_WAVES; ++w) q += s_ctx[w][tid];
+        }
         s_q[tid] = q;
     }
     __syncthreads();
+    if constexpr (TILE_LDS) tile.load(s_tile, lane);
 
     // this lane's share of sum(v): its 32 attention dims (s_v holds -2 v)
     float vsum = 0.f;
@@ -726,12 +806,45 @@ __global__ __launch_bounds__(PROJ_THREADS) void k_proj(DevPtrs d, int cur)
     constexpr int NKW = NK / PROJ_WAVES;
     static_assert(NK % PROJ_WAVES == 0, "K must split evenly over the waves");
     constexpr int NM = PROJ_ROWS / 16;
-    // The projection weights do not depend on which tile this workgroup serves, and one CU pulling
-    // them is what bounds the kernel: with bf16 weights the wave's whole share (all row tiles of its
-    // K range) is requested before the table is even read.  fp32 fragments are twice the registers:
-    // there the row tiles go MH at a time.
+    // One CU pulling the projection weights (64 bytes a clock) is what bounds this kernel, so
+    // everything is requested at once, small things first: the activations and the slots'
+    // bookkeeping words (a workgroup serves the 16 slots blockIdx.x * 16 ..: no list of active
+    // tiles to wait for), the biases, then the weights.  With bf16 weights the wave's whole share
+    // (all row tiles of its K range) is in flight together; fp32 fragments are twice the
+    // registers: there the row tiles go one at a time.  A tile without a running request is
+    // computed and dropped (there is no early exit: the compiler would move the loads below it).
     constexpr bool W_EARLY = sizeof(XT) == 2;
     constexpr int MH = W_EARLY ? NM : 1;          // row tiles whose fragments are in flight together
+    const int tile = blockIdx.x;
+
+    __shared__ __attribute__((aligned(16))) float s_big[PROJ_WAVES * PROJ_ROWS * 16];   // partial sums, later hid
+    // row strides of 100 and 260 floats (an odd number of 16-byte pieces): the 16 columns of a
+    // fragment read then fall into 16 different bank groups instead of one
+    constexpr int MEL_LD = PROJ_ROWS + 4, HID_LD = PRENET + 4;
+    __shared__ __attribute__((aligned(16))) float s_mel[16][MEL_LD];
+    __shared__ int s_slot[16], s_t[16], s_cap[16];
+    float (*s_part)[PROJ_ROWS][16] = reinterpret_cast<float (*)[PROJ_ROWS][16]>(s_big);
+    float (*s_hid)[HID_LD] = reinterpret_cast<float (*)[HID_LD]>(s_big);
+    static_assert(16 * HID_LD <= PROJ_WAVES * PROJ_ROWS * 16, "hid must fit the partial-sum buffer it aliases");
+
+    const uint4* xnew = reinterpret_cast<const uint4*>(d.xdec[cur ^ 1]);   // h_dec of this step
+    const uint4* xcur = reinterpret_cast<const uint4*>(d.xdec[cur]);       // a of this step
+    uint4 b[NKW];
+#pragma unroll
+    for (int f = 0; f < NKW; ++f) {
+        const int ks = wave * NKW + f;
+        b[f] = ks < HID / KB ? xnew[xfrag(NKD, tile, XD_HD / KB + ks, lane)]
+                             : xcur[xfrag(NKD, tile, XD_A / KB + ks - HID / KB, lane)];
+    }
+    // slot bookkeeping of the 16 columns and this thread's biases of the reduction phase
+    const int my_sl = tile * 16 + (tid & 15);
+    const int my_live = d.live[my_sl], my_done = d.done[my_sl], my_t = d.t[my_sl], my_cap = d.n_steps[my_sl];
+    constexpr int RED_IT = 16 * PROJ_ROWS / PROJ_THREADS;
+    static_assert(16 * PROJ_ROWS % PROJ_THREADS == 0, "the reduction phase splits evenly");
+    float bias_r[RED_IT];
+#pragma unroll
+    for (int it = 0; it < RED_IT; ++it) bias_r[it] = d.bmel[min((tid + it * PROJ_THREADS) >> 4, N_PROJ - 1)];
+
     const uint4* W = reinterpret_cast<const uint4*>(d.Wmel) + lane;
     uint4 a[MH][NKW];
     auto load_proj_weights = [&](int m0) {
@@ -744,50 +857,22 @@ __global__ __launch_bounds__(PROJ_THREADS) void k_proj(DevPtrs d, int cur)
                 if (m0 + m < NM - 1 || jl == 0) a[m][f] = W[((size_t)(m0 + m) * NK + wave * NKW + f) * 64];
             }
     };
-    // (loads return in issue order: the two table words go out before the weights, so that the wait
-    // for them does not wait for the weights)
-    // A workgroup serves the 16 slots blockIdx.x * 16 ..: no list of active tiles to wait for, so the
-    // activations and the slots' bookkeeping words are requested together with the weights.  A tile
-    // without a running request is computed and dropped (there is no early exit: the compiler would
-    // move the loads below it).
-    const int tile = blockIdx.x;
     if constexpr (W_EARLY) load_proj_weights(0);
-
-    __shared__ __attribute__((aligned(16))) float s_big[PROJ_WAVES * PROJ_ROWS * 16];   // partial sums, later hid
-    __shared__ __attribute__((aligned(16))) float s_mel[16][PROJ_ROWS];
-    __shared__ int s_slot[16], s_t[16], s_cap[16];
-    float (*s_part)[PROJ_ROWS][16] = reinterpret_cast<float (*)[PROJ_ROWS][16]>(s_big);
-    float (*s_hid)[PRENET] = reinterpret_cast<float (*)[PRENET]>(s_big);
-
-    // slot bookkeeping of the 16 columns: four independent loads, consumed after phase 1
-    int my_sl = tile * 16 + (tid & 15);
-    const int my_live = d.live[my_sl], my_done = d.done[my_sl], my_t = d.t[my_sl], my_cap = d.n_steps[my_sl];
+    // keep the loads in this order: left alone, the scheduler issues the activation loads one at a
+    // time between the MFMAs, each a full round trip
+    __builtin_amdgcn_sched_barrier(0);
 
     // ---- phase 1: projection of [h_dec; a], K split over the waves
-    {
-        const uint4* xnew = reinterpret_cast<const uint4*>(d.xdec[cur ^ 1]);   // h_dec of this step
-        const uint4* xcur = reinterpret_cast<const uint4*>(d.xdec[cur]);       // a of this step
-        uint4 b[NKW];
 #pragma unroll
-        for (int f = 0; f < NKW; ++f) {
-            const int ks = wave * NKW + f;
-            b[f] = ks < HID / KB ? xnew[xfrag(NKD, tile, XD_HD / KB + ks, lane)]
-                                 : xcur[xfrag(NKD, tile, XD_A / KB + ks - HID / KB, lane)];
-        }
-        // keep these loads (and the bookkeeping loads above) here: left alone, the scheduler issues
-        // them one at a time between the MFMAs, each a full round trip
-        __builtin_amdgcn_sched_barrier(0);
+    for (int m0 = 0; m0 < NM; m0 += MH) {
+        if constexpr (!W_EARLY) load_proj_weights(m0);
 #pragma unroll
-        for (int m0 = 0; m0 < NM; m0 += MH) {
-            if constexpr (!W_EARLY) load_proj_weights(m0);
+        for (int m = 0; m < MH; ++m) {
+            floatx4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int m = 0; m < MH; ++m) {
-                floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+            for (int f = 0; f < NKW; ++f) acc = mfma_frag<XT>(a[m][f], b[f], acc);
 #pragma unroll
-                for (int f = 0; f < NKW; ++f) acc = mfma_frag<XT>(a[m][f], b[f], acc);
-#pragma unroll
-                for (int i = 0; i < 4; ++i) s_part[wave][16 * (m0 + m) + 4 * g + i][jl] = acc[i];
-            }
+            for (int i = 0; i < 4; ++i) s_part[wave][16 * (m0 + m) + 4 * g + i][jl] = acc[i];
         }
     }
 
@@ -818,11 +903,13 @@ __global__ __launch_bounds__(PROJ_THREADS) void k_proj(DevPtrs d, int cur)
     __syncthreads();
 
     // ---- phase 2: reduce, bias, hand the frame out
-    for (int idx = tid; idx < 16 * PROJ_ROWS; idx += PROJ_THREADS) {
+#pragma unroll
+    for (int it = 0; it < RED_IT; ++it) {
+        const int idx = tid + it * PROJ_THREADS;
         const int o = idx >> 4, r = idx & 15;
         float v = 0.f;
         if (o < N_PROJ) {
-            v = d.bmel[o];
+            v = bias_r[it];
 #pragma unroll
             for (int w = 0; w < PROJ_WAVES; ++w) v += s_part[w][o][r];
         }
@@ -1003,7 +1090,7 @@ __global__ __launch_bounds__(256) void k_x_set(XT* X, int NK, int slot, int off,
 // launch wrappers
 // ---------------------------------------------------------------------------
 template <typename XT, typename MT>
-static hipError_t step_typed(const DevPtrs& d, int n_req, int n_tiles, int lsa_split, bool wide, int cur, hipStream_t s, hipEvent_t* ev)
+static hipError_t step_typed(const DevPtrs& d, int n_req, int n_tiles, int lsa_split, bool wide, bool qpart, int cur, hipStream_t s, hipEvent_t* ev)
 {
     constexpr int KB = Frag<XT>::KB;
     auto mark = [&](int i) { if (ev) (void)hipEventRecord(ev[i], s); };
@@ -1015,19 +1102,30 @@ static hipError_t step_typed(const DevPtrs& d, int n_req, int n_tiles, int lsa_s
     // H_att(t): consumed by this step's decoder LSTM / attention and by the next step's attention LSTM
     constexpr bool HAS_WIDE = sizeof(XT) == 2;     // the fp32 fragments of two row tiles do not fit the register file
     if (!HAS_WIDE) wide = false;
+    if (qpart) wide = false;                       // pools that pass q as partial products are small: one-row-tile kernels
     if (wide) {
         if constexpr (HAS_WIDE)
             hipLaunchKernelGGL((k_lstm2<XT, K_ATT>), dim3(HID / 4), dim3(LSTM_WAVES * 64), 0, s,
                                d.Wa, d.ba, xatt_cur, d.c_att, xdec_cur, K_DEC / KB, XD_HA, xatt_nxt, K_ATT / KB, XA_H,
                                d.table, d.live, d.done);
-    } else
-        hipLaunchKernelGGL((k_lstm<XT, K_ATT>), dim3(HID / 4), dim3(LSTM_WAVES * 64), 0, s,
+    } else if (qpart)
+        hipLaunchKernelGGL((k_lstm<XT, K_ATT, true>), dim3(HID / 4), dim3(LSTM_WAVES * 64), 0, s,
                            d.Wa, d.ba, xatt_cur, d.c_att, xdec_cur, K_DEC / KB, XD_HA, xatt_nxt, K_ATT / KB, XA_H,
-                           d.table, d.live, d.done);
+                           d.table, d.live, d.done, d.Wq_epi, d.qpart);
+    else
+        hipLaunchKernelGGL((k_lstm<XT, K_ATT, false>), dim3(HID / 4), dim3(LSTM_WAVES * 64), 0, s,
+                           d.Wa, d.ba, xatt_cur, d.c_att, xdec_cur, K_DEC / KB, XD_HA, xatt_nxt, K_ATT / KB, XA_H,
+                           d.table, d.live, d.done, nullptr, nullptr);
     mark(1);
-    if (lsa_split == 4) hipLaunchKernelGGL((k_lsa<XT, MT, 4>), dim3(n_req * 4), dim3(LSA_THREADS), 0, s, d, cur);
-    else if (lsa_split == 2) hipLaunchKernelGGL((k_lsa<XT, MT, 2>), dim3(n_req * 2), dim3(LSA_THREADS), 0, s, d, cur);
-    else hipLaunchKernelGGL((k_lsa<XT, MT, 1>), dim3(n_req), dim3(LSA_THREADS), 0, s, d, cur);
+    if (qpart) {
+        if (lsa_split == 4) hipLaunchKernelGGL((k_lsa<XT, MT, 4, true>), dim3(n_req * 4), dim3(LSA_THREADS), 0, s, d, cur);
+        else if (lsa_split == 2) hipLaunchKernelGGL((k_lsa<XT, MT, 2, true>), dim3(n_req * 2), dim3(LSA_THREADS), 0, s, d, cur);
+        else hipLaunchKernelGGL((k_lsa<XT, MT, 1, true>), dim3(n_req), dim3(LSA_THREADS), 0, s, d, cur);
+    } else {
+        if (lsa_split == 4) hipLaunchKernelGGL((k_lsa<XT, MT, 4, false>), dim3(n_req * 4), dim3(LSA_THREADS), 0, s, d, cur);
+        else if (lsa_split == 2) hipLaunchKernelGGL((k_lsa<XT, MT, 2, false>), dim3(n_req * 2), dim3(LSA_THREADS), 0, s, d, cur);
+        else hipLaunchKernelGGL((k_lsa<XT, MT, 1, false>), dim3(n_req), dim3(LSA_THREADS), 0, s, d, cur);
+    }
     mark(2);
     // H_dec(t): consumed by this step's projection and the next step's decoder LSTM (same buffer)
     if (wide) {
@@ -1036,9 +1134,9 @@ static hipError_t step_typed(const DevPtrs& d, int n_req, int n_tiles, int lsa_s
                                d.Wd, d.bd, reinterpret_cast<const uint4*>(d.xdec[cur]), d.c_dec, xdec_nxt, K_DEC / KB, XD_HD,
                                xdec_nxt, K_DEC / KB, XD_HD, d.table, d.live, d.done);
     } else
-        hipLaunchKernelGGL((k_lstm<XT, K_DEC>), dim3(HID / 4), dim3(LSTM_WAVES * 64), 0, s,
+        hipLaunchKernelGGL((k_lstm<XT, K_DEC, false>), dim3(HID / 4), dim3(LSTM_WAVES * 64), 0, s,
                            d.Wd, d.bd, reinterpret_cast<const uint4*>(d.xdec[cur]), d.c_dec, xdec_nxt, K_DEC / KB, XD_HD,
-                           xdec_nxt, K_DEC / KB, XD_HD, d.table, d.live, d.done);
+                           xdec_nxt, K_DEC / KB, XD_HD, d.table, d.live, d.done, nullptr, nullptr);
     mark(3);
     hipLaunchKernelGGL((k_proj<XT>), dim3(n_tiles), dim3(PROJ_THREADS), 0, s, d, cur);
     mark(4);
@@ -1048,9 +1146,9 @@ static hipError_t step_typed(const DevPtrs& d, int n_req, int n_tiles, int lsa_s
 hipError_t launch_step(const DevPtrs& d, const StepLaunch& cfg, int cur, hipStream_t s, hipEvent_t* ev)
 {
     if (cfg.n_blocks < 1 || cfg.n_tiles < 1) return hipSuccess;
-    if (cfg.wdtype == 0 && cfg.mdtype == 0) return step_typed<float, float>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cfg.wide_lstm != 0, cur, s, ev);
-    if (cfg.wdtype == 1 && cfg.mdtype == 1) return step_typed<bf16_t, bf16_t>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cfg.wide_lstm != 0, cur, s, ev);
-    if (cfg.wdtype == 1 && cfg.mdtype == 0) return step_typed<bf16_t, float>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cfg.wide_lstm != 0, cur, s, ev);
+    if (cfg.wdtype == 0 && cfg.mdtype == 0) return step_typed<float, float>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cfg.wide_lstm != 0, cfg.q_partials != 0, cur, s, ev);
+    if (cfg.wdtype == 1 && cfg.mdtype == 1) return step_typed<bf16_t, bf16_t>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cfg.wide_lstm != 0, cfg.q_partials != 0, cur, s, ev);
+    if (cfg.wdtype == 1 && cfg.mdtype == 0) return step_typed<bf16_t, float>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cfg.wide_lstm != 0, cfg.q_partials != 0, cur, s, ev);
     return hipErrorInvalidValue;
 }
 

@@ -80,11 +80,16 @@ struct Carver {
 };
 
 struct Layout {
-    size_t Wa, Wd, ba, bd, Wq, WmemT, lsa_kfrag, lsa_wfrag, v, Wmel, bmel, Wp1, Wp2;
+    size_t Wa, Wd, ba, bd, Wq, Wq_epi, qpart, WmemT, lsa_kfrag, lsa_wfrag, v, Wmel, bmel, Wp1, Wp2;
     size_t xatt[2], xdec[2], c_att, c_dec, m_last, w_last[2], w_acc[2], Fmem, PM, mel_ring, stop_ring;
     size_t L, t, n_steps, done, live, table, stage;
     size_t total;
 };
+
+// Pools of at most 32 slots pass the attention query from the attention LSTM to the attention
+// kernel as partial products (cheaper when a step is latency-bound, 128 KB of stores per request
+// otherwise).  Fixed per pool, so that a request's frames never depend on who else is in the pool.
+bool q_partials_for(const tts_config& c) { return c.max_pool <= 32; }
 
 Layout make_layout(const tts_config& c)
 {
@@ -98,6 +103,7 @@ Layout make_layout(const tts_config& c)
     l.ba = a.take((size_t)4 * HID * 4);
     l.bd = a.take((size_t)4 * HID * 4);
     l.Wq = a.take((size_t)ATT * HID * ws);
+    l.Wq_epi = a.take((size_t)ATT * HID * 4);
     l.WmemT = a.take((size_t)ENC * ATT * 4);
     l.lsa_kfrag = a.take((size_t)2 * 16 * 64 * 4);
     l.lsa_wfrag = a.take((size_t)16 * 64 * 16);
@@ -110,6 +116,7 @@ Layout make_layout(const tts_config& c)
         l.xatt[b] = a.take(S * K_ATT * ws);
         l.xdec[b] = a.take(S * K_DEC * ws);
     }
+    l.qpart = a.take((q_partials_for(c) ? S : 0) * (size_t)(HID / 4) * ATT * 4);
     l.c_att = a.take(S * HID * 4);
     l.c_dec = a.take(S * HID * 4);
     l.m_last = a.take(S * N_MEL * 4);
@@ -138,6 +145,13 @@ uint16_t host_f2bf(float f)
     memcpy(&u, &f, 4);
     u += 0x7FFFu + ((u >> 16) & 1u);
     return (uint16_t)(u >> 16);
+}
+float host_bf2f(uint16_t b)
+{
+    uint32_t u = (uint32_t)b << 16;
+    float f;
+    memcpy(&f, &u, 4);
+    return f;
 }
 // fp32 host values -> device array of the weight dtype
 int upload(void* dst, const std::vector<float>& src, bool bf16)
@@ -275,6 +289,17 @@ static int upload_weights(tts_pool* p, const tts_weights* w, char* base, const L
     if ((rc = upload(base + l.bd, bd, false))) return rc;
     if ((rc = upload(base + l.Wq, pack_fragments(ATT, HID, bf, [&](int r, int k) { return w->q_w[(size_t)r * HID + k]; }), bf)))
         return rc;
+    // W_q for the attention LSTM's epilogue: row tile rt of the gates = hidden units 4rt..4rt+3;
+    // lane l of A operand `at` holds W_q[16 at + l%16][4 rt + l/16] (kept in fp32: the values of the
+    // weight dtype; the product runs on the fp32 MFMA in both modes)
+    std::vector<float> wq_epi((size_t)ATT * HID);
+    for (int rt = 0; rt < HID / 4; ++rt)
+        for (int at = 0; at < ATT / 16; ++at)
+            for (int lane = 0; lane < 64; ++lane) {
+                const float x = w->q_w[(size_t)(16 * at + (lane & 15)) * HID + 4 * rt + (lane >> 4)];
+                wq_epi[((size_t)rt * (ATT / 16) + at) * 64 + lane] = bf ? host_bf2f(host_f2bf(x)) : x;
+            }
+    if ((rc = upload(base + l.Wq_epi, wq_epi, false))) return rc;
     std::vector<float> memT((size_t)ENC * ATT);
     for (int a = 0; a < ATT; ++a)
         for (int k = 0; k < ENC; ++k) memT[(size_t)k * ATT + a] = w->mem_w[(size_t)a * ENC + k];
@@ -339,6 +364,8 @@ extern "C" int tts_pool_create(const tts_config* cfg, const tts_weights* w, void
     d.ba = (const float*)(base + l.ba);
     d.bd = (const float*)(base + l.bd);
     d.Wq = base + l.Wq;
+    d.Wq_epi = reinterpret_cast<const float*>(base + l.Wq_epi);
+    d.qpart = reinterpret_cast<float*>(base + l.qpart);
     d.WmemT = (const float*)(base + l.WmemT);
     d.lsa_kfrag = base + l.lsa_kfrag;
     d.lsa_wfrag = base + l.lsa_wfrag;
@@ -483,6 +510,7 @@ static void shape_for(const tts_pool* p, int span, StepLaunch* sl)
     sl->n_tiles = (span + 15) / 16;
     sl->lsa_split = lsa_split_for(span);
     sl->wide_lstm = wide_lstm_for(span);
+    sl->q_partials = q_partials_for(p->cfg) ? 1 : 0;
 }
 
 // Queue `nsteps` consecutive steps for the current membership.  With graphs the

@@ -26,9 +26,9 @@ def make_pool(wl, weights, max_pool=None, max_enc_len=None, max_steps=None, use_
     return binding.Pool(cfg, weights)
 
 
-def gpu_decode(wl, weights, idx, window, **kw):
+def gpu_decode(wl, weights, idx, window, max_pool=None, **kw):
     """All requests `idx` join at step 0, `window` steps; returns mel [n, window, 80] (NaN past the end)."""
-    pool = make_pool(wl, weights, max_pool=max(len(idx), 1), **kw)
+    pool = make_pool(wl, weights, max_pool=max_pool or max(len(idx), 1), **kw)
     ids = [pool.add_request(wl.encoder_outputs(i), int(min(wl.n_steps[i], window))) for i in idx]
     pool.step_n(window)
     out = np.full((len(idx), window, wl.dims["n_mel"]), np.nan, np.float32)

@@ -275,8 +275,20 @@ def test_c4_full_pool_bf16(weights_bf16):
     err = max_err(gpu[sample], ref)
     say(f"  max abs err {err:.3e}")
     assert err <= TOL_BF16
-    solo = gpu_decode(wl, weights_bf16, [37], 50)
+    # alone in a pool of the same capacity (the capacity fixes how the attention query is computed)
+    solo = gpu_decode(wl, weights_bf16, [37], 50, max_pool=256)
     np.testing.assert_array_equal(solo[0], gpu[37])
+
+
+def test_small_and_large_capacity_pools_agree(wl8, weights_fp32, solo_frames):
+    """Pools of at most 32 slots hand the attention query over as partial products
+    from the attention LSTM, larger ones compute it in the attention kernel: the
+    same numbers up to summation order."""
+    say("case capacity: max_pool 8 vs 40, fp32")
+    big = gpu_decode(wl8, weights_fp32, list(range(8)), 24, max_pool=40)
+    for i in range(8):
+        n = solo_frames[i].shape[0]
+        assert np.abs(big[i, :n] - solo_frames[i]).max() <= 1e-5
 
 
 def test_c3_shrinking_pool_full_job(weights_bf16):
