@@ -24,15 +24,6 @@ constexpr int N_PROJ = N_MEL + 1;           // mel rows + stop row
 constexpr int MAX_POOL = 256;
 constexpr int MAX_ENC_LEN = 1024;
 constexpr int MAX_TILES = MAX_POOL / 16;     // a pool tile = 16 consecutive slots = the 16 columns of one MFMA
-// device table: [0] = number of active requests, [1] = number of active tiles,
-// [TABLE_TILES + i] = i-th active tile (header and tile list share the first 128 bytes, so a
-// kernel gets both with one round trip), [TABLE_SLOTS + i] = slot of active request i.
-// Only the LSTM kernels walk the tile list; the attention and projection kernels are laid over
-// slots / tiles directly and look at live[] and done[].
-constexpr int TABLE_TILES = 2;
-constexpr int TABLE_SLOTS = 32;
-constexpr int TABLE_INTS = TABLE_SLOTS + MAX_POOL;
-
 // offsets inside the activation rows
 constexpr int XA_P = 0, XA_A = PRENET, XA_H = PRENET + ENC;       // x_att = [p | a | h_att]
 constexpr int XD_HA = 0, XD_A = HID, XD_HD = HID + ENC;           // x_dec = [h_att | a | h_dec]
@@ -70,19 +61,16 @@ struct DevPtrs {
     int* t;               // [slots] frames produced
     int* n_steps;         // [slots]
     int* done;            // [slots] reached its last frame (or tripped the stop threshold)
-    int* live;            // [MAX_POOL] listed in the table (advanced by the next step)
-    int* table;           // [TABLE_INTS]
+    int* live;            // [MAX_POOL] 1 = the slot's request is advanced by the next step (set by the host's membership upload)
     float* stage;         // [max_enc_len][ENC] fp32 staging for host-side encoder outputs
     int max_enc_len;
     int max_steps;
     float stop_threshold; // < 0: disabled
 };
 
-struct TableArgs {
-    int n_active;
-    int n_tiles;
-    uint16_t slot[MAX_POOL];
-    uint8_t tile[MAX_TILES];
+// membership upload: which slots the next steps advance (kernel argument, 40 bytes)
+struct LiveArgs {
+    uint32_t bits[MAX_POOL / 32];
 };
 
 }  // namespace tts

@@ -15,14 +15,14 @@ struct StepLaunch {
     int q_partials; // non-zero: the attention LSTM hands the query over as partial products (pools of <= 32 slots)
 };
 
-// One decoder step (paper Eq. 2) for every request listed in d.table.
+// One decoder step (paper Eq. 2) for every request whose slot is flagged in d.live.
 // `cur` selects which half of the double-buffered activations is read.
 // If `ev` is given it holds N_STEP_KERNELS + 1 events: ev[0] is recorded before the
 // first kernel and ev[i + 1] after kernel i (per-kernel device times).
 constexpr int N_STEP_KERNELS = 4;
 hipError_t launch_step(const DevPtrs& d, const StepLaunch& cfg, int cur, hipStream_t s, hipEvent_t* ev = nullptr);
 
-hipError_t launch_set_table(const DevPtrs& d, const TableArgs& args, hipStream_t s);
+hipError_t launch_set_live(const DevPtrs& d, const LiveArgs& args, hipStream_t s);
 hipError_t launch_slot_init(const DevPtrs& d, int wdtype, int slot, int L, int n_steps, hipStream_t s);
 // F_enc (fp32, device) -> slot memory, and processed memory PM = F W_mem^T
 hipError_t launch_join_memory(const DevPtrs& d, int mdtype, const float* F_dev, int slot, int L, hipStream_t s);

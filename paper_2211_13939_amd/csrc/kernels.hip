@@ -149,7 +149,7 @@ __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm(
     const uint4* __restrict__ Wfrag, const float* __restrict__ bias, const uint4* __restrict__ X,
     float* __restrict__ c_state, XT* __restrict__ hout0, int nk0, int off0,
     XT* __restrict__ hout1, int nk1, int off1,
-    const int* __restrict__ table, const int* __restrict__ live, const int* __restrict__ done,
+    int n_tiles, const int* __restrict__ live, const int* __restrict__ done,
     const float* __restrict__ wq_epi, float* __restrict__ qpart)
 {
     constexpr int NW = LSTM_WAVES;
@@ -161,17 +161,13 @@ __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm(
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int rt = blockIdx.x;
 
-    // Loads come back in the order they were issued, and waiting for one waits for everything
-    // issued before it.  So the header and tile list go out FIRST (one round trip; the activation
-    // loads depend on it), then this workgroup's slice of the gate matrix, the only HBM stream:
-    // the activations are then requested while the weights are still on their way.
-    int hdr[TABLE_TILES + MAX_TILES];
-#pragma unroll
-    for (int i = 0; i < TABLE_TILES + MAX_TILES; ++i) hdr[i] = table[i];
+    // The pool tiles 0 .. n_tiles - 1 (a launch argument: all active slots lie below) are walked
+    // directly, not through a list of active tiles: nothing has to be read before the activations
+    // can be requested, they go out together with this workgroup's slice of the gate matrix (the
+    // only HBM stream).  A tile without a running request is computed and dropped.
     uint4 a[NF];
 #pragma unroll
     for (int f = 0; f < NF; ++f) a[f] = Wfrag[xfrag(NK, rt, wave + f * NW, lane)];
-    const int n_tiles = hdr[1];
     // the first four waves also own the cell update of (pool tile in flight = wave, lane)
     const int unit = rt * 4 + (lane >> 4);
     floatx4 bias4 = {0.f, 0.f, 0.f, 0.f};
@@ -191,10 +187,8 @@ __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm(
         // The cell update's inputs: three independent, unconditional loads (a load inside a branch
         // makes the compiler wait for every load in flight, the weights included, where the branch
         // rejoins).  Waves without a cell update load the same words as wave % 4 and drop them.
-        const int wsel = wave & 3;
-        const int my_tile = wsel == 0 ? hdr[TABLE_TILES + tg] : wsel == 1 ? hdr[TABLE_TILES + tg + 1]
-                          : wsel == 2 ? hdr[TABLE_TILES + tg + 2] : hdr[TABLE_TILES + tg + 3];
-        const int sl = (my_tile & (MAX_TILES - 1)) * 16 + (lane & 15);   // entries past n_tiles are stale: keep them in bounds
+        const int my_tile = min(tg + (wave & 3), n_tiles - 1);
+        const int sl = my_tile * 16 + (lane & 15);
         const int lv = live[sl], dn = done[sl];
         const float c_old = c_state[(size_t)sl * HID + unit];
         __builtin_amdgcn_sched_barrier(0);   // issued here, looked at after the products
@@ -204,7 +198,7 @@ __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm(
 #pragma unroll
             for (int t = 0; t < TIF; ++t) {
                 if (tg + t0 + t < n_tiles) {
-                    const int tile = hdr[TABLE_TILES + tg + t0 + t];
+                    const int tile = tg + t0 + t;
 #pragma unroll
                     for (int f = 0; f < NF; ++f) b[t][f] = X[xfrag(NK, tile, wave + f * NW, lane)];
                 }
@@ -263,7 +257,7 @@ __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm2(
     const uint4* __restrict__ Wfrag, const float* __restrict__ bias, const uint4* __restrict__ X,
     float* __restrict__ c_state, XT* __restrict__ hout0, int nk0, int off0,
     XT* __restrict__ hout1, int nk1, int off1,
-    const int* __restrict__ table, const int* __restrict__ live, const int* __restrict__ done)
+    int n_tiles, const int* __restrict__ live, const int* __restrict__ done)
 {
     constexpr int NW = LSTM_WAVES;
     constexpr int NK = K / Frag<XT>::KB;
@@ -273,19 +267,12 @@ __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm2(
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int rg = blockIdx.x & 127, cg = blockIdx.x >> 7;
 
-    // table first, weights second (see k_lstm): the wait for the table must not wait for the weights
-    __shared__ int s_hdr[TABLE_TILES + MAX_TILES];
     __shared__ floatx4 red[NW][2 * TP][64];
-    int hdr_mine = 0;
-    if (threadIdx.x < TABLE_TILES + MAX_TILES) hdr_mine = table[threadIdx.x];
     uint4 a[2][NF];
 #pragma unroll
     for (int r = 0; r < 2; ++r)
 #pragma unroll
         for (int f = 0; f < NF; ++f) a[r][f] = Wfrag[xfrag(NK, 2 * rg + r, wave + f * NW, lane)];
-    if (threadIdx.x < TABLE_TILES + MAX_TILES) s_hdr[threadIdx.x] = hdr_mine;
-    __syncthreads();
-    const int n_tiles = s_hdr[1];
     const int half = (n_tiles + 1) >> 1;
     const int c0 = cg == 0 ? 0 : half, c1 = cg == 0 ? half : n_tiles;
 
@@ -297,8 +284,7 @@ __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm2(
 
     for (int tp = c0; tp < c1; tp += TP) {
         // cell update inputs: independent, unconditional loads (see k_lstm)
-        const int tq = min(tp + (et & (TP - 1)), c1 - 1);
-        const int sl = (s_hdr[TABLE_TILES + tq] & (MAX_TILES - 1)) * 16 + (lane & 15);
+        const int sl = min(tp + (et & (TP - 1)), c1 - 1) * 16 + (lane & 15);
         const int lv = live[sl], dn = done[sl];
         const float c_old = c_state[(size_t)sl * HID + unit];
         __builtin_amdgcn_sched_barrier(0);
@@ -306,7 +292,7 @@ __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm2(
 #pragma unroll
         for (int t = 0; t < TP; ++t) {
             if (tp + t < c1) {
-                const int tile = s_hdr[TABLE_TILES + tp + t];
+                const int tile = tp + t;
 #pragma unroll
                 for (int f = 0; f < NF; ++f) b[t][f] = X[xfrag(NK, tile, wave + f * NW, lane)];
             }
@@ -1013,17 +999,10 @@ __global__ __launch_bounds__(256) void k_prenet_slot(DevPtrs d, int slot)
 // ---------------------------------------------------------------------------
 // Pool bookkeeping on the device
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(MAX_POOL) void k_set_table(TableArgs a, int* table, int* live)
+__global__ __launch_bounds__(MAX_POOL) void k_set_live(LiveArgs a, int* live)
 {
     const int tid = threadIdx.x;
-    live[tid] = 0;
-    __syncthreads();
-    if (tid == 0) { table[0] = a.n_active; table[1] = a.n_tiles; }
-    if (tid < a.n_active) {
-        table[TABLE_SLOTS + tid] = a.slot[tid];
-        live[a.slot[tid]] = 1;
-    }
-    if (tid < a.n_tiles) table[TABLE_TILES + tid] = a.tile[tid];
+    live[tid] = (a.bits[tid >> 5] >> (tid & 31)) & 1u;
 }
 
 // a joining request starts from all-zero state
@@ -1107,15 +1086,15 @@ static hipError_t step_typed(const DevPtrs& d, int n_req, int n_tiles, int lsa_s
         if constexpr (HAS_WIDE)
             hipLaunchKernelGGL((k_lstm2<XT, K_ATT>), dim3(HID / 4), dim3(LSTM_WAVES * 64), 0, s,
                                d.Wa, d.ba, xatt_cur, d.c_att, xdec_cur, K_DEC / KB, XD_HA, xatt_nxt, K_ATT / KB, XA_H,
-                               d.table, d.live, d.done);
+                               n_tiles, d.live, d.done);
     } else if (qpart)
         hipLaunchKernelGGL((k_lstm<XT, K_ATT, true>), dim3(HID / 4), dim3(LSTM_WAVES * 64), 0, s,
                            d.Wa, d.ba, xatt_cur, d.c_att, xdec_cur, K_DEC / KB, XD_HA, xatt_nxt, K_ATT / KB, XA_H,
-                           d.table, d.live, d.done, d.Wq_epi, d.qpart);
+                           n_tiles, d.live, d.done, d.Wq_epi, d.qpart);
     else
         hipLaunchKernelGGL((k_lstm<XT, K_ATT, false>), dim3(HID / 4), dim3(LSTM_WAVES * 64), 0, s,
                            d.Wa, d.ba, xatt_cur, d.c_att, xdec_cur, K_DEC / KB, XD_HA, xatt_nxt, K_ATT / KB, XA_H,
-                           d.table, d.live, d.done, nullptr, nullptr);
+                           n_tiles, d.live, d.done, nullptr, nullptr);
     mark(1);
     if (qpart) {
         if (lsa_split == 4) hipLaunchKernelGGL((k_lsa<XT, MT, 4, true>), dim3(n_req * 4), dim3(LSA_THREADS), 0, s, d, cur);
@@ -1132,11 +1111,11 @@ static hipError_t step_typed(const DevPtrs& d, int n_req, int n_tiles, int lsa_s
         if constexpr (HAS_WIDE)
             hipLaunchKernelGGL((k_lstm2<XT, K_DEC>), dim3(HID / 4), dim3(LSTM_WAVES * 64), 0, s,
                                d.Wd, d.bd, reinterpret_cast<const uint4*>(d.xdec[cur]), d.c_dec, xdec_nxt, K_DEC / KB, XD_HD,
-                               xdec_nxt, K_DEC / KB, XD_HD, d.table, d.live, d.done);
+                               xdec_nxt, K_DEC / KB, XD_HD, n_tiles, d.live, d.done);
     } else
         hipLaunchKernelGGL((k_lstm<XT, K_DEC, false>), dim3(HID / 4), dim3(LSTM_WAVES * 64), 0, s,
                            d.Wd, d.bd, reinterpret_cast<const uint4*>(d.xdec[cur]), d.c_dec, xdec_nxt, K_DEC / KB, XD_HD,
-                           xdec_nxt, K_DEC / KB, XD_HD, d.table, d.live, d.done, nullptr, nullptr);
+                           xdec_nxt, K_DEC / KB, XD_HD, n_tiles, d.live, d.done, nullptr, nullptr);
     mark(3);
     hipLaunchKernelGGL((k_proj<XT>), dim3(n_tiles), dim3(PROJ_THREADS), 0, s, d, cur);
     mark(4);
@@ -1152,9 +1131,9 @@ hipError_t launch_step(const DevPtrs& d, const StepLaunch& cfg, int cur, hipStre
     return hipErrorInvalidValue;
 }
 
-hipError_t launch_set_table(const DevPtrs& d, const TableArgs& args, hipStream_t s)
+hipError_t launch_set_live(const DevPtrs& d, const LiveArgs& args, hipStream_t s)
 {
-    hipLaunchKernelGGL(k_set_table, dim3(1), dim3(MAX_POOL), 0, s, args, d.table, d.live);
+    hipLaunchKernelGGL(k_set_live, dim3(1), dim3(MAX_POOL), 0, s, args, d.live);
     return hipGetLastError();
 }
 

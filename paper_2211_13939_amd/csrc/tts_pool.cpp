@@ -82,7 +82,7 @@ struct Carver {
 struct Layout {
     size_t Wa, Wd, ba, bd, Wq, Wq_epi, qpart, WmemT, lsa_kfrag, lsa_wfrag, v, Wmel, bmel, Wp1, Wp2;
     size_t xatt[2], xdec[2], c_att, c_dec, m_last, w_last[2], w_acc[2], Fmem, PM, mel_ring, stop_ring;
-    size_t L, t, n_steps, done, live, table, stage;
+    size_t L, t, n_steps, done, live, stage;
     size_t total;
 };
 
@@ -133,7 +133,6 @@ Layout make_layout(const tts_config& c)
     l.n_steps = a.take(S * 4);
     l.done = a.take(S * 4);
     l.live = a.take(MAX_POOL * 4);
-    l.table = a.take(TABLE_INTS * 4);
     l.stage = a.take(ML * ENC * 4);
     l.total = a.off;
     return l;
@@ -261,7 +260,6 @@ struct tts_pool {
     hipStream_t stream = nullptr;
     std::unique_ptr<PoolBook> book;
     int parity = 0;               // activation buffer half the next step reads
-    int n_tiles = 0;              // 16-slot tiles with at least one active request (as last uploaded)
     int slot_span = 0;            // highest active slot + 1 (as last uploaded): what the per-slot grids must cover
     bool stop_enabled = false;
     bool timing = false;
@@ -394,7 +392,6 @@ extern "C" int tts_pool_create(const tts_config* cfg, const tts_weights* w, void
     d.n_steps = (int*)(base + l.n_steps);
     d.done = (int*)(base + l.done);
     d.live = (int*)(base + l.live);
-    d.table = (int*)(base + l.table);
     d.stage = (float*)(base + l.stage);
     d.max_enc_len = cfg->max_enc_len;
     d.max_steps = cfg->max_steps;
@@ -474,25 +471,19 @@ static int bucket_for(int n)
     return b;
 }
 
-static int push_table(tts_pool* p)
+// Tell the device which slots the next steps advance (only when the membership changed).
+static int push_membership(tts_pool* p)
 {
     if (!p->book->dirty()) return TTS_OK;
-    TableArgs a;
+    LiveArgs a;
     memset(&a, 0, sizeof a);
-    const std::vector<int>& act = p->book->active();
-    a.n_active = (int)act.size();
-    bool used[MAX_TILES] = {false};
     int span = 0;
-    for (size_t i = 0; i < act.size(); ++i) {
-        a.slot[i] = (uint16_t)act[i];
-        used[act[i] >> 4] = true;
-        if (act[i] + 1 > span) span = act[i] + 1;
+    for (int sl : p->book->active()) {
+        a.bits[sl >> 5] |= 1u << (sl & 31);
+        if (sl + 1 > span) span = sl + 1;
     }
     p->slot_span = span;
-    for (int t = 0; t < MAX_TILES; ++t)
-        if (used[t]) a.tile[a.n_tiles++] = (uint8_t)t;
-    p->n_tiles = a.n_tiles;
-    HIP_TRY(launch_set_table(p->d, a, p->stream));
+    HIP_TRY(launch_set_live(p->d, a, p->stream));
     p->book->clear_dirty();
     return TTS_OK;
 }
@@ -559,7 +550,7 @@ static int step_impl(tts_pool* p, int n, int64_t* out_frames, int* out_last_acti
         const int n_active = (int)p->book->active().size();
         last = n_active;
         if (n_active == 0) break;
-        int rc = push_table(p);
+        int rc = push_membership(p);
         if (rc) return rc;
         int g = 1;
         if (p->cfg.use_graph)
@@ -611,7 +602,7 @@ extern "C" int tts_pool_kernel_times(tts_pool* p, int n, float* out_us, int cap,
     for (int i = 0; i < n && rc == TTS_OK; ++i) {
         const int n_active = (int)p->book->active().size();
         if (n_active == 0) break;
-        if ((rc = push_table(p))) break;
+        if ((rc = push_membership(p))) break;
         StepLaunch sl;
         sl.wdtype = p->cfg.weight_dtype;
         sl.mdtype = p->cfg.memory_dtype;
