@@ -116,6 +116,38 @@ def pool_sweep(binding, synth, torch, use_graph):
     return rows
 
 
+HOP_S = 256.0 / 22050.0        # seconds of audio per mel frame (Sec. 3.1: 22.05 kHz; 32 frames ~ 372 ms)
+
+
+def stream_arrivals(w5, kind, qps, n=None):
+    """Arrival times for (the first n of) the c5 request set: its own Poisson trace, or evenly spaced at `qps`."""
+    if kind == "poisson" and qps == 100.0 and n is None:
+        return w5.arrival_s
+    n = n or w5.n_requests
+    if kind == "even":
+        return np.arange(n, dtype=np.float64) / qps
+    rng = np.random.default_rng([w5.seed, int(qps)])
+    return np.cumsum(rng.exponential(1.0 / qps, size=n))
+
+
+def stream_run(stream, pool5, w5, enc, arrival, join_every, max_pool):
+    n = len(arrival)
+    n_steps = w5.n_steps[:n]
+    be = stream.GpuBackend(pool5, lambda i, e=enc: e[i], n_steps, w5.chunk_frames)
+    r = stream.simulate(be, arrival, n_steps, w5.chunk_frames, join_every=join_every, max_pool=max_pool)
+    pc = r.percentiles("first")
+    lc = r.percentiles("last")
+    rtf = r.last_chunk_latency_s / (n_steps.astype(np.float64) * HOP_S)
+    return {"p50_ms": pc["p50"] * 1e3, "p95_ms": pc["p95"] * 1e3, "p99_ms": pc["p99"] * 1e3,
+            "last_chunk_p50_ms": lc["p50"] * 1e3, "last_chunk_p95_ms": lc["p95"] * 1e3,
+            "rtf_p50": float(np.percentile(rtf, 50)), "rtf_p95": float(np.percentile(rtf, 95)),
+            "mean_pool": sum(k * v for k, v in r.pool_size_hist.items()) / max(1, r.n_steps),
+            "max_pool_seen": max(r.pool_size_hist), "busy_s": r.busy_s, "requests": int(n),
+            "pool_size_hist_steps": {str(k): int(v) for k, v in sorted(r.pool_size_hist.items())},
+            "steps": r.n_steps, "host_segments": r.n_segments,
+            "wall_us_per_step": r.busy_s * 1e6 / max(1, r.n_steps)}
+
+
 def job_roofline_bytes(wl, s_w, s_m):
     """Algorithmic bytes of the whole shrinking-pool job: the per-step bytes integrated over the
     actual membership (request i is active during steps 0 .. n_i - 1)."""
@@ -140,6 +172,11 @@ def main():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run ten plain device copies of 256 MiB: a kernel of known traffic to scale "
                          "rocprofv3's FETCH_SIZE / WRITE_SIZE readings with")
+    ap.add_argument("--arrivals", default="poisson", choices=["poisson", "even"],
+                    help="stream load: Poisson arrivals (the c5 workload) or evenly spaced ones (the paper's pressure test)")
+    ap.add_argument("--qps", type=float, default=100.0, help="stream load: requests per second")
+    ap.add_argument("--qps-sweep", action="store_true",
+                    help="only the stream load, evenly spaced arrivals at 10..100 requests/s (Sec. 3.2.1's pressure test, 10 s each)")
     ap.add_argument("--pool-sweep", action="store_true",
                     help="only time the full-pool step for pools of 1..256 requests (bf16, L ~ U{30..300})")
     ap.add_argument("--profile-only", action="store_true",
@@ -167,6 +204,24 @@ def main():
         return
     if args.pool_sweep:
         print(json.dumps({"pool_sweep": pool_sweep(binding, synth, torch, not args.no_graph)}))
+        return
+    if args.qps_sweep:
+        from paper_2211_13939_amd import stream
+        w5 = synth.workload("c5")
+        cfg5 = binding.make_config(w5.dims, max_pool=32, max_enc_len=int(w5.enc_len.max()),
+                                   max_steps=int(w5.n_steps.max()), chunk_frames=w5.chunk_frames, bf16=True,
+                                   use_graph=not args.no_graph)
+        pool5 = binding.Pool(cfg5, synth.make_weights(bf16=True))
+        n_req = 300
+        enc = [torch.from_numpy(w5.encoder_outputs(i)).to(pool5.device) for i in range(n_req)]
+        torch.cuda.synchronize()
+        rows = []
+        for qps in range(10, 101, 10):
+            r = stream_run(stream, pool5, w5, enc, stream_arrivals(w5, "even", float(qps), n_req), 1, 32)
+            rows.append({"qps": qps, **{k: r[k] for k in ("p50_ms", "p95_ms", "last_chunk_p50_ms", "rtf_p50", "mean_pool",
+                                                          "max_pool_seen", "busy_s")}})
+        pool5.close()
+        print(json.dumps({"qps_sweep": {"arrivals": "evenly spaced, the first 300 requests of the c5 set", "rows": rows}}))
         return
     wl = synth.workload(args.workload)
     weights = synth.make_weights(bf16=wl.bf16)
@@ -292,21 +347,16 @@ def main():
         enc5_host = [w5.encoder_outputs(i) for i in range(w5.n_requests)]
         enc5_dev = [torch.from_numpy(a).to(dev) for a in enc5_host]
         torch.cuda.synchronize()
+        arrival = stream_arrivals(w5, args.arrivals, args.qps)
         res = {}
         for name, je, enc in (("per_step_join", 1, enc5_dev), ("per_chunk_join", w5.chunk_frames, enc5_dev),
                               ("per_step_join_host_input", 1, enc5_host)):
-            be = stream.GpuBackend(pool5, lambda i, e=enc: e[i], w5.n_steps, w5.chunk_frames)
-            r = stream.simulate(be, w5.arrival_s, w5.n_steps, w5.chunk_frames, join_every=je, max_pool=32)
-            pc = r.percentiles("first")
-            res[name] = {"p50_ms": pc["p50"] * 1e3, "p95_ms": pc["p95"] * 1e3, "p99_ms": pc["p99"] * 1e3,
-                         "last_chunk_p50_ms": r.percentiles("last")["p50"] * 1e3,
-                         "mean_pool": sum(k * v for k, v in r.pool_size_hist.items()) / max(1, r.n_steps),
-                         "max_pool_seen": max(r.pool_size_hist), "busy_s": r.busy_s, "requests": int(w5.n_requests),
-                         "steps": r.n_steps,
-                         "host_segments": r.n_segments, "wall_us_per_step": r.busy_s * 1e6 / max(1, r.n_steps)}
-        out["stream"] = {"workload": "c5: Poisson 100 QPS x 10 s, L~U{30..300}, frames=4L, 40-frame chunks; encoder "
-                                     "outputs resident in HBM (per_step_join_host_input: handed over from pageable "
-                                     "host memory, PCIe copy included)",
+            res[name] = stream_run(stream, pool5, w5, enc, arrival, je, 32)
+        out["stream"] = {"workload": f"c5: {args.arrivals} arrivals at {args.qps:g}/s, {w5.n_requests} requests, L~U{{30..300}}, "
+                                     "frames=4L, 40-frame chunks; encoder outputs resident in HBM "
+                                     "(per_step_join_host_input: handed over from pageable host memory, PCIe copy "
+                                     "included); rtf = last-chunk latency / audio duration at 256 samples per frame, "
+                                     "22.05 kHz (decoder only)",
                          **res, "paper_context": "first-chunk latency < 80 ms at 100 QPS, full pipeline, one A10"}
         pool5.close()
     else:
