@@ -5,14 +5,16 @@ import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 SRC = os.path.join(HERE, "tts_oracle.c")
+SRC_POSTNET = os.path.join(HERE, "postnet_oracle.c")
 OUT = os.path.join(HERE, "liboracle.so")
 
 
 def build(force: bool = True) -> str:
-    if not force and os.path.exists(OUT) and os.path.getmtime(OUT) >= os.path.getmtime(SRC):
+    newest = max(os.path.getmtime(SRC), os.path.getmtime(SRC_POSTNET))
+    if not force and os.path.exists(OUT) and os.path.getmtime(OUT) >= newest:
         return OUT
     cmd = ["gcc", "-O2", "-std=c99", "-fPIC", "-shared", "-fopenmp", "-Wall", "-Wextra",
-           "-o", OUT, SRC, "-lm"]
+           "-o", OUT, SRC, SRC_POSTNET, "-lm"]
     subprocess.run(cmd, check=True)
     return OUT
 

@@ -54,7 +54,8 @@ def lib() -> C.CDLL:
     global _lib
     if _lib is None:
         path = _build.OUT
-        if not os.path.exists(path) or os.path.getmtime(path) < os.path.getmtime(_build.SRC):
+        if (not os.path.exists(path) or os.path.getmtime(path) < os.path.getmtime(_build.SRC)
+                or os.path.getmtime(path) < os.path.getmtime(_build.SRC_POSTNET)):
             _build.build(force=True)
         _lib = load(path)
     return _lib
@@ -80,6 +81,10 @@ def _declare(L: C.CDLL) -> None:
     L.orc_pool_decode.argtypes = [C.POINTER(OrcDims), C.POINTER(OrcWeights), C.c_int,
                                   C.POINTER(_fp), _ip, _ip, C.c_int, C.c_int, C.c_double, C.c_int,
                                   _dp, _dp, _ip]
+    L.orc_conv5.argtypes = [C.c_int, C.c_int, C.c_int, _fp, _fp, _dp, C.c_int, _dp]
+    L.orc_postnet.argtypes = [C.c_int, C.c_int, C.c_int, C.POINTER(_fp), C.POINTER(_fp), C.c_int, _dp, _dp]
+    L.orc_postnet_chunk.argtypes = [C.c_int, C.c_int, C.c_int, C.POINTER(_fp), C.POINTER(_fp), C.c_int, C.c_int,
+                                    _dp, _dp]
 
 
 def _f(a: np.ndarray):
@@ -252,3 +257,47 @@ def pool_decode(dims, weights: Weights, F_list: Sequence[np.ndarray], n_steps: S
                                  int(pm_round_bf16), float(stop_threshold), int(n_threads),
                                  _d(mel), _d(stop), frames.ctypes.data_as(_ip))
     return mel, stop, frames, used
+
+
+# ---- PostNet (oracle/postnet_oracle.c)
+class PostnetWeights:
+    """conv_w[l]: [c_out, c_in, 5], conv_b[l]: [c_out], fp32."""
+
+    def __init__(self, conv_w: Sequence[np.ndarray], conv_b: Sequence[np.ndarray]):
+        self.w = [np.ascontiguousarray(a, np.float32) for a in conv_w]
+        self.b = [np.ascontiguousarray(a, np.float32) for a in conv_b]
+        self.n_layers = len(self.w)
+        self.n_mel = self.w[0].shape[1]
+        self.channels = self.w[0].shape[0]
+        assert self.w[-1].shape[0] == self.n_mel and all(a.shape[2] == 5 for a in self.w)
+        self.wp = (_fp * self.n_layers)(*[_f(a) for a in self.w])
+        self.bp = (_fp * self.n_layers)(*[_f(a) for a in self.b])
+
+
+def conv5(w, b, x, apply_tanh=False):
+    w = np.ascontiguousarray(w, np.float32)
+    b = np.ascontiguousarray(b, np.float32)
+    x = np.ascontiguousarray(x, np.float64)
+    T, c_in = x.shape
+    c_out = w.shape[0]
+    assert w.shape == (c_out, c_in, 5) and b.shape == (c_out,)
+    y = np.zeros((T, c_out), np.float64)
+    lib().orc_conv5(T, c_in, c_out, _f(w), _f(b), _d(x), int(apply_tanh), _d(y))
+    return y
+
+
+def postnet(W: PostnetWeights, mel):
+    mel = np.ascontiguousarray(mel, np.float64)
+    T = mel.shape[0]
+    out = np.zeros((T, W.n_mel), np.float64)
+    lib().orc_postnet(W.n_layers, W.n_mel, W.channels, W.wp, W.bp, T, _d(mel), _d(out))
+    return out
+
+
+def postnet_chunk(W: PostnetWeights, mel_so_far, s: int):
+    """Chunk [s, e) with e = len(mel_so_far)."""
+    mel = np.ascontiguousarray(mel_so_far, np.float64)
+    e = mel.shape[0]
+    out = np.zeros((e - s, W.n_mel), np.float64)
+    lib().orc_postnet_chunk(W.n_layers, W.n_mel, W.channels, W.wp, W.bp, int(s), int(e), _d(mel), _d(out))
+    return out

@@ -105,6 +105,25 @@ def make_weights(seed: int = WEIGHT_SEED, dims: Dict[str, int] = DIMS,
     return w
 
 
+POSTNET = dict(n_layers=5, kernel=5, channels=512)
+
+
+def make_postnet_weights(seed: int = 1235, bf16: bool = False, n_mel: int = 80, channels: int = 512,
+                         n_layers: int = 5, std: float = 0.05):
+    """PostNet stand-in: conv weights [c_out, c_in, 5] and biases [c_out] ~ N(0, std^2) (weights rounded
+    to bf16 values when bf16).  Returns (list of weights, list of biases)."""
+    rng = np.random.default_rng(seed)
+    ws, bs = [], []
+    for l in range(n_layers):
+        c_in = n_mel if l == 0 else channels
+        c_out = n_mel if l == n_layers - 1 else channels
+        w = (rng.standard_normal((c_out, c_in, POSTNET["kernel"])) * std).astype(np.float32)
+        b = (rng.standard_normal(c_out) * std).astype(np.float32)
+        ws.append(np.ascontiguousarray(round_to_bf16(w) if bf16 else w))
+        bs.append(np.ascontiguousarray(b))
+    return ws, bs
+
+
 @dataclass
 class Workload:
     """One synthetic job: per-request encoder lengths, step counts and outputs."""

@@ -101,7 +101,8 @@ def _build_variant(src_text: str, workdir: str, name: str):
     so = os.path.join(workdir, name + ".so")
     with open(c, "w") as f:
         f.write(src_text)
-    subprocess.run(["gcc", "-O1", "-std=c99", "-fPIC", "-shared", "-fopenmp", "-w", "-o", so, c, "-lm"], check=True)
+    subprocess.run(["gcc", "-O1", "-std=c99", "-fPIC", "-shared", "-fopenmp", "-w", "-o", so, c, obuild.SRC_POSTNET, "-lm"],
+                   check=True)
     return orc.load(so)
 
 
