@@ -143,6 +143,18 @@ int tts_pool_step_n(tts_pool *pool, int n, int64_t *out_frames);
  */
 int tts_pool_drain_chunk(tts_pool *pool, int64_t id, float *dst, int *out_frames, int *out_finished);
 
+/*
+ * The same hand-out for a consumer on the device (the chunk-level modules that follow the decoder step,
+ * Sec. 2.2.2: each module builds its batch from the pool items that are ready): copy the next chunk of
+ * request `id`, preceded by up to `context` earlier frames of the same request, into DEVICE memory `d_dst`
+ * (room for (context + chunk_frames) * n_mel floats).  *out_context = frames in front of the chunk that were
+ * copied (fewer than `context` only at the start of the utterance), *out_frames = frames of the chunk (0 if
+ * none is ready: nothing is copied), *out_finished as in tts_pool_drain_chunk.  The copy is queued on the
+ * pool's stream; the chunk counts as handed out.
+ */
+int tts_pool_chunk_window(tts_pool *pool, int64_t id, int context, float *d_dst, int *out_context, int *out_frames,
+                          int *out_finished);
+
 /* Stop logits of frames [first, first+count) of request `id` into HOST `dst`; waits for the stream. */
 int tts_pool_get_stop_logits(tts_pool *pool, int64_t id, int first, int count, float *dst);
 

@@ -37,6 +37,9 @@ EXPORTS = (
     "tts_last_error",
     "tts_book_create", "tts_book_add", "tts_book_step", "tts_book_drain", "tts_book_retire",
     "tts_book_destroy",
+    "tts_pool_chunk_window",
+    "tts_postnet_workspace_bytes", "tts_postnet_create", "tts_postnet_run", "tts_postnet_elapsed_ms",
+    "tts_postnet_destroy",
 )
 
 _fp = C.POINTER(C.c_float)
@@ -50,6 +53,17 @@ class TtsConfig(C.Structure):
 
 class TtsWeights(C.Structure):
     _fields_ = [(n, _fp) for n in WEIGHT_FIELDS]
+
+
+class TtsPostnetConfig(C.Structure):
+    _fields_ = [("n_mel", C.c_int), ("channels", C.c_int), ("max_columns", C.c_int), ("weight_dtype", C.c_int)]
+
+
+class TtsPostnetWeights(C.Structure):
+    _fields_ = [("conv_w", C.POINTER(C.c_float) * 5), ("conv_b", C.POINTER(C.c_float) * 5)]
+
+
+POSTNET_CONTEXT = 10      # frames in front of a chunk that can influence it (2 per layer)
 
 
 class TtsError(RuntimeError):
@@ -102,6 +116,15 @@ def lib() -> C.CDLL:
     L.tts_book_retire.argtypes = [vp, C.c_int64]
     L.tts_book_destroy.restype = None
     L.tts_book_destroy.argtypes = [vp]
+    L.tts_pool_chunk_window.argtypes = [vp, C.c_int64, C.c_int, vp, _ip, _ip, _ip]
+    L.tts_postnet_workspace_bytes.restype = C.c_size_t
+    L.tts_postnet_workspace_bytes.argtypes = [C.POINTER(TtsPostnetConfig)]
+    L.tts_postnet_create.argtypes = [C.POINTER(TtsPostnetConfig), C.POINTER(TtsPostnetWeights), vp, C.c_size_t, vp,
+                                     C.POINTER(vp)]
+    L.tts_postnet_run.argtypes = [vp, vp, _ip, _ip, C.c_int, vp]
+    L.tts_postnet_elapsed_ms.argtypes = [vp, _fp]
+    L.tts_postnet_destroy.restype = None
+    L.tts_postnet_destroy.argtypes = [vp]
     _lib = L
     return L
 
@@ -255,6 +278,16 @@ class Pool:
                 break
         return np.concatenate(out, axis=0) if out else np.zeros((0, self.n_mel), np.float32)
 
+    def chunk_window(self, rid: int, context: int, d_dst) -> Tuple[int, int, bool]:
+        """Next chunk of `rid` preceded by up to `context` earlier frames, into the CUDA fp32 tensor d_dst
+        ([>= context + chunk, n_mel]); returns (context frames copied, chunk frames, finished)."""
+        assert d_dst.is_cuda and d_dst.dtype == self._torch.float32 and d_dst.is_contiguous()
+        assert d_dst.numel() >= (context + self.chunk) * self.n_mel
+        c, n, fin = C.c_int(), C.c_int(), C.c_int()
+        _check(lib().tts_pool_chunk_window(self._h, rid, int(context), C.c_void_p(d_dst.data_ptr()), C.byref(c),
+                                           C.byref(n), C.byref(fin)))
+        return c.value, n.value, bool(fin.value)
+
     def close(self) -> None:
         if getattr(self, "_h", None):
             lib().tts_pool_destroy(self._h)
@@ -298,6 +331,85 @@ class Book:
     def close(self):
         if self._h:
             lib().tts_book_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def make_postnet_config(max_columns: int, bf16: bool = False, n_mel: int = 80, channels: int = 512) -> TtsPostnetConfig:
+    return TtsPostnetConfig(n_mel, channels, int(max_columns), DTYPE_BF16 if bf16 else DTYPE_F32)
+
+
+def postnet_workspace_bytes(cfg: TtsPostnetConfig) -> int:
+    return int(lib().tts_postnet_workspace_bytes(C.byref(cfg)))
+
+
+class Postnet:
+    """tts_postnet_* calls; owns its torch arena.  `stream` is a torch.cuda.Stream (e.g. a Pool's)."""
+
+    def __init__(self, cfg: TtsPostnetConfig, conv_w, conv_b, stream=None, device: str = "cuda:0"):
+        import torch
+        if not torch.cuda.is_available():
+            raise RuntimeError("no GPU visible: the PostNet has no CPU path")
+        self._torch = torch
+        self.cfg = cfg
+        self.device = torch.device(device)
+        nbytes = postnet_workspace_bytes(cfg)
+        if nbytes == 0:
+            _check(TTS_E_INVAL)
+        with torch.cuda.device(self.device):
+            self.arena = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+            self.stream = stream if stream is not None else torch.cuda.Stream(device=self.device)
+        self._w = [np.ascontiguousarray(a, np.float32) for a in conv_w]
+        self._b = [np.ascontiguousarray(a, np.float32) for a in conv_b]
+        w = TtsPostnetWeights((_fp * 5)(*[a.ctypes.data_as(_fp) for a in self._w]),
+                              (_fp * 5)(*[a.ctypes.data_as(_fp) for a in self._b]))
+        h = C.c_void_p()
+        with torch.cuda.device(self.device):
+            _check(lib().tts_postnet_create(C.byref(cfg), C.byref(w), C.c_void_p(self.arena.data_ptr()), nbytes,
+                                            C.c_void_p(self.stream.cuda_stream), C.byref(h)))
+        self._h = h
+
+    def run_device(self, d_mel, win_len, keep_from, d_out) -> None:
+        """d_mel / d_out: CUDA fp32 tensors (packed windows in, packed chunks out); queued on the stream."""
+        wl = np.ascontiguousarray(win_len, np.int32)
+        kf = np.ascontiguousarray(keep_from, np.int32)
+        assert d_mel.is_cuda and d_out.is_cuda and d_mel.is_contiguous() and d_out.is_contiguous()
+        assert d_mel.numel() >= int(wl.sum()) * self.cfg.n_mel and d_out.numel() >= int((wl - kf).sum()) * self.cfg.n_mel
+        _check(lib().tts_postnet_run(self._h, C.c_void_p(d_mel.data_ptr()), wl.ctypes.data_as(_ip),
+                                     kf.ctypes.data_as(_ip), int(wl.shape[0]), C.c_void_p(d_out.data_ptr())))
+
+    def run(self, windows, keep_from) -> list:
+        """windows: list of numpy [T_i, n_mel]; returns the post-processed chunks as numpy arrays."""
+        torch = self._torch
+        wl = [int(w.shape[0]) for w in windows]
+        packed = np.ascontiguousarray(np.concatenate(windows, axis=0), np.float32)
+        n_out = sum(t - k for t, k in zip(wl, keep_from))
+        with torch.cuda.stream(self.stream):
+            d_in = torch.from_numpy(packed).to(self.device, non_blocking=False)
+            d_out = torch.empty((n_out, self.cfg.n_mel), dtype=torch.float32, device=self.device)
+        self.stream.synchronize()
+        self.run_device(d_in, wl, keep_from, d_out)
+        self.stream.synchronize()
+        out = d_out.cpu().numpy()
+        res, r = [], 0
+        for t, k in zip(wl, keep_from):
+            res.append(out[r:r + t - k])
+            r += t - k
+        return res
+
+    def elapsed_ms(self) -> float:
+        ms = C.c_float()
+        _check(lib().tts_postnet_elapsed_ms(self._h, C.byref(ms)))
+        return ms.value
+
+    def close(self) -> None:
+        if getattr(self, "_h", None):
+            lib().tts_postnet_destroy(self._h)
             self._h = None
 
     def __del__(self):

@@ -1,0 +1,114 @@
+// Device helpers shared by the step kernels and the PostNet kernels: bf16 <-> fp32, fast sigmoid / tanh,
+// the MFMA fragment geometry and the fragment-order activation layout.  Device code only.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace tts {
+
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+struct bf16_t { uint16_t bits; };
+
+__device__ __forceinline__ float to_float(float x) { return x; }
+__device__ __forceinline__ float to_float(bf16_t x) { return __uint_as_float(((uint32_t)x.bits) << 16); }
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
+
+// round to nearest even; inputs are finite here
+__device__ __forceinline__ uint16_t f2bf_bits(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
+{
+    return (uint32_t)f2bf_bits(lo) | ((uint32_t)f2bf_bits(hi) << 16);
+}
+template <typename T> __device__ __forceinline__ T from_float(float x);
+template <> __device__ __forceinline__ float from_float<float>(float x) { return x; }
+template <> __device__ __forceinline__ bf16_t from_float<bf16_t>(float x) { bf16_t r; r.bits = f2bf_bits(x); return r; }
+
+__device__ __forceinline__ float sigmoidf_(float x) { return __builtin_amdgcn_rcpf(1.0f + __expf(-x)); }
+// 1 - 2/(1+e^{2x}) with the hardware reciprocal (1 ulp): absolute error ~1e-7, saturates cleanly at +-1
+__device__ __forceinline__ float tanhf_(float x) { return 1.0f - 2.0f * __builtin_amdgcn_rcpf(1.0f + __expf(2.0f * x)); }
+
+// (1 - tanh(x)) / 2 = 1 / (1 + e^{2x})
+__device__ __forceinline__ float half_one_minus_tanh(float x)
+{
+    return __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(2.8853900817779268f * x));
+}
+
+__device__ __forceinline__ float wave_sum(float x)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o, 64);
+    return x;
+}
+__device__ __forceinline__ float wave_max(float x)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) x = fmaxf(x, __shfl_xor(x, o, 64));
+    return x;
+}
+
+// 16 bytes of T -> floats (4 for fp32, 8 for bf16)
+template <typename T> struct Vec16;
+template <> struct Vec16<float> {
+    static constexpr int N = 4;
+    __device__ static __forceinline__ void unpack(const uint4& u, float* f)
+    {
+        f[0] = __uint_as_float(u.x); f[1] = __uint_as_float(u.y);
+        f[2] = __uint_as_float(u.z); f[3] = __uint_as_float(u.w);
+    }
+};
+template <> struct Vec16<bf16_t> {
+    static constexpr int N = 8;
+    __device__ static __forceinline__ void unpack(const uint4& u, float* f)
+    {
+        f[0] = bf16_lo(u.x); f[1] = bf16_hi(u.x); f[2] = bf16_lo(u.y); f[3] = bf16_hi(u.y);
+        f[4] = bf16_lo(u.z); f[5] = bf16_hi(u.z); f[6] = bf16_lo(u.w); f[7] = bf16_hi(u.w);
+    }
+};
+
+// Fragment geometry for element type T: a fragment is 64 bytes of k per row / column.
+template <typename T> struct Frag {
+    static constexpr int KB = 64 / (int)sizeof(T);    // k elements per fragment
+    static constexpr int EPL = 16 / (int)sizeof(T);   // k elements per lane
+};
+
+// element offset of (slot, k) in a slot-tiled activation array with NK fragments per tile
+template <typename T>
+__device__ __forceinline__ size_t xoff(int NK, int slot, int k)
+{
+    constexpr int KB = Frag<T>::KB, EPL = Frag<T>::EPL;
+    return ((((size_t)(slot >> 4) * NK + k / KB) * 64) + (slot & 15) + 16 * ((k % KB) / EPL)) * EPL + (k % EPL);
+}
+// uint4 index of fragment `frag` of tile `tile`, lane `lane`
+__device__ __forceinline__ size_t xfrag(int NK, int tile, int frag, int lane)
+{
+    return ((size_t)tile * NK + frag) * 64 + lane;
+}
+
+// D(16x16) += A(16 x 64B of k) * B(64B of k x 16): one fragment each.
+// Lane l of A holds row l%16, bytes [16*(l/16), +16) of that row's 64-byte k chunk;
+// lane l of B the same for column l%16.  A and B use the same k <-> (lane group,
+// element) map, so the contraction is over the whole chunk whatever order the
+// instruction walks it in.  D: lane l holds column l%16, rows 4*(l/16)..+3.
+template <typename T> __device__ __forceinline__ floatx4 mfma_frag(const uint4& a, const uint4& b, floatx4 acc);
+template <> __device__ __forceinline__ floatx4 mfma_frag<bf16_t>(const uint4& a, const uint4& b, floatx4 acc)
+{
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), acc, 0, 0, 0);
+}
+template <> __device__ __forceinline__ floatx4 mfma_frag<float>(const uint4& a, const uint4& b, floatx4 acc)
+{
+    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a.x), __uint_as_float(b.x), acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a.y), __uint_as_float(b.y), acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a.z), __uint_as_float(b.z), acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a.w), __uint_as_float(b.w), acc, 0, 0, 0);
+    return acc;
+}
+
+}  // namespace tts

@@ -1,0 +1,170 @@
+// Host side of the tts_postnet C ABI: argument checks, arena carve-up, weight re-layout, the
+// per-call column tables.  All arithmetic is in postnet.hip.
+#include "../../include/tts_postnet.h"
+
+#include <hip/hip_runtime.h>
+
+#include <new>
+#include <vector>
+
+#include "hostutil.h"
+#include "postnet_kernels.h"
+
+using namespace tts;
+
+namespace {
+
+int check(const tts_postnet_config* c)
+{
+    if (!c) return fail(TTS_E_INVAL, "config is null");
+    if (c->n_mel != PN_N_MEL || c->channels != PN_CHANNELS)
+        return fail(TTS_E_UNSUPPORTED, "kernels are built for %d mel bins and %d channels", PN_N_MEL, PN_CHANNELS);
+    if (c->max_columns < 1 || c->max_columns > (1 << 20)) return fail(TTS_E_INVAL, "max_columns must be in 1..2^20");
+    if (c->weight_dtype != TTS_DTYPE_F32 && c->weight_dtype != TTS_DTYPE_BF16)
+        return fail(TTS_E_INVAL, "weight_dtype must be 0 (fp32) or 1 (bf16)");
+    return TTS_OK;
+}
+
+int c_in_of(int l) { return l == 0 ? PN_N_MEL : PN_CHANNELS; }
+int c_in_padded(int l) { return l == 0 ? PN_CIN0 : PN_CHANNELS; }
+int c_out_of(int l) { return l == PN_LAYERS - 1 ? PN_COUT_LAST : PN_CHANNELS; }
+
+struct PnLayout {
+    size_t W[PN_LAYERS], b[PN_LAYERS], act[2], cmeta, orow, total;
+};
+
+PnLayout layout_of(const tts_postnet_config& c)
+{
+    const size_t ws = c.weight_dtype == TTS_DTYPE_BF16 ? 2 : 4;
+    const size_t cols = (size_t)(c.max_columns + 15) / 16 * 16;
+    Carver a;
+    PnLayout l;
+    for (int i = 0; i < PN_LAYERS; ++i) {
+        l.W[i] = a.take((size_t)c_out_of(i) * PN_TAPS * c_in_padded(i) * ws);
+        l.b[i] = a.take((size_t)c_out_of(i) * 4);
+    }
+    for (int i = 0; i < 2; ++i) l.act[i] = a.take(cols * PN_CHANNELS * ws);
+    l.cmeta = a.take(cols * 4);
+    l.orow = a.take(cols * 4);
+    l.total = a.off;
+    return l;
+}
+
+}  // namespace
+
+struct tts_postnet {
+    tts_postnet_config cfg;
+    PostnetPtrs d;
+    hipStream_t stream = nullptr;
+    hipEvent_t ev0 = nullptr, ev1 = nullptr;
+    bool ev_valid = false;
+    std::vector<int> h_cmeta, h_orow;
+};
+
+extern "C" size_t tts_postnet_workspace_bytes(const tts_postnet_config* cfg)
+{
+    if (check(cfg) != TTS_OK) return 0;
+    return layout_of(*cfg).total;
+}
+
+extern "C" int tts_postnet_create(const tts_postnet_config* cfg, const tts_postnet_weights* w, void* dev_arena,
+                                  size_t arena_bytes, void* hip_stream, tts_postnet** out)
+{
+    if (!out) return fail(TTS_E_INVAL, "out is null");
+    *out = nullptr;
+    int rc = check(cfg);
+    if (rc) return rc;
+    if (!w || !dev_arena) return fail(TTS_E_INVAL, "null argument");
+    for (int l = 0; l < PN_LAYERS; ++l)
+        if (!w->conv_w[l] || !w->conv_b[l]) return fail(TTS_E_INVAL, "weights of layer %d are null", l);
+    const PnLayout lay = layout_of(*cfg);
+    if (arena_bytes < lay.total) return fail(TTS_E_INVAL, "arena has %zu bytes, %zu needed", arena_bytes, lay.total);
+    if ((uintptr_t)dev_arena % 256) return fail(TTS_E_INVAL, "arena must be 256-byte aligned");
+    hipPointerAttribute_t attr;
+    if (hipPointerGetAttributes(&attr, dev_arena) != hipSuccess || attr.type != hipMemoryTypeDevice) {
+        (void)hipGetLastError();
+        return fail(TTS_E_INVAL, "arena is not device memory");
+    }
+    tts_postnet* p = new (std::nothrow) tts_postnet();
+    if (!p) return fail(TTS_E_INVAL, "out of host memory");
+    p->cfg = *cfg;
+    p->stream = (hipStream_t)hip_stream;
+    char* base = (char*)dev_arena;
+    const bool bf = cfg->weight_dtype == TTS_DTYPE_BF16;
+    for (int l = 0; l < PN_LAYERS && rc == TTS_OK; ++l) {
+        const int ci = c_in_of(l), cip = c_in_padded(l), co = c_out_of(l);
+        const float* src = w->conv_w[l];
+        // GEMM row = output channel, k = tap * (padded input channels) + input channel
+        rc = upload(base + lay.W[l], pack_fragments(co, PN_TAPS * cip, bf, [&](int r, int k) {
+                        const int tap = k / cip, c = k - tap * cip;
+                        return c < ci ? src[((size_t)r * ci + c) * PN_TAPS + tap] : 0.f;
+                    }), bf);
+        if (rc == TTS_OK) rc = upload(base + lay.b[l], std::vector<float>(w->conv_b[l], w->conv_b[l] + co), false);
+        p->d.W[l] = base + lay.W[l];
+        p->d.b[l] = (const float*)(base + lay.b[l]);
+    }
+    if (rc == TTS_OK && hipMemset(base + lay.act[0], 0, lay.total - lay.act[0]) != hipSuccess)
+        rc = fail(TTS_E_HIP, "clearing the activation buffers failed");
+    if (rc == TTS_OK && (hipEventCreate(&p->ev0) != hipSuccess || hipEventCreate(&p->ev1) != hipSuccess))
+        rc = fail(TTS_E_HIP, "hipEventCreate failed");
+    if (rc) {
+        tts_postnet_destroy(p);
+        return rc;
+    }
+    p->d.act[0] = base + lay.act[0];
+    p->d.act[1] = base + lay.act[1];
+    p->d.cmeta = (int*)(base + lay.cmeta);
+    p->d.orow = (int*)(base + lay.orow);
+    p->d.n_mel = cfg->n_mel;
+    *out = p;
+    return TTS_OK;
+}
+
+extern "C" int tts_postnet_run(tts_postnet* p, const float* d_mel, const int* win_len, const int* keep_from, int n,
+                               float* d_out)
+{
+    if (!p || !d_mel || !win_len || !keep_from || !d_out) return fail(TTS_E_INVAL, "null argument");
+    if (n < 1) return fail(TTS_E_INVAL, "n = %d windows", n);
+    long long cols = 0;
+    for (int i = 0; i < n; ++i) {
+        if (win_len[i] < 1 || win_len[i] > 0x7FFF) return fail(TTS_E_INVAL, "window %d has %d frames", i, win_len[i]);
+        if (keep_from[i] < 0 || keep_from[i] >= win_len[i])
+            return fail(TTS_E_INVAL, "window %d: keep_from = %d outside [0, %d)", i, keep_from[i], win_len[i]);
+        cols += win_len[i];
+    }
+    if (cols > p->cfg.max_columns) return fail(TTS_E_INVAL, "%lld frames in one call, max_columns = %d", cols, p->cfg.max_columns);
+    const int n_col = (int)cols, n_pad = (n_col + 15) / 16 * 16;
+    // per column: where it sits in its window (for the zero padding) and which output row it becomes
+    p->h_cmeta.assign(n_pad, 0);
+    p->h_orow.assign(n_pad, -1);
+    int c = 0, r = 0;
+    for (int i = 0; i < n; ++i)
+        for (int t = 0; t < win_len[i]; ++t, ++c) {
+            p->h_cmeta[c] = (win_len[i] << 16) | t;
+            if (t >= keep_from[i]) p->h_orow[c] = r++;
+        }
+    HIP_TRY(hipEventRecord(p->ev0, p->stream));
+    HIP_TRY(hipMemcpyAsync(p->d.cmeta, p->h_cmeta.data(), (size_t)n_pad * 4, hipMemcpyHostToDevice, p->stream));
+    HIP_TRY(hipMemcpyAsync(p->d.orow, p->h_orow.data(), (size_t)n_pad * 4, hipMemcpyHostToDevice, p->stream));
+    HIP_TRY(launch_postnet(p->d, p->cfg.weight_dtype, d_mel, n_col, d_out, p->stream));
+    HIP_TRY(hipEventRecord(p->ev1, p->stream));
+    p->ev_valid = true;
+    return TTS_OK;
+}
+
+extern "C" int tts_postnet_elapsed_ms(tts_postnet* p, float* out_ms)
+{
+    if (!p || !out_ms) return fail(TTS_E_INVAL, "null argument");
+    if (!p->ev_valid) return fail(TTS_E_INVAL, "nothing has run yet");
+    HIP_TRY(hipEventSynchronize(p->ev1));
+    HIP_TRY(hipEventElapsedTime(out_ms, p->ev0, p->ev1));
+    return TTS_OK;
+}
+
+extern "C" void tts_postnet_destroy(tts_postnet* p)
+{
+    if (!p) return;
+    if (p->ev0) (void)hipEventDestroy(p->ev0);
+    if (p->ev1) (void)hipEventDestroy(p->ev1);
+    delete p;
+}

@@ -17,6 +17,7 @@
 
 #include "book.h"
 #include "dev.h"
+#include "hostutil.h"
 #include "kernels.h"
 
 using namespace tts;
@@ -24,7 +25,7 @@ using namespace tts;
 // ------------------------------------------------------------------ errors
 static thread_local std::string g_err;
 
-static int fail(int code, const char* fmt, ...)
+int tts::fail(int code, const char* fmt, ...)
 {
     char buf[512];
     va_list ap;
@@ -34,12 +35,6 @@ static int fail(int code, const char* fmt, ...)
     g_err = buf;
     return code;
 }
-
-#define HIP_TRY(expr)                                                                         \
-    do {                                                                                      \
-        hipError_t e_ = (expr);                                                               \
-        if (e_ != hipSuccess) return fail(TTS_E_HIP, "%s: %s", #expr, hipGetErrorString(e_)); \
-    } while (0)
 
 extern "C" const char* tts_last_error(void) { return g_err.c_str(); }
 
@@ -68,16 +63,6 @@ static int check_config(const tts_config* c)
 
 // ------------------------------------------------------------------ arena
 namespace {
-
-struct Carver {
-    size_t off = 0;
-    size_t take(size_t bytes)
-    {
-        size_t o = off;
-        off += (bytes + 255) & ~size_t(255);
-        return o;
-    }
-};
 
 struct Layout {
     size_t Wa, Wd, ba, bd, Wq, Wq_epi, qpart, WmemT, lsa_kfrag, lsa_wfrag, v, Wmel, bmel, Wp1, Wp2;
@@ -136,52 +121,6 @@ Layout make_layout(const tts_config& c)
     l.stage = a.take(ML * ENC * 4);
     l.total = a.off;
     return l;
-}
-
-uint16_t host_f2bf(float f)
-{
-    uint32_t u;
-    memcpy(&u, &f, 4);
-    u += 0x7FFFu + ((u >> 16) & 1u);
-    return (uint16_t)(u >> 16);
-}
-float host_bf2f(uint16_t b)
-{
-    uint32_t u = (uint32_t)b << 16;
-    float f;
-    memcpy(&f, &u, 4);
-    return f;
-}
-// fp32 host values -> device array of the weight dtype
-int upload(void* dst, const std::vector<float>& src, bool bf16)
-{
-    if (!bf16) {
-        HIP_TRY(hipMemcpy(dst, src.data(), src.size() * 4, hipMemcpyHostToDevice));
-    } else {
-        std::vector<uint16_t> h(src.size());
-        for (size_t i = 0; i < src.size(); ++i) h[i] = host_f2bf(src[i]);
-        HIP_TRY(hipMemcpy(dst, h.data(), h.size() * 2, hipMemcpyHostToDevice));
-    }
-    return TTS_OK;
-}
-
-// A [rows][K] matrix given by an element accessor -> MFMA A-operand fragment
-// order: tiles of 16 rows x (64 bytes of k); within a tile lane l holds row
-// l%16, 16 bytes at byte offset 16*(l/16).
-template <typename Get>
-std::vector<float> pack_fragments(int rows, int K, bool bf16, Get get)
-{
-    const int KB = bf16 ? 32 : 16;   // k elements per 64-byte fragment row
-    const int EPL = KB / 4;          // elements per lane
-    const int NK = K / KB;
-    std::vector<float> out((size_t)rows * K);
-    for (int rt = 0; rt < rows / 16; ++rt)
-        for (int ks = 0; ks < NK; ++ks)
-            for (int lane = 0; lane < 64; ++lane)
-                for (int i = 0; i < EPL; ++i)
-                    out[(((size_t)rt * NK + ks) * 64 + lane) * EPL + i] =
-                        get(rt * 16 + (lane & 15), ks * KB + (lane >> 4) * EPL + i);
-    return out;
 }
 
 // Gate matrix [W_ih | W_hh] (rows i,f,g,o blocks of HID): rows re-ordered
@@ -667,6 +606,29 @@ extern "C" int tts_pool_drain_chunk(tts_pool* p, int64_t id, float* dst, int* ou
         HIP_TRY(hipStreamSynchronize(p->stream));
         p->book->drain_commit(slot, count);
     }
+    *out_frames = count;
+    *out_finished = fin;
+    return TTS_OK;
+}
+
+extern "C" int tts_pool_chunk_window(tts_pool* p, int64_t id, int context, float* d_dst, int* out_context,
+                                     int* out_frames, int* out_finished)
+{
+    if (!p || !d_dst || !out_context || !out_frames || !out_finished) return fail(TTS_E_INVAL, "null argument");
+    if (context < 0) return fail(TTS_E_INVAL, "context = %d", context);
+    const int slot = p->book->find(id);
+    if (slot < 0) return fail(TTS_E_NOTFOUND, "no request with id %lld", (long long)id);
+    int rc = refresh_slot(p, slot);
+    if (rc) return rc;
+    int first, count, fin;
+    p->book->drain_plan(slot, &first, &count, &fin);
+    const int ctx = count > 0 ? (first < context ? first : context) : 0;
+    if (count > 0) {
+        const float* src = p->d.mel_ring + ((size_t)slot * p->cfg.max_steps + (first - ctx)) * N_MEL;
+        HIP_TRY(hipMemcpyAsync(d_dst, src, (size_t)(ctx + count) * N_MEL * 4, hipMemcpyDeviceToDevice, p->stream));
+        p->book->drain_commit(slot, count);
+    }
+    *out_context = ctx;
     *out_frames = count;
     *out_finished = fin;
     return TTS_OK;

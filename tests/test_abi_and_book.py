@@ -13,9 +13,12 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def _declared_symbols():
-    text = open(os.path.join(ROOT, "include", "tts_pool.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(tts_(?:pool|book|last)_\w+)\s*\(", text)))
+    names = set()
+    for header in ("tts_pool.h", "tts_postnet.h"):
+        text = open(os.path.join(ROOT, "include", header)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"\b(tts_(?:pool|book|last|postnet)_\w+)\s*\(", text))
+    return sorted(names)
 
 
 def test_library_exports_every_declared_symbol():
@@ -99,3 +102,14 @@ def test_book_errors_and_slot_reuse():
     b.retire(c)                            # retiring an unfinished request is allowed
     assert b.step() == [d]
     assert b.step() == []                  # empty step is a no-op
+
+
+def test_postnet_config_validation_without_gpu():
+    good = binding.make_postnet_config(max_columns=100)
+    assert binding.postnet_workspace_bytes(good) > 5 * 512 * 512 * 4 * 3
+    bf = binding.make_postnet_config(max_columns=100, bf16=True)
+    assert 0 < binding.postnet_workspace_bytes(bf) < binding.postnet_workspace_bytes(good)
+    for field, bad in (("n_mel", 64), ("channels", 256), ("max_columns", 0), ("weight_dtype", 3)):
+        c = binding.make_postnet_config(max_columns=100)
+        setattr(c, field, bad)
+        assert binding.postnet_workspace_bytes(c) == 0, field

@@ -1,0 +1,173 @@
+"""PostNet on the GPU against the CPU oracle (oracle/postnet_oracle.c), through the C ABI."""
+import numpy as np
+import pytest
+
+from paper_2211_13939_amd import binding, synth
+from tests.helpers import TOL_F32, make_pool, say
+
+pytestmark = pytest.mark.gpu
+
+CTX = binding.POSTNET_CONTEXT
+# bf16 PostNet: the input and four layers of activations are rounded to bf16 (2^-9 relative each) and a
+# layer's gain with the synthetic N(0, 0.05^2) weights is about 2.5: the CPU emulation of exactly those
+# rounding points is 3.6e-2 away (max; rms 1e-2) from the exact stack on outputs of rms 2.2 and
+# magnitude up to 8.  The bound is relative to the largest output: 1 %.
+PN_TOL_BF16_REL = 1e-2
+
+
+def _oracle_chunks(W, utterances, cuts):
+    """cuts[i] = chunk boundaries of utterance i; returns the chunk-wise result of every chunk."""
+    from oracle import oracle as orc
+    out = []
+    for mel, cut in zip(utterances, cuts):
+        out.append([orc.postnet_chunk(W, mel[:e], s) for s, e in zip(cut[:-1], cut[1:])])
+    return out
+
+
+def _windows(utterances, cuts, k):
+    """Window of chunk k of every utterance that has one: (frames [s - ctx, e), keep_from)."""
+    wins, keeps, who = [], [], []
+    for i, (mel, cut) in enumerate(zip(utterances, cuts)):
+        if k + 1 < len(cut):
+            s, e = cut[k], cut[k + 1]
+            c = min(CTX, s)
+            wins.append(mel[s - c:e])
+            keeps.append(c)
+            who.append(i)
+    return wins, keeps, who
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+def test_ragged_batch_of_chunks_matches_oracle(bf16):
+    """Utterances of different lengths cut into chunks of 16 (ragged last chunk, a one-frame chunk, a
+    chunk shorter than the context): every chunk, batched with the other utterances' chunks of the
+    same round, equals the oracle's "stack applied to the utterance so far"."""
+    from oracle import oracle as orc
+    ws, bs = synth.make_postnet_weights(bf16=bf16)
+    W = orc.PostnetWeights(ws, bs)
+    rng = np.random.default_rng(21)
+    lens = [1, 5, 16, 17, 40, 53, 33]
+    utter = [rng.standard_normal((n, 80)).astype(np.float32) for n in lens]
+    cuts = [list(range(0, n, 16)) + [n] for n in lens]
+    say(f"case postnet: {len(lens)} utterances of {lens} frames, chunks of 16, {'bf16' if bf16 else 'fp32'}")
+    ref = _oracle_chunks(W, [u.astype(np.float64) for u in utter], cuts)
+    pn = binding.Postnet(binding.make_postnet_config(max_columns=7 * (16 + CTX), bf16=bf16), ws, bs)
+    worst = 0.0
+    for k in range(4):
+        wins, keeps, who = _windows(utter, cuts, k)
+        if not wins:
+            break
+        got = pn.run(wins, keeps)
+        for g, i in zip(got, who):
+            assert g.shape == ref[i][k].shape
+            worst = max(worst, float(np.abs(g - ref[i][k]).max()))
+    scale = max(float(np.abs(c).max()) for r in ref for c in r)
+    say(f"  max abs err {worst:.3e} (largest output {scale:.2f})")
+    assert worst <= (PN_TOL_BF16_REL * scale if bf16 else TOL_F32)
+    pn.close()
+
+
+def test_bf16_rounding_points():
+    """bf16 mode rounds the input mel and every tanh output to bf16 and accumulates in fp32.  The same
+    rounding points applied to the oracle's layers on the CPU must land within a few rounding flips of
+    the GPU (an activation next to a bf16 boundary may fall either way under fp32 accumulation)."""
+    from oracle import oracle as orc
+    ws, bs = synth.make_postnet_weights(bf16=True)
+    mel = np.random.default_rng(21).standard_normal((53, 80)).astype(np.float32)
+    x = synth.round_to_bf16(mel).astype(np.float64)
+    for l in range(5):
+        y = orc.conv5(ws[l], bs[l], x, apply_tanh=(l < 4))
+        x = synth.round_to_bf16(y.astype(np.float32)).astype(np.float64) if l < 4 else y
+    emulated = mel + x
+    exact = orc.postnet(orc.PostnetWeights(ws, bs), mel.astype(np.float64))
+    pn = binding.Postnet(binding.make_postnet_config(max_columns=64, bf16=True), ws, bs)
+    got = pn.run([mel], [0])[0]
+    pn.close()
+    say(f"case postnet bf16 rounding points: gpu vs emulation {np.abs(got - emulated).max():.3e}, "
+        f"emulation vs exact {np.abs(emulated - exact).max():.3e}, gpu vs exact {np.abs(got - exact).max():.3e}")
+    assert np.abs(got - emulated).max() <= 0.25 * np.abs(emulated - exact).max()
+    assert np.abs(got - exact).max() <= PN_TOL_BF16_REL * np.abs(exact).max()
+
+
+def test_window_without_full_context_is_rejected_or_exact_at_start():
+    """A window that starts at frame 0 needs no context: the zeros in front are the utterance's own padding."""
+    from oracle import oracle as orc
+    ws, bs = synth.make_postnet_weights()
+    W = orc.PostnetWeights(ws, bs)
+    mel = np.random.default_rng(4).standard_normal((7, 80)).astype(np.float32)
+    pn = binding.Postnet(binding.make_postnet_config(max_columns=64), ws, bs)
+    got = pn.run([mel], [0])[0]
+    assert np.abs(got - orc.postnet(W, mel.astype(np.float64))).max() <= TOL_F32
+    with pytest.raises(binding.TtsError):
+        pn.run([mel], [7])                      # nothing to keep
+    with pytest.raises(binding.TtsError):
+        pn.run([np.zeros((65, 80), np.float32)], [0])   # more frames than max_columns
+    pn.close()
+
+
+def test_result_does_not_depend_on_batch_composition():
+    """A chunk post-processed alone and in a batch of others: identical bits (every column only sees its own window)."""
+    ws, bs = synth.make_postnet_weights(bf16=True)
+    rng = np.random.default_rng(8)
+    wins = [rng.standard_normal((n, 80)).astype(np.float32) for n in (26, 50, 11, 37, 18)]
+    keeps = [10, 10, 0, 10, 2]
+    pn = binding.Postnet(binding.make_postnet_config(max_columns=256, bf16=True), ws, bs)
+    together = pn.run(wins, keeps)
+    for i in (0, 2, 4):
+        alone = pn.run([wins[i]], [keeps[i]])[0]
+        np.testing.assert_array_equal(alone, together[i])
+    shuffled = pn.run(wins[::-1], keeps[::-1])[::-1]
+    for a, b in zip(together, shuffled):
+        np.testing.assert_array_equal(a, b)
+    pn.close()
+
+
+def test_decoder_chunks_through_postnet_on_device(weights_fp32):
+    """The decoder's chunks handed to the PostNet on the device (tts_pool_chunk_window): three requests,
+    chunks of 8 frames, each round one dynamic batch; equals the oracle decoder followed by the oracle PostNet."""
+    import torch
+    from oracle import oracle as orc
+    wl = synth.small_workload(3, 10, 60, 20, 27, seed=31)
+    chunk = 8
+    pool = make_pool(wl, weights_fp32, chunk_frames=chunk)
+    ws, bs = synth.make_postnet_weights()
+    pn = binding.Postnet(binding.make_postnet_config(max_columns=3 * (chunk + CTX)), ws, bs, stream=pool.stream)
+    W = orc.PostnetWeights(ws, bs)
+    Wd = orc.Weights(weights_fp32)
+    ref_mel, _, frames, _ = orc.pool_decode(wl.dims, Wd, [wl.encoder_outputs(i) for i in range(3)],
+                                            [int(n) for n in wl.n_steps], int(wl.n_steps.max()))
+    ids = [pool.add_request(wl.encoder_outputs(i), int(wl.n_steps[i])) for i in range(3)]
+    done = [0, 0, 0]
+    finished = [False] * 3
+    dev = pool.device
+    d_in = torch.empty((3 * (chunk + CTX), 80), dtype=torch.float32, device=dev)
+    d_out = torch.empty((3 * chunk, 80), dtype=torch.float32, device=dev)
+    worst = 0.0
+    say(f"case decoder -> postnet on device: steps {wl.n_steps.tolist()}, chunks of {chunk}")
+    while not all(finished):
+        pool.step_n(chunk)
+        lens, keeps, who, row = [], [], [], 0
+        for i, rid in enumerate(ids):
+            if finished[i]:
+                continue
+            c, n, fin = pool.chunk_window(rid, CTX, d_in[row:])
+            if n:
+                lens.append(c + n); keeps.append(c); who.append((i, n)); row += c + n
+            finished[i] = fin
+        if not lens:
+            continue
+        pn.run_device(d_in, lens, keeps, d_out)
+        pool.sync()
+        out = d_out.cpu().numpy()
+        r = 0
+        for i, n in who:
+            s = done[i]
+            want = orc.postnet_chunk(W, ref_mel[i, : s + n], s)
+            worst = max(worst, float(np.abs(out[r:r + n] - want).max()))
+            r += n
+            done[i] += n
+    say(f"  max abs err {worst:.3e}")
+    assert done == [int(n) for n in wl.n_steps]
+    assert worst <= 5 * TOL_F32      # decoder error (<= 1e-4) passes through five layers of gain
+    pn.close()
+    pool.close()
