@@ -148,6 +148,35 @@ def stream_run(stream, pool5, w5, enc, arrival, join_every, max_pool):
             "wall_us_per_step": r.busy_s * 1e6 / max(1, r.n_steps)}
 
 
+def postnet_bench(binding, synth, torch):
+    """One round of the chunk-level module that follows the decoder: every request's 40-frame chunk with its 10
+    frames of context through the five-layer PostNet (bf16 weights / activations, fp32 accumulation)."""
+    MFMA_PEAK_TFLOPS = 2500.0
+    macs_per_frame = 80 * 5 * 512 + 3 * 512 * 5 * 512 + 512 * 5 * 80
+    ws, bs = synth.make_postnet_weights(bf16=True)
+    rows = []
+    pn = binding.Postnet(binding.make_postnet_config(max_columns=256 * 50, bf16=True), ws, bs)
+    rng = np.random.default_rng(5)
+    for n_req in (3, 64, 256):
+        lens, keeps = [50] * n_req, [10] * n_req
+        d_in = torch.from_numpy(rng.standard_normal((n_req * 50, 80)).astype(np.float32)).to(pn.device)
+        d_out = torch.empty((n_req * 40, 80), dtype=torch.float32, device=pn.device)
+        torch.cuda.synchronize()
+        for _ in range(5):
+            pn.run_device(d_in, lens, keeps, d_out)
+        times = []
+        for _ in range(20):
+            pn.run_device(d_in, lens, keeps, d_out)
+            times.append(pn.elapsed_ms() * 1e3)
+        us = float(np.median(times))
+        flops = 2.0 * macs_per_frame * n_req * 50
+        rows.append({"requests": n_req, "frames_in": n_req * 50, "frames_out": n_req * 40, "us_per_round": us,
+                     "us_min": float(min(times)), "us_max": float(max(times)), "chunk_frames_per_s": n_req * 40 / (us * 1e-6),
+                     "tflops": flops / (us * 1e-6) / 1e12, "frac_of_bf16_mfma_peak": flops / (us * 1e-6) / 1e12 / MFMA_PEAK_TFLOPS})
+    pn.close()
+    return rows
+
+
 def job_roofline_bytes(wl, s_w, s_m):
     """Algorithmic bytes of the whole shrinking-pool job: the per-step bytes integrated over the
     actual membership (request i is active during steps 0 .. n_i - 1)."""
@@ -177,6 +206,9 @@ def main():
     ap.add_argument("--qps", type=float, default=100.0, help="stream load: requests per second")
     ap.add_argument("--qps-sweep", action="store_true",
                     help="only the stream load, evenly spaced arrivals at 10..100 requests/s (Sec. 3.2.1's pressure test, 10 s each)")
+    ap.add_argument("--postnet", action="store_true",
+                    help="only time the chunk-wise PostNet (bf16): one round of 40-frame chunks with 10 frames of context for "
+                         "3, 64 and 256 requests")
     ap.add_argument("--pool-sweep", action="store_true",
                     help="only time the full-pool step for pools of 1..256 requests (bf16, L ~ U{30..300})")
     ap.add_argument("--profile-only", action="store_true",
@@ -204,6 +236,9 @@ def main():
         return
     if args.pool_sweep:
         print(json.dumps({"pool_sweep": pool_sweep(binding, synth, torch, not args.no_graph)}))
+        return
+    if args.postnet:
+        print(json.dumps({"postnet": postnet_bench(binding, synth, torch)}))
         return
     if args.qps_sweep:
         from paper_2211_13939_amd import stream
