@@ -338,7 +338,7 @@ extern "C" int tts_pool_create(const tts_config* cfg, const tts_weights* w, void
 
     rc = upload_weights(p, w, base, l);
     if (rc == TTS_OK) {
-        // slot counters and the table start defined: nothing active, everything "done"
+        // slot counters and flags start defined: nothing live, no frames produced
         hipError_t e = hipMemset(base + l.L, 0, l.stage - l.L);
         if (e == hipSuccess) e = hipEventCreate(&p->ev0);
         if (e == hipSuccess) e = hipEventCreate(&p->ev1);
