@@ -88,6 +88,54 @@ template <int NL> static int stream(hipStream_t s, const uint4* big, unsigned* o
     return 0;
 }
 
+// ---- 2b. the same exchange inside independent groups of `GS` neighbouring workgroups (each waits for its own
+// group only): data through agent-scope stores, the flag stored with release / loaded with acquire semantics
+template <int GS>
+__global__ __launch_bounds__(512) void k_group_rounds(unsigned* flags, float* buf, int per, int iters, unsigned* fail, float* out)
+{
+    const int tid = threadIdx.x, wg = blockIdx.x, G = gridDim.x;
+    const int g0 = wg / GS * GS;
+    __shared__ int s_ok;
+    float acc = 0.f;
+    for (int it = 0; it < iters; ++it) {
+        float* mine = buf + ((size_t)(it & 1) * G + wg) * per;
+        for (int i = tid; i < per; i += 512) __hip_atomic_store(&mine[i], (float)(it + wg + i), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __syncthreads();
+        if (tid == 0) __hip_atomic_store(&flags[wg], (unsigned)(it + 1), __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+        if (tid < 64) {
+            int ok = 0;
+            for (int spin = 0; spin < (1 << 18); ++spin) {          // bounded
+                bool all = true;
+                if (tid < GS) all = __hip_atomic_load(&flags[g0 + tid], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) >= (unsigned)(it + 1);
+                if (__all(all)) { ok = 1; break; }
+            }
+            if (tid == 0) { s_ok = ok; if (!ok) *fail = 1; }
+        }
+        __syncthreads();
+        if (!s_ok) return;
+        const int peer = g0 + (wg - g0 + 1) % GS;
+        const float* other = buf + ((size_t)(it & 1) * G + peer) * per;
+        for (int i = tid; i < per; i += 512) acc += __hip_atomic_load(&other[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - (float)(it + peer + i);
+    }
+    if (acc != 0.f) out[0] = acc;
+}
+
+template <int GS> static int group_rounds(hipStream_t s, unsigned* flags, float* buf, unsigned* fail, float* out, int grid, int per)
+{
+    const int iters = 2000;
+    hipEvent_t e0, e1; CK(hipEventCreate(&e0)); CK(hipEventCreate(&e1));
+    CK(hipMemsetAsync(flags, 0, 4096, s)); CK(hipMemsetAsync(fail, 0, 4, s)); CK(hipMemsetAsync(out, 0, 4, s));
+    CK(hipEventRecord(e0, s));
+    hipLaunchKernelGGL(k_group_rounds<GS>, dim3(grid), dim3(512), 0, s, flags, buf, per, iters, fail, out);
+    CK(hipEventRecord(e1, s)); CK(hipEventSynchronize(e1));
+    float ms; CK(hipEventElapsedTime(&ms, e0, e1));
+    unsigned hf; float ho; CK(hipMemcpy(&hf, fail, 4, hipMemcpyDeviceToHost)); CK(hipMemcpy(&ho, out, 4, hipMemcpyDeviceToHost));
+    printf("  groups of %d among %3d workgroups, %5d B each, release/acquire flags: %6.2f us per round%s%s\n", GS, grid, per * 4,
+           ms * 1e3 / iters, hf ? "  TIMED OUT" : "", ho != 0.f ? "  STALE DATA READ" : "");
+    fflush(stdout);
+    return hf ? 1 : 0;
+}
+
 template <int MODE> static int rounds(hipStream_t s, unsigned* flags, float* buf, unsigned* fail, float* out, int grid, int per, const char* name)
 {
     const int iters = 2000;
@@ -143,6 +191,11 @@ int main()
         if (rounds<0>(s, flags, buf, fail, out, grid, 0, "flags only")) return 2;
         if (rounds<1>(s, flags, buf, fail, out, grid, 512, "data, release/acquire fences")) return 2;
         if (rounds<2>(s, flags, buf, fail, out, grid, 512, "data through coherent stores/loads")) return 2;
+    }
+
+    for (int grid : {4, 64, 256}) {
+        if (group_rounds<4>(s, flags, buf, fail, out, grid, 300)) return 2;
+        if (group_rounds<2>(s, flags, buf, fail, out, grid, 300)) return 2;
     }
 
     printf("3. streaming reads, all loads of a workgroup in flight at once (time includes the launch; slope = sustained rate)\n");
