@@ -58,7 +58,6 @@ struct tts_postnet {
     hipStream_t stream = nullptr;
     hipEvent_t ev0 = nullptr, ev1 = nullptr;
     bool ev_valid = false;
-    std::vector<int> h_cmeta, h_orow;
 };
 
 extern "C" size_t tts_postnet_workspace_bytes(const tts_postnet_config* cfg)
@@ -134,18 +133,24 @@ extern "C" int tts_postnet_run(tts_postnet* p, const float* d_mel, const int* wi
     }
     if (cols > p->cfg.max_columns) return fail(TTS_E_INVAL, "%lld frames in one call, max_columns = %d", cols, p->cfg.max_columns);
     const int n_col = (int)cols, n_pad = (n_col + 15) / 16 * 16;
-    // per column: where it sits in its window (for the zero padding) and which output row it becomes
-    p->h_cmeta.assign(n_pad, 0);
-    p->h_orow.assign(n_pad, -1);
-    int c = 0, r = 0;
-    for (int i = 0; i < n; ++i)
-        for (int t = 0; t < win_len[i]; ++t, ++c) {
-            p->h_cmeta[c] = (win_len[i] << 16) | t;
-            if (t >= keep_from[i]) p->h_orow[c] = r++;
-        }
+    // the window list travels as kernel arguments, 256 windows at a time; the device expands it into the
+    // per-column tables (position inside the window for the zero padding, output row of the column)
     HIP_TRY(hipEventRecord(p->ev0, p->stream));
-    HIP_TRY(hipMemcpyAsync(p->d.cmeta, p->h_cmeta.data(), (size_t)n_pad * 4, hipMemcpyHostToDevice, p->stream));
-    HIP_TRY(hipMemcpyAsync(p->d.orow, p->h_orow.data(), (size_t)n_pad * 4, hipMemcpyHostToDevice, p->stream));
+    int c = 0, r = 0;
+    for (int i0 = 0; i0 < n; i0 += PN_META_WINDOWS) {
+        PnWindows w;
+        w.n = n - i0 < PN_META_WINDOWS ? n - i0 : PN_META_WINDOWS;
+        for (int k = 0; k < w.n; ++k) {
+            const int i = i0 + k;
+            w.col0[k] = c;
+            w.row0[k] = r;
+            w.len[k] = (uint16_t)win_len[i];
+            w.keep[k] = (uint16_t)keep_from[i];
+            c += win_len[i];
+            r += win_len[i] - keep_from[i];
+        }
+        HIP_TRY(launch_postnet_meta(p->d, w, n_col, n_pad, i0 == 0, p->stream));
+    }
     HIP_TRY(launch_postnet(p->d, p->cfg.weight_dtype, d_mel, n_col, d_out, p->stream));
     HIP_TRY(hipEventRecord(p->ev1, p->stream));
     p->ev_valid = true;

@@ -24,6 +24,32 @@ constexpr int PN_HALO = PN_TAPS / 2;             // columns needed on either sid
 // column tiles per workgroup: what fits 64 KB of LDS next to the reduction buffer
 template <typename XT> struct PnCT { static constexpr int value = sizeof(XT) == 2 ? 2 : 1; };
 
+// Per-column tables from the call's window list: one workgroup per window; the first launch of a call
+// also marks the columns that pad the last tile.
+__global__ __launch_bounds__(64) void k_pn_meta(PnWindows w, int n_col, int n_col_pad, int clear_pad, int* __restrict__ cmeta,
+                                                int* __restrict__ orow)
+{
+    const int i = blockIdx.x;
+    if (i < w.n) {
+        const int T = w.len[i], keep = w.keep[i];
+        for (int t = threadIdx.x; t < T; t += 64) {
+            cmeta[w.col0[i] + t] = (T << 16) | t;
+            orow[w.col0[i] + t] = t >= keep ? w.row0[i] + (t - keep) : -1;
+        }
+    }
+    if (clear_pad && i == 0)
+        for (int c = n_col + threadIdx.x; c < n_col_pad; c += 64) {
+            cmeta[c] = 0;
+            orow[c] = -1;
+        }
+}
+
+hipError_t launch_postnet_meta(const PostnetPtrs& d, const PnWindows& w, int n_col, int n_col_pad, bool first, hipStream_t s)
+{
+    hipLaunchKernelGGL(k_pn_meta, dim3(w.n > 0 ? w.n : 1), dim3(64), 0, s, w, n_col, n_col_pad, first ? 1 : 0, d.cmeta, d.orow);
+    return hipGetLastError();
+}
+
 // mel fp32 [n_col][n_mel] -> layer-1 input in fragment order, channels zero-padded to CIN
 template <typename XT, int CIN>
 __global__ __launch_bounds__(256) void k_pn_pack(const float* __restrict__ mel, int n_mel, int n_col, int n_col_pad, XT* __restrict__ X)

@@ -21,6 +21,19 @@ struct PostnetPtrs {
     int n_mel;
 };
 
+// Up to PN_META_WINDOWS windows of one call, as a kernel argument (no host-to-device copy): the device
+// expands it into the per-column tables.
+constexpr int PN_META_WINDOWS = 256;
+struct PnWindows {
+    int n;
+    int col0[PN_META_WINDOWS];        // first column of the window
+    int row0[PN_META_WINDOWS];        // output row of the window's first kept frame
+    uint16_t len[PN_META_WINDOWS];    // frames in the window
+    uint16_t keep[PN_META_WINDOWS];   // frames of context in front of the chunk
+};
+// n_col_pad: columns rounded up to whole tiles; `first` clears the padding columns too
+hipError_t launch_postnet_meta(const PostnetPtrs& d, const PnWindows& w, int n_col, int n_col_pad, bool first, hipStream_t s);
+
 // mel: device fp32 [n_col][n_mel]; out: device fp32 [kept rows][n_mel]
 hipError_t launch_postnet(const PostnetPtrs& d, int wdtype, const float* mel, int n_col, float* out, hipStream_t s);
 
