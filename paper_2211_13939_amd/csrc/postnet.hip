@@ -162,27 +162,148 @@ __global__ __launch_bounds__(PN_THREADS) void k_pn_conv(
     }
 }
 
+// The same layer for large batches.  The kernel above spreads a small batch over many workgroups (one
+// row tile each, K split over the waves) but pulls 80 KB of weights per 160 MFMAs; here a workgroup owns
+// 8 row tiles (one per wave, no K split, no reduction) and PN_WCT column tiles, whose staged columns in LDS
+// serve all eight waves: 8 x 80 KB of weights for 8 x 80 x PN_WCT MFMAs.
+constexpr int PN_WCT = 4;
+template <typename XT, int CIN, int COUT, bool LAST>
+__global__ __launch_bounds__(PN_THREADS) void k_pn_conv_wide(
+    const uint4* __restrict__ Wfrag, const float* __restrict__ bias, const uint4* __restrict__ Xin, XT* __restrict__ Xout,
+    const int* __restrict__ cmeta, int n_ctiles, const float* __restrict__ mel, int n_mel, const int* __restrict__ orow,
+    float* __restrict__ out)
+{
+    constexpr int KB = Frag<XT>::KB, EPL = Frag<XT>::EPL;
+    constexpr int NKF = CIN / KB, NKT = PN_TAPS * NKF;
+    constexpr int ROWS = PN_WCT * 16 + 2 * PN_HALO;
+    constexpr int LD = CIN * (int)sizeof(XT) + 16;
+    constexpr int NRT = COUT / 16;
+    extern __shared__ __attribute__((aligned(16))) unsigned char s_dyn[];   // ROWS * LD bytes
+    unsigned char* s_x = s_dyn;
+
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int jl = lane & 15, g = lane >> 4;
+    const int rt = blockIdx.x * PN_WAVES + wave;           // this wave's row tile (may lie beyond the last one)
+    const bool row_on = rt < NRT;
+    const int rtc = row_on ? rt : NRT - 1;
+    const int ct0 = blockIdx.y * PN_WCT;
+    const int n_col_pad = n_ctiles * 16;
+    const int col_first = ct0 * 16 - PN_HALO;
+
+    for (int p = tid; p < ROWS * NKF * 4; p += PN_THREADS) {
+        const int row = p / (NKF * 4), rem = p - row * (NKF * 4);
+        const int cf = rem >> 2, gg = rem & 3;
+        const int col = col_first + row;
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (col >= 0 && col < n_col_pad) v = Xin[xfrag(NKF, col >> 4, cf, (col & 15) + 16 * gg)];
+        *reinterpret_cast<uint4*>(&s_x[row * LD + (cf * KB + gg * EPL) * (int)sizeof(XT)]) = v;
+    }
+    int tapmask[PN_WCT];
+#pragma unroll
+    for (int c = 0; c < PN_WCT; ++c) {
+        const int col = min((ct0 + c) * 16 + jl, n_col_pad - 1);
+        const int m = cmeta[col];
+        const int t = m & 0xFFFF, T = m >> 16;
+        int bits = 0;
+#pragma unroll
+        for (int d = -PN_HALO; d <= PN_HALO; ++d) bits |= (t + d >= 0 && t + d < T) ? (1 << (d + PN_HALO)) : 0;
+        tapmask[c] = bits;
+    }
+    const floatx4 bias4 = *reinterpret_cast<const floatx4*>(bias + rtc * 16 + 4 * g);
+    __syncthreads();
+
+    floatx4 acc[PN_WCT];
+#pragma unroll
+    for (int c = 0; c < PN_WCT; ++c) acc[c] = floatx4{0.f, 0.f, 0.f, 0.f};
+    // weights of the wave's row tile stream through registers, PF fragments ahead
+    constexpr int PF = 16;
+    uint4 a[PF];
+#pragma unroll
+    for (int i = 0; i < PF; ++i) a[i] = Wfrag[xfrag(NKT, rtc, i < NKT ? i : NKT - 1, lane)];
+#pragma unroll 1
+    for (int f0 = 0; f0 < NKT; f0 += PF) {
+#pragma unroll
+        for (int i = 0; i < PF; ++i) {
+            const int f = f0 + i;
+            const uint4 af = a[i];
+            a[i] = Wfrag[xfrag(NKT, rtc, min(f + PF, NKT - 1), lane)];   // unconditional: past the end it re-reads the last one
+            if (f < NKT) {
+                const int tap = f / NKF, cf = f - tap * NKF;
+#pragma unroll
+                for (int c = 0; c < PN_WCT; ++c) {
+                    uint4 b = *reinterpret_cast<const uint4*>(&s_x[(c * 16 + jl + tap) * LD + (cf * KB + g * EPL) * (int)sizeof(XT)]);
+                    if (!((tapmask[c] >> tap) & 1)) b = make_uint4(0, 0, 0, 0);
+                    acc[c] = mfma_frag<XT>(af, b, acc[c]);
+                }
+            }
+        }
+    }
+    if (!row_on) return;
+#pragma unroll
+    for (int c = 0; c < PN_WCT; ++c) {
+        if (ct0 + c >= n_ctiles) break;
+        const floatx4 y = acc[c] + bias4;
+        const int col = (ct0 + c) * 16 + jl;
+        const int ch = rt * 16 + 4 * g;
+        if constexpr (!LAST) {
+            const float y0 = tanhf_(y[0]), y1 = tanhf_(y[1]), y2 = tanhf_(y[2]), y3 = tanhf_(y[3]);
+            XT* dst = Xout + xoff<XT>(COUT / KB, col, ch);
+            if constexpr (sizeof(XT) == 2) *reinterpret_cast<uint2*>(dst) = make_uint2(pack_bf16x2(y0, y1), pack_bf16x2(y2, y3));
+            else *reinterpret_cast<float4*>(dst) = make_float4(y0, y1, y2, y3);
+        } else {
+            const int r = orow[col];
+            if (r >= 0 && ch < n_mel) {
+                const float4 m = *reinterpret_cast<const float4*>(mel + (size_t)col * n_mel + ch);
+                *reinterpret_cast<float4*>(out + (size_t)r * n_mel + ch) = make_float4(m.x + y[0], m.y + y[1], m.z + y[2], m.w + y[3]);
+            }
+        }
+    }
+}
+
+template <typename XT, int CIN, int COUT, bool LAST>
+static hipError_t conv_layer(bool wide, const void* W, const float* b, const void* xin, XT* xout, const int* cmeta, int n_ctiles,
+                             const float* mel, int n_mel, const int* orow, float* out, hipStream_t s)
+{
+    if (wide) {
+        constexpr int LDS = (PN_WCT * 16 + 2 * PN_HALO) * (CIN * (int)sizeof(XT) + 16);
+        auto kern = k_pn_conv_wide<XT, CIN, COUT, LAST>;
+        static bool attr_set = false;             // dynamic LDS above 64 KB has to be allowed once per kernel
+        if (!attr_set) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+            if (e != hipSuccess) return e;
+            attr_set = true;
+        }
+        const dim3 grid((COUT / 16 + PN_WAVES - 1) / PN_WAVES, (n_ctiles + PN_WCT - 1) / PN_WCT);
+        hipLaunchKernelGGL(kern, grid, dim3(PN_THREADS), LDS, s, (const uint4*)W, b, (const uint4*)xin, xout, cmeta, n_ctiles,
+                           mel, n_mel, orow, out);
+    } else {
+        constexpr int CT = PnCT<XT>::value;
+        const dim3 grid(COUT / 16, (n_ctiles + CT - 1) / CT);
+        hipLaunchKernelGGL((k_pn_conv<XT, CIN, COUT, LAST>), grid, dim3(PN_THREADS), 0, s, (const uint4*)W, b, (const uint4*)xin,
+                           xout, cmeta, n_ctiles, mel, n_mel, orow, out);
+    }
+    return hipGetLastError();
+}
+
+// batches of at least this many column tiles take the wide kernel
+constexpr int PN_WIDE_FROM = 24;
+
 template <typename XT>
 static hipError_t run_typed(const PostnetPtrs& d, const float* mel, int n_col, int n_ctiles, float* out, hipStream_t s)
 {
     constexpr int C1 = PN_CIN0, C = PN_CHANNELS, CO = PN_COUT_LAST;
-    constexpr int PN_CT = PnCT<XT>::value;
     const int n_col_pad = n_ctiles * 16;
+    const bool wide = n_ctiles >= PN_WIDE_FROM;
     XT* x0 = reinterpret_cast<XT*>(d.act[0]);
     XT* x1 = reinterpret_cast<XT*>(d.act[1]);
-    const dim3 gw(C / 16, (n_ctiles + PN_CT - 1) / PN_CT), gl(CO / 16, (n_ctiles + PN_CT - 1) / PN_CT);
     hipLaunchKernelGGL((k_pn_pack<XT, C1>), dim3((n_col_pad * C1 + 255) / 256), dim3(256), 0, s, mel, d.n_mel, n_col, n_col_pad, x0);
-    hipLaunchKernelGGL((k_pn_conv<XT, C1, C, false>), gw, dim3(PN_THREADS), 0, s, (const uint4*)d.W[0], d.b[0],
-                       (const uint4*)x0, x1, d.cmeta, n_ctiles, nullptr, 0, nullptr, nullptr);
-    hipLaunchKernelGGL((k_pn_conv<XT, C, C, false>), gw, dim3(PN_THREADS), 0, s, (const uint4*)d.W[1], d.b[1],
-                       (const uint4*)x1, x0, d.cmeta, n_ctiles, nullptr, 0, nullptr, nullptr);
-    hipLaunchKernelGGL((k_pn_conv<XT, C, C, false>), gw, dim3(PN_THREADS), 0, s, (const uint4*)d.W[2], d.b[2],
-                       (const uint4*)x0, x1, d.cmeta, n_ctiles, nullptr, 0, nullptr, nullptr);
-    hipLaunchKernelGGL((k_pn_conv<XT, C, C, false>), gw, dim3(PN_THREADS), 0, s, (const uint4*)d.W[3], d.b[3],
-                       (const uint4*)x1, x0, d.cmeta, n_ctiles, nullptr, 0, nullptr, nullptr);
-    hipLaunchKernelGGL((k_pn_conv<XT, C, CO, true>), gl, dim3(PN_THREADS), 0, s, (const uint4*)d.W[4], d.b[4],
-                       (const uint4*)x0, (XT*)nullptr, d.cmeta, n_ctiles, mel, d.n_mel, d.orow, out);
-    return hipGetLastError();
+    hipError_t e = hipGetLastError();
+    if (e == hipSuccess) e = conv_layer<XT, C1, C, false>(wide, d.W[0], d.b[0], x0, x1, d.cmeta, n_ctiles, nullptr, 0, nullptr, nullptr, s);
+    if (e == hipSuccess) e = conv_layer<XT, C, C, false>(wide, d.W[1], d.b[1], x1, x0, d.cmeta, n_ctiles, nullptr, 0, nullptr, nullptr, s);
+    if (e == hipSuccess) e = conv_layer<XT, C, C, false>(wide, d.W[2], d.b[2], x0, x1, d.cmeta, n_ctiles, nullptr, 0, nullptr, nullptr, s);
+    if (e == hipSuccess) e = conv_layer<XT, C, C, false>(wide, d.W[3], d.b[3], x1, x0, d.cmeta, n_ctiles, nullptr, 0, nullptr, nullptr, s);
+    if (e == hipSuccess) e = conv_layer<XT, C, CO, true>(wide, d.W[4], d.b[4], x0, (XT*)nullptr, d.cmeta, n_ctiles, mel, d.n_mel, d.orow, out, s);
+    return e;
 }
 
 hipError_t launch_postnet(const PostnetPtrs& d, int wdtype, const float* mel, int n_col, float* out, hipStream_t s)
