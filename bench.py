@@ -243,7 +243,7 @@ def main():
     if args.qps_sweep:
         from paper_2211_13939_amd import stream
         w5 = synth.workload("c5")
-        cfg5 = binding.make_config(w5.dims, max_pool=32, max_enc_len=int(w5.enc_len.max()),
+        cfg5 = binding.make_config(w5.dims, max_pool=16, max_enc_len=int(w5.enc_len.max()),
                                    max_steps=int(w5.n_steps.max()), chunk_frames=w5.chunk_frames, bf16=True,
                                    use_graph=not args.no_graph)
         pool5 = binding.Pool(cfg5, synth.make_weights(bf16=True))
@@ -252,7 +252,7 @@ def main():
         torch.cuda.synchronize()
         rows = []
         for qps in range(10, 101, 10):
-            r = stream_run(stream, pool5, w5, enc, stream_arrivals(w5, "even", float(qps), n_req), 1, 32)
+            r = stream_run(stream, pool5, w5, enc, stream_arrivals(w5, "even", float(qps), n_req), 1, 16)
             rows.append({"qps": qps, **{k: r[k] for k in ("p50_ms", "p95_ms", "last_chunk_p50_ms", "rtf_p50", "mean_pool",
                                                           "max_pool_seen", "busy_s")}})
         pool5.close()
@@ -370,9 +370,9 @@ def main():
     if not args.no_stream:
         from paper_2211_13939_amd import stream
         w5 = synth.workload("c5")
-        # the offered load (100 requests/s x ~660 frames) keeps about 3 requests in the pool: a
-        # capacity of 32 is ample (arrivals beyond it would wait for a free slot)
-        cfg5 = binding.make_config(w5.dims, max_pool=32, max_enc_len=int(w5.enc_len.max()),
+        # the offered load (100 requests/s x ~660 frames) keeps about 3 requests in the pool (12 at most
+        # in this trace): a capacity of 16 is ample (arrivals beyond it would wait for a free slot)
+        cfg5 = binding.make_config(w5.dims, max_pool=16, max_enc_len=int(w5.enc_len.max()),
                                    max_steps=int(w5.n_steps.max()), chunk_frames=w5.chunk_frames, bf16=True,
                                    use_graph=not args.no_graph)
         pool.close()
@@ -386,7 +386,7 @@ def main():
         res = {}
         for name, je, enc in (("per_step_join", 1, enc5_dev), ("per_chunk_join", w5.chunk_frames, enc5_dev),
                               ("per_step_join_host_input", 1, enc5_host)):
-            res[name] = stream_run(stream, pool5, w5, enc, arrival, je, 32)
+            res[name] = stream_run(stream, pool5, w5, enc, arrival, je, 16)
         out["stream"] = {"workload": f"c5: {args.arrivals} arrivals at {args.qps:g}/s, {w5.n_requests} requests, L~U{{30..300}}, "
                                      "frames=4L, 40-frame chunks; encoder outputs resident in HBM "
                                      "(per_step_join_host_input: handed over from pageable host memory, PCIe copy "

@@ -11,8 +11,8 @@ struct StepLaunch {
     int n_blocks;   // the attention grid covers slots 0 .. n_blocks - 1 (all active slots lie below)
     int n_tiles;    // the projection grid covers 16-slot tiles 0 .. n_tiles - 1
     int lsa_split;  // workgroups per request in the attention kernel (1, 2 or 4; they split the context columns)
-    int wide_lstm;  // non-zero: LSTM workgroups own two row tiles and half of the pool tiles (pools of many tiles)
-    int q_partials; // non-zero: the attention LSTM hands the query over as partial products (pools of <= 32 slots)
+    int lstm_rows;  // row tiles per LSTM workgroup: 1 (all pool tiles each), 2 or 4 (1/2 or 1/4 of the pool tiles each)
+    int q_partials; // non-zero: the attention LSTM hands the query over as partial products (pools of <= 16 slots)
 };
 
 // One decoder step (paper Eq. 2) for every request whose slot is flagged in d.live.

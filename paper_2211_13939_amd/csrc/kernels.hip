@@ -33,7 +33,7 @@ namespace tts {
 // The attention kernel then adds up a request's 256 partials (128 KB) instead
 // of pulling all of W_q (256 KB in bf16, 512 KB in fp32) through its CU, which
 // bounds its prologue.  The partials cost this kernel 128 KB of stores per
-// request, so the scheme is used by pools of at most 32 slots only (where a
+// request, so the scheme is used by pools of at most 16 slots only (where a
 // step is latency-bound); larger pools compute q in the attention kernel.
 // qpart[slot][row tile][a].
 // ---------------------------------------------------------------------------
@@ -140,16 +140,15 @@ __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm(
     }
 }
 
-// Variant for pools of more than two tiles: a workgroup owns TWO row tiles
-// (8 hidden units) and half of the pool tiles, grid = 128 row pairs x 2 pool
-// halves.  Every workgroup then pulls 2/16 of the weights' rows and half of the
-// activations through its CU instead of 1/16 and all of them, which is what
-// bounds the kernel once the pool is large (the activations come from L2, and
-// a CU's L2 port, not HBM, is the bottleneck).  The two workgroups that share
-// a row pair sit on the same XCD (blockIdx differs by 128), so the second
-// read of the weights hits that XCD's L2.
-template <typename XT, int K>
-__global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm2(
+// Variants for pools of many tiles: a workgroup owns R row tiles (4 R hidden units) and 1/R of the pool
+// tiles, grid = (256 / R) row groups x R pool groups = 256 workgroups.  What bounds the kernel once the
+// pool is large is the bytes that pass through one CU (the activations come from L2, and a CU's load path,
+// not HBM, is the bottleneck): per workgroup R row tiles of weights + (tiles / R) tiles of activations,
+// against 1 + tiles for the one-row-tile kernel.  R = 2 is the minimum at 4 tiles, R = 4 at 16.  The
+// workgroups that share rows sit on the same XCD (their blockIdx differ by a multiple of 64), so the
+// repeated reads of the weights hit that XCD's L2.  The sums are taken in the same order as in k_lstm.
+template <typename XT, int K, int R>
+__global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm_rc(
     const uint4* __restrict__ Wfrag, const float* __restrict__ bias, const uint4* __restrict__ X,
     float* __restrict__ c_state, XT* __restrict__ hout0, int nk0, int off0,
     XT* __restrict__ hout1, int nk1, int off1,
@@ -158,29 +157,31 @@ __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm2(
     constexpr int NW = LSTM_WAVES;
     constexpr int NK = K / Frag<XT>::KB;
     constexpr int NF = NK / NW;
-    constexpr int TP = sizeof(XT) == 2 ? 2 : 1;    // pool tiles per round
+    constexpr int TP = 4 / R;                      // pool tiles per round: R x TP = 4 cell-update waves
+    constexpr int NRG = HID / 4 / R;               // row groups
+    static_assert(R == 2 || R == 4, "two or four row tiles per workgroup");
 
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int rg = blockIdx.x & 127, cg = blockIdx.x >> 7;
+    const int rg = blockIdx.x % NRG, cg = blockIdx.x / NRG;
 
-    __shared__ floatx4 red[NW][2 * TP][64];
-    uint4 a[2][NF];
+    __shared__ floatx4 red[NW][4][64];
+    uint4 a[R][NF];
 #pragma unroll
-    for (int r = 0; r < 2; ++r)
+    for (int r = 0; r < R; ++r)
 #pragma unroll
-        for (int f = 0; f < NF; ++f) a[r][f] = Wfrag[xfrag(NK, 2 * rg + r, wave + f * NW, lane)];
-    const int half = (n_tiles + 1) >> 1;
-    const int c0 = cg == 0 ? 0 : half, c1 = cg == 0 ? half : n_tiles;
+        for (int f = 0; f < NF; ++f) a[r][f] = Wfrag[xfrag(NK, R * rg + r, wave + f * NW, lane)];
+    const int per = (n_tiles + R - 1) / R;
+    const int c0 = min(cg * per, n_tiles), c1 = min(c0 + per, n_tiles);
 
-    // waves 0 .. 2 TP - 1 also own a cell update: (pool tile of the round = wave / 2, row tile = wave % 2)
-    const int er = wave & 1, et = wave >> 1;
-    const int unit = (2 * rg + er) * 4 + (lane >> 4);
+    // waves 0 .. 3 also own a cell update: (pool tile of the round = wave / R, row tile = wave % R)
+    const int er = wave % R, et = (wave / R) % TP;
+    const int unit = (R * rg + er) * 4 + (lane >> 4);
     floatx4 bias4 = {0.f, 0.f, 0.f, 0.f};
-    if (wave < 2 * TP) bias4 = *reinterpret_cast<const floatx4*>(bias + unit * 4);
+    if (wave < 4) bias4 = *reinterpret_cast<const floatx4*>(bias + unit * 4);
 
     for (int tp = c0; tp < c1; tp += TP) {
         // cell update inputs: independent, unconditional loads (see k_lstm)
-        const int sl = min(tp + (et & (TP - 1)), c1 - 1) * 16 + (lane & 15);
+        const int sl = min(tp + et, c1 - 1) * 16 + (lane & 15);
         const int lv = live[sl], dn = done[sl];
         const float c_old = c_state[(size_t)sl * HID + unit];
         __builtin_amdgcn_sched_barrier(0);
@@ -197,16 +198,16 @@ __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm2(
         for (int t = 0; t < TP; ++t) {
             if (tp + t < c1) {
 #pragma unroll
-                for (int r = 0; r < 2; ++r) {
+                for (int r = 0; r < R; ++r) {
                     floatx4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                     for (int f = 0; f < NF; ++f) acc = mfma_frag<XT>(a[r][f], b[t][f], acc);
-                    red[wave][2 * t + r][lane] = acc;
+                    red[wave][R * t + r][lane] = acc;
                 }
             }
         }
         __syncthreads();
-        const int slotE = (wave < 2 * TP && tp + et < c1 && lv && !dn) ? sl : -1;
+        const int slotE = (wave < 4 && tp + et < c1 && lv && !dn) ? sl : -1;
         if (slotE >= 0) {
             floatx4 g = bias4;
 #pragma unroll
@@ -230,7 +231,7 @@ __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm2(
 //   e_j = v . tanh(q + W_loc loc[j] + PM[j])
 //   w = softmax_{j<L}(e);  A = sum_j w_j F[j];  W_last <- w;  W_acc <- W_acc + w
 // The contractions run on MFMA with 16 positions (or, for q, 16 copies of h_att)
-// as the columns (pools of at most 32 slots get q as partial sums from the
+// as the columns (pools of at most 16 slots get q as partial sums from the
 // attention LSTM's epilogue instead):
 //   q      (128 x 16, K split over the waves) = W_q * h_att
 //   loc^T  (32 x 16)          = Kc (32 x 64 taps) * U^T (64 taps x 16 positions)
@@ -965,7 +966,7 @@ __global__ __launch_bounds__(256) void k_x_set(XT* X, int NK, int slot, int off,
 // launch wrappers
 // ---------------------------------------------------------------------------
 template <typename XT, typename MT>
-static hipError_t step_typed(const DevPtrs& d, int n_req, int n_tiles, int lsa_split, bool wide, bool qpart, int cur, hipStream_t s, hipEvent_t* ev)
+static hipError_t step_typed(const DevPtrs& d, int n_req, int n_tiles, int lsa_split, int rows, bool qpart, int cur, hipStream_t s, hipEvent_t* ev)
 {
     constexpr int KB = Frag<XT>::KB;
     auto mark = [&](int i) { if (ev) (void)hipEventRecord(ev[i], s); };
@@ -975,20 +976,19 @@ static hipError_t step_typed(const DevPtrs& d, int n_req, int n_tiles, int lsa_s
     XT* xdec_nxt = reinterpret_cast<XT*>(d.xdec[cur ^ 1]);
     mark(0);
     // H_att(t): consumed by this step's decoder LSTM / attention and by the next step's attention LSTM
-    constexpr bool HAS_WIDE = sizeof(XT) == 2;     // the fp32 fragments of two row tiles do not fit the register file
-    if (!HAS_WIDE) wide = false;
-    if (qpart) wide = false;                       // pools that pass q as partial products are small: one-row-tile kernels
-    if (wide) {
+    constexpr bool HAS_WIDE = sizeof(XT) == 2;     // the fp32 fragments of several row tiles do not fit the register file
+    if (!HAS_WIDE || qpart) rows = 1;              // pools that pass q as partial products are small: one-row-tile kernels
+    const dim3 lg(HID / 4), lb(LSTM_WAVES * 64);
+    if (rows >= 2) {                               // the attention LSTM never takes four row tiles
         if constexpr (HAS_WIDE)
-            hipLaunchKernelGGL((k_lstm2<XT, K_ATT>), dim3(HID / 4), dim3(LSTM_WAVES * 64), 0, s,
-                               d.Wa, d.ba, xatt_cur, d.c_att, xdec_cur, K_DEC / KB, XD_HA, xatt_nxt, K_ATT / KB, XA_H,
-                               n_tiles, d.live, d.done);
+            hipLaunchKernelGGL((k_lstm_rc<XT, K_ATT, 2>), lg, lb, 0, s, d.Wa, d.ba, xatt_cur, d.c_att, xdec_cur, K_DEC / KB, XD_HA,
+                               xatt_nxt, K_ATT / KB, XA_H, n_tiles, d.live, d.done);
     } else if (qpart)
-        hipLaunchKernelGGL((k_lstm<XT, K_ATT, true>), dim3(HID / 4), dim3(LSTM_WAVES * 64), 0, s,
+        hipLaunchKernelGGL((k_lstm<XT, K_ATT, true>), lg, lb, 0, s,
                            d.Wa, d.ba, xatt_cur, d.c_att, xdec_cur, K_DEC / KB, XD_HA, xatt_nxt, K_ATT / KB, XA_H,
                            n_tiles, d.live, d.done, d.Wq_epi, d.qpart);
     else
-        hipLaunchKernelGGL((k_lstm<XT, K_ATT, false>), dim3(HID / 4), dim3(LSTM_WAVES * 64), 0, s,
+        hipLaunchKernelGGL((k_lstm<XT, K_ATT, false>), lg, lb, 0, s,
                            d.Wa, d.ba, xatt_cur, d.c_att, xdec_cur, K_DEC / KB, XD_HA, xatt_nxt, K_ATT / KB, XA_H,
                            n_tiles, d.live, d.done, nullptr, nullptr);
     mark(1);
@@ -1003,14 +1003,17 @@ static hipError_t step_typed(const DevPtrs& d, int n_req, int n_tiles, int lsa_s
     }
     mark(2);
     // H_dec(t): consumed by this step's projection and the next step's decoder LSTM (same buffer)
-    if (wide) {
+    const uint4* xdec_in = reinterpret_cast<const uint4*>(d.xdec[cur]);
+    if (rows == 4) {
         if constexpr (HAS_WIDE)
-            hipLaunchKernelGGL((k_lstm2<XT, K_DEC>), dim3(HID / 4), dim3(LSTM_WAVES * 64), 0, s,
-                               d.Wd, d.bd, reinterpret_cast<const uint4*>(d.xdec[cur]), d.c_dec, xdec_nxt, K_DEC / KB, XD_HD,
+            hipLaunchKernelGGL((k_lstm_rc<XT, K_DEC, 4>), lg, lb, 0, s, d.Wd, d.bd, xdec_in, d.c_dec, xdec_nxt, K_DEC / KB, XD_HD,
+                               xdec_nxt, K_DEC / KB, XD_HD, n_tiles, d.live, d.done);
+    } else if (rows == 2) {
+        if constexpr (HAS_WIDE)
+            hipLaunchKernelGGL((k_lstm_rc<XT, K_DEC, 2>), lg, lb, 0, s, d.Wd, d.bd, xdec_in, d.c_dec, xdec_nxt, K_DEC / KB, XD_HD,
                                xdec_nxt, K_DEC / KB, XD_HD, n_tiles, d.live, d.done);
     } else
-        hipLaunchKernelGGL((k_lstm<XT, K_DEC, false>), dim3(HID / 4), dim3(LSTM_WAVES * 64), 0, s,
-                           d.Wd, d.bd, reinterpret_cast<const uint4*>(d.xdec[cur]), d.c_dec, xdec_nxt, K_DEC / KB, XD_HD,
+        hipLaunchKernelGGL((k_lstm<XT, K_DEC, false>), lg, lb, 0, s, d.Wd, d.bd, xdec_in, d.c_dec, xdec_nxt, K_DEC / KB, XD_HD,
                            xdec_nxt, K_DEC / KB, XD_HD, n_tiles, d.live, d.done, nullptr, nullptr);
     mark(3);
     hipLaunchKernelGGL((k_proj<XT>), dim3(n_tiles), dim3(PROJ_THREADS), 0, s, d, cur);
@@ -1021,9 +1024,9 @@ static hipError_t step_typed(const DevPtrs& d, int n_req, int n_tiles, int lsa_s
 hipError_t launch_step(const DevPtrs& d, const StepLaunch& cfg, int cur, hipStream_t s, hipEvent_t* ev)
 {
     if (cfg.n_blocks < 1 || cfg.n_tiles < 1) return hipSuccess;
-    if (cfg.wdtype == 0 && cfg.mdtype == 0) return step_typed<float, float>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cfg.wide_lstm != 0, cfg.q_partials != 0, cur, s, ev);
-    if (cfg.wdtype == 1 && cfg.mdtype == 1) return step_typed<bf16_t, bf16_t>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cfg.wide_lstm != 0, cfg.q_partials != 0, cur, s, ev);
-    if (cfg.wdtype == 1 && cfg.mdtype == 0) return step_typed<bf16_t, float>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cfg.wide_lstm != 0, cfg.q_partials != 0, cur, s, ev);
+    if (cfg.wdtype == 0 && cfg.mdtype == 0) return step_typed<float, float>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cfg.lstm_rows, cfg.q_partials != 0, cur, s, ev);
+    if (cfg.wdtype == 1 && cfg.mdtype == 1) return step_typed<bf16_t, bf16_t>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cfg.lstm_rows, cfg.q_partials != 0, cur, s, ev);
+    if (cfg.wdtype == 1 && cfg.mdtype == 0) return step_typed<bf16_t, float>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cfg.lstm_rows, cfg.q_partials != 0, cur, s, ev);
     return hipErrorInvalidValue;
 }
 

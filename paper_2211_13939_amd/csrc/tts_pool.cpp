@@ -71,10 +71,10 @@ struct Layout {
     size_t total;
 };
 
-// Pools of at most 32 slots pass the attention query from the attention LSTM to the attention
+// Pools of at most 16 slots (one tile) pass the attention query from the attention LSTM to the attention
 // kernel as partial products (cheaper when a step is latency-bound, 128 KB of stores per request
 // otherwise).  Fixed per pool, so that a request's frames never depend on who else is in the pool.
-bool q_partials_for(const tts_config& c) { return c.max_pool <= 32; }
+bool q_partials_for(const tts_config& c) { return c.max_pool <= 16; }
 
 Layout make_layout(const tts_config& c)
 {
@@ -397,8 +397,10 @@ extern "C" int tts_pool_add_request(tts_pool* p, const float* enc_out, int L, in
 // workgroups per request in the attention kernel: more when the pool alone cannot fill the chip
 static int lsa_split_for(int n_blocks) { return n_blocks <= 64 ? 4 : (n_blocks <= 128 ? 2 : 1); }
 
-// LSTM tiling: above two pool tiles a workgroup takes two row tiles and half of the pool tiles
-static int wide_lstm_for(int n_blocks) { return n_blocks > 32 ? 1 : 0; }
+// LSTM tiling by the slots spanned: up to 2 pool tiles a workgroup takes one row tile and all pool
+// tiles, up to 8 tiles two row tiles and half of them, above that the decoder LSTM takes four row tiles and a
+// quarter (the attention LSTM, with its shorter K, stays at two: its four-row variant measured slower)
+static int lstm_rows_for(int n_blocks) { return n_blocks > 128 ? 4 : (n_blocks > 32 ? 2 : 1); }
 
 // most steps captured into one graph
 static const int MAX_GRAPH_STEPS = 32;
@@ -439,7 +441,7 @@ static void shape_for(const tts_pool* p, int span, StepLaunch* sl)
     sl->n_blocks = span;
     sl->n_tiles = (span + 15) / 16;
     sl->lsa_split = lsa_split_for(span);
-    sl->wide_lstm = wide_lstm_for(span);
+    sl->lstm_rows = lstm_rows_for(span);
     sl->q_partials = q_partials_for(p->cfg) ? 1 : 0;
 }
 
@@ -491,6 +493,8 @@ static int step_impl(tts_pool* p, int n, int64_t* out_frames, int* out_last_acti
         if (n_active == 0) break;
         int rc = push_membership(p);
         if (rc) return rc;
+        // graphs exist for powers of two up to MAX_GRAPH_STEPS (a graph of 40 steps, one whole chunk, ran
+        // about 1.5 us per step slower than graphs of 32 on this machine)
         int g = 1;
         if (p->cfg.use_graph)
             while (g * 2 <= n - i && g * 2 <= MAX_GRAPH_STEPS) g *= 2;

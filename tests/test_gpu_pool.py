@@ -281,7 +281,7 @@ def test_c4_full_pool_bf16(weights_bf16):
 
 
 def test_small_and_large_capacity_pools_agree(wl8, weights_fp32, solo_frames):
-    """Pools of at most 32 slots hand the attention query over as partial products
+    """Pools of at most 16 slots hand the attention query over as partial products
     from the attention LSTM, larger ones compute it in the attention kernel: the
     same numbers up to summation order."""
     say("case capacity: max_pool 8 vs 40, fp32")
