@@ -147,7 +147,9 @@ __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm(
 // against 1 + tiles for the one-row-tile kernel.  R = 2 is the minimum at 4 tiles, R = 4 at 16.  The
 // workgroups that share rows sit on the same XCD (their blockIdx differ by a multiple of 64), so the
 // repeated reads of the weights hit that XCD's L2.  The sums are taken in the same order as in k_lstm.
-template <typename XT, int K, int R>
+// PIPE (R = 4, one pool tile per round): the activations of the next tile are requested before the
+// products of the current one, two tiles per trip through the loop so that both buffers stay in registers.
+template <typename XT, int K, int R, bool PIPE = false>
 __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm_rc(
     const uint4* __restrict__ Wfrag, const float* __restrict__ bias, const uint4* __restrict__ X,
     float* __restrict__ c_state, XT* __restrict__ hout0, int nk0, int off0,
@@ -178,6 +180,59 @@ __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm_rc(
     const int unit = (R * rg + er) * 4 + (lane >> 4);
     floatx4 bias4 = {0.f, 0.f, 0.f, 0.f};
     if (wave < 4) bias4 = *reinterpret_cast<const floatx4*>(bias + unit * 4);
+
+    if constexpr (PIPE) {
+        static_assert(!PIPE || TP == 1, "the pipelined loop handles one pool tile per round");
+        // one round: products of tile `tp` from `bc`, cell update of the four row tiles
+        auto round = [&](int tp, const uint4 (&bc)[NF], int lv, int dn, float c_old) {
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int f = 0; f < NF; ++f) acc = mfma_frag<XT>(a[r][f], bc[f], acc);
+                red[wave][r][lane] = acc;
+            }
+            __syncthreads();
+            const int sl = tp * 16 + (lane & 15);
+            if (wave < 4 && lv && !dn) {
+                floatx4 g = bias4;
+#pragma unroll
+                for (int w = 0; w < NW; ++w) g += red[w][wave][lane];
+                const float gi = sigmoidf_(g[0]), gf = sigmoidf_(g[1]);
+                const float gg = tanhf_(g[2]), go = sigmoidf_(g[3]);
+                const float c = gf * c_old + gi * gg;
+                c_state[(size_t)sl * HID + unit] = c;
+                const XT h = from_float<XT>(go * tanhf_(c));
+                hout0[xoff<XT>(nk0, sl, off0 + unit)] = h;
+                hout1[xoff<XT>(nk1, sl, off1 + unit)] = h;
+            }
+            __syncthreads();
+        };
+        auto fetch = [&](int tp, uint4 (&bn)[NF], int& lv, int& dn, float& c_old) {
+            const int t = min(tp, c1 - 1);                 // past the end: the last tile again, never used
+            const int sl = t * 16 + (lane & 15);
+            lv = live[sl];
+            dn = done[sl];
+            c_old = c_state[(size_t)sl * HID + unit];
+#pragma unroll
+            for (int f = 0; f < NF; ++f) bn[f] = X[xfrag(NK, t, wave + f * NW, lane)];
+        };
+        if (c0 >= c1) return;
+        uint4 b0[NF], b1[NF];
+        int lv0, dn0, lv1, dn1;
+        float co0, co1;
+        fetch(c0, b0, lv0, dn0, co0);
+        for (int tp = c0; tp < c1; tp += 2) {
+            fetch(tp + 1, b1, lv1, dn1, co1);
+            __builtin_amdgcn_sched_barrier(0);
+            round(tp, b0, lv0, dn0, co0);
+            if (tp + 1 >= c1) break;
+            fetch(tp + 2, b0, lv0, dn0, co0);
+            __builtin_amdgcn_sched_barrier(0);
+            round(tp + 1, b1, lv1, dn1, co1);
+        }
+        return;
+    }
 
     for (int tp = c0; tp < c1; tp += TP) {
         // cell update inputs: independent, unconditional loads (see k_lstm)
@@ -979,7 +1034,11 @@ static hipError_t step_typed(const DevPtrs& d, int n_req, int n_tiles, int lsa_s
     constexpr bool HAS_WIDE = sizeof(XT) == 2;     // the fp32 fragments of several row tiles do not fit the register file
     if (!HAS_WIDE || qpart) rows = 1;              // pools that pass q as partial products are small: one-row-tile kernels
     const dim3 lg(HID / 4), lb(LSTM_WAVES * 64);
-    if (rows >= 2) {                               // the attention LSTM never takes four row tiles
+    if (rows == 4) {
+        if constexpr (HAS_WIDE)
+            hipLaunchKernelGGL((k_lstm_rc<XT, K_ATT, 4, true>), lg, lb, 0, s, d.Wa, d.ba, xatt_cur, d.c_att, xdec_cur, K_DEC / KB, XD_HA,
+                               xatt_nxt, K_ATT / KB, XA_H, n_tiles, d.live, d.done);
+    } else if (rows == 2) {
         if constexpr (HAS_WIDE)
             hipLaunchKernelGGL((k_lstm_rc<XT, K_ATT, 2>), lg, lb, 0, s, d.Wa, d.ba, xatt_cur, d.c_att, xdec_cur, K_DEC / KB, XD_HA,
                                xatt_nxt, K_ATT / KB, XA_H, n_tiles, d.live, d.done);
