@@ -542,6 +542,22 @@ __global__ __launch_bounds__(LSA_THREADS) void k_lsa(DevPtrs d, int cur)
         vsum += (vv.x + vv.y) + (vv.z + vv.w);
     }
     vsum *= -0.5f;
+    // |e_j| <= sum |v| =: bound.  The softmax does not care which constant is subtracted from the
+    // energies, so when the bound is small enough for exp(e - bound) to stay far from underflow
+    // (exp(-2 * 30) = 9e-27) it replaces the maximum: the weights' numerators and their sum are then
+    // formed right here in the energy loop, and the two passes over s_e (maximum, exponentials) with
+    // their barriers fall away.  A model with a larger bound takes those passes.
+    float bound = 0.f;
+#pragma unroll
+    for (int at = 0; at < 8; ++at) {
+        const float4 vv = *reinterpret_cast<const float4*>(&s_v[32 * g + 4 * at]);
+        bound += (fabsf(vv.x) + fabsf(vv.y)) + (fabsf(vv.z) + fabsf(vv.w));
+    }
+    bound += __shfl_xor(bound, 16, 64);
+    bound += __shfl_xor(bound, 32, 64);
+    bound *= 0.5f;
+    const bool fast_softmax = bound <= 30.f;        // the same in every lane of every wave
+    float psum = 0.f;
     // ---- energies, one 16-position tile per wave at a time; PM of the next tile is already in flight.
     // With S > 1 every workgroup of the request computes all energies: they are cheap next to the
     // encoder-row stream, and it keeps the softmax exact and local.
@@ -584,8 +600,14 @@ __global__ __launch_bounds__(LSA_THREADS) void k_lsa(DevPtrs d, int cur)
         }
         e += __shfl_xor(e, 16, 64);
         e += __shfl_xor(e, 32, 64);
-        if (g == 0 && j < L) s_e[j] = e;
+        if (fast_softmax) e = __expf(e - bound);
+        if (g == 0 && j < L) {
+            s_e[j] = e;
+            psum += e;
+        }
     }
+    psum = wave_sum(psum);
+    if (lane == 0) s_red[LSA_WAVES + wave] = psum;
 
     // ---- context over this workgroup's ENC / S columns: a wave-wide load covers S encoder rows
     // (64 / S lanes x 8 columns each), NR loads in flight per wave.  The first batch is requested
@@ -613,24 +635,27 @@ __global__ __launch_bounds__(LSA_THREADS) void k_lsa(DevPtrs d, int cur)
         }
     __syncthreads();
 
-    // ---- ragged softmax over j < L
-    float mx = -INFINITY;
-    for (int x = tid; x < L; x += LSA_THREADS) mx = fmaxf(mx, s_e[x]);
-    mx = wave_max(mx);
-    if (lane == 0) s_red[wave] = mx;
-    __syncthreads();
-    mx = s_red[0];
+    // ---- ragged softmax over j < L: s_e holds the numerators already, or the energies
+    float sum;
+    if (!fast_softmax) {
+        float mx = -INFINITY;
+        for (int x = tid; x < L; x += LSA_THREADS) mx = fmaxf(mx, s_e[x]);
+        mx = wave_max(mx);
+        if (lane == 0) s_red[wave] = mx;
+        __syncthreads();
+        mx = s_red[0];
 #pragma unroll
-    for (int w = 1; w < LSA_WAVES; ++w) mx = fmaxf(mx, s_red[w]);
-    float sum = 0.f;
-    for (int x = tid; x < L; x += LSA_THREADS) {
-        const float p = __expf(s_e[x] - mx);
-        s_e[x] = p;
-        sum += p;
+        for (int w = 1; w < LSA_WAVES; ++w) mx = fmaxf(mx, s_red[w]);
+        sum = 0.f;
+        for (int x = tid; x < L; x += LSA_THREADS) {
+            const float p = __expf(s_e[x] - mx);
+            s_e[x] = p;
+            sum += p;
+        }
+        sum = wave_sum(sum);
+        if (lane == 0) s_red[LSA_WAVES + wave] = sum;
+        __syncthreads();
     }
-    sum = wave_sum(sum);
-    if (lane == 0) s_red[LSA_WAVES + wave] = sum;
-    __syncthreads();
     sum = 0.f;
 #pragma unroll
     for (int w = 0; w < LSA_WAVES; ++w) sum += s_red[LSA_WAVES + w];

@@ -314,3 +314,19 @@ def test_c3_shrinking_pool_full_job(weights_bf16):
         assert got.shape[0] == wl.n_steps[i] and np.isfinite(got).all()
         assert np.abs(got[:50] - ref[k]).max() <= TOL_BF16
     pool.close()
+
+
+def test_large_attention_vector_takes_the_two_pass_softmax(weights_fp32):
+    """With sum |v| <= 30 the attention kernel subtracts that bound instead of the maximum energy and
+    forms the softmax in one pass; a model with a larger v takes the maximum-subtracting passes.
+    Both must match the oracle: v scaled up eight-fold (sum |v| about 40) here, the default elsewhere."""
+    w = dict(weights_fp32)
+    w["v"] = (w["v"] * 8.0).astype(np.float32)
+    assert np.abs(w["v"]).sum() > 30.0 > np.abs(weights_fp32["v"]).sum()
+    wl = synth.small_workload(5, 10, 120, 12, 12, seed=41)
+    say("case large v: 5 requests, 12 steps, fp32, sum|v| = %.1f" % np.abs(w["v"]).sum())
+    gpu = gpu_decode(wl, w, list(range(5)), 12)
+    ref, _, _ = oracle_decode(wl, w, list(range(5)), 12, n_threads=5)
+    err = max_err(gpu, ref)
+    say(f"  max abs err {err:.3e}")
+    assert err <= TOL_F32
