@@ -130,10 +130,13 @@ def stream_arrivals(w5, kind, qps, n=None):
     return np.cumsum(rng.exponential(1.0 / qps, size=n))
 
 
-def stream_run(stream, pool5, w5, enc, arrival, join_every, max_pool):
+def stream_run(stream, pool5, w5, enc, arrival, join_every, max_pool, postnet=None):
     n = len(arrival)
     n_steps = w5.n_steps[:n]
-    be = stream.GpuBackend(pool5, lambda i, e=enc: e[i], n_steps, w5.chunk_frames)
+    if postnet is not None:
+        be = stream.GpuPostnetBackend(pool5, postnet, lambda i, e=enc: e[i], n_steps, w5.chunk_frames, 10)
+    else:
+        be = stream.GpuBackend(pool5, lambda i, e=enc: e[i], n_steps, w5.chunk_frames)
     r = stream.simulate(be, arrival, n_steps, w5.chunk_frames, join_every=join_every, max_pool=max_pool)
     pc = r.percentiles("first")
     lc = r.percentiles("last")
@@ -395,10 +398,16 @@ def main():
         for name, je, enc in (("per_step_join", 1, enc5_dev), ("per_chunk_join", w5.chunk_frames, enc5_dev),
                               ("per_step_join_host_input", 1, enc5_host)):
             res[name] = stream_run(stream, pool5, w5, enc, arrival, je, 16)
+        # module D complete: every chunk also goes through the chunk-level PostNet before it leaves the device
+        ws5, bs5 = synth.make_postnet_weights(bf16=True)
+        pn5 = binding.Postnet(binding.make_postnet_config(max_columns=16 * 50, bf16=True), ws5, bs5, stream=pool5.stream)
+        res["per_step_join_with_postnet"] = stream_run(stream, pool5, w5, enc5_dev, arrival, 1, 16, postnet=pn5)
+        pn5.close()
         out["stream"] = {"workload": f"c5: {args.arrivals} arrivals at {args.qps:g}/s, {w5.n_requests} requests, L~U{{30..300}}, "
                                      "frames=4L, 40-frame chunks; encoder outputs resident in HBM "
                                      "(per_step_join_host_input: handed over from pageable host memory, PCIe copy "
-                                     "included); rtf = last-chunk latency / audio duration at 256 samples per frame, "
+                                     "included; per_step_join_with_postnet: each chunk also passes the chunk-level "
+                                     "PostNet on the device before it is copied out); rtf = last-chunk latency / audio duration at 256 samples per frame, "
                                      "22.05 kHz (decoder only)",
                          **res, "paper_context": "first-chunk latency < 80 ms at 100 QPS, full pipeline, one A10"}
         pool5.close()

@@ -131,7 +131,7 @@ class GpuBackend(PoolBackend):
 
     def add(self, index: int) -> int:
         rid = self.pool.add_request(self.enc(index), int(self.n_steps[index]))
-        self.live[rid] = dict(done=0, total=int(self.n_steps[index]), drained=0)
+        self.live[rid] = dict(index=index, done=0, total=int(self.n_steps[index]), drained=0)
         return rid
 
     def run(self, k: int):
@@ -157,3 +157,57 @@ class GpuBackend(PoolBackend):
     def retire(self, rid: int) -> None:
         self.pool.retire(rid)
         self.live.pop(rid, None)
+
+
+class GpuPostnetBackend(GpuBackend):
+    """Module D complete: the decoder step followed by the chunk-level PostNet.  Every chunk that
+    becomes ready in a segment is handed over on the device (with its context frames) and all of
+    them go through the PostNet as one dynamic batch (Sec. 2.2.2: each module batches the pool
+    items it has to process), then one copy brings the post-processed chunks to the host."""
+
+    def __init__(self, pool, postnet, enc, n_steps, chunk: int, context: int, on_chunk=None):
+        """on_chunk(request index, first frame, frames [n, n_mel]) is called for every chunk handed out."""
+        super().__init__(pool, enc, n_steps, chunk)
+        import torch
+        self.postnet, self.context, self.on_chunk = postnet, context, on_chunk
+        cap = int(pool.cfg.max_pool)
+        self._d_in = torch.empty((cap * (chunk + context), pool.n_mel), dtype=torch.float32, device=pool.device)
+        self._d_out = torch.empty((cap * chunk, pool.n_mel), dtype=torch.float32, device=pool.device)
+        self._h_out = torch.empty((cap * chunk, pool.n_mel), dtype=torch.float32).pin_memory()
+
+    def run(self, k: int):
+        self.pool.step_n(k)
+        for s in self.live.values():
+            s["done"] = min(s["total"], s["done"] + k)
+        chunk_ids, fin_ids = [], []
+        span = self.chunk + self.context
+        while True:                         # a request that ends may hand out a full chunk and then its rest
+            lens, keeps, row, out_rows, handed = [], [], 0, 0, []
+            for rid, s in self.live.items():
+                ready = s["done"] - s["drained"] >= self.chunk or s["done"] == s["total"]
+                if not ready or rid in fin_ids or row + span > self._d_in.shape[0]:
+                    continue
+                c, n, fin = self.pool.chunk_window(rid, self.context, self._d_in[row:])
+                if n:
+                    lens.append(c + n)
+                    keeps.append(c)
+                    row += c + n
+                    handed.append((s["index"], s["drained"], out_rows, n))
+                    out_rows += n
+                    s["drained"] += n
+                    if rid not in chunk_ids:
+                        chunk_ids.append(rid)
+                if fin:
+                    fin_ids.append(rid)
+            if not lens:
+                break
+            self.postnet.run_device(self._d_in, lens, keeps, self._d_out)
+            with self.pool._torch.cuda.stream(self.pool.stream):
+                self._h_out[:out_rows].copy_(self._d_out[:out_rows], non_blocking=True)
+            if self.on_chunk is not None:
+                self.pool.sync()
+                host = self._h_out.numpy()
+                for index, first, r0, n in handed:
+                    self.on_chunk(index, first, host[r0:r0 + n].copy())
+        self.pool.sync()
+        return None, chunk_ids, fin_ids

@@ -195,3 +195,39 @@ def test_decoder_chunks_through_postnet_on_device(weights_fp32):
     assert worst <= 5 * TOL_F32      # decoder error (<= 1e-4) passes through five layers of gain
     pn.close()
     pool.close()
+
+
+def test_serving_loop_with_postnet_matches_oracle(weights_fp32):
+    """The arrival-driven loop with the PostNet behind the decoder: six requests arriving over time into a
+    pool of four slots, chunks of 8 frames; every chunk handed out equals the oracle decoder followed by the
+    oracle PostNet on the utterance so far, whatever the pool held when the chunk was made."""
+    from oracle import oracle as orc
+    from paper_2211_13939_amd import stream
+    n = 6
+    wl = synth.small_workload(n, 10, 60, 17, 41, seed=47)
+    chunk = 8
+    pool = make_pool(wl, weights_fp32, chunk_frames=chunk, max_pool=4)
+    ws, bs = synth.make_postnet_weights()
+    pn = binding.Postnet(binding.make_postnet_config(max_columns=4 * (chunk + CTX)), ws, bs, stream=pool.stream)
+    got = {i: [] for i in range(n)}
+    be = stream.GpuPostnetBackend(pool, pn, lambda i: wl.encoder_outputs(i), wl.n_steps, chunk, CTX,
+                                  on_chunk=lambda i, first, fr: got[i].append((first, fr)))
+    arrivals = np.array([0.0, 0.0, 1e-4, 2e-4, 2e-4, 5e-3])
+    say(f"case serving loop with postnet: steps {wl.n_steps.tolist()}, pool of 4, chunks of {chunk}")
+    res = stream.simulate(be, arrivals, wl.n_steps, chunk, join_every=1, max_pool=4)
+    assert not np.isnan(res.first_chunk_latency_s).any() and not np.isnan(res.last_chunk_latency_s).any()
+    W, Wd = orc.PostnetWeights(ws, bs), orc.Weights(weights_fp32)
+    worst = 0.0
+    for i in range(n):
+        ref_mel, _, _, _ = orc.pool_decode(wl.dims, Wd, [wl.encoder_outputs(i)], [int(wl.n_steps[i])], int(wl.n_steps[i]))
+        at = 0
+        for first, fr in got[i]:
+            assert first == at and fr.shape[0] == min(chunk, int(wl.n_steps[i]) - at)
+            want = orc.postnet_chunk(W, ref_mel[0, : first + fr.shape[0]], first)
+            worst = max(worst, float(np.abs(fr - want).max()))
+            at += fr.shape[0]
+        assert at == int(wl.n_steps[i])
+    say(f"  max abs err {worst:.3e}")
+    assert worst <= 5 * TOL_F32
+    pn.close()
+    pool.close()
