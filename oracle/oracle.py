@@ -61,6 +61,15 @@ def lib() -> C.CDLL:
     return _lib
 
 
+class OrcGenerator(C.Structure):
+    _fields_ = [("n_mel", C.c_int), ("c0", C.c_int), ("n_stages", C.c_int), ("n_blocks", C.c_int),
+                ("n_pairs", C.c_int), ("k_pre", C.c_int), ("k_post", C.c_int),
+                ("rates", _ip), ("block_k", _ip), ("dils", _ip), ("slope", C.c_double),
+                ("pre_w", _fp), ("pre_b", _fp), ("post_w", _fp), ("post_b", _fp),
+                ("up_w", C.POINTER(_fp)), ("up_b", C.POINTER(_fp)),
+                ("res_w", C.POINTER(_fp)), ("res_b", C.POINTER(_fp))]
+
+
 def _declare(L: C.CDLL) -> None:
     L.orc_prenet.argtypes = [C.POINTER(OrcDims), _fp, _fp, _dp, _dp]
     L.orc_lstm_cell.argtypes = [C.c_int, C.c_int, _fp, _fp, _fp, _dp, _dp, _dp]
@@ -85,6 +94,11 @@ def _declare(L: C.CDLL) -> None:
     L.orc_postnet.argtypes = [C.c_int, C.c_int, C.c_int, C.POINTER(_fp), C.POINTER(_fp), C.c_int, _dp, _dp]
     L.orc_postnet_chunk.argtypes = [C.c_int, C.c_int, C.c_int, C.POINTER(_fp), C.POINTER(_fp), C.c_int, C.c_int,
                                     _dp, _dp]
+    L.orc_conv1d.argtypes = [C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, _fp, _fp, _dp, _dp]
+    L.orc_conv_transpose1d.argtypes = [C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, _fp, _fp, _dp, _dp]
+    L.orc_generator.argtypes = [C.POINTER(OrcGenerator), C.c_int, _dp, _dp]
+    L.orc_fade.argtypes = [C.c_int, _dp, _dp]
+    L.orc_crossfade.argtypes = [C.c_int, _dp, _dp, _dp]
 
 
 def _f(a: np.ndarray):
@@ -301,3 +315,125 @@ def postnet_chunk(W: PostnetWeights, mel_so_far, s: int):
     out = np.zeros((e - s, W.n_mel), np.float64)
     lib().orc_postnet_chunk(W.n_layers, W.n_mel, W.channels, W.wp, W.bp, int(s), int(e), _d(mel), _d(out))
     return out
+
+
+# ---- vocoder (oracle/vocoder_oracle.c)
+class VocoderWeights:
+    """w: dict with pre_w [c0, n_mel, 7], pre_b, post_w [1, c_last, 7], post_b, up_w[s] [c_in, c_in / 2, 2 u_s],
+    up_b[s], res_w[s][block][2 pair + {0: dilated, 1: plain}] [c, c, k_block], res_b likewise.  fp32."""
+
+    def __init__(self, w: dict, rates=(8, 8, 2, 2), block_k=(3, 7, 11), dils=(1, 3, 5), slope=0.1):
+        c32 = lambda a: np.ascontiguousarray(a, np.float32)
+        self.rates, self.block_k, self.dils, self.slope = tuple(rates), tuple(block_k), tuple(dils), float(slope)
+        self.pre_w, self.pre_b, self.post_w, self.post_b = c32(w["pre_w"]), c32(w["pre_b"]), c32(w["post_w"]), c32(w["post_b"])
+        self.up_w = [c32(a) for a in w["up_w"]]
+        self.up_b = [c32(a) for a in w["up_b"]]
+        self.res_w = [[[c32(a) for a in blk] for blk in st] for st in w["res_w"]]
+        self.res_b = [[[c32(a) for a in blk] for blk in st] for st in w["res_b"]]
+        ns, nb, npair = len(self.rates), len(self.block_k), len(self.dils)
+        self.n_mel, self.c0 = self.pre_w.shape[1], self.pre_w.shape[0]
+        self.hop = int(np.prod(self.rates))
+        c = self.c0
+        for s_ in range(ns):
+            assert self.up_w[s_].shape == (c, c // 2, 2 * self.rates[s_])
+            c //= 2
+            for b_ in range(nb):
+                assert len(self.res_w[s_][b_]) == 2 * npair
+                assert all(a.shape == (c, c, self.block_k[b_]) for a in self.res_w[s_][b_])
+        assert self.post_w.shape == (1, c, 7) and self.pre_w.shape[2] == 7
+        self._rates = (C.c_int * ns)(*self.rates)
+        self._bk = (C.c_int * nb)(*self.block_k)
+        self._dils = (C.c_int * npair)(*self.dils)
+        self._up_w = (_fp * ns)(*[_f(a) for a in self.up_w])
+        self._up_b = (_fp * ns)(*[_f(a) for a in self.up_b])
+        flat_w = [a for st in self.res_w for blk in st for a in blk]
+        flat_b = [a for st in self.res_b for blk in st for a in blk]
+        self._res_w = (_fp * len(flat_w))(*[_f(a) for a in flat_w])
+        self._res_b = (_fp * len(flat_b))(*[_f(a) for a in flat_b])
+        self.c = OrcGenerator(self.n_mel, self.c0, ns, nb, npair, 7, 7,
+                              C.cast(self._rates, _ip), C.cast(self._bk, _ip), C.cast(self._dils, _ip), self.slope,
+                              _f(self.pre_w), _f(self.pre_b), _f(self.post_w), _f(self.post_b),
+                              C.cast(self._up_w, C.POINTER(_fp)), C.cast(self._up_b, C.POINTER(_fp)),
+                              C.cast(self._res_w, C.POINTER(_fp)), C.cast(self._res_b, C.POINTER(_fp)))
+
+
+def conv1d(w, b, x, dil=1):
+    """x [T, c_in] -> [T, c_out]; w [c_out, c_in, k], zero 'same' padding."""
+    w, b = np.ascontiguousarray(w, np.float32), np.ascontiguousarray(b, np.float32)
+    x = np.ascontiguousarray(x, np.float64)
+    T, c_in = x.shape
+    c_out, _, k = w.shape
+    assert w.shape[1] == c_in and k % 2 == 1
+    y = np.zeros((T, c_out), np.float64)
+    lib().orc_conv1d(T, c_in, c_out, k, int(dil), _f(w), _f(b), _d(x), _d(y))
+    return y
+
+
+def conv_transpose1d(w, b, x, stride, pad):
+    """x [T, c_in] -> [T * stride, c_out]; w [c_in, c_out, k] with k - 2 pad = stride."""
+    w, b = np.ascontiguousarray(w, np.float32), np.ascontiguousarray(b, np.float32)
+    x = np.ascontiguousarray(x, np.float64)
+    T, c_in = x.shape
+    _, c_out, k = w.shape
+    assert w.shape[0] == c_in and k - 2 * pad == stride
+    y = np.zeros((T * stride, c_out), np.float64)
+    lib().orc_conv_transpose1d(T, c_in, c_out, k, int(stride), int(pad), _f(w), _f(b), _d(x), _d(y))
+    return y
+
+
+def generator(W: VocoderWeights, mel):
+    """audio [T * hop] = G(mel [T, n_mel])"""
+    mel = np.ascontiguousarray(mel, np.float64)
+    T = mel.shape[0]
+    assert mel.shape[1] == W.n_mel
+    audio = np.zeros(T * W.hop, np.float64)
+    lib().orc_generator(C.byref(W.c), T, _d(mel), _d(audio))
+    return audio
+
+
+def fade(n: int):
+    al, be = np.zeros(n, np.float64), np.zeros(n, np.float64)
+    lib().orc_fade(n, _d(al), _d(be))
+    return al, be
+
+
+def crossfade(head_cur, tail_pre):
+    a = np.ascontiguousarray(head_cur, np.float64)
+    b = np.ascontiguousarray(tail_pre, np.float64)
+    out = np.zeros_like(a)
+    lib().orc_crossfade(a.shape[0], _d(a), _d(b), _d(out))
+    return out
+
+
+class VocoderStream:
+    """One request's vocoder state across chunks (Sec. 2.2.2 lists it: M_pre, M_cur, S_pre, S_cur).
+
+    chunk(M_cur, last): S_cur = G([tail(M_pre), M_cur]) (Eq. 3, first line; the tail is `overlap` frames, absent for
+    the first chunk), the head of S_cur that overlaps the tail of S_pre is fused with it (Eq. 3, second line), then
+    M_pre = M_cur, S_pre = S_cur (Eq. 4).  Reading of what a response carries: the overlap region is sent once, fused,
+    with the chunk that completes it; so every chunk but the last holds back its final overlap * hop samples, and the
+    responses tile the utterance: sum of their lengths = hop * frames."""
+
+    def __init__(self, W: VocoderWeights, overlap: int):
+        self.W, self.ov = W, int(overlap)
+        self.m_pre = None
+        self.s_pre = None
+
+    def chunk(self, m_cur, last: bool):
+        m_cur = np.ascontiguousarray(m_cur, np.float64)
+        hop, ov = self.W.hop, self.ov
+        if self.m_pre is None:
+            s_cur = generator(self.W, m_cur)
+            body = s_cur
+        else:
+            tail = self.m_pre[-ov:] if ov else self.m_pre[:0]
+            n_ov = tail.shape[0] * hop
+            s_cur = generator(self.W, np.concatenate([tail, m_cur], axis=0))
+            if n_ov:
+                s_cur[:n_ov] = crossfade(s_cur[:n_ov], self.s_pre[-n_ov:])
+            body = s_cur
+        self.m_pre, self.s_pre = m_cur, s_cur
+        if last:
+            return body
+        hold = min(ov, m_cur.shape[0]) * hop
+        return body[: body.shape[0] - hold]

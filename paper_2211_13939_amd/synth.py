@@ -124,6 +124,39 @@ def make_postnet_weights(seed: int = 1235, bf16: bool = False, n_mel: int = 80, 
     return ws, bs
 
 
+VOCODER = dict(c0=128, rates=(8, 8, 2, 2), block_k=(3, 7, 11), dils=(1, 3, 5), k_pre=7, k_post=7, hop=256)
+
+
+def make_vocoder_weights(seed: int = 1236, bf16: bool = False, n_mel: int = 80, c0: int = 128,
+                         rates=(8, 8, 2, 2), block_k=(3, 7, 11), dils=(1, 3, 5)):
+    """Generator stand-in (Sec. 3.1: 128 initial channels, upsampling 8, 8, 2, 2).  Every tensor ~ N(0, (g / sqrt(fan_in))^2)
+    with g = 1 for conv_pre, the transposed convolutions and conv_post and g = 0.5 inside the residual blocks,
+    biases ~ N(0, 0.02^2), so that activations stay of order one; weights rounded to bf16 values when bf16.
+    Returns a dict: pre_w [c0, n_mel, 7], pre_b, up_w[s] [c, c/2, 2 u_s], up_b[s],
+    res_w[s][block][2 pair + {0: dilated, 1: plain}] [c, c, k], res_b likewise, post_w [1, c_last, 7], post_b."""
+    rng = np.random.default_rng(seed)
+
+    def tensor(shape, fan_in, gain):
+        w = (rng.standard_normal(shape) * (gain / np.sqrt(fan_in))).astype(np.float32)
+        return np.ascontiguousarray(round_to_bf16(w) if bf16 else w)
+
+    def bias(n):
+        return np.ascontiguousarray((rng.standard_normal(n) * 0.02).astype(np.float32))
+
+    w = dict(pre_w=tensor((c0, n_mel, 7), n_mel * 7, 1.0), pre_b=bias(c0), up_w=[], up_b=[], res_w=[], res_b=[])
+    c = c0
+    for u in rates:
+        # every output sample of the transposed convolution sees two taps of every input channel
+        w["up_w"].append(tensor((c, c // 2, 2 * u), 2 * c, 1.0))
+        w["up_b"].append(bias(c // 2))
+        c //= 2
+        w["res_w"].append([[tensor((c, c, k), c * k, 0.5) for _ in range(2 * len(dils))] for k in block_k])
+        w["res_b"].append([[bias(c) for _ in range(2 * len(dils))] for _ in block_k])
+    w["post_w"] = tensor((1, c, 7), c * 7, 1.0)
+    w["post_b"] = bias(1)
+    return w
+
+
 @dataclass
 class Workload:
     """One synthetic job: per-request encoder lengths, step counts and outputs."""

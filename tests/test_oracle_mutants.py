@@ -101,15 +101,15 @@ def _build_variant(src_text: str, workdir: str, name: str):
     so = os.path.join(workdir, name + ".so")
     with open(c, "w") as f:
         f.write(src_text)
-    subprocess.run(["gcc", "-O1", "-std=c99", "-fPIC", "-shared", "-fopenmp", "-w", "-o", so, c, obuild.SRC_POSTNET, "-lm"],
-                   check=True)
+    subprocess.run(["gcc", "-O1", "-std=c99", "-fPIC", "-shared", "-fopenmp", "-w", "-o", so, c, obuild.SRC_POSTNET,
+                    obuild.SRC_VOCODER, "-lm"], check=True)
     return orc.load(so)
 
 
-def _pins_fail(lib) -> bool:
+def _pins_fail(lib, tests=None) -> bool:
     prev = orc.use_library(lib)
     try:
-        for t in PIN_TESTS:
+        for t in (PIN_TESTS if tests is None else tests):
             try:
                 t()
             except (AssertionError, ValueError):
@@ -136,3 +136,83 @@ def test_pins_catch_planted_mistake(name, source):
     with tempfile.TemporaryDirectory() as tmp:
         lib = _build_variant(source.replace(old, new), tmp, "mutant")
         assert _pins_fail(lib), f"no pin noticed: {name}"
+
+
+# ---- the vocoder oracle (oracle/vocoder_oracle.c), same method
+from tests import test_vocoder_oracle as vpins
+
+VOCODER_MUTANTS = {
+    "convolution flipped":
+        ("int tt = t + (j - half) * dil;", "int tt = t - (j - half) * dil;"),
+    "dilation ignored":
+        ("int tt = t + (j - half) * dil;", "int tt = t + (j - half);"),
+    "convolution bias dropped":
+        ("double s = (double)b[co];\n            for (int ci = 0; ci < c_in; ++ci)\n                for (int j = 0; j < k; ++j) {\n                    int tt = t + (j - half) * dil;",
+         "double s = 0.0;\n            for (int ci = 0; ci < c_in; ++ci)\n                for (int j = 0; j < k; ++j) {\n                    int tt = t + (j - half) * dil;"),
+    "transposed convolution padding dropped":
+        ("int o = t * stride + j - pad;", "int o = t * stride + j;"),
+    "transposed convolution weight transposed":
+        ("w[((size_t)ci * c_out + co) * k + j] * xv", "w[(((size_t)co * c_in + ci) * k + j) % ((size_t)c_in * c_out * k)] * xv"),
+    "residual connection dropped":
+        ("for (size_t q = 0; q < n; ++q) x[q] += t[q];", "for (size_t q = 0; q < n; ++q) x[q] = t[q];"),
+    "second convolution of a pair dilated too":
+        ("orc_conv1d(T, c, c, k, 1, w[2 * i + 1], b[2 * i + 1], a, t);", "orc_conv1d(T, c, c, k, dils[i], w[2 * i + 1], b[2 * i + 1], a, t);"),
+    "no activation before the second convolution":
+        ("orc_leaky_relu(n, slope, t, a);\n        orc_conv1d(T, c, c, k, 1,", "memcpy(a, t, sizeof(double) * n);\n        orc_conv1d(T, c, c, k, 1,"),
+    "blocks summed, not averaged":
+        ("for (size_t q = 0; q < n_out; ++q) acc[q] /= (double)g->n_blocks;", ""),
+    "blocks chained instead of parallel":
+        ("memcpy(r, y, sizeof(double) * n_out);\n            orc_resblock(", "if (bk == 0) memcpy(r, y, sizeof(double) * n_out);\n            orc_resblock("),
+    "no activation before the upsampling":
+        ("orc_leaky_relu(n_in, g->slope, x, a);\n        orc_conv_transpose1d(", "memcpy(a, x, sizeof(double) * n_in);\n        orc_conv_transpose1d("),
+    "no tanh at the output":
+        ("audio[t] = tanh(audio[t]);", "audio[t] = audio[t];"),
+    "leaky slope applied to positives":
+        ("y[i] = x[i] > 0.0 ? x[i] : slope * x[i];", "y[i] = x[i] < 0.0 ? x[i] : slope * x[i];"),
+    "fade sampled at the left edge":
+        ("double u = ((double)i + 0.5) / (double)n;", "double u = ((double)i) / (double)n;"),
+    "fade coefficients swapped":
+        ("fused[i] = al[i] * head_cur[i] + be[i] * tail_pre[i];", "fused[i] = be[i] * head_cur[i] + al[i] * tail_pre[i];"),
+    "linear fade":
+        ("alpha[i] = sin(0.5 * ORC_PI * u);\n        beta[i] = cos(0.5 * ORC_PI * u);", "alpha[i] = u;\n        beta[i] = 1.0 - u;"),
+}
+
+VOCODER_PINS = [
+    lambda: [vpins.test_conv1d_equals_library_routine(*a) for a in ((3, 5, 3, 1, 11), (8, 8, 7, 3, 40), (4, 2, 11, 5, 23))],
+    lambda: [vpins.test_conv_transpose1d_equals_library_routine(*a) for a in ((4, 2, 8, 7), (6, 3, 2, 13))],
+    lambda: vpins.test_conv1d_impulse_by_hand(),
+    lambda: vpins.test_conv_transpose1d_impulse_by_hand(),
+    lambda: vpins.test_generator_equals_composition_of_library_routines(),
+    lambda: vpins.test_fade_is_equal_power(),
+    lambda: vpins.test_crossfade_by_hand(),
+    lambda: vpins.test_stream_tiles_the_utterance_and_follows_eq3_eq4(),
+]
+
+
+def _build_vocoder_variant(src_text: str, workdir: str, name: str):
+    c = os.path.join(workdir, name + ".c")
+    so = os.path.join(workdir, name + ".so")
+    with open(c, "w") as f:
+        f.write(src_text)
+    subprocess.run(["gcc", "-O1", "-std=c99", "-fPIC", "-shared", "-fopenmp", "-w", "-o", so, obuild.SRC, obuild.SRC_POSTNET,
+                    c, "-lm"], check=True)
+    return orc.load(so)
+
+
+@pytest.fixture(scope="module")
+def vocoder_source():
+    return open(obuild.SRC_VOCODER).read()
+
+
+def test_unmodified_vocoder_source_passes_every_pin(vocoder_source):
+    with tempfile.TemporaryDirectory() as tmp:
+        assert not _pins_fail(_build_vocoder_variant(vocoder_source, tmp, "clean"), VOCODER_PINS)
+
+
+@pytest.mark.parametrize("name", sorted(VOCODER_MUTANTS))
+def test_vocoder_pins_catch_planted_mistake(name, vocoder_source):
+    old, new = VOCODER_MUTANTS[name]
+    assert vocoder_source.count(old) == 1, f"mutation site for '{name}' not found exactly once"
+    with tempfile.TemporaryDirectory() as tmp:
+        lib = _build_vocoder_variant(vocoder_source.replace(old, new), tmp, "mutant")
+        assert _pins_fail(lib, VOCODER_PINS), f"no pin noticed: {name}"
