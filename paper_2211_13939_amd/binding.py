@@ -40,6 +40,8 @@ EXPORTS = (
     "tts_pool_chunk_window",
     "tts_postnet_workspace_bytes", "tts_postnet_create", "tts_postnet_run", "tts_postnet_elapsed_ms",
     "tts_postnet_destroy",
+    "tts_vocoder_workspace_bytes", "tts_vocoder_create", "tts_vocoder_run", "tts_vocoder_elapsed_ms",
+    "tts_vocoder_destroy",
 )
 
 _fp = C.POINTER(C.c_float)
@@ -63,6 +65,17 @@ class TtsPostnetWeights(C.Structure):
     _fields_ = [("conv_w", C.POINTER(C.c_float) * 5), ("conv_b", C.POINTER(C.c_float) * 5)]
 
 
+class TtsVocoderConfig(C.Structure):
+    _fields_ = [(n, C.c_int) for n in ("n_mel", "c0", "overlap", "max_chunk", "max_requests", "max_batch", "weight_dtype")]
+
+
+class TtsVocoderWeights(C.Structure):
+    _fields_ = [("pre_w", _fp), ("pre_b", _fp), ("up_w", _fp * 4), ("up_b", _fp * 4),
+                ("res_w", _fp * 6 * 3 * 4), ("res_b", _fp * 6 * 3 * 4), ("post_w", _fp), ("post_b", _fp)]
+
+
+VOCODER_HOP = 256
+VOCODER_FIRST, VOCODER_LAST = 1, 2
 POSTNET_CONTEXT = 10      # frames in front of a chunk that can influence it (2 per layer)
 
 
@@ -125,6 +138,14 @@ def lib() -> C.CDLL:
     L.tts_postnet_elapsed_ms.argtypes = [vp, _fp]
     L.tts_postnet_destroy.restype = None
     L.tts_postnet_destroy.argtypes = [vp]
+    L.tts_vocoder_workspace_bytes.restype = C.c_size_t
+    L.tts_vocoder_workspace_bytes.argtypes = [C.POINTER(TtsVocoderConfig)]
+    L.tts_vocoder_create.argtypes = [C.POINTER(TtsVocoderConfig), C.POINTER(TtsVocoderWeights), vp, C.c_size_t, vp,
+                                     C.POINTER(vp)]
+    L.tts_vocoder_run.argtypes = [vp, vp, _ip, _ip, _ip, C.c_int, vp, _ip]
+    L.tts_vocoder_elapsed_ms.argtypes = [vp, _fp]
+    L.tts_vocoder_destroy.restype = None
+    L.tts_vocoder_destroy.argtypes = [vp]
     _lib = L
     return L
 
@@ -410,6 +431,105 @@ class Postnet:
     def close(self) -> None:
         if getattr(self, "_h", None):
             lib().tts_postnet_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def make_vocoder_config(overlap: int, max_chunk: int, max_requests: int, max_batch: int, bf16: bool = False,
+                        n_mel: int = 80, c0: int = 128) -> TtsVocoderConfig:
+    return TtsVocoderConfig(n_mel, c0, int(overlap), int(max_chunk), int(max_requests), int(max_batch),
+                            DTYPE_BF16 if bf16 else DTYPE_F32)
+
+
+def vocoder_workspace_bytes(cfg: TtsVocoderConfig) -> int:
+    return int(lib().tts_vocoder_workspace_bytes(C.byref(cfg)))
+
+
+class Vocoder:
+    """tts_vocoder_* calls; owns its torch arena.  `weights` is the dict of synth.make_vocoder_weights."""
+
+    def __init__(self, cfg: TtsVocoderConfig, weights: dict, stream=None, device: str = "cuda:0"):
+        import torch
+        if not torch.cuda.is_available():
+            raise RuntimeError("no GPU visible: the vocoder has no CPU path")
+        self._torch = torch
+        self.cfg = cfg
+        self.device = torch.device(device)
+        nbytes = vocoder_workspace_bytes(cfg)
+        if nbytes == 0:
+            _check(TTS_E_INVAL)
+        with torch.cuda.device(self.device):
+            self.arena = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+            self.stream = stream if stream is not None else torch.cuda.Stream(device=self.device)
+        keep = []
+
+        def ptr(a):
+            a = np.ascontiguousarray(a, np.float32)
+            keep.append(a)
+            return a.ctypes.data_as(_fp)
+
+        w = TtsVocoderWeights()
+        w.pre_w, w.pre_b, w.post_w, w.post_b = ptr(weights["pre_w"]), ptr(weights["pre_b"]), ptr(weights["post_w"]), ptr(weights["post_b"])
+        for s_ in range(4):
+            w.up_w[s_], w.up_b[s_] = ptr(weights["up_w"][s_]), ptr(weights["up_b"][s_])
+            for b_ in range(3):
+                for i in range(6):
+                    w.res_w[s_][b_][i] = ptr(weights["res_w"][s_][b_][i])
+                    w.res_b[s_][b_][i] = ptr(weights["res_b"][s_][b_][i])
+        h = C.c_void_p()
+        with torch.cuda.device(self.device):
+            _check(lib().tts_vocoder_create(C.byref(cfg), C.byref(w), C.c_void_p(self.arena.data_ptr()), nbytes,
+                                            C.c_void_p(self.stream.cuda_stream), C.byref(h)))
+        self._h = h
+
+    def run_device(self, d_mel, n_frames, state_slot, flags, d_audio) -> list:
+        """d_mel: CUDA fp32 [sum n_frames, n_mel] (the chunks back to back); d_audio: CUDA fp32 with room for
+        256 * (overlap + n_frames[i]) samples per chunk.  Queued on the stream; returns the responses' lengths."""
+        nf = np.ascontiguousarray(n_frames, np.int32)
+        sl = np.ascontiguousarray(state_slot, np.int32)
+        fl = np.ascontiguousarray(flags, np.int32)
+        n = int(nf.shape[0])
+        assert sl.shape[0] == n and fl.shape[0] == n
+        assert d_mel.is_cuda and d_audio.is_cuda and d_mel.is_contiguous() and d_audio.is_contiguous()
+        assert d_mel.dtype == self._torch.float32 and d_audio.dtype == self._torch.float32
+        assert d_mel.numel() >= int(nf.sum()) * self.cfg.n_mel
+        assert d_audio.numel() >= int((nf + self.cfg.overlap).sum()) * VOCODER_HOP
+        out = np.zeros(n, np.int32)
+        _check(lib().tts_vocoder_run(self._h, C.c_void_p(d_mel.data_ptr()), nf.ctypes.data_as(_ip), sl.ctypes.data_as(_ip),
+                                     fl.ctypes.data_as(_ip), n, C.c_void_p(d_audio.data_ptr()), out.ctypes.data_as(_ip)))
+        return [int(x) for x in out]
+
+    def run(self, chunks, state_slot, flags) -> list:
+        """chunks: list of numpy [n_i, n_mel]; returns the responses as numpy arrays."""
+        torch = self._torch
+        nf = [int(c.shape[0]) for c in chunks]
+        packed = np.ascontiguousarray(np.concatenate(chunks, axis=0), np.float32)
+        with torch.cuda.stream(self.stream):
+            d_in = torch.from_numpy(packed).to(self.device, non_blocking=False)
+            d_out = torch.empty(sum(n + self.cfg.overlap for n in nf) * VOCODER_HOP, dtype=torch.float32, device=self.device)
+        self.stream.synchronize()
+        lens = self.run_device(d_in, nf, state_slot, flags, d_out)
+        self.stream.synchronize()
+        out = d_out.cpu().numpy()
+        res, r = [], 0
+        for n in lens:
+            res.append(out[r:r + n])
+            r += n
+        return res
+
+    def elapsed_ms(self) -> float:
+        ms = C.c_float()
+        _check(lib().tts_vocoder_elapsed_ms(self._h, C.byref(ms)))
+        return ms.value
+
+    def close(self) -> None:
+        if getattr(self, "_h", None):
+            lib().tts_vocoder_destroy(self._h)
             self._h = None
 
     def __del__(self):

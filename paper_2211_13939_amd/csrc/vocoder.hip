@@ -1,0 +1,336 @@
+// Vocoder kernels (Sec. 2.1.4, Eq. 3, Eq. 4): the generator G as a chain of one-dimensional convolutions on
+// MFMA, the splice of [tail(M_pre), M_cur] and the equal-power fade of the overlapping audio.
+//
+// Every convolution of G -- plain, dilated or transposed -- is one GEMM  Y[row][p] = sum_k W[row][k] X[k][p]
+// over the positions p of a window, with k = tap * C_in + channel and X[k][p] = act(x[p + (tap - half) * dil][channel]):
+//   plain / dilated   rows = output channels, taps = the kernel's taps
+//   transposed        stride u, kernel 2u, padding u/2: output u p + r depends on inputs p - 1, p, p + 1 only, so it is
+//                     a 3-tap convolution with rows = (phase r, output channel) and one zero tap per phase
+// Activations live in HBM as fp32 [position][channel]; a workgroup stages the positions of its tile plus the halo
+// in LDS (leaky ReLU and the conversion to the MFMA operand type happen there, once per element), so that a lane's
+// B operand -- consecutive channels of one tap at one position -- is one 16-byte LDS read.  Rows of LDS are padded
+// to an odd number of 16-byte pieces.  The weights are stored in A-fragment order and stream from L2.
+// Windows of different requests lie at a fixed stride; positions outside a window's own length read as zero, which
+// is the zero padding of every layer.
+#include "vocoder_kernels.h"
+
+#include "mfma.h"
+
+namespace tts {
+namespace {
+
+constexpr int VC_THREADS = 256;
+constexpr int VC_WAVES = VC_THREADS / 64;
+constexpr float VC_SLOPE = 0.1f;
+constexpr int VC_LDS_BYTES = 48 * 1024;
+constexpr int VC_HALO_BLOCKS = 5 * 5;        // kernel 11, dilation 5
+
+enum { EPI_PLAIN = 0, EPI_RESID = 1, EPI_UP = 2, EPI_POST = 3 };
+
+template <typename XT, int CIN> struct VcGeom {
+    static constexpr int EPL = Frag<XT>::EPL;
+    static constexpr int GP = CIN / EPL;         // 16-byte pieces per position
+    static constexpr int GPP = GP | 1;           // ... padded to an odd count
+    static constexpr int CINP = GPP * EPL;
+    static_assert(CIN % EPL == 0, "channels must fill whole 16-byte pieces");
+};
+
+// positions per workgroup: as many as the accumulators (64 registers) and 48 KB of LDS allow
+template <typename XT, int CIN, int ROWS, int HALO> constexpr int vc_tp()
+{
+    constexpr int RT = ROWS / 16, RG = RT < 4 ? RT : 4;
+    int tp = 1024 / RG;
+    while (tp > 64 && (tp + 2 * HALO) * VcGeom<XT, CIN>::GPP * 16 > VC_LDS_BYTES) tp /= 2;
+    return tp;
+}
+
+struct VcArgs {
+    const float* in0;     // input activations [position][C_in]
+    const float* in1;     // with SRC3 the input is the mean of in0, in1, in2 (the three residual blocks of a stage)
+    const float* in2;
+    const float* res;     // EPI_RESID: out = res + convolution
+    float* out;
+    const uint4* W;
+    const float* bias;
+    int dil;
+};
+struct VcArgs3 { VcArgs b[VOC_BLOCKS]; };
+
+__device__ __forceinline__ float lrelu(float x) { return x > 0.f ? x : VC_SLOPE * x; }
+
+template <typename XT> __device__ __forceinline__ void lds_put4(uint4* lds, int elem, float4 v);
+template <> __device__ __forceinline__ void lds_put4<float>(uint4* lds, int elem, float4 v)
+{
+    *reinterpret_cast<float4*>(reinterpret_cast<float*>(lds) + elem) = v;
+}
+template <> __device__ __forceinline__ void lds_put4<bf16_t>(uint4* lds, int elem, float4 v)
+{
+    uint2 u;
+    u.x = pack_bf16x2(v.x, v.y);
+    u.y = pack_bf16x2(v.z, v.w);
+    *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(lds) + elem) = u;
+}
+
+// One tile of TP positions of one window, all ROWS output rows.
+//   valid  positions of this window that exist (input side); wbase = first position of the window in the arrays
+//   p0     first position of the tile inside the window
+template <typename XT, int CIN, int ROWS, int COUT, int KS, int TP, int EPI, bool PRE_ACT, bool SRC3, int U>
+__device__ __forceinline__ void conv_tile(const VcArgs& a, int valid, size_t wbase, int p0, uint4* lds)
+{
+    using G = VcGeom<XT, CIN>;
+    constexpr int KB = Frag<XT>::KB;
+    constexpr int RT = ROWS / 16, RG = RT < 4 ? RT : 4, CT = TP / (16 * VC_WAVES);
+    constexpr int NK = (KS * CIN + KB - 1) / KB;     // K fragments (the weights are zero padded to whole fragments)
+    constexpr int NQ = KS * G::GP;                   // 16-byte pieces of k that exist
+    constexpr int C4 = CIN / 4;
+    static_assert(ROWS % 16 == 0 && RT % RG == 0 && TP % (16 * VC_WAVES) == 0, "tile shape");
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int n = lane & 15, g = lane >> 4;
+    const int halo = (KS - 1) / 2 * a.dil;
+    const int nrows = TP + 2 * halo;
+
+    // ---- stage positions [p0 - halo, p0 + TP + halo): activation and operand type applied once per element
+    for (int idx = tid; idx < nrows * C4; idx += VC_THREADS) {
+        const int row = idx / C4, c4 = idx - row * C4;
+        const int p = p0 - halo + row;
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (p >= 0 && p < valid) {
+            const size_t off = (wbase + p) * CIN + 4 * c4;
+            v = *reinterpret_cast<const float4*>(a.in0 + off);
+            if constexpr (SRC3) {
+                const float4 v1 = *reinterpret_cast<const float4*>(a.in1 + off);
+                const float4 v2 = *reinterpret_cast<const float4*>(a.in2 + off);
+                constexpr float third = 1.0f / 3.0f;
+                v.x = ((v.x + v1.x) + v2.x) * third; v.y = ((v.y + v1.y) + v2.y) * third;
+                v.z = ((v.z + v1.z) + v2.z) * third; v.w = ((v.w + v1.w) + v2.w) * third;
+            }
+            if constexpr (PRE_ACT) { v.x = lrelu(v.x); v.y = lrelu(v.y); v.z = lrelu(v.z); v.w = lrelu(v.w); }
+        }
+        lds_put4<XT>(lds, row * G::CINP + 4 * c4, v);
+    }
+    __syncthreads();
+
+    const int colbase = wave * (TP / VC_WAVES);
+#pragma unroll 1
+    for (int rt0 = 0; rt0 < RT; rt0 += RG) {
+        floatx4 acc[RG][CT];
+#pragma unroll
+        for (int rg = 0; rg < RG; ++rg)
+#pragma unroll
+            for (int ct = 0; ct < CT; ++ct) acc[rg][ct] = floatx4{0.f, 0.f, 0.f, 0.f};
+        const uint4* Wl = a.W + (size_t)rt0 * NK * 64 + lane;
+#pragma unroll 4
+        for (int kf = 0; kf < NK; ++kf) {
+            uint4 af[RG];
+#pragma unroll
+            for (int rg = 0; rg < RG; ++rg) af[rg] = Wl[((size_t)rg * NK + kf) * 64];
+            // this lane's 16 bytes of k: piece q = (tap, channel group); pieces past the end meet zero weights
+            const int q = min(kf * 4 + g, NQ - 1);
+            const int tap = q / G::GP, cg = q - tap * G::GP;
+            const uint4* bl = lds + (colbase + n + tap * a.dil) * G::GPP + cg;
+#pragma unroll
+            for (int ct = 0; ct < CT; ++ct) {
+                const uint4 bv = bl[ct * 16 * G::GPP];
+#pragma unroll
+                for (int rg = 0; rg < RG; ++rg) acc[rg][ct] = mfma_frag<XT>(af[rg], bv, acc[rg][ct]);
+            }
+        }
+        // ---- epilogue: lane holds rows row0 .. row0 + 3 of column n of every tile
+#pragma unroll
+        for (int rg = 0; rg < RG; ++rg) {
+            const int row0 = (rt0 + rg) * 16 + 4 * g;
+            if (row0 >= (EPI == EPI_UP ? ROWS : COUT)) continue;
+            if constexpr (EPI == EPI_POST) {
+                if (row0 != 0) continue;
+                const float b0 = a.bias[0];
+#pragma unroll
+                for (int ct = 0; ct < CT; ++ct) {
+                    const int p = p0 + colbase + ct * 16 + n;
+                    if (p < valid) a.out[wbase + p] = tanhf_(acc[rg][ct][0] + b0);
+                }
+            } else {
+                const int co = EPI == EPI_UP ? row0 % COUT : row0;
+                const int phase = EPI == EPI_UP ? row0 / COUT : 0;
+                const float4 bv = *reinterpret_cast<const float4*>(a.bias + co);
+#pragma unroll
+                for (int ct = 0; ct < CT; ++ct) {
+                    const int p = p0 + colbase + ct * 16 + n;
+                    if (p >= valid) continue;
+                    const size_t o = ((wbase + p) * U + phase) * COUT + co;
+                    float4 r = make_float4(acc[rg][ct][0] + bv.x, acc[rg][ct][1] + bv.y, acc[rg][ct][2] + bv.z, acc[rg][ct][3] + bv.w);
+                    if constexpr (EPI == EPI_RESID) {
+                        const float4 x = *reinterpret_cast<const float4*>(a.res + o);
+                        r.x += x.x; r.y += x.y; r.z += x.z; r.w += x.w;
+                    }
+                    *reinterpret_cast<float4*>(a.out + o) = r;
+                }
+            }
+        }
+    }
+}
+
+// grid = (tiles of a window, windows): one convolution of one kind
+template <typename XT, int CIN, int ROWS, int COUT, int KS, int EPI, bool PRE_ACT, bool SRC3, int U>
+__global__ __launch_bounds__(VC_THREADS) void k_vconv(VcArgs a, const int* __restrict__ len, int rate, int window)
+{
+    constexpr int TP = vc_tp<XT, CIN, ROWS, (KS - 1) / 2>();
+    __shared__ uint4 lds[(TP + 2 * ((KS - 1) / 2)) * VcGeom<XT, CIN>::GPP];
+    const int w = blockIdx.y, valid = len[w] * rate, p0 = blockIdx.x * TP;
+    if (p0 >= valid) return;
+    conv_tile<XT, CIN, ROWS, COUT, KS, TP, EPI, PRE_ACT, SRC3, U>(a, valid, (size_t)w * window * rate, p0, lds);
+}
+
+// grid = (tiles, windows, 3): the same convolution of the three residual blocks (kernels 3, 7, 11) of a stage
+template <typename XT, int C, int EPI>
+__global__ __launch_bounds__(VC_THREADS) void k_vconv_blocks(VcArgs3 a3, const int* __restrict__ len, int rate, int window)
+{
+    constexpr int ROWS = C < 16 ? 16 : C;
+    constexpr int TP = vc_tp<XT, C, ROWS, VC_HALO_BLOCKS>();
+    __shared__ uint4 lds[(TP + 2 * VC_HALO_BLOCKS) * VcGeom<XT, C>::GPP];
+    const int w = blockIdx.y, valid = len[w] * rate, p0 = blockIdx.x * TP;
+    if (p0 >= valid) return;
+    const size_t wbase = (size_t)w * window * rate;
+    if (blockIdx.z == 0) conv_tile<XT, C, ROWS, C, 3, TP, EPI, true, false, 1>(a3.b[0], valid, wbase, p0, lds);
+    else if (blockIdx.z == 1) conv_tile<XT, C, ROWS, C, 7, TP, EPI, true, false, 1>(a3.b[1], valid, wbase, p0, lds);
+    else conv_tile<XT, C, ROWS, C, 11, TP, EPI, true, false, 1>(a3.b[2], valid, wbase, p0, lds);
+}
+
+// One workgroup per window: rows [0, ov) <- tail(M_pre) of the slot (if the request has a previous chunk), then M_cur;
+// the slot's tail becomes M_cur's last ov frames (Eq. 4) unless this was the request's last chunk.
+__global__ __launch_bounds__(256) void k_voc_splice(VocBatch b, const float* __restrict__ d_mel, float* __restrict__ x_mel,
+                                                    float* __restrict__ m_tail, int* __restrict__ len, int ov, int window)
+{
+    const int w = blockIdx.x, tid = threadIdx.x;
+    const int nf = b.n_frames[w], hp = b.has_prev[w], last = b.last[w];
+    const float* src = d_mel + (size_t)b.src_row[w] * VOC_N_MEL;
+    float* dst = x_mel + (size_t)w * window * VOC_N_MEL;
+    float* tail = m_tail + (size_t)b.slot[w] * ov * VOC_N_MEL;
+    const int ovw = hp ? ov : 0;
+    for (int e = tid; e < ov * VOC_N_MEL; e += 256) {
+        if (hp) dst[e] = tail[e];
+        if (!last) tail[e] = src[(size_t)(nf - ov) * VOC_N_MEL + e];
+    }
+    for (int e = tid; e < nf * VOC_N_MEL; e += 256) dst[(size_t)ovw * VOC_N_MEL + e] = src[e];
+    if (tid == 0) len[w] = ovw + nf;
+}
+
+// grid = (frames of a window, windows), one sample per thread.  The thread that owns sample i of the overlap
+// region reads the slot's old tail(S_pre)[i] before it writes the new one, so nothing races.
+__global__ __launch_bounds__(VOC_HOP) void k_voc_fade(VocBatch b, const float* __restrict__ audio, const float* __restrict__ alpha,
+                                                      const float* __restrict__ beta, float* __restrict__ s_tail,
+                                                      float* __restrict__ d_audio, int ov, int window)
+{
+    const int w = blockIdx.y, i = blockIdx.x * VOC_HOP + threadIdx.x;
+    const int hp = b.has_prev[w], last = b.last[w];
+    const int N = ov * VOC_HOP;
+    const int L = ((hp ? ov : 0) + b.n_frames[w]) * VOC_HOP;
+    if (i >= L) return;
+    const float* S = audio + (size_t)w * window * VOC_HOP;
+    float v = S[i];
+    if (i < N) {
+        float* tail = s_tail + (size_t)b.slot[w] * N;
+        if (hp) v = alpha[i] * v + beta[i] * tail[i];
+        if (!last) tail[i] = S[L - N + i];
+    }
+    const int emit = last ? L : L - N;
+    if (i < emit) d_audio[(size_t)b.out_off[w] + i] = v;
+}
+
+template <typename XT, int CIN, int ROWS, int COUT, int KS, int EPI, bool PRE_ACT, bool SRC3, int U>
+void conv_launch(const VcArgs& a, const int* len, int rate, int window, int n_windows, hipStream_t s)
+{
+    constexpr int TP = vc_tp<XT, CIN, ROWS, (KS - 1) / 2>();
+    const dim3 grid((window * rate + TP - 1) / TP, n_windows);
+    hipLaunchKernelGGL((k_vconv<XT, CIN, ROWS, COUT, KS, EPI, PRE_ACT, SRC3, U>), grid, dim3(VC_THREADS), 0, s, a, len, rate, window);
+}
+
+template <typename XT, int C, int EPI>
+void blocks_launch(const VcArgs3& a, const int* len, int rate, int window, int n_windows, hipStream_t s)
+{
+    constexpr int ROWS = C < 16 ? 16 : C;
+    constexpr int TP = vc_tp<XT, C, ROWS, VC_HALO_BLOCKS>();
+    const dim3 grid((window * rate + TP - 1) / TP, n_windows, VOC_BLOCKS);
+    hipLaunchKernelGGL((k_vconv_blocks<XT, C, EPI>), grid, dim3(VC_THREADS), 0, s, a, len, rate, window);
+}
+
+template <typename XT, int S>
+void stage_launch(const VocoderPtrs& d, int n_windows, hipStream_t s)
+{
+    constexpr int CIN = VOC_C0 >> S, C = CIN / 2, U = voc_rate(S);
+    constexpr int rate_in = S == 0 ? 1 : voc_cum_rate(S - 1), rate = voc_cum_rate(S);
+    VcArgs up{};
+    up.in0 = S == 0 ? d.x0 : d.r[0];
+    up.in1 = d.r[1];
+    up.in2 = d.r[2];
+    up.out = d.y;
+    up.W = reinterpret_cast<const uint4*>(d.up_w[S]);
+    up.bias = d.up_b[S];
+    up.dil = 1;
+    conv_launch<XT, CIN, U * C, C, 3, EPI_UP, true, (S > 0), U>(up, d.len, rate_in, d.window, n_windows, s);
+    for (int p = 0; p < VOC_PAIRS; ++p) {
+        VcArgs3 c1{}, c2{};
+        for (int b = 0; b < VOC_BLOCKS; ++b) {
+            c1.b[b].in0 = p == 0 ? d.y : d.r[b];
+            c1.b[b].out = d.t[b];
+            c1.b[b].W = reinterpret_cast<const uint4*>(d.res_w[S][b][2 * p]);
+            c1.b[b].bias = d.res_b[S][b][2 * p];
+            c1.b[b].dil = voc_dil(p);
+            c2.b[b].in0 = d.t[b];
+            c2.b[b].res = p == 0 ? d.y : d.r[b];
+            c2.b[b].out = d.r[b];
+            c2.b[b].W = reinterpret_cast<const uint4*>(d.res_w[S][b][2 * p + 1]);
+            c2.b[b].bias = d.res_b[S][b][2 * p + 1];
+            c2.b[b].dil = 1;
+        }
+        blocks_launch<XT, C, EPI_PLAIN>(c1, d.len, rate, d.window, n_windows, s);
+        blocks_launch<XT, C, EPI_RESID>(c2, d.len, rate, d.window, n_windows, s);
+    }
+}
+
+template <typename XT>
+hipError_t generator_typed(const VocoderPtrs& d, int n_windows, hipStream_t s)
+{
+    VcArgs pre{};
+    pre.in0 = d.x_mel;
+    pre.out = d.x0;
+    pre.W = reinterpret_cast<const uint4*>(d.pre_w);
+    pre.bias = d.pre_b;
+    pre.dil = 1;
+    conv_launch<XT, VOC_N_MEL, VOC_C0, VOC_C0, VOC_K_PRE, EPI_PLAIN, false, false, 1>(pre, d.len, 1, d.window, n_windows, s);
+    stage_launch<XT, 0>(d, n_windows, s);
+    stage_launch<XT, 1>(d, n_windows, s);
+    stage_launch<XT, 2>(d, n_windows, s);
+    stage_launch<XT, 3>(d, n_windows, s);
+    VcArgs post{};
+    post.in0 = d.r[0];
+    post.in1 = d.r[1];
+    post.in2 = d.r[2];
+    post.out = d.audio;
+    post.W = reinterpret_cast<const uint4*>(d.post_w);
+    post.bias = d.post_b;
+    post.dil = 1;
+    conv_launch<XT, voc_channels(VOC_STAGES - 1), 16, 1, VOC_K_POST, EPI_POST, true, true, 1>(post, d.len, VOC_HOP, d.window, n_windows, s);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_vocoder_splice(const VocoderPtrs& d, const VocBatch& b, const float* d_mel, hipStream_t s)
+{
+    hipLaunchKernelGGL(k_voc_splice, dim3(b.n), dim3(256), 0, s, b, d_mel, d.x_mel, d.m_tail, d.len, d.overlap, d.window);
+    return hipGetLastError();
+}
+
+hipError_t launch_vocoder_generator(const VocoderPtrs& d, int wdtype, int n_windows, hipStream_t s)
+{
+    return wdtype == 0 ? generator_typed<float>(d, n_windows, s) : generator_typed<bf16_t>(d, n_windows, s);
+}
+
+hipError_t launch_vocoder_fade(const VocoderPtrs& d, const VocBatch& b, float* d_audio, hipStream_t s)
+{
+    hipLaunchKernelGGL(k_voc_fade, dim3(d.window, b.n), dim3(VOC_HOP), 0, s, b, d.audio, d.alpha, d.beta, d.s_tail, d_audio,
+                       d.overlap, d.window);
+    return hipGetLastError();
+}
+
+}  // namespace tts

@@ -14,10 +14,10 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 def _declared_symbols():
     names = set()
-    for header in ("tts_pool.h", "tts_postnet.h"):
+    for header in ("tts_pool.h", "tts_postnet.h", "tts_vocoder.h"):
         text = open(os.path.join(ROOT, "include", header)).read()
         text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-        names |= set(re.findall(r"\b(tts_(?:pool|book|last|postnet)_\w+)\s*\(", text))
+        names |= set(re.findall(r"\b(tts_(?:pool|book|last|postnet|vocoder)_\w+)\s*\(", text))
     return sorted(names)
 
 
@@ -113,3 +113,16 @@ def test_postnet_config_validation_without_gpu():
         c = binding.make_postnet_config(max_columns=100)
         setattr(c, field, bad)
         assert binding.postnet_workspace_bytes(c) == 0, field
+
+
+def test_vocoder_config_validation_without_gpu():
+    good = binding.make_vocoder_config(overlap=8, max_chunk=40, max_requests=16, max_batch=4)
+    assert binding.vocoder_workspace_bytes(good) > 4 * 48 * 2048 * 4 * 7          # seven activation buffers
+    bf = binding.make_vocoder_config(overlap=8, max_chunk=40, max_requests=16, max_batch=4, bf16=True)
+    assert 0 < binding.vocoder_workspace_bytes(bf) < binding.vocoder_workspace_bytes(good)
+    for field, bad in (("n_mel", 64), ("c0", 512), ("overlap", -1), ("overlap", 17), ("max_chunk", 0), ("max_chunk", 7),
+                       ("max_requests", 0), ("max_batch", 0), ("max_batch", 257), ("weight_dtype", 2)):
+        c = binding.make_vocoder_config(overlap=8, max_chunk=40, max_requests=16, max_batch=4)
+        setattr(c, field, bad)
+        assert binding.vocoder_workspace_bytes(c) == 0, field
+        assert binding.lib().tts_last_error()
