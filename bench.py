@@ -180,6 +180,51 @@ def postnet_bench(binding, synth, torch):
     return rows
 
 
+def vocoder_macs_per_frame():
+    """Multiply-accumulates of the generator per mel frame (the transposed convolutions counted by their two
+    useful taps per output sample)."""
+    macs = 80 * 7 * 128
+    c_in, rate = 128, 1
+    for u in (8, 8, 2, 2):
+        c, rate = c_in // 2, rate * u
+        macs += rate * (2 * c_in * c + 6 * (3 + 7 + 11) * c * c)
+        c_in = c
+    return macs + rate * c_in * 7
+
+
+def vocoder_bench(binding, synth, torch, sizes=(1, 3, 16, 64, 256)):
+    """One round of the vocoder module: every request's 40-frame chunk behind 8 frames of the previous one through
+    the generator (bf16 operands, fp32 accumulation), fade and write-back included."""
+    MFMA_PEAK_TFLOPS = 2500.0
+    w = synth.make_vocoder_weights(bf16=True)
+    rows = []
+    rng = np.random.default_rng(6)
+    ov, chunk = 8, 40
+    voc = binding.Vocoder(binding.make_vocoder_config(overlap=ov, max_chunk=chunk, max_requests=256, max_batch=256, bf16=True), w)
+    for n_req in sizes:
+        nf, slots = [chunk] * n_req, list(range(n_req))
+        d_in = torch.from_numpy(rng.standard_normal((n_req * chunk, 80)).astype(np.float32)).to(voc.device)
+        d_out = torch.empty(n_req * (chunk + ov) * 256, dtype=torch.float32, device=voc.device)
+        torch.cuda.synchronize()
+        voc.run_device(d_in, nf, slots, [binding.VOCODER_FIRST] * n_req, d_out)
+        for _ in range(3):
+            voc.run_device(d_in, nf, slots, [0] * n_req, d_out)
+        times = []
+        for _ in range(10):
+            voc.run_device(d_in, nf, slots, [0] * n_req, d_out)
+            times.append(voc.elapsed_ms() * 1e3)
+        voc.run_device(d_in, nf, slots, [binding.VOCODER_LAST] * n_req, d_out)
+        voc.stream.synchronize()
+        us = float(np.median(times))
+        flops = 2.0 * vocoder_macs_per_frame() * n_req * (chunk + ov)
+        rows.append({"requests": n_req, "frames_in": n_req * (chunk + ov), "samples_out": n_req * chunk * 256, "us_per_round": us,
+                     "us_min": float(min(times)), "us_max": float(max(times)),
+                     "audio_seconds_per_s": n_req * chunk * 256 / 22050.0 / (us * 1e-6),
+                     "tflops": flops / (us * 1e-6) / 1e12, "frac_of_bf16_mfma_peak": flops / (us * 1e-6) / 1e12 / MFMA_PEAK_TFLOPS})
+    voc.close()
+    return rows
+
+
 def job_roofline_bytes(wl, s_w, s_m):
     """Algorithmic bytes of the whole shrinking-pool job: the per-step bytes integrated over the
     actual membership (request i is active during steps 0 .. n_i - 1)."""
@@ -212,6 +257,10 @@ def main():
     ap.add_argument("--postnet", action="store_true",
                     help="only time the chunk-wise PostNet (bf16): one round of 40-frame chunks with 10 frames of context for "
                          "3, 64 and 256 requests")
+    ap.add_argument("--vocoder", action="store_true",
+                    help="only time the vocoder module (bf16): one round of 40-frame chunks behind 8 overlap frames for "
+                         "1 .. 256 requests")
+    ap.add_argument("--vocoder-sizes", default="1,3,16,64,256", help="batch sizes of --vocoder")
     ap.add_argument("--pool-sweep", action="store_true",
                     help="only time the full-pool step for pools of 1..256 requests (bf16, L ~ U{30..300})")
     ap.add_argument("--profile-only", action="store_true",
@@ -242,6 +291,9 @@ def main():
         return
     if args.postnet:
         print(json.dumps({"postnet": postnet_bench(binding, synth, torch)}))
+        return
+    if args.vocoder:
+        print(json.dumps({"vocoder": vocoder_bench(binding, synth, torch, [int(x) for x in args.vocoder_sizes.split(",")]), "macs_per_frame": vocoder_macs_per_frame()}))
         return
     if args.qps_sweep:
         from paper_2211_13939_amd import stream

@@ -50,7 +50,7 @@ ConvShape post_shape(bool bf) { return shape_of(1, voc_channels(VOC_STAGES - 1),
 struct VocLayout {
     size_t pre_w, pre_b, up_w[VOC_STAGES], up_b[VOC_STAGES];
     size_t res_w[VOC_STAGES][VOC_BLOCKS][2 * VOC_PAIRS], res_b[VOC_STAGES][VOC_BLOCKS][2 * VOC_PAIRS];
-    size_t post_w, post_b, alpha, beta, m_tail, s_tail, len, x_mel, x0, y, t[VOC_BLOCKS], r[VOC_BLOCKS], audio, total;
+    size_t post_w, post_b, alpha, beta, m_tail, s_tail, len, x_mel, x0, y, r[VOC_BLOCKS], audio, total;
     size_t state_begin;   // everything from here on is cleared at creation
 };
 
@@ -86,7 +86,6 @@ VocLayout layout_of(const tts_vocoder_config& c)
     // positions x channels per frame: 8 * 64, 64 * 32, 128 * 16, 256 * 8 -- at most 2048
     const size_t act = frames * 2048 * 4;
     l.y = a.take(act);
-    for (int b = 0; b < VOC_BLOCKS; ++b) l.t[b] = a.take(act);
     for (int b = 0; b < VOC_BLOCKS; ++b) l.r[b] = a.take(act);
     l.audio = a.take(frames * VOC_HOP * 4);
     l.total = a.off;
@@ -219,7 +218,6 @@ extern "C" int tts_vocoder_create(const tts_vocoder_config* cfg, const tts_vocod
     d.x0 = (float*)(base + lay.x0);
     d.y = (float*)(base + lay.y);
     for (int b = 0; b < VOC_BLOCKS; ++b) {
-        d.t[b] = (float*)(base + lay.t[b]);
         d.r[b] = (float*)(base + lay.r[b]);
     }
     d.audio = (float*)(base + lay.audio);

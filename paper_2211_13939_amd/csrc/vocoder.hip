@@ -23,9 +23,8 @@ constexpr int VC_THREADS = 256;
 constexpr int VC_WAVES = VC_THREADS / 64;
 constexpr float VC_SLOPE = 0.1f;
 constexpr int VC_LDS_BYTES = 48 * 1024;
-constexpr int VC_HALO_BLOCKS = 5 * 5;        // kernel 11, dilation 5
 
-enum { EPI_PLAIN = 0, EPI_RESID = 1, EPI_UP = 2, EPI_POST = 3 };
+enum { EPI_PLAIN = 0, EPI_UP = 2, EPI_POST = 3 };
 
 template <typename XT, int CIN> struct VcGeom {
     static constexpr int EPL = Frag<XT>::EPL;
@@ -48,13 +47,11 @@ struct VcArgs {
     const float* in0;     // input activations [position][C_in]
     const float* in1;     // with SRC3 the input is the mean of in0, in1, in2 (the three residual blocks of a stage)
     const float* in2;
-    const float* res;     // EPI_RESID: out = res + convolution
     float* out;
     const uint4* W;
     const float* bias;
     int dil;
 };
-struct VcArgs3 { VcArgs b[VOC_BLOCKS]; };
 
 __device__ __forceinline__ float lrelu(float x) { return x > 0.f ? x : VC_SLOPE * x; }
 
@@ -157,11 +154,7 @@ __device__ __forceinline__ void conv_tile(const VcArgs& a, int valid, size_t wba
                     const int p = p0 + colbase + ct * 16 + n;
                     if (p >= valid) continue;
                     const size_t o = ((wbase + p) * U + phase) * COUT + co;
-                    float4 r = make_float4(acc[rg][ct][0] + bv.x, acc[rg][ct][1] + bv.y, acc[rg][ct][2] + bv.z, acc[rg][ct][3] + bv.w);
-                    if constexpr (EPI == EPI_RESID) {
-                        const float4 x = *reinterpret_cast<const float4*>(a.res + o);
-                        r.x += x.x; r.y += x.y; r.z += x.z; r.w += x.w;
-                    }
+                    const float4 r = make_float4(acc[rg][ct][0] + bv.x, acc[rg][ct][1] + bv.y, acc[rg][ct][2] + bv.z, acc[rg][ct][3] + bv.w);
                     *reinterpret_cast<float4*>(a.out + o) = r;
                 }
             }
@@ -180,19 +173,159 @@ __global__ __launch_bounds__(VC_THREADS) void k_vconv(VcArgs a, const int* __res
     conv_tile<XT, CIN, ROWS, COUT, KS, TP, EPI, PRE_ACT, SRC3, U>(a, valid, (size_t)w * window * rate, p0, lds);
 }
 
-// grid = (tiles, windows, 3): the same convolution of the three residual blocks (kernels 3, 7, 11) of a stage
-template <typename XT, int C, int EPI>
-__global__ __launch_bounds__(VC_THREADS) void k_vconv_blocks(VcArgs3 a3, const int* __restrict__ len, int rate, int window)
+// ---------------------------------------------------------------------------
+// One residual block, all three convolution pairs, on one tile of positions without leaving the CU:
+//   for d in (1, 3, 5):  x += conv_{k,1}(lrelu(conv_{k,d}(lrelu(x))))
+// The residual stream x of the tile -- TP positions plus the halo H = (k-1)/2 * 12 that the six convolutions
+// eat on each side -- stays in registers in the MFMA accumulator layout (lane = one position, four channels
+// per row tile), so the second convolution of a pair accumulates straight onto it.  The operand of the next
+// convolution (leaky ReLU applied, operand type, zero outside the request's window) goes through one LDS
+// buffer: written by the lanes that own the values, read as B fragments by every wave.  Values near the
+// edge of the region are wrong after a convolution (their neighbours were not staged); the error front moves
+// inwards by one halo per convolution and stops exactly at the TP positions that are written out.
+// ---------------------------------------------------------------------------
+struct VrArgs {
+    const float* in;                         // the stage's upsampled activations
+    float* out;                              // the block's output
+    const uint4* W[2 * VOC_PAIRS];           // [2 pair + {0: dilated, 1: plain}]
+    const float* bias[2 * VOC_PAIRS];
+};
+struct VrArgs3 { VrArgs b[VOC_BLOCKS]; };
+
+template <typename XT, int C, int KS, int TP> struct VrGeom {
+    static constexpr int HALF = (KS - 1) / 2;
+    static constexpr int H = HALF * 12;                       // sum over d = 1, 3, 5 of (d + 1) * HALF
+    static constexpr int NCOL = (TP + 2 * H + 63) / 64;       // column tiles per wave
+    static constexpr int W = 64 * NCOL;                       // positions of the region
+    static constexpr int PADR = HALF * 5;                     // zero rows on each side: the widest tap offset
+    static constexpr int BYTES = (W + 2 * PADR) * VcGeom<XT, C>::GPP * 16;
+};
+
+// positions per workgroup of the fused kernel: the region's accumulators (x and one convolution's output) fit the
+// register file, the operand buffer fits LDS
+template <int C> constexpr int vr_tp() { return C >= 64 ? 256 : (C >= 32 ? 512 : 1024); }
+
+// acc[rt][ct] += W (rows rt, all k) * operand(columns of tile ct shifted by the taps)
+template <typename XT, int C, int KS, int NCOL, int PADR>
+__device__ __forceinline__ void conv_regs(const uint4* __restrict__ Wf, int dil, const uint4* lds, int col0, int lane,
+                                          floatx4 (&acc)[(C < 16 ? 16 : C) / 16][NCOL])
 {
-    constexpr int ROWS = C < 16 ? 16 : C;
-    constexpr int TP = vc_tp<XT, C, ROWS, VC_HALO_BLOCKS>();
-    __shared__ uint4 lds[(TP + 2 * VC_HALO_BLOCKS) * VcGeom<XT, C>::GPP];
+    using G = VcGeom<XT, C>;
+    constexpr int KB = Frag<XT>::KB;
+    constexpr int RT = (C < 16 ? 16 : C) / 16;
+    constexpr int NK = (KS * C + KB - 1) / KB;
+    constexpr int NQ = KS * G::GP;
+    const int n = lane & 15, g = lane >> 4;
+    const uint4* Wl = Wf + lane;
+#pragma unroll 2
+    for (int kf = 0; kf < NK; ++kf) {
+        uint4 af[RT];
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) af[rt] = Wl[((size_t)rt * NK + kf) * 64];
+        const int q = min(kf * 4 + g, NQ - 1);
+        const int tap = q / G::GP, cg = q - tap * G::GP;
+        const uint4* bl = lds + (col0 + n + PADR + (tap - (KS - 1) / 2) * dil) * G::GPP + cg;
+#pragma unroll
+        for (int ct = 0; ct < NCOL; ++ct) {
+            const uint4 bv = bl[ct * 16 * G::GPP];
+#pragma unroll
+            for (int rt = 0; rt < RT; ++rt) acc[rt][ct] = mfma_frag<XT>(af[rt], bv, acc[rt][ct]);
+        }
+    }
+}
+
+template <typename XT, int C, int KS, int TP>
+__device__ __forceinline__ void resblock_tile(const VrArgs& a, int valid, size_t wbase, int p0, uint4* lds)
+{
+    using G = VcGeom<XT, C>;
+    using R = VrGeom<XT, C, KS, TP>;
+    constexpr int RT = (C < 16 ? 16 : C) / 16, NCOL = R::NCOL;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int n = lane & 15, g = lane >> 4;
+    const int col0 = wave * 16 * NCOL;           // this wave's first position of the region
+    const int pbase = p0 - R::H;                 // the region's first position inside the window
+    const bool rows_ok = 4 * g < C;              // C = 8: the upper half of the 16-row tile is padding
+
+    // zero rows in front of and behind the region: never written again
+    for (int idx = tid; idx < 2 * R::PADR * G::GPP; idx += VC_THREADS) {
+        const int r = idx / G::GPP, c = idx - r * G::GPP;
+        lds[(r < R::PADR ? r : R::W + r) * G::GPP + c] = make_uint4(0, 0, 0, 0);
+    }
+    floatx4 x[RT][NCOL];
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+        for (int ct = 0; ct < NCOL; ++ct) {
+            const int p = pbase + col0 + ct * 16 + n;
+            floatx4 v = {0.f, 0.f, 0.f, 0.f};
+            if (p >= 0 && p < valid && rows_ok) v = *reinterpret_cast<const floatx4*>(a.in + (wbase + p) * C + rt * 16 + 4 * g);
+            x[rt][ct] = v;
+        }
+    // operand of the next convolution: lrelu, zero outside the window, operand type
+    auto put = [&](const floatx4 (&v)[RT][NCOL]) {
+        if (!rows_ok) return;
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+            for (int ct = 0; ct < NCOL; ++ct) {
+                const int j = col0 + ct * 16 + n, p = pbase + j;
+                const bool in = p >= 0 && p < valid;
+                const float4 o = make_float4(in ? lrelu(v[rt][ct][0]) : 0.f, in ? lrelu(v[rt][ct][1]) : 0.f,
+                                             in ? lrelu(v[rt][ct][2]) : 0.f, in ? lrelu(v[rt][ct][3]) : 0.f);
+                lds_put4<XT>(lds, (j + R::PADR) * G::CINP + rt * 16 + 4 * g, o);
+            }
+    };
+    auto bias_of = [&](const float* b, int rt) {
+        floatx4 v = {0.f, 0.f, 0.f, 0.f};
+        if (rows_ok) v = *reinterpret_cast<const floatx4*>(b + rt * 16 + 4 * g);
+        return v;
+    };
+#pragma unroll 1
+    for (int pair = 0; pair < VOC_PAIRS; ++pair) {
+        put(x);
+        __syncthreads();
+        floatx4 t[RT][NCOL];
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) {
+            const floatx4 b1 = bias_of(a.bias[2 * pair], rt);
+#pragma unroll
+            for (int ct = 0; ct < NCOL; ++ct) t[rt][ct] = b1;
+        }
+        conv_regs<XT, C, KS, NCOL, R::PADR>(a.W[2 * pair], 2 * pair + 1, lds, col0, lane, t);
+        __syncthreads();                          // every wave has read the old operand
+        put(t);
+        __syncthreads();
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) {
+            const floatx4 b2 = bias_of(a.bias[2 * pair + 1], rt);
+#pragma unroll
+            for (int ct = 0; ct < NCOL; ++ct) x[rt][ct] += b2;
+        }
+        conv_regs<XT, C, KS, NCOL, R::PADR>(a.W[2 * pair + 1], 1, lds, col0, lane, x);
+        __syncthreads();
+    }
+    if (!rows_ok) return;
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+        for (int ct = 0; ct < NCOL; ++ct) {
+            const int j = col0 + ct * 16 + n, p = pbase + j;
+            if (j >= R::H && j < R::H + TP && p < valid)
+                *reinterpret_cast<floatx4*>(a.out + (wbase + p) * C + rt * 16 + 4 * g) = x[rt][ct];
+        }
+}
+
+// grid = (tiles, windows, 3): the three residual blocks (kernels 3, 7, 11) of a stage
+template <typename XT, int C, int TP>
+__global__ __launch_bounds__(VC_THREADS) void k_vres(VrArgs3 a3, const int* __restrict__ len, int rate, int window)
+{
+    extern __shared__ uint4 lds_dyn[];
     const int w = blockIdx.y, valid = len[w] * rate, p0 = blockIdx.x * TP;
     if (p0 >= valid) return;
     const size_t wbase = (size_t)w * window * rate;
-    if (blockIdx.z == 0) conv_tile<XT, C, ROWS, C, 3, TP, EPI, true, false, 1>(a3.b[0], valid, wbase, p0, lds);
-    else if (blockIdx.z == 1) conv_tile<XT, C, ROWS, C, 7, TP, EPI, true, false, 1>(a3.b[1], valid, wbase, p0, lds);
-    else conv_tile<XT, C, ROWS, C, 11, TP, EPI, true, false, 1>(a3.b[2], valid, wbase, p0, lds);
+    if (blockIdx.z == 0) resblock_tile<XT, C, 3, TP>(a3.b[0], valid, wbase, p0, lds_dyn);
+    else if (blockIdx.z == 1) resblock_tile<XT, C, 7, TP>(a3.b[1], valid, wbase, p0, lds_dyn);
+    else resblock_tile<XT, C, 11, TP>(a3.b[2], valid, wbase, p0, lds_dyn);
 }
 
 // One workgroup per window: rows [0, ov) <- tail(M_pre) of the slot (if the request has a previous chunk), then M_cur;
@@ -244,17 +377,25 @@ void conv_launch(const VcArgs& a, const int* len, int rate, int window, int n_wi
     hipLaunchKernelGGL((k_vconv<XT, CIN, ROWS, COUT, KS, EPI, PRE_ACT, SRC3, U>), grid, dim3(VC_THREADS), 0, s, a, len, rate, window);
 }
 
-template <typename XT, int C, int EPI>
-void blocks_launch(const VcArgs3& a, const int* len, int rate, int window, int n_windows, hipStream_t s)
+template <typename XT, int C>
+hipError_t blocks_launch(const VrArgs3& a, const int* len, int rate, int window, int n_windows, hipStream_t s)
 {
-    constexpr int ROWS = C < 16 ? 16 : C;
-    constexpr int TP = vc_tp<XT, C, ROWS, VC_HALO_BLOCKS>();
+    constexpr int TP = vr_tp<C>();
+    constexpr int LDS = VrGeom<XT, C, 11, TP>::BYTES;       // the widest of the three kernels
+    auto kern = k_vres<XT, C, TP>;
+    static bool attr_set = false;                            // dynamic LDS above 64 KB has to be allowed once per kernel
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
     const dim3 grid((window * rate + TP - 1) / TP, n_windows, VOC_BLOCKS);
-    hipLaunchKernelGGL((k_vconv_blocks<XT, C, EPI>), grid, dim3(VC_THREADS), 0, s, a, len, rate, window);
+    hipLaunchKernelGGL(kern, grid, dim3(VC_THREADS), LDS, s, a, len, rate, window);
+    return hipSuccess;
 }
 
 template <typename XT, int S>
-void stage_launch(const VocoderPtrs& d, int n_windows, hipStream_t s)
+hipError_t stage_launch(const VocoderPtrs& d, int n_windows, hipStream_t s)
 {
     constexpr int CIN = VOC_C0 >> S, C = CIN / 2, U = voc_rate(S);
     constexpr int rate_in = S == 0 ? 1 : voc_cum_rate(S - 1), rate = voc_cum_rate(S);
@@ -267,24 +408,16 @@ void stage_launch(const VocoderPtrs& d, int n_windows, hipStream_t s)
     up.bias = d.up_b[S];
     up.dil = 1;
     conv_launch<XT, CIN, U * C, C, 3, EPI_UP, true, (S > 0), U>(up, d.len, rate_in, d.window, n_windows, s);
-    for (int p = 0; p < VOC_PAIRS; ++p) {
-        VcArgs3 c1{}, c2{};
-        for (int b = 0; b < VOC_BLOCKS; ++b) {
-            c1.b[b].in0 = p == 0 ? d.y : d.r[b];
-            c1.b[b].out = d.t[b];
-            c1.b[b].W = reinterpret_cast<const uint4*>(d.res_w[S][b][2 * p]);
-            c1.b[b].bias = d.res_b[S][b][2 * p];
-            c1.b[b].dil = voc_dil(p);
-            c2.b[b].in0 = d.t[b];
-            c2.b[b].res = p == 0 ? d.y : d.r[b];
-            c2.b[b].out = d.r[b];
-            c2.b[b].W = reinterpret_cast<const uint4*>(d.res_w[S][b][2 * p + 1]);
-            c2.b[b].bias = d.res_b[S][b][2 * p + 1];
-            c2.b[b].dil = 1;
+    VrArgs3 rb{};
+    for (int b = 0; b < VOC_BLOCKS; ++b) {
+        rb.b[b].in = d.y;
+        rb.b[b].out = d.r[b];
+        for (int i = 0; i < 2 * VOC_PAIRS; ++i) {
+            rb.b[b].W[i] = reinterpret_cast<const uint4*>(d.res_w[S][b][i]);
+            rb.b[b].bias[i] = d.res_b[S][b][i];
         }
-        blocks_launch<XT, C, EPI_PLAIN>(c1, d.len, rate, d.window, n_windows, s);
-        blocks_launch<XT, C, EPI_RESID>(c2, d.len, rate, d.window, n_windows, s);
     }
+    return blocks_launch<XT, C>(rb, d.len, rate, d.window, n_windows, s);
 }
 
 template <typename XT>
@@ -297,10 +430,11 @@ hipError_t generator_typed(const VocoderPtrs& d, int n_windows, hipStream_t s)
     pre.bias = d.pre_b;
     pre.dil = 1;
     conv_launch<XT, VOC_N_MEL, VOC_C0, VOC_C0, VOC_K_PRE, EPI_PLAIN, false, false, 1>(pre, d.len, 1, d.window, n_windows, s);
-    stage_launch<XT, 0>(d, n_windows, s);
-    stage_launch<XT, 1>(d, n_windows, s);
-    stage_launch<XT, 2>(d, n_windows, s);
-    stage_launch<XT, 3>(d, n_windows, s);
+    hipError_t e = stage_launch<XT, 0>(d, n_windows, s);
+    if (e == hipSuccess) e = stage_launch<XT, 1>(d, n_windows, s);
+    if (e == hipSuccess) e = stage_launch<XT, 2>(d, n_windows, s);
+    if (e == hipSuccess) e = stage_launch<XT, 3>(d, n_windows, s);
+    if (e != hipSuccess) return e;
     VcArgs post{};
     post.in0 = d.r[0];
     post.in1 = d.r[1];

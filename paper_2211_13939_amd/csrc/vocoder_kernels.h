@@ -35,8 +35,7 @@ struct VocoderPtrs {
     float* x_mel;       // [max_batch * window][n_mel]      the spliced windows
     float* x0;          // [max_batch * window][c0]         conv_pre output
     float* y;           // upsampled activations of the current stage, [positions][channels]
-    float* t[VOC_BLOCKS];   // first convolution of a pair
-    float* r[VOC_BLOCKS];   // residual stream of every block
+    float* r[VOC_BLOCKS];   // output of every residual block of the current stage
     float* audio;       // [max_batch * window * 256]       S_cur of every window
     int overlap, window;    // window = overlap + max_chunk frames: the stride between windows, in frames
 };

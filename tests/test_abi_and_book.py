@@ -117,7 +117,7 @@ def test_postnet_config_validation_without_gpu():
 
 def test_vocoder_config_validation_without_gpu():
     good = binding.make_vocoder_config(overlap=8, max_chunk=40, max_requests=16, max_batch=4)
-    assert binding.vocoder_workspace_bytes(good) > 4 * 48 * 2048 * 4 * 7          # seven activation buffers
+    assert binding.vocoder_workspace_bytes(good) > 4 * 48 * 2048 * 4 * 4          # four activation buffers
     bf = binding.make_vocoder_config(overlap=8, max_chunk=40, max_requests=16, max_batch=4, bf16=True)
     assert 0 < binding.vocoder_workspace_bytes(bf) < binding.vocoder_workspace_bytes(good)
     for field, bad in (("n_mel", 64), ("c0", 512), ("overlap", -1), ("overlap", 17), ("max_chunk", 0), ("max_chunk", 7),
