@@ -23,6 +23,7 @@ constexpr int VC_THREADS = 256;
 constexpr int VC_WAVES = VC_THREADS / 64;
 constexpr float VC_SLOPE = 0.1f;
 constexpr int VC_LDS_BYTES = 48 * 1024;
+constexpr int VC_AHEAD = 4;                  // k steps between the request for a weight fragment and its use
 
 enum { EPI_PLAIN = 0, EPI_UP = 2, EPI_POST = 3 };
 
@@ -35,10 +36,10 @@ template <typename XT, int CIN> struct VcGeom {
 };
 
 // positions per workgroup: as many as the accumulators (64 registers) and 48 KB of LDS allow
-template <typename XT, int CIN, int ROWS, int HALO> constexpr int vc_tp()
+template <typename XT, int CIN, int ROWS, int HALO, bool SHORT = false> constexpr int vc_tp()
 {
     constexpr int RT = ROWS / 16, RG = RT < 4 ? RT : 4;
-    int tp = 1024 / RG;
+    int tp = SHORT ? 64 : 1024 / RG;
     while (tp > 64 && (tp + 2 * HALO) * VcGeom<XT, CIN>::GPP * 16 > VC_LDS_BYTES) tp /= 2;
     return tp;
 }
@@ -53,7 +54,8 @@ struct VcArgs {
     int dil;
 };
 
-__device__ __forceinline__ float lrelu(float x) { return x > 0.f ? x : VC_SLOPE * x; }
+// slope < 1: the larger of x and slope * x
+__device__ __forceinline__ float lrelu(float x) { return fmaxf(x, VC_SLOPE * x); }
 
 template <typename XT> __device__ __forceinline__ void lds_put4(uint4* lds, int elem, float4 v);
 template <> __device__ __forceinline__ void lds_put4<float>(uint4* lds, int elem, float4 v)
@@ -108,29 +110,42 @@ __device__ __forceinline__ void conv_tile(const VcArgs& a, int valid, size_t wba
     __syncthreads();
 
     const int colbase = wave * (TP / VC_WAVES);
-#pragma unroll 1
-    for (int rt0 = 0; rt0 < RT; rt0 += RG) {
+    // The workgroup's share of the output rows: row group blockIdx.z.  Its weights stream from L2 / HBM through a
+    // ring of registers, requested VC_AHEAD k steps before they are used.
+    {
+        const int rt0 = blockIdx.z * RG;
         floatx4 acc[RG][CT];
 #pragma unroll
         for (int rg = 0; rg < RG; ++rg)
 #pragma unroll
             for (int ct = 0; ct < CT; ++ct) acc[rg][ct] = floatx4{0.f, 0.f, 0.f, 0.f};
         const uint4* Wl = a.W + (size_t)rt0 * NK * 64 + lane;
-#pragma unroll 4
+        constexpr int AHEAD = NK < VC_AHEAD ? NK : VC_AHEAD;
+        uint4 ring[AHEAD][RG];
+#pragma unroll
+        for (int d = 0; d < AHEAD; ++d)
+#pragma unroll
+            for (int rg = 0; rg < RG; ++rg) ring[d][rg] = Wl[((size_t)rg * NK + d) * 64];
+#pragma unroll
         for (int kf = 0; kf < NK; ++kf) {
             uint4 af[RG];
 #pragma unroll
-            for (int rg = 0; rg < RG; ++rg) af[rg] = Wl[((size_t)rg * NK + kf) * 64];
+            for (int rg = 0; rg < RG; ++rg) {
+                af[rg] = ring[kf % AHEAD][rg];
+                if (kf + AHEAD < NK) ring[kf % AHEAD][rg] = Wl[((size_t)rg * NK + kf + AHEAD) * 64];
+            }
             // this lane's 16 bytes of k: piece q = (tap, channel group); pieces past the end meet zero weights
             const int q = min(kf * 4 + g, NQ - 1);
             const int tap = q / G::GP, cg = q - tap * G::GP;
             const uint4* bl = lds + (colbase + n + tap * a.dil) * G::GPP + cg;
+            uint4 bv[CT];
 #pragma unroll
-            for (int ct = 0; ct < CT; ++ct) {
-                const uint4 bv = bl[ct * 16 * G::GPP];
+            for (int ct = 0; ct < CT; ++ct) bv[ct] = bl[ct * 16 * G::GPP];
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int rg = 0; rg < RG; ++rg) acc[rg][ct] = mfma_frag<XT>(af[rg], bv, acc[rg][ct]);
-            }
+            for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+                for (int rg = 0; rg < RG; ++rg) acc[rg][ct] = mfma_frag<XT>(af[rg], bv[ct], acc[rg][ct]);
         }
         // ---- epilogue: lane holds rows row0 .. row0 + 3 of column n of every tile
 #pragma unroll
@@ -163,10 +178,10 @@ __device__ __forceinline__ void conv_tile(const VcArgs& a, int valid, size_t wba
 }
 
 // grid = (tiles of a window, windows): one convolution of one kind
-template <typename XT, int CIN, int ROWS, int COUT, int KS, int EPI, bool PRE_ACT, bool SRC3, int U>
+template <typename XT, int CIN, int ROWS, int COUT, int KS, int EPI, bool PRE_ACT, bool SRC3, int U, bool SHORT>
 __global__ __launch_bounds__(VC_THREADS) void k_vconv(VcArgs a, const int* __restrict__ len, int rate, int window)
 {
-    constexpr int TP = vc_tp<XT, CIN, ROWS, (KS - 1) / 2>();
+    constexpr int TP = vc_tp<XT, CIN, ROWS, (KS - 1) / 2, SHORT>();
     __shared__ uint4 lds[(TP + 2 * ((KS - 1) / 2)) * VcGeom<XT, CIN>::GPP];
     const int w = blockIdx.y, valid = len[w] * rate, p0 = blockIdx.x * TP;
     if (p0 >= valid) return;
@@ -192,18 +207,26 @@ struct VrArgs {
 };
 struct VrArgs3 { VrArgs b[VOC_BLOCKS]; };
 
+constexpr int VR_LDS_MAX = 160 * 1024;
+
 template <typename XT, int C, int KS, int TP> struct VrGeom {
     static constexpr int HALF = (KS - 1) / 2;
     static constexpr int H = HALF * 12;                       // sum over d = 1, 3, 5 of (d + 1) * HALF
     static constexpr int NCOL = (TP + 2 * H + 63) / 64;       // column tiles per wave
     static constexpr int W = 64 * NCOL;                       // positions of the region
     static constexpr int PADR = HALF * 5;                     // zero rows on each side: the widest tap offset
-    static constexpr int BYTES = (W + 2 * PADR) * VcGeom<XT, C>::GPP * 16;
+    static constexpr int OPERAND_VECS = (W + 2 * PADR) * VcGeom<XT, C>::GPP;     // 16-byte pieces of the operand buffer
+    // one convolution's weights (A-fragment order) as 16-byte pieces; they go through LDS when both fit
+    static constexpr int W_VECS = ((C < 16 ? 16 : C) / 16) * ((KS * C + Frag<XT>::KB - 1) / Frag<XT>::KB) * 64;
+    static constexpr bool W_LDS = (OPERAND_VECS + W_VECS) * 16 <= VR_LDS_MAX;
+    static constexpr int BYTES = (OPERAND_VECS + (W_LDS ? W_VECS : 0)) * 16;
 };
 
-// positions per workgroup of the fused kernel: the region's accumulators (x and one convolution's output) fit the
-// register file, the operand buffer fits LDS
-template <int C> constexpr int vr_tp() { return C >= 64 ? 256 : (C >= 32 ? 512 : 1024); }
+// Positions per workgroup of the fused kernel.  The region's accumulators (x and one convolution's output) and the
+// operand buffer are sized so that two workgroups share a CU: while one is in a convolution (MFMA) the other can be
+// preparing an operand (VALU).  Small batches take half of that: more workgroups, each with a shorter chain.
+template <int C, bool SMALL> constexpr int vr_tp() { return (C >= 32 ? 256 : 512) / (SMALL ? 2 : 1); }
+constexpr int VR_SMALL_BELOW = 1024;             // workgroups of the large tiling below which the small one is used
 
 // acc[rt][ct] += W (rows rt, all k) * operand(columns of tile ct shifted by the taps)
 template <typename XT, int C, int KS, int NCOL, int PADR>
@@ -225,12 +248,15 @@ __device__ __forceinline__ void conv_regs(const uint4* __restrict__ Wf, int dil,
         const int q = min(kf * 4 + g, NQ - 1);
         const int tap = q / G::GP, cg = q - tap * G::GP;
         const uint4* bl = lds + (col0 + n + PADR + (tap - (KS - 1) / 2) * dil) * G::GPP + cg;
+        // all B fragments of this k step are requested before the first MFMA waits for one
+        uint4 bv[NCOL];
 #pragma unroll
-        for (int ct = 0; ct < NCOL; ++ct) {
-            const uint4 bv = bl[ct * 16 * G::GPP];
+        for (int ct = 0; ct < NCOL; ++ct) bv[ct] = bl[ct * 16 * G::GPP];
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int rt = 0; rt < RT; ++rt) acc[rt][ct] = mfma_frag<XT>(af[rt], bv, acc[rt][ct]);
-        }
+        for (int ct = 0; ct < NCOL; ++ct)
+#pragma unroll
+            for (int rt = 0; rt < RT; ++rt) acc[rt][ct] = mfma_frag<XT>(af[rt], bv[ct], acc[rt][ct]);
     }
 }
 
@@ -251,6 +277,26 @@ __device__ __forceinline__ void resblock_tile(const VrArgs& a, int valid, size_t
         const int r = idx / G::GPP, c = idx - r * G::GPP;
         lds[(r < R::PADR ? r : R::W + r) * G::GPP + c] = make_uint4(0, 0, 0, 0);
     }
+    // The weights of the next convolution are fetched into registers while the current one computes and
+    // handed to LDS together with its operand, so no MFMA loop waits for L2 (where they fit beside the operand).
+    constexpr int W_PER = (R::W_VECS + VC_THREADS - 1) / VC_THREADS;
+    uint4* wbuf = lds + R::OPERAND_VECS;
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    u32x4 wreg[R::W_LDS ? W_PER : 1];
+    auto fetch = [&](const uint4* __restrict__ Wg) __attribute__((always_inline)) {
+        if constexpr (R::W_LDS) {
+#pragma unroll
+            for (int i = 0; i < W_PER; ++i) wreg[i] = reinterpret_cast<const u32x4*>(Wg)[min(tid + i * VC_THREADS, R::W_VECS - 1)];
+        }
+    };
+    auto stash = [&]() __attribute__((always_inline)) {
+        if constexpr (R::W_LDS) {
+#pragma unroll
+            for (int i = 0; i < W_PER; ++i)
+                if (tid + i * VC_THREADS < R::W_VECS) reinterpret_cast<u32x4*>(wbuf)[tid + i * VC_THREADS] = wreg[i];
+        }
+    };
+    fetch(a.W[0]);
     floatx4 x[RT][NCOL];
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt)
@@ -262,28 +308,31 @@ __device__ __forceinline__ void resblock_tile(const VrArgs& a, int valid, size_t
             x[rt][ct] = v;
         }
     // operand of the next convolution: lrelu, zero outside the window, operand type
-    auto put = [&](const floatx4 (&v)[RT][NCOL]) {
+    const bool edge = pbase < 0 || pbase + R::W > valid;        // only tiles at a window's ends need the mask
+    auto put = [&](const floatx4 (&v)[RT][NCOL]) __attribute__((always_inline)) {
         if (!rows_ok) return;
 #pragma unroll
         for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
             for (int ct = 0; ct < NCOL; ++ct) {
                 const int j = col0 + ct * 16 + n, p = pbase + j;
-                const bool in = p >= 0 && p < valid;
+                const bool in = !edge || (p >= 0 && p < valid);
                 const float4 o = make_float4(in ? lrelu(v[rt][ct][0]) : 0.f, in ? lrelu(v[rt][ct][1]) : 0.f,
                                              in ? lrelu(v[rt][ct][2]) : 0.f, in ? lrelu(v[rt][ct][3]) : 0.f);
                 lds_put4<XT>(lds, (j + R::PADR) * G::CINP + rt * 16 + 4 * g, o);
             }
     };
-    auto bias_of = [&](const float* b, int rt) {
+    auto bias_of = [&](const float* b, int rt) __attribute__((always_inline)) {
         floatx4 v = {0.f, 0.f, 0.f, 0.f};
         if (rows_ok) v = *reinterpret_cast<const floatx4*>(b + rt * 16 + 4 * g);
         return v;
     };
+    put(x);
+    stash();
+    __syncthreads();
 #pragma unroll 1
     for (int pair = 0; pair < VOC_PAIRS; ++pair) {
-        put(x);
-        __syncthreads();
+        fetch(a.W[2 * pair + 1]);
         floatx4 t[RT][NCOL];
 #pragma unroll
         for (int rt = 0; rt < RT; ++rt) {
@@ -291,18 +340,25 @@ __device__ __forceinline__ void resblock_tile(const VrArgs& a, int valid, size_t
 #pragma unroll
             for (int ct = 0; ct < NCOL; ++ct) t[rt][ct] = b1;
         }
-        conv_regs<XT, C, KS, NCOL, R::PADR>(a.W[2 * pair], 2 * pair + 1, lds, col0, lane, t);
-        __syncthreads();                          // every wave has read the old operand
+        conv_regs<XT, C, KS, NCOL, R::PADR>(R::W_LDS ? wbuf : a.W[2 * pair], 2 * pair + 1, lds, col0, lane, t);
+        __syncthreads();                          // every wave has read the old operand and the old weights
         put(t);
+        stash();
         __syncthreads();
+        if (pair + 1 < VOC_PAIRS) fetch(a.W[2 * pair + 2]);
 #pragma unroll
         for (int rt = 0; rt < RT; ++rt) {
             const floatx4 b2 = bias_of(a.bias[2 * pair + 1], rt);
 #pragma unroll
             for (int ct = 0; ct < NCOL; ++ct) x[rt][ct] += b2;
         }
-        conv_regs<XT, C, KS, NCOL, R::PADR>(a.W[2 * pair + 1], 1, lds, col0, lane, x);
-        __syncthreads();
+        conv_regs<XT, C, KS, NCOL, R::PADR>(R::W_LDS ? wbuf : a.W[2 * pair + 1], 1, lds, col0, lane, x);
+        if (pair + 1 < VOC_PAIRS) {
+            __syncthreads();
+            put(x);
+            stash();
+            __syncthreads();
+        }
     }
     if (!rows_ok) return;
 #pragma unroll
@@ -369,19 +425,23 @@ __global__ __launch_bounds__(VOC_HOP) void k_voc_fade(VocBatch b, const float* _
     if (i < emit) d_audio[(size_t)b.out_off[w] + i] = v;
 }
 
-template <typename XT, int CIN, int ROWS, int COUT, int KS, int EPI, bool PRE_ACT, bool SRC3, int U>
+// grid = (tiles of a window, windows, row groups).  SHORT: the layer runs at one position per frame, where a window
+// is a few dozen positions long.
+template <typename XT, int CIN, int ROWS, int COUT, int KS, int EPI, bool PRE_ACT, bool SRC3, int U, bool SHORT>
 void conv_launch(const VcArgs& a, const int* len, int rate, int window, int n_windows, hipStream_t s)
 {
-    constexpr int TP = vc_tp<XT, CIN, ROWS, (KS - 1) / 2>();
-    const dim3 grid((window * rate + TP - 1) / TP, n_windows);
-    hipLaunchKernelGGL((k_vconv<XT, CIN, ROWS, COUT, KS, EPI, PRE_ACT, SRC3, U>), grid, dim3(VC_THREADS), 0, s, a, len, rate, window);
+    constexpr int TP = vc_tp<XT, CIN, ROWS, (KS - 1) / 2, SHORT>();
+    constexpr int RT = ROWS / 16, RG = RT < 4 ? RT : 4;
+    const dim3 grid((window * rate + TP - 1) / TP, n_windows, RT / RG);
+    hipLaunchKernelGGL((k_vconv<XT, CIN, ROWS, COUT, KS, EPI, PRE_ACT, SRC3, U, SHORT>), grid, dim3(VC_THREADS), 0, s, a, len, rate, window);
 }
 
-template <typename XT, int C>
-hipError_t blocks_launch(const VrArgs3& a, const int* len, int rate, int window, int n_windows, hipStream_t s)
+template <typename XT, int C, bool SMALL>
+hipError_t blocks_launch_tp(const VrArgs3& a, const int* len, int rate, int window, int n_windows, hipStream_t s)
 {
-    constexpr int TP = vr_tp<C>();
-    constexpr int LDS = VrGeom<XT, C, 11, TP>::BYTES;       // the widest of the three kernels
+    constexpr int TP = vr_tp<C, SMALL>();
+    constexpr int L3 = VrGeom<XT, C, 3, TP>::BYTES, L7 = VrGeom<XT, C, 7, TP>::BYTES, L11 = VrGeom<XT, C, 11, TP>::BYTES;
+    constexpr int LDS = L3 > L7 ? (L3 > L11 ? L3 : L11) : (L7 > L11 ? L7 : L11);      // the three kernels share a launch
     auto kern = k_vres<XT, C, TP>;
     static bool attr_set = false;                            // dynamic LDS above 64 KB has to be allowed once per kernel
     if (!attr_set) {
@@ -392,6 +452,14 @@ hipError_t blocks_launch(const VrArgs3& a, const int* len, int rate, int window,
     const dim3 grid((window * rate + TP - 1) / TP, n_windows, VOC_BLOCKS);
     hipLaunchKernelGGL(kern, grid, dim3(VC_THREADS), LDS, s, a, len, rate, window);
     return hipSuccess;
+}
+
+template <typename XT, int C>
+hipError_t blocks_launch(const VrArgs3& a, const int* len, int rate, int window, int n_windows, hipStream_t s)
+{
+    const long wgs = (long)((window * rate + vr_tp<C, false>() - 1) / vr_tp<C, false>()) * n_windows * VOC_BLOCKS;
+    return wgs < VR_SMALL_BELOW ? blocks_launch_tp<XT, C, true>(a, len, rate, window, n_windows, s)
+                                : blocks_launch_tp<XT, C, false>(a, len, rate, window, n_windows, s);
 }
 
 template <typename XT, int S>
@@ -407,7 +475,7 @@ hipError_t stage_launch(const VocoderPtrs& d, int n_windows, hipStream_t s)
     up.W = reinterpret_cast<const uint4*>(d.up_w[S]);
     up.bias = d.up_b[S];
     up.dil = 1;
-    conv_launch<XT, CIN, U * C, C, 3, EPI_UP, true, (S > 0), U>(up, d.len, rate_in, d.window, n_windows, s);
+    conv_launch<XT, CIN, U * C, C, 3, EPI_UP, true, (S > 0), U, (S == 0)>(up, d.len, rate_in, d.window, n_windows, s);
     VrArgs3 rb{};
     for (int b = 0; b < VOC_BLOCKS; ++b) {
         rb.b[b].in = d.y;
@@ -429,7 +497,7 @@ hipError_t generator_typed(const VocoderPtrs& d, int n_windows, hipStream_t s)
     pre.W = reinterpret_cast<const uint4*>(d.pre_w);
     pre.bias = d.pre_b;
     pre.dil = 1;
-    conv_launch<XT, VOC_N_MEL, VOC_C0, VOC_C0, VOC_K_PRE, EPI_PLAIN, false, false, 1>(pre, d.len, 1, d.window, n_windows, s);
+    conv_launch<XT, VOC_N_MEL, VOC_C0, VOC_C0, VOC_K_PRE, EPI_PLAIN, false, false, 1, true>(pre, d.len, 1, d.window, n_windows, s);
     hipError_t e = stage_launch<XT, 0>(d, n_windows, s);
     if (e == hipSuccess) e = stage_launch<XT, 1>(d, n_windows, s);
     if (e == hipSuccess) e = stage_launch<XT, 2>(d, n_windows, s);
@@ -443,7 +511,7 @@ hipError_t generator_typed(const VocoderPtrs& d, int n_windows, hipStream_t s)
     post.W = reinterpret_cast<const uint4*>(d.post_w);
     post.bias = d.post_b;
     post.dil = 1;
-    conv_launch<XT, voc_channels(VOC_STAGES - 1), 16, 1, VOC_K_POST, EPI_POST, true, true, 1>(post, d.len, VOC_HOP, d.window, n_windows, s);
+    conv_launch<XT, voc_channels(VOC_STAGES - 1), 16, 1, VOC_K_POST, EPI_POST, true, true, 1, false>(post, d.len, VOC_HOP, d.window, n_windows, s);
     return hipGetLastError();
 }
 
