@@ -130,11 +130,11 @@ def stream_arrivals(w5, kind, qps, n=None):
     return np.cumsum(rng.exponential(1.0 / qps, size=n))
 
 
-def stream_run(stream, pool5, w5, enc, arrival, join_every, max_pool, postnet=None):
+def stream_run(stream, pool5, w5, enc, arrival, join_every, max_pool, postnet=None, vocoder=None):
     n = len(arrival)
     n_steps = w5.n_steps[:n]
     if postnet is not None:
-        be = stream.GpuPostnetBackend(pool5, postnet, lambda i, e=enc: e[i], n_steps, w5.chunk_frames, 10)
+        be = stream.GpuPostnetBackend(pool5, postnet, lambda i, e=enc: e[i], n_steps, w5.chunk_frames, 10, vocoder=vocoder)
     else:
         be = stream.GpuBackend(pool5, lambda i, e=enc: e[i], n_steps, w5.chunk_frames)
     r = stream.simulate(be, arrival, n_steps, w5.chunk_frames, join_every=join_every, max_pool=max_pool)
@@ -454,12 +454,18 @@ def main():
         ws5, bs5 = synth.make_postnet_weights(bf16=True)
         pn5 = binding.Postnet(binding.make_postnet_config(max_columns=16 * 50, bf16=True), ws5, bs5, stream=pool5.stream)
         res["per_step_join_with_postnet"] = stream_run(stream, pool5, w5, enc5_dev, arrival, 1, 16, postnet=pn5)
+        # modules D and V: the post-processed chunk goes on through the vocoder (8 frames of overlap); the response is audio
+        voc5 = binding.Vocoder(binding.make_vocoder_config(overlap=8, max_chunk=w5.chunk_frames, max_requests=16, max_batch=16, bf16=True),
+                               synth.make_vocoder_weights(bf16=True), stream=pool5.stream)
+        res["per_step_join_with_postnet_and_vocoder"] = stream_run(stream, pool5, w5, enc5_dev, arrival, 1, 16, postnet=pn5, vocoder=voc5)
+        voc5.close()
         pn5.close()
         out["stream"] = {"workload": f"c5: {args.arrivals} arrivals at {args.qps:g}/s, {w5.n_requests} requests, L~U{{30..300}}, "
                                      "frames=4L, 40-frame chunks; encoder outputs resident in HBM "
                                      "(per_step_join_host_input: handed over from pageable host memory, PCIe copy "
                                      "included; per_step_join_with_postnet: each chunk also passes the chunk-level "
-                                     "PostNet on the device before it is copied out); rtf = last-chunk latency / audio duration at 256 samples per frame, "
+                                     "PostNet on the device before it is copied out; per_step_join_with_postnet_and_vocoder: the chunk then goes through the "
+                                     "vocoder on the device and the response is its 256 samples per frame); rtf = last-chunk latency / audio duration at 256 samples per frame, "
                                      "22.05 kHz (decoder only)",
                          **res, "paper_context": "first-chunk latency < 80 ms at 100 QPS, full pipeline, one A10"}
         pool5.close()

@@ -155,6 +155,12 @@ class GpuBackend(PoolBackend):
         return None, chunk_ids, fin_ids
 
     def retire(self, rid: int) -> None:
+        s = self.live.get(rid)
+        if s is not None and "vslot" in s:
+            self._free_slots.append(s["vslot"])
+        super().retire(rid)
+
+    def retire(self, rid: int) -> None:
         self.pool.retire(rid)
         self.live.pop(rid, None)
 
@@ -165,11 +171,22 @@ class GpuPostnetBackend(GpuBackend):
     them go through the PostNet as one dynamic batch (Sec. 2.2.2: each module batches the pool
     items it has to process), then one copy brings the post-processed chunks to the host."""
 
-    def __init__(self, pool, postnet, enc, n_steps, chunk: int, context: int, on_chunk=None):
-        """on_chunk(request index, first frame, frames [n, n_mel]) is called for every chunk handed out."""
+    def __init__(self, pool, postnet, enc, n_steps, chunk: int, context: int, on_chunk=None, vocoder=None, on_audio=None):
+        """on_chunk(request index, first frame, frames [n, n_mel]) is called for every chunk handed out.
+        With a vocoder (module V) the post-processed chunks of a round go on, still on the device, through
+        tts_vocoder_run as one dynamic batch (Eq. 3, Eq. 4: splice, generator, fade, state write-back) and the
+        responses are the waveform pieces: on_audio(request index, samples [m])."""
         super().__init__(pool, enc, n_steps, chunk)
         import torch
         self.postnet, self.context, self.on_chunk = postnet, context, on_chunk
+        self.vocoder, self.on_audio = vocoder, on_audio
+        if vocoder is not None:
+            cap_v = int(pool.cfg.max_pool)
+            assert vocoder.cfg.max_requests >= cap_v and vocoder.cfg.max_batch >= cap_v and vocoder.cfg.max_chunk >= chunk
+            self._free_slots = list(range(cap_v))[::-1]
+            hop = 256
+            self._d_audio = torch.empty(cap_v * (chunk + vocoder.cfg.overlap) * hop, dtype=torch.float32, device=pool.device)
+            self._h_audio = torch.empty(cap_v * (chunk + vocoder.cfg.overlap) * hop, dtype=torch.float32).pin_memory()
         cap = int(pool.cfg.max_pool)
         self._d_in = torch.empty((cap * (chunk + context), pool.n_mel), dtype=torch.float32, device=pool.device)
         self._d_out = torch.empty((cap * chunk, pool.n_mel), dtype=torch.float32, device=pool.device)
@@ -182,7 +199,7 @@ class GpuPostnetBackend(GpuBackend):
         chunk_ids, fin_ids = [], []
         span = self.chunk + self.context
         while True:                         # a request that ends may hand out a full chunk and then its rest
-            lens, keeps, row, out_rows, handed = [], [], 0, 0, []
+            lens, keeps, row, out_rows, handed, voc = [], [], 0, 0, [], []
             for rid, s in self.live.items():
                 ready = s["done"] - s["drained"] >= self.chunk or s["done"] == s["total"]
                 if not ready or rid in fin_ids or row + span > self._d_in.shape[0]:
@@ -193,17 +210,39 @@ class GpuPostnetBackend(GpuBackend):
                     keeps.append(c)
                     row += c + n
                     handed.append((s["index"], s["drained"], out_rows, n))
+                    if self.vocoder is not None:
+                        if "vslot" not in s:
+                            s["vslot"] = self._free_slots.pop()
+                            first = 1
+                        else:
+                            first = 0
+                        voc.append((n, s["vslot"], first | (2 if fin else 0), s["index"]))
                     out_rows += n
                     s["drained"] += n
                     if rid not in chunk_ids:
                         chunk_ids.append(rid)
                 if fin:
+                    # the request's last frames always leave with a chunk of their own: the vocoder's LAST flag rides on it
+                    assert n > 0 or self.vocoder is None or "vslot" not in s
                     fin_ids.append(rid)
             if not lens:
                 break
             self.postnet.run_device(self._d_in, lens, keeps, self._d_out)
-            with self.pool._torch.cuda.stream(self.pool.stream):
-                self._h_out[:out_rows].copy_(self._d_out[:out_rows], non_blocking=True)
+            if self.vocoder is not None:
+                n_out = self.vocoder.run_device(self._d_out, [v[0] for v in voc], [v[1] for v in voc], [v[2] for v in voc],
+                                                self._d_audio)
+                total = sum(n_out)
+                with self.pool._torch.cuda.stream(self.pool.stream):
+                    self._h_audio[:total].copy_(self._d_audio[:total], non_blocking=True)
+                if self.on_audio is not None:
+                    self.pool.sync()
+                    host, at = self._h_audio.numpy(), 0
+                    for (_, _, _, index), m in zip(voc, n_out):
+                        self.on_audio(index, host[at:at + m].copy())
+                        at += m
+            if self.vocoder is None or self.on_chunk is not None:
+                with self.pool._torch.cuda.stream(self.pool.stream):
+                    self._h_out[:out_rows].copy_(self._d_out[:out_rows], non_blocking=True)
             if self.on_chunk is not None:
                 self.pool.sync()
                 host = self._h_out.numpy()
@@ -211,3 +250,9 @@ class GpuPostnetBackend(GpuBackend):
                     self.on_chunk(index, first, host[r0:r0 + n].copy())
         self.pool.sync()
         return None, chunk_ids, fin_ids
+
+    def retire(self, rid: int) -> None:
+        s = self.live.get(rid)
+        if s is not None and "vslot" in s:
+            self._free_slots.append(s["vslot"])
+        super().retire(rid)

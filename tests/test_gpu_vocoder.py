@@ -3,7 +3,7 @@ import numpy as np
 import pytest
 
 from paper_2211_13939_amd import binding, synth
-from tests.helpers import TOL_BF16, TOL_F32, say
+from tests.helpers import TOL_BF16, TOL_F32, make_pool, say
 
 pytestmark = pytest.mark.gpu
 
@@ -159,3 +159,44 @@ def test_bad_calls_are_rejected_and_change_nothing():
     with pytest.raises(binding.TtsError):
         voc.run([m], [0], [0])                 # closed by LAST
     voc.close()
+
+
+def test_serving_loop_decoder_postnet_vocoder_matches_oracle(weights_fp32):
+    """Modules D and V behind each other in the arrival-driven loop: five requests arriving over time into a pool
+    of three slots, chunks of 12 frames, overlap 4.  Every request's waveform (its responses in order) equals the
+    oracle's: decoder alone, PostNet on the utterance so far, vocoder stream with splice, fade and write-back."""
+    from oracle import oracle as orc
+    from paper_2211_13939_amd import stream
+    n, chunk, ov = 5, 12, 4
+    wl = synth.small_workload(n, 10, 50, 13, 40, seed=53)
+    pool = make_pool(wl, weights_fp32, chunk_frames=chunk, max_pool=3)
+    ws, bs = synth.make_postnet_weights()
+    wv = synth.make_vocoder_weights()
+    pn = binding.Postnet(binding.make_postnet_config(max_columns=3 * (chunk + binding.POSTNET_CONTEXT)), ws, bs, stream=pool.stream)
+    voc = binding.Vocoder(binding.make_vocoder_config(overlap=ov, max_chunk=chunk, max_requests=3, max_batch=3), wv, stream=pool.stream)
+    audio = {i: [] for i in range(n)}
+    be = stream.GpuPostnetBackend(pool, pn, lambda i: wl.encoder_outputs(i), wl.n_steps, chunk, binding.POSTNET_CONTEXT,
+                                  vocoder=voc, on_audio=lambda i, a: audio[i].append(a))
+    say(f"case serving loop decoder -> postnet -> vocoder: steps {wl.n_steps.tolist()}, pool of 3, chunks of {chunk}, overlap {ov}")
+    res = stream.simulate(be, np.array([0.0, 0.0, 1e-4, 1e-4, 4e-3]), wl.n_steps, chunk, join_every=1, max_pool=3)
+    assert not np.isnan(res.last_chunk_latency_s).any()
+    Wp, Wd, Wv = orc.PostnetWeights(ws, bs), orc.Weights(weights_fp32), orc.VocoderWeights(wv)
+    worst = 0.0
+    for i in range(n):
+        T = int(wl.n_steps[i])
+        mel, _, _, _ = orc.pool_decode(wl.dims, Wd, [wl.encoder_outputs(i)], [T], T)
+        vs = orc.VocoderStream(Wv, ov)
+        want = []
+        for s0 in range(0, T, chunk):
+            e0 = min(T, s0 + chunk)
+            want.append(vs.chunk(orc.postnet_chunk(Wp, mel[0, :e0], s0), e0 == T))
+        assert [a.shape[0] for a in audio[i]] == [w.shape[0] for w in want], i
+        got = np.concatenate(audio[i])
+        assert got.shape == (T * HOP,)
+        worst = max(worst, float(np.abs(got - np.concatenate(want)).max()))
+    say(f"  max abs err {worst:.3e}")
+    # the decoder's error (<= 1e-4 per mel bin) passes through the PostNet (gain about 5) and the generator
+    assert worst <= 1e-3
+    voc.close()
+    pn.close()
+    pool.close()
