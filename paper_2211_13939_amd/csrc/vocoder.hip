@@ -222,9 +222,10 @@ template <typename XT, int C, int KS, int TP> struct VrGeom {
     static constexpr int BYTES = (OPERAND_VECS + (W_LDS ? W_VECS : 0)) * 16;
 };
 
-// Positions per workgroup of the fused kernel.  The region's accumulators (x and one convolution's output) and the
-// operand buffer are sized so that two workgroups share a CU: while one is in a convolution (MFMA) the other can be
-// preparing an operand (VALU).  Small batches take half of that: more workgroups, each with a shorter chain.
+// Positions per workgroup of the fused kernel.  Up to 32 channels the region's accumulators (x and one convolution's
+// output) and the operand buffer are small enough for two workgroups to share a CU: while one is in a convolution
+// (MFMA) the other can be preparing an operand (VALU).  Small batches take half of that: more workgroups, each with
+// a shorter chain.
 template <int C, bool SMALL> constexpr int vr_tp() { return (C >= 32 ? 256 : 512) / (SMALL ? 2 : 1); }
 constexpr int VR_SMALL_BELOW = 1024;             // workgroups of the large tiling below which the small one is used
 
