@@ -98,6 +98,12 @@ def _declare(L: C.CDLL) -> None:
     L.orc_conv_transpose1d.argtypes = [C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, _fp, _fp, _dp, _dp]
     L.orc_generator.argtypes = [C.POINTER(OrcGenerator), C.c_int, _dp, _dp]
     L.orc_fade.argtypes = [C.c_int, _dp, _dp]
+    _ipp, _fpp = C.POINTER(_ip), C.POINTER(_fp)
+    L.orc_encoder_embed.argtypes = [C.c_int, C.c_int, C.c_int, _fpp, _ipp, _dp]
+    L.orc_encoder_conv_relu.argtypes = [C.c_int, C.c_int, C.c_int, C.c_int, _fp, _fp, _dp, _dp]
+    L.orc_bilstm.argtypes = [C.c_int, C.c_int, C.c_int, _fp, _fp, _fp, _fp, _fp, _fp, _dp, _dp]
+    L.orc_encoder.argtypes = [C.c_int, C.c_int, C.c_int, C.c_int, _fpp, _ipp, C.c_int, C.c_int, _fpp, _fpp,
+                              _fp, _fp, _fp, _fp, _fp, _fp, _dp]
     L.orc_crossfade.argtypes = [C.c_int, _dp, _dp, _dp]
 
 
@@ -437,3 +443,78 @@ class VocoderStream:
             return body
         hold = min(ov, m_cur.shape[0]) * hop
         return body[: body.shape[0] - hold]
+
+
+# ---- acoustic encoder (oracle/encoder_oracle.c)
+class EncoderWeights:
+    """w: dict with tables (list of [vocab_t, dim]), conv_w (list of [dim, dim, 5]), conv_b, and per direction
+    d in ('f', 'b'): w_ih_d [4 hid, dim], w_hh_d [4 hid, hid], b_d [4 hid].  fp32."""
+
+    def __init__(self, w: dict):
+        c32 = lambda a: np.ascontiguousarray(a, np.float32)
+        self.tables = [c32(a) for a in w["tables"]]
+        self.conv_w = [c32(a) for a in w["conv_w"]]
+        self.conv_b = [c32(a) for a in w["conv_b"]]
+        self.lstm = {k: c32(w[k]) for k in ("w_ih_f", "w_hh_f", "b_f", "w_ih_b", "w_hh_b", "b_b")}
+        self.dim = self.tables[0].shape[1]
+        self.hid = self.lstm["w_hh_f"].shape[1]
+        self.ksz = self.conv_w[0].shape[2]
+        assert all(t.shape[1] == self.dim for t in self.tables)
+        assert all(a.shape == (self.dim, self.dim, self.ksz) for a in self.conv_w)
+        assert self.lstm["w_ih_f"].shape == (4 * self.hid, self.dim) and self.lstm["w_hh_b"].shape == (4 * self.hid, self.hid)
+        self._tables = (_fp * len(self.tables))(*[_f(a) for a in self.tables])
+        self._cw = (_fp * len(self.conv_w))(*[_f(a) for a in self.conv_w])
+        self._cb = (_fp * len(self.conv_b))(*[_f(a) for a in self.conv_b])
+
+
+def _ids(ids, n_tables):
+    ids = np.ascontiguousarray(ids, np.int32)
+    assert ids.ndim == 2 and ids.shape[0] == n_tables
+    rows = [np.ascontiguousarray(ids[t]) for t in range(n_tables)]
+    return rows, (_ip * n_tables)(*[r.ctypes.data_as(_ip) for r in rows])
+
+
+def encoder_embed(W: EncoderWeights, ids):
+    rows, ptrs = _ids(ids, len(W.tables))
+    L = rows[0].shape[0]
+    for r, t in zip(rows, W.tables):
+        assert r.min(initial=0) >= 0 and r.max(initial=0) < t.shape[0]
+    E = np.zeros((L, W.dim), np.float64)
+    lib().orc_encoder_embed(L, W.dim, len(W.tables), C.cast(W._tables, C.POINTER(_fp)), C.cast(ptrs, C.POINTER(_ip)), _d(E))
+    return E
+
+
+def encoder_conv_relu(w, b, x):
+    w, b = np.ascontiguousarray(w, np.float32), np.ascontiguousarray(b, np.float32)
+    x = np.ascontiguousarray(x, np.float64)
+    L, c_in = x.shape
+    c_out, _, k = w.shape
+    y = np.zeros((L, c_out), np.float64)
+    lib().orc_encoder_conv_relu(L, c_in, c_out, k, _f(w), _f(b), _d(x), _d(y))
+    return y
+
+
+def bilstm(lstm: dict, x):
+    x = np.ascontiguousarray(x, np.float64)
+    L, in_dim = x.shape
+    c32 = lambda a: np.ascontiguousarray(a, np.float32)
+    w = {k: c32(v) for k, v in lstm.items()}
+    hid = w["w_hh_f"].shape[1]
+    out = np.zeros((L, 2 * hid), np.float64)
+    lib().orc_bilstm(L, in_dim, hid, _f(w["w_ih_f"]), _f(w["w_hh_f"]), _f(w["b_f"]), _f(w["w_ih_b"]), _f(w["w_hh_b"]),
+                     _f(w["b_b"]), _d(x), _d(out))
+    return out
+
+
+def encoder(W: EncoderWeights, ids):
+    """F_enc [L, 2 hid] of one request from its id sequences ids [n_tables, L] (Eq. 1)."""
+    rows, ptrs = _ids(ids, len(W.tables))
+    L = rows[0].shape[0]
+    for r, t in zip(rows, W.tables):
+        assert r.min(initial=0) >= 0 and r.max(initial=0) < t.shape[0]
+    out = np.zeros((L, 2 * W.hid), np.float64)
+    l = W.lstm
+    lib().orc_encoder(L, W.dim, W.hid, len(W.tables), C.cast(W._tables, C.POINTER(_fp)), C.cast(ptrs, C.POINTER(_ip)),
+                      len(W.conv_w), W.ksz, C.cast(W._cw, C.POINTER(_fp)), C.cast(W._cb, C.POINTER(_fp)),
+                      _f(l["w_ih_f"]), _f(l["w_hh_f"]), _f(l["b_f"]), _f(l["w_ih_b"]), _f(l["w_hh_b"]), _f(l["b_b"]), _d(out))
+    return out

@@ -157,6 +157,36 @@ def make_vocoder_weights(seed: int = 1236, bf16: bool = False, n_mel: int = 80, 
     return w
 
 
+ENCODER = dict(dim=512, hid=256, n_conv=3, kernel=5, vocab=(128, 4, 4, 4))
+
+
+def make_encoder_weights(seed: int = 1237, bf16: bool = False, dim: int = 512, hid: int = 256, n_conv: int = 3,
+                         vocab=(128, 4, 4, 4)):
+    """Encoder stand-in (Eq. 1): four embedding tables (tokens, pw, pph, iph) ~ N(0, 0.5^2), convolutions
+    [dim, dim, 5] ~ N(0, 2 / fan_in) (ReLU keeps the scale), biases ~ N(0, 0.02^2), LSTM matrices ~ N(0, 1 / fan_in)
+    per direction with one merged bias ~ N(0, 0.05^2); matrices and tables rounded to bf16 values when bf16."""
+    rng = np.random.default_rng(seed)
+
+    def mat(shape, std):
+        w = (rng.standard_normal(shape) * std).astype(np.float32)
+        return np.ascontiguousarray(round_to_bf16(w) if bf16 else w)
+
+    w = dict(tables=[mat((v, dim), 0.5) for v in vocab],
+             conv_w=[mat((dim, dim, ENCODER["kernel"]), np.sqrt(2.0 / (dim * ENCODER["kernel"]))) for _ in range(n_conv)],
+             conv_b=[np.ascontiguousarray((rng.standard_normal(dim) * 0.02).astype(np.float32)) for _ in range(n_conv)])
+    for d in ("f", "b"):
+        w["w_ih_" + d] = mat((4 * hid, dim), 1.0 / np.sqrt(dim))
+        w["w_hh_" + d] = mat((4 * hid, hid), 1.0 / np.sqrt(hid))
+        w["b_" + d] = np.ascontiguousarray((rng.standard_normal(4 * hid) * 0.05).astype(np.float32))
+    return w
+
+
+def encoder_ids(L: int, seed: int, vocab=(128, 4, 4, 4)) -> np.ndarray:
+    """Id sequences of one request, int32 [4, L]: phoneme tokens and the three prosodic-structure tokens."""
+    rng = np.random.default_rng([seed, 104729, int(L)])
+    return np.stack([rng.integers(0, v, size=L) for v in vocab]).astype(np.int32)
+
+
 @dataclass
 class Workload:
     """One synthetic job: per-request encoder lengths, step counts and outputs."""

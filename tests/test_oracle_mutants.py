@@ -102,7 +102,7 @@ def _build_variant(src_text: str, workdir: str, name: str):
     with open(c, "w") as f:
         f.write(src_text)
     subprocess.run(["gcc", "-O1", "-std=c99", "-fPIC", "-shared", "-fopenmp", "-w", "-o", so, c, obuild.SRC_POSTNET,
-                    obuild.SRC_VOCODER, "-lm"], check=True)
+                    obuild.SRC_VOCODER, obuild.SRC_ENCODER, "-lm"], check=True)
     return orc.load(so)
 
 
@@ -195,7 +195,7 @@ def _build_vocoder_variant(src_text: str, workdir: str, name: str):
     with open(c, "w") as f:
         f.write(src_text)
     subprocess.run(["gcc", "-O1", "-std=c99", "-fPIC", "-shared", "-fopenmp", "-w", "-o", so, obuild.SRC, obuild.SRC_POSTNET,
-                    c, "-lm"], check=True)
+                    c, obuild.SRC_ENCODER, "-lm"], check=True)
     return orc.load(so)
 
 
@@ -216,3 +216,70 @@ def test_vocoder_pins_catch_planted_mistake(name, vocoder_source):
     with tempfile.TemporaryDirectory() as tmp:
         lib = _build_vocoder_variant(vocoder_source.replace(old, new), tmp, "mutant")
         assert _pins_fail(lib, VOCODER_PINS), f"no pin noticed: {name}"
+
+
+# ---- the encoder oracle (oracle/encoder_oracle.c), same method
+from tests import test_encoder_oracle as epins
+
+ENCODER_MUTANTS = {
+    "one embedding table left out":
+        ("for (int t = 0; t < n_tables; ++t) s +=", "for (int t = 0; t < n_tables - 1; ++t) s +="),
+    "every id sequence reads the token table":
+        ("tables[t][(size_t)ids[t][j] * dim + d]", "tables[0][(size_t)(ids[t][j] % 3) * dim + d]"),
+    "convolution flipped":
+        ("int jj = j + k - half;", "int jj = j - k + half;"),
+    "no relu":
+        ("y[(size_t)j * c_out + co] = s > 0.0 ? s : 0.0;", "y[(size_t)j * c_out + co] = s;"),
+    "convolution bias dropped":
+        ("double s = (double)b[co];", "double s = 0.0;"),
+    "backward direction runs forwards":
+        ("for (int j = L - 1; j >= 0; --j) {", "for (int j = 0; j < L; ++j) {"),
+    "backward direction keeps the forward state":
+        ("    memset(h, 0, sizeof(double) * hid);\n    memset(c, 0, sizeof(double) * hid);\n", ""),
+    "halves of the output swapped":
+        ("memcpy(out + (size_t)j * 2 * hid, h, sizeof(double) * hid);\n    }\n    memset",
+         "memcpy(out + (size_t)j * 2 * hid + hid, h, sizeof(double) * hid);\n    }\n    memset"),
+    "backward direction uses the forward weights":
+        ("orc_lstm_cell(in_dim, hid, W_ih_b, W_hh_b, b_b,", "orc_lstm_cell(in_dim, hid, W_ih_f, W_hh_f, b_f,"),
+    "one convolution layer skipped":
+        ("for (int l = 0; l < n_conv; ++l) {", "for (int l = 1; l < n_conv; ++l) {"),
+}
+
+ENCODER_PINS = [
+    lambda: epins.test_embedding_sum_is_indexing(),
+    lambda: [epins.test_conv_relu_equals_library_routine(L) for L in (1, 5, 23)],
+    lambda: epins.test_conv_orientation_by_hand(),
+    lambda: [epins.test_bilstm_equals_library_routine(L) for L in (1, 9)],
+    lambda: epins.test_bilstm_directions_mirror_each_other(),
+    lambda: epins.test_bilstm_zero_weights_closed_form(),
+    lambda: [epins.test_encoder_equals_composition_of_library_routines(L) for L in (1, 30)],
+]
+
+
+def _build_encoder_variant(src_text: str, workdir: str, name: str):
+    c = os.path.join(workdir, name + ".c")
+    so = os.path.join(workdir, name + ".so")
+    with open(c, "w") as f:
+        f.write(src_text)
+    subprocess.run(["gcc", "-O1", "-std=c99", "-fPIC", "-shared", "-fopenmp", "-w", "-o", so, obuild.SRC, obuild.SRC_POSTNET,
+                    obuild.SRC_VOCODER, c, "-lm"], check=True)
+    return orc.load(so)
+
+
+@pytest.fixture(scope="module")
+def encoder_source():
+    return open(obuild.SRC_ENCODER).read()
+
+
+def test_unmodified_encoder_source_passes_every_pin(encoder_source):
+    with tempfile.TemporaryDirectory() as tmp:
+        assert not _pins_fail(_build_encoder_variant(encoder_source, tmp, "clean"), ENCODER_PINS)
+
+
+@pytest.mark.parametrize("name", sorted(ENCODER_MUTANTS))
+def test_encoder_pins_catch_planted_mistake(name, encoder_source):
+    old, new = ENCODER_MUTANTS[name]
+    assert encoder_source.count(old) == 1, f"mutation site for '{name}' not found exactly once"
+    with tempfile.TemporaryDirectory() as tmp:
+        lib = _build_encoder_variant(encoder_source.replace(old, new), tmp, "mutant")
+        assert _pins_fail(lib, ENCODER_PINS), f"no pin noticed: {name}"
