@@ -42,6 +42,8 @@ EXPORTS = (
     "tts_postnet_destroy",
     "tts_vocoder_workspace_bytes", "tts_vocoder_create", "tts_vocoder_run", "tts_vocoder_elapsed_ms",
     "tts_vocoder_destroy",
+    "tts_encoder_workspace_bytes", "tts_encoder_create", "tts_encoder_run", "tts_encoder_elapsed_ms",
+    "tts_encoder_destroy",
 )
 
 _fp = C.POINTER(C.c_float)
@@ -72,6 +74,15 @@ class TtsVocoderConfig(C.Structure):
 class TtsVocoderWeights(C.Structure):
     _fields_ = [("pre_w", _fp), ("pre_b", _fp), ("up_w", _fp * 4), ("up_b", _fp * 4),
                 ("res_w", _fp * 6 * 3 * 4), ("res_b", _fp * 6 * 3 * 4), ("post_w", _fp), ("post_b", _fp)]
+
+
+class TtsEncoderConfig(C.Structure):
+    _fields_ = [("dim", C.c_int), ("hid", C.c_int), ("vocab", C.c_int * 4), ("max_tokens", C.c_int), ("max_len", C.c_int),
+                ("weight_dtype", C.c_int)]
+
+
+class TtsEncoderWeights(C.Structure):
+    _fields_ = [("tables", _fp * 4), ("conv_w", _fp * 3), ("conv_b", _fp * 3), ("w_ih", _fp * 2), ("w_hh", _fp * 2), ("b", _fp * 2)]
 
 
 VOCODER_HOP = 256
@@ -146,6 +157,14 @@ def lib() -> C.CDLL:
     L.tts_vocoder_elapsed_ms.argtypes = [vp, _fp]
     L.tts_vocoder_destroy.restype = None
     L.tts_vocoder_destroy.argtypes = [vp]
+    L.tts_encoder_workspace_bytes.restype = C.c_size_t
+    L.tts_encoder_workspace_bytes.argtypes = [C.POINTER(TtsEncoderConfig)]
+    L.tts_encoder_create.argtypes = [C.POINTER(TtsEncoderConfig), C.POINTER(TtsEncoderWeights), vp, C.c_size_t, vp,
+                                     C.POINTER(vp)]
+    L.tts_encoder_run.argtypes = [vp, _ip, _ip, C.c_int, vp]
+    L.tts_encoder_elapsed_ms.argtypes = [vp, _fp]
+    L.tts_encoder_destroy.restype = None
+    L.tts_encoder_destroy.argtypes = [vp]
     _lib = L
     return L
 
@@ -530,6 +549,93 @@ class Vocoder:
     def close(self) -> None:
         if getattr(self, "_h", None):
             lib().tts_vocoder_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def make_encoder_config(max_tokens: int, max_len: int, bf16: bool = False, vocab=(128, 4, 4, 4), dim: int = 512,
+                        hid: int = 256) -> TtsEncoderConfig:
+    return TtsEncoderConfig(dim, hid, (C.c_int * 4)(*vocab), int(max_tokens), int(max_len), DTYPE_BF16 if bf16 else DTYPE_F32)
+
+
+def encoder_workspace_bytes(cfg: TtsEncoderConfig) -> int:
+    return int(lib().tts_encoder_workspace_bytes(C.byref(cfg)))
+
+
+class Encoder:
+    """tts_encoder_* calls; owns its torch arena.  `weights` is the dict of synth.make_encoder_weights."""
+
+    def __init__(self, cfg: TtsEncoderConfig, weights: dict, stream=None, device: str = "cuda:0"):
+        import torch
+        if not torch.cuda.is_available():
+            raise RuntimeError("no GPU visible: the encoder has no CPU path")
+        self._torch = torch
+        self.cfg = cfg
+        self.device = torch.device(device)
+        nbytes = encoder_workspace_bytes(cfg)
+        if nbytes == 0:
+            _check(TTS_E_INVAL)
+        with torch.cuda.device(self.device):
+            self.arena = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+            self.stream = stream if stream is not None else torch.cuda.Stream(device=self.device)
+        keep = []
+
+        def ptr(a):
+            a = np.ascontiguousarray(a, np.float32)
+            keep.append(a)
+            return a.ctypes.data_as(_fp)
+
+        w = TtsEncoderWeights()
+        for t in range(4):
+            w.tables[t] = ptr(weights["tables"][t])
+        for i in range(3):
+            w.conv_w[i], w.conv_b[i] = ptr(weights["conv_w"][i]), ptr(weights["conv_b"][i])
+        for d, k in enumerate(("f", "b")):
+            w.w_ih[d], w.w_hh[d], w.b[d] = ptr(weights["w_ih_" + k]), ptr(weights["w_hh_" + k]), ptr(weights["b_" + k])
+        h = C.c_void_p()
+        with torch.cuda.device(self.device):
+            _check(lib().tts_encoder_create(C.byref(cfg), C.byref(w), C.c_void_p(self.arena.data_ptr()), nbytes,
+                                            C.c_void_p(self.stream.cuda_stream), C.byref(h)))
+        self._h = h
+
+    def run_device(self, ids_list, d_out) -> list:
+        """ids_list: one int array [4, L_i] per request; d_out: CUDA fp32 [>= sum L_i, 2 hid].  Queued on the stream;
+        returns the first row of every request in d_out."""
+        lens = np.ascontiguousarray([a.shape[1] for a in ids_list], np.int32)
+        ids = np.ascontiguousarray(np.concatenate([np.asarray(a, np.int32) for a in ids_list], axis=1))   # [4, total]
+        total = int(lens.sum())
+        assert ids.shape == (4, total)
+        assert d_out.is_cuda and d_out.is_contiguous() and d_out.dtype == self._torch.float32
+        assert d_out.numel() >= total * 2 * self.cfg.hid
+        _check(lib().tts_encoder_run(self._h, ids.ctypes.data_as(_ip), lens.ctypes.data_as(_ip), int(lens.shape[0]),
+                                     C.c_void_p(d_out.data_ptr())))
+        return [int(x) for x in np.concatenate([[0], np.cumsum(lens)[:-1]])]
+
+    def run(self, ids_list) -> list:
+        """Returns F_enc of every request as numpy [L_i, 2 hid]."""
+        torch = self._torch
+        total = sum(a.shape[1] for a in ids_list)
+        with torch.cuda.stream(self.stream):
+            d_out = torch.empty((max(total, 1), 2 * self.cfg.hid), dtype=torch.float32, device=self.device)
+        self.stream.synchronize()
+        starts = self.run_device(ids_list, d_out)
+        self.stream.synchronize()
+        out = d_out.cpu().numpy()
+        return [out[s:s + a.shape[1]] for s, a in zip(starts, ids_list)]
+
+    def elapsed_ms(self) -> float:
+        ms = C.c_float()
+        _check(lib().tts_encoder_elapsed_ms(self._h, C.byref(ms)))
+        return ms.value
+
+    def close(self) -> None:
+        if getattr(self, "_h", None):
+            lib().tts_encoder_destroy(self._h)
             self._h = None
 
     def __del__(self):

@@ -7,7 +7,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "libtts_pool.so")
-SOURCES = ["kernels.hip", "tts_pool.cpp", "postnet.hip", "postnet.cpp", "vocoder.hip", "vocoder.cpp"]
+SOURCES = ["kernels.hip", "tts_pool.cpp", "postnet.hip", "postnet.cpp", "vocoder.hip", "vocoder.cpp", "encoder.hip", "encoder.cpp"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -26,6 +26,7 @@ def stale() -> bool:
     deps.append(os.path.join(HERE, "..", "include", "tts_pool.h"))
     deps.append(os.path.join(HERE, "..", "include", "tts_postnet.h"))
     deps.append(os.path.join(HERE, "..", "include", "tts_vocoder.h"))
+    deps.append(os.path.join(HERE, "..", "include", "tts_encoder.h"))
     return any(os.path.getmtime(d) > t for d in deps)
 
 

@@ -1,0 +1,211 @@
+// Acoustic encoder kernels (Sec. 2.1.2, Eq. 1) for a ragged batch of requests whose tokens are packed back to back:
+//   k_enc_embed   E_all = sum of the four embedding rows of every token, stored as the first convolution's input
+//   (conv5_kernels.h: three kernel-5 convolutions with ReLU, "same" padding inside each request)
+//   k_enc_xproj   W_ih x + b for every token and both directions: the part of the LSTM that has no recurrence
+//   k_enc_lstm    the recurrence, one workgroup per direction and group of 16 requests
+//
+// The recurrence is a chain of L dependent steps of a 1024 x 256 matrix-vector product: latency, not bandwidth.
+// In bf16 the matrix of one direction (512 KB) is made resident in ONE compute unit -- six of its eight k fragments
+// in the registers of the workgroup's four waves (384 of the 512 registers a lane may have at one wave per SIMD),
+// the other two in 128 KB of LDS -- so a step touches no memory beyond the 16 KB of precomputed input projections.
+// The hidden state goes round through 8 KB of LDS in B-fragment order; the 16 MFMA columns are 16 requests.
+// Gate rows are stored unit-major / gate-minor, so a lane's four accumulator rows are the i, f, g, o of one unit
+// and the cell update needs no exchange.  (fp32 matrices do not fit a compute unit: they stream from L2 every step.)
+#include "encoder_kernels.h"
+
+#include "conv5_kernels.h"
+
+namespace tts {
+namespace {
+
+struct EncTables { const float* t[ENC_TABLES]; };
+
+template <typename XT>
+__global__ __launch_bounds__(256) void k_enc_embed(EncTables tb, const int* __restrict__ ids, int max_tokens, int n_col,
+                                                   int n_col_pad, XT* __restrict__ X)
+{
+    constexpr int KB = Frag<XT>::KB;
+    const int idx = blockIdx.x * 256 + threadIdx.x;
+    const int col = idx / ENC_DIM, ch = idx - col * ENC_DIM;
+    if (col >= n_col_pad) return;
+    float v = 0.f;
+    if (col < n_col) {
+#pragma unroll
+        for (int t = 0; t < ENC_TABLES; ++t) v += tb.t[t][(size_t)ids[(size_t)t * max_tokens + col] * ENC_DIM + ch];
+    }
+    X[xoff<XT>(ENC_DIM / KB, col, ch)] = from_float<XT>(v);
+}
+
+// grid = (row tiles / 4, column tiles, 2 directions); a wave = one 16-row tile x one 16-column tile, K = dim
+template <typename XT>
+__global__ __launch_bounds__(256) void k_enc_xproj(const uint4* __restrict__ W0, const uint4* __restrict__ W1, const float* __restrict__ b0,
+                                                   const float* __restrict__ b1, const uint4* __restrict__ X, int n_col, int max_tokens,
+                                                   float* __restrict__ Y)
+{
+    constexpr int NKF = ENC_DIM / Frag<XT>::KB;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, n = lane & 15, g = lane >> 4;
+    const int rt = blockIdx.x * 4 + wave, ct = blockIdx.y, dir = blockIdx.z;
+    const uint4* W = dir ? W1 : W0;
+    const float* b = dir ? b1 : b0;
+    floatx4 acc = *reinterpret_cast<const floatx4*>(b + rt * 16 + 4 * g);
+#pragma unroll 4
+    for (int kf = 0; kf < NKF; ++kf) acc = mfma_frag<XT>(W[xfrag(NKF, rt, kf, lane)], X[xfrag(NKF, ct, kf, lane)], acc);
+    const int col = ct * 16 + n;
+    if (col < n_col) *reinterpret_cast<floatx4*>(Y + ((size_t)dir * max_tokens + col) * ENC_GATES + rt * 16 + 4 * g) = acc;
+}
+
+template <typename XT> struct EncLstmGeom {
+    static constexpr int KB = Frag<XT>::KB, EPL = Frag<XT>::EPL;
+    static constexpr int NK = ENC_HID / KB;                       // k fragments of W_hh
+    static constexpr int KREG = sizeof(XT) == 2 ? 6 : 0;          // ... held in registers
+    static constexpr int KLDS = sizeof(XT) == 2 ? 2 : 0;          // ... held in LDS; the rest streams from L2
+    static constexpr int ROW_TILES = ENC_GATES / 16;              // 64
+    static constexpr int TILES_PER_WAVE = ROW_TILES / 4;          // 16: a wave owns 64 units
+    static constexpr int W_VECS = KLDS * ROW_TILES * 64;
+    static constexpr int H_VECS = NK * 64;                        // one copy of h; there are two (read one, write the other)
+    static constexpr int C_VECS = ENC_HID * 16 / 4;              // the cell state of 256 units x 16 requests, fp32
+    static constexpr int LDS_BYTES = (W_VECS + 2 * H_VECS + C_VECS) * 16;
+};
+
+// grid = (2 directions, groups of 16 requests), 256 threads
+template <typename XT>
+__global__ __launch_bounds__(256) void k_enc_lstm(const uint4* __restrict__ Whh0, const uint4* __restrict__ Whh1,
+                                                  const float* __restrict__ xproj, PnWindows w, int max_tokens, float* __restrict__ out)
+{
+    using G = EncLstmGeom<XT>;
+    constexpr int NK = G::NK, KREG = G::KREG, KLDS = G::KLDS, TPW = G::TILES_PER_WAVE;
+    extern __shared__ uint4 lds_enc[];
+    uint4* wl = lds_enc;                     // [KLDS][64 row tiles][64 lanes]
+    uint4* hb = lds_enc + G::W_VECS;         // h of the 16 requests, B-fragment order, [NK][64 lanes]
+    float* cl = reinterpret_cast<float*>(hb + 2 * G::H_VECS); // cell state [unit][request]: only its owner lane touches an entry
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n = lane & 15, g = lane >> 4;
+    const int dir = blockIdx.x, req = blockIdx.y * 16 + n;
+    const bool active = req < w.n;
+    const int len = active ? (int)w.len[req] : 0, col0 = active ? w.col0[req] : 0;
+    int lmax = len;
+#pragma unroll
+    for (int o = 1; o < 16; o <<= 1) lmax = max(lmax, __shfl_xor(lmax, o, 64));
+    const uint4* Whh = dir ? Whh1 : Whh0;
+
+    uint4 wreg[TPW][KREG > 0 ? KREG : 1];
+    if constexpr (KREG > 0) {
+#pragma unroll
+        for (int i = 0; i < TPW; ++i)
+#pragma unroll
+            for (int kf = 0; kf < KREG; ++kf) wreg[i][kf] = Whh[xfrag(NK, TPW * wave + i, kf, lane)];
+    }
+    for (int idx = tid; idx < G::W_VECS; idx += 256) {
+        const int kl = idx / (G::ROW_TILES * 64), rem = idx - kl * (G::ROW_TILES * 64);
+        wl[idx] = Whh[xfrag(NK, rem >> 6, KREG + kl, rem & 63)];
+    }
+    for (int idx = tid; idx < 2 * G::H_VECS; idx += 256) hb[idx] = make_uint4(0, 0, 0, 0);
+
+    // token of this lane's request at step s: forwards from 0, backwards from its own last token; clamped so that
+    // a request that has ended keeps reading (and computing on) valid memory -- its results are not stored
+    auto token = [&](int s) { return min(max(dir ? len - 1 - s : s, 0), max(len - 1, 0)); };
+    const float* xp = xproj + ((size_t)dir * max_tokens + col0) * ENC_GATES + (TPW * wave) * 16 + 4 * g;
+    floatx4 acc[TPW];
+#pragma unroll
+    for (int i = 0; i < TPW; ++i) {
+        acc[i] = *reinterpret_cast<const floatx4*>(xp + (size_t)token(0) * ENC_GATES + i * 16);
+        cl[(4 * (TPW * wave + i) + g) * 16 + n] = 0.f;
+    }
+    __syncthreads();
+
+    // A step in two halves of eight row tiles.  h is read from one buffer and written to the other, so a half's cell
+    // update can follow its MFMAs at once (and overlap the other half's MFMAs); when a half's accumulators have been
+    // consumed, the next step's input projection for those tiles is requested into them: half a step ahead of its use.
+    constexpr int HALF = TPW / 2;
+    for (int s = 0; s < lmax; ++s) {
+        const uint4* hr = hb + (s & 1) * G::H_VECS;
+        XT* hx = reinterpret_cast<XT*>(hb + ((s + 1) & 1) * G::H_VECS);
+        const int t_cur = dir ? len - 1 - s : s;
+        const bool store = active && s < len;
+        const int tn = token(s + 1);
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            if constexpr (KREG + KLDS == NK) {
+#pragma unroll
+                for (int kf = 0; kf < NK; ++kf) {
+                    const uint4 bv = hr[kf * 64 + lane];
+#pragma unroll
+                    for (int j = 0; j < HALF; ++j) {
+                        const int i = half * HALF + j;
+                        const uint4 av = kf < KREG ? wreg[i][kf < KREG ? kf : 0] : wl[((kf - KREG) * G::ROW_TILES + TPW * wave + i) * 64 + lane];
+                        acc[i] = mfma_frag<XT>(av, bv, acc[i]);
+                    }
+                }
+            } else {
+                // nothing resident: the matrix streams from L2, one k fragment of the half's row tiles at a time
+#pragma unroll 1
+                for (int kf = 0; kf < NK; ++kf) {
+                    const uint4 bv = hr[kf * 64 + lane];
+#pragma unroll
+                    for (int j = 0; j < HALF; ++j)
+                        acc[half * HALF + j] = mfma_frag<XT>(Whh[xfrag(NK, TPW * wave + half * HALF + j, kf, lane)], bv, acc[half * HALF + j]);
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < HALF; ++j) {
+                const int i = half * HALF + j;
+                const float gi = sigmoidf_(acc[i][0]), gf = sigmoidf_(acc[i][1]), gg = tanhf_(acc[i][2]), go = sigmoidf_(acc[i][3]);
+                const int u = 4 * (TPW * wave + i) + g;           // this lane's unit of tile i
+                const float cn = gf * cl[u * 16 + n] + gi * gg;
+                cl[u * 16 + n] = cn;
+                const float h = go * tanhf_(cn);
+                hx[(((u / G::KB) * 64 + n + 16 * ((u % G::KB) / G::EPL)) * G::EPL) + (u % G::EPL)] = from_float<XT>(h);
+                if (store) out[(size_t)(col0 + t_cur) * (2 * ENC_HID) + dir * ENC_HID + u] = h;
+                acc[i] = *reinterpret_cast<const floatx4*>(xp + (size_t)tn * ENC_GATES + i * 16);
+            }
+        }
+        __syncthreads();                       // the new h is complete; the old one is free to be overwritten next step
+    }
+}
+
+template <typename XT>
+hipError_t run_typed(const EncoderPtrs& d, const PnWindows& w, int n_col, float* out, hipStream_t s)
+{
+    constexpr int C = ENC_DIM;
+    const int n_ctiles = (n_col + 15) / 16, n_col_pad = n_ctiles * 16;
+    const bool wide = n_ctiles >= PN_WIDE_FROM;
+    XT* x0 = reinterpret_cast<XT*>(d.act[0]);
+    XT* x1 = reinterpret_cast<XT*>(d.act[1]);
+    PostnetPtrs tables{};                     // the shared per-column table kernel only needs these two
+    tables.cmeta = d.cmeta;
+    tables.orow = d.orow;
+    hipError_t e = launch_postnet_meta(tables, w, n_col, n_col_pad, true, s);
+    if (e != hipSuccess) return e;
+    EncTables tb;
+    for (int t = 0; t < ENC_TABLES; ++t) tb.t[t] = d.tables[t];
+    hipLaunchKernelGGL((k_enc_embed<XT>), dim3((n_col_pad * C + 255) / 256), dim3(256), 0, s, tb, d.ids, d.max_tokens, n_col, n_col_pad, x0);
+    e = hipGetLastError();
+    if (e == hipSuccess) e = conv_layer<XT, C, C, PN_EPI_RELU>(wide, d.conv_w[0], d.conv_b[0], x0, x1, d.cmeta, n_ctiles, nullptr, 0, nullptr, nullptr, s);
+    if (e == hipSuccess) e = conv_layer<XT, C, C, PN_EPI_RELU>(wide, d.conv_w[1], d.conv_b[1], x1, x0, d.cmeta, n_ctiles, nullptr, 0, nullptr, nullptr, s);
+    if (e == hipSuccess) e = conv_layer<XT, C, C, PN_EPI_RELU>(wide, d.conv_w[2], d.conv_b[2], x0, x1, d.cmeta, n_ctiles, nullptr, 0, nullptr, nullptr, s);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((k_enc_xproj<XT>), dim3(ENC_GATES / 16 / 4, n_ctiles, 2), dim3(256), 0, s, (const uint4*)d.w_ih[0], (const uint4*)d.w_ih[1],
+                       d.b[0], d.b[1], (const uint4*)x1, n_col, d.max_tokens, d.xproj);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    constexpr int LDS = EncLstmGeom<XT>::LDS_BYTES;
+    auto kern = k_enc_lstm<XT>;
+    static bool attr_set = false;             // dynamic LDS above 64 KB has to be allowed once per kernel
+    if (!attr_set) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(2, (w.n + 15) / 16), dim3(256), LDS, s, (const uint4*)d.w_hh[0], (const uint4*)d.w_hh[1], d.xproj, w,
+                       d.max_tokens, out);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_encoder(const EncoderPtrs& d, int wdtype, const PnWindows& w, int n_col, float* out, hipStream_t s)
+{
+    if (n_col < 1 || w.n < 1) return hipSuccess;
+    return wdtype == 0 ? run_typed<float>(d, w, n_col, out, s) : run_typed<bf16_t>(d, w, n_col, out, s);
+}
+
+}  // namespace tts

@@ -14,10 +14,10 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 def _declared_symbols():
     names = set()
-    for header in ("tts_pool.h", "tts_postnet.h", "tts_vocoder.h"):
+    for header in ("tts_pool.h", "tts_postnet.h", "tts_vocoder.h", "tts_encoder.h"):
         text = open(os.path.join(ROOT, "include", header)).read()
         text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-        names |= set(re.findall(r"\b(tts_(?:pool|book|last|postnet|vocoder)_\w+)\s*\(", text))
+        names |= set(re.findall(r"\b(tts_(?:pool|book|last|postnet|vocoder|encoder)_\w+)\s*\(", text))
     return sorted(names)
 
 
@@ -126,3 +126,16 @@ def test_vocoder_config_validation_without_gpu():
         setattr(c, field, bad)
         assert binding.vocoder_workspace_bytes(c) == 0, field
         assert binding.lib().tts_last_error()
+
+
+def test_encoder_config_validation_without_gpu():
+    good = binding.make_encoder_config(max_tokens=600, max_len=300)
+    assert binding.encoder_workspace_bytes(good) > 3 * 512 * 512 * 5 * 4          # the three convolutions alone
+    bf = binding.make_encoder_config(max_tokens=600, max_len=300, bf16=True)
+    assert 0 < binding.encoder_workspace_bytes(bf) < binding.encoder_workspace_bytes(good)
+    for field, bad in (("dim", 256), ("hid", 128), ("max_tokens", 10), ("max_len", 0), ("max_len", 40000), ("weight_dtype", 2)):
+        c = binding.make_encoder_config(max_tokens=600, max_len=300)
+        setattr(c, field, bad)
+        assert binding.encoder_workspace_bytes(c) == 0, field
+    c = binding.make_encoder_config(max_tokens=600, max_len=300, vocab=(128, 0, 4, 4))
+    assert binding.encoder_workspace_bytes(c) == 0

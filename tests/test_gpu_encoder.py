@@ -1,0 +1,108 @@
+"""Acoustic encoder on the GPU against the CPU oracle (oracle/encoder_oracle.c), through the C ABI."""
+import numpy as np
+import pytest
+
+from paper_2211_13939_amd import binding, synth
+from tests.helpers import TOL_BF16, TOL_F32, make_pool, say
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+def test_ragged_batch_matches_oracle(bf16):
+    """Six requests of 1 .. 77 tokens in one call (several column tiles, ragged ends, a one-token request; fewer
+    requests than MFMA columns): F_enc of every request equals the oracle's, which encodes each request alone."""
+    from oracle import oracle as orc
+    w = synth.make_encoder_weights(bf16=bf16)
+    W = orc.EncoderWeights(w)
+    lens = [1, 5, 16, 17, 77, 33]
+    ids = [synth.encoder_ids(L, 100 + i) for i, L in enumerate(lens)]
+    enc = binding.Encoder(binding.make_encoder_config(max_tokens=256, max_len=100, bf16=bf16), w)
+    say(f"case encoder: requests of {lens} tokens, {'bf16' if bf16 else 'fp32'}")
+    got = enc.run(ids)
+    worst = 0.0
+    for a, g in zip(ids, got):
+        want = orc.encoder(W, a)
+        assert g.shape == want.shape
+        worst = max(worst, float(np.abs(g - want).max()))
+    say(f"  max abs err {worst:.3e} on F_enc in (-1, 1), {enc.elapsed_ms() * 1e3:.0f} us")
+    assert worst <= (TOL_BF16 if bf16 else TOL_F32)
+    enc.close()
+
+
+def test_more_requests_than_mfma_columns_and_long_request():
+    """20 requests (two groups of 16 columns in the recurrence) and one of 300 tokens, bf16."""
+    from oracle import oracle as orc
+    w = synth.make_encoder_weights(bf16=True)
+    W = orc.EncoderWeights(w)
+    rng = np.random.default_rng(7)
+    lens = [int(x) for x in rng.integers(3, 40, size=19)] + [300]
+    ids = [synth.encoder_ids(L, 200 + i) for i, L in enumerate(lens)]
+    enc = binding.Encoder(binding.make_encoder_config(max_tokens=1024, max_len=300, bf16=True), w)
+    say(f"case encoder: 20 requests, {sum(lens)} tokens, longest 300, bf16")
+    got = enc.run(ids)
+    worst = 0.0
+    for k in (0, 7, 15, 16, 18, 19):
+        worst = max(worst, float(np.abs(got[k] - orc.encoder(W, ids[k])).max()))
+    say(f"  max abs err {worst:.3e}, {enc.elapsed_ms() * 1e3:.0f} us")
+    assert worst <= TOL_BF16
+    enc.close()
+
+
+def test_result_does_not_depend_on_batch_composition():
+    w = synth.make_encoder_weights(bf16=True)
+    ids = [synth.encoder_ids(L, 300 + i) for i, L in enumerate((40, 9, 23, 61))]
+    enc = binding.Encoder(binding.make_encoder_config(max_tokens=256, max_len=100, bf16=True), w)
+    alone = enc.run([ids[2]])[0]
+    mixed = enc.run(ids)[2]
+    last = enc.run([ids[3], ids[2]])[1]
+    np.testing.assert_array_equal(alone, mixed)
+    np.testing.assert_array_equal(alone, last)
+    enc.close()
+
+
+def test_bad_calls_are_rejected():
+    w = synth.make_encoder_weights()
+    enc = binding.Encoder(binding.make_encoder_config(max_tokens=64, max_len=40), w)
+    good = synth.encoder_ids(10, 1)
+    bad = good.copy(); bad[1, 3] = 4                     # the prosody tables have four rows
+    for case in ([bad], [synth.encoder_ids(41, 2)], [synth.encoder_ids(40, 3), synth.encoder_ids(30, 4)]):
+        with pytest.raises(binding.TtsError) as e:
+            enc.run(case)
+        assert e.value.code == binding.TTS_E_INVAL
+    neg = good.copy(); neg[0, 0] = -1
+    with pytest.raises(binding.TtsError):
+        enc.run([neg])
+    assert enc.run([good])[0].shape == (10, 512)
+    enc.close()
+
+
+def test_encoder_output_feeds_the_pool_on_device(weights_fp32):
+    """Eq. 1 then Eq. 2 without leaving the device: F_enc of two requests goes from the encoder's output buffer
+    straight into tts_pool_add_request; the mel frames equal the oracle decoder run on the oracle encoder's F_enc."""
+    import torch
+    from oracle import oracle as orc
+    we = synth.make_encoder_weights()
+    We = orc.EncoderWeights(we)
+    lens, steps = [37, 12], [14, 9]
+    ids = [synth.encoder_ids(L, 400 + i) for i, L in enumerate(lens)]
+    wl = synth.small_workload(2, 12, 37, 9, 14, seed=3)
+    pool = make_pool(wl, weights_fp32, max_pool=2, max_enc_len=64, max_steps=16)
+    enc = binding.Encoder(binding.make_encoder_config(max_tokens=64, max_len=64), we, stream=pool.stream)
+    d_f = torch.empty((sum(lens), 512), dtype=torch.float32, device=pool.device)
+    starts = enc.run_device(ids, d_f)
+    rids = [pool.add_request(d_f[s:s + L], n) for s, L, n in zip(starts, lens, steps)]
+    pool.step_n(max(steps))
+    Wd = orc.Weights(weights_fp32)
+    worst = 0.0
+    say(f"case encoder -> pool on device: tokens {lens}, steps {steps}")
+    for rid, a, n in zip(rids, ids, steps):
+        f_enc = orc.encoder(We, a).astype(np.float32)
+        ref, _, _, _ = orc.pool_decode(wl.dims, Wd, [f_enc], [n], n)
+        got = pool.drain_all(rid)
+        assert got.shape == (n, 80)
+        worst = max(worst, float(np.abs(got - ref[0]).max()))
+    say(f"  max abs err {worst:.3e}")
+    assert worst <= TOL_F32
+    enc.close()
+    pool.close()
