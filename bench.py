@@ -225,6 +225,29 @@ def vocoder_bench(binding, synth, torch, sizes=(1, 3, 16, 64, 256)):
     return rows
 
 
+def encoder_bench(binding, synth, torch):
+    """The encoder at join (Eq. 1): embedding sum, three convolutions, input projections, bidirectional LSTM, for one
+    request and for batches, bf16.  The recurrence is a chain of L dependent steps: its time is L x the step latency."""
+    w = synth.make_encoder_weights(bf16=True)
+    enc = binding.Encoder(binding.make_encoder_config(max_tokens=16 * 300, max_len=300, bf16=True), w)
+    rows = []
+    for n_req, L in ((1, 30), (1, 165), (1, 300), (4, 165), (16, 165), (16, 300)):
+        ids = [synth.encoder_ids(L, 500 + i) for i in range(n_req)]
+        d_out = torch.empty((n_req * L, 512), dtype=torch.float32, device=enc.device)
+        torch.cuda.synchronize()
+        for _ in range(3):
+            enc.run_device(ids, d_out)
+        times = []
+        for _ in range(10):
+            enc.run_device(ids, d_out)
+            times.append(enc.elapsed_ms() * 1e3)
+        us = float(np.median(times))
+        rows.append({"requests": n_req, "tokens_each": L, "us": us, "us_min": float(min(times)), "us_max": float(max(times)),
+                     "us_per_token_of_the_longest": us / L, "tokens_per_s": n_req * L / (us * 1e-6)})
+    enc.close()
+    return rows
+
+
 def job_roofline_bytes(wl, s_w, s_m):
     """Algorithmic bytes of the whole shrinking-pool job: the per-step bytes integrated over the
     actual membership (request i is active during steps 0 .. n_i - 1)."""
@@ -257,6 +280,8 @@ def main():
     ap.add_argument("--postnet", action="store_true",
                     help="only time the chunk-wise PostNet (bf16): one round of 40-frame chunks with 10 frames of context for "
                          "3, 64 and 256 requests")
+    ap.add_argument("--encoder", action="store_true",
+                    help="only time the encoder (bf16) for one request of 30 / 165 / 300 tokens and for batches of 4 and 16")
     ap.add_argument("--vocoder", action="store_true",
                     help="only time the vocoder module (bf16): one round of 40-frame chunks behind 8 overlap frames for "
                          "1 .. 256 requests")
@@ -291,6 +316,9 @@ def main():
         return
     if args.postnet:
         print(json.dumps({"postnet": postnet_bench(binding, synth, torch)}))
+        return
+    if args.encoder:
+        print(json.dumps({"encoder": encoder_bench(binding, synth, torch)}))
         return
     if args.vocoder:
         print(json.dumps({"vocoder": vocoder_bench(binding, synth, torch, [int(x) for x in args.vocoder_sizes.split(",")]), "macs_per_frame": vocoder_macs_per_frame()}))

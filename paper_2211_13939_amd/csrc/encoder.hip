@@ -7,10 +7,10 @@
 // The recurrence is a chain of L dependent steps of a 1024 x 256 matrix-vector product: latency, not bandwidth.
 // In bf16 the matrix of one direction (512 KB) is made resident in ONE compute unit -- six of its eight k fragments
 // in the registers of the workgroup's four waves (384 of the 512 registers a lane may have at one wave per SIMD),
-// the other two in 128 KB of LDS -- so a step touches no memory beyond the 16 KB of precomputed input projections.
-// The hidden state goes round through 8 KB of LDS in B-fragment order; the 16 MFMA columns are 16 requests.
-// Gate rows are stored unit-major / gate-minor, so a lane's four accumulator rows are the i, f, g, o of one unit
-// and the cell update needs no exchange.  (fp32 matrices do not fit a compute unit: they stream from L2 every step.)
+// the other two in 128 KB of LDS -- so a step touches no memory beyond the precomputed input projections of the
+// requests in flight.  The hidden state goes round through 8 KB of LDS in B-fragment order; the 16 MFMA columns are
+// 16 requests.  Gate rows are stored unit-major / gate-minor, so the four gate sums of a unit are contiguous.
+// (fp32 matrices do not fit a compute unit: they stream from L2 every step.)
 #include "encoder_kernels.h"
 
 #include "conv5_kernels.h"
@@ -19,6 +19,7 @@ namespace tts {
 namespace {
 
 struct EncTables { const float* t[ENC_TABLES]; };
+constexpr int ENC_COMPACT_UP_TO = 2;       // requests per call up to which the recurrence compacts its cell update
 
 template <typename XT>
 __global__ __launch_bounds__(256) void k_enc_embed(EncTables tb, const int* __restrict__ ids, int max_tokens, int n_col,
@@ -61,18 +62,158 @@ template <typename XT> struct EncLstmGeom {
     static constexpr int KLDS = sizeof(XT) == 2 ? 2 : 0;          // ... held in LDS; the rest streams from L2
     static constexpr int ROW_TILES = ENC_GATES / 16;              // 64
     static constexpr int TILES_PER_WAVE = ROW_TILES / 4;          // 16: a wave owns 64 units
+    static constexpr int GCOLS = 2;                               // requests whose gates pass through LDS at a time
+    static constexpr int W_VECS = KLDS * ROW_TILES * 64;
+    static constexpr int H_VECS = NK * 64;                        // h of the 16 requests, B-fragment order
+    static constexpr int C_VECS = ENC_HID * 16 / 4;               // the cell state of 256 units x 16 requests, fp32
+    static constexpr int G_VECS = GCOLS * ENC_GATES / 4;          // W_hh h of GCOLS requests, fp32
+    static constexpr int LDS_BYTES = (W_VECS + H_VECS + C_VECS + G_VECS) * 16;
+};
+
+// grid = (2 directions, groups of 16 requests), 256 threads.
+// One step:  (1) every wave: its 16 row tiles of W_hh h on MFMA, the 16 requests of the group as the columns;
+//            (2) two requests at a time, the lanes that hold their columns put the sums into LDS;
+//            (3) thread u = hidden unit u takes the four gate sums of its unit, adds the precomputed input
+//                projection, updates the cell and writes h (B-fragment order in LDS for the next step, fp32 to F_enc).
+// The cell update runs on compacted data: with one request in flight the MFMA columns are 1/16 full, and so would
+// every vector instruction be that worked on the accumulators where they are.
+template <typename XT>
+__global__ __launch_bounds__(256) void k_enc_lstm(const uint4* __restrict__ Whh0, const uint4* __restrict__ Whh1,
+                                                  const float* __restrict__ xproj, PnWindows w, int max_tokens, float* __restrict__ out)
+{
+    using G = EncLstmGeom<XT>;
+    constexpr int NK = G::NK, KREG = G::KREG, KLDS = G::KLDS, TPW = G::TILES_PER_WAVE, GCOLS = G::GCOLS;
+    extern __shared__ uint4 lds_enc[];
+    uint4* wl = lds_enc;                                          // [KLDS][64 row tiles][64 lanes]
+    uint4* hb = lds_enc + G::W_VECS;                              // [NK][64 lanes]
+    float* cl = reinterpret_cast<float*>(hb + G::H_VECS);         // [unit][request]
+    float* gl = cl + ENC_HID * 16;                                // [GCOLS][gate row]
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n = lane & 15, g = lane >> 4;
+    const int dir = blockIdx.x, req0 = blockIdx.y * 16;
+    const int nact = min(16, w.n - req0);                         // requests of this group
+    int lmax = 0;
+    for (int j = 0; j < nact; ++j) lmax = max(lmax, (int)w.len[req0 + j]);
+    const uint4* Whh = dir ? Whh1 : Whh0;
+
+    uint4 wreg[TPW][KREG > 0 ? KREG : 1];
+    if constexpr (KREG > 0) {
+#pragma unroll
+        for (int i = 0; i < TPW; ++i)
+#pragma unroll
+            for (int kf = 0; kf < KREG; ++kf) wreg[i][kf] = Whh[xfrag(NK, TPW * wave + i, kf, lane)];
+    }
+    for (int idx = tid; idx < G::W_VECS; idx += 256) {
+        const int kl = idx / (G::ROW_TILES * 64), rem = idx - kl * (G::ROW_TILES * 64);
+        wl[idx] = Whh[xfrag(NK, rem >> 6, KREG + kl, rem & 63)];
+    }
+    for (int idx = tid; idx < G::H_VECS + G::C_VECS; idx += 256) hb[idx] = make_uint4(0, 0, 0, 0);    // h = 0, c = 0
+
+    // token of request j at step s: forwards from 0, backwards from the request's own last token
+    auto token = [&](int j, int s) { return dir ? (int)w.len[req0 + j] - 1 - s : s; };
+    // this thread's unit: four gate sums of a request are 16 contiguous bytes of the input projection
+    const float* xp = xproj + (size_t)dir * max_tokens * ENC_GATES + 4 * tid;
+    // the first two requests' input projections are requested a step ahead (a batch at join time is that small)
+    floatx4 xnext[GCOLS];
+#pragma unroll
+    for (int j = 0; j < GCOLS; ++j) {
+        const int jj = min(j, nact - 1);
+        const int t0 = min(max(token(jj, 0), 0), (int)w.len[req0 + jj] - 1);
+        xnext[j] = *reinterpret_cast<const floatx4*>(xp + (size_t)(w.col0[req0 + jj] + t0) * ENC_GATES);
+    }
+    __syncthreads();
+
+    for (int s = 0; s < lmax; ++s) {
+        // ---- (1) W_hh h
+        floatx4 acc[TPW];
+#pragma unroll
+        for (int i = 0; i < TPW; ++i) acc[i] = floatx4{0.f, 0.f, 0.f, 0.f};
+        if constexpr (KREG + KLDS == NK) {
+            uint4 bn = hb[lane];
+#pragma unroll
+            for (int kf = 0; kf < NK; ++kf) {
+                const uint4 bv = bn;
+                if (kf + 1 < NK) bn = hb[(kf + 1) * 64 + lane];
+                if (kf < KREG) {
+#pragma unroll
+                    for (int i = 0; i < TPW; ++i) acc[i] = mfma_frag<XT>(wreg[i][kf < KREG ? kf : 0], bv, acc[i]);
+                } else {
+                    const uint4* wk = wl + ((kf - KREG) * G::ROW_TILES + TPW * wave) * 64 + lane;
+                    uint4 an = wk[0];
+#pragma unroll
+                    for (int i = 0; i < TPW; ++i) {
+                        const uint4 av = an;
+                        if (i + 1 < TPW) an = wk[(i + 1) * 64];
+                        acc[i] = mfma_frag<XT>(av, bv, acc[i]);
+                    }
+                }
+            }
+        } else {
+            // nothing resident: the matrix streams from L2, one k fragment of the wave's row tiles at a time
+#pragma unroll 1
+            for (int kf = 0; kf < NK; ++kf) {
+                const uint4 bv = hb[kf * 64 + lane];
+#pragma unroll
+                for (int i = 0; i < TPW; ++i) acc[i] = mfma_frag<XT>(Whh[xfrag(NK, TPW * wave + i, kf, lane)], bv, acc[i]);
+            }
+        }
+        __syncthreads();                                   // every wave has read h: it may be overwritten below
+        // ---- (2), (3): GCOLS requests at a time
+        for (int q = 0; q * GCOLS < nact; ++q) {
+            if (n / GCOLS == q) {
+                float* dst = gl + (n % GCOLS) * ENC_GATES + (TPW * wave) * 16 + 4 * g;
+#pragma unroll
+                for (int i = 0; i < TPW; ++i) *reinterpret_cast<floatx4*>(dst + i * 16) = acc[i];
+            }
+            __syncthreads();
+#pragma unroll
+            for (int jl = 0; jl < GCOLS; ++jl) {
+                const int j = q * GCOLS + jl;              // request of the group; uniform over the workgroup
+                if (j >= nact) break;
+                const int len = w.len[req0 + j], col0 = w.col0[req0 + j];
+                if (s >= len) continue;                    // this request has ended
+                const int t = token(j, s);
+                floatx4 x;
+                if (q == 0) x = xnext[jl];
+                else x = *reinterpret_cast<const floatx4*>(xp + (size_t)(col0 + t) * ENC_GATES);
+                const floatx4 gs = *reinterpret_cast<const floatx4*>(gl + jl * ENC_GATES + 4 * tid) + x;
+                const float gi = sigmoidf_(gs[0]), gf = sigmoidf_(gs[1]), gg = tanhf_(gs[2]), go = sigmoidf_(gs[3]);
+                const float cn = gf * cl[tid * 16 + j] + gi * gg;
+                cl[tid * 16 + j] = cn;
+                const float h = go * tanhf_(cn);
+                reinterpret_cast<XT*>(hb)[(((tid / G::KB) * 64 + j + 16 * ((tid % G::KB) / G::EPL)) * G::EPL) + (tid % G::EPL)] = from_float<XT>(h);
+                out[(size_t)(col0 + t) * (2 * ENC_HID) + dir * ENC_HID + tid] = h;
+                if (q == 0) {                              // next step's input projection, clamped to the request
+                    const int tn = min(max(token(j, s + 1), 0), len - 1);
+                    xnext[jl] = *reinterpret_cast<const floatx4*>(xp + (size_t)(col0 + tn) * ENC_GATES);
+                }
+            }
+            __syncthreads();                               // the gate buffer is free again; after the last group h is complete
+        }
+    }
+}
+
+template <typename XT> struct EncLstmWideGeom {
+    static constexpr int KB = Frag<XT>::KB, EPL = Frag<XT>::EPL;
+    static constexpr int NK = ENC_HID / KB;                       // k fragments of W_hh
+    static constexpr int KREG = sizeof(XT) == 2 ? 6 : 0;          // ... held in registers
+    static constexpr int KLDS = sizeof(XT) == 2 ? 2 : 0;          // ... held in LDS; the rest streams from L2
+    static constexpr int ROW_TILES = ENC_GATES / 16;              // 64
+    static constexpr int TILES_PER_WAVE = ROW_TILES / 4;          // 16: a wave owns 64 units
     static constexpr int W_VECS = KLDS * ROW_TILES * 64;
     static constexpr int H_VECS = NK * 64;                        // one copy of h; there are two (read one, write the other)
     static constexpr int C_VECS = ENC_HID * 16 / 4;              // the cell state of 256 units x 16 requests, fp32
     static constexpr int LDS_BYTES = (W_VECS + 2 * H_VECS + C_VECS) * 16;
 };
 
+// The recurrence for well-filled groups (more than ENC_COMPACT_UP_TO requests in the call): the cell update runs where
+// the accumulators are -- a lane owns the four gates of one unit for its request's column -- so nothing passes through
+// LDS but h, and the next step's input projection lands in the accumulators half a step ahead.
 // grid = (2 directions, groups of 16 requests), 256 threads
 template <typename XT>
-__global__ __launch_bounds__(256) void k_enc_lstm(const uint4* __restrict__ Whh0, const uint4* __restrict__ Whh1,
+__global__ __launch_bounds__(256) void k_enc_lstm_wide(const uint4* __restrict__ Whh0, const uint4* __restrict__ Whh1,
                                                   const float* __restrict__ xproj, PnWindows w, int max_tokens, float* __restrict__ out)
 {
-    using G = EncLstmGeom<XT>;
+    using G = EncLstmWideGeom<XT>;
     constexpr int NK = G::NK, KREG = G::KREG, KLDS = G::KLDS, TPW = G::TILES_PER_WAVE;
     extern __shared__ uint4 lds_enc[];
     uint4* wl = lds_enc;                     // [KLDS][64 row tiles][64 lanes]
@@ -187,15 +328,17 @@ hipError_t run_typed(const EncoderPtrs& d, const PnWindows& w, int n_col, float*
                        d.b[0], d.b[1], (const uint4*)x1, n_col, d.max_tokens, d.xproj);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
-    constexpr int LDS = EncLstmGeom<XT>::LDS_BYTES;
-    auto kern = k_enc_lstm<XT>;
-    static bool attr_set = false;             // dynamic LDS above 64 KB has to be allowed once per kernel
-    if (!attr_set) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+    // a call with a few requests (the usual case at join time) takes the kernel that compacts the cell update
+    const bool compact = w.n <= ENC_COMPACT_UP_TO;
+    const int lds = compact ? EncLstmGeom<XT>::LDS_BYTES : EncLstmWideGeom<XT>::LDS_BYTES;
+    auto kern = compact ? k_enc_lstm<XT> : k_enc_lstm_wide<XT>;
+    static bool attr_set[2] = {false, false};   // dynamic LDS above 64 KB has to be allowed once per kernel
+    if (!attr_set[compact]) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
         if (e != hipSuccess) return e;
-        attr_set = true;
+        attr_set[compact] = true;
     }
-    hipLaunchKernelGGL(kern, dim3(2, (w.n + 15) / 16), dim3(256), LDS, s, (const uint4*)d.w_hh[0], (const uint4*)d.w_hh[1], d.xproj, w,
+    hipLaunchKernelGGL(kern, dim3(2, (w.n + 15) / 16), dim3(256), lds, s, (const uint4*)d.w_hh[0], (const uint4*)d.w_hh[1], d.xproj, w,
                        d.max_tokens, out);
     return hipGetLastError();
 }
