@@ -134,7 +134,7 @@ def stream_run(stream, pool5, w5, enc, arrival, join_every, max_pool, postnet=No
     n = len(arrival)
     n_steps = w5.n_steps[:n]
     if postnet is not None:
-        be = stream.GpuPostnetBackend(pool5, postnet, lambda i, e=enc: e[i], n_steps, w5.chunk_frames, 10, vocoder=vocoder)
+        be = stream.GpuPostnetBackend(pool5, postnet, enc if callable(enc) else (lambda i, e=enc: e[i]), n_steps, w5.chunk_frames, 10, vocoder=vocoder)
     else:
         be = stream.GpuBackend(pool5, lambda i, e=enc: e[i], n_steps, w5.chunk_frames)
     r = stream.simulate(be, arrival, n_steps, w5.chunk_frames, join_every=join_every, max_pool=max_pool)
@@ -486,6 +486,21 @@ def main():
         voc5 = binding.Vocoder(binding.make_vocoder_config(overlap=8, max_chunk=w5.chunk_frames, max_requests=16, max_batch=16, bf16=True),
                                synth.make_vocoder_weights(bf16=True), stream=pool5.stream)
         res["per_step_join_with_postnet_and_vocoder"] = stream_run(stream, pool5, w5, enc5_dev, arrival, 1, 16, postnet=pn5, vocoder=voc5)
+        # the whole acoustic path: encoder at join (Eq. 1), decoder steps (Eq. 2), PostNet, vocoder (Eq. 3, Eq. 4)
+        enc5 = binding.Encoder(binding.make_encoder_config(max_tokens=int(w5.enc_len.max()), max_len=int(w5.enc_len.max()), bf16=True),
+                               synth.make_encoder_weights(bf16=True), stream=pool5.stream)
+        ids5 = {}
+
+        def ids_of(i):
+            if i not in ids5:
+                ids5[i] = synth.encoder_ids(int(w5.enc_len[i]), 9000 + i)
+            return ids5[i]
+
+        for i in range(len(arrival)):
+            ids_of(i)
+        join5 = stream.EncoderAtJoin(enc5, ids_of, int(w5.enc_len.max()))
+        res["per_step_join_encoder_to_vocoder"] = stream_run(stream, pool5, w5, join5, arrival, 1, 16, postnet=pn5, vocoder=voc5)
+        enc5.close()
         voc5.close()
         pn5.close()
         out["stream"] = {"workload": f"c5: {args.arrivals} arrivals at {args.qps:g}/s, {w5.n_requests} requests, L~U{{30..300}}, "
@@ -493,7 +508,8 @@ def main():
                                      "(per_step_join_host_input: handed over from pageable host memory, PCIe copy "
                                      "included; per_step_join_with_postnet: each chunk also passes the chunk-level "
                                      "PostNet on the device before it is copied out; per_step_join_with_postnet_and_vocoder: the chunk then goes through the "
-                                     "vocoder on the device and the response is its 256 samples per frame); rtf = last-chunk latency / audio duration at 256 samples per frame, "
+                                     "vocoder on the device and the response is its 256 samples per frame; per_step_join_encoder_to_vocoder: in addition F_enc is "
+                                     "not given but computed at join time by the encoder from the request's token ids); rtf = last-chunk latency / audio duration at 256 samples per frame, "
                                      "22.05 kHz (decoder only)",
                          **res, "paper_context": "first-chunk latency < 80 ms at 100 QPS, full pipeline, one A10"}
         pool5.close()

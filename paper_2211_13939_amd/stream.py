@@ -256,3 +256,19 @@ class GpuPostnetBackend(GpuBackend):
         if s is not None and "vslot" in s:
             self._free_slots.append(s["vslot"])
         super().retire(rid)
+
+
+class EncoderAtJoin:
+    """Module E for the serving loop (Eq. 1; Sec. 2.2.1: once per request): `enc(i)` for a GpuBackend.  The request's
+    id sequences go through tts_encoder_run on the pool's stream and F_enc stays on the device; the pool copies it
+    into its own memory when the request is added, so one output buffer serves every join."""
+
+    def __init__(self, encoder, ids_of, max_len: int):
+        import torch
+        self.encoder, self.ids_of = encoder, ids_of
+        self._d_f = torch.empty((max_len, 2 * encoder.cfg.hid), dtype=torch.float32, device=encoder.device)
+
+    def __call__(self, index: int):
+        ids = self.ids_of(index)
+        self.encoder.run_device([ids], self._d_f)
+        return self._d_f[: ids.shape[1]]

@@ -110,3 +110,56 @@ def test_encoder_output_feeds_the_pool_on_device(weights_fp32):
     assert worst <= TOL_F32
     enc.close()
     pool.close()
+
+
+def test_serving_loop_with_encoder_at_join_matches_oracle(weights_fp32):
+    """The arrival-driven loop with module E in front: every request joins with its token ids, the encoder produces
+    F_enc on the device at join time, the decoder runs on it.  Mel frames equal the oracle chain (encoder, decoder)."""
+    from oracle import oracle as orc
+    from paper_2211_13939_amd import stream
+    n, chunk = 4, 8
+    wl = synth.small_workload(n, 8, 45, 11, 30, seed=61)
+    ids = [synth.encoder_ids(int(L), 700 + i) for i, L in enumerate(wl.enc_len)]
+    we = synth.make_encoder_weights()
+    pool = make_pool(wl, weights_fp32, chunk_frames=chunk, max_pool=3, max_enc_len=64)
+    enc = binding.Encoder(binding.make_encoder_config(max_tokens=64, max_len=64), we, stream=pool.stream)
+    join = stream.EncoderAtJoin(enc, lambda i: ids[i], 64)
+    got = {i: [] for i in range(n)}
+
+    class Collect(stream.GpuBackend):
+        def run(self, k):
+            self.pool.step_n(k)
+            chunk_ids, fin_ids = [], []
+            for rid, s in self.live.items():
+                s["done"] = min(s["total"], s["done"] + k)
+                if s["done"] - s["drained"] >= self.chunk or s["done"] == s["total"]:
+                    while True:
+                        frames, fin = self.pool.drain_chunk(rid)
+                        s["drained"] += frames.shape[0]
+                        if frames.shape[0]:
+                            got[s["index"]].append(frames.copy())
+                            chunk_ids.append(rid)
+                        if fin:
+                            fin_ids.append(rid)
+                        if fin or frames.shape[0] == 0 or s["done"] - s["drained"] < self.chunk:
+                            break
+            self.pool.sync()
+            return None, chunk_ids, fin_ids
+
+    be = Collect(pool, join, wl.n_steps, chunk)
+    say(f"case serving loop with encoder at join: tokens {wl.enc_len.tolist()}, steps {wl.n_steps.tolist()}, pool of 3")
+    res = stream.simulate(be, np.array([0.0, 0.0, 1e-4, 3e-3]), wl.n_steps, chunk, join_every=1, max_pool=3)
+    assert not np.isnan(res.last_chunk_latency_s).any()
+    We, Wd = orc.EncoderWeights(we), orc.Weights(weights_fp32)
+    worst = 0.0
+    for i in range(n):
+        T = int(wl.n_steps[i])
+        f_enc = orc.encoder(We, ids[i]).astype(np.float32)
+        ref, _, _, _ = orc.pool_decode(wl.dims, Wd, [f_enc], [T], T)
+        mel = np.concatenate(got[i])
+        assert mel.shape == (T, 80)
+        worst = max(worst, float(np.abs(mel - ref[0]).max()))
+    say(f"  max abs err {worst:.3e}")
+    assert worst <= TOL_F32
+    enc.close()
+    pool.close()
