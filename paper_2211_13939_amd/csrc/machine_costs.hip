@@ -184,6 +184,39 @@ int main()
                    mask == 4095 ? "16 KiB" : "64 MiB", ms * 1e3 / 200 / 32);
         }
 
+    // A step of two dependent kernels A -> B; a third kernel P that B also needs, either in line (A -> P -> B) or on a
+    // side branch of the graph next to A (P and A both follow the previous B, B waits for both).
+    printf("1b. a side branch in a graph (16 steps per graph; every kernel 256 workgroups with 2 dependent loads over the 64 MiB table)\n");
+    {
+        hipStream_t s1; CK(hipStreamCreate(&s1));
+        hipEvent_t ef, ej; CK(hipEventCreateWithFlags(&ef, hipEventDisableTiming)); CK(hipEventCreateWithFlags(&ej, hipEventDisableTiming));
+        int* out_p; CK(hipMalloc(&out_p, 64));
+        for (int mode = 0; mode < 3; ++mode) {
+            hipGraph_t g; hipGraphExec_t ge;
+            CK(hipStreamBeginCapture(s, hipStreamCaptureModeThreadLocal));
+            for (int i = 0; i < 16; ++i) {
+                if (mode == 2) {
+                    CK(hipEventRecord(ef, s));
+                    CK(hipStreamWaitEvent(s1, ef, 0));
+                    hipLaunchKernelGGL(k_chain, dim3(256), dim3(256), 0, s1, chain, NBIG - 1, 2, out_p);     // P beside A
+                    CK(hipEventRecord(ej, s1));
+                }
+                hipLaunchKernelGGL(k_chain, dim3(256), dim3(256), 0, s, chain, NBIG - 1, 2, out_i);          // A
+                if (mode == 1) hipLaunchKernelGGL(k_chain, dim3(256), dim3(256), 0, s, chain, NBIG - 1, 2, out_p);   // P in line
+                if (mode == 2) CK(hipStreamWaitEvent(s, ej, 0));
+                hipLaunchKernelGGL(k_chain, dim3(256), dim3(256), 0, s, chain, NBIG - 1, 2, out_i);          // B
+            }
+            CK(hipStreamEndCapture(s, &g)); CK(hipGraphInstantiate(&ge, g, nullptr, nullptr, 0));
+            for (int i = 0; i < 10; ++i) CK(hipGraphLaunch(ge, s));
+            CK(hipStreamSynchronize(s));
+            CK(hipEventRecord(e0, s));
+            for (int i = 0; i < 200; ++i) CK(hipGraphLaunch(ge, s));
+            CK(hipEventRecord(e1, s)); CK(hipEventSynchronize(e1)); CK(hipEventElapsedTime(&ms, e0, e1));
+            printf("  %-34s %.2f us per step\n", mode == 0 ? "A -> B:" : (mode == 1 ? "A -> P -> B:" : "A and P side by side -> B:"), ms * 1e3 / 200 / 16);
+            CK(hipGraphExecDestroy(ge)); CK(hipGraphDestroy(g));
+        }
+    }
+
     printf("2. all-to-all synchronisation inside one persistent kernel\n");
     unsigned *flags, *fail; float *buf, *out;
     CK(hipMalloc(&flags, 4096)); CK(hipMalloc(&fail, 4)); CK(hipMalloc(&out, 4)); CK(hipMalloc(&buf, 64 << 20));
