@@ -200,3 +200,31 @@ def test_serving_loop_decoder_postnet_vocoder_matches_oracle(weights_fp32):
     voc.close()
     pn.close()
     pool.close()
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+def test_full_size_batch_in_the_benchmarked_launch_shape(bf16):
+    """64 requests, 40-frame chunks behind 8 overlap frames: the batch `bench.py --vocoder` times, which takes the
+    large tilings of the fused kernels.  Two rounds (first chunks, then middle chunks); the responses of four sampled
+    requests are checked against the oracle's streams, the rest for size and range."""
+    from oracle import oracle as orc
+    w = synth.make_vocoder_weights(bf16=bf16)
+    W = orc.VocoderWeights(w)
+    rng = np.random.default_rng(21)
+    n, chunk, ov = 64, 40, 8
+    first = [_mel(rng, chunk) for _ in range(n)]
+    second = [_mel(rng, chunk) for _ in range(n)]
+    voc = binding.Vocoder(binding.make_vocoder_config(overlap=ov, max_chunk=chunk, max_requests=n, max_batch=n, bf16=bf16), w)
+    say(f"case vocoder full batch: {n} requests x ({ov} + {chunk}) frames, {'bf16' if bf16 else 'fp32'}")
+    r1 = voc.run(first, list(range(n)), [FIRST] * n)
+    r2 = voc.run(second, list(range(n)), [0] * n)
+    assert all(a.shape == ((chunk - ov) * HOP,) for a in r1) and all(a.shape == (chunk * HOP,) for a in r2)
+    assert all(np.isfinite(a).all() and np.abs(a).max() < 1.0 for a in r1 + r2)
+    worst = 0.0
+    for k in (0, 17, 42, 63):
+        vs = orc.VocoderStream(W, ov)
+        worst = max(worst, float(np.abs(r1[k] - vs.chunk(first[k], False)).max()))
+        worst = max(worst, float(np.abs(r2[k] - vs.chunk(second[k], False)).max()))
+    say(f"  max abs err {worst:.3e} on four sampled requests, {voc.elapsed_ms() * 1e3:.0f} us for the second round")
+    assert worst <= (TOL_BF16 if bf16 else TOL_F32)
+    voc.close()
