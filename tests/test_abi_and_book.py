@@ -62,7 +62,14 @@ def test_timeline_membership_trace():
     b.retire(r2)
     r4 = b.add(10, 9)
     trace += [b.step()]                    # step 6
-    assert trace == [[r1], [r1], [r1, r2, r3], [r1, r2, r3], [r2, r3], [r2, r3], [r3, r4]]
+    ids = {1: r1, 2: r2, 3: r3, 4: r4}
+    golden = []                            # the walk-through as the paper prints it
+    for line in open(os.path.join(ROOT, "tests", "golden", "timeline_sec_2_2_3.txt")):
+        if line.strip() and not line.startswith("#"):
+            step, members = line.split(":")
+            assert int(step) == len(golden)
+            golden.append([ids[int(x)] for x in members.split()])
+    assert len(golden) == 7 and trace == golden
     first, n, fin = b.drain(r3)
     assert (first, n, fin) == (0, 4, False)
     first, n, fin = b.drain(r3)

@@ -1,8 +1,22 @@
 """Host logic of the arrival-driven serving loop (Sec. 2.2.2) against the
 latency closed form of Sec. 2.2.3, with a model backend of constant step time."""
+import os
+
 import numpy as np
 
 from paper_2211_13939_amd import stream
+
+GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "first_chunk_latency_sec_2_2_3.txt")
+
+
+def _paper_bounds():
+    """name -> (coefficient of T_t, coefficient of T_{t+1}) as the paper states them."""
+    out = {}
+    for line in open(GOLDEN):
+        if line.strip() and not line.startswith("#"):
+            name, a, b = line.split()
+            out[name] = (float(a), float(b))
+    return out
 
 
 class ModelBackend(stream.PoolBackend):
@@ -54,9 +68,12 @@ def test_first_chunk_latency_closed_form():
     res = stream.simulate(be, arrivals, n_steps, chunk, join_every=chunk)
     fcl = res.first_chunk_latency_s[1:]
     assert np.isfinite(fcl).all()
-    assert fcl.min() >= T - 1e-12 and fcl.max() <= 2 * T + 1e-12
-    assert abs(fcl.mean() - 1.5 * T) < 0.02 * T
-    assert abs(res.first_chunk_latency_s[0] - T) < 1e-12      # arrived right before an iteration: the minimum
+    b = _paper_bounds()
+    t_max, t_mean, t_min = (sum(b[k]) * T for k in ("maximum", "expectation", "minimum_equal_iterations"))
+    assert (t_max, t_mean, t_min) == (2 * T, 1.5 * T, T)
+    assert fcl.min() >= t_min - 1e-12 and fcl.max() <= t_max + 1e-12
+    assert abs(fcl.mean() - t_mean) < 0.02 * T
+    assert abs(res.first_chunk_latency_s[0] - t_min) < 1e-12  # arrived right before an iteration: the minimum
 
 
 def test_idle_server_serves_immediately_and_clock_jumps():
