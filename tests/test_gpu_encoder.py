@@ -163,3 +163,28 @@ def test_serving_loop_with_encoder_at_join_matches_oracle(weights_fp32):
     assert worst <= TOL_F32
     enc.close()
     pool.close()
+
+
+def test_largest_batch_and_a_very_long_request():
+    """256 requests in one call (16 groups of MFMA columns per direction) and, in another call, one request of 1000
+    tokens (the recurrence runs 1000 dependent steps), fp32."""
+    from oracle import oracle as orc
+    w = synth.make_encoder_weights()
+    W = orc.EncoderWeights(w)
+    rng = np.random.default_rng(29)
+    lens = [int(x) for x in rng.integers(1, 12, size=256)]
+    ids = [synth.encoder_ids(L, 800 + i) for i, L in enumerate(lens)]
+    enc = binding.Encoder(binding.make_encoder_config(max_tokens=4096, max_len=1000), w)
+    say(f"case encoder largest batch: 256 requests, {sum(lens)} tokens; then one request of 1000 tokens")
+    got = enc.run(ids)
+    worst = 0.0
+    for k in (0, 15, 16, 100, 255):
+        worst = max(worst, float(np.abs(got[k] - orc.encoder(W, ids[k])).max()))
+    long_ids = synth.encoder_ids(1000, 999)
+    g = enc.run([long_ids])[0]
+    worst_long = float(np.abs(g - orc.encoder(W, long_ids)).max())
+    say(f"  max abs err {worst:.3e} (batch), {worst_long:.3e} (1000 tokens)")
+    assert worst <= TOL_F32 and worst_long <= TOL_F32
+    with pytest.raises(binding.TtsError):
+        enc.run(ids + [ids[0]])                # 257 requests
+    enc.close()

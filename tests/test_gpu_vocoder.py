@@ -228,3 +228,38 @@ def test_full_size_batch_in_the_benchmarked_launch_shape(bf16):
     say(f"  max abs err {worst:.3e} on four sampled requests, {voc.elapsed_ms() * 1e3:.0f} us for the second round")
     assert worst <= (TOL_BF16 if bf16 else TOL_F32)
     voc.close()
+
+
+def test_largest_batch_of_short_chunks():
+    """256 chunks in one call (the most the call's batch table holds), chunks of 2 .. 5 frames with overlap 2, a mix of
+    first, middle and last chunks: sizes follow the response rule and sampled responses match the oracle."""
+    from oracle import oracle as orc
+    w = synth.make_vocoder_weights()
+    W = orc.VocoderWeights(w)
+    rng = np.random.default_rng(23)
+    n, ov = 256, 2
+    voc = binding.Vocoder(binding.make_vocoder_config(overlap=ov, max_chunk=5, max_requests=n, max_batch=n), w)
+    a = [_mel(rng, int(k)) for k in rng.integers(2, 6, size=n)]
+    b = [_mel(rng, int(k)) for k in rng.integers(1, 6, size=n)]          # last chunks may be shorter than the overlap
+    single = rng.random(n) < 0.25                                         # a quarter of the requests have one chunk only
+    say("case vocoder largest batch: 256 chunks of 2..5 frames, overlap 2")
+    r1 = voc.run(a, list(range(n)), [FIRST | (LAST if s else 0) for s in single])
+    for k in range(n):
+        assert r1[k].shape == ((a[k].shape[0] - (0 if single[k] else ov)) * HOP,)
+    cont = [k for k in range(n) if not single[k]]
+    r2 = voc.run([b[k] for k in cont], cont, [LAST] * len(cont))
+    worst = 0.0
+    for pos in (0, len(cont) // 2, len(cont) - 1):
+        k = cont[pos]
+        vs = orc.VocoderStream(W, ov)
+        worst = max(worst, float(np.abs(r1[k] - vs.chunk(a[k], False)).max()))
+        want = vs.chunk(b[k], True)
+        assert r2[pos].shape == want.shape == ((ov + b[k].shape[0]) * HOP,)
+        worst = max(worst, float(np.abs(r2[pos] - want).max()))
+    k = int(np.nonzero(single)[0][0])
+    worst = max(worst, float(np.abs(r1[k] - orc.generator(W, a[k])).max()))
+    say(f"  max abs err {worst:.3e}")
+    assert worst <= TOL_F32
+    with pytest.raises(binding.TtsError):
+        voc.run([a[0]] * 257, list(range(256)) + [0], [FIRST] * 257)
+    voc.close()
