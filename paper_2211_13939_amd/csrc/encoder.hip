@@ -62,7 +62,8 @@ template <typename XT> struct EncLstmGeom {
     static constexpr int KLDS = sizeof(XT) == 2 ? 2 : 0;          // ... held in LDS; the rest streams from L2
     static constexpr int ROW_TILES = ENC_GATES / 16;              // 64
     static constexpr int TILES_PER_WAVE = ROW_TILES / 4;          // 16: a wave owns 64 units
-    static constexpr int GCOLS = 2;                               // requests whose gates pass through LDS at a time
+    static constexpr int GCOLS = 2;                               // requests whose gate sums pass through LDS: the most a call may have
+    static_assert(GCOLS >= ENC_COMPACT_UP_TO, "the compacting kernel serves calls of up to ENC_COMPACT_UP_TO requests");
     static constexpr int W_VECS = KLDS * ROW_TILES * 64;
     static constexpr int H_VECS = NK * 64;                        // h of the 16 requests, B-fragment order
     static constexpr int C_VECS = ENC_HID * 16 / 4;               // the cell state of 256 units x 16 requests, fp32
@@ -70,9 +71,9 @@ template <typename XT> struct EncLstmGeom {
     static constexpr int LDS_BYTES = (W_VECS + H_VECS + C_VECS + G_VECS) * 16;
 };
 
-// grid = (2 directions, groups of 16 requests), 256 threads.
-// One step:  (1) every wave: its 16 row tiles of W_hh h on MFMA, the 16 requests of the group as the columns;
-//            (2) two requests at a time, the lanes that hold their columns put the sums into LDS;
+// grid = (2 directions, 1), 256 threads; for calls of at most GCOLS requests.
+// One step:  (1) every wave: its 16 row tiles of W_hh h on MFMA, the requests as the first of the 16 columns;
+//            (2) the lanes that hold those columns put the sums into LDS;
 //            (3) thread u = hidden unit u takes the four gate sums of its unit, adds the precomputed input
 //                projection, updates the cell and writes h (B-fragment order in LDS for the next step, fp32 to F_enc).
 // The cell update runs on compacted data: with one request in flight the MFMA columns are 1/16 full, and so would
@@ -90,9 +91,17 @@ __global__ __launch_bounds__(256) void k_enc_lstm(const uint4* __restrict__ Whh0
     float* gl = cl + ENC_HID * 16;                                // [GCOLS][gate row]
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n = lane & 15, g = lane >> 4;
     const int dir = blockIdx.x, req0 = blockIdx.y * 16;
-    const int nact = min(16, w.n - req0);                         // requests of this group
-    int lmax = 0;
-    for (int j = 0; j < nact; ++j) lmax = max(lmax, (int)w.len[req0 + j]);
+    const int nact = min(GCOLS, w.n - req0);                      // requests of this call
+    // lengths and first tokens once, into registers: the request table is a kernel argument, and indexing it inside
+    // the step loop would cost a memory round trip per use
+    int len_of[GCOLS], col0_of[GCOLS], lmax = 0;
+#pragma unroll
+    for (int j = 0; j < GCOLS; ++j) {
+        const int jj = min(j, nact - 1);
+        len_of[j] = w.len[req0 + jj];
+        col0_of[j] = w.col0[req0 + jj];
+        if (j < nact) lmax = max(lmax, len_of[j]);
+    }
     const uint4* Whh = dir ? Whh1 : Whh0;
 
     uint4 wreg[TPW][KREG > 0 ? KREG : 1];
@@ -109,86 +118,91 @@ __global__ __launch_bounds__(256) void k_enc_lstm(const uint4* __restrict__ Whh0
     for (int idx = tid; idx < G::H_VECS + G::C_VECS; idx += 256) hb[idx] = make_uint4(0, 0, 0, 0);    // h = 0, c = 0
 
     // token of request j at step s: forwards from 0, backwards from the request's own last token
-    auto token = [&](int j, int s) { return dir ? (int)w.len[req0 + j] - 1 - s : s; };
+    auto token = [&](int j, int s) { return dir ? len_of[j] - 1 - s : s; };
     // this thread's unit: four gate sums of a request are 16 contiguous bytes of the input projection
     const float* xp = xproj + (size_t)dir * max_tokens * ENC_GATES + 4 * tid;
     // the first two requests' input projections are requested a step ahead (a batch at join time is that small)
     floatx4 xnext[GCOLS];
 #pragma unroll
     for (int j = 0; j < GCOLS; ++j) {
-        const int jj = min(j, nact - 1);
-        const int t0 = min(max(token(jj, 0), 0), (int)w.len[req0 + jj] - 1);
-        xnext[j] = *reinterpret_cast<const floatx4*>(xp + (size_t)(w.col0[req0 + jj] + t0) * ENC_GATES);
+        const int t0 = min(max(token(j, 0), 0), len_of[j] - 1);
+        xnext[j] = *reinterpret_cast<const floatx4*>(xp + (size_t)(col0_of[j] + t0) * ENC_GATES);
     }
     __syncthreads();
 
+    // One step.  The row tiles are taken two at a time with all of h's fragments held in registers: while the pair's
+    // sixteen MFMAs run, the LDS-resident weight fragments of the next pair are on their way, and a finished pair's
+    // sums leave for the gate buffer at once, so only two tiles of accumulators are ever live.
     for (int s = 0; s < lmax; ++s) {
-        // ---- (1) W_hh h
-        floatx4 acc[TPW];
-#pragma unroll
-        for (int i = 0; i < TPW; ++i) acc[i] = floatx4{0.f, 0.f, 0.f, 0.f};
+        // ---- (1) W_hh h, (2) the sums of this call's (at most GCOLS) requests into LDS
+        float* dst = gl + (n % GCOLS) * ENC_GATES + (TPW * wave) * 16 + 4 * g;
         if constexpr (KREG + KLDS == NK) {
-            uint4 bn = hb[lane];
+            uint4 bv[NK];
 #pragma unroll
-            for (int kf = 0; kf < NK; ++kf) {
-                const uint4 bv = bn;
-                if (kf + 1 < NK) bn = hb[(kf + 1) * 64 + lane];
-                if (kf < KREG) {
+            for (int kf = 0; kf < NK; ++kf) bv[kf] = hb[kf * 64 + lane];
+            const uint4* wk = wl + (TPW * wave) * 64 + lane;           // [KLDS][row tile][lane], this wave's tiles
+            uint4 an[2][KLDS > 0 ? KLDS : 1];
 #pragma unroll
-                    for (int i = 0; i < TPW; ++i) acc[i] = mfma_frag<XT>(wreg[i][kf < KREG ? kf : 0], bv, acc[i]);
-                } else {
-                    const uint4* wk = wl + ((kf - KREG) * G::ROW_TILES + TPW * wave) * 64 + lane;
-                    uint4 an = wk[0];
+            for (int e = 0; e < 2; ++e)
 #pragma unroll
-                    for (int i = 0; i < TPW; ++i) {
-                        const uint4 av = an;
-                        if (i + 1 < TPW) an = wk[(i + 1) * 64];
-                        acc[i] = mfma_frag<XT>(av, bv, acc[i]);
+                for (int kl = 0; kl < KLDS; ++kl) an[e][kl] = wk[(kl * G::ROW_TILES + e) * 64];
+#pragma unroll
+            for (int i = 0; i < TPW; i += 2) {
+                uint4 ac[2][KLDS > 0 ? KLDS : 1];
+#pragma unroll
+                for (int e = 0; e < 2; ++e)
+#pragma unroll
+                    for (int kl = 0; kl < KLDS; ++kl) {
+                        ac[e][kl] = an[e][kl];
+                        if (i + 2 < TPW) an[e][kl] = wk[(kl * G::ROW_TILES + i + 2 + e) * 64];
                     }
+                __builtin_amdgcn_sched_barrier(0);
+                floatx4 a0 = {0.f, 0.f, 0.f, 0.f}, a1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int kf = 0; kf < NK; ++kf) {
+                    a0 = mfma_frag<XT>(kf < KREG ? wreg[i][kf < KREG ? kf : 0] : ac[0][kf >= KREG ? kf - KREG : 0], bv[kf], a0);
+                    a1 = mfma_frag<XT>(kf < KREG ? wreg[i + 1][kf < KREG ? kf : 0] : ac[1][kf >= KREG ? kf - KREG : 0], bv[kf], a1);
+                }
+                if (n < GCOLS) {
+                    *reinterpret_cast<floatx4*>(dst + i * 16) = a0;
+                    *reinterpret_cast<floatx4*>(dst + (i + 1) * 16) = a1;
                 }
             }
         } else {
             // nothing resident: the matrix streams from L2, one k fragment of the wave's row tiles at a time
+            floatx4 acc[TPW];
+#pragma unroll
+            for (int i = 0; i < TPW; ++i) acc[i] = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll 1
             for (int kf = 0; kf < NK; ++kf) {
                 const uint4 bv = hb[kf * 64 + lane];
 #pragma unroll
                 for (int i = 0; i < TPW; ++i) acc[i] = mfma_frag<XT>(Whh[xfrag(NK, TPW * wave + i, kf, lane)], bv, acc[i]);
             }
-        }
-        __syncthreads();                                   // every wave has read h: it may be overwritten below
-        // ---- (2), (3): GCOLS requests at a time
-        for (int q = 0; q * GCOLS < nact; ++q) {
-            if (n / GCOLS == q) {
-                float* dst = gl + (n % GCOLS) * ENC_GATES + (TPW * wave) * 16 + 4 * g;
+            if (n < GCOLS) {
 #pragma unroll
                 for (int i = 0; i < TPW; ++i) *reinterpret_cast<floatx4*>(dst + i * 16) = acc[i];
             }
-            __syncthreads();
-#pragma unroll
-            for (int jl = 0; jl < GCOLS; ++jl) {
-                const int j = q * GCOLS + jl;              // request of the group; uniform over the workgroup
-                if (j >= nact) break;
-                const int len = w.len[req0 + j], col0 = w.col0[req0 + j];
-                if (s >= len) continue;                    // this request has ended
-                const int t = token(j, s);
-                floatx4 x;
-                if (q == 0) x = xnext[jl];
-                else x = *reinterpret_cast<const floatx4*>(xp + (size_t)(col0 + t) * ENC_GATES);
-                const floatx4 gs = *reinterpret_cast<const floatx4*>(gl + jl * ENC_GATES + 4 * tid) + x;
-                const float gi = sigmoidf_(gs[0]), gf = sigmoidf_(gs[1]), gg = tanhf_(gs[2]), go = sigmoidf_(gs[3]);
-                const float cn = gf * cl[tid * 16 + j] + gi * gg;
-                cl[tid * 16 + j] = cn;
-                const float h = go * tanhf_(cn);
-                reinterpret_cast<XT*>(hb)[(((tid / G::KB) * 64 + j + 16 * ((tid % G::KB) / G::EPL)) * G::EPL) + (tid % G::EPL)] = from_float<XT>(h);
-                out[(size_t)(col0 + t) * (2 * ENC_HID) + dir * ENC_HID + tid] = h;
-                if (q == 0) {                              // next step's input projection, clamped to the request
-                    const int tn = min(max(token(j, s + 1), 0), len - 1);
-                    xnext[jl] = *reinterpret_cast<const floatx4*>(xp + (size_t)(col0 + tn) * ENC_GATES);
-                }
-            }
-            __syncthreads();                               // the gate buffer is free again; after the last group h is complete
         }
+        __syncthreads();                                   // the sums are in LDS and every wave has read h
+        // ---- (3) thread = hidden unit
+#pragma unroll
+        for (int j = 0; j < GCOLS; ++j) {
+            if (j >= nact) break;                          // uniform over the workgroup
+            const int len = len_of[j], col0 = col0_of[j];
+            if (s >= len) continue;                        // this request has ended
+            const int t = token(j, s);
+            const floatx4 gs = *reinterpret_cast<const floatx4*>(gl + j * ENC_GATES + 4 * tid) + xnext[j];
+            const float gi = sigmoidf_(gs[0]), gf = sigmoidf_(gs[1]), gg = tanhf_(gs[2]), go = sigmoidf_(gs[3]);
+            const float cn = gf * cl[tid * 16 + j] + gi * gg;
+            cl[tid * 16 + j] = cn;
+            const float h = go * tanhf_(cn);
+            reinterpret_cast<XT*>(hb)[(((tid / G::KB) * 64 + j + 16 * ((tid % G::KB) / G::EPL)) * G::EPL) + (tid % G::EPL)] = from_float<XT>(h);
+            out[(size_t)(col0 + t) * (2 * ENC_HID) + dir * ENC_HID + tid] = h;
+            const int tn = min(max(token(j, s + 1), 0), len - 1);      // next step's input projection, clamped to the request
+            xnext[j] = *reinterpret_cast<const floatx4*>(xp + (size_t)(col0 + tn) * ENC_GATES);
+        }
+        __syncthreads();                                   // h is complete and the gate buffer free for the next step
     }
 }
 
