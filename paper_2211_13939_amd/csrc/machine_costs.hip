@@ -72,6 +72,39 @@ __global__ __launch_bounds__(512) void k_stream(const uint4* __restrict__ a, uns
     if (acc == 0x12345678u) *out = acc;
 }
 
+// ---- 3b. the same, PASSES times over the same NL * 8 KiB inside one kernel: passes after the first find the data in L2
+template <int NL, int PASSES>
+__global__ __launch_bounds__(512) void k_restream(const uint4* __restrict__ a, unsigned* out)
+{
+    const uint4* p = a + (size_t)blockIdx.x * NL * 512 + threadIdx.x;
+    unsigned acc = 0;
+    for (int pass = 0; pass < PASSES; ++pass) {
+        uint4 v[NL];
+#pragma unroll
+        for (int k = 0; k < NL; ++k) v[k] = p[(size_t)k * 512];
+#pragma unroll
+        for (int k = 0; k < NL; ++k) acc ^= v[k].x ^ v[k].w;
+        p += (acc == 0x9abcdef0u);              // unknown to the compiler: the next pass cannot reuse this one's registers
+    }
+    if (acc == 0x12345678u) *out = acc;
+}
+
+template <int NL, int PASSES> static int restream(hipStream_t s, const uint4* big, unsigned* out_u, double* t_prev)
+{
+    hipEvent_t e0, e1; CK(hipEventCreate(&e0)); CK(hipEventCreate(&e1));
+    float ms;
+    for (int i = 0; i < 3; ++i) hipLaunchKernelGGL((k_restream<NL, PASSES>), dim3(1), dim3(512), 0, s, big, out_u);
+    CK(hipEventRecord(e0, s));
+    for (int i = 0; i < 50; ++i) hipLaunchKernelGGL((k_restream<NL, PASSES>), dim3(1), dim3(512), 0, s, big, out_u);
+    CK(hipEventRecord(e1, s)); CK(hipEventSynchronize(e1)); CK(hipEventElapsedTime(&ms, e0, e1));
+    const double t = ms * 1e3 / 50;
+    printf("    1 workgroup, %d pass(es) over the same %3d KiB: %6.2f us per launch", PASSES, NL * 8, t);
+    if (*t_prev > 0) printf("   (each further pass: %.2f us = %.0f GB/s)", (t - *t_prev), NL * 8192.0 / ((t - *t_prev) * 1e-6) / 1e9);
+    printf("\n");
+    *t_prev = t;
+    return 0;
+}
+
 template <int NL> static int stream(hipStream_t s, const uint4* big, unsigned* out_u, int grid, double* t_prev, double* b_prev)
 {
     hipEvent_t e0, e1; CK(hipEventCreate(&e0)); CK(hipEventCreate(&e1));
@@ -241,6 +274,16 @@ int main()
         if (stream<16>(s, big, out_u, grid, &t_prev, &b_prev)) return 1;
         if (stream<32>(s, big, out_u, grid, &t_prev, &b_prev)) return 1;
         if (stream<48>(s, big, out_u, grid, &t_prev, &b_prev)) return 1;
+    }
+    printf("3b. one workgroup re-reading what it has just read (later passes are L2 hits)\n");
+    {
+        double tp = 0;
+        if (restream<32, 1>(s, big, out_u, &tp)) return 1;
+        if (restream<32, 2>(s, big, out_u, &tp)) return 1;
+        tp = 0;
+        if (restream<48, 1>(s, big, out_u, &tp)) return 1;
+        if (restream<48, 2>(s, big, out_u, &tp)) return 1;
+        if (restream<48, 3>(s, big, out_u, &tp)) return 1;
     }
     return 0;
 }
