@@ -105,6 +105,33 @@ template <int NL, int PASSES> static int restream(hipStream_t s, const uint4* bi
     return 0;
 }
 
+// ---- 3c. one workgroup of T threads streams BYTES with all loads in flight: does the rate follow the number of waves?
+template <int T, int BYTES>
+__global__ __launch_bounds__(T) void k_stream_threads(const uint4* __restrict__ a, unsigned* out)
+{
+    constexpr int NL = BYTES / 16 / T;
+    const uint4* p = a + threadIdx.x;
+    uint4 v[NL];
+#pragma unroll
+    for (int k = 0; k < NL; ++k) v[k] = p[(size_t)k * T];
+    unsigned acc = 0;
+#pragma unroll
+    for (int k = 0; k < NL; ++k) acc ^= v[k].x ^ v[k].w;
+    if (acc == 0x12345678u) *out = acc;
+}
+
+template <int T, int BYTES> static int stream_threads(hipStream_t s, const uint4* big, unsigned* out_u)
+{
+    hipEvent_t e0, e1; CK(hipEventCreate(&e0)); CK(hipEventCreate(&e1));
+    float ms;
+    for (int i = 0; i < 3; ++i) hipLaunchKernelGGL((k_stream_threads<T, BYTES>), dim3(1), dim3(T), 0, s, big, out_u);
+    CK(hipEventRecord(e0, s));
+    for (int i = 0; i < 50; ++i) hipLaunchKernelGGL((k_stream_threads<T, BYTES>), dim3(1), dim3(T), 0, s, big, out_u);
+    CK(hipEventRecord(e1, s)); CK(hipEventSynchronize(e1)); CK(hipEventElapsedTime(&ms, e0, e1));
+    printf("    1 workgroup of %4d threads x %3d KiB: %6.2f us per launch\n", T, BYTES / 1024, ms * 1e3 / 50);
+    return 0;
+}
+
 template <int NL> static int stream(hipStream_t s, const uint4* big, unsigned* out_u, int grid, double* t_prev, double* b_prev)
 {
     hipEvent_t e0, e1; CK(hipEventCreate(&e0)); CK(hipEventCreate(&e1));
@@ -285,5 +312,12 @@ int main()
         if (restream<48, 2>(s, big, out_u, &tp)) return 1;
         if (restream<48, 3>(s, big, out_u, &tp)) return 1;
     }
+    printf("3c. one workgroup, the same bytes with more or fewer waves\n");
+    if (stream_threads<256, 128 << 10>(s, big, out_u)) return 1;
+    if (stream_threads<512, 128 << 10>(s, big, out_u)) return 1;
+    if (stream_threads<1024, 128 << 10>(s, big, out_u)) return 1;
+    if (stream_threads<256, 256 << 10>(s, big, out_u)) return 1;
+    if (stream_threads<512, 256 << 10>(s, big, out_u)) return 1;
+    if (stream_threads<1024, 256 << 10>(s, big, out_u)) return 1;
     return 0;
 }
