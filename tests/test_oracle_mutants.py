@@ -283,3 +283,67 @@ def test_encoder_pins_catch_planted_mistake(name, encoder_source):
     with tempfile.TemporaryDirectory() as tmp:
         lib = _build_encoder_variant(encoder_source.replace(old, new), tmp, "mutant")
         assert _pins_fail(lib, ENCODER_PINS), f"no pin noticed: {name}"
+
+
+# ---- the PostNet oracle (oracle/postnet_oracle.c), same method
+from tests import test_postnet_oracle as ppins
+
+POSTNET_MUTANTS = {
+    "convolution flipped":
+        ("int tt = t + k - ORC_PN_TAPS / 2;", "int tt = t - k + ORC_PN_TAPS / 2;"),
+    "padding off by one":
+        ("int tt = t + k - ORC_PN_TAPS / 2;", "int tt = t + k - ORC_PN_TAPS / 2 - 1;"),
+    "bias dropped":
+        ("double s = (double)b[co];", "double s = 0.0;"),
+    "weights transposed":
+        ("w[((size_t)co * c_in + ci) * ORC_PN_TAPS + k]", "w[(((size_t)ci * c_out + co) * ORC_PN_TAPS + k) % ((size_t)c_in * c_out * ORC_PN_TAPS)]"),
+    "tanh after the last layer too":
+        ("orc_conv5(T, c_in, c_out, w[l], b[l], cur, l != n_layers - 1, nxt);", "orc_conv5(T, c_in, c_out, w[l], b[l], cur, 1, nxt);"),
+    "no tanh between layers":
+        ("orc_conv5(T, c_in, c_out, w[l], b[l], cur, l != n_layers - 1, nxt);", "orc_conv5(T, c_in, c_out, w[l], b[l], cur, 0, nxt);"),
+    "residual sum dropped":
+        ("out[i] = mel[i] + cur[i];", "out[i] = cur[i];"),
+    "one layer skipped":
+        ("for (int l = 0; l < n_layers; ++l) {\n        int c_in = l == 0 ? n_mel : channels;",
+         "for (int l = 0; l < n_layers; ++l) {\n        if (l == 1) continue;\n        int c_in = l == 0 ? n_mel : channels;"),
+    "chunk taken from the wrong end":
+        ("memcpy(out, all + (size_t)s * n_mel,", "memcpy(out, all,"),
+}
+
+POSTNET_PINS = [
+    lambda: [ppins.test_stack_equals_library_convolutions(T) for T in (1, 5, 23)],
+    lambda: ppins.test_single_layer_delta_kernels_shift_with_zero_fill(),
+    lambda: ppins.test_bias_and_channel_order(),
+    lambda: ppins.test_centre_tap_identity_stack_closed_form(),
+    lambda: ppins.test_last_chunk_equals_whole_utterance_and_chunks_tile(),
+    lambda: ppins.test_receptive_field_of_a_chunk(),
+]
+
+
+def _build_postnet_variant(src_text: str, workdir: str, name: str):
+    c = os.path.join(workdir, name + ".c")
+    so = os.path.join(workdir, name + ".so")
+    with open(c, "w") as f:
+        f.write(src_text)
+    subprocess.run(["gcc", "-O1", "-std=c99", "-fPIC", "-shared", "-fopenmp", "-w", "-o", so, obuild.SRC, c,
+                    obuild.SRC_VOCODER, obuild.SRC_ENCODER, "-lm"], check=True)
+    return orc.load(so)
+
+
+@pytest.fixture(scope="module")
+def postnet_source():
+    return open(obuild.SRC_POSTNET).read()
+
+
+def test_unmodified_postnet_source_passes_every_pin(postnet_source):
+    with tempfile.TemporaryDirectory() as tmp:
+        assert not _pins_fail(_build_postnet_variant(postnet_source, tmp, "clean"), POSTNET_PINS)
+
+
+@pytest.mark.parametrize("name", sorted(POSTNET_MUTANTS))
+def test_postnet_pins_catch_planted_mistake(name, postnet_source):
+    old, new = POSTNET_MUTANTS[name]
+    assert postnet_source.count(old) == 1, f"mutation site for '{name}' not found exactly once"
+    with tempfile.TemporaryDirectory() as tmp:
+        lib = _build_postnet_variant(postnet_source.replace(old, new), tmp, "mutant")
+        assert _pins_fail(lib, POSTNET_PINS), f"no pin noticed: {name}"
