@@ -17,6 +17,8 @@
 #include "kernels.h"
 #include "mfma.h"
 
+#include <type_traits>
+
 namespace tts {
 
 // ---------------------------------------------------------------------------
@@ -149,13 +151,15 @@ __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm(
 // repeated reads of the weights hit that XCD's L2.  The sums are taken in the same order as in k_lstm.
 // PIPE (R = 4, one pool tile per round): the activations of the next tile are requested before the
 // products of the current one, two tiles per trip through the loop so that both buffers stay in registers.
-template <typename XT, int K, int R, bool PIPE = false>
+template <typename XT, int K, int R, bool PIPE = false, bool QP = false>
 __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm_rc(
     const uint4* __restrict__ Wfrag, const float* __restrict__ bias, const uint4* __restrict__ X,
     float* __restrict__ c_state, XT* __restrict__ hout0, int nk0, int off0,
     XT* __restrict__ hout1, int nk1, int off1,
-    int n_tiles, const int* __restrict__ live, const int* __restrict__ done)
+    int n_tiles, const int* __restrict__ live, const int* __restrict__ done,
+    const float* __restrict__ wq_epi = nullptr, float* __restrict__ qpart = nullptr)
 {
+    static_assert(!QP || (R == 2 && !PIPE), "the query partials are built for the two-row-tile kernel");
     constexpr int NW = LSTM_WAVES;
     constexpr int NK = K / Frag<XT>::KB;
     constexpr int NF = NK / NW;
@@ -180,6 +184,17 @@ __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm_rc(
     const int unit = (R * rg + er) * 4 + (lane >> 4);
     floatx4 bias4 = {0.f, 0.f, 0.f, 0.f};
     if (wave < 4) bias4 = *reinterpret_cast<const floatx4*>(bias + unit * 4);
+    // QP: the workgroup's eight units of h give a rank-8 partial of q = W_q h per slot (see k_lstm): the wave that
+    // owns row tile 0 of a pool tile takes the other row tile's four units from LDS and chains two MFMAs.
+    float wq[QP ? 2 : 1][QP ? 8 : 1];
+    __shared__ float s_hq[QP ? 2 : 1][4][64];
+    if constexpr (QP) {
+#pragma unroll
+        for (int r = 0; r < 2; ++r)
+#pragma unroll
+            for (int at = 0; at < 8; ++at) wq[r][at] = wq_epi[((size_t)(R * rg + r) * 8 + at) * 64 + lane];
+    }
+    int round_no = 0;
 
     if constexpr (PIPE) {
         static_assert(!PIPE || TP == 1, "the pipelined loop handles one pool tile per round");
@@ -263,6 +278,7 @@ __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm_rc(
         }
         __syncthreads();
         const int slotE = (wave < 4 && tp + et < c1 && lv && !dn) ? sl : -1;
+        float hq = 0.f;
         if (slotE >= 0) {
             floatx4 g = bias4;
 #pragma unroll
@@ -274,8 +290,26 @@ __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm_rc(
             const XT h = from_float<XT>(go * tanhf_(c));
             hout0[xoff<XT>(nk0, slotE, off0 + unit)] = h;
             hout1[xoff<XT>(nk1, slotE, off1 + unit)] = h;
+            hq = to_float(h);
+        }
+        if constexpr (QP) {
+            if (wave < 4) s_hq[round_no & 1][wave][lane] = hq;
         }
         __syncthreads();
+        if constexpr (QP) {
+            if ((wave == 0 || wave == 2) && tp + et < c1) {      // whole waves: the MFMAs run outside the per-lane branch
+                const float other = s_hq[round_no & 1][wave + 1][lane];
+#pragma unroll
+                for (int at = 0; at < 8; ++at) {
+                    const floatx4 z = {0.f, 0.f, 0.f, 0.f};
+                    floatx4 part = __builtin_amdgcn_mfma_f32_16x16x4f32(wq[0][at], hq, z, 0, 0, 0);
+                    part = __builtin_amdgcn_mfma_f32_16x16x4f32(wq[1][at], other, part, 0, 0, 0);
+                    if (slotE >= 0)
+                        *reinterpret_cast<floatx4*>(qpart + ((size_t)slotE * QP_STRIDE + rg) * ATT + 16 * at + 4 * (lane >> 4)) = part;
+                }
+            }
+            ++round_no;
+        }
     }
 }
 
@@ -383,7 +417,7 @@ template <> struct LsaTile<bf16_t> {
     }
 };
 
-template <typename XT, typename MT, int S, bool QP>
+template <typename XT, typename MT, int S, int QP>
 __global__ __launch_bounds__(LSA_THREADS) void k_lsa(DevPtrs d, int cur)
 {
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
@@ -403,7 +437,7 @@ __global__ __launch_bounds__(LSA_THREADS) void k_lsa(DevPtrs d, int cur)
     // increasing i; then q[a] = (s0 + s1) + (s2 + s3).
     // Otherwise: on MFMA here, wave w contracting k in [128 w, 128 w + 128) for all 128 outputs
     // with 16 copies of h_att as the columns; the weights do not depend on the request.
-    constexpr int QN = QP ? 64 : 1;
+    constexpr int QN = QP ? QP / 4 : 1;           // partials per thread: QP partial products per slot, four quarters
     constexpr int NKQ = HID / Frag<XT>::KB;       // fragments per row tile of W_q
     constexpr int NKW = NKQ / LSA_WAVES;          // fragments per wave
     constexpr int MG = QP ? 1 : (sizeof(XT) == 2 ? 8 : 2);   // row tiles whose fragments are in flight together
@@ -1046,7 +1080,7 @@ __global__ __launch_bounds__(256) void k_x_set(XT* X, int NK, int slot, int off,
 // launch wrappers
 // ---------------------------------------------------------------------------
 template <typename XT, typename MT>
-static hipError_t step_typed(const DevPtrs& d, int n_req, int n_tiles, int lsa_split, int rows, bool qpart, int cur, hipStream_t s, hipEvent_t* ev)
+static hipError_t step_typed(const DevPtrs& d, int n_req, int n_tiles, int lsa_split, int rows, int qpart, int cur, hipStream_t s, hipEvent_t* ev)
 {
     constexpr int KB = Frag<XT>::KB;
     auto mark = [&](int i) { if (ev) (void)hipEventRecord(ev[i], s); };
@@ -1057,17 +1091,25 @@ static hipError_t step_typed(const DevPtrs& d, int n_req, int n_tiles, int lsa_s
     mark(0);
     // H_att(t): consumed by this step's decoder LSTM / attention and by the next step's attention LSTM
     constexpr bool HAS_WIDE = sizeof(XT) == 2;     // the fp32 fragments of several row tiles do not fit the register file
-    if (!HAS_WIDE || qpart) rows = 1;              // pools that pass q as partial products are small: one-row-tile kernels
+    // q as partial products: mode 1 = rank-4 partials from the one-row-tile kernel (small pools), mode 2 = rank-8
+    // partials from the two-row-tile kernel; the mode is fixed per pool, so is the kernel that goes with it
+    if (!HAS_WIDE) { rows = 1; if (qpart == 2) qpart = 0; }
+    if (qpart == 1) rows = 1;
+    const int att_rows = qpart == 2 ? 2 : rows;
     const dim3 lg(HID / 4), lb(LSTM_WAVES * 64);
-    if (rows == 4) {
+    if (qpart == 2) {
+        if constexpr (HAS_WIDE)
+            hipLaunchKernelGGL((k_lstm_rc<XT, K_ATT, 2, false, true>), lg, lb, 0, s, d.Wa, d.ba, xatt_cur, d.c_att, xdec_cur, K_DEC / KB, XD_HA,
+                               xatt_nxt, K_ATT / KB, XA_H, n_tiles, d.live, d.done, d.Wq_epi, d.qpart);
+    } else if (att_rows == 4) {
         if constexpr (HAS_WIDE)
             hipLaunchKernelGGL((k_lstm_rc<XT, K_ATT, 4, true>), lg, lb, 0, s, d.Wa, d.ba, xatt_cur, d.c_att, xdec_cur, K_DEC / KB, XD_HA,
-                               xatt_nxt, K_ATT / KB, XA_H, n_tiles, d.live, d.done);
-    } else if (rows == 2) {
+                               xatt_nxt, K_ATT / KB, XA_H, n_tiles, d.live, d.done, nullptr, nullptr);
+    } else if (att_rows == 2) {
         if constexpr (HAS_WIDE)
             hipLaunchKernelGGL((k_lstm_rc<XT, K_ATT, 2>), lg, lb, 0, s, d.Wa, d.ba, xatt_cur, d.c_att, xdec_cur, K_DEC / KB, XD_HA,
-                               xatt_nxt, K_ATT / KB, XA_H, n_tiles, d.live, d.done);
-    } else if (qpart)
+                               xatt_nxt, K_ATT / KB, XA_H, n_tiles, d.live, d.done, nullptr, nullptr);
+    } else if (qpart == 1)
         hipLaunchKernelGGL((k_lstm<XT, K_ATT, true>), lg, lb, 0, s,
                            d.Wa, d.ba, xatt_cur, d.c_att, xdec_cur, K_DEC / KB, XD_HA, xatt_nxt, K_ATT / KB, XA_H,
                            n_tiles, d.live, d.done, d.Wq_epi, d.qpart);
@@ -1076,15 +1118,15 @@ static hipError_t step_typed(const DevPtrs& d, int n_req, int n_tiles, int lsa_s
                            d.Wa, d.ba, xatt_cur, d.c_att, xdec_cur, K_DEC / KB, XD_HA, xatt_nxt, K_ATT / KB, XA_H,
                            n_tiles, d.live, d.done, nullptr, nullptr);
     mark(1);
-    if (qpart) {
-        if (lsa_split == 4) hipLaunchKernelGGL((k_lsa<XT, MT, 4, true>), dim3(n_req * 4), dim3(LSA_THREADS), 0, s, d, cur);
-        else if (lsa_split == 2) hipLaunchKernelGGL((k_lsa<XT, MT, 2, true>), dim3(n_req * 2), dim3(LSA_THREADS), 0, s, d, cur);
-        else hipLaunchKernelGGL((k_lsa<XT, MT, 1, true>), dim3(n_req), dim3(LSA_THREADS), 0, s, d, cur);
-    } else {
-        if (lsa_split == 4) hipLaunchKernelGGL((k_lsa<XT, MT, 4, false>), dim3(n_req * 4), dim3(LSA_THREADS), 0, s, d, cur);
-        else if (lsa_split == 2) hipLaunchKernelGGL((k_lsa<XT, MT, 2, false>), dim3(n_req * 2), dim3(LSA_THREADS), 0, s, d, cur);
-        else hipLaunchKernelGGL((k_lsa<XT, MT, 1, false>), dim3(n_req), dim3(LSA_THREADS), 0, s, d, cur);
-    }
+    auto lsa = [&](auto qp) {
+        constexpr int QPN = decltype(qp)::value;
+        if (lsa_split == 4) hipLaunchKernelGGL((k_lsa<XT, MT, 4, QPN>), dim3(n_req * 4), dim3(LSA_THREADS), 0, s, d, cur);
+        else if (lsa_split == 2) hipLaunchKernelGGL((k_lsa<XT, MT, 2, QPN>), dim3(n_req * 2), dim3(LSA_THREADS), 0, s, d, cur);
+        else hipLaunchKernelGGL((k_lsa<XT, MT, 1, QPN>), dim3(n_req), dim3(LSA_THREADS), 0, s, d, cur);
+    };
+    if (qpart == 1) lsa(std::integral_constant<int, HID / 4>{});         // 256 rank-4 partials per slot
+    else if (qpart == 2) lsa(std::integral_constant<int, HID / 8>{});    // 128 rank-8 partials
+    else lsa(std::integral_constant<int, 0>{});
     mark(2);
     // H_dec(t): consumed by this step's projection and the next step's decoder LSTM (same buffer)
     const uint4* xdec_in = reinterpret_cast<const uint4*>(d.xdec[cur]);
@@ -1108,9 +1150,9 @@ static hipError_t step_typed(const DevPtrs& d, int n_req, int n_tiles, int lsa_s
 hipError_t launch_step(const DevPtrs& d, const StepLaunch& cfg, int cur, hipStream_t s, hipEvent_t* ev)
 {
     if (cfg.n_blocks < 1 || cfg.n_tiles < 1) return hipSuccess;
-    if (cfg.wdtype == 0 && cfg.mdtype == 0) return step_typed<float, float>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cfg.lstm_rows, cfg.q_partials != 0, cur, s, ev);
-    if (cfg.wdtype == 1 && cfg.mdtype == 1) return step_typed<bf16_t, bf16_t>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cfg.lstm_rows, cfg.q_partials != 0, cur, s, ev);
-    if (cfg.wdtype == 1 && cfg.mdtype == 0) return step_typed<bf16_t, float>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cfg.lstm_rows, cfg.q_partials != 0, cur, s, ev);
+    if (cfg.wdtype == 0 && cfg.mdtype == 0) return step_typed<float, float>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cfg.lstm_rows, cfg.q_partials, cur, s, ev);
+    if (cfg.wdtype == 1 && cfg.mdtype == 1) return step_typed<bf16_t, bf16_t>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cfg.lstm_rows, cfg.q_partials, cur, s, ev);
+    if (cfg.wdtype == 1 && cfg.mdtype == 0) return step_typed<bf16_t, float>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cfg.lstm_rows, cfg.q_partials, cur, s, ev);
     return hipErrorInvalidValue;
 }
 

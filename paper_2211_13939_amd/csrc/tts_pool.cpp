@@ -74,7 +74,18 @@ struct Layout {
 // Pools of at most 16 slots (one tile) pass the attention query from the attention LSTM to the attention
 // kernel as partial products (cheaper when a step is latency-bound, 128 KB of stores per request
 // otherwise).  Fixed per pool, so that a request's frames never depend on who else is in the pool.
-bool q_partials_for(const tts_config& c) { return c.max_pool <= 16; }
+// how the attention query reaches the attention kernel: 0 = computed there from W_q; 1 = rank-4 partial products from
+// the attention LSTM (pools of at most 16 slots); 2 = rank-8 partials from its two-row-tile kernel (bf16 pools of up
+// to QP8_MAX_POOL slots: measured 1.5 us per step faster at 32 slots, 0.8 us slower at 64, where the attention
+// LSTM pays more for the partials than the attention kernel saves).  Fixed per pool: a request's bits do not
+// depend on what else the pool holds.
+constexpr int QP8_MAX_POOL = 32;
+int q_partials_for(const tts_config& c)
+{
+    if (c.max_pool <= 16) return 1;
+    if (c.max_pool <= QP8_MAX_POOL && c.weight_dtype == TTS_DTYPE_BF16) return 2;
+    return 0;
+}
 
 Layout make_layout(const tts_config& c)
 {
@@ -442,7 +453,7 @@ static void shape_for(const tts_pool* p, int span, StepLaunch* sl)
     sl->n_tiles = (span + 15) / 16;
     sl->lsa_split = lsa_split_for(span);
     sl->lstm_rows = lstm_rows_for(span);
-    sl->q_partials = q_partials_for(p->cfg) ? 1 : 0;
+    sl->q_partials = q_partials_for(p->cfg);
 }
 
 // Queue `nsteps` consecutive steps for the current membership.  With graphs the

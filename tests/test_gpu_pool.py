@@ -291,6 +291,24 @@ def test_small_and_large_capacity_pools_agree(wl8, weights_fp32, solo_frames):
         assert np.abs(big[i, :n] - solo_frames[i]).max() <= 1e-5
 
 
+def test_mid_capacity_bf16_pool_rank8_query_partials(weights_bf16):
+    """bf16 pools of 17 .. 32 slots take the two-row-tile attention LSTM that hands the query over as rank-8
+    partial products: 24 requests against the oracle, and a request's bits do not depend on the pool's
+    composition (alone in slot 0 vs among 24, vs among 5 joining in another order)."""
+    wl = synth.small_workload(24, 10, 120, 30, 30, seed=71, bf16=True)
+    say("case capacity 32, bf16: 24 requests, 30 steps")
+    full = gpu_decode(wl, weights_bf16, list(range(24)), 30, max_pool=32)
+    sample = [0, 7, 16, 23]
+    ref, _, _ = oracle_decode(wl, weights_bf16, sample, 30, n_threads=4)
+    for k, i in enumerate(sample):
+        assert np.abs(full[i] - ref[k]).max() <= TOL_BF16
+    alone = gpu_decode(wl, weights_bf16, [7], 30, max_pool=32)[0]
+    np.testing.assert_array_equal(alone, full[7])
+    few = gpu_decode(wl, weights_bf16, [20, 3, 7, 11, 0], 30, max_pool=32)
+    np.testing.assert_array_equal(few[2], full[7])
+    np.testing.assert_array_equal(few[4], full[0])
+
+
 def test_c3_shrinking_pool_full_job(weights_bf16):
     """The whole c3 job as the benchmark runs it (requests retire at their own
     end): every request produces exactly its frame count, sampled requests match
