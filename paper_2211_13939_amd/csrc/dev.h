@@ -35,7 +35,7 @@ struct DevPtrs {
     const float* ba;      // [HID][4] gate-interleaved merged bias
     const float* bd;
     const void* Wq;       // [ATT][HID] WT, MFMA fragment order (8 row tiles): pools that compute q in the attention kernel
-    const float* Wq_epi;  // W_q as the A operands of the attention LSTM's rank-4 query products: [HID/4][8][64 lanes]
+    const float* Wq_epi;  // W_q as the A operands of the attention LSTM's rank-4 (or, two row tiles chained, rank-8) query products: [HID/4][8][64 lanes]
     float* qpart;         // [slots][HID/4][ATT] partial sums of q = W_q h_att, written and read within one step
     const void* lsa_kfrag; // location filters as per-lane MFMA A operands (layout depends on WT)
     const void* lsa_wfrag; // W_loc as per-lane MFMA A operands (layout depends on WT)

@@ -12,7 +12,7 @@ struct StepLaunch {
     int n_tiles;    // the projection grid covers 16-slot tiles 0 .. n_tiles - 1
     int lsa_split;  // workgroups per request in the attention kernel (1, 2 or 4; they split the context columns)
     int lstm_rows;  // row tiles per LSTM workgroup: 1 (all pool tiles each), 2 or 4 (1/2 or 1/4 of the pool tiles each)
-    int q_partials; // non-zero: the attention LSTM hands the query over as partial products (pools of <= 16 slots)
+    int q_partials; // how the attention LSTM hands the query over: 0 = not at all, 1 = rank-4 partial products (pools of <= 16 slots), 2 = rank-8 (<= 32)
 };
 
 // One decoder step (paper Eq. 2) for every request whose slot is flagged in d.live.

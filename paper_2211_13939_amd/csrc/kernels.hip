@@ -36,8 +36,10 @@ namespace tts {
 // of pulling all of W_q (256 KB in bf16, 512 KB in fp32) through its CU, which
 // bounds its prologue.  The partials cost this kernel 128 KB of stores per
 // request, so the scheme is used by pools of at most 16 slots only (where a
-// step is latency-bound); larger pools compute q in the attention kernel.
-// qpart[slot][row tile][a].
+// step is latency-bound); bf16 pools of up to 32 slots take the two-row-tile
+// kernel below with rank-8 partials (64 KB per request), and larger pools
+// compute q in the attention kernel.
+// qpart[slot][row tile or row group][a].
 // ---------------------------------------------------------------------------
 constexpr int LSTM_WAVES = 8;
 constexpr int QP_STRIDE = HID / 4;   // partial rows per slot in qpart
