@@ -408,10 +408,11 @@ extern "C" int tts_pool_add_request(tts_pool* p, const float* enc_out, int L, in
 // workgroups per request in the attention kernel: more when the pool alone cannot fill the chip
 static int lsa_split_for(int n_blocks) { return n_blocks <= 64 ? 4 : (n_blocks <= 128 ? 2 : 1); }
 
-// LSTM tiling by the slots spanned: up to 2 pool tiles a workgroup takes one row tile and all pool
-// tiles, up to 8 tiles two row tiles and half of them, above that the decoder LSTM takes four row tiles and a
+// LSTM tiling by the slots spanned: with one pool tile a workgroup takes one row tile, up to 8 tiles two row
+// tiles and half of the pool tiles (32 slots: 32.1 -> 31.0 us per step against one row tile), above that the
+// decoder LSTM takes four row tiles and a
 // quarter (the attention LSTM, with its shorter K, stays at two: its four-row variant measured slower)
-static int lstm_rows_for(int n_blocks) { return n_blocks > 128 ? 4 : (n_blocks > 32 ? 2 : 1); }
+static int lstm_rows_for(int n_blocks) { return n_blocks > 128 ? 4 : (n_blocks > 16 ? 2 : 1); }
 
 // most steps captured into one graph
 static const int MAX_GRAPH_STEPS = 32;
