@@ -37,6 +37,9 @@ struct DevPtrs {
     const void* Wq;       // [ATT][HID] WT, MFMA fragment order (8 row tiles): pools that compute q in the attention kernel
     const float* Wq_epi;  // W_q as the A operands of the attention LSTM's rank-4 (or, two row tiles chained, rank-8) query products: [HID/4][8][64 lanes]
     float* qpart;         // [slots][HID/4][ATT] partial sums of q = W_q h_att, written and read within one step
+    float* pre_att;       // [tiles][HID/4 row tiles][64 lanes][4]: the attention LSTM's gate sums over [A; H_att], MFMA accumulator layout,
+                          // written by the projection kernel's launch for the next step (null: the LSTM kernels contract all of K)
+    float* pre_dec;       // same for the decoder LSTM's sums over H_dec
     const void* lsa_kfrag; // location filters as per-lane MFMA A operands (layout depends on WT)
     const void* lsa_wfrag; // W_loc as per-lane MFMA A operands (layout depends on WT)
     const float* WmemT;   // [ENC][ATT] fp32 (join time only)

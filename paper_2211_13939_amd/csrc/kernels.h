@@ -13,7 +13,11 @@ struct StepLaunch {
     int lsa_split;  // workgroups per request in the attention kernel (1, 2 or 4; they split the context columns)
     int lstm_rows;  // row tiles per LSTM workgroup: 1 (all pool tiles each), 2 or 4 (1/2 or 1/4 of the pool tiles each)
     int q_partials; // how the attention LSTM hands the query over: 0 = not at all, 1 = rank-4 partial products (pools of <= 16 slots), 2 = rank-8 (<= 32)
+    int pre_gates;  // 1: the projection's launch also forms the next step's gate pre-sums (d.pre_att / d.pre_dec; n_tiles <= PRESUM_MAX_TILES)
 };
+
+// pools of at most this many 16-slot tiles can run with gate pre-sums
+constexpr int PRESUM_MAX_TILES = 4;
 
 // One decoder step (paper Eq. 2) for every request whose slot is flagged in d.live.
 // `cur` selects which half of the double-buffered activations is read.
@@ -26,6 +30,8 @@ hipError_t launch_set_live(const DevPtrs& d, const LiveArgs& args, hipStream_t s
 hipError_t launch_slot_init(const DevPtrs& d, int wdtype, int slot, int L, int n_steps, hipStream_t s);
 // F_enc (fp32, device) -> slot memory, and processed memory PM = F W_mem^T
 hipError_t launch_join_memory(const DevPtrs& d, int mdtype, const float* F_dev, int slot, int L, hipStream_t s);
+// the gate pre-sums of one pool tile from activation half `nxt` (after a state overwrite between steps)
+hipError_t launch_presum_tile(const DevPtrs& d, int wdtype, int tile, int nxt, hipStream_t s);
 // p = Pre(m_last) into both activation buffers of one slot (after a state overwrite)
 hipError_t launch_prenet_slot(const DevPtrs& d, int wdtype, int slot, hipStream_t s);
 

@@ -44,17 +44,33 @@ namespace tts {
 constexpr int LSTM_WAVES = 8;
 constexpr int QP_STRIDE = HID / 4;   // partial rows per slot in qpart
 
-template <typename XT, int K, bool QP>
+// Gate pre-sums (PRE).  Part of an LSTM's input is known long before the kernel runs: [A; H_att] of the attention
+// LSTM's input is complete once the attention kernel of the previous step has finished, H_dec of the decoder LSTM's
+// input once the previous step's decoder LSTM has.  Pools of few tiles leave almost every CU idle during the
+// projection kernel (one workgroup per 16 slots), so that launch carries extra workgroups which contract those parts
+// with their columns of the gate matrices and store the sums in accumulator layout:
+//   pre[pool tile][row tile][lane] (floatx4) = sum over the late fragments of W[row tile] x[pool tile].
+// The LSTM kernels of the next step then contract only the early fragments -- Pre(M_last) (K = 256 of 1792) and
+// [H_att; A] (K = 1536 of 2560) -- and add pre in the cell update.  Wave w owns fragments w, w + 8, ...: the early part
+// is the first lstm_main_frags() of them, for both matrices.
+template <typename XT, int K> constexpr int lstm_main_frags()
+{
+    static_assert(K == K_ATT || K == K_DEC, "the two gate matrices");
+    return (K == K_ATT ? PRENET : HID + ENC) / Frag<XT>::KB / LSTM_WAVES;
+}
+static_assert(XA_P == 0 && XD_HA == 0 && XD_A == HID, "the early parts lead the activation rows");
+
+template <typename XT, int K, bool QP, bool PRE>
 __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm(
     const uint4* __restrict__ Wfrag, const float* __restrict__ bias, const uint4* __restrict__ X,
     float* __restrict__ c_state, XT* __restrict__ hout0, int nk0, int off0,
     XT* __restrict__ hout1, int nk1, int off1,
     int n_tiles, const int* __restrict__ live, const int* __restrict__ done,
-    const float* __restrict__ wq_epi, float* __restrict__ qpart)
+    const float* __restrict__ wq_epi, float* __restrict__ qpart, const floatx4* __restrict__ pre)
 {
     constexpr int NW = LSTM_WAVES;
     constexpr int NK = K / Frag<XT>::KB;      // fragments per row tile / per pool tile
-    constexpr int NF = NK / NW;               // fragments per wave
+    constexpr int NF = PRE ? lstm_main_frags<XT, K>() : NK / NW;   // fragments per wave (the early ones only with PRE)
     static_assert(NK % NW == 0, "K must split evenly over the waves");
     constexpr int TIF = sizeof(XT) == 2 ? 4 : 1;   // pool tiles whose activations are in flight together
 
@@ -91,6 +107,8 @@ __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm(
         const int sl = my_tile * 16 + (lane & 15);
         const int lv = live[sl], dn = done[sl];
         const float c_old = c_state[(size_t)sl * HID + unit];
+        floatx4 pre4 = {0.f, 0.f, 0.f, 0.f};
+        if constexpr (PRE) pre4 = pre[((size_t)my_tile * (HID / 4) + rt) * 64 + lane];
         __builtin_amdgcn_sched_barrier(0);   // issued here, looked at after the products
 #pragma unroll
         for (int t0 = 0; t0 < 4; t0 += TIF) {
@@ -120,6 +138,7 @@ __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm(
             floatx4 g = bias4;
 #pragma unroll
             for (int w = 0; w < NW; ++w) g += red[w][wave][lane];
+            if constexpr (PRE) g += pre4;
             const float gi = sigmoidf_(g[0]), gf = sigmoidf_(g[1]);
             const float gg = tanhf_(g[2]), go = sigmoidf_(g[3]);
             const float c = gf * c_old + gi * gg;
@@ -153,18 +172,19 @@ __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm(
 // repeated reads of the weights hit that XCD's L2.  The sums are taken in the same order as in k_lstm.
 // PIPE (R = 4, one pool tile per round): the activations of the next tile are requested before the
 // products of the current one, two tiles per trip through the loop so that both buffers stay in registers.
-template <typename XT, int K, int R, bool PIPE = false, bool QP = false>
+template <typename XT, int K, int R, bool PIPE = false, bool QP = false, bool PRE = false>
 __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm_rc(
     const uint4* __restrict__ Wfrag, const float* __restrict__ bias, const uint4* __restrict__ X,
     float* __restrict__ c_state, XT* __restrict__ hout0, int nk0, int off0,
     XT* __restrict__ hout1, int nk1, int off1,
     int n_tiles, const int* __restrict__ live, const int* __restrict__ done,
-    const float* __restrict__ wq_epi = nullptr, float* __restrict__ qpart = nullptr)
+    const float* __restrict__ wq_epi = nullptr, float* __restrict__ qpart = nullptr, const floatx4* __restrict__ pre = nullptr)
 {
     static_assert(!QP || (R == 2 && !PIPE), "the query partials are built for the two-row-tile kernel");
+    static_assert(!PRE || !PIPE, "pools large enough for the pipelined kernel leave no idle CUs for the pre-sums");
     constexpr int NW = LSTM_WAVES;
     constexpr int NK = K / Frag<XT>::KB;
-    constexpr int NF = NK / NW;
+    constexpr int NF = PRE ? lstm_main_frags<XT, K>() : NK / NW;
     constexpr int TP = 4 / R;                      // pool tiles per round: R x TP = 4 cell-update waves
     constexpr int NRG = HID / 4 / R;               // row groups
     static_assert(R == 2 || R == 4, "two or four row tiles per workgroup");
@@ -256,6 +276,8 @@ __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm_rc(
         const int sl = min(tp + et, c1 - 1) * 16 + (lane & 15);
         const int lv = live[sl], dn = done[sl];
         const float c_old = c_state[(size_t)sl * HID + unit];
+        floatx4 pre4 = {0.f, 0.f, 0.f, 0.f};
+        if constexpr (PRE) pre4 = pre[((size_t)min(tp + et, c1 - 1) * (HID / 4) + R * rg + er) * 64 + lane];
         __builtin_amdgcn_sched_barrier(0);
         uint4 b[TP][NF];
 #pragma unroll
@@ -285,6 +307,7 @@ __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm_rc(
             floatx4 g = bias4;
 #pragma unroll
             for (int w = 0; w < NW; ++w) g += red[w][wave][lane];
+            if constexpr (PRE) g += pre4;
             const float gi = sigmoidf_(g[0]), gf = sigmoidf_(g[1]);
             const float gg = tanhf_(g[2]), go = sigmoidf_(g[3]);
             const float c = gf * c_old + gi * gg;
@@ -313,6 +336,190 @@ __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm_rc(
             ++round_no;
         }
     }
+}
+
+// ---------------------------------------------------------------------------
+// Attention LSTM of pools with gate pre-sums.  What is left of its gates is K = 256 (the prenet output), so the shape
+// of a workgroup's tile no longer matters for the bytes it pulls, and the tile is chosen for the attention query
+// instead: a workgroup owns 8 row tiles (32 hidden units, one row tile per wave, no split of K) of one pool tile and
+// hands q = W_q h over as rank-32 partial products, 32 per slot (16 KB) instead of W_q itself (256 KB in bf16) through
+// every workgroup of the attention kernel.  Wave w forms the rows 16 w .. 16 w + 15 of the partial from the 32 units
+// of h the workgroup has just produced (eight chained 16x16x4 fp32 MFMAs, h through LDS).
+//   grid = 32 row groups x pool tiles; qpart[slot][row group][a]
+// ---------------------------------------------------------------------------
+constexpr int TALL_RT = 8;                      // row tiles per workgroup
+constexpr int QP_TALL = HID / 4 / TALL_RT;      // partials per slot
+
+template <typename XT>
+__global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm_att_tall(
+    const uint4* __restrict__ Wfrag, const float* __restrict__ bias, const uint4* __restrict__ X,
+    float* __restrict__ c_state, XT* __restrict__ hout0, int nk0, int off0,
+    XT* __restrict__ hout1, int nk1, int off1,
+    const int* __restrict__ live, const int* __restrict__ done,
+    const float* __restrict__ wq_epi, float* __restrict__ qpart, const floatx4* __restrict__ pre)
+{
+    static_assert(TALL_RT == LSTM_WAVES, "one row tile per wave");
+    constexpr int NK = K_ATT / Frag<XT>::KB;
+    constexpr int NF = PRENET / Frag<XT>::KB;       // the early fragments: all of them in every wave
+    constexpr int BPW = NF / LSTM_WAVES;            // of the pool tile's, fetched per wave
+    static_assert(NF % LSTM_WAVES == 0, "the activations' fragments split evenly over the waves");
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int rg = blockIdx.x % QP_TALL, tile = blockIdx.x / QP_TALL;
+    const int rt = rg * TALL_RT + wave;
+
+    uint4 a[NF];
+#pragma unroll
+    for (int f = 0; f < NF; ++f) a[f] = Wfrag[xfrag(NK, rt, f, lane)];
+    uint4 bw[BPW];
+#pragma unroll
+    for (int i = 0; i < BPW; ++i) bw[i] = X[xfrag(NK, tile, wave + i * LSTM_WAVES, lane)];
+    const int unit = rt * 4 + (lane >> 4), sl = tile * 16 + (lane & 15);
+    const floatx4 bias4 = *reinterpret_cast<const floatx4*>(bias + unit * 4);
+    const floatx4 pre4 = pre[((size_t)tile * (HID / 4) + rt) * 64 + lane];
+    const int lv = live[sl], dn = done[sl];
+    const float c_old = c_state[(size_t)sl * HID + unit];
+    // W_q[16 wave + lane % 16][32 rg + 4 s + lane / 16]: the A operands of the query partial's eight k steps
+    float wq[TALL_RT];
+#pragma unroll
+    for (int s = 0; s < TALL_RT; ++s) wq[s] = wq_epi[((size_t)(rg * TALL_RT + s) * 8 + wave) * 64 + lane];
+    __builtin_amdgcn_sched_barrier(0);
+
+    __shared__ uint4 s_b[NF][64];
+    __shared__ float s_h[4 * TALL_RT][16];
+#pragma unroll
+    for (int i = 0; i < BPW; ++i) s_b[wave + i * LSTM_WAVES][lane] = bw[i];
+    __syncthreads();
+    floatx4 g = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int f = 0; f < NF; ++f) g = mfma_frag<XT>(a[f], s_b[f][lane], g);
+    g += bias4;
+    g += pre4;
+    const bool active = lv && !dn;
+    const float gi = sigmoidf_(g[0]), gf = sigmoidf_(g[1]);
+    const float gg = tanhf_(g[2]), go = sigmoidf_(g[3]);
+    const float c = gf * c_old + gi * gg;
+    const XT h = from_float<XT>(go * tanhf_(c));
+    if (active) {
+        c_state[(size_t)sl * HID + unit] = c;
+        hout0[xoff<XT>(nk0, sl, off0 + unit)] = h;
+        hout1[xoff<XT>(nk1, sl, off1 + unit)] = h;
+    }
+    s_h[4 * wave + (lane >> 4)][lane & 15] = active ? to_float(h) : 0.f;
+    __syncthreads();
+    floatx4 part = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int s = 0; s < TALL_RT; ++s)
+        part = __builtin_amdgcn_mfma_f32_16x16x4f32(wq[s], s_h[4 * s + (lane >> 4)][lane & 15], part, 0, 0, 0);
+    if (active)
+        *reinterpret_cast<floatx4*>(qpart + ((size_t)sl * QP_STRIDE + rg) * ATT + 16 * wave + 4 * (lane >> 4)) = part;
+}
+
+// ---------------------------------------------------------------------------
+// The pre-sums themselves: one workgroup contracts the late fragments of NR <= 3 row tiles (from r0) with those of
+// NT <= 2 pool tiles (from t0), first for the attention LSTM, then for the decoder LSTM, as one stream of chunks (two
+// fragments per wave, row tile and pool tile) with PG_WIN chunks in flight: the loads never pause between the two
+// matrices.  Every (row tile, pool tile) sum is formed the same way whatever the split: wave w chains its fragments
+// w + 8 f in increasing f, the eight waves' sums are added in wave order.  `red` is 48 KB of LDS.
+// ---------------------------------------------------------------------------
+constexpr int PG_R = 3, PG_T = 2;
+constexpr int PG_CH = 2, PG_WIN = 4;
+typedef floatx4 (*PresumRed)[PG_R * PG_T][64];
+
+template <typename XT, int NR, int NT>
+__device__ __forceinline__ void gate_presums_rt(const DevPtrs& d, int nxt, int r0, int t0, PresumRed red)
+{
+    constexpr int NW = LSTM_WAVES, KB = Frag<XT>::KB;
+    constexpr int NK_A = K_ATT / KB, NK_D = K_DEC / KB;
+    constexpr int F0_A = lstm_main_frags<XT, K_ATT>(), F0_D = lstm_main_frags<XT, K_DEC>();
+    constexpr int NA = (NK_A / NW - F0_A) / PG_CH, ND = (NK_D / NW - F0_D) / PG_CH, N = NA + ND;   // chunks
+    static_assert((NK_A / NW - F0_A) % PG_CH == 0 && (NK_D / NW - F0_D) % PG_CH == 0, "the late fragments split evenly into chunks");
+    static_assert(NR * NT <= NW, "one wave adds up one (row tile, pool tile) sum");
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const uint4* __restrict__ Wa = d.Wa;
+    const uint4* __restrict__ Wd = d.Wd;
+    const uint4* __restrict__ xa = reinterpret_cast<const uint4*>(d.xatt[nxt]);
+    const uint4* __restrict__ xd = reinterpret_cast<const uint4*>(d.xdec[nxt]);
+
+    uint4 a[PG_WIN][NR][PG_CH], b[PG_WIN][NT][PG_CH];
+    floatx4 acc[NR][NT];
+    // chunk i (a compile-time number once the loops below are unrolled) into window slot i % PG_WIN
+    auto issue = [&](int i) __attribute__((always_inline)) {
+        const bool att = i < NA;
+        const uint4* W = att ? Wa : Wd;
+        const uint4* X = att ? xa : xd;
+        const int NK = att ? NK_A : NK_D;
+        const int f0 = att ? F0_A + i * PG_CH : F0_D + (i - NA) * PG_CH;
+#pragma unroll
+        for (int c = 0; c < PG_CH; ++c) {
+#pragma unroll
+            for (int r = 0; r < NR; ++r) a[i % PG_WIN][r][c] = W[xfrag(NK, r0 + r, wave + (f0 + c) * NW, lane)];
+#pragma unroll
+            for (int t = 0; t < NT; ++t) b[i % PG_WIN][t][c] = X[xfrag(NK, t0 + t, wave + (f0 + c) * NW, lane)];
+        }
+    };
+    auto clear = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int r = 0; r < NR; ++r)
+#pragma unroll
+            for (int t = 0; t < NT; ++t) acc[r][t] = floatx4{0.f, 0.f, 0.f, 0.f};
+    };
+    auto finish = [&](float* out) __attribute__((always_inline)) {
+#pragma unroll
+        for (int r = 0; r < NR; ++r)
+#pragma unroll
+            for (int t = 0; t < NT; ++t) red[wave][r * NT + t][lane] = acc[r][t];
+        __syncthreads();
+        if (wave < NR * NT) {
+            floatx4 g = red[0][wave][lane];
+#pragma unroll
+            for (int w = 1; w < NW; ++w) g += red[w][wave][lane];
+            reinterpret_cast<floatx4*>(out)[((size_t)(t0 + wave % NT) * (HID / 4) + r0 + wave / NT) * 64 + lane] = g;
+        }
+        __syncthreads();
+    };
+#pragma unroll
+    for (int i = 0; i < PG_WIN - 1 && i < N; ++i) issue(i);
+    clear();
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+        if (i + PG_WIN - 1 < N) issue(i + PG_WIN - 1);
+        __builtin_amdgcn_sched_barrier(0);       // the next chunk is requested before this one's products wait for theirs
+#pragma unroll
+        for (int c = 0; c < PG_CH; ++c)
+#pragma unroll
+            for (int r = 0; r < NR; ++r)
+#pragma unroll
+                for (int t = 0; t < NT; ++t) acc[r][t] = mfma_frag<XT>(a[i % PG_WIN][r][c], b[i % PG_WIN][t][c], acc[r][t]);
+        if (i == NA - 1) {
+            finish(d.pre_att);
+            clear();
+        }
+    }
+    finish(d.pre_dec);
+}
+
+// Both pre-sums of the next step, from the activation halves that step will read (cur ^ 1 of the step that is running),
+// for nr in 1 .. PG_R row tiles and nt in 1 .. PG_T pool tiles (the same for the whole workgroup).
+template <typename XT>
+__device__ __forceinline__ void gate_presums(const DevPtrs& d, int nxt, int r0, int nr, int t0, int nt, PresumRed red)
+{
+    if (nt == 1) {
+        if (nr == 1) gate_presums_rt<XT, 1, 1>(d, nxt, r0, t0, red);
+        else if (nr == 2) gate_presums_rt<XT, 2, 1>(d, nxt, r0, t0, red);
+        else gate_presums_rt<XT, 3, 1>(d, nxt, r0, t0, red);
+    } else {
+        if (nr == 1) gate_presums_rt<XT, 1, 2>(d, nxt, r0, t0, red);
+        else if (nr == 2) gate_presums_rt<XT, 2, 2>(d, nxt, r0, t0, red);
+        else gate_presums_rt<XT, 3, 2>(d, nxt, r0, t0, red);
+    }
+}
+
+// The pre-sums of one pool tile outside a step (after a state overwrite): one row tile per workgroup.
+template <typename XT>
+__global__ __launch_bounds__(LSTM_WAVES * 64) void k_presum_tile(DevPtrs d, int nxt, int tile)
+{
+    __shared__ floatx4 red[LSTM_WAVES][PG_R * PG_T][64];
+    gate_presums<XT>(d, nxt, blockIdx.x, 1, tile, 1, red);
 }
 
 // ---------------------------------------------------------------------------
@@ -793,8 +1000,8 @@ template <> __device__ __forceinline__ uint4 frag_from_f32<bf16_t>(const float* 
     return make_uint4(pack_bf16x2(p[0], p[1]), pack_bf16x2(p[2], p[3]), pack_bf16x2(p[4], p[5]), pack_bf16x2(p[6], p[7]));
 }
 
-template <typename XT>
-__global__ __launch_bounds__(PROJ_THREADS) void k_proj(DevPtrs d, int cur)
+template <typename XT, bool PRE>
+__global__ __launch_bounds__(PROJ_THREADS) void k_proj(DevPtrs d, int cur, int n_tiles)
 {
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int jl = lane & 15, g = lane >> 4;
@@ -814,7 +1021,6 @@ __global__ __launch_bounds__(PROJ_THREADS) void k_proj(DevPtrs d, int cur)
     // computed and dropped (there is no early exit: the compiler would move the loads below it).
     constexpr bool W_EARLY = sizeof(XT) == 2;
     constexpr int MH = W_EARLY ? NM : 1;          // row tiles whose fragments are in flight together
-    const int tile = blockIdx.x;
 
     __shared__ __attribute__((aligned(16))) float s_big[PROJ_WAVES * PROJ_ROWS * 16];   // partial sums, later hid
     // row strides of 100 and 260 floats (an odd number of 16-byte pieces): the 16 columns of a
@@ -825,6 +1031,34 @@ __global__ __launch_bounds__(PROJ_THREADS) void k_proj(DevPtrs d, int cur)
     float (*s_part)[PROJ_ROWS][16] = reinterpret_cast<float (*)[PROJ_ROWS][16]>(s_big);
     float (*s_hid)[HID_LD] = reinterpret_cast<float (*)[HID_LD]>(s_big);
     static_assert(16 * HID_LD <= PROJ_WAVES * PROJ_ROWS * 16, "hid must fit the partial-sum buffer it aliases");
+
+    if constexpr (PRE) {
+        // The launch has 256 workgroups, one per CU; workgroup b runs on XCD b % 8.  XCD 0 holds the projection's own
+        // workgroups (b = 8 * tile) and is otherwise left idle: beside workgroups that stream at full rate, the
+        // projection's loads took a quarter longer.  The other seven XCDs form the next step's gate pre-sums: XCD x takes
+        // row tiles 256 (x - 1) / 7 .. 256 x / 7 of both matrices (every weight is fetched from HBM once), its 32
+        // workgroups split into one or two groups by pool tiles (two from three tiles on: 32 x 32 is the shape that
+        // moves the fewest bytes through a CU), and a group's workgroups share the XCD's 36 or 37 row tiles evenly:
+        // two or three each (one or two without the split).
+        const int x = blockIdx.x & 7, i = blockIdx.x >> 3;
+        if (x != 0) {
+            static_assert(sizeof(floatx4) * LSTM_WAVES * PG_R * PG_T * 64 <= sizeof(s_big), "the reduction buffer aliases the partial sums");
+            static_assert(PROJ_WAVES == LSTM_WAVES, "the pre-sums split K over eight waves");
+            const int rx0 = (HID / 4) * (x - 1) / 7, rx1 = (HID / 4) * x / 7;
+            int k = i, Mc = 32, t0 = 0, nt = n_tiles;
+            if (n_tiles > 2) {
+                const int per = (n_tiles + 1) / 2;
+                Mc = 16;
+                if (k < 16) nt = per;
+                else { k -= 16; t0 = per; nt = n_tiles - per; }
+            }
+            const int lo = rx0 + (rx1 - rx0) * k / Mc, hi = rx0 + (rx1 - rx0) * (k + 1) / Mc;
+            gate_presums<XT>(d, cur ^ 1, lo, hi - lo, t0, nt, reinterpret_cast<PresumRed>(s_big));
+            return;
+        }
+        if (i >= n_tiles) return;
+    }
+    const int tile = PRE ? blockIdx.x >> 3 : blockIdx.x;
 
     const uint4* xnew = reinterpret_cast<const uint4*>(d.xdec[cur ^ 1]);   // h_dec of this step
     const uint4* xcur = reinterpret_cast<const uint4*>(d.xdec[cur]);       // a of this step
@@ -1040,6 +1274,18 @@ __global__ __launch_bounds__(256) void k_slot_init(DevPtrs d, int slot, int L, i
         d.c_dec[(size_t)slot * HID + i] = 0.f;
     }
     if (tid < N_MEL) d.m_last[(size_t)slot * N_MEL + tid] = 0.f;
+    // gate pre-sums of a zero state: this slot's column of every row tile (thread = row tile)
+    if (d.pre_att) {
+        static_assert(HID / 4 == 256, "one thread per row tile");
+        const floatx4 z4 = {0.f, 0.f, 0.f, 0.f};
+        floatx4* pa = reinterpret_cast<floatx4*>(d.pre_att) + ((size_t)(slot >> 4) * (HID / 4) + tid) * 64 + (slot & 15);
+        floatx4* pd = reinterpret_cast<floatx4*>(d.pre_dec) + ((size_t)(slot >> 4) * (HID / 4) + tid) * 64 + (slot & 15);
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            pa[16 * g] = z4;
+            pd[16 * g] = z4;
+        }
+    }
     if (tid == 0) {
         d.L[slot] = L;
         d.t[slot] = 0;
@@ -1081,7 +1327,7 @@ __global__ __launch_bounds__(256) void k_x_set(XT* X, int NK, int slot, int off,
 // ---------------------------------------------------------------------------
 // launch wrappers
 // ---------------------------------------------------------------------------
-template <typename XT, typename MT>
+template <typename XT, typename MT, bool PRE>
 static hipError_t step_typed(const DevPtrs& d, int n_req, int n_tiles, int lsa_split, int rows, int qpart, int cur, hipStream_t s, hipEvent_t* ev)
 {
     constexpr int KB = Frag<XT>::KB;
@@ -1090,6 +1336,8 @@ static hipError_t step_typed(const DevPtrs& d, int n_req, int n_tiles, int lsa_s
     XT* xatt_nxt = reinterpret_cast<XT*>(d.xatt[cur ^ 1]);
     XT* xdec_cur = reinterpret_cast<XT*>(d.xdec[cur]);
     XT* xdec_nxt = reinterpret_cast<XT*>(d.xdec[cur ^ 1]);
+    const floatx4* pre_att = reinterpret_cast<const floatx4*>(d.pre_att);
+    const floatx4* pre_dec = reinterpret_cast<const floatx4*>(d.pre_dec);
     mark(0);
     // H_att(t): consumed by this step's decoder LSTM / attention and by the next step's attention LSTM
     constexpr bool HAS_WIDE = sizeof(XT) == 2;     // the fp32 fragments of several row tiles do not fit the register file
@@ -1097,28 +1345,34 @@ static hipError_t step_typed(const DevPtrs& d, int n_req, int n_tiles, int lsa_s
     // partials from the two-row-tile kernel; the mode is fixed per pool, so is the kernel that goes with it
     if (!HAS_WIDE) { rows = 1; if (qpart == 2) qpart = 0; }
     if (qpart == 1) rows = 1;
+    if (PRE && rows > 2) return hipErrorInvalidValue;   // pools with pre-sums span at most four tiles
     const int att_rows = qpart == 2 ? 2 : rows;
     const dim3 lg(HID / 4), lb(LSTM_WAVES * 64);
-    if (qpart == 2) {
+    if (qpart == 3) {
+        if constexpr (PRE)
+            hipLaunchKernelGGL((k_lstm_att_tall<XT>), dim3(QP_TALL * n_tiles), lb, 0, s, d.Wa, d.ba, xatt_cur, d.c_att, xdec_cur, K_DEC / KB, XD_HA,
+                               xatt_nxt, K_ATT / KB, XA_H, d.live, d.done, d.Wq_epi, d.qpart, pre_att);
+        else return hipErrorInvalidValue;
+    } else if (qpart == 2) {
         if constexpr (HAS_WIDE)
-            hipLaunchKernelGGL((k_lstm_rc<XT, K_ATT, 2, false, true>), lg, lb, 0, s, d.Wa, d.ba, xatt_cur, d.c_att, xdec_cur, K_DEC / KB, XD_HA,
-                               xatt_nxt, K_ATT / KB, XA_H, n_tiles, d.live, d.done, d.Wq_epi, d.qpart);
+            hipLaunchKernelGGL((k_lstm_rc<XT, K_ATT, 2, false, true, PRE>), lg, lb, 0, s, d.Wa, d.ba, xatt_cur, d.c_att, xdec_cur, K_DEC / KB, XD_HA,
+                               xatt_nxt, K_ATT / KB, XA_H, n_tiles, d.live, d.done, d.Wq_epi, d.qpart, pre_att);
     } else if (att_rows == 4) {
-        if constexpr (HAS_WIDE)
+        if constexpr (HAS_WIDE && !PRE)
             hipLaunchKernelGGL((k_lstm_rc<XT, K_ATT, 4, true>), lg, lb, 0, s, d.Wa, d.ba, xatt_cur, d.c_att, xdec_cur, K_DEC / KB, XD_HA,
-                               xatt_nxt, K_ATT / KB, XA_H, n_tiles, d.live, d.done, nullptr, nullptr);
+                               xatt_nxt, K_ATT / KB, XA_H, n_tiles, d.live, d.done, nullptr, nullptr, nullptr);
     } else if (att_rows == 2) {
         if constexpr (HAS_WIDE)
-            hipLaunchKernelGGL((k_lstm_rc<XT, K_ATT, 2>), lg, lb, 0, s, d.Wa, d.ba, xatt_cur, d.c_att, xdec_cur, K_DEC / KB, XD_HA,
-                               xatt_nxt, K_ATT / KB, XA_H, n_tiles, d.live, d.done, nullptr, nullptr);
+            hipLaunchKernelGGL((k_lstm_rc<XT, K_ATT, 2, false, false, PRE>), lg, lb, 0, s, d.Wa, d.ba, xatt_cur, d.c_att, xdec_cur, K_DEC / KB, XD_HA,
+                               xatt_nxt, K_ATT / KB, XA_H, n_tiles, d.live, d.done, nullptr, nullptr, pre_att);
     } else if (qpart == 1)
-        hipLaunchKernelGGL((k_lstm<XT, K_ATT, true>), lg, lb, 0, s,
+        hipLaunchKernelGGL((k_lstm<XT, K_ATT, true, PRE>), lg, lb, 0, s,
                            d.Wa, d.ba, xatt_cur, d.c_att, xdec_cur, K_DEC / KB, XD_HA, xatt_nxt, K_ATT / KB, XA_H,
-                           n_tiles, d.live, d.done, d.Wq_epi, d.qpart);
+                           n_tiles, d.live, d.done, d.Wq_epi, d.qpart, pre_att);
     else
-        hipLaunchKernelGGL((k_lstm<XT, K_ATT, false>), lg, lb, 0, s,
+        hipLaunchKernelGGL((k_lstm<XT, K_ATT, false, PRE>), lg, lb, 0, s,
                            d.Wa, d.ba, xatt_cur, d.c_att, xdec_cur, K_DEC / KB, XD_HA, xatt_nxt, K_ATT / KB, XA_H,
-                           n_tiles, d.live, d.done, nullptr, nullptr);
+                           n_tiles, d.live, d.done, nullptr, nullptr, pre_att);
     mark(1);
     auto lsa = [&](auto qp) {
         constexpr int QPN = decltype(qp)::value;
@@ -1128,23 +1382,25 @@ static hipError_t step_typed(const DevPtrs& d, int n_req, int n_tiles, int lsa_s
     };
     if (qpart == 1) lsa(std::integral_constant<int, HID / 4>{});         // 256 rank-4 partials per slot
     else if (qpart == 2) lsa(std::integral_constant<int, HID / 8>{});    // 128 rank-8 partials
+    else if (qpart == 3) lsa(std::integral_constant<int, QP_TALL>{});    // 32 rank-32 partials
     else lsa(std::integral_constant<int, 0>{});
     mark(2);
     // H_dec(t): consumed by this step's projection and the next step's decoder LSTM (same buffer)
     const uint4* xdec_in = reinterpret_cast<const uint4*>(d.xdec[cur]);
     if (rows == 4) {
-        if constexpr (HAS_WIDE)
+        if constexpr (HAS_WIDE && !PRE)
             hipLaunchKernelGGL((k_lstm_rc<XT, K_DEC, 4>), lg, lb, 0, s, d.Wd, d.bd, xdec_in, d.c_dec, xdec_nxt, K_DEC / KB, XD_HD,
                                xdec_nxt, K_DEC / KB, XD_HD, n_tiles, d.live, d.done);
     } else if (rows == 2) {
         if constexpr (HAS_WIDE)
-            hipLaunchKernelGGL((k_lstm_rc<XT, K_DEC, 2>), lg, lb, 0, s, d.Wd, d.bd, xdec_in, d.c_dec, xdec_nxt, K_DEC / KB, XD_HD,
-                               xdec_nxt, K_DEC / KB, XD_HD, n_tiles, d.live, d.done);
+            hipLaunchKernelGGL((k_lstm_rc<XT, K_DEC, 2, false, false, PRE>), lg, lb, 0, s, d.Wd, d.bd, xdec_in, d.c_dec, xdec_nxt, K_DEC / KB, XD_HD,
+                               xdec_nxt, K_DEC / KB, XD_HD, n_tiles, d.live, d.done, nullptr, nullptr, pre_dec);
     } else
-        hipLaunchKernelGGL((k_lstm<XT, K_DEC, false>), lg, lb, 0, s, d.Wd, d.bd, xdec_in, d.c_dec, xdec_nxt, K_DEC / KB, XD_HD,
-                           xdec_nxt, K_DEC / KB, XD_HD, n_tiles, d.live, d.done, nullptr, nullptr);
+        hipLaunchKernelGGL((k_lstm<XT, K_DEC, false, PRE>), lg, lb, 0, s, d.Wd, d.bd, xdec_in, d.c_dec, xdec_nxt, K_DEC / KB, XD_HD,
+                           xdec_nxt, K_DEC / KB, XD_HD, n_tiles, d.live, d.done, nullptr, nullptr, pre_dec);
     mark(3);
-    hipLaunchKernelGGL((k_proj<XT>), dim3(n_tiles), dim3(PROJ_THREADS), 0, s, d, cur);
+    // with pre-sums the projection's launch fills the chip: its own workgroups first, the rest form the pre-sums
+    hipLaunchKernelGGL((k_proj<XT, PRE>), dim3(PRE ? 256 : n_tiles), dim3(PROJ_THREADS), 0, s, d, cur, n_tiles);
     mark(4);
     return hipGetLastError();
 }
@@ -1152,9 +1408,17 @@ static hipError_t step_typed(const DevPtrs& d, int n_req, int n_tiles, int lsa_s
 hipError_t launch_step(const DevPtrs& d, const StepLaunch& cfg, int cur, hipStream_t s, hipEvent_t* ev)
 {
     if (cfg.n_blocks < 1 || cfg.n_tiles < 1) return hipSuccess;
-    if (cfg.wdtype == 0 && cfg.mdtype == 0) return step_typed<float, float>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cfg.lstm_rows, cfg.q_partials, cur, s, ev);
-    if (cfg.wdtype == 1 && cfg.mdtype == 1) return step_typed<bf16_t, bf16_t>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cfg.lstm_rows, cfg.q_partials, cur, s, ev);
-    if (cfg.wdtype == 1 && cfg.mdtype == 0) return step_typed<bf16_t, float>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cfg.lstm_rows, cfg.q_partials, cur, s, ev);
+    if (cfg.pre_gates) {
+        // the pre-sum workgroups are laid out for at most four pool tiles, and the buffers must be there
+        if (cfg.n_tiles > PRESUM_MAX_TILES || !d.pre_att || !d.pre_dec) return hipErrorInvalidValue;
+        if (cfg.wdtype == 0 && cfg.mdtype == 0) return step_typed<float, float, true>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cfg.lstm_rows, cfg.q_partials, cur, s, ev);
+        if (cfg.wdtype == 1 && cfg.mdtype == 1) return step_typed<bf16_t, bf16_t, true>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cfg.lstm_rows, cfg.q_partials, cur, s, ev);
+        if (cfg.wdtype == 1 && cfg.mdtype == 0) return step_typed<bf16_t, float, true>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cfg.lstm_rows, cfg.q_partials, cur, s, ev);
+        return hipErrorInvalidValue;
+    }
+    if (cfg.wdtype == 0 && cfg.mdtype == 0) return step_typed<float, float, false>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cfg.lstm_rows, cfg.q_partials, cur, s, ev);
+    if (cfg.wdtype == 1 && cfg.mdtype == 1) return step_typed<bf16_t, bf16_t, false>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cfg.lstm_rows, cfg.q_partials, cur, s, ev);
+    if (cfg.wdtype == 1 && cfg.mdtype == 0) return step_typed<bf16_t, float, false>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cfg.lstm_rows, cfg.q_partials, cur, s, ev);
     return hipErrorInvalidValue;
 }
 
@@ -1175,6 +1439,14 @@ hipError_t launch_join_memory(const DevPtrs& d, int mdtype, const float* F_dev, 
 {
     if (mdtype == 0) hipLaunchKernelGGL((k_join_memory<float>), dim3(L), dim3(ATT), 0, s, d, F_dev, slot);
     else hipLaunchKernelGGL((k_join_memory<bf16_t>), dim3(L), dim3(ATT), 0, s, d, F_dev, slot);
+    return hipGetLastError();
+}
+
+hipError_t launch_presum_tile(const DevPtrs& d, int wdtype, int tile, int nxt, hipStream_t s)
+{
+    if (!d.pre_att || !d.pre_dec || tile < 0 || tile >= PRESUM_MAX_TILES) return hipErrorInvalidValue;
+    if (wdtype == 0) hipLaunchKernelGGL((k_presum_tile<float>), dim3(HID / 4), dim3(LSTM_WAVES * 64), 0, s, d, nxt, tile);
+    else hipLaunchKernelGGL((k_presum_tile<bf16_t>), dim3(HID / 4), dim3(LSTM_WAVES * 64), 0, s, d, nxt, tile);
     return hipGetLastError();
 }
 

@@ -65,7 +65,7 @@ static int check_config(const tts_config* c)
 namespace {
 
 struct Layout {
-    size_t Wa, Wd, ba, bd, Wq, Wq_epi, qpart, WmemT, lsa_kfrag, lsa_wfrag, v, Wmel, bmel, Wp1, Wp2;
+    size_t Wa, Wd, ba, bd, Wq, Wq_epi, qpart, pre_att, pre_dec, WmemT, lsa_kfrag, lsa_wfrag, v, Wmel, bmel, Wp1, Wp2;
     size_t xatt[2], xdec[2], c_att, c_dec, m_last, w_last[2], w_acc[2], Fmem, PM, mel_ring, stop_ring;
     size_t L, t, n_steps, done, live, stage;
     size_t total;
@@ -82,10 +82,16 @@ struct Layout {
 constexpr int QP8_MAX_POOL = 32;
 int q_partials_for(const tts_config& c)
 {
+    if ((c.max_pool + 15) / 16 <= PRESUM_MAX_TILES) return 3;
     if (c.max_pool <= 16) return 1;
     if (c.max_pool <= QP8_MAX_POOL && c.weight_dtype == TTS_DTYPE_BF16) return 2;
     return 0;
 }
+
+// Gate pre-sums: pools of at most PRESUM_MAX_TILES tiles leave all but a few CUs idle during the projection kernel,
+// whose launch then also contracts what the next step's two LSTMs already have of their inputs ([A; H_att] and H_dec).
+// Fixed per pool (it changes the order in which the gates are summed), like the query's path.
+bool pre_gates_for(const tts_config& c) { return (c.max_pool + 15) / 16 <= PRESUM_MAX_TILES; }
 
 Layout make_layout(const tts_config& c)
 {
@@ -113,6 +119,8 @@ Layout make_layout(const tts_config& c)
         l.xdec[b] = a.take(S * K_DEC * ws);
     }
     l.qpart = a.take((q_partials_for(c) ? S : 0) * (size_t)(HID / 4) * ATT * 4);
+    l.pre_att = a.take((pre_gates_for(c) ? S / 16 : 0) * (size_t)(HID / 4) * 64 * 16);
+    l.pre_dec = a.take((pre_gates_for(c) ? S / 16 : 0) * (size_t)(HID / 4) * 64 * 16);
     l.c_att = a.take(S * HID * 4);
     l.c_dec = a.take(S * HID * 4);
     l.m_last = a.take(S * N_MEL * 4);
@@ -314,6 +322,8 @@ extern "C" int tts_pool_create(const tts_config* cfg, const tts_weights* w, void
     d.Wq = base + l.Wq;
     d.Wq_epi = reinterpret_cast<const float*>(base + l.Wq_epi);
     d.qpart = reinterpret_cast<float*>(base + l.qpart);
+    d.pre_att = pre_gates_for(*cfg) ? reinterpret_cast<float*>(base + l.pre_att) : nullptr;
+    d.pre_dec = pre_gates_for(*cfg) ? reinterpret_cast<float*>(base + l.pre_dec) : nullptr;
     d.WmemT = (const float*)(base + l.WmemT);
     d.lsa_kfrag = base + l.lsa_kfrag;
     d.lsa_wfrag = base + l.lsa_wfrag;
@@ -455,6 +465,7 @@ static void shape_for(const tts_pool* p, int span, StepLaunch* sl)
     sl->lsa_split = lsa_split_for(span);
     sl->lstm_rows = lstm_rows_for(span);
     sl->q_partials = q_partials_for(p->cfg);
+    sl->pre_gates = pre_gates_for(p->cfg) ? 1 : 0;
 }
 
 // Queue `nsteps` consecutive steps for the current membership.  With graphs the
@@ -798,6 +809,9 @@ extern "C" int tts_pool_set_state(tts_pool* p, int64_t id, int which, const floa
             HIP_TRY(launch_x_set(p->cfg.weight_dtype, s.x[i], s.xK[i], slot, s.xoff[i], n, p->d.stage, p->stream));
     }
     if (which == TTS_STATE_M_LAST) HIP_TRY(launch_prenet_slot(p->d, p->cfg.weight_dtype, slot, p->stream));
+    // the next step's gate pre-sums were formed from the old state: redo the slot's tile from the half that step reads
+    if (pre_gates_for(p->cfg) && (which == TTS_STATE_A || which == TTS_STATE_H_ATT || which == TTS_STATE_H_DEC))
+        HIP_TRY(launch_presum_tile(p->d, p->cfg.weight_dtype, slot >> 4, p->parity, p->stream));
     HIP_TRY(hipStreamSynchronize(p->stream));
     return TTS_OK;
 }
