@@ -35,8 +35,9 @@ struct DevPtrs {
     const float* ba;      // [HID][4] gate-interleaved merged bias
     const float* bd;
     const void* Wq;       // [ATT][HID] WT, MFMA fragment order (8 row tiles): pools that compute q in the attention kernel
-    const float* Wq_epi;  // W_q as the A operands of the attention LSTM's rank-4 (or, two row tiles chained, rank-8) query products: [HID/4][8][64 lanes]
-    float* qpart;         // [slots][HID/4][ATT] partial sums of q = W_q h_att, written and read within one step
+    const float* Wq_epi;  // W_q as fp32 16x16x4 MFMA A operands, [HID/4][8][64 lanes]: entry (u, a, l) = W_q[16 a + l % 16][4 u + l / 16]
+                          // (the attention LSTM's query partials, pools with gate pre-sums)
+    float* qpart;         // [slots][32][ATT] rank-32 partial sums of q = W_q h_att, written and read within one step (null without pre-sums)
     float* pre_att;       // [tiles][HID/4 row tiles][64 lanes][4]: the attention LSTM's gate sums over [A; H_att], MFMA accumulator layout,
                           // written by the projection kernel's launch for the next step (null: the LSTM kernels contract all of K)
     float* pre_dec;       // same for the decoder LSTM's sums over H_dec

@@ -12,12 +12,14 @@ struct StepLaunch {
     int n_tiles;    // the projection grid covers 16-slot tiles 0 .. n_tiles - 1
     int lsa_split;  // workgroups per request in the attention kernel (1, 2 or 4; they split the context columns)
     int lstm_rows;  // row tiles per LSTM workgroup: 1 (all pool tiles each), 2 or 4 (1/2 or 1/4 of the pool tiles each)
-    int q_partials; // how the attention LSTM hands the query over: 0 = not at all, 1 = rank-4 partial products (pools of <= 16 slots), 2 = rank-8 (<= 32)
-    int pre_gates;  // 1: the projection's launch also forms the next step's gate pre-sums (d.pre_att / d.pre_dec; n_tiles <= PRESUM_MAX_TILES)
+    int pre_gates;  // 1: the projection's launch also forms the next step's gate pre-sums (d.pre_att / d.pre_dec; n_tiles <= PRESUM_MAX_TILES),
+                    // and the attention LSTM hands the query to the attention kernel as rank-32 partial products (d.qpart)
 };
 
 // pools of at most this many 16-slot tiles can run with gate pre-sums
 constexpr int PRESUM_MAX_TILES = 4;
+// such a pool's attention LSTM writes this many partial products of the attention query per slot (d.qpart)
+constexpr int QUERY_PARTIALS = 32;
 
 // One decoder step (paper Eq. 2) for every request whose slot is flagged in d.live.
 // `cur` selects which half of the double-buffered activations is read.

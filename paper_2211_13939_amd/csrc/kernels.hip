@@ -17,7 +17,6 @@
 #include "kernels.h"
 #include "mfma.h"
 
-#include <type_traits>
 
 namespace tts {
 
@@ -28,21 +27,10 @@ namespace tts {
 // The accumulator of lane l is (column l%16, gates i,f,g,o of unit l/16): the
 // cell update needs no data movement beyond the cross-wave reduction.
 //
-// With QP (the attention LSTM) the epilogue also starts the attention query
-// q = W_q h of the same step: the wave that has just produced four units of h
-// for 16 slots multiplies them by the matching four columns of W_q (one
-// 16x16x4 fp32 MFMA per 16 attention dims) and stores that rank-4 partial.
-// The attention kernel then adds up a request's 256 partials (128 KB) instead
-// of pulling all of W_q (256 KB in bf16, 512 KB in fp32) through its CU, which
-// bounds its prologue.  The partials cost this kernel 128 KB of stores per
-// request, so the scheme is used by pools of at most 16 slots only (where a
-// step is latency-bound); bf16 pools of up to 32 slots take the two-row-tile
-// kernel below with rank-8 partials (64 KB per request), and larger pools
-// compute q in the attention kernel.
-// qpart[slot][row tile or row group][a].
+// With PRE only the early part of K is contracted here and the rest arrives as
+// pre-sums (below).
 // ---------------------------------------------------------------------------
 constexpr int LSTM_WAVES = 8;
-constexpr int QP_STRIDE = HID / 4;   // partial rows per slot in qpart
 
 // Gate pre-sums (PRE).  Part of an LSTM's input is known long before the kernel runs: [A; H_att] of the attention
 // LSTM's input is complete once the attention kernel of the previous step has finished, H_dec of the decoder LSTM's
@@ -60,13 +48,12 @@ template <typename XT, int K> constexpr int lstm_main_frags()
 }
 static_assert(XA_P == 0 && XD_HA == 0 && XD_A == HID, "the early parts lead the activation rows");
 
-template <typename XT, int K, bool QP, bool PRE>
+template <typename XT, int K, bool PRE>
 __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm(
     const uint4* __restrict__ Wfrag, const float* __restrict__ bias, const uint4* __restrict__ X,
     float* __restrict__ c_state, XT* __restrict__ hout0, int nk0, int off0,
     XT* __restrict__ hout1, int nk1, int off1,
-    int n_tiles, const int* __restrict__ live, const int* __restrict__ done,
-    const float* __restrict__ wq_epi, float* __restrict__ qpart, const floatx4* __restrict__ pre)
+    int n_tiles, const int* __restrict__ live, const int* __restrict__ done, const floatx4* __restrict__ pre)
 {
     constexpr int NW = LSTM_WAVES;
     constexpr int NK = K / Frag<XT>::KB;      // fragments per row tile / per pool tile
@@ -88,12 +75,6 @@ __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm(
     const int unit = rt * 4 + (lane >> 4);
     floatx4 bias4 = {0.f, 0.f, 0.f, 0.f};
     if (wave < 4) bias4 = *reinterpret_cast<const floatx4*>(bias + unit * 4);
-    // W_q[16 at + lane%16][4 rt + lane/16]: the A operands of the query partial
-    float wq[QP ? 8 : 1];
-    if constexpr (QP) {
-#pragma unroll
-        for (int at = 0; at < 8; ++at) wq[at] = wq_epi[((size_t)rt * 8 + at) * 64 + lane];
-    }
 
     __shared__ floatx4 red[NW][4][64];
 
@@ -133,7 +114,6 @@ __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm(
         }
         __syncthreads();
         const int slotE = (wave < 4 && tg + wave < n_tiles && lv && !dn) ? sl : -1;
-        float hq = 0.f;
         if (slotE >= 0) {
             floatx4 g = bias4;
 #pragma unroll
@@ -146,18 +126,6 @@ __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm(
             const XT h = from_float<XT>(go * tanhf_(c));
             hout0[xoff<XT>(nk0, slotE, off0 + unit)] = h;
             hout1[xoff<XT>(nk1, slotE, off1 + unit)] = h;
-            hq = to_float(h);
-        }
-        if constexpr (QP) {
-            if (wave < 4 && tg + wave < n_tiles) {   // whole waves: the MFMA runs outside the per-lane branch
-#pragma unroll
-                for (int at = 0; at < 8; ++at) {
-                    const floatx4 z = {0.f, 0.f, 0.f, 0.f};
-                    const floatx4 part = __builtin_amdgcn_mfma_f32_16x16x4f32(wq[at], hq, z, 0, 0, 0);
-                    if (slotE >= 0)
-                        *reinterpret_cast<floatx4*>(qpart + ((size_t)slotE * QP_STRIDE + rt) * ATT + 16 * at + 4 * (lane >> 4)) = part;
-                }
-            }
         }
         __syncthreads();
     }
@@ -172,15 +140,13 @@ __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm(
 // repeated reads of the weights hit that XCD's L2.  The sums are taken in the same order as in k_lstm.
 // PIPE (R = 4, one pool tile per round): the activations of the next tile are requested before the
 // products of the current one, two tiles per trip through the loop so that both buffers stay in registers.
-template <typename XT, int K, int R, bool PIPE = false, bool QP = false, bool PRE = false>
+template <typename XT, int K, int R, bool PIPE = false, bool PRE = false>
 __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm_rc(
     const uint4* __restrict__ Wfrag, const float* __restrict__ bias, const uint4* __restrict__ X,
     float* __restrict__ c_state, XT* __restrict__ hout0, int nk0, int off0,
     XT* __restrict__ hout1, int nk1, int off1,
-    int n_tiles, const int* __restrict__ live, const int* __restrict__ done,
-    const float* __restrict__ wq_epi = nullptr, float* __restrict__ qpart = nullptr, const floatx4* __restrict__ pre = nullptr)
+    int n_tiles, const int* __restrict__ live, const int* __restrict__ done, const floatx4* __restrict__ pre = nullptr)
 {
-    static_assert(!QP || (R == 2 && !PIPE), "the query partials are built for the two-row-tile kernel");
     static_assert(!PRE || !PIPE, "pools large enough for the pipelined kernel leave no idle CUs for the pre-sums");
     constexpr int NW = LSTM_WAVES;
     constexpr int NK = K / Frag<XT>::KB;
@@ -206,18 +172,6 @@ __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm_rc(
     const int unit = (R * rg + er) * 4 + (lane >> 4);
     floatx4 bias4 = {0.f, 0.f, 0.f, 0.f};
     if (wave < 4) bias4 = *reinterpret_cast<const floatx4*>(bias + unit * 4);
-    // QP: the workgroup's eight units of h give a rank-8 partial of q = W_q h per slot (see k_lstm): the wave that
-    // owns row tile 0 of a pool tile takes the other row tile's four units from LDS and chains two MFMAs.
-    float wq[QP ? 2 : 1][QP ? 8 : 1];
-    __shared__ float s_hq[QP ? 2 : 1][4][64];
-    if constexpr (QP) {
-#pragma unroll
-        for (int r = 0; r < 2; ++r)
-#pragma unroll
-            for (int at = 0; at < 8; ++at) wq[r][at] = wq_epi[((size_t)(R * rg + r) * 8 + at) * 64 + lane];
-    }
-    int round_no = 0;
-
     if constexpr (PIPE) {
         static_assert(!PIPE || TP == 1, "the pipelined loop handles one pool tile per round");
         // one round: products of tile `tp` from `bc`, cell update of the four row tiles
@@ -302,7 +256,6 @@ __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm_rc(
         }
         __syncthreads();
         const int slotE = (wave < 4 && tp + et < c1 && lv && !dn) ? sl : -1;
-        float hq = 0.f;
         if (slotE >= 0) {
             floatx4 g = bias4;
 #pragma unroll
@@ -315,26 +268,8 @@ __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm_rc(
             const XT h = from_float<XT>(go * tanhf_(c));
             hout0[xoff<XT>(nk0, slotE, off0 + unit)] = h;
             hout1[xoff<XT>(nk1, slotE, off1 + unit)] = h;
-            hq = to_float(h);
-        }
-        if constexpr (QP) {
-            if (wave < 4) s_hq[round_no & 1][wave][lane] = hq;
         }
         __syncthreads();
-        if constexpr (QP) {
-            if ((wave == 0 || wave == 2) && tp + et < c1) {      // whole waves: the MFMAs run outside the per-lane branch
-                const float other = s_hq[round_no & 1][wave + 1][lane];
-#pragma unroll
-                for (int at = 0; at < 8; ++at) {
-                    const floatx4 z = {0.f, 0.f, 0.f, 0.f};
-                    floatx4 part = __builtin_amdgcn_mfma_f32_16x16x4f32(wq[0][at], hq, z, 0, 0, 0);
-                    part = __builtin_amdgcn_mfma_f32_16x16x4f32(wq[1][at], other, part, 0, 0, 0);
-                    if (slotE >= 0)
-                        *reinterpret_cast<floatx4*>(qpart + ((size_t)slotE * QP_STRIDE + rg) * ATT + 16 * at + 4 * (lane >> 4)) = part;
-                }
-            }
-            ++round_no;
-        }
     }
 }
 
@@ -349,6 +284,7 @@ __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm_rc(
 // ---------------------------------------------------------------------------
 constexpr int TALL_RT = 8;                      // row tiles per workgroup
 constexpr int QP_TALL = HID / 4 / TALL_RT;      // partials per slot
+static_assert(QP_TALL == QUERY_PARTIALS, "the arena holds QUERY_PARTIALS partials per slot");
 
 template <typename XT>
 __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm_att_tall(
@@ -411,7 +347,7 @@ __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm_att_tall(
     for (int s = 0; s < TALL_RT; ++s)
         part = __builtin_amdgcn_mfma_f32_16x16x4f32(wq[s], s_h[4 * s + (lane >> 4)][lane & 15], part, 0, 0, 0);
     if (active)
-        *reinterpret_cast<floatx4*>(qpart + ((size_t)sl * QP_STRIDE + rg) * ATT + 16 * wave + 4 * (lane >> 4)) = part;
+        *reinterpret_cast<floatx4*>(qpart + ((size_t)sl * QP_TALL + rg) * ATT + 16 * wave + 4 * (lane >> 4)) = part;
 }
 
 // ---------------------------------------------------------------------------
@@ -626,7 +562,7 @@ template <> struct LsaTile<bf16_t> {
     }
 };
 
-template <typename XT, typename MT, int S, int QP>
+template <typename XT, typename MT, int S, bool QP>
 __global__ __launch_bounds__(LSA_THREADS) void k_lsa(DevPtrs d, int cur)
 {
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
@@ -641,12 +577,12 @@ __global__ __launch_bounds__(LSA_THREADS) void k_lsa(DevPtrs d, int cur)
     const int slot = blockIdx.x / S, sp = blockIdx.x % S;
     const int live_w = d.live[slot], done_w = d.done[slot], L_w = d.L[slot];
     // q = W_q h_att, one of two ways.
-    // QP: it arrives as 256 rank-4 partial products written by this step's attention LSTM.  Thread
-    // (a = tid % 128, quarter = tid / 128) adds up its quarter's 32 pair sums P[2i] + P[2i+1] in
+    // QP (pools with gate pre-sums): it arrives as QP_TALL rank-32 partial products written by this step's attention
+    // LSTM.  Thread (a = tid % 128, quarter = tid / 128) adds up its quarter's pair sums P[2i] + P[2i+1] in
     // increasing i; then q[a] = (s0 + s1) + (s2 + s3).
     // Otherwise: on MFMA here, wave w contracting k in [128 w, 128 w + 128) for all 128 outputs
     // with 16 copies of h_att as the columns; the weights do not depend on the request.
-    constexpr int QN = QP ? QP / 4 : 1;           // partials per thread: QP partial products per slot, four quarters
+    constexpr int QN = QP ? QP_TALL / 4 : 1;      // partials per thread: QP_TALL partial products per slot, four quarters
     constexpr int NKQ = HID / Frag<XT>::KB;       // fragments per row tile of W_q
     constexpr int NKW = NKQ / LSA_WAVES;          // fragments per wave
     constexpr int MG = QP ? 1 : (sizeof(XT) == 2 ? 8 : 2);   // row tiles whose fragments are in flight together
@@ -654,7 +590,7 @@ __global__ __launch_bounds__(LSA_THREADS) void k_lsa(DevPtrs d, int cur)
     uint4 qa[MG][QP ? 1 : NKW];
     const uint4* Wq = reinterpret_cast<const uint4*>(d.Wq) + (size_t)(wave * NKW) * 64 + lane;
     if constexpr (QP) {
-        const float* qp = d.qpart + ((size_t)slot * QP_STRIDE + (tid >> 7) * QN) * ATT + (tid & (ATT - 1));
+        const float* qp = d.qpart + ((size_t)slot * QP_TALL + (tid >> 7) * QN) * ATT + (tid & (ATT - 1));
 #pragma unroll
         for (int i = 0; i < QN; ++i) qv[i] = qp[(size_t)i * ATT];
     } else {
@@ -1328,7 +1264,7 @@ __global__ __launch_bounds__(256) void k_x_set(XT* X, int NK, int slot, int off,
 // launch wrappers
 // ---------------------------------------------------------------------------
 template <typename XT, typename MT, bool PRE>
-static hipError_t step_typed(const DevPtrs& d, int n_req, int n_tiles, int lsa_split, int rows, int qpart, int cur, hipStream_t s, hipEvent_t* ev)
+static hipError_t step_typed(const DevPtrs& d, int n_req, int n_tiles, int lsa_split, int rows, int cur, hipStream_t s, hipEvent_t* ev)
 {
     constexpr int KB = Frag<XT>::KB;
     auto mark = [&](int i) { if (ev) (void)hipEventRecord(ev[i], s); };
@@ -1336,70 +1272,49 @@ static hipError_t step_typed(const DevPtrs& d, int n_req, int n_tiles, int lsa_s
     XT* xatt_nxt = reinterpret_cast<XT*>(d.xatt[cur ^ 1]);
     XT* xdec_cur = reinterpret_cast<XT*>(d.xdec[cur]);
     XT* xdec_nxt = reinterpret_cast<XT*>(d.xdec[cur ^ 1]);
-    const floatx4* pre_att = reinterpret_cast<const floatx4*>(d.pre_att);
-    const floatx4* pre_dec = reinterpret_cast<const floatx4*>(d.pre_dec);
     mark(0);
-    // H_att(t): consumed by this step's decoder LSTM / attention and by the next step's attention LSTM
     constexpr bool HAS_WIDE = sizeof(XT) == 2;     // the fp32 fragments of several row tiles do not fit the register file
-    // q as partial products: mode 1 = rank-4 partials from the one-row-tile kernel (small pools), mode 2 = rank-8
-    // partials from the two-row-tile kernel; the mode is fixed per pool, so is the kernel that goes with it
-    if (!HAS_WIDE) { rows = 1; if (qpart == 2) qpart = 0; }
-    if (qpart == 1) rows = 1;
+    if (!HAS_WIDE) rows = 1;
     if (PRE && rows > 2) return hipErrorInvalidValue;   // pools with pre-sums span at most four tiles
-    const int att_rows = qpart == 2 ? 2 : rows;
     const dim3 lg(HID / 4), lb(LSTM_WAVES * 64);
-    if (qpart == 3) {
-        if constexpr (PRE)
-            hipLaunchKernelGGL((k_lstm_att_tall<XT>), dim3(QP_TALL * n_tiles), lb, 0, s, d.Wa, d.ba, xatt_cur, d.c_att, xdec_cur, K_DEC / KB, XD_HA,
-                               xatt_nxt, K_ATT / KB, XA_H, d.live, d.done, d.Wq_epi, d.qpart, pre_att);
-        else return hipErrorInvalidValue;
-    } else if (qpart == 2) {
+    // H_att(t): consumed by this step's decoder LSTM / attention and by the next step's attention LSTM.
+    // With pre-sums: the tall kernel, which also hands the query over as partial products.
+    if constexpr (PRE) {
+        hipLaunchKernelGGL((k_lstm_att_tall<XT>), dim3(QP_TALL * n_tiles), lb, 0, s, d.Wa, d.ba, xatt_cur, d.c_att, xdec_cur, K_DEC / KB, XD_HA,
+                           xatt_nxt, K_ATT / KB, XA_H, d.live, d.done, d.Wq_epi, d.qpart, reinterpret_cast<const floatx4*>(d.pre_att));
+    } else if (rows == 4) {
         if constexpr (HAS_WIDE)
-            hipLaunchKernelGGL((k_lstm_rc<XT, K_ATT, 2, false, true, PRE>), lg, lb, 0, s, d.Wa, d.ba, xatt_cur, d.c_att, xdec_cur, K_DEC / KB, XD_HA,
-                               xatt_nxt, K_ATT / KB, XA_H, n_tiles, d.live, d.done, d.Wq_epi, d.qpart, pre_att);
-    } else if (att_rows == 4) {
-        if constexpr (HAS_WIDE && !PRE)
             hipLaunchKernelGGL((k_lstm_rc<XT, K_ATT, 4, true>), lg, lb, 0, s, d.Wa, d.ba, xatt_cur, d.c_att, xdec_cur, K_DEC / KB, XD_HA,
-                               xatt_nxt, K_ATT / KB, XA_H, n_tiles, d.live, d.done, nullptr, nullptr, nullptr);
-    } else if (att_rows == 2) {
+                               xatt_nxt, K_ATT / KB, XA_H, n_tiles, d.live, d.done, nullptr);
+    } else if (rows == 2) {
         if constexpr (HAS_WIDE)
-            hipLaunchKernelGGL((k_lstm_rc<XT, K_ATT, 2, false, false, PRE>), lg, lb, 0, s, d.Wa, d.ba, xatt_cur, d.c_att, xdec_cur, K_DEC / KB, XD_HA,
-                               xatt_nxt, K_ATT / KB, XA_H, n_tiles, d.live, d.done, nullptr, nullptr, pre_att);
-    } else if (qpart == 1)
-        hipLaunchKernelGGL((k_lstm<XT, K_ATT, true, PRE>), lg, lb, 0, s,
+            hipLaunchKernelGGL((k_lstm_rc<XT, K_ATT, 2>), lg, lb, 0, s, d.Wa, d.ba, xatt_cur, d.c_att, xdec_cur, K_DEC / KB, XD_HA,
+                               xatt_nxt, K_ATT / KB, XA_H, n_tiles, d.live, d.done, nullptr);
+    } else
+        hipLaunchKernelGGL((k_lstm<XT, K_ATT, false>), lg, lb, 0, s,
                            d.Wa, d.ba, xatt_cur, d.c_att, xdec_cur, K_DEC / KB, XD_HA, xatt_nxt, K_ATT / KB, XA_H,
-                           n_tiles, d.live, d.done, d.Wq_epi, d.qpart, pre_att);
-    else
-        hipLaunchKernelGGL((k_lstm<XT, K_ATT, false, PRE>), lg, lb, 0, s,
-                           d.Wa, d.ba, xatt_cur, d.c_att, xdec_cur, K_DEC / KB, XD_HA, xatt_nxt, K_ATT / KB, XA_H,
-                           n_tiles, d.live, d.done, nullptr, nullptr, pre_att);
+                           n_tiles, d.live, d.done, nullptr);
     mark(1);
-    auto lsa = [&](auto qp) {
-        constexpr int QPN = decltype(qp)::value;
-        if (lsa_split == 4) hipLaunchKernelGGL((k_lsa<XT, MT, 4, QPN>), dim3(n_req * 4), dim3(LSA_THREADS), 0, s, d, cur);
-        else if (lsa_split == 2) hipLaunchKernelGGL((k_lsa<XT, MT, 2, QPN>), dim3(n_req * 2), dim3(LSA_THREADS), 0, s, d, cur);
-        else hipLaunchKernelGGL((k_lsa<XT, MT, 1, QPN>), dim3(n_req), dim3(LSA_THREADS), 0, s, d, cur);
-    };
-    if (qpart == 1) lsa(std::integral_constant<int, HID / 4>{});         // 256 rank-4 partials per slot
-    else if (qpart == 2) lsa(std::integral_constant<int, HID / 8>{});    // 128 rank-8 partials
-    else if (qpart == 3) lsa(std::integral_constant<int, QP_TALL>{});    // 32 rank-32 partials
-    else lsa(std::integral_constant<int, 0>{});
+    if (lsa_split == 4) hipLaunchKernelGGL((k_lsa<XT, MT, 4, PRE>), dim3(n_req * 4), dim3(LSA_THREADS), 0, s, d, cur);
+    else if (lsa_split == 2) hipLaunchKernelGGL((k_lsa<XT, MT, 2, PRE>), dim3(n_req * 2), dim3(LSA_THREADS), 0, s, d, cur);
+    else hipLaunchKernelGGL((k_lsa<XT, MT, 1, PRE>), dim3(n_req), dim3(LSA_THREADS), 0, s, d, cur);
     mark(2);
     // H_dec(t): consumed by this step's projection and the next step's decoder LSTM (same buffer)
     const uint4* xdec_in = reinterpret_cast<const uint4*>(d.xdec[cur]);
+    const floatx4* pre_dec = reinterpret_cast<const floatx4*>(d.pre_dec);
     if (rows == 4) {
         if constexpr (HAS_WIDE && !PRE)
             hipLaunchKernelGGL((k_lstm_rc<XT, K_DEC, 4>), lg, lb, 0, s, d.Wd, d.bd, xdec_in, d.c_dec, xdec_nxt, K_DEC / KB, XD_HD,
-                               xdec_nxt, K_DEC / KB, XD_HD, n_tiles, d.live, d.done);
+                               xdec_nxt, K_DEC / KB, XD_HD, n_tiles, d.live, d.done, nullptr);
     } else if (rows == 2) {
         if constexpr (HAS_WIDE)
-            hipLaunchKernelGGL((k_lstm_rc<XT, K_DEC, 2, false, false, PRE>), lg, lb, 0, s, d.Wd, d.bd, xdec_in, d.c_dec, xdec_nxt, K_DEC / KB, XD_HD,
-                               xdec_nxt, K_DEC / KB, XD_HD, n_tiles, d.live, d.done, nullptr, nullptr, pre_dec);
+            hipLaunchKernelGGL((k_lstm_rc<XT, K_DEC, 2, false, PRE>), lg, lb, 0, s, d.Wd, d.bd, xdec_in, d.c_dec, xdec_nxt, K_DEC / KB, XD_HD,
+                               xdec_nxt, K_DEC / KB, XD_HD, n_tiles, d.live, d.done, pre_dec);
     } else
-        hipLaunchKernelGGL((k_lstm<XT, K_DEC, false, PRE>), lg, lb, 0, s, d.Wd, d.bd, xdec_in, d.c_dec, xdec_nxt, K_DEC / KB, XD_HD,
-                           xdec_nxt, K_DEC / KB, XD_HD, n_tiles, d.live, d.done, nullptr, nullptr, pre_dec);
+        hipLaunchKernelGGL((k_lstm<XT, K_DEC, PRE>), lg, lb, 0, s, d.Wd, d.bd, xdec_in, d.c_dec, xdec_nxt, K_DEC / KB, XD_HD,
+                           xdec_nxt, K_DEC / KB, XD_HD, n_tiles, d.live, d.done, pre_dec);
     mark(3);
-    // with pre-sums the projection's launch fills the chip: its own workgroups first, the rest form the pre-sums
+    // with pre-sums the projection's launch fills the chip: XCD 0 runs the projection, the rest form the pre-sums
     hipLaunchKernelGGL((k_proj<XT, PRE>), dim3(PRE ? 256 : n_tiles), dim3(PROJ_THREADS), 0, s, d, cur, n_tiles);
     mark(4);
     return hipGetLastError();
@@ -1410,15 +1325,15 @@ hipError_t launch_step(const DevPtrs& d, const StepLaunch& cfg, int cur, hipStre
     if (cfg.n_blocks < 1 || cfg.n_tiles < 1) return hipSuccess;
     if (cfg.pre_gates) {
         // the pre-sum workgroups are laid out for at most four pool tiles, and the buffers must be there
-        if (cfg.n_tiles > PRESUM_MAX_TILES || !d.pre_att || !d.pre_dec) return hipErrorInvalidValue;
-        if (cfg.wdtype == 0 && cfg.mdtype == 0) return step_typed<float, float, true>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cfg.lstm_rows, cfg.q_partials, cur, s, ev);
-        if (cfg.wdtype == 1 && cfg.mdtype == 1) return step_typed<bf16_t, bf16_t, true>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cfg.lstm_rows, cfg.q_partials, cur, s, ev);
-        if (cfg.wdtype == 1 && cfg.mdtype == 0) return step_typed<bf16_t, float, true>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cfg.lstm_rows, cfg.q_partials, cur, s, ev);
+        if (cfg.n_tiles > PRESUM_MAX_TILES || !d.pre_att || !d.pre_dec || !d.qpart) return hipErrorInvalidValue;
+        if (cfg.wdtype == 0 && cfg.mdtype == 0) return step_typed<float, float, true>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cfg.lstm_rows, cur, s, ev);
+        if (cfg.wdtype == 1 && cfg.mdtype == 1) return step_typed<bf16_t, bf16_t, true>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cfg.lstm_rows, cur, s, ev);
+        if (cfg.wdtype == 1 && cfg.mdtype == 0) return step_typed<bf16_t, float, true>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cfg.lstm_rows, cur, s, ev);
         return hipErrorInvalidValue;
     }
-    if (cfg.wdtype == 0 && cfg.mdtype == 0) return step_typed<float, float, false>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cfg.lstm_rows, cfg.q_partials, cur, s, ev);
-    if (cfg.wdtype == 1 && cfg.mdtype == 1) return step_typed<bf16_t, bf16_t, false>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cfg.lstm_rows, cfg.q_partials, cur, s, ev);
-    if (cfg.wdtype == 1 && cfg.mdtype == 0) return step_typed<bf16_t, float, false>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cfg.lstm_rows, cfg.q_partials, cur, s, ev);
+    if (cfg.wdtype == 0 && cfg.mdtype == 0) return step_typed<float, float, false>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cfg.lstm_rows, cur, s, ev);
+    if (cfg.wdtype == 1 && cfg.mdtype == 1) return step_typed<bf16_t, bf16_t, false>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cfg.lstm_rows, cur, s, ev);
+    if (cfg.wdtype == 1 && cfg.mdtype == 0) return step_typed<bf16_t, float, false>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cfg.lstm_rows, cur, s, ev);
     return hipErrorInvalidValue;
 }
 

@@ -71,26 +71,12 @@ struct Layout {
     size_t total;
 };
 
-// Pools of at most 16 slots (one tile) pass the attention query from the attention LSTM to the attention
-// kernel as partial products (cheaper when a step is latency-bound, 128 KB of stores per request
-// otherwise).  Fixed per pool, so that a request's frames never depend on who else is in the pool.
-// how the attention query reaches the attention kernel: 0 = computed there from W_q; 1 = rank-4 partial products from
-// the attention LSTM (pools of at most 16 slots); 2 = rank-8 partials from its two-row-tile kernel (bf16 pools of up
-// to QP8_MAX_POOL slots: measured 1.5 us per step faster at 32 slots, 0.8 us slower at 64, where the attention
-// LSTM pays more for the partials than the attention kernel saves).  Fixed per pool: a request's bits do not
-// depend on what else the pool holds.
-constexpr int QP8_MAX_POOL = 32;
-int q_partials_for(const tts_config& c)
-{
-    if ((c.max_pool + 15) / 16 <= PRESUM_MAX_TILES) return 3;
-    if (c.max_pool <= 16) return 1;
-    if (c.max_pool <= QP8_MAX_POOL && c.weight_dtype == TTS_DTYPE_BF16) return 2;
-    return 0;
-}
-
 // Gate pre-sums: pools of at most PRESUM_MAX_TILES tiles leave all but a few CUs idle during the projection kernel,
 // whose launch then also contracts what the next step's two LSTMs already have of their inputs ([A; H_att] and H_dec).
-// Fixed per pool (it changes the order in which the gates are summed), like the query's path.
+// The attention LSTM, left with K = 256, then runs as tall tiles and hands the attention query over as 32 rank-32
+// partial products per slot (16 KB) instead of the attention kernel pulling W_q (256 KB in bf16) through each of its
+// CUs.  Fixed per pool (it changes the order in which gates and query are summed): a request's bits do not depend on
+// what else the pool holds.
 bool pre_gates_for(const tts_config& c) { return (c.max_pool + 15) / 16 <= PRESUM_MAX_TILES; }
 
 Layout make_layout(const tts_config& c)
@@ -118,7 +104,7 @@ Layout make_layout(const tts_config& c)
         l.xatt[b] = a.take(S * K_ATT * ws);
         l.xdec[b] = a.take(S * K_DEC * ws);
     }
-    l.qpart = a.take((q_partials_for(c) ? S : 0) * (size_t)(HID / 4) * ATT * 4);
+    l.qpart = a.take((pre_gates_for(c) ? S : 0) * (size_t)QUERY_PARTIALS * ATT * 4);
     l.pre_att = a.take((pre_gates_for(c) ? S / 16 : 0) * (size_t)(HID / 4) * 64 * 16);
     l.pre_dec = a.take((pre_gates_for(c) ? S / 16 : 0) * (size_t)(HID / 4) * 64 * 16);
     l.c_att = a.take(S * HID * 4);
@@ -321,7 +307,7 @@ extern "C" int tts_pool_create(const tts_config* cfg, const tts_weights* w, void
     d.bd = (const float*)(base + l.bd);
     d.Wq = base + l.Wq;
     d.Wq_epi = reinterpret_cast<const float*>(base + l.Wq_epi);
-    d.qpart = reinterpret_cast<float*>(base + l.qpart);
+    d.qpart = pre_gates_for(*cfg) ? reinterpret_cast<float*>(base + l.qpart) : nullptr;
     d.pre_att = pre_gates_for(*cfg) ? reinterpret_cast<float*>(base + l.pre_att) : nullptr;
     d.pre_dec = pre_gates_for(*cfg) ? reinterpret_cast<float*>(base + l.pre_dec) : nullptr;
     d.WmemT = (const float*)(base + l.WmemT);
@@ -464,7 +450,6 @@ static void shape_for(const tts_pool* p, int span, StepLaunch* sl)
     sl->n_tiles = (span + 15) / 16;
     sl->lsa_split = lsa_split_for(span);
     sl->lstm_rows = lstm_rows_for(span);
-    sl->q_partials = q_partials_for(p->cfg);
     sl->pre_gates = pre_gates_for(p->cfg) ? 1 : 0;
 }
 

@@ -281,32 +281,64 @@ def test_c4_full_pool_bf16(weights_bf16):
 
 
 def test_small_and_large_capacity_pools_agree(wl8, weights_fp32, solo_frames):
-    """Pools of at most 16 slots hand the attention query over as partial products
-    from the attention LSTM, larger ones compute it in the attention kernel: the
-    same numbers up to summation order."""
-    say("case capacity: max_pool 8 vs 40, fp32")
-    big = gpu_decode(wl8, weights_fp32, list(range(8)), 24, max_pool=40)
+    """Pools of at most 64 slots form part of the next step's gates beside the projection and
+    hand the attention query over as partial products, larger ones contract all of K in the
+    LSTM kernels and compute the query in the attention kernel: the same numbers up to
+    summation order."""
+    say("case capacity: max_pool 8 vs 80, fp32")
+    big = gpu_decode(wl8, weights_fp32, list(range(8)), 24, max_pool=80)
     for i in range(8):
         n = solo_frames[i].shape[0]
         assert np.abs(big[i, :n] - solo_frames[i]).max() <= 1e-5
 
 
-def test_mid_capacity_bf16_pool_rank8_query_partials(weights_bf16):
-    """bf16 pools of 17 .. 32 slots take the two-row-tile attention LSTM that hands the query over as rank-8
-    partial products: 24 requests against the oracle, and a request's bits do not depend on the pool's
-    composition (alone in slot 0 vs among 24, vs among 5 joining in another order)."""
-    wl = synth.small_workload(24, 10, 120, 30, 30, seed=71, bf16=True)
-    say("case capacity 32, bf16: 24 requests, 30 steps")
-    full = gpu_decode(wl, weights_bf16, list(range(24)), 30, max_pool=32)
-    sample = [0, 7, 16, 23]
-    ref, _, _ = oracle_decode(wl, weights_bf16, sample, 30, n_threads=4)
+@pytest.mark.parametrize("bf16,max_pool,n_req", [(True, 32, 24), (True, 48, 40), (False, 48, 36), (False, 64, 52)])
+def test_pools_of_several_tiles_with_gate_presums(bf16, max_pool, n_req, weights_bf16, weights_fp32):
+    """Pools of two to four tiles: the pre-sum workgroups split by pool tiles (one group up to two
+    tiles, two groups of 2 + 1 or 2 + 2 tiles above) and take one to three row tiles each.  Against the
+    oracle on a sample, and a request's bits do not depend on the pool's composition (alone in slot 0
+    vs among all, vs among 5 joining in another order)."""
+    weights = weights_bf16 if bf16 else weights_fp32
+    wl = synth.small_workload(n_req, 10, 120, 30, 30, seed=71, bf16=bf16)
+    say(f"case capacity {max_pool}, {'bf16' if bf16 else 'fp32'}: {n_req} requests, 30 steps")
+    full = gpu_decode(wl, weights, list(range(n_req)), 30, max_pool=max_pool)
+    sample = [0, 7, 16, n_req - 1]
+    ref, _, _ = oracle_decode(wl, weights, sample, 30, n_threads=4)
     for k, i in enumerate(sample):
-        assert np.abs(full[i] - ref[k]).max() <= TOL_BF16
-    alone = gpu_decode(wl, weights_bf16, [7], 30, max_pool=32)[0]
+        assert np.abs(full[i] - ref[k]).max() <= (TOL_BF16 if bf16 else TOL_F32)
+    alone = gpu_decode(wl, weights, [7], 30, max_pool=max_pool)[0]
     np.testing.assert_array_equal(alone, full[7])
-    few = gpu_decode(wl, weights_bf16, [20, 3, 7, 11, 0], 30, max_pool=32)
+    few = gpu_decode(wl, weights, [20, 3, 7, 11, 0], 30, max_pool=max_pool)
     np.testing.assert_array_equal(few[2], full[7])
     np.testing.assert_array_equal(few[4], full[0])
+
+
+def test_state_overwrite_refreshes_the_gate_presums(wl8, weights_fp32):
+    """A request's H_att, A and H_dec are overwritten between steps with another request's: the
+    pre-sums formed from the old state during the last projection must not reach the next step.
+    Two pools run the same request; in the second its recurrent state is first replaced by
+    garbage, then by the first pool's: the following frames are identical."""
+    say("case: set_state between steps in a pool with gate pre-sums")
+    pools, rids = [], []
+    for k in range(2):
+        pool = make_pool(wl8, weights_fp32, max_pool=20, max_enc_len=int(wl8.enc_len.max()), max_steps=24, chunk_frames=24)
+        # the neighbour in the same tile keeps its own state (its pre-sums are formed again with the tile's)
+        ids = [pool.add_request(wl8.encoder_outputs(i), 24) for i in (2, 5)]
+        pool.step_n(7)
+        pools.append(pool)
+        rids.append(ids)
+    a, b = pools
+    rng = np.random.default_rng(5)
+    for name in ("h_att", "a", "h_dec"):
+        good = a.get_state(rids[0][0], name)
+        b.set_state(rids[1][0], name, rng.standard_normal(good.shape).astype(np.float32))
+        b.set_state(rids[1][0], name, good)
+    for pool in pools:
+        pool.step_n(17)
+    for k in range(2):
+        np.testing.assert_array_equal(_drain(a, rids[0][k]), _drain(b, rids[1][k]))
+    for pool in pools:
+        pool.close()
 
 
 def test_c3_shrinking_pool_full_job(weights_bf16):
