@@ -29,23 +29,36 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 
 
-def algorithmic_bytes(P, sum_L, s_w, s_m):
+PRESUM_MAX_POOL = 64   # pools of up to four 16-slot tiles run with gate pre-sums (tts_pool.cpp: pre_gates_for)
+
+
+def algorithmic_bytes(P, sum_L, s_w, s_m, pre_gates=None):
     """Bytes one step must move, per kernel, for P requests with sum_L encoder
     positions: every step weight once, each request's processed memory and
-    encoder output once, carried state read and written, mel written."""
-    gates_att = 4096 * 1792 * s_w + 4096 * 4
-    gates_dec = 4096 * 2560 * s_w + 4096 * 4
-    lsa_w = 128 * 1024 * s_w + (32 * 2 * 31 + 128 * 32 + 128) * 4
-    proj_w = (81 * 1536 + 80 * 256 + 256 * 256) * s_w + 81 * 4
+    encoder output once, carried state read and written, mel written.  The sum
+    does not depend on `pre_gates`; the split does: pools with gate pre-sums
+    move the gate matrices' columns for [A; H_att] (attention LSTM) and H_dec
+    (decoder LSTM) in the projection kernel's launch, and W_q in the attention
+    LSTM's.  (The pre-sums and query partials themselves, written by one kernel
+    and read by the next, are traffic of the implementation, not of the
+    algorithm, and are not counted.)"""
+    if pre_gates is None:
+        pre_gates = P <= PRESUM_MAX_POOL
     st = 4  # carried state counted in fp32: read + write
+    k_att_late, k_dec_late = (512 + 1024, 1024) if pre_gates else (0, 0)
+    w_q = 128 * 1024 * s_w
+    lsa_w = (32 * 2 * 31 + 128 * 32 + 128) * 4
+    proj_w = (81 * 1536 + 80 * 256 + 256 * 256) * s_w + 81 * 4
     return {
         # x = [p; a; h_att] read, c_att read+write, h_att written
-        "k_lstm_att": gates_att + P * (1792 * st + 2 * 1024 * st + 1024 * st),
+        "k_lstm_att": 4096 * (1792 - k_att_late) * s_w + 4096 * 4 + (w_q if pre_gates else 0)
+                      + P * ((1792 - k_att_late) * st + 2 * 1024 * st + 1024 * st),
         # h_att read, PM + F_enc streamed, W_last/W_acc read+write, a written
-        "k_lsa": lsa_w + sum_L * ((128 + 512) * s_m + 16) + P * (1024 * st + 512 * st),
-        "k_lstm_dec": gates_dec + P * (2560 * st + 2 * 1024 * st + 1024 * st),
+        "k_lsa": lsa_w + (0 if pre_gates else w_q) + sum_L * ((128 + 512) * s_m + 16) + P * (1024 * st + 512 * st),
+        "k_lstm_dec": 4096 * (2560 - k_dec_late) * s_w + 4096 * 4 + P * ((2560 - k_dec_late) * st + 2 * 1024 * st + 1024 * st),
         # [h_dec; a] read, mel ring + m_last + stop written, p written
-        "k_proj": proj_w + P * (1536 * st + 80 * 4 * 2 + 4 + 256 * st),
+        "k_proj": proj_w + P * (1536 * st + 80 * 4 * 2 + 4 + 256 * st)
+                  + 4096 * (k_att_late + k_dec_late) * s_w + P * (k_att_late + k_dec_late) * st,
     }
 
 

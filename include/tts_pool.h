@@ -140,6 +140,7 @@ int tts_pool_step_n(tts_pool *pool, int n, int64_t *out_frames);
  * frames exist and the request is unfinished, *out_frames = 0 and TTS_OK.  The
  * last chunk of a finished request may be short.  *out_finished = 1 once the
  * request is finished AND everything has been drained.  Waits for the stream.
+ * TTS_E_HIP if a step's kernels could not finish their work (see tts_pool_sync).
  */
 int tts_pool_drain_chunk(tts_pool *pool, int64_t id, float *dst, int *out_frames, int *out_finished);
 
@@ -177,7 +178,11 @@ int tts_pool_frames(tts_pool *pool, int64_t id, int *out_frames, int *out_finish
 int tts_pool_size(const tts_pool *pool);
 int tts_pool_n_active(const tts_pool *pool);
 
-/* Wait until everything queued on the pool's stream has run. */
+/* Wait until everything queued on the pool's stream has run.
+ * In pools of at most 64 slots the projection of a step is shared by several workgroups that wait for each
+ * other's partial sums a bounded number of polls; should such a wait ever run out (the GPU so oversubscribed by
+ * other work that a partner is not scheduled for a quarter of a second), the kernels still finish, the frames
+ * produced since are invalid, and this call and tts_pool_drain_chunk return TTS_E_HIP from then on. */
 int tts_pool_sync(tts_pool *pool);
 
 /* Device time of the kernels of the most recent tts_pool_step / step_n call,

@@ -41,6 +41,10 @@ struct DevPtrs {
     float* pre_att;       // [tiles][HID/4 row tiles][64 lanes][4]: the attention LSTM's gate sums over [A; H_att], MFMA accumulator layout,
                           // written by the projection kernel's launch for the next step (null: the LSTM kernels contract all of K)
     float* pre_dec;       // same for the decoder LSTM's sums over H_dec
+    unsigned long long* proj_part; // [tiles][5][96 * 16] (sequence number << 32 | float bits): partial sums of the projection's helper
+                          // workgroups (pools with pre-sums), written and read within one kernel
+    unsigned* proj_seq;   // [tiles][6]: steps each of a tile's projection workgroups has taken part in (zero at creation)
+    int* fault;           // pinned host memory: set by a projection leader whose wait for its helpers ran out
     const void* lsa_kfrag; // location filters as per-lane MFMA A operands (layout depends on WT)
     const void* lsa_wfrag; // W_loc as per-lane MFMA A operands (layout depends on WT)
     const float* WmemT;   // [ENC][ATT] fp32 (join time only)

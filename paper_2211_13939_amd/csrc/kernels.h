@@ -20,6 +20,9 @@ struct StepLaunch {
 constexpr int PRESUM_MAX_TILES = 4;
 // such a pool's attention LSTM writes this many partial products of the attention query per slot (d.qpart)
 constexpr int QUERY_PARTIALS = 32;
+// and its projection runs as this many workgroups per tile: d.proj_seq holds one sequence number for each, d.proj_part
+// the 96 x 16 partial sums of all but the first
+constexpr int PROJ_GROUP = 6;
 
 // One decoder step (paper Eq. 2) for every request whose slot is flagged in d.live.
 // `cur` selects which half of the double-buffered activations is read.

@@ -911,16 +911,25 @@ __global__ __launch_bounds__(LSA_THREADS) void k_lsa(DevPtrs d, int cur)
 
 // ---------------------------------------------------------------------------
 // Mel + stop projection of [H_dec; A] (Eq. 2 line 5), ring write, frame counter
-// and the prenet of the new frame (the Pre(M_last) of the next step), one
-// workgroup per pool tile (16 slots).  Three chained MFMA products with the
-// slots as the 16 columns:
+// and the prenet of the new frame (the Pre(M_last) of the next step), per pool
+// tile (16 slots).  Three chained MFMA products with the slots as the 16 columns:
 //   mel^T (96 x 16)  = W_proj (81 rows padded to 96, K = 1536, split over the waves) * Y^T
 //   hid^T (256 x 16) = relu(W_p1 (K = 80, zero padded) * mel^T)
 //   p^T   (256 x 16) = relu(W_p2 * hid^T)
+// What bounds it is the weights that pass through one CU (475 KB in bf16 at 60 - 85 GB/s).  Pools without gate
+// pre-sums run one workgroup per tile.  With pre-sums the launch fills the chip anyway and XCD 0 is reserved for the
+// projection, so a tile gets PROJ_G workgroups there that split the K of the first product: the helpers store their
+// 96 x 16 partial sums and raise a sequence number each, the leader (which meanwhile pulls the prenet weights) waits
+// for those numbers, adds the partials in helper order and goes on alone.  The wait is bounded: a leader that gives
+// up raises d.fault and finishes with whatever it has, so the grid always drains.
 // ---------------------------------------------------------------------------
 constexpr int PROJ_THREADS = 512;
 constexpr int PROJ_WAVES = PROJ_THREADS / 64;
 constexpr int PROJ_ROWS = 96;
+constexpr int PROJ_G = 6;                        // workgroups per pool tile in pools with gate pre-sums
+constexpr int PROJ_SPIN = 1 << 18;               // polls of the helpers' sequence numbers before a leader gives up
+constexpr int PROJ_MEL_LD = PROJ_ROWS + 4, PROJ_HID_LD = PRENET + 4;
+static_assert(PROJ_G == PROJ_GROUP, "the arena holds PROJ_GROUP sequence numbers and PROJ_GROUP - 1 partial sums per tile");
 
 template <typename XT> struct PrenetK1 { static constexpr int value = 80; };
 template <> struct PrenetK1<bf16_t> { static constexpr int value = 96; };
@@ -936,8 +945,16 @@ template <> __device__ __forceinline__ uint4 frag_from_f32<bf16_t>(const float* 
     return make_uint4(pack_bf16x2(p[0], p[1]), pack_bf16x2(p[2], p[3]), pack_bf16x2(p[4], p[5]), pack_bf16x2(p[6], p[7]));
 }
 
-template <typename XT, bool PRE>
-__global__ __launch_bounds__(PROJ_THREADS) void k_proj(DevPtrs d, int cur, int n_tiles)
+struct ProjShared {
+    float* big;                          // PROJ_WAVES * PROJ_ROWS * 16 floats: partial sums, later hid
+    float (*mel)[PROJ_MEL_LD];           // [16][PROJ_MEL_LD]
+    int *slot, *t, *cap;                 // [16] each
+    int* ok;
+};
+
+// One workgroup's part of a tile: workgroup `kp` of G contracts fragments [kp, kp + 1) * NK / G of K; kp = 0 leads.
+template <typename XT, int G, bool LEADER>
+__device__ __forceinline__ void proj_tile(const DevPtrs& d, int cur, int tile, int kp, const ProjShared& sh)
 {
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int jl = lane & 15, g = lane >> 4;
@@ -945,88 +962,78 @@ __global__ __launch_bounds__(PROJ_THREADS) void k_proj(DevPtrs d, int cur, int n
     constexpr int EPL = Frag<XT>::EPL;
     constexpr int NKD = K_DEC / KB;
     constexpr int NK = K_PROJ / KB;
-    constexpr int NKW = NK / PROJ_WAVES;
-    static_assert(NK % PROJ_WAVES == 0, "K must split evenly over the waves");
+    constexpr int NKW = NK / G / PROJ_WAVES;
+    static_assert(NK % (G * PROJ_WAVES) == 0, "K must split evenly over the workgroups' waves");
     constexpr int NM = PROJ_ROWS / 16;
-    // One CU pulling the projection weights (64 bytes a clock) is what bounds this kernel, so
-    // everything is requested at once, small things first: the activations and the slots'
-    // bookkeeping words (a workgroup serves the 16 slots blockIdx.x * 16 ..: no list of active
-    // tiles to wait for), the biases, then the weights.  With bf16 weights the wave's whole share
-    // (all row tiles of its K range) is in flight together; fp32 fragments are twice the
-    // registers: there the row tiles go one at a time.  A tile without a running request is
-    // computed and dropped (there is no early exit: the compiler would move the loads below it).
-    constexpr bool W_EARLY = sizeof(XT) == 2;
+    // Everything is requested at once, small things first: the activations and the slots' bookkeeping words (a
+    // workgroup serves the 16 slots tile * 16 ..: no list of active tiles to wait for), the biases, then the
+    // weights.  A wave's whole share of W_proj (all row tiles of its K range) is in flight together, except for fp32
+    // fragments of the whole K: there the row tiles go one at a time.  A tile without a running request is computed
+    // and dropped (there is no early exit: the compiler would move the loads below it).
+    constexpr bool W_EARLY = sizeof(XT) == 2 || G > 1;
     constexpr int MH = W_EARLY ? NM : 1;          // row tiles whose fragments are in flight together
+    // the leader's prenet weights go out before the first product when its share of W_proj is small
+    constexpr bool PRENET_FIRST = false;
 
-    __shared__ __attribute__((aligned(16))) float s_big[PROJ_WAVES * PROJ_ROWS * 16];   // partial sums, later hid
-    // row strides of 100 and 260 floats (an odd number of 16-byte pieces): the 16 columns of a
-    // fragment read then fall into 16 different bank groups instead of one
-    constexpr int MEL_LD = PROJ_ROWS + 4, HID_LD = PRENET + 4;
-    __shared__ __attribute__((aligned(16))) float s_mel[16][MEL_LD];
-    __shared__ int s_slot[16], s_t[16], s_cap[16];
-    float (*s_part)[PROJ_ROWS][16] = reinterpret_cast<float (*)[PROJ_ROWS][16]>(s_big);
-    float (*s_hid)[HID_LD] = reinterpret_cast<float (*)[HID_LD]>(s_big);
-    static_assert(16 * HID_LD <= PROJ_WAVES * PROJ_ROWS * 16, "hid must fit the partial-sum buffer it aliases");
-
-    if constexpr (PRE) {
-        // The launch has 256 workgroups, one per CU; workgroup b runs on XCD b % 8.  XCD 0 holds the projection's own
-        // workgroups (b = 8 * tile) and is otherwise left idle: beside workgroups that stream at full rate, the
-        // projection's loads took a quarter longer.  The other seven XCDs form the next step's gate pre-sums: XCD x takes
-        // row tiles 256 (x - 1) / 7 .. 256 x / 7 of both matrices (every weight is fetched from HBM once), its 32
-        // workgroups split into one or two groups by pool tiles (two from three tiles on: 32 x 32 is the shape that
-        // moves the fewest bytes through a CU), and a group's workgroups share the XCD's 36 or 37 row tiles evenly:
-        // two or three each (one or two without the split).
-        const int x = blockIdx.x & 7, i = blockIdx.x >> 3;
-        if (x != 0) {
-            static_assert(sizeof(floatx4) * LSTM_WAVES * PG_R * PG_T * 64 <= sizeof(s_big), "the reduction buffer aliases the partial sums");
-            static_assert(PROJ_WAVES == LSTM_WAVES, "the pre-sums split K over eight waves");
-            const int rx0 = (HID / 4) * (x - 1) / 7, rx1 = (HID / 4) * x / 7;
-            int k = i, Mc = 32, t0 = 0, nt = n_tiles;
-            if (n_tiles > 2) {
-                const int per = (n_tiles + 1) / 2;
-                Mc = 16;
-                if (k < 16) nt = per;
-                else { k -= 16; t0 = per; nt = n_tiles - per; }
-            }
-            const int lo = rx0 + (rx1 - rx0) * k / Mc, hi = rx0 + (rx1 - rx0) * (k + 1) / Mc;
-            gate_presums<XT>(d, cur ^ 1, lo, hi - lo, t0, nt, reinterpret_cast<PresumRed>(s_big));
-            return;
-        }
-        if (i >= n_tiles) return;
-    }
-    const int tile = PRE ? blockIdx.x >> 3 : blockIdx.x;
+    float (*s_part)[PROJ_ROWS][16] = reinterpret_cast<float (*)[PROJ_ROWS][16]>(sh.big);
+    float (*s_hid)[PROJ_HID_LD] = reinterpret_cast<float (*)[PROJ_HID_LD]>(sh.big);
+    static_assert(16 * PROJ_HID_LD <= PROJ_WAVES * PROJ_ROWS * 16, "hid must fit the partial-sum buffer it aliases");
 
     const uint4* xnew = reinterpret_cast<const uint4*>(d.xdec[cur ^ 1]);   // h_dec of this step
     const uint4* xcur = reinterpret_cast<const uint4*>(d.xdec[cur]);       // a of this step
+    const int ks0 = (kp * PROJ_WAVES + wave) * NKW;
     uint4 b[NKW];
 #pragma unroll
     for (int f = 0; f < NKW; ++f) {
-        const int ks = wave * NKW + f;
+        const int ks = ks0 + f;
         b[f] = ks < HID / KB ? xnew[xfrag(NKD, tile, XD_HD / KB + ks, lane)]
                              : xcur[xfrag(NKD, tile, XD_A / KB + ks - HID / KB, lane)];
     }
+    // this workgroup's sequence number: the steps it has taken part in
+    unsigned my_seq = 0;
+    if constexpr (G > 1) my_seq = d.proj_seq[tile * G + kp];
     // slot bookkeeping of the 16 columns and this thread's biases of the reduction phase
     const int my_sl = tile * 16 + (tid & 15);
-    const int my_live = d.live[my_sl], my_done = d.done[my_sl], my_t = d.t[my_sl], my_cap = d.n_steps[my_sl];
+    int my_live = 0, my_done = 0, my_t = 0, my_cap = 0;
     constexpr int RED_IT = 16 * PROJ_ROWS / PROJ_THREADS;
     static_assert(16 * PROJ_ROWS % PROJ_THREADS == 0, "the reduction phase splits evenly");
     float bias_r[RED_IT];
+    if constexpr (LEADER) {
+        my_live = d.live[my_sl]; my_done = d.done[my_sl]; my_t = d.t[my_sl]; my_cap = d.n_steps[my_sl];
 #pragma unroll
-    for (int it = 0; it < RED_IT; ++it) bias_r[it] = d.bmel[min((tid + it * PROJ_THREADS) >> 4, N_PROJ - 1)];
+        for (int it = 0; it < RED_IT; ++it) bias_r[it] = d.bmel[min((tid + it * PROJ_THREADS) >> 4, N_PROJ - 1)];
+    }
 
     const uint4* W = reinterpret_cast<const uint4*>(d.Wmel) + lane;
     uint4 a[MH][NKW];
-    auto load_proj_weights = [&](int m0) {
+    auto load_proj_weights = [&](int m0) __attribute__((always_inline)) {
 #pragma unroll
         for (int m = 0; m < MH; ++m)
 #pragma unroll
             for (int f = 0; f < NKW; ++f) {
                 // the last row tile holds the stop row and 15 rows of zeros: do not fetch the zeros
                 a[m][f] = make_uint4(0, 0, 0, 0);
-                if (m0 + m < NM - 1 || jl == 0) a[m][f] = W[((size_t)(m0 + m) * NK + wave * NKW + f) * 64];
+                if (m0 + m < NM - 1 || jl == 0) a[m][f] = W[((size_t)(m0 + m) * NK + ks0 + f) * 64];
             }
     };
     if constexpr (W_EARLY) load_proj_weights(0);
+    // weights of the two prenet layers for this wave's row tiles (w and w + 8), used after the two reduction phases
+    constexpr int NK3 = PrenetK1<XT>::value / KB;
+    constexpr int NK4 = PRENET / KB;
+    uint4 a3[LEADER ? 2 : 1][NK3], a4[LEADER ? 2 : 1][NK4];
+    auto load_prenet_weights = [&]() __attribute__((always_inline)) {
+        const uint4* W1 = reinterpret_cast<const uint4*>(d.Wp1) + lane;
+        const uint4* W2 = reinterpret_cast<const uint4*>(d.Wp2) + lane;
+#pragma unroll
+        for (int m = 0; m < 2; ++m) {
+            const int mt = wave + m * PROJ_WAVES;
+#pragma unroll
+            for (int f = 0; f < NK3; ++f) a3[m][f] = W1[((size_t)mt * NK3 + f) * 64];
+#pragma unroll
+            for (int f = 0; f < NK4; ++f) a4[m][f] = W2[((size_t)mt * NK4 + f) * 64];
+        }
+    };
+    if constexpr (PRENET_FIRST) load_prenet_weights();
     // keep the loads in this order: left alone, the scheduler issues the activation loads one at a
     // time between the MFMAs, each a full round trip
     __builtin_amdgcn_sched_barrier(0);
@@ -1045,110 +1052,181 @@ __global__ __launch_bounds__(PROJ_THREADS) void k_proj(DevPtrs d, int cur, int n
         }
     }
 
-    if (tid < 16) {
-        const bool on = my_live && !my_done;
-        s_slot[tid] = on ? my_sl : -1;
-        s_t[tid] = on ? my_t : 0;
-        s_cap[tid] = on ? my_cap : 0;
-    }
-
-    // weights of the two prenet layers for this wave's row tiles (w and w + 8): requested now that the
-    // projection fragments have left the registers, used after the two reduction phases below
-    constexpr int NK3 = PrenetK1<XT>::value / KB;
-    constexpr int NK4 = PRENET / KB;
-    uint4 a3[2][NK3], a4[2][NK4];
-    {
-        const uint4* W1 = reinterpret_cast<const uint4*>(d.Wp1) + lane;
-        const uint4* W2 = reinterpret_cast<const uint4*>(d.Wp2) + lane;
-#pragma unroll
-        for (int m = 0; m < 2; ++m) {
-            const int mt = wave + m * PROJ_WAVES;
-#pragma unroll
-            for (int f = 0; f < NK3; ++f) a3[m][f] = W1[((size_t)mt * NK3 + f) * 64];
-#pragma unroll
-            for (int f = 0; f < NK4; ++f) a4[m][f] = W2[((size_t)mt * NK4 + f) * 64];
+    if constexpr (LEADER) {
+        if (tid < 16) {
+            const bool on = my_live && !my_done;
+            sh.slot[tid] = on ? my_sl : -1;
+            sh.t[tid] = on ? my_t : 0;
+            sh.cap[tid] = on ? my_cap : 0;
         }
+        // requested now that the projection fragments have left the registers
+        if constexpr (!PRENET_FIRST) load_prenet_weights();
     }
     __syncthreads();
 
-    // ---- phase 2: reduce, bias, hand the frame out
+    // ---- phase 2: reduce over the waves ...
+    float v[RED_IT];
 #pragma unroll
     for (int it = 0; it < RED_IT; ++it) {
         const int idx = tid + it * PROJ_THREADS;
         const int o = idx >> 4, r = idx & 15;
-        float v = 0.f;
+        v[it] = 0.f;
         if (o < N_PROJ) {
-            v = bias_r[it];
+            if constexpr (LEADER) v[it] = bias_r[it];
 #pragma unroll
-            for (int w = 0; w < PROJ_WAVES; ++w) v += s_part[w][o][r];
+            for (int w = 0; w < PROJ_WAVES; ++w) v[it] += s_part[w][o][r];
         }
-        s_mel[r][o] = v;
     }
-    __syncthreads();
-    for (int idx = tid; idx < 16 * N_PROJ; idx += PROJ_THREADS) {
-        const int r = idx / N_PROJ, o = idx - r * N_PROJ;
-        const int sl = s_slot[r];
-        if (sl >= 0) {
-            const float v = s_mel[r][o];
-            if (o < N_MEL) {
-                d.mel_ring[((size_t)sl * d.max_steps + s_t[r]) * N_MEL + o] = v;
-                d.m_last[(size_t)sl * N_MEL + o] = v;
-            } else {
-                d.stop_ring[(size_t)sl * d.max_steps + s_t[r]] = v;
+    if constexpr (!LEADER) {
+        // ... a helper hands its sums over, each word with the sequence number beside it in one 8-byte store: the
+        // leader knows a word is this step's from the number it carries, no flag and no fence are needed
+        unsigned long long* mine = d.proj_part + (size_t)(tile * (G - 1) + kp - 1) * (16 * PROJ_ROWS);
+#pragma unroll
+        for (int it = 0; it < RED_IT; ++it)
+            __hip_atomic_store(&mine[tid + it * PROJ_THREADS], ((unsigned long long)(my_seq + 1u) << 32) | __float_as_uint(v[it]),
+                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (tid == 0) d.proj_seq[tile * G + kp] = my_seq + 1u;
+        return;
+    } else {
+        if constexpr (G > 1) {
+            // ... the leader takes the helpers' words as they arrive (every thread polls its own, a bounded number of
+            // times) and adds them in helper order
+            unsigned long long w[G - 1][RED_IT];
+            bool all_in = false;
+            for (int spin = 0; spin < PROJ_SPIN && !all_in; ++spin) {
+                all_in = true;
+#pragma unroll
+                for (int h = 0; h < G - 1; ++h) {
+                    const unsigned long long* theirs = d.proj_part + (size_t)(tile * (G - 1) + h) * (16 * PROJ_ROWS);
+#pragma unroll
+                    for (int it = 0; it < RED_IT; ++it) {
+                        w[h][it] = __hip_atomic_load(&theirs[tid + it * PROJ_THREADS], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        all_in = all_in && (unsigned)(w[h][it] >> 32) == my_seq + 1u;
+                    }
+                }
             }
+            if (!all_in) *d.fault = 1;
+#pragma unroll
+            for (int h = 0; h < G - 1; ++h)
+#pragma unroll
+                for (int it = 0; it < RED_IT; ++it) v[it] += __uint_as_float((unsigned)w[h][it]);
+            if (tid == 0) d.proj_seq[tile * G] = my_seq + 1u;
         }
-    }
-
-    // ---- phase 3: hid^T = relu(W_p1 mel^T); wave w owns row tiles w and w + 8
-    {
-        uint4 b[NK3];
+        // ... bias is in; hand the frame out
 #pragma unroll
-        for (int f = 0; f < NK3; ++f) b[f] = frag_from_f32<XT>(&s_mel[jl][f * KB + g * EPL]);
-        floatx4 acc[2];
-#pragma unroll
-        for (int m = 0; m < 2; ++m) {
-            acc[m] = floatx4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int f = 0; f < NK3; ++f) acc[m] = mfma_frag<XT>(a3[m][f], b[f], acc[m]);
+        for (int it = 0; it < RED_IT; ++it) {
+            const int idx = tid + it * PROJ_THREADS;
+            sh.mel[idx & 15][idx >> 4] = v[it];
         }
-        // s_hid aliases the partial sums: every read of those finished before the last barrier
-#pragma unroll
-        for (int m = 0; m < 2; ++m)
-#pragma unroll
-            for (int i = 0; i < 4; ++i) s_hid[jl][16 * (wave + m * PROJ_WAVES) + 4 * g + i] = fmaxf(acc[m][i], 0.f);
-    }
-    __syncthreads();
-
-    // ---- phase 4: p^T = relu(W_p2 hid^T)
-    {
-        uint4 b[NK4];
-#pragma unroll
-        for (int f = 0; f < NK4; ++f) b[f] = frag_from_f32<XT>(&s_hid[jl][f * KB + g * EPL]);
-        const int sl = s_slot[jl];
-        XT* xa = reinterpret_cast<XT*>(d.xatt[cur ^ 1]);
-#pragma unroll
-        for (int m = 0; m < 2; ++m) {
-            const int mt = wave + m * PROJ_WAVES;
-            floatx4 acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int f = 0; f < NK4; ++f) acc = mfma_frag<XT>(a4[m][f], b[f], acc);
+        __syncthreads();
+        for (int idx = tid; idx < 16 * N_PROJ; idx += PROJ_THREADS) {
+            const int r = idx / N_PROJ, o = idx - r * N_PROJ;
+            const int sl = sh.slot[r];
             if (sl >= 0) {
-                // four consecutive k inside one 16-byte piece: one store
-                XT* dst = xa + xoff<XT>(K_ATT / KB, sl, XA_P + 16 * mt + 4 * g);
-                const float p0 = fmaxf(acc[0], 0.f), p1 = fmaxf(acc[1], 0.f), p2 = fmaxf(acc[2], 0.f), p3 = fmaxf(acc[3], 0.f);
-                if constexpr (sizeof(XT) == 2) *reinterpret_cast<uint2*>(dst) = make_uint2(pack_bf16x2(p0, p1), pack_bf16x2(p2, p3));
-                else *reinterpret_cast<float4*>(dst) = make_float4(p0, p1, p2, p3);
+                const float m = sh.mel[r][o];
+                if (o < N_MEL) {
+                    d.mel_ring[((size_t)sl * d.max_steps + sh.t[r]) * N_MEL + o] = m;
+                    d.m_last[(size_t)sl * N_MEL + o] = m;
+                } else {
+                    d.stop_ring[(size_t)sl * d.max_steps + sh.t[r]] = m;
+                }
             }
         }
-    }
 
-    if (tid < 16 && s_slot[tid] >= 0) {
-        const int sl = s_slot[tid];
-        const int tn = s_t[tid] + 1;
-        d.t[sl] = tn;
-        bool fin = tn >= s_cap[tid];
-        if (d.stop_threshold >= 0.f && sigmoidf_(s_mel[tid][N_MEL]) > d.stop_threshold) fin = true;
-        if (fin) d.done[sl] = 1;
+        // ---- phase 3: hid^T = relu(W_p1 mel^T); wave w owns row tiles w and w + 8
+        {
+            uint4 bm[NK3];
+#pragma unroll
+            for (int f = 0; f < NK3; ++f) bm[f] = frag_from_f32<XT>(&sh.mel[jl][f * KB + g * EPL]);
+            floatx4 acc[2];
+#pragma unroll
+            for (int m = 0; m < 2; ++m) {
+                acc[m] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int f = 0; f < NK3; ++f) acc[m] = mfma_frag<XT>(a3[m][f], bm[f], acc[m]);
+            }
+            // s_hid aliases the partial sums: every read of those finished before the last barrier
+#pragma unroll
+            for (int m = 0; m < 2; ++m)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) s_hid[jl][16 * (wave + m * PROJ_WAVES) + 4 * g + i] = fmaxf(acc[m][i], 0.f);
+        }
+        __syncthreads();
+
+        // ---- phase 4: p^T = relu(W_p2 hid^T)
+        {
+            uint4 bh[NK4];
+#pragma unroll
+            for (int f = 0; f < NK4; ++f) bh[f] = frag_from_f32<XT>(&s_hid[jl][f * KB + g * EPL]);
+            const int sl = sh.slot[jl];
+            XT* xa = reinterpret_cast<XT*>(d.xatt[cur ^ 1]);
+#pragma unroll
+            for (int m = 0; m < 2; ++m) {
+                const int mt = wave + m * PROJ_WAVES;
+                floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int f = 0; f < NK4; ++f) acc = mfma_frag<XT>(a4[m][f], bh[f], acc);
+                if (sl >= 0) {
+                    // four consecutive k inside one 16-byte piece: one store
+                    XT* dst = xa + xoff<XT>(K_ATT / KB, sl, XA_P + 16 * mt + 4 * g);
+                    const float p0 = fmaxf(acc[0], 0.f), p1 = fmaxf(acc[1], 0.f), p2 = fmaxf(acc[2], 0.f), p3 = fmaxf(acc[3], 0.f);
+                    if constexpr (sizeof(XT) == 2) *reinterpret_cast<uint2*>(dst) = make_uint2(pack_bf16x2(p0, p1), pack_bf16x2(p2, p3));
+                    else *reinterpret_cast<float4*>(dst) = make_float4(p0, p1, p2, p3);
+                }
+            }
+        }
+
+        if (tid < 16 && sh.slot[tid] >= 0) {
+            const int sl = sh.slot[tid];
+            const int tn = sh.t[tid] + 1;
+            d.t[sl] = tn;
+            bool fin = tn >= sh.cap[tid];
+            if (d.stop_threshold >= 0.f && sigmoidf_(sh.mel[tid][N_MEL]) > d.stop_threshold) fin = true;
+            if (fin) d.done[sl] = 1;
+        }
+    }
+}
+
+template <typename XT, bool PRE>
+__global__ __launch_bounds__(PROJ_THREADS) void k_proj(DevPtrs d, int cur, int n_tiles)
+{
+    __shared__ __attribute__((aligned(16))) float s_big[PROJ_WAVES * PROJ_ROWS * 16];
+    // row strides of 100 and 260 floats (an odd number of 16-byte pieces): the 16 columns of a
+    // fragment read then fall into 16 different bank groups instead of one
+    __shared__ __attribute__((aligned(16))) float s_mel[16][PROJ_MEL_LD];
+    __shared__ int s_slot[16], s_t[16], s_cap[16], s_ok;
+    const ProjShared sh = {s_big, s_mel, s_slot, s_t, s_cap, &s_ok};
+
+    if constexpr (PRE) {
+        // The launch has 256 workgroups, one per CU; workgroup b runs on XCD b % 8.  XCD 0 holds the projection's own
+        // workgroups (b = 8 * (PROJ_G * tile + part)) and is otherwise left idle: beside workgroups that stream at full
+        // rate, the projection's loads took a quarter longer.  The other seven XCDs form the next step's gate pre-sums:
+        // XCD x takes row tiles 256 (x - 1) / 7 .. 256 x / 7 of both matrices (every weight is fetched from HBM once),
+        // its 32 workgroups split into one or two groups by pool tiles (two from three tiles on: 32 x 32 is the shape
+        // that moves the fewest bytes through a CU), and a group's workgroups share the XCD's 36 or 37 row tiles
+        // evenly: two or three each (one or two without the split).
+        const int x = blockIdx.x & 7, i = blockIdx.x >> 3;
+        if (x != 0) {
+            static_assert(sizeof(floatx4) * LSTM_WAVES * PG_R * PG_T * 64 <= sizeof(s_big), "the reduction buffer aliases the partial sums");
+            static_assert(PROJ_WAVES == LSTM_WAVES, "the pre-sums split K over eight waves");
+            const int rx0 = (HID / 4) * (x - 1) / 7, rx1 = (HID / 4) * x / 7;
+            int k = i, Mc = 32, t0 = 0, nt = n_tiles;
+            if (n_tiles > 2) {
+                const int per = (n_tiles + 1) / 2;
+                Mc = 16;
+                if (k < 16) nt = per;
+                else { k -= 16; t0 = per; nt = n_tiles - per; }
+            }
+            const int lo = rx0 + (rx1 - rx0) * k / Mc, hi = rx0 + (rx1 - rx0) * (k + 1) / Mc;
+            gate_presums<XT>(d, cur ^ 1, lo, hi - lo, t0, nt, reinterpret_cast<PresumRed>(s_big));
+            return;
+        }
+        static_assert(PROJ_G * PRESUM_MAX_TILES <= 32, "the projection's workgroups fit XCD 0");
+        if (i >= n_tiles * PROJ_G) return;
+        if (i % PROJ_G == 0) proj_tile<XT, PROJ_G, true>(d, cur, i / PROJ_G, 0, sh);
+        else proj_tile<XT, PROJ_G, false>(d, cur, i / PROJ_G, i % PROJ_G, sh);
+    } else {
+        proj_tile<XT, 1, true>(d, cur, blockIdx.x, 0, sh);
     }
 }
 

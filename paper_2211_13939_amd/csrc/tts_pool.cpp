@@ -65,10 +65,10 @@ static int check_config(const tts_config* c)
 namespace {
 
 struct Layout {
-    size_t Wa, Wd, ba, bd, Wq, Wq_epi, qpart, pre_att, pre_dec, WmemT, lsa_kfrag, lsa_wfrag, v, Wmel, bmel, Wp1, Wp2;
+    size_t Wa, Wd, ba, bd, Wq, Wq_epi, qpart, pre_att, pre_dec, proj_part, WmemT, lsa_kfrag, lsa_wfrag, v, Wmel, bmel, Wp1, Wp2;
     size_t xatt[2], xdec[2], c_att, c_dec, m_last, w_last[2], w_acc[2], Fmem, PM, mel_ring, stop_ring;
-    size_t L, t, n_steps, done, live, stage;
-    size_t total;
+    size_t L, t, n_steps, done, live, proj_seq, stage;
+    size_t total, proj_part_bytes;
 };
 
 // Gate pre-sums: pools of at most PRESUM_MAX_TILES tiles leave all but a few CUs idle during the projection kernel,
@@ -107,6 +107,8 @@ Layout make_layout(const tts_config& c)
     l.qpart = a.take((pre_gates_for(c) ? S : 0) * (size_t)QUERY_PARTIALS * ATT * 4);
     l.pre_att = a.take((pre_gates_for(c) ? S / 16 : 0) * (size_t)(HID / 4) * 64 * 16);
     l.pre_dec = a.take((pre_gates_for(c) ? S / 16 : 0) * (size_t)(HID / 4) * 64 * 16);
+    l.proj_part_bytes = (pre_gates_for(c) ? S / 16 : 0) * (size_t)(PROJ_GROUP - 1) * 96 * 16 * 8;
+    l.proj_part = a.take(l.proj_part_bytes);
     l.c_att = a.take(S * HID * 4);
     l.c_dec = a.take(S * HID * 4);
     l.m_last = a.take(S * N_MEL * 4);
@@ -123,6 +125,7 @@ Layout make_layout(const tts_config& c)
     l.n_steps = a.take(S * 4);
     l.done = a.take(S * 4);
     l.live = a.take(MAX_POOL * 4);
+    l.proj_seq = a.take((size_t)PRESUM_MAX_TILES * PROJ_GROUP * 4);     // zeroed at creation with the counters above
     l.stage = a.take(ML * ENC * 4);
     l.total = a.off;
     return l;
@@ -211,7 +214,16 @@ struct tts_pool {
     bool ev_valid = false;
     std::map<int, hipGraphExec_t> graphs;   // key = ((steps * 1024 + bucket) * 2 + parity
     std::vector<hipGraph_t> graph_defs;
+    int* h_fault = nullptr;       // pinned, mapped: non-zero once a kernel's bounded wait has run out
 };
+
+// After a synchronisation that hands results to the caller: did every kernel finish its work?
+static int device_ok(const tts_pool* p)
+{
+    if (p->h_fault && *p->h_fault)
+        return fail(TTS_E_HIP, "a projection workgroup gave up waiting for its partners' partial sums: frames since the last check are invalid");
+    return TTS_OK;
+}
 
 static int upload_weights(tts_pool* p, const tts_weights* w, char* base, const Layout& l)
 {
@@ -310,6 +322,21 @@ extern "C" int tts_pool_create(const tts_config* cfg, const tts_weights* w, void
     d.qpart = pre_gates_for(*cfg) ? reinterpret_cast<float*>(base + l.qpart) : nullptr;
     d.pre_att = pre_gates_for(*cfg) ? reinterpret_cast<float*>(base + l.pre_att) : nullptr;
     d.pre_dec = pre_gates_for(*cfg) ? reinterpret_cast<float*>(base + l.pre_dec) : nullptr;
+    d.proj_part = pre_gates_for(*cfg) ? reinterpret_cast<unsigned long long*>(base + l.proj_part) : nullptr;
+    d.proj_seq = reinterpret_cast<unsigned*>(base + l.proj_seq);
+    // one pinned word the kernels can reach: a projection leader that gives up on its helpers says so here
+    {
+        hipError_t e = hipHostMalloc(reinterpret_cast<void**>(&p->h_fault), sizeof(int), hipHostMallocMapped);
+        if (e == hipSuccess) {
+            *p->h_fault = 0;
+            e = hipHostGetDevicePointer(reinterpret_cast<void**>(&d.fault), p->h_fault, 0);
+        }
+        if (e != hipSuccess) {
+            const int rc0 = fail(TTS_E_HIP, "pinned status word: %s", hipGetErrorString(e));
+            tts_pool_destroy(p);
+            return rc0;
+        }
+    }
     d.WmemT = (const float*)(base + l.WmemT);
     d.lsa_kfrag = base + l.lsa_kfrag;
     d.lsa_wfrag = base + l.lsa_wfrag;
@@ -347,6 +374,8 @@ extern "C" int tts_pool_create(const tts_config* cfg, const tts_weights* w, void
     if (rc == TTS_OK) {
         // slot counters and flags start defined: nothing live, no frames produced
         hipError_t e = hipMemset(base + l.L, 0, l.stage - l.L);
+        // no word of the projection's hand-over buffer may carry a sequence number a leader could wait for
+        if (e == hipSuccess && d.proj_part) e = hipMemset(base + l.proj_part, 0, l.proj_part_bytes);
         if (e == hipSuccess) e = hipEventCreate(&p->ev0);
         if (e == hipSuccess) e = hipEventCreate(&p->ev1);
         if (e == hipSuccess) e = hipDeviceSynchronize();
@@ -368,6 +397,7 @@ extern "C" void tts_pool_destroy(tts_pool* p)
     for (auto g : p->graph_defs) (void)hipGraphDestroy(g);
     if (p->ev0) (void)hipEventDestroy(p->ev0);
     if (p->ev1) (void)hipEventDestroy(p->ev1);
+    if (p->h_fault) (void)hipHostFree(p->h_fault);
     delete p;
 }
 
@@ -616,6 +646,7 @@ extern "C" int tts_pool_drain_chunk(tts_pool* p, int64_t id, float* dst, int* ou
         const float* src = p->d.mel_ring + ((size_t)slot * p->cfg.max_steps + first) * N_MEL;
         HIP_TRY(hipMemcpyAsync(dst, src, (size_t)count * N_MEL * 4, hipMemcpyDeviceToHost, p->stream));
         HIP_TRY(hipStreamSynchronize(p->stream));
+        if ((rc = device_ok(p))) return rc;
         p->book->drain_commit(slot, count);
     }
     *out_frames = count;
@@ -688,7 +719,7 @@ extern "C" int tts_pool_sync(tts_pool* p)
 {
     if (!p) return fail(TTS_E_INVAL, "pool is null");
     HIP_TRY(hipStreamSynchronize(p->stream));
-    return TTS_OK;
+    return device_ok(p);
 }
 
 extern "C" int tts_pool_timing(tts_pool* p, int enable)
