@@ -44,7 +44,9 @@ struct DevPtrs {
     unsigned long long* proj_part; // [tiles][5][96 * 16] (sequence number << 32 | float bits): partial sums of the projection's helper
                           // workgroups (pools with pre-sums), written and read within one kernel
     unsigned* proj_seq;   // [tiles][6]: steps each of a tile's projection workgroups has taken part in (zero at creation)
-    int* fault;           // pinned host memory: set by a projection leader whose wait for its helpers ran out
+    unsigned long long* lsa_x; // [slots][max_enc_len] (step number << 32 | float bits): the energies the workgroups of a request hand each other
+    unsigned* step_seq;   // [1] steps taken (zero at creation; advanced by the projection kernel)
+    int* fault;           // pinned host memory: set by a workgroup whose bounded wait for another's words ran out
     const void* lsa_kfrag; // location filters as per-lane MFMA A operands (layout depends on WT)
     const void* lsa_wfrag; // W_loc as per-lane MFMA A operands (layout depends on WT)
     const float* WmemT;   // [ENC][ATT] fp32 (join time only)

@@ -479,6 +479,7 @@ __global__ __launch_bounds__(LSTM_WAVES * 64) void k_presum_tile(DevPtrs d, int 
 constexpr int LSA_THREADS = 512;
 constexpr int LSA_WAVES = LSA_THREADS / 64;
 constexpr int LSA_UPAD = MAX_ENC_LEN + 48;
+constexpr int LSA_SPIN = 1 << 18;             // polls of another workgroup's energy word before giving up
 
 template <typename XT> struct LsaTile;
 
@@ -576,6 +577,10 @@ __global__ __launch_bounds__(LSA_THREADS) void k_lsa(DevPtrs d, int cur)
     // slot holds (all reads stay inside the slot's arrays) and writes nothing.
     const int slot = blockIdx.x / S, sp = blockIdx.x % S;
     const int live_w = d.live[slot], done_w = d.done[slot], L_w = d.L[slot];
+    // the request's S workgroups share the energies (below): this step's number marks the words they exchange
+    constexpr bool XCH = S > 1;
+    unsigned seq = 0;
+    if constexpr (XCH) seq = d.step_seq[0] + 1u;
     // q = W_q h_att, one of two ways.
     // QP (pools with gate pre-sums): it arrives as QP_TALL rank-32 partial products written by this step's attention
     // LSTM.  Thread (a = tid % 128, quarter = tid / 128) adds up its quarter's pair sums P[2i] + P[2i+1] in
@@ -650,7 +655,7 @@ __global__ __launch_bounds__(LSA_THREADS) void k_lsa(DevPtrs d, int cur)
     constexpr bool PM_AHEAD = sizeof(XT) == 2;    // fp32 operands leave no registers for a second PM row
     uint4 pmv[NV];
     if constexpr (PM_AHEAD) {
-        const MT* pm = PMs + (size_t)min(wave * 16 + jl, ML - 1) * ATT;
+        const MT* pm = PMs + (size_t)min((sp + S * wave) * 16 + jl, ML - 1) * ATT;
 #pragma unroll
         for (int i = 0; i < NV; ++i) pmv[i] = *reinterpret_cast<const uint4*>(pm + i * NPM);
     }
@@ -738,16 +743,19 @@ __global__ __launch_bounds__(LSA_THREADS) void k_lsa(DevPtrs d, int cur)
     const bool fast_softmax = bound <= 30.f;        // the same in every lane of every wave
     float psum = 0.f;
     // ---- energies, one 16-position tile per wave at a time; PM of the next tile is already in flight.
-    // With S > 1 every workgroup of the request computes all energies: they are cheap next to the
-    // encoder-row stream, and it keeps the softmax exact and local.
-    for (int tt = wave; tt < ntile; tt += LSA_WAVES) {
+    // The request's S workgroups share them: workgroup sp takes tiles sp, sp + S, ... and stores every energy
+    // (numerator) beside this step's number as one 8-byte word; the others' words are fetched below.  The
+    // energies are VALU work (128 exp + 128 rcp per position): computing all of them in each of the S
+    // workgroups held the request's longest workgroup for 3 us at 300 positions.
+    unsigned long long* ex = d.lsa_x + (size_t)slot * ML;
+    for (int tt = sp + S * wave; tt < ntile; tt += S * LSA_WAVES) {
         const int j = tt * 16 + jl;
         uint4 pmc[NV];
         if constexpr (PM_AHEAD) {
 #pragma unroll
             for (int i = 0; i < NV; ++i) pmc[i] = pmv[i];
             // unconditional: past the end it re-reads the last row, which is never used
-            const MT* pm = PMs + (size_t)min(j + LSA_WAVES * 16, L - 1) * ATT;
+            const MT* pm = PMs + (size_t)min(j + S * LSA_WAVES * 16, L - 1) * ATT;
 #pragma unroll
             for (int i = 0; i < NV; ++i) pmv[i] = *reinterpret_cast<const uint4*>(pm + i * NPM);
         } else {
@@ -782,11 +790,12 @@ __global__ __launch_bounds__(LSA_THREADS) void k_lsa(DevPtrs d, int cur)
         if (fast_softmax) e = __expf(e - bound);
         if (g == 0 && j < L) {
             s_e[j] = e;
-            psum += e;
+            if constexpr (XCH)
+                __hip_atomic_store(&ex[j], ((unsigned long long)seq << 32) | __float_as_uint(e), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            else
+                psum += e;
         }
     }
-    psum = wave_sum(psum);
-    if (lane == 0) s_red[LSA_WAVES + wave] = psum;
 
     // ---- context over this workgroup's ENC / S columns: a wave-wide load covers S encoder rows
     // (64 / S lanes x 8 columns each), NR loads in flight per wave.  The first batch is requested
@@ -812,6 +821,30 @@ __global__ __launch_bounds__(LSA_THREADS) void k_lsa(DevPtrs d, int cur)
 #pragma unroll
             for (int v = 0; v < VPR; ++v) rows[pp][c][v] = *reinterpret_cast<const uint4*>(row + v * NPM);
         }
+    if constexpr (XCH) {
+        // the other workgroups' energies: every thread polls its own words until they carry this step's number
+        // (bounded: the request's workgroups are resident together, S * slots <= 256 = one per CU)
+        for (int x = tid; x < L; x += LSA_THREADS) {
+            if ((x >> 4) % S != sp) {
+                unsigned long long w = 0;
+                bool in = false;
+                for (int spin = 0; spin < LSA_SPIN && !in; ++spin) {
+                    w = __hip_atomic_load(&ex[x], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    in = (unsigned)(w >> 32) == seq;
+                }
+                if (!in) *d.fault = 1;
+                s_e[x] = __uint_as_float((unsigned)w);
+            }
+        }
+        __syncthreads();
+        // the sum in the order the one-workgroup form takes it: wave w adds tiles w, w + 8, ...
+        for (int tt = wave; tt < ntile; tt += LSA_WAVES) {
+            const int j = tt * 16 + jl;
+            if (g == 0 && j < L) psum += s_e[j];
+        }
+    }
+    psum = wave_sum(psum);
+    if (lane == 0) s_red[LSA_WAVES + wave] = psum;
     __syncthreads();
 
     // ---- ragged softmax over j < L: s_e holds the numerators already, or the energies
@@ -998,7 +1031,9 @@ __device__ __forceinline__ void proj_tile(const DevPtrs& d, int cur, int tile, i
     constexpr int RED_IT = 16 * PROJ_ROWS / PROJ_THREADS;
     static_assert(16 * PROJ_ROWS % PROJ_THREADS == 0, "the reduction phase splits evenly");
     float bias_r[RED_IT];
+    unsigned step_no = 0;
     if constexpr (LEADER) {
+        step_no = d.step_seq[0];
         my_live = d.live[my_sl]; my_done = d.done[my_sl]; my_t = d.t[my_sl]; my_cap = d.n_steps[my_sl];
 #pragma unroll
         for (int it = 0; it < RED_IT; ++it) bias_r[it] = d.bmel[min((tid + it * PROJ_THREADS) >> 4, N_PROJ - 1)];
@@ -1176,6 +1211,8 @@ __device__ __forceinline__ void proj_tile(const DevPtrs& d, int cur, int tile, i
             }
         }
 
+        // one step further: the number the attention kernel's workgroups mark their exchanged words with
+        if (tile == 0 && tid == 0) d.step_seq[0] = step_no + 1u;
         if (tid < 16 && sh.slot[tid] >= 0) {
             const int sl = sh.slot[tid];
             const int tn = sh.t[tid] + 1;

@@ -67,7 +67,7 @@ namespace {
 struct Layout {
     size_t Wa, Wd, ba, bd, Wq, Wq_epi, qpart, pre_att, pre_dec, proj_part, WmemT, lsa_kfrag, lsa_wfrag, v, Wmel, bmel, Wp1, Wp2;
     size_t xatt[2], xdec[2], c_att, c_dec, m_last, w_last[2], w_acc[2], Fmem, PM, mel_ring, stop_ring;
-    size_t L, t, n_steps, done, live, proj_seq, stage;
+    size_t L, t, n_steps, done, live, proj_seq, step_seq, lsa_x, stage;
     size_t total, proj_part_bytes;
 };
 
@@ -126,6 +126,8 @@ Layout make_layout(const tts_config& c)
     l.done = a.take(S * 4);
     l.live = a.take(MAX_POOL * 4);
     l.proj_seq = a.take((size_t)PRESUM_MAX_TILES * PROJ_GROUP * 4);     // zeroed at creation with the counters above
+    l.step_seq = a.take(4);
+    l.lsa_x = a.take(S * ML * 8);                                       // zeroed too: no word carries a step's number yet
     l.stage = a.take(ML * ENC * 4);
     l.total = a.off;
     return l;
@@ -221,7 +223,7 @@ struct tts_pool {
 static int device_ok(const tts_pool* p)
 {
     if (p->h_fault && *p->h_fault)
-        return fail(TTS_E_HIP, "a projection workgroup gave up waiting for its partners' partial sums: frames since the last check are invalid");
+        return fail(TTS_E_HIP, "a workgroup gave up waiting for the words of its partners (projection sums or attention energies): frames since the last check are invalid");
     return TTS_OK;
 }
 
@@ -324,6 +326,8 @@ extern "C" int tts_pool_create(const tts_config* cfg, const tts_weights* w, void
     d.pre_dec = pre_gates_for(*cfg) ? reinterpret_cast<float*>(base + l.pre_dec) : nullptr;
     d.proj_part = pre_gates_for(*cfg) ? reinterpret_cast<unsigned long long*>(base + l.proj_part) : nullptr;
     d.proj_seq = reinterpret_cast<unsigned*>(base + l.proj_seq);
+    d.step_seq = reinterpret_cast<unsigned*>(base + l.step_seq);
+    d.lsa_x = reinterpret_cast<unsigned long long*>(base + l.lsa_x);
     // one pinned word the kernels can reach: a projection leader that gives up on its helpers says so here
     {
         hipError_t e = hipHostMalloc(reinterpret_cast<void**>(&p->h_fault), sizeof(int), hipHostMallocMapped);
