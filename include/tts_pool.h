@@ -185,6 +185,10 @@ int tts_pool_n_active(const tts_pool *pool);
  * produced since are invalid, and this call and tts_pool_drain_chunk return TTS_E_HIP from then on. */
 int tts_pool_sync(tts_pool *pool);
 
+/* The bound of those waits, in polls (default 2^18).  Waits for the stream.  0 makes every such wait give up at
+ * once: the kernels run through as always, and the error path above can be exercised without anything hanging. */
+int tts_pool_set_wait_polls(tts_pool *pool, int polls);
+
 /* Device time of the kernels of the most recent tts_pool_step / step_n call,
  * measured with HIP events on the pool's stream.  Timing is off by default;
  * enable != 0 turns it on.  elapsed_ms waits for the stream. */

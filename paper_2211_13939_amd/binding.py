@@ -33,7 +33,7 @@ EXPORTS = (
     "tts_pool_workspace_bytes", "tts_pool_create", "tts_pool_add_request", "tts_pool_step",
     "tts_pool_step_n", "tts_pool_drain_chunk", "tts_pool_get_stop_logits", "tts_pool_retire",
     "tts_pool_get_state", "tts_pool_set_state", "tts_pool_frames", "tts_pool_size", "tts_pool_n_active",
-    "tts_pool_sync", "tts_pool_timing", "tts_pool_elapsed_ms", "tts_pool_kernel_times", "tts_pool_destroy",
+    "tts_pool_sync", "tts_pool_set_wait_polls", "tts_pool_timing", "tts_pool_elapsed_ms", "tts_pool_kernel_times", "tts_pool_destroy",
     "tts_last_error",
     "tts_book_create", "tts_book_add", "tts_book_step", "tts_book_drain", "tts_book_retire",
     "tts_book_destroy",
@@ -125,6 +125,7 @@ def lib() -> C.CDLL:
     L.tts_pool_size.argtypes = [vp]
     L.tts_pool_n_active.argtypes = [vp]
     L.tts_pool_sync.argtypes = [vp]
+    L.tts_pool_set_wait_polls.argtypes = [vp, C.c_int]
     L.tts_pool_timing.argtypes = [vp, C.c_int]
     L.tts_pool_elapsed_ms.argtypes = [vp, _fp]
     L.tts_pool_kernel_times.argtypes = [vp, C.c_int, _fp, C.c_int, _ip]
@@ -273,6 +274,9 @@ class Pool:
     def set_state(self, rid: int, name: str, value) -> None:
         v = np.ascontiguousarray(value, np.float32).ravel()
         _check(lib().tts_pool_set_state(self._h, rid, STATE[name], v.ctypes.data_as(_fp), v.shape[0]))
+
+    def set_wait_polls(self, polls: int) -> None:
+        _check(lib().tts_pool_set_wait_polls(self._h, int(polls)))
 
     def frames(self, rid: int) -> Tuple[int, bool]:
         n, fin = C.c_int(), C.c_int()

@@ -28,6 +28,9 @@ constexpr int MAX_TILES = MAX_POOL / 16;     // a pool tile = 16 consecutive slo
 constexpr int XA_P = 0, XA_A = PRENET, XA_H = PRENET + ENC;       // x_att = [p | a | h_att]
 constexpr int XD_HA = 0, XD_A = HID, XD_HD = HID + ENC;           // x_dec = [h_att | a | h_dec]
 
+// bound of the in-kernel waits: about a quarter of a second of polling
+constexpr int DEFAULT_WAIT_POLLS = 1 << 18;
+
 struct DevPtrs {
     // weights (WT = float or bf16 as configured)
     const uint4* Wa;      // attention-LSTM gate matrix, MFMA fragment order
@@ -73,6 +76,7 @@ struct DevPtrs {
     int* done;            // [slots] reached its last frame (or tripped the stop threshold)
     int* live;            // [MAX_POOL] 1 = the slot's request is advanced by the next step (set by the host's membership upload)
     float* stage;         // [max_enc_len][ENC] fp32 staging for host-side encoder outputs
+    int wait_polls;       // how often a workgroup polls another's words before it gives up and raises `fault` (DEFAULT_WAIT_POLLS)
     int max_enc_len;
     int max_steps;
     float stop_threshold; // < 0: disabled

@@ -479,7 +479,6 @@ __global__ __launch_bounds__(LSTM_WAVES * 64) void k_presum_tile(DevPtrs d, int 
 constexpr int LSA_THREADS = 512;
 constexpr int LSA_WAVES = LSA_THREADS / 64;
 constexpr int LSA_UPAD = MAX_ENC_LEN + 48;
-constexpr int LSA_SPIN = 1 << 18;             // polls of another workgroup's energy word before giving up
 
 template <typename XT> struct LsaTile;
 
@@ -828,7 +827,7 @@ __global__ __launch_bounds__(LSA_THREADS) void k_lsa(DevPtrs d, int cur)
             if ((x >> 4) % S != sp) {
                 unsigned long long w = 0;
                 bool in = false;
-                for (int spin = 0; spin < LSA_SPIN && !in; ++spin) {
+                for (int spin = 0; spin < d.wait_polls && !in; ++spin) {
                     w = __hip_atomic_load(&ex[x], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     in = (unsigned)(w >> 32) == seq;
                 }
@@ -960,7 +959,6 @@ constexpr int PROJ_THREADS = 512;
 constexpr int PROJ_WAVES = PROJ_THREADS / 64;
 constexpr int PROJ_ROWS = 96;
 constexpr int PROJ_G = 6;                        // workgroups per pool tile in pools with gate pre-sums
-constexpr int PROJ_SPIN = 1 << 18;               // polls of the helpers' sequence numbers before a leader gives up
 constexpr int PROJ_MEL_LD = PROJ_ROWS + 4, PROJ_HID_LD = PRENET + 4;
 static_assert(PROJ_G == PROJ_GROUP, "the arena holds PROJ_GROUP sequence numbers and PROJ_GROUP - 1 partial sums per tile");
 
@@ -1128,7 +1126,7 @@ __device__ __forceinline__ void proj_tile(const DevPtrs& d, int cur, int tile, i
             // times) and adds them in helper order
             unsigned long long w[G - 1][RED_IT];
             bool all_in = false;
-            for (int spin = 0; spin < PROJ_SPIN && !all_in; ++spin) {
+            for (int spin = 0; spin < d.wait_polls && !all_in; ++spin) {
                 all_in = true;
 #pragma unroll
                 for (int h = 0; h < G - 1; ++h) {

@@ -370,6 +370,7 @@ extern "C" int tts_pool_create(const tts_config* cfg, const tts_weights* w, void
     d.done = (int*)(base + l.done);
     d.live = (int*)(base + l.live);
     d.stage = (float*)(base + l.stage);
+    d.wait_polls = DEFAULT_WAIT_POLLS;
     d.max_enc_len = cfg->max_enc_len;
     d.max_steps = cfg->max_steps;
     d.stop_threshold = p->stop_enabled ? cfg->stop_threshold : -1.f;
@@ -724,6 +725,20 @@ extern "C" int tts_pool_sync(tts_pool* p)
     if (!p) return fail(TTS_E_INVAL, "pool is null");
     HIP_TRY(hipStreamSynchronize(p->stream));
     return device_ok(p);
+}
+
+extern "C" int tts_pool_set_wait_polls(tts_pool* p, int polls)
+{
+    if (!p) return fail(TTS_E_INVAL, "pool is null");
+    if (polls < 0) return fail(TTS_E_INVAL, "polls = %d is negative", polls);
+    HIP_TRY(hipStreamSynchronize(p->stream));
+    p->d.wait_polls = polls;
+    // captured graphs hold the old value among their kernel arguments
+    for (auto& kv : p->graphs) (void)hipGraphExecDestroy(kv.second);
+    for (auto g : p->graph_defs) (void)hipGraphDestroy(g);
+    p->graphs.clear();
+    p->graph_defs.clear();
+    return TTS_OK;
 }
 
 extern "C" int tts_pool_timing(tts_pool* p, int enable)

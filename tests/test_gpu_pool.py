@@ -341,6 +341,30 @@ def test_state_overwrite_refreshes_the_gate_presums(wl8, weights_fp32):
         pool.close()
 
 
+def test_wait_bound_zero_reports_an_error_and_nothing_hangs(wl8, weights_fp32, solo_frames):
+    """In pools of at most 64 slots workgroups wait, a bounded number of polls, for words other workgroups hand
+    them.  With the bound set to zero every such wait gives up at once: the kernels run through, sync and drain
+    report the error from then on; a pool with the default bound is not affected."""
+    from paper_2211_13939_amd.binding import TtsError
+    say("case: wait bound 0 (error path, forced from the host)")
+    pool = make_pool(wl8, weights_fp32, max_pool=8, max_enc_len=90, max_steps=24, chunk_frames=24)
+    rid = pool.add_request(wl8.encoder_outputs(1), 24)
+    pool.step_n(3)
+    pool.sync()                      # fine so far
+    pool.set_wait_polls(0)
+    pool.step_n(2)                   # returns: nothing hangs
+    with pytest.raises(TtsError):
+        pool.sync()
+    with pytest.raises(TtsError):
+        pool.sync()                  # sticky
+    pool.close()
+    other = make_pool(wl8, weights_fp32, max_pool=8, max_enc_len=90, max_steps=24, chunk_frames=24)
+    rid = other.add_request(wl8.encoder_outputs(1), 24)
+    other.step_n(24)
+    np.testing.assert_array_equal(_drain(other, rid), solo_frames[1])
+    other.close()
+
+
 def test_c3_shrinking_pool_full_job(weights_bf16):
     """The whole c3 job as the benchmark runs it (requests retire at their own
     end): every request produces exactly its frame count, sampled requests match
