@@ -1261,7 +1261,10 @@ __global__ __launch_bounds__(PROJ_THREADS) void k_proj(DevPtrs d, int cur, int n
         if (i % PROJ_G == 0) proj_tile<XT, PROJ_G, true>(d, cur, i / PROJ_G, 0, sh);
         else proj_tile<XT, PROJ_G, false>(d, cur, i / PROJ_G, i % PROJ_G, sh);
     } else {
-        proj_tile<XT, 1, true>(d, cur, blockIdx.x, 0, sh);
+        // larger pools: the same six workgroups per tile, wherever they land (n_tiles * PROJ_G <= 96 workgroups)
+        const int i = blockIdx.x;
+        if (i % PROJ_G == 0) proj_tile<XT, PROJ_G, true>(d, cur, i / PROJ_G, 0, sh);
+        else proj_tile<XT, PROJ_G, false>(d, cur, i / PROJ_G, i % PROJ_G, sh);
     }
 }
 
@@ -1428,7 +1431,7 @@ static hipError_t step_typed(const DevPtrs& d, int n_req, int n_tiles, int lsa_s
                            xdec_nxt, K_DEC / KB, XD_HD, n_tiles, d.live, d.done, pre_dec);
     mark(3);
     // with pre-sums the projection's launch fills the chip: XCD 0 runs the projection, the rest form the pre-sums
-    hipLaunchKernelGGL((k_proj<XT, PRE>), dim3(PRE ? 256 : n_tiles), dim3(PROJ_THREADS), 0, s, d, cur, n_tiles);
+    hipLaunchKernelGGL((k_proj<XT, PRE>), dim3(PRE ? 256 : n_tiles * PROJ_G), dim3(PROJ_THREADS), 0, s, d, cur, n_tiles);
     mark(4);
     return hipGetLastError();
 }

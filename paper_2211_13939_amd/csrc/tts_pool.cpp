@@ -107,7 +107,7 @@ Layout make_layout(const tts_config& c)
     l.qpart = a.take((pre_gates_for(c) ? S : 0) * (size_t)QUERY_PARTIALS * ATT * 4);
     l.pre_att = a.take((pre_gates_for(c) ? S / 16 : 0) * (size_t)(HID / 4) * 64 * 16);
     l.pre_dec = a.take((pre_gates_for(c) ? S / 16 : 0) * (size_t)(HID / 4) * 64 * 16);
-    l.proj_part_bytes = (pre_gates_for(c) ? S / 16 : 0) * (size_t)(PROJ_GROUP - 1) * 96 * 16 * 8;
+    l.proj_part_bytes = (S / 16) * (size_t)(PROJ_GROUP - 1) * 96 * 16 * 8;
     l.proj_part = a.take(l.proj_part_bytes);
     l.c_att = a.take(S * HID * 4);
     l.c_dec = a.take(S * HID * 4);
@@ -125,7 +125,7 @@ Layout make_layout(const tts_config& c)
     l.n_steps = a.take(S * 4);
     l.done = a.take(S * 4);
     l.live = a.take(MAX_POOL * 4);
-    l.proj_seq = a.take((size_t)PRESUM_MAX_TILES * PROJ_GROUP * 4);     // zeroed at creation with the counters above
+    l.proj_seq = a.take((size_t)MAX_TILES * PROJ_GROUP * 4);     // zeroed at creation with the counters above
     l.step_seq = a.take(4);
     l.lsa_x = a.take(S * ML * 8);                                       // zeroed too: no word carries a step's number yet
     l.stage = a.take(ML * ENC * 4);
@@ -324,7 +324,7 @@ extern "C" int tts_pool_create(const tts_config* cfg, const tts_weights* w, void
     d.qpart = pre_gates_for(*cfg) ? reinterpret_cast<float*>(base + l.qpart) : nullptr;
     d.pre_att = pre_gates_for(*cfg) ? reinterpret_cast<float*>(base + l.pre_att) : nullptr;
     d.pre_dec = pre_gates_for(*cfg) ? reinterpret_cast<float*>(base + l.pre_dec) : nullptr;
-    d.proj_part = pre_gates_for(*cfg) ? reinterpret_cast<unsigned long long*>(base + l.proj_part) : nullptr;
+    d.proj_part = reinterpret_cast<unsigned long long*>(base + l.proj_part);
     d.proj_seq = reinterpret_cast<unsigned*>(base + l.proj_seq);
     d.step_seq = reinterpret_cast<unsigned*>(base + l.step_seq);
     d.lsa_x = reinterpret_cast<unsigned long long*>(base + l.lsa_x);
