@@ -155,12 +155,6 @@ class GpuBackend(PoolBackend):
         return None, chunk_ids, fin_ids
 
     def retire(self, rid: int) -> None:
-        s = self.live.get(rid)
-        if s is not None and "vslot" in s:
-            self._free_slots.append(s["vslot"])
-        super().retire(rid)
-
-    def retire(self, rid: int) -> None:
         self.pool.retire(rid)
         self.live.pop(rid, None)
 

@@ -365,6 +365,27 @@ def test_wait_bound_zero_reports_an_error_and_nothing_hangs(wl8, weights_fp32, s
     other.close()
 
 
+def test_steps_beside_other_work_on_the_gpu(wl8, weights_fp32, solo_frames):
+    """The kernels of a step wait for words of partner workgroups (bounded).  With another stream keeping the CUs
+    busy a partner may start late: the frames must not change and no wait may run out."""
+    import torch
+    say("case: decoder steps while a second stream runs large matrix products")
+    pool = make_pool(wl8, weights_fp32, max_pool=8, max_enc_len=90, max_steps=24, chunk_frames=24)
+    rids = [pool.add_request(wl8.encoder_outputs(i), 24) for i in range(8)]
+    side = torch.cuda.Stream(device=pool.device)
+    a = torch.randn(4096, 4096, device=pool.device)
+    with torch.cuda.stream(side):
+        for _ in range(40):
+            a = (a @ a) * 1e-4
+    for _ in range(6):
+        pool.step_n(4)
+    pool.sync()                      # raises if a wait ran out
+    side.synchronize()
+    for i, rid in enumerate(rids):
+        np.testing.assert_array_equal(_drain(pool, rid), solo_frames[i])
+    pool.close()
+
+
 def test_c3_shrinking_pool_full_job(weights_bf16):
     """The whole c3 job as the benchmark runs it (requests retire at their own
     end): every request produces exactly its frame count, sampled requests match
