@@ -563,7 +563,7 @@ template <> struct LsaTile<bf16_t> {
 };
 
 template <typename XT, typename MT, int S, bool QP>
-__global__ __launch_bounds__(LSA_THREADS) void k_lsa(DevPtrs d, int cur)
+__global__ __launch_bounds__(LSA_THREADS) void k_lsa(DevPtrs d, int cur, int n_slots)
 {
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int jl = lane & 15, g = lane >> 4;
@@ -574,8 +574,15 @@ __global__ __launch_bounds__(LSA_THREADS) void k_lsa(DevPtrs d, int cur)
     // compiler moves loads below a branch that may leave the kernel, which would serialise them
     // behind that branch's condition.  A workgroup with nothing to do computes on whatever its
     // slot holds (all reads stay inside the slot's arrays) and writes nothing.
-    const int slot = blockIdx.x / S, sp = blockIdx.x % S;
+    // A slot's S workgroups sit on one XCD (workgroup b runs on XCD b % 8): what they all read - the query's partial
+    // products, the words they hand each other - then crosses into that XCD's L2 once.  Slots are dealt to the XCDs in
+    // eights; the grid is padded to whole eights, and a workgroup past the last slot repeats the last slot's work
+    // (every read stays inside the arrays) and stores nothing but the same words as its twin.
+    const int xcd = blockIdx.x & 7, kx = blockIdx.x >> 3;
+    const int slot_raw = (kx / S) * 8 + xcd, sp = kx % S;
+    const int slot = min(slot_raw, n_slots - 1);
     const int live_w = d.live[slot], done_w = d.done[slot], L_w = d.L[slot];
+    const bool twin = slot_raw >= n_slots;       // computes what the last slot's workgroup computes, keeps it to itself
     // the request's S workgroups share the energies (below): this step's number marks the words they exchange
     constexpr bool XCH = S > 1;
     unsigned seq = 0;
@@ -924,7 +931,7 @@ __global__ __launch_bounds__(LSA_THREADS) void k_lsa(DevPtrs d, int cur)
         }
         const XT a = from_float<XT>(c * inv);
         const int k = sp * FS + f;
-        if (active) {
+        if (active && !twin) {
             xa[xoff<XT>(K_ATT / KB, slot, XA_A + k)] = a;
             xd[xoff<XT>(K_DEC / KB, slot, XD_A + k)] = a;
         }
@@ -934,7 +941,7 @@ __global__ __launch_bounds__(LSA_THREADS) void k_lsa(DevPtrs d, int cur)
     float* wa_out = d.w_acc[cur ^ 1] + (size_t)slot * d.max_enc_len;
     for (int x = sp + S * tid; x < L; x += S * LSA_THREADS) {
         const float w = s_e[x] * inv;
-        if (active) {
+        if (active && !twin) {
             wl_out[x] = w;
             wa_out[x] = s_u[1][x + LOC_PAD] + w;
         }
@@ -1411,9 +1418,10 @@ static hipError_t step_typed(const DevPtrs& d, int n_req, int n_tiles, int lsa_s
                            d.Wa, d.ba, xatt_cur, d.c_att, xdec_cur, K_DEC / KB, XD_HA, xatt_nxt, K_ATT / KB, XA_H,
                            n_tiles, d.live, d.done, nullptr);
     mark(1);
-    if (lsa_split == 4) hipLaunchKernelGGL((k_lsa<XT, MT, 4, PRE>), dim3(n_req * 4), dim3(LSA_THREADS), 0, s, d, cur);
-    else if (lsa_split == 2) hipLaunchKernelGGL((k_lsa<XT, MT, 2, PRE>), dim3(n_req * 2), dim3(LSA_THREADS), 0, s, d, cur);
-    else hipLaunchKernelGGL((k_lsa<XT, MT, 1, PRE>), dim3(n_req), dim3(LSA_THREADS), 0, s, d, cur);
+    const int n_pad = (n_req + 7) / 8 * 8;      // slots are dealt to the XCDs in eights
+    if (lsa_split == 4) hipLaunchKernelGGL((k_lsa<XT, MT, 4, PRE>), dim3(n_pad * 4), dim3(LSA_THREADS), 0, s, d, cur, n_req);
+    else if (lsa_split == 2) hipLaunchKernelGGL((k_lsa<XT, MT, 2, PRE>), dim3(n_pad * 2), dim3(LSA_THREADS), 0, s, d, cur, n_req);
+    else hipLaunchKernelGGL((k_lsa<XT, MT, 1, PRE>), dim3(n_pad), dim3(LSA_THREADS), 0, s, d, cur, n_req);
     mark(2);
     // H_dec(t): consumed by this step's projection and the next step's decoder LSTM (same buffer)
     const uint4* xdec_in = reinterpret_cast<const uint4*>(d.xdec[cur]);
