@@ -43,7 +43,7 @@ typedef enum {
     TTS_E_NOTFOUND = -3,  /* unknown or already retired request id */
     TTS_E_HIP = -4,       /* a HIP call failed; tts_last_error() carries its text */
     TTS_E_ARENA = -5,     /* device arena too small or misaligned */
-    TTS_E_UNSUPPORTED = -6 /* dimensions outside what the kernels are built for */
+    TTS_E_UNSUPPORTED = -6 /* dimensions outside what the kernels are built for, or a device with fewer than 256 CUs */
 } tts_status;
 
 enum { TTS_DTYPE_F32 = 0, TTS_DTYPE_BF16 = 1 };

@@ -16,6 +16,10 @@ struct StepLaunch {
                     // and the attention LSTM hands the query to the attention kernel as rank-32 partial products (d.qpart)
 };
 
+// CUs the launches count on: the projection's launch of a pool with gate pre-sums has this many workgroups, one per CU,
+// and the attention kernel at most this many
+constexpr int MIN_DEVICE_CUS = 256;
+
 // pools of at most this many 16-slot tiles can run with gate pre-sums
 constexpr int PRESUM_MAX_TILES = 4;
 // such a pool's attention LSTM writes this many partial products of the attention query per slot (d.qpart)

@@ -305,6 +305,18 @@ extern "C" int tts_pool_create(const tts_config* cfg, const tts_weights* w, void
         (void)hipGetLastError();
         return fail(TTS_E_ARENA, "arena is not device memory");
     }
+    // Workgroups of one launch wait for each other's words (the projection's helpers and leader, the attention
+    // workgroups of a slot): every launch is laid out so that all its workgroups are resident at once on the 256 CUs
+    // of an MI355X, one per CU.  On a device (or partition) with fewer they would wait for partners that cannot start.
+    {
+        int n_cu = 0;
+        if (hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, attr.device) != hipSuccess) {
+            (void)hipGetLastError();
+            return fail(TTS_E_HIP, "cannot read the device's CU count");
+        }
+        if (n_cu < MIN_DEVICE_CUS)
+            return fail(TTS_E_UNSUPPORTED, "the device has %d CUs; the step kernels are laid out for %d", n_cu, MIN_DEVICE_CUS);
+    }
 
     tts_pool* p = new (std::nothrow) tts_pool();
     if (!p) return fail(TTS_E_INVAL, "out of host memory");
