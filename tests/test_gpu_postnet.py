@@ -90,6 +90,33 @@ def test_large_batch_matches_oracle(bf16):
     assert worst <= (PN_TOL_BF16_REL * scale if bf16 else TOL_F32)
 
 
+def test_very_large_batch_matches_oracle_and_small_batches():
+    """26 windows of 50 frames and a ragged one (1337 columns, 84 tiles: 21 workgroups of columns in the
+    large-batch kernel, the last one partial), bf16.  Against the oracle on every window, and against the same
+    windows in batches of nine (small enough for the other kernel, whose summation order differs)."""
+    from oracle import oracle as orc
+    ws, bs = synth.make_postnet_weights(bf16=True)
+    W = orc.PostnetWeights(ws, bs)
+    rng = np.random.default_rng(78)
+    lens = [50] * 26 + [37]
+    keeps = [10] * 26 + [3]
+    wins = [rng.standard_normal((n, 80)).astype(np.float32) for n in lens]
+    say(f"case postnet very large batch: {sum(lens)} columns, bf16")
+    ref = [orc.postnet_chunk(W, w.astype(np.float64), k) for w, k in zip(wins, keeps)]
+    pn = binding.Postnet(binding.make_postnet_config(max_columns=2048, bf16=True), ws, bs)
+    got = pn.run(wins, keeps)
+    small = []
+    for i in range(0, len(wins), 9):
+        small += pn.run(wins[i:i + 9], keeps[i:i + 9])
+    pn.close()
+    scale = max(float(np.abs(r).max()) for r in ref)
+    worst = max(float(np.abs(g - r).max()) for g, r in zip(got, ref))
+    between = max(float(np.abs(g - h).max()) for g, h in zip(got, small))
+    say(f"  max abs err {worst:.3e} (largest output {scale:.2f}); against the other kernels {between:.3e}")
+    assert worst <= PN_TOL_BF16_REL * scale
+    assert between <= PN_TOL_BF16_REL * scale
+
+
 def test_bf16_rounding_points():
     """bf16 mode rounds the input mel and every tanh output to bf16 and accumulates in fp32.  The same
     rounding points applied to the oracle's layers on the CPU must land within a few rounding flips of
