@@ -12,21 +12,24 @@ struct StepLaunch {
     int n_tiles;    // the projection grid covers 16-slot tiles 0 .. n_tiles - 1
     int lsa_split;  // workgroups per request in the attention kernel (1, 2 or 4; they split the context columns)
     int lstm_rows;  // row tiles per LSTM workgroup: 1 (all pool tiles each), 2 or 4 (1/2 or 1/4 of the pool tiles each)
-    int pre_gates;  // 1: the projection's launch also forms the next step's gate pre-sums (d.pre_att / d.pre_dec; n_tiles <= PRESUM_MAX_TILES),
-                    // and the attention LSTM hands the query to the attention kernel as rank-32 partial products (d.qpart)
+    int proj_group; // workgroups per pool tile in the projection kernel: 6, 3 or 2 (fixed per pool; with pre_gates, n_tiles * proj_group <= 32)
+    int pre_gates;  // 2: the projection's launch also forms the next step's gate pre-sums (d.pre_att / d.pre_dec; fp32: n_tiles <= PRESUM_SMALL_TILES),
+                    // 1: the attention LSTM's only (pools of more than PRESUM_SMALL_TILES tiles: d.pre_dec is null);
+                    // either way the attention LSTM hands the query to the attention kernel as rank-32 partial products (d.qpart)
 };
 
 // CUs the launches count on: the projection's launch of a pool with gate pre-sums has this many workgroups, one per CU,
 // and the attention kernel at most this many
 constexpr int MIN_DEVICE_CUS = 256;
 
-// pools of at most this many 16-slot tiles can run with gate pre-sums
-constexpr int PRESUM_MAX_TILES = 4;
+// up to this many 16-slot tiles a pre-sum workgroup holds all its pool tiles' sums at once (both dtypes); beyond, it walks
+// them with its row tiles' weights in registers (bf16 only)
+constexpr int PRESUM_SMALL_TILES = 4;
 // such a pool's attention LSTM writes this many partial products of the attention query per slot (d.qpart)
 constexpr int QUERY_PARTIALS = 32;
 // and its projection runs as this many workgroups per tile: d.proj_seq holds one sequence number for each, d.proj_part
 // the 96 x 16 partial sums of all but the first
-constexpr int PROJ_GROUP = 6;
+constexpr int PROJ_GROUP = 6;       // the largest group
 
 // One decoder step (paper Eq. 2) for every request whose slot is flagged in d.live.
 // `cur` selects which half of the double-buffered activations is read.

@@ -147,7 +147,6 @@ __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm_rc(
     XT* __restrict__ hout1, int nk1, int off1,
     int n_tiles, const int* __restrict__ live, const int* __restrict__ done, const floatx4* __restrict__ pre = nullptr)
 {
-    static_assert(!PRE || !PIPE, "pools large enough for the pipelined kernel leave no idle CUs for the pre-sums");
     constexpr int NW = LSTM_WAVES;
     constexpr int NK = K / Frag<XT>::KB;
     constexpr int NF = PRE ? lstm_main_frags<XT, K>() : NK / NW;
@@ -175,7 +174,7 @@ __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm_rc(
     if constexpr (PIPE) {
         static_assert(!PIPE || TP == 1, "the pipelined loop handles one pool tile per round");
         // one round: products of tile `tp` from `bc`, cell update of the four row tiles
-        auto round = [&](int tp, const uint4 (&bc)[NF], int lv, int dn, float c_old) {
+        auto round = [&](int tp, const uint4 (&bc)[NF], int lv, int dn, float c_old, floatx4 pre4) {
 #pragma unroll
             for (int r = 0; r < R; ++r) {
                 floatx4 acc = {0.f, 0.f, 0.f, 0.f};
@@ -189,6 +188,7 @@ __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm_rc(
                 floatx4 g = bias4;
 #pragma unroll
                 for (int w = 0; w < NW; ++w) g += red[w][wave][lane];
+                if constexpr (PRE) g += pre4;
                 const float gi = sigmoidf_(g[0]), gf = sigmoidf_(g[1]);
                 const float gg = tanhf_(g[2]), go = sigmoidf_(g[3]);
                 const float c = gf * c_old + gi * gg;
@@ -199,12 +199,13 @@ __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm_rc(
             }
             __syncthreads();
         };
-        auto fetch = [&](int tp, uint4 (&bn)[NF], int& lv, int& dn, float& c_old) {
+        auto fetch = [&](int tp, uint4 (&bn)[NF], int& lv, int& dn, float& c_old, floatx4& pre4) {
             const int t = min(tp, c1 - 1);                 // past the end: the last tile again, never used
             const int sl = t * 16 + (lane & 15);
             lv = live[sl];
             dn = done[sl];
             c_old = c_state[(size_t)sl * HID + unit];
+            if constexpr (PRE) pre4 = pre[((size_t)t * (HID / 4) + R * rg + er) * 64 + lane];
 #pragma unroll
             for (int f = 0; f < NF; ++f) bn[f] = X[xfrag(NK, t, wave + f * NW, lane)];
         };
@@ -212,15 +213,16 @@ __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm_rc(
         uint4 b0[NF], b1[NF];
         int lv0, dn0, lv1, dn1;
         float co0, co1;
-        fetch(c0, b0, lv0, dn0, co0);
+        floatx4 p0 = {0.f, 0.f, 0.f, 0.f}, p1 = {0.f, 0.f, 0.f, 0.f};
+        fetch(c0, b0, lv0, dn0, co0, p0);
         for (int tp = c0; tp < c1; tp += 2) {
-            fetch(tp + 1, b1, lv1, dn1, co1);
+            fetch(tp + 1, b1, lv1, dn1, co1, p1);
             __builtin_amdgcn_sched_barrier(0);
-            round(tp, b0, lv0, dn0, co0);
+            round(tp, b0, lv0, dn0, co0, p0);
             if (tp + 1 >= c1) break;
-            fetch(tp + 2, b0, lv0, dn0, co0);
+            fetch(tp + 2, b0, lv0, dn0, co0, p0);
             __builtin_amdgcn_sched_barrier(0);
-            round(tp + 1, b1, lv1, dn1, co1);
+            round(tp + 1, b1, lv1, dn1, co1, p1);
         }
         return;
     }
@@ -361,13 +363,15 @@ constexpr int PG_R = 3, PG_T = 2;
 constexpr int PG_CH = 2, PG_WIN = 4;
 typedef floatx4 (*PresumRed)[PG_R * PG_T][64];
 
-template <typename XT, int NR, int NT>
+// DEC: the decoder LSTM's pre-sums too (pools of at most four tiles; larger pools keep all of its K in its own kernel
+// and have no buffer for them)
+template <typename XT, int NR, int NT, bool DEC>
 __device__ __forceinline__ void gate_presums_rt(const DevPtrs& d, int nxt, int r0, int t0, PresumRed red)
 {
     constexpr int NW = LSTM_WAVES, KB = Frag<XT>::KB;
     constexpr int NK_A = K_ATT / KB, NK_D = K_DEC / KB;
     constexpr int F0_A = lstm_main_frags<XT, K_ATT>(), F0_D = lstm_main_frags<XT, K_DEC>();
-    constexpr int NA = (NK_A / NW - F0_A) / PG_CH, ND = (NK_D / NW - F0_D) / PG_CH, N = NA + ND;   // chunks
+    constexpr int NA = (NK_A / NW - F0_A) / PG_CH, ND = DEC ? (NK_D / NW - F0_D) / PG_CH : 0, N = NA + ND;   // chunks
     static_assert((NK_A / NW - F0_A) % PG_CH == 0 && (NK_D / NW - F0_D) % PG_CH == 0, "the late fragments split evenly into chunks");
     static_assert(NR * NT <= NW, "one wave adds up one (row tile, pool tile) sum");
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -431,22 +435,104 @@ __device__ __forceinline__ void gate_presums_rt(const DevPtrs& d, int nxt, int r
             clear();
         }
     }
-    finish(d.pre_dec);
+    if constexpr (DEC) finish(d.pre_dec);
 }
 
-// Both pre-sums of the next step, from the activation halves that step will read (cur ^ 1 of the step that is running),
+template <typename XT, bool DEC>
+__device__ __forceinline__ void gate_presums_sel(const DevPtrs& d, int nxt, int r0, int nr, int t0, int nt, PresumRed red)
+{
+    if (nt == 1) {
+        if (nr == 1) gate_presums_rt<XT, 1, 1, DEC>(d, nxt, r0, t0, red);
+        else if (nr == 2) gate_presums_rt<XT, 2, 1, DEC>(d, nxt, r0, t0, red);
+        else gate_presums_rt<XT, 3, 1, DEC>(d, nxt, r0, t0, red);
+    } else {
+        if (nr == 1) gate_presums_rt<XT, 1, 2, DEC>(d, nxt, r0, t0, red);
+        else if (nr == 2) gate_presums_rt<XT, 2, 2, DEC>(d, nxt, r0, t0, red);
+        else gate_presums_rt<XT, 3, 2, DEC>(d, nxt, r0, t0, red);
+    }
+}
+
+// The pre-sums of the next step, from the activation halves that step will read (cur ^ 1 of the step that is running),
 // for nr in 1 .. PG_R row tiles and nt in 1 .. PG_T pool tiles (the same for the whole workgroup).
 template <typename XT>
 __device__ __forceinline__ void gate_presums(const DevPtrs& d, int nxt, int r0, int nr, int t0, int nt, PresumRed red)
 {
-    if (nt == 1) {
-        if (nr == 1) gate_presums_rt<XT, 1, 1>(d, nxt, r0, t0, red);
-        else if (nr == 2) gate_presums_rt<XT, 2, 1>(d, nxt, r0, t0, red);
-        else gate_presums_rt<XT, 3, 1>(d, nxt, r0, t0, red);
-    } else {
-        if (nr == 1) gate_presums_rt<XT, 1, 2>(d, nxt, r0, t0, red);
-        else if (nr == 2) gate_presums_rt<XT, 2, 2>(d, nxt, r0, t0, red);
-        else gate_presums_rt<XT, 3, 2>(d, nxt, r0, t0, red);
+    if (d.pre_dec) gate_presums_sel<XT, true>(d, nxt, r0, nr, t0, nt, red);
+    else gate_presums_sel<XT, false>(d, nxt, r0, nr, t0, nt, red);
+}
+
+// Pools that span more than four tiles: a workgroup has up to PG_WALK_R row tiles and up to four pool tiles.  Its row
+// tiles' late fragments stay in registers and the pool tiles are walked one at a time, the next tile's activations
+// requested before the current tile's products (the loop of the decoder LSTM's large-pool kernel without the cell).
+// Each (row tile, pool tile) sum is formed in the same order as above.  bf16 only (fp32 fragments of five row tiles
+// do not fit the register file).
+constexpr int PG_WALK_R = 5;
+typedef floatx4 (*WalkRed)[PG_WALK_R][64];
+
+template <typename XT, int K, int NR>
+__device__ __forceinline__ void gate_presum_walk(const uint4* __restrict__ W, const uint4* __restrict__ X, floatx4* __restrict__ pre,
+                                                 int r0, int t0, int nt, WalkRed red)
+{
+    constexpr int NW = LSTM_WAVES;
+    constexpr int NK = K / Frag<XT>::KB;
+    constexpr int F0 = lstm_main_frags<XT, K>();
+    constexpr int NFP = NK / NW - F0;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    uint4 a[NR][NFP];
+#pragma unroll
+    for (int r = 0; r < NR; ++r)
+#pragma unroll
+        for (int f = 0; f < NFP; ++f) a[r][f] = W[xfrag(NK, r0 + r, wave + (F0 + f) * NW, lane)];
+    auto fetch = [&](int t, uint4 (&b)[NFP]) __attribute__((always_inline)) {
+        const int tile = t0 + min(t, nt - 1);            // past the end: the last tile again, never used
+#pragma unroll
+        for (int f = 0; f < NFP; ++f) b[f] = X[xfrag(NK, tile, wave + (F0 + f) * NW, lane)];
+    };
+    auto round = [&](int t, const uint4 (&b)[NFP]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int r = 0; r < NR; ++r) {
+            floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int f = 0; f < NFP; ++f) acc = mfma_frag<XT>(a[r][f], b[f], acc);
+            red[wave][r][lane] = acc;
+        }
+        __syncthreads();
+        if (wave < NR) {
+            floatx4 g = red[0][wave][lane];
+#pragma unroll
+            for (int w = 1; w < NW; ++w) g += red[w][wave][lane];
+            pre[((size_t)(t0 + t) * (HID / 4) + r0 + wave) * 64 + lane] = g;
+        }
+        __syncthreads();
+    };
+    uint4 b0[NFP], b1[NFP];
+    fetch(0, b0);
+    for (int t = 0; t < nt; t += 2) {
+        fetch(t + 1, b1);
+        __builtin_amdgcn_sched_barrier(0);
+        round(t, b0);
+        if (t + 1 >= nt) break;
+        fetch(t + 2, b0);
+        __builtin_amdgcn_sched_barrier(0);
+        round(t + 1, b1);
+    }
+}
+
+template <typename XT>
+__device__ __forceinline__ void gate_presums_walk(const DevPtrs& d, int nxt, int r0, int nr, int t0, int nt, WalkRed red)
+{
+    const uint4* xa = reinterpret_cast<const uint4*>(d.xatt[nxt]);
+    const uint4* xd = reinterpret_cast<const uint4*>(d.xdec[nxt]);
+    floatx4* pa = reinterpret_cast<floatx4*>(d.pre_att);
+    floatx4* pd = reinterpret_cast<floatx4*>(d.pre_dec);
+    if constexpr (sizeof(XT) == 2) {
+        switch (nr) {
+        case 1: gate_presum_walk<XT, K_ATT, 1>(d.Wa, xa, pa, r0, t0, nt, red); if (pd) gate_presum_walk<XT, K_DEC, 1>(d.Wd, xd, pd, r0, t0, nt, red); break;
+        case 2: gate_presum_walk<XT, K_ATT, 2>(d.Wa, xa, pa, r0, t0, nt, red); if (pd) gate_presum_walk<XT, K_DEC, 2>(d.Wd, xd, pd, r0, t0, nt, red); break;
+        case 3: gate_presum_walk<XT, K_ATT, 3>(d.Wa, xa, pa, r0, t0, nt, red); if (pd) gate_presum_walk<XT, K_DEC, 3>(d.Wd, xd, pd, r0, t0, nt, red); break;
+        case 4: gate_presum_walk<XT, K_ATT, 4>(d.Wa, xa, pa, r0, t0, nt, red); if (pd) gate_presum_walk<XT, K_DEC, 4>(d.Wd, xd, pd, r0, t0, nt, red); break;
+        default: gate_presum_walk<XT, K_ATT, 5>(d.Wa, xa, pa, r0, t0, nt, red); if (pd) gate_presum_walk<XT, K_DEC, 5>(d.Wd, xd, pd, r0, t0, nt, red); break;
+        }
     }
 }
 
@@ -455,7 +541,9 @@ template <typename XT>
 __global__ __launch_bounds__(LSTM_WAVES * 64) void k_presum_tile(DevPtrs d, int nxt, int tile)
 {
     __shared__ floatx4 red[LSTM_WAVES][PG_R * PG_T][64];
-    gate_presums<XT>(d, nxt, blockIdx.x, 1, tile, 1, red);
+    static_assert(PG_WALK_R <= PG_R * PG_T, "either form's reduction buffer");
+    if (d.pre_dec) gate_presums<XT>(d, nxt, blockIdx.x, 1, tile, 1, red);
+    else gate_presums_walk<XT>(d, nxt, blockIdx.x, 1, tile, 1, reinterpret_cast<WalkRed>(&red[0][0][0]));   // the attention LSTM's only
 }
 
 // ---------------------------------------------------------------------------
@@ -957,7 +1045,7 @@ __global__ __launch_bounds__(LSA_THREADS) void k_lsa(DevPtrs d, int cur, int n_s
 //   p^T   (256 x 16) = relu(W_p2 * hid^T)
 // What bounds it is the weights that pass through one CU (475 KB in bf16 at 60 - 85 GB/s).  Pools without gate
 // pre-sums run one workgroup per tile.  With pre-sums the launch fills the chip anyway and XCD 0 is reserved for the
-// projection, so a tile gets PROJ_G workgroups there that split the K of the first product: the helpers store their
+// projection, so a tile gets G workgroups there (six, or fewer in pools of many tiles) that split the K of the first product: the helpers store their
 // 96 x 16 partial sums and raise a sequence number each, the leader (which meanwhile pulls the prenet weights) waits
 // for those numbers, adds the partials in helper order and goes on alone.  The wait is bounded: a leader that gives
 // up raises d.fault and finishes with whatever it has, so the grid always drains.
@@ -965,9 +1053,7 @@ __global__ __launch_bounds__(LSA_THREADS) void k_lsa(DevPtrs d, int cur, int n_s
 constexpr int PROJ_THREADS = 512;
 constexpr int PROJ_WAVES = PROJ_THREADS / 64;
 constexpr int PROJ_ROWS = 96;
-constexpr int PROJ_G = 6;                        // workgroups per pool tile in pools with gate pre-sums
 constexpr int PROJ_MEL_LD = PROJ_ROWS + 4, PROJ_HID_LD = PRENET + 4;
-static_assert(PROJ_G == PROJ_GROUP, "the arena holds PROJ_GROUP sequence numbers and PROJ_GROUP - 1 partial sums per tile");
 
 template <typename XT> struct PrenetK1 { static constexpr int value = 80; };
 template <> struct PrenetK1<bf16_t> { static constexpr int value = 96; };
@@ -1229,7 +1315,8 @@ __device__ __forceinline__ void proj_tile(const DevPtrs& d, int cur, int tile, i
     }
 }
 
-template <typename XT, bool PRE>
+// G: workgroups per pool tile (fixed per pool: it sets the order in which the mel projection is summed)
+template <typename XT, bool PRE, int G>
 __global__ __launch_bounds__(PROJ_THREADS) void k_proj(DevPtrs d, int cur, int n_tiles)
 {
     __shared__ __attribute__((aligned(16))) float s_big[PROJ_WAVES * PROJ_ROWS * 16];
@@ -1241,37 +1328,48 @@ __global__ __launch_bounds__(PROJ_THREADS) void k_proj(DevPtrs d, int cur, int n
 
     if constexpr (PRE) {
         // The launch has 256 workgroups, one per CU; workgroup b runs on XCD b % 8.  XCD 0 holds the projection's own
-        // workgroups (b = 8 * (PROJ_G * tile + part)) and is otherwise left idle: beside workgroups that stream at full
+        // workgroups (b = 8 * (G * tile + part)) and is otherwise left idle: beside workgroups that stream at full
         // rate, the projection's loads took a quarter longer.  The other seven XCDs form the next step's gate pre-sums:
         // XCD x takes row tiles 256 (x - 1) / 7 .. 256 x / 7 of both matrices (every weight is fetched from HBM once),
-        // its 32 workgroups split into one or two groups by pool tiles (two from three tiles on: 32 x 32 is the shape
-        // that moves the fewest bytes through a CU), and a group's workgroups share the XCD's 36 or 37 row tiles
-        // evenly: two or three each (one or two without the split).
+        // its 32 workgroups split into groups by pool tiles and a group's workgroups share the XCD's 36 or 37 row tiles
+        // evenly.  Up to four tiles: one or two groups (two from three tiles on: 32 x 32 is the shape that moves the
+        // fewest bytes through a CU), two or three row tiles each (one or two without the split).  Above: groups of at
+        // most four tiles, two to five row tiles each, the tiles walked one at a time.
         const int x = blockIdx.x & 7, i = blockIdx.x >> 3;
         if (x != 0) {
             static_assert(sizeof(floatx4) * LSTM_WAVES * PG_R * PG_T * 64 <= sizeof(s_big), "the reduction buffer aliases the partial sums");
+            static_assert(sizeof(floatx4) * LSTM_WAVES * PG_WALK_R * 64 <= sizeof(s_big), "the reduction buffer aliases the partial sums");
             static_assert(PROJ_WAVES == LSTM_WAVES, "the pre-sums split K over eight waves");
             const int rx0 = (HID / 4) * (x - 1) / 7, rx1 = (HID / 4) * x / 7;
-            int k = i, Mc = 32, t0 = 0, nt = n_tiles;
-            if (n_tiles > 2) {
-                const int per = (n_tiles + 1) / 2;
-                Mc = 16;
-                if (k < 16) nt = per;
-                else { k -= 16; t0 = per; nt = n_tiles - per; }
+            if (n_tiles <= 4) {
+                int k = i, Mc = 32, t0 = 0, nt = n_tiles;
+                if (n_tiles > 2) {
+                    const int per = (n_tiles + 1) / 2;
+                    Mc = 16;
+                    if (k < 16) nt = per;
+                    else { k -= 16; t0 = per; nt = n_tiles - per; }
+                }
+                const int lo = rx0 + (rx1 - rx0) * k / Mc, hi = rx0 + (rx1 - rx0) * (k + 1) / Mc;
+                gate_presums<XT>(d, cur ^ 1, lo, hi - lo, t0, nt, reinterpret_cast<PresumRed>(s_big));
+            } else {
+                const int CG = (n_tiles + 3) / 4, Mc = 32 / CG;          // 2, 3 or 4 groups of 16, 10 or 8 workgroups
+                const int cg = i / Mc, k = i - cg * Mc;
+                if (cg >= CG) return;                                     // 32 = 3 * 10 + 2: two workgroups stay idle
+                const int per = (n_tiles + CG - 1) / CG, t0 = cg * per;
+                const int nt = min(per, n_tiles - t0);
+                const int lo = rx0 + (rx1 - rx0) * k / Mc, hi = rx0 + (rx1 - rx0) * (k + 1) / Mc;
+                if (nt > 0) gate_presums_walk<XT>(d, cur ^ 1, lo, hi - lo, t0, nt, reinterpret_cast<WalkRed>(s_big));
             }
-            const int lo = rx0 + (rx1 - rx0) * k / Mc, hi = rx0 + (rx1 - rx0) * (k + 1) / Mc;
-            gate_presums<XT>(d, cur ^ 1, lo, hi - lo, t0, nt, reinterpret_cast<PresumRed>(s_big));
             return;
         }
-        static_assert(PROJ_G * PRESUM_MAX_TILES <= 32, "the projection's workgroups fit XCD 0");
-        if (i >= n_tiles * PROJ_G) return;
-        if (i % PROJ_G == 0) proj_tile<XT, PROJ_G, true>(d, cur, i / PROJ_G, 0, sh);
-        else proj_tile<XT, PROJ_G, false>(d, cur, i / PROJ_G, i % PROJ_G, sh);
+        if (i >= n_tiles * G) return;
+        if (i % G == 0) proj_tile<XT, G, true>(d, cur, i / G, 0, sh);
+        else proj_tile<XT, G, false>(d, cur, i / G, i % G, sh);
     } else {
-        // larger pools: the same six workgroups per tile, wherever they land (n_tiles * PROJ_G <= 96 workgroups)
+        // without pre-sums: the same workgroups per tile, wherever they land (n_tiles * G <= 96 workgroups)
         const int i = blockIdx.x;
-        if (i % PROJ_G == 0) proj_tile<XT, PROJ_G, true>(d, cur, i / PROJ_G, 0, sh);
-        else proj_tile<XT, PROJ_G, false>(d, cur, i / PROJ_G, i % PROJ_G, sh);
+        if (i % G == 0) proj_tile<XT, G, true>(d, cur, i / G, 0, sh);
+        else proj_tile<XT, G, false>(d, cur, i / G, i % G, sh);
     }
 }
 
@@ -1342,7 +1440,7 @@ __global__ __launch_bounds__(256) void k_slot_init(DevPtrs d, int slot, int L, i
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
             pa[16 * g] = z4;
-            pd[16 * g] = z4;
+            if (d.pre_dec) pd[16 * g] = z4;
         }
     }
     if (tid == 0) {
@@ -1386,8 +1484,9 @@ __global__ __launch_bounds__(256) void k_x_set(XT* X, int NK, int slot, int off,
 // ---------------------------------------------------------------------------
 // launch wrappers
 // ---------------------------------------------------------------------------
-template <typename XT, typename MT, bool PRE>
-static hipError_t step_typed(const DevPtrs& d, int n_req, int n_tiles, int lsa_split, int rows, int cur, hipStream_t s, hipEvent_t* ev)
+// PM: 0 = no gate pre-sums, 1 = the attention LSTM's only (pools of more than four tiles), 2 = both LSTMs'
+template <typename XT, typename MT, int PM>
+static hipError_t step_typed(const DevPtrs& d, int n_req, int n_tiles, int lsa_split, int rows, int proj_group, int cur, hipStream_t s, hipEvent_t* ev)
 {
     constexpr int KB = Frag<XT>::KB;
     auto mark = [&](int i) { if (ev) (void)hipEventRecord(ev[i], s); };
@@ -1396,9 +1495,12 @@ static hipError_t step_typed(const DevPtrs& d, int n_req, int n_tiles, int lsa_s
     XT* xdec_cur = reinterpret_cast<XT*>(d.xdec[cur]);
     XT* xdec_nxt = reinterpret_cast<XT*>(d.xdec[cur ^ 1]);
     mark(0);
+    constexpr bool PRE = PM != 0, PRE_DEC = PM == 2;
     constexpr bool HAS_WIDE = sizeof(XT) == 2;     // the fp32 fragments of several row tiles do not fit the register file
     if (!HAS_WIDE) rows = 1;
-    if (PRE && rows > 2) return hipErrorInvalidValue;   // pools with pre-sums span at most four tiles
+    // pre-sums beyond four tiles need the several-row-tile kernels (bf16)
+    if (PRE && !HAS_WIDE && n_tiles > PRESUM_SMALL_TILES) return hipErrorInvalidValue;
+    if (PRE && n_tiles * proj_group > 32) return hipErrorInvalidValue;   // the projection's workgroups must fit XCD 0
     const dim3 lg(HID / 4), lb(LSTM_WAVES * 64);
     // H_att(t): consumed by this step's decoder LSTM / attention and by the next step's attention LSTM.
     // With pre-sums: the tall kernel, which also hands the query over as partial products.
@@ -1427,19 +1529,24 @@ static hipError_t step_typed(const DevPtrs& d, int n_req, int n_tiles, int lsa_s
     const uint4* xdec_in = reinterpret_cast<const uint4*>(d.xdec[cur]);
     const floatx4* pre_dec = reinterpret_cast<const floatx4*>(d.pre_dec);
     if (rows == 4) {
-        if constexpr (HAS_WIDE && !PRE)
-            hipLaunchKernelGGL((k_lstm_rc<XT, K_DEC, 4>), lg, lb, 0, s, d.Wd, d.bd, xdec_in, d.c_dec, xdec_nxt, K_DEC / KB, XD_HD,
-                               xdec_nxt, K_DEC / KB, XD_HD, n_tiles, d.live, d.done, nullptr);
+        if constexpr (HAS_WIDE)
+            // (with pre-sums the decoder LSTM's K = 1536 leaves registers for the pipelined form)
+            hipLaunchKernelGGL((k_lstm_rc<XT, K_DEC, 4, PRE_DEC, PRE_DEC>), lg, lb, 0, s, d.Wd, d.bd, xdec_in, d.c_dec, xdec_nxt, K_DEC / KB, XD_HD,
+                               xdec_nxt, K_DEC / KB, XD_HD, n_tiles, d.live, d.done, pre_dec);
     } else if (rows == 2) {
         if constexpr (HAS_WIDE)
-            hipLaunchKernelGGL((k_lstm_rc<XT, K_DEC, 2, false, PRE>), lg, lb, 0, s, d.Wd, d.bd, xdec_in, d.c_dec, xdec_nxt, K_DEC / KB, XD_HD,
+            hipLaunchKernelGGL((k_lstm_rc<XT, K_DEC, 2, false, PRE_DEC>), lg, lb, 0, s, d.Wd, d.bd, xdec_in, d.c_dec, xdec_nxt, K_DEC / KB, XD_HD,
                                xdec_nxt, K_DEC / KB, XD_HD, n_tiles, d.live, d.done, pre_dec);
     } else
-        hipLaunchKernelGGL((k_lstm<XT, K_DEC, PRE>), lg, lb, 0, s, d.Wd, d.bd, xdec_in, d.c_dec, xdec_nxt, K_DEC / KB, XD_HD,
+        hipLaunchKernelGGL((k_lstm<XT, K_DEC, PRE_DEC>), lg, lb, 0, s, d.Wd, d.bd, xdec_in, d.c_dec, xdec_nxt, K_DEC / KB, XD_HD,
                            xdec_nxt, K_DEC / KB, XD_HD, n_tiles, d.live, d.done, pre_dec);
     mark(3);
     // with pre-sums the projection's launch fills the chip: XCD 0 runs the projection, the rest form the pre-sums
-    hipLaunchKernelGGL((k_proj<XT, PRE>), dim3(PRE ? 256 : n_tiles * PROJ_G), dim3(PROJ_THREADS), 0, s, d, cur, n_tiles);
+    const dim3 pg(PRE ? 256 : n_tiles * proj_group), pb(PROJ_THREADS);
+    if (proj_group == 6) hipLaunchKernelGGL((k_proj<XT, PRE, 6>), pg, pb, 0, s, d, cur, n_tiles);
+    else if (proj_group == 3) hipLaunchKernelGGL((k_proj<XT, PRE, 3>), pg, pb, 0, s, d, cur, n_tiles);
+    else if (proj_group == 2) hipLaunchKernelGGL((k_proj<XT, PRE, 2>), pg, pb, 0, s, d, cur, n_tiles);
+    else return hipErrorInvalidValue;
     mark(4);
     return hipGetLastError();
 }
@@ -1448,16 +1555,21 @@ hipError_t launch_step(const DevPtrs& d, const StepLaunch& cfg, int cur, hipStre
 {
     if (cfg.n_blocks < 1 || cfg.n_tiles < 1) return hipSuccess;
     if (cfg.pre_gates) {
-        // the pre-sum workgroups are laid out for at most four pool tiles, and the buffers must be there
-        if (cfg.n_tiles > PRESUM_MAX_TILES || !d.pre_att || !d.pre_dec || !d.qpart) return hipErrorInvalidValue;
-        if (cfg.wdtype == 0 && cfg.mdtype == 0) return step_typed<float, float, true>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cfg.lstm_rows, cur, s, ev);
-        if (cfg.wdtype == 1 && cfg.mdtype == 1) return step_typed<bf16_t, bf16_t, true>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cfg.lstm_rows, cur, s, ev);
-        if (cfg.wdtype == 1 && cfg.mdtype == 0) return step_typed<bf16_t, float, true>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cfg.lstm_rows, cur, s, ev);
+        if (cfg.n_tiles > MAX_TILES || !d.pre_att || !d.qpart || (cfg.pre_gates == 2) != (d.pre_dec != nullptr)) return hipErrorInvalidValue;
+        if (cfg.pre_gates == 1) {
+            if (cfg.wdtype == 1 && cfg.mdtype == 1) return step_typed<bf16_t, bf16_t, 1>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cfg.lstm_rows, cfg.proj_group, cur, s, ev);
+            if (cfg.wdtype == 1 && cfg.mdtype == 0) return step_typed<bf16_t, float, 1>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cfg.lstm_rows, cfg.proj_group, cur, s, ev);
+            return hipErrorInvalidValue;
+        }
+        if (cfg.n_tiles > PRESUM_SMALL_TILES) return hipErrorInvalidValue;
+        if (cfg.wdtype == 0 && cfg.mdtype == 0) return step_typed<float, float, 2>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cfg.lstm_rows, cfg.proj_group, cur, s, ev);
+        if (cfg.wdtype == 1 && cfg.mdtype == 1) return step_typed<bf16_t, bf16_t, 2>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cfg.lstm_rows, cfg.proj_group, cur, s, ev);
+        if (cfg.wdtype == 1 && cfg.mdtype == 0) return step_typed<bf16_t, float, 2>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cfg.lstm_rows, cfg.proj_group, cur, s, ev);
         return hipErrorInvalidValue;
     }
-    if (cfg.wdtype == 0 && cfg.mdtype == 0) return step_typed<float, float, false>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cfg.lstm_rows, cur, s, ev);
-    if (cfg.wdtype == 1 && cfg.mdtype == 1) return step_typed<bf16_t, bf16_t, false>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cfg.lstm_rows, cur, s, ev);
-    if (cfg.wdtype == 1 && cfg.mdtype == 0) return step_typed<bf16_t, float, false>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cfg.lstm_rows, cur, s, ev);
+    if (cfg.wdtype == 0 && cfg.mdtype == 0) return step_typed<float, float, 0>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cfg.lstm_rows, cfg.proj_group, cur, s, ev);
+    if (cfg.wdtype == 1 && cfg.mdtype == 1) return step_typed<bf16_t, bf16_t, 0>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cfg.lstm_rows, cfg.proj_group, cur, s, ev);
+    if (cfg.wdtype == 1 && cfg.mdtype == 0) return step_typed<bf16_t, float, 0>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cfg.lstm_rows, cfg.proj_group, cur, s, ev);
     return hipErrorInvalidValue;
 }
 
@@ -1483,7 +1595,7 @@ hipError_t launch_join_memory(const DevPtrs& d, int mdtype, const float* F_dev, 
 
 hipError_t launch_presum_tile(const DevPtrs& d, int wdtype, int tile, int nxt, hipStream_t s)
 {
-    if (!d.pre_att || !d.pre_dec || tile < 0 || tile >= PRESUM_MAX_TILES) return hipErrorInvalidValue;
+    if (!d.pre_att || tile < 0 || tile >= MAX_TILES) return hipErrorInvalidValue;
     if (wdtype == 0) hipLaunchKernelGGL((k_presum_tile<float>), dim3(HID / 4), dim3(LSTM_WAVES * 64), 0, s, d, nxt, tile);
     else hipLaunchKernelGGL((k_presum_tile<bf16_t>), dim3(HID / 4), dim3(LSTM_WAVES * 64), 0, s, d, nxt, tile);
     return hipGetLastError();

@@ -71,13 +71,29 @@ struct Layout {
     size_t total, proj_part_bytes;
 };
 
+// measured per pool size: see the design notes
+static bool pre_gates_large() { return true; }
+
 // Gate pre-sums: pools of at most PRESUM_MAX_TILES tiles leave all but a few CUs idle during the projection kernel,
 // whose launch then also contracts what the next step's two LSTMs already have of their inputs ([A; H_att] and H_dec).
 // The attention LSTM, left with K = 256, then runs as tall tiles and hands the attention query over as 32 rank-32
 // partial products per slot (16 KB) instead of the attention kernel pulling W_q (256 KB in bf16) through each of its
 // CUs.  Fixed per pool (it changes the order in which gates and query are summed): a request's bits do not depend on
 // what else the pool holds.
-bool pre_gates_for(const tts_config& c) { return (c.max_pool + 15) / 16 <= PRESUM_MAX_TILES; }
+bool pre_gates_for(const tts_config& c)
+{
+    return (c.max_pool + 15) / 16 <= PRESUM_SMALL_TILES || (c.weight_dtype == TTS_DTYPE_BF16 && pre_gates_large());
+}
+// the decoder LSTM's pre-sum too: only where the pre-sum workgroups still finish in the projection's shadow (beyond four
+// tiles it saved the decoder LSTM 1.8 us and kept the projection's launch 5 us longer)
+bool pre_dec_for(const tts_config& c) { return pre_gates_for(c) && (c.max_pool + 15) / 16 <= PRESUM_SMALL_TILES; }
+// workgroups per pool tile in the projection kernel: with pre-sums they must fit XCD 0 (32 CUs)
+int proj_group_for(const tts_config& c)
+{
+    const int tiles = (c.max_pool + 15) / 16;
+    if (!pre_gates_for(c) || tiles <= 5) return 6;
+    return tiles <= 10 ? 3 : 2;
+}
 
 Layout make_layout(const tts_config& c)
 {
@@ -106,7 +122,7 @@ Layout make_layout(const tts_config& c)
     }
     l.qpart = a.take((pre_gates_for(c) ? S : 0) * (size_t)QUERY_PARTIALS * ATT * 4);
     l.pre_att = a.take((pre_gates_for(c) ? S / 16 : 0) * (size_t)(HID / 4) * 64 * 16);
-    l.pre_dec = a.take((pre_gates_for(c) ? S / 16 : 0) * (size_t)(HID / 4) * 64 * 16);
+    l.pre_dec = a.take((pre_dec_for(c) ? S / 16 : 0) * (size_t)(HID / 4) * 64 * 16);
     l.proj_part_bytes = (S / 16) * (size_t)(PROJ_GROUP - 1) * 96 * 16 * 8;
     l.proj_part = a.take(l.proj_part_bytes);
     l.c_att = a.take(S * HID * 4);
@@ -335,7 +351,7 @@ extern "C" int tts_pool_create(const tts_config* cfg, const tts_weights* w, void
     d.Wq_epi = reinterpret_cast<const float*>(base + l.Wq_epi);
     d.qpart = pre_gates_for(*cfg) ? reinterpret_cast<float*>(base + l.qpart) : nullptr;
     d.pre_att = pre_gates_for(*cfg) ? reinterpret_cast<float*>(base + l.pre_att) : nullptr;
-    d.pre_dec = pre_gates_for(*cfg) ? reinterpret_cast<float*>(base + l.pre_dec) : nullptr;
+    d.pre_dec = pre_dec_for(*cfg) ? reinterpret_cast<float*>(base + l.pre_dec) : nullptr;
     d.proj_part = reinterpret_cast<unsigned long long*>(base + l.proj_part);
     d.proj_seq = reinterpret_cast<unsigned*>(base + l.proj_seq);
     d.step_seq = reinterpret_cast<unsigned*>(base + l.step_seq);
@@ -497,7 +513,8 @@ static void shape_for(const tts_pool* p, int span, StepLaunch* sl)
     sl->n_tiles = (span + 15) / 16;
     sl->lsa_split = lsa_split_for(span);
     sl->lstm_rows = lstm_rows_for(span);
-    sl->pre_gates = pre_gates_for(p->cfg) ? 1 : 0;
+    sl->pre_gates = !pre_gates_for(p->cfg) ? 0 : (pre_dec_for(p->cfg) ? 2 : 1);
+    sl->proj_group = proj_group_for(p->cfg);
 }
 
 // Queue `nsteps` consecutive steps for the current membership.  With graphs the
@@ -857,7 +874,7 @@ extern "C" int tts_pool_set_state(tts_pool* p, int64_t id, int which, const floa
     }
     if (which == TTS_STATE_M_LAST) HIP_TRY(launch_prenet_slot(p->d, p->cfg.weight_dtype, slot, p->stream));
     // the next step's gate pre-sums were formed from the old state: redo the slot's tile from the half that step reads
-    if (pre_gates_for(p->cfg) && (which == TTS_STATE_A || which == TTS_STATE_H_ATT || which == TTS_STATE_H_DEC))
+    if (pre_gates_for(p->cfg) && (which == TTS_STATE_A || which == TTS_STATE_H_ATT || (which == TTS_STATE_H_DEC && pre_dec_for(p->cfg))))
         HIP_TRY(launch_presum_tile(p->d, p->cfg.weight_dtype, slot >> 4, p->parity, p->stream));
     HIP_TRY(hipStreamSynchronize(p->stream));
     return TTS_OK;

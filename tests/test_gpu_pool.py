@@ -292,12 +292,16 @@ def test_small_and_large_capacity_pools_agree(wl8, weights_fp32, solo_frames):
         assert np.abs(big[i, :n] - solo_frames[i]).max() <= 1e-5
 
 
-@pytest.mark.parametrize("bf16,max_pool,n_req", [(True, 32, 24), (True, 48, 40), (False, 48, 36), (False, 64, 52)])
+@pytest.mark.parametrize("bf16,max_pool,n_req", [(True, 32, 24), (True, 48, 40), (False, 48, 36), (False, 64, 52),
+                                                  (True, 96, 90), (True, 128, 120), (True, 176, 170)])
 def test_pools_of_several_tiles_with_gate_presums(bf16, max_pool, n_req, weights_bf16, weights_fp32):
     """Pools of two to four tiles: the pre-sum workgroups split by pool tiles (one group up to two
-    tiles, two groups of 2 + 1 or 2 + 2 tiles above) and take one to three row tiles each.  Against the
-    oracle on a sample, and a request's bits do not depend on the pool's composition (alone in slot 0
-    vs among all, vs among 5 joining in another order)."""
+    tiles, two groups of 2 + 1 or 2 + 2 tiles above) and take one to three row tiles each.  bf16 pools of
+    more tiles pre-sum the attention LSTM's late columns only, in groups of at most four tiles walked one
+    at a time (6 tiles: two groups; 8: two; 11: three, with two idle workgroups per XCD), and their
+    projection runs as three or two workgroups per tile.  Against the oracle on a sample, and a request's
+    bits do not depend on the pool's composition (alone in slot 0 vs among all, vs among 5 joining in
+    another order: the same sums whether the pool spans one tile or eleven)."""
     weights = weights_bf16 if bf16 else weights_fp32
     wl = synth.small_workload(n_req, 10, 120, 30, 30, seed=71, bf16=bf16)
     say(f"case capacity {max_pool}, {'bf16' if bf16 else 'fp32'}: {n_req} requests, 30 steps")
@@ -313,15 +317,19 @@ def test_pools_of_several_tiles_with_gate_presums(bf16, max_pool, n_req, weights
     np.testing.assert_array_equal(few[4], full[0])
 
 
-def test_state_overwrite_refreshes_the_gate_presums(wl8, weights_fp32):
+@pytest.mark.parametrize("bf16,max_pool", [(False, 20), (True, 200)])
+def test_state_overwrite_refreshes_the_gate_presums(bf16, max_pool, weights_bf16, weights_fp32):
     """A request's H_att, A and H_dec are overwritten between steps with another request's: the
     pre-sums formed from the old state during the last projection must not reach the next step.
     Two pools run the same request; in the second its recurrent state is first replaced by
-    garbage, then by the first pool's: the following frames are identical."""
-    say("case: set_state between steps in a pool with gate pre-sums")
+    garbage, then by the first pool's: the following frames are identical.  (Capacity 200, bf16: the
+    pool keeps pre-sums of the attention LSTM only.)"""
+    say(f"case: set_state between steps in a pool with gate pre-sums, capacity {max_pool}")
+    wl8 = synth.small_workload(8, 5, 90, 24, 24, seed=11, bf16=bf16)
+    weights_fp32 = weights_bf16 if bf16 else weights_fp32
     pools, rids = [], []
     for k in range(2):
-        pool = make_pool(wl8, weights_fp32, max_pool=20, max_enc_len=int(wl8.enc_len.max()), max_steps=24, chunk_frames=24)
+        pool = make_pool(wl8, weights_fp32, max_pool=max_pool, max_enc_len=int(wl8.enc_len.max()), max_steps=24, chunk_frames=24)
         # the neighbour in the same tile keeps its own state (its pre-sums are formed again with the tile's)
         ids = [pool.add_request(wl8.encoder_outputs(i), 24) for i in (2, 5)]
         pool.step_n(7)
