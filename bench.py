@@ -29,23 +29,25 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 
 
-PRESUM_MAX_POOL = 64   # pools of up to four 16-slot tiles run with gate pre-sums (tts_pool.cpp: pre_gates_for)
+PRESUM_BOTH_MAX_POOL = 64   # pools of up to four 16-slot tiles pre-sum both LSTMs' late columns (tts_pool.cpp: pre_dec_for)
 
 
 def algorithmic_bytes(P, sum_L, s_w, s_m, pre_gates=None):
     """Bytes one step must move, per kernel, for P requests with sum_L encoder
     positions: every step weight once, each request's processed memory and
     encoder output once, carried state read and written, mel written.  The sum
-    does not depend on `pre_gates`; the split does: pools with gate pre-sums
-    move the gate matrices' columns for [A; H_att] (attention LSTM) and H_dec
-    (decoder LSTM) in the projection kernel's launch, and W_q in the attention
-    LSTM's.  (The pre-sums and query partials themselves, written by one kernel
-    and read by the next, are traffic of the implementation, not of the
-    algorithm, and are not counted.)"""
+    does not depend on `pre_gates`; the split does.  pre_gates = 2 (pools of at
+    most 64 slots): the gate matrices' columns for [A; H_att] (attention LSTM)
+    and H_dec (decoder LSTM) move in the projection kernel's launch, and W_q in
+    the attention LSTM's; 1 (larger bf16 pools): the attention LSTM's only;
+    0 (larger fp32 pools): none.  (The pre-sums and query partials themselves,
+    written by one kernel and read by the next, are traffic of the
+    implementation, not of the algorithm, and are not counted.)"""
     if pre_gates is None:
-        pre_gates = P <= PRESUM_MAX_POOL
+        pre_gates = 2 if P <= PRESUM_BOTH_MAX_POOL else (1 if s_w == 2 else 0)
     st = 4  # carried state counted in fp32: read + write
-    k_att_late, k_dec_late = (512 + 1024, 1024) if pre_gates else (0, 0)
+    k_att_late = 512 + 1024 if pre_gates else 0
+    k_dec_late = 1024 if pre_gates == 2 else 0
     w_q = 128 * 1024 * s_w
     lsa_w = (32 * 2 * 31 + 128 * 32 + 128) * 4
     proj_w = (81 * 1536 + 80 * 256 + 256 * 256) * s_w + 81 * 4

@@ -179,8 +179,8 @@ int tts_pool_size(const tts_pool *pool);
 int tts_pool_n_active(const tts_pool *pool);
 
 /* Wait until everything queued on the pool's stream has run.
- * In pools of at most 64 slots the projection of a step is shared by several workgroups that wait for each
- * other's partial sums a bounded number of polls; should such a wait ever run out (the GPU so oversubscribed by
+ * Workgroups of one launch hand each other words (the projection's partial sums, the attention energies of a
+ * request) and wait for them a bounded number of polls; should such a wait ever run out (the GPU so oversubscribed by
  * other work that a partner is not scheduled for a quarter of a second), the kernels still finish, the frames
  * produced since are invalid, and this call and tts_pool_drain_chunk return TTS_E_HIP from then on. */
 int tts_pool_sync(tts_pool *pool);

@@ -138,9 +138,7 @@ __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm(
 // against 1 + tiles for the one-row-tile kernel.  R = 2 is the minimum at 4 tiles, R = 4 at 16.  The
 // workgroups that share rows sit on the same XCD (their blockIdx differ by a multiple of 64), so the
 // repeated reads of the weights hit that XCD's L2.  The sums are taken in the same order as in k_lstm.
-// PIPE (R = 4, one pool tile per round): the activations of the next tile are requested before the
-// products of the current one, two tiles per trip through the loop so that both buffers stay in registers.
-template <typename XT, int K, int R, bool PIPE = false, bool PRE = false>
+template <typename XT, int K, int R, bool PRE = false>
 __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm_rc(
     const uint4* __restrict__ Wfrag, const float* __restrict__ bias, const uint4* __restrict__ X,
     float* __restrict__ c_state, XT* __restrict__ hout0, int nk0, int off0,
@@ -171,62 +169,6 @@ __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm_rc(
     const int unit = (R * rg + er) * 4 + (lane >> 4);
     floatx4 bias4 = {0.f, 0.f, 0.f, 0.f};
     if (wave < 4) bias4 = *reinterpret_cast<const floatx4*>(bias + unit * 4);
-    if constexpr (PIPE) {
-        static_assert(!PIPE || TP == 1, "the pipelined loop handles one pool tile per round");
-        // one round: products of tile `tp` from `bc`, cell update of the four row tiles
-        auto round = [&](int tp, const uint4 (&bc)[NF], int lv, int dn, float c_old, floatx4 pre4) {
-#pragma unroll
-            for (int r = 0; r < R; ++r) {
-                floatx4 acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int f = 0; f < NF; ++f) acc = mfma_frag<XT>(a[r][f], bc[f], acc);
-                red[wave][r][lane] = acc;
-            }
-            __syncthreads();
-            const int sl = tp * 16 + (lane & 15);
-            if (wave < 4 && lv && !dn) {
-                floatx4 g = bias4;
-#pragma unroll
-                for (int w = 0; w < NW; ++w) g += red[w][wave][lane];
-                if constexpr (PRE) g += pre4;
-                const float gi = sigmoidf_(g[0]), gf = sigmoidf_(g[1]);
-                const float gg = tanhf_(g[2]), go = sigmoidf_(g[3]);
-                const float c = gf * c_old + gi * gg;
-                c_state[(size_t)sl * HID + unit] = c;
-                const XT h = from_float<XT>(go * tanhf_(c));
-                hout0[xoff<XT>(nk0, sl, off0 + unit)] = h;
-                hout1[xoff<XT>(nk1, sl, off1 + unit)] = h;
-            }
-            __syncthreads();
-        };
-        auto fetch = [&](int tp, uint4 (&bn)[NF], int& lv, int& dn, float& c_old, floatx4& pre4) {
-            const int t = min(tp, c1 - 1);                 // past the end: the last tile again, never used
-            const int sl = t * 16 + (lane & 15);
-            lv = live[sl];
-            dn = done[sl];
-            c_old = c_state[(size_t)sl * HID + unit];
-            if constexpr (PRE) pre4 = pre[((size_t)t * (HID / 4) + R * rg + er) * 64 + lane];
-#pragma unroll
-            for (int f = 0; f < NF; ++f) bn[f] = X[xfrag(NK, t, wave + f * NW, lane)];
-        };
-        if (c0 >= c1) return;
-        uint4 b0[NF], b1[NF];
-        int lv0, dn0, lv1, dn1;
-        float co0, co1;
-        floatx4 p0 = {0.f, 0.f, 0.f, 0.f}, p1 = {0.f, 0.f, 0.f, 0.f};
-        fetch(c0, b0, lv0, dn0, co0, p0);
-        for (int tp = c0; tp < c1; tp += 2) {
-            fetch(tp + 1, b1, lv1, dn1, co1, p1);
-            __builtin_amdgcn_sched_barrier(0);
-            round(tp, b0, lv0, dn0, co0, p0);
-            if (tp + 1 >= c1) break;
-            fetch(tp + 2, b0, lv0, dn0, co0, p0);
-            __builtin_amdgcn_sched_barrier(0);
-            round(tp + 1, b1, lv1, dn1, co1, p1);
-        }
-        return;
-    }
-
     for (int tp = c0; tp < c1; tp += TP) {
         // cell update inputs: independent, unconditional loads (see k_lstm)
         const int sl = min(tp + et, c1 - 1) * 16 + (lane & 15);
@@ -1501,24 +1443,19 @@ static hipError_t step_typed(const DevPtrs& d, int n_req, int n_tiles, int lsa_s
     // pre-sums beyond four tiles need the several-row-tile kernels (bf16)
     if (PRE && !HAS_WIDE && n_tiles > PRESUM_SMALL_TILES) return hipErrorInvalidValue;
     if (PRE && n_tiles * proj_group > 32) return hipErrorInvalidValue;   // the projection's workgroups must fit XCD 0
+    if (PRE_DEC && rows > 2) return hipErrorInvalidValue;                // both pre-sums: at most four tiles
     const dim3 lg(HID / 4), lb(LSTM_WAVES * 64);
     // H_att(t): consumed by this step's decoder LSTM / attention and by the next step's attention LSTM.
-    // With pre-sums: the tall kernel, which also hands the query over as partial products.
+    // With pre-sums: the tall kernel, which also hands the query over as partial products.  Without (fp32 pools of
+    // more than four tiles): one row tile per workgroup, all of K.
     if constexpr (PRE) {
         hipLaunchKernelGGL((k_lstm_att_tall<XT>), dim3(QP_TALL * n_tiles), lb, 0, s, d.Wa, d.ba, xatt_cur, d.c_att, xdec_cur, K_DEC / KB, XD_HA,
                            xatt_nxt, K_ATT / KB, XA_H, d.live, d.done, d.Wq_epi, d.qpart, reinterpret_cast<const floatx4*>(d.pre_att));
-    } else if (rows == 4) {
-        if constexpr (HAS_WIDE)
-            hipLaunchKernelGGL((k_lstm_rc<XT, K_ATT, 4, true>), lg, lb, 0, s, d.Wa, d.ba, xatt_cur, d.c_att, xdec_cur, K_DEC / KB, XD_HA,
-                               xatt_nxt, K_ATT / KB, XA_H, n_tiles, d.live, d.done, nullptr);
-    } else if (rows == 2) {
-        if constexpr (HAS_WIDE)
-            hipLaunchKernelGGL((k_lstm_rc<XT, K_ATT, 2>), lg, lb, 0, s, d.Wa, d.ba, xatt_cur, d.c_att, xdec_cur, K_DEC / KB, XD_HA,
-                               xatt_nxt, K_ATT / KB, XA_H, n_tiles, d.live, d.done, nullptr);
-    } else
+    } else {
         hipLaunchKernelGGL((k_lstm<XT, K_ATT, false>), lg, lb, 0, s,
                            d.Wa, d.ba, xatt_cur, d.c_att, xdec_cur, K_DEC / KB, XD_HA, xatt_nxt, K_ATT / KB, XA_H,
                            n_tiles, d.live, d.done, nullptr);
+    }
     mark(1);
     const int n_pad = (n_req + 7) / 8 * 8;      // slots are dealt to the XCDs in eights
     if (lsa_split == 4) hipLaunchKernelGGL((k_lsa<XT, MT, 4, PRE>), dim3(n_pad * 4), dim3(LSA_THREADS), 0, s, d, cur, n_req);
@@ -1529,13 +1466,12 @@ static hipError_t step_typed(const DevPtrs& d, int n_req, int n_tiles, int lsa_s
     const uint4* xdec_in = reinterpret_cast<const uint4*>(d.xdec[cur]);
     const floatx4* pre_dec = reinterpret_cast<const floatx4*>(d.pre_dec);
     if (rows == 4) {
-        if constexpr (HAS_WIDE)
-            // (with pre-sums the decoder LSTM's K = 1536 leaves registers for the pipelined form)
-            hipLaunchKernelGGL((k_lstm_rc<XT, K_DEC, 4, PRE_DEC, PRE_DEC>), lg, lb, 0, s, d.Wd, d.bd, xdec_in, d.c_dec, xdec_nxt, K_DEC / KB, XD_HD,
+        if constexpr (HAS_WIDE && !PRE_DEC)
+            hipLaunchKernelGGL((k_lstm_rc<XT, K_DEC, 4>), lg, lb, 0, s, d.Wd, d.bd, xdec_in, d.c_dec, xdec_nxt, K_DEC / KB, XD_HD,
                                xdec_nxt, K_DEC / KB, XD_HD, n_tiles, d.live, d.done, pre_dec);
     } else if (rows == 2) {
         if constexpr (HAS_WIDE)
-            hipLaunchKernelGGL((k_lstm_rc<XT, K_DEC, 2, false, PRE_DEC>), lg, lb, 0, s, d.Wd, d.bd, xdec_in, d.c_dec, xdec_nxt, K_DEC / KB, XD_HD,
+            hipLaunchKernelGGL((k_lstm_rc<XT, K_DEC, 2, PRE_DEC>), lg, lb, 0, s, d.Wd, d.bd, xdec_in, d.c_dec, xdec_nxt, K_DEC / KB, XD_HD,
                                xdec_nxt, K_DEC / KB, XD_HD, n_tiles, d.live, d.done, pre_dec);
     } else
         hipLaunchKernelGGL((k_lstm<XT, K_DEC, PRE_DEC>), lg, lb, 0, s, d.Wd, d.bd, xdec_in, d.c_dec, xdec_nxt, K_DEC / KB, XD_HD,
@@ -1567,9 +1503,8 @@ hipError_t launch_step(const DevPtrs& d, const StepLaunch& cfg, int cur, hipStre
         if (cfg.wdtype == 1 && cfg.mdtype == 0) return step_typed<bf16_t, float, 2>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cfg.lstm_rows, cfg.proj_group, cur, s, ev);
         return hipErrorInvalidValue;
     }
+    // without pre-sums: fp32 pools of more than four tiles (the fp32 mode is the parity vehicle)
     if (cfg.wdtype == 0 && cfg.mdtype == 0) return step_typed<float, float, 0>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cfg.lstm_rows, cfg.proj_group, cur, s, ev);
-    if (cfg.wdtype == 1 && cfg.mdtype == 1) return step_typed<bf16_t, bf16_t, 0>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cfg.lstm_rows, cfg.proj_group, cur, s, ev);
-    if (cfg.wdtype == 1 && cfg.mdtype == 0) return step_typed<bf16_t, float, 0>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cfg.lstm_rows, cfg.proj_group, cur, s, ev);
     return hipErrorInvalidValue;
 }
 
