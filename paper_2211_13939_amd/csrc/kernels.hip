@@ -34,8 +34,8 @@ constexpr int LSTM_WAVES = 8;
 
 // Gate pre-sums (PRE).  Part of an LSTM's input is known long before the kernel runs: [A; H_att] of the attention
 // LSTM's input is complete once the attention kernel of the previous step has finished, H_dec of the decoder LSTM's
-// input once the previous step's decoder LSTM has.  Pools of few tiles leave almost every CU idle during the
-// projection kernel (one workgroup per 16 slots), so that launch carries extra workgroups which contract those parts
+// input once the previous step's decoder LSTM has.  The projection kernel leaves almost every CU idle (a few
+// workgroups per 16 slots), so that launch carries extra workgroups which contract those parts
 // with their columns of the gate matrices and store the sums in accumulator layout:
 //   pre[pool tile][row tile][lane] (floatx4) = sum over the late fragments of W[row tile] x[pool tile].
 // The LSTM kernels of the next step then contract only the early fragments -- Pre(M_last) (K = 256 of 1792) and
@@ -495,7 +495,7 @@ __global__ __launch_bounds__(LSTM_WAVES * 64) void k_presum_tile(DevPtrs d, int 
 //   e_j = v . tanh(q + W_loc loc[j] + PM[j])
 //   w = softmax_{j<L}(e);  A = sum_j w_j F[j];  W_last <- w;  W_acc <- W_acc + w
 // The contractions run on MFMA with 16 positions (or, for q, 16 copies of h_att)
-// as the columns (pools of at most 16 slots get q as partial sums from the
+// as the columns (pools with gate pre-sums get q as partial sums from the
 // attention LSTM's epilogue instead):
 //   q      (128 x 16, K split over the waves) = W_q * h_att
 //   loc^T  (32 x 16)          = Kc (32 x 64 taps) * U^T (64 taps x 16 positions)

@@ -71,18 +71,16 @@ struct Layout {
     size_t total, proj_part_bytes;
 };
 
-// measured per pool size: see the design notes
-static bool pre_gates_large() { return true; }
-
-// Gate pre-sums: pools of at most PRESUM_MAX_TILES tiles leave all but a few CUs idle during the projection kernel,
-// whose launch then also contracts what the next step's two LSTMs already have of their inputs ([A; H_att] and H_dec).
-// The attention LSTM, left with K = 256, then runs as tall tiles and hands the attention query over as 32 rank-32
-// partial products per slot (16 KB) instead of the attention kernel pulling W_q (256 KB in bf16) through each of its
-// CUs.  Fixed per pool (it changes the order in which gates and query are summed): a request's bits do not depend on
-// what else the pool holds.
+// Gate pre-sums: the projection kernel needs a handful of CUs, so its launch also contracts what the next step's LSTMs
+// already have of their inputs ([A; H_att] of the attention LSTM; in pools of at most four tiles also H_dec of the
+// decoder LSTM).  The attention LSTM, left with K = 256, then runs as tall tiles and hands the attention query over as
+// 32 rank-32 partial products per slot (16 KB) instead of the attention kernel pulling W_q (256 KB in bf16) through
+// each of its CUs.  Fixed per pool (it changes the order in which gates and query are summed): a request's bits do
+// not depend on what else the pool holds.  Every bf16 pool has them; fp32 pools up to four tiles (the pre-sum
+// workgroups of larger pools hold several row tiles' fragments in registers, which fp32 fragments do not fit).
 bool pre_gates_for(const tts_config& c)
 {
-    return (c.max_pool + 15) / 16 <= PRESUM_SMALL_TILES || (c.weight_dtype == TTS_DTYPE_BF16 && pre_gates_large());
+    return (c.max_pool + 15) / 16 <= PRESUM_SMALL_TILES || c.weight_dtype == TTS_DTYPE_BF16;
 }
 // the decoder LSTM's pre-sum too: only where the pre-sum workgroups still finish in the projection's shadow (beyond four
 // tiles it saved the decoder LSTM 1.8 us and kept the projection's launch 5 us longer)
