@@ -293,12 +293,13 @@ def test_small_and_large_capacity_pools_agree(wl8, weights_fp32, solo_frames):
 
 
 @pytest.mark.parametrize("bf16,max_pool,n_req", [(True, 32, 24), (True, 48, 40), (False, 48, 36), (False, 64, 52),
-                                                  (True, 96, 90), (True, 128, 120), (True, 176, 170)])
+                                                  (True, 96, 90), (True, 128, 120), (True, 160, 150), (True, 176, 170), (True, 208, 200)])
 def test_pools_of_several_tiles_with_gate_presums(bf16, max_pool, n_req, weights_bf16, weights_fp32):
     """Pools of two to four tiles: the pre-sum workgroups split by pool tiles (one group up to two
     tiles, two groups of 2 + 1 or 2 + 2 tiles above) and take one to three row tiles each.  bf16 pools of
     more tiles pre-sum the attention LSTM's late columns only, in groups of at most four tiles walked one
-    at a time (6 tiles: two groups; 8: two; 11: three, with two idle workgroups per XCD), and their
+    at a time (6 and 8 tiles: two groups; 10 and 11: three, with two idle workgroups per XCD; 13: four, the last of
+    one tile), and their
     projection runs as three or two workgroups per tile.  Against the oracle on a sample, and a request's
     bits do not depend on the pool's composition (alone in slot 0 vs among all, vs among 5 joining in
     another order: the same sums whether the pool spans one tile or eleven)."""
