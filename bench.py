@@ -145,11 +145,12 @@ def stream_arrivals(w5, kind, qps, n=None):
     return np.cumsum(rng.exponential(1.0 / qps, size=n))
 
 
-def stream_run(stream, pool5, w5, enc, arrival, join_every, max_pool, postnet=None, vocoder=None):
+def stream_run(stream, pool5, w5, enc, arrival, join_every, max_pool, postnet=None, vocoder=None, overlap=False):
     n = len(arrival)
     n_steps = w5.n_steps[:n]
     if postnet is not None:
-        be = stream.GpuPostnetBackend(pool5, postnet, enc if callable(enc) else (lambda i, e=enc: e[i]), n_steps, w5.chunk_frames, 10, vocoder=vocoder)
+        be = stream.GpuPostnetBackend(pool5, postnet, enc if callable(enc) else (lambda i, e=enc: e[i]), n_steps, w5.chunk_frames, 10,
+                                      vocoder=vocoder, overlap=overlap)
     else:
         be = stream.GpuBackend(pool5, lambda i, e=enc: e[i], n_steps, w5.chunk_frames)
     r = stream.simulate(be, arrival, n_steps, w5.chunk_frames, join_every=join_every, max_pool=max_pool)
@@ -515,6 +516,17 @@ def main():
             ids_of(i)
         join5 = stream.EncoderAtJoin(enc5, ids_of, int(w5.enc_len.max()))
         res["per_step_join_encoder_to_vocoder"] = stream_run(stream, pool5, w5, join5, arrival, 1, 16, postnet=pn5, vocoder=voc5)
+        # the same two with PostNet and vocoder on a stream of their own, beside the next decoder steps
+        side = torch.cuda.Stream(device=pool5.device)
+        pn5s = binding.Postnet(binding.make_postnet_config(max_columns=16 * 50, bf16=True), ws5, bs5, stream=side)
+        voc5s = binding.Vocoder(binding.make_vocoder_config(overlap=8, max_chunk=w5.chunk_frames, max_requests=16, max_batch=16, bf16=True),
+                                synth.make_vocoder_weights(bf16=True), stream=side)
+        res["per_step_join_with_postnet_and_vocoder_overlapped"] = stream_run(stream, pool5, w5, enc5_dev, arrival, 1, 16, postnet=pn5s,
+                                                                              vocoder=voc5s, overlap=True)
+        res["per_step_join_encoder_to_vocoder_overlapped"] = stream_run(stream, pool5, w5, join5, arrival, 1, 16, postnet=pn5s,
+                                                                        vocoder=voc5s, overlap=True)
+        pn5s.close()
+        voc5s.close()
         enc5.close()
         voc5.close()
         pn5.close()
@@ -523,7 +535,8 @@ def main():
                                      "(per_step_join_host_input: handed over from pageable host memory, PCIe copy "
                                      "included; per_step_join_with_postnet: each chunk also passes the chunk-level "
                                      "PostNet on the device before it is copied out; per_step_join_with_postnet_and_vocoder: the chunk then goes through the "
-                                     "vocoder on the device and the response is its 256 samples per frame; per_step_join_encoder_to_vocoder: in addition F_enc is "
+                                     "vocoder on the device and the response is its 256 samples per frame; ..._overlapped: PostNet and vocoder on a stream of their own beside "
+                                     "the next decoder steps, a chunk counted when its response has reached the host; per_step_join_encoder_to_vocoder: in addition F_enc is "
                                      "not given but computed at join time by the encoder from the request's token ids); rtf = last-chunk latency / audio duration at 256 samples per frame, "
                                      "22.05 kHz (decoder only)",
                          **res, "paper_context": "first-chunk latency < 80 ms at 100 QPS, full pipeline, one A10"}

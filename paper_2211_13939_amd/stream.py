@@ -27,7 +27,22 @@ import numpy as np
 class PoolBackend:
     """What the loop needs from a pool.  `run(k)` advances every pooled request
     by k steps, hands out every chunk that became ready and returns
-    (elapsed seconds, ids whose chunk was handed out, ids that finished)."""
+    (elapsed seconds, ids whose chunk was handed out, ids that finished).
+
+    A backend whose later modules run beside the decoder (on another stream)
+    hands chunks out after the segment that produced them.  It returns a fourth
+    element, a list of deliveries (request index, when, is the request's last):
+    `when` is a time.perf_counter() value if the backend is timed by the loop
+    (elapsed is None), else seconds from the start of the segment.  Its second
+    element is then empty and its third names the requests that have finished
+    DECODING (they leave the pool); `pending()` says whether deliveries are
+    still out and `flush()` waits for them and returns (elapsed, deliveries)."""
+
+    def pending(self) -> bool:
+        return False
+
+    def flush(self):
+        return 0.0, []
 
     def add(self, index: int) -> int:
         raise NotImplementedError
@@ -71,16 +86,40 @@ def simulate(backend: PoolBackend, arrival_s: Sequence[float], n_steps: Sequence
     busy = 0.0
     step_est = step_time_guess_s
 
-    while nxt < n or live:
+    def deliver(items, clock0, t0, timed_by_loop):
+        for index, when, last in items:
+            t = clock0 + ((when - t0) if timed_by_loop else when)
+            if np.isnan(fcl[index]):
+                fcl[index] = t - arrival_s[index]
+            if last:
+                lcl[index] = t - arrival_s[index]
+
+    t_end = None                             # perf_counter at the end of the last timed stretch, while the pool stays busy
+    while nxt < n or live or backend.pending():
+        if not live and backend.pending():
+            # nothing left to decode: wait for the chunks that the later modules still hold
+            t0 = t_end if t_end is not None else time.perf_counter()
+            elapsed, items = backend.flush()
+            t_end = time.perf_counter()
+            dt = (t_end - t0) if elapsed is None else float(elapsed)
+            deliver(items, clock, t0, elapsed is None)
+            clock += dt
+            busy += dt
+            if nxt >= n:
+                continue
         if not live and nxt < n and arrival_s[order[nxt]] > clock:
             clock = float(arrival_s[order[nxt]])          # idle until the next arrival
-        # admit everything that has arrived (bounded by the pool's capacity)
-        t0 = time.perf_counter()
+            t_end = None
+        # admit everything that has arrived (bounded by the pool's capacity); while the pool stays busy the clock
+        # runs on from the end of the last segment, so that the loop's own bookkeeping is inside the measured time
+        t0 = t_end if t_end is not None else time.perf_counter()
         while nxt < n and arrival_s[order[nxt]] <= clock and (max_pool is None or len(live) < max_pool):
             i = int(order[nxt])
             rid = backend.add(i)
             live[rid] = dict(index=i, done=0, total=int(n_steps[i]), first=False)
             nxt += 1
+        if not live:
+            continue
         # how many steps until something must happen on the host
         if join_every > 1:
             k = join_every
@@ -90,9 +129,13 @@ def simulate(backend: PoolBackend, arrival_s: Sequence[float], n_steps: Sequence
                 gap = arrival_s[order[nxt]] - clock
                 k = max(1, min(k, int(np.ceil(gap / max(step_est, 1e-9)))))
         hist[len(live)] = hist.get(len(live), 0) + k
-        elapsed, chunk_ids, fin_ids = backend.run(k)
+        out = backend.run(k)
+        elapsed, chunk_ids, fin_ids = out[0], out[1], out[2]
         # a real backend is timed here (joins, steps, drains); a model backend reports its own time
-        dt = (time.perf_counter() - t0) if elapsed is None else float(elapsed)
+        t_end = time.perf_counter()
+        dt = (t_end - t0) if elapsed is None else float(elapsed)
+        if len(out) > 3:
+            deliver(out[3], clock, t0, elapsed is None)
         clock += dt
         busy += dt
         n_seg += 1
@@ -107,9 +150,10 @@ def simulate(backend: PoolBackend, arrival_s: Sequence[float], n_steps: Sequence
                 fcl[s["index"]] = clock - arrival_s[s["index"]]
         for rid in fin_ids:
             s = live.pop(rid)
-            if not s["first"]:
-                fcl[s["index"]] = clock - arrival_s[s["index"]]
-            lcl[s["index"]] = clock - arrival_s[s["index"]]
+            if len(out) <= 3:
+                if not s["first"]:
+                    fcl[s["index"]] = clock - arrival_s[s["index"]]
+                lcl[s["index"]] = clock - arrival_s[s["index"]]
             backend.retire(rid)
     return StreamResult(fcl, lcl, hist, n_seg, total_steps, busy, clock)
 
@@ -165,15 +209,28 @@ class GpuPostnetBackend(GpuBackend):
     them go through the PostNet as one dynamic batch (Sec. 2.2.2: each module batches the pool
     items it has to process), then one copy brings the post-processed chunks to the host."""
 
-    def __init__(self, pool, postnet, enc, n_steps, chunk: int, context: int, on_chunk=None, vocoder=None, on_audio=None):
+    N_SETS = 4      # staging buffer sets of the overlapped form: rounds that may be out at one time
+
+    def __init__(self, pool, postnet, enc, n_steps, chunk: int, context: int, on_chunk=None, vocoder=None, on_audio=None,
+                 overlap: bool = False):
         """on_chunk(request index, first frame, frames [n, n_mel]) is called for every chunk handed out.
         With a vocoder (module V) the post-processed chunks of a round go on, still on the device, through
         tts_vocoder_run as one dynamic batch (Eq. 3, Eq. 4: splice, generator, fade, state write-back) and the
-        responses are the waveform pieces: on_audio(request index, samples [m])."""
+        responses are the waveform pieces: on_audio(request index, samples [m]).
+
+        overlap: the modules behind the decoder run on their own stream (the one `postnet` and `vocoder` were
+        created on, which must not be the pool's) beside the next decoder steps: a round only waits for the copy of
+        its chunks out of the pool, and the loop hears of a chunk when its response has reached the host (the
+        deliveries of PoolBackend); the callbacks are made then."""
         super().__init__(pool, enc, n_steps, chunk)
         import torch
         self.postnet, self.context, self.on_chunk = postnet, context, on_chunk
         self.vocoder, self.on_audio = vocoder, on_audio
+        self.overlap = overlap
+        if overlap:
+            assert postnet.stream.cuda_stream != pool.stream.cuda_stream, "the later modules need a stream of their own"
+            assert vocoder is None or vocoder.stream.cuda_stream == postnet.stream.cuda_stream
+            self._out = []          # rounds on the side stream: dict(ev, items, set)
         if vocoder is not None:
             cap_v = int(pool.cfg.max_pool)
             assert vocoder.cfg.max_requests >= cap_v and vocoder.cfg.max_batch >= cap_v and vocoder.cfg.max_chunk >= chunk
@@ -185,8 +242,114 @@ class GpuPostnetBackend(GpuBackend):
         self._d_in = torch.empty((cap * (chunk + context), pool.n_mel), dtype=torch.float32, device=pool.device)
         self._d_out = torch.empty((cap * chunk, pool.n_mel), dtype=torch.float32, device=pool.device)
         self._h_out = torch.empty((cap * chunk, pool.n_mel), dtype=torch.float32).pin_memory()
+        if overlap:
+            def one_set(first):
+                d = dict(d_in=self._d_in if first else torch.empty_like(self._d_in),
+                         d_out=self._d_out if first else torch.empty_like(self._d_out),
+                         h_out=self._h_out if first else torch.empty_like(self._h_out).pin_memory(), ev=None)
+                if vocoder is not None:
+                    d["d_audio"] = self._d_audio if first else torch.empty_like(self._d_audio)
+                    d["h_audio"] = self._h_audio if first else torch.empty_like(self._h_audio).pin_memory()
+                return d
+            self._sets = [one_set(i == 0) for i in range(self.N_SETS)]
+            self._next_set = 0
+
+    # ---- the overlapped form
+    def _harvest(self):
+        """Rounds whose responses have reached the host, oldest first: [(request index, perf_counter, last)]."""
+        got = []
+        while self._out and self._out[0]["ev"].query():
+            r = self._out.pop(0)
+            t = time.perf_counter()
+            got += [(index, t, last) for index, last in r["items"]]
+            st = r["set"]                   # its host buffers stay as they are until N_SETS - 1 more rounds have gone out
+            if self.on_audio is not None and "n_out" in r:
+                host, at = st["h_audio"].numpy(), 0
+                for (index, _), m in zip(r["items"], r["n_out"]):
+                    self.on_audio(index, host[at:at + m].copy())
+                    at += m
+            if self.on_chunk is not None:
+                host = st["h_out"].numpy()
+                for index, first, r0, n in r["handed"]:
+                    self.on_chunk(index, first, host[r0:r0 + n].copy())
+        return got
+
+    def pending(self) -> bool:
+        return self.overlap and bool(self._out)
+
+    def flush(self):
+        got = []
+        while self._out:
+            got += self._harvest()
+        return None, got
+
+    def _run_overlapped(self, k: int):
+        torch = self.pool._torch
+        main, side = self.pool.stream, self.postnet.stream
+        self.pool.step_n(k)
+        for s in self.live.values():
+            s["done"] = min(s["total"], s["done"] + k)
+        fin_ids, span = [], self.chunk + self.context
+        while True:                         # a request that ends may hand out a full chunk and then its rest
+            st = self._sets[self._next_set]
+            if st["ev"] is not None:
+                st["ev"].synchronize()      # the round that used this set last (N_SETS rounds ago) is through
+            lens, keeps, row, out_rows, items, voc, handed = [], [], 0, 0, [], [], []
+            for rid, s in self.live.items():
+                ready = s["done"] - s["drained"] >= self.chunk or s["done"] == s["total"]
+                if not ready or rid in fin_ids or row + span > st["d_in"].shape[0]:
+                    continue
+                c, n, fin = self.pool.chunk_window(rid, self.context, st["d_in"][row:])
+                if n:
+                    lens.append(c + n)
+                    keeps.append(c)
+                    row += c + n
+                    items.append((s["index"], bool(fin)))
+                    handed.append((s["index"], s["drained"], out_rows, n))
+                    if self.vocoder is not None:
+                        first = 0
+                        if "vslot" not in s:
+                            s["vslot"] = self._free_slots.pop()
+                            first = 1
+                        voc.append((n, s["vslot"], first | (2 if fin else 0)))
+                    out_rows += n
+                    s["drained"] += n
+                if fin:
+                    assert n > 0 or self.vocoder is None or "vslot" not in s
+                    fin_ids.append(rid)
+            if not lens:
+                break
+            copied = torch.cuda.Event()
+            copied.record(main)             # the chunks are out of the pool's ring: the decoder may go on
+            side.wait_event(copied)
+            self.postnet.run_device(st["d_in"], lens, keeps, st["d_out"])
+            rnd = dict(items=items, set=st, handed=handed)
+            with torch.cuda.stream(side):
+                if self.vocoder is not None:
+                    rnd["n_out"] = self.vocoder.run_device(st["d_out"], [v[0] for v in voc], [v[1] for v in voc],
+                                                           [v[2] for v in voc], st["d_audio"])
+                    total = sum(rnd["n_out"])
+                    st["h_audio"][:total].copy_(st["d_audio"][:total], non_blocking=True)
+                if self.vocoder is None or self.on_chunk is not None:
+                    st["h_out"][:out_rows].copy_(st["d_out"][:out_rows], non_blocking=True)
+                st["ev"] = torch.cuda.Event()
+                st["ev"].record(side)
+            rnd["ev"] = st["ev"]
+            self._out.append(rnd)
+            self._next_set = (self._next_set + 1) % self.N_SETS
+        # the segment ends when the decoder's steps (and the copies out of its ring) are through; responses that
+        # arrive meanwhile are taken as they come
+        stepped = torch.cuda.Event()
+        stepped.record(main)
+        got = []
+        while not stepped.query():
+            got += self._harvest()
+        got += self._harvest()
+        return None, [], fin_ids, got
 
     def run(self, k: int):
+        if self.overlap:
+            return self._run_overlapped(k)
         self.pool.step_n(k)
         for s in self.live.values():
             s["done"] = min(s["total"], s["done"] + k)

@@ -161,10 +161,14 @@ def test_bad_calls_are_rejected_and_change_nothing():
     voc.close()
 
 
-def test_serving_loop_decoder_postnet_vocoder_matches_oracle(weights_fp32):
+@pytest.mark.parametrize("overlap", [False, True])
+def test_serving_loop_decoder_postnet_vocoder_matches_oracle(overlap, weights_fp32):
     """Modules D and V behind each other in the arrival-driven loop: five requests arriving over time into a pool
     of three slots, chunks of 12 frames, overlap 4.  Every request's waveform (its responses in order) equals the
-    oracle's: decoder alone, PostNet on the utterance so far, vocoder stream with splice, fade and write-back."""
+    oracle's: decoder alone, PostNet on the utterance so far, vocoder stream with splice, fade and write-back.
+    overlap: PostNet and vocoder on a stream of their own beside the next decoder steps (more rounds out than the
+    loop has staging sets: 14 chunks through 4 sets), responses taken as they reach the host."""
+    import torch
     from oracle import oracle as orc
     from paper_2211_13939_amd import stream
     n, chunk, ov = 5, 12, 4
@@ -172,14 +176,17 @@ def test_serving_loop_decoder_postnet_vocoder_matches_oracle(weights_fp32):
     pool = make_pool(wl, weights_fp32, chunk_frames=chunk, max_pool=3)
     ws, bs = synth.make_postnet_weights()
     wv = synth.make_vocoder_weights()
-    pn = binding.Postnet(binding.make_postnet_config(max_columns=3 * (chunk + binding.POSTNET_CONTEXT)), ws, bs, stream=pool.stream)
-    voc = binding.Vocoder(binding.make_vocoder_config(overlap=ov, max_chunk=chunk, max_requests=3, max_batch=3), wv, stream=pool.stream)
+    side = torch.cuda.Stream(device=pool.device) if overlap else pool.stream
+    pn = binding.Postnet(binding.make_postnet_config(max_columns=3 * (chunk + binding.POSTNET_CONTEXT)), ws, bs, stream=side)
+    voc = binding.Vocoder(binding.make_vocoder_config(overlap=ov, max_chunk=chunk, max_requests=3, max_batch=3), wv, stream=side)
     audio = {i: [] for i in range(n)}
     be = stream.GpuPostnetBackend(pool, pn, lambda i: wl.encoder_outputs(i), wl.n_steps, chunk, binding.POSTNET_CONTEXT,
-                                  vocoder=voc, on_audio=lambda i, a: audio[i].append(a))
-    say(f"case serving loop decoder -> postnet -> vocoder: steps {wl.n_steps.tolist()}, pool of 3, chunks of {chunk}, overlap {ov}")
+                                  vocoder=voc, on_audio=lambda i, a: audio[i].append(a), overlap=overlap)
+    say(f"case serving loop decoder -> postnet -> vocoder{' (overlapped)' if overlap else ''}: steps {wl.n_steps.tolist()}, "
+        f"pool of 3, chunks of {chunk}, overlap {ov}")
     res = stream.simulate(be, np.array([0.0, 0.0, 1e-4, 1e-4, 4e-3]), wl.n_steps, chunk, join_every=1, max_pool=3)
-    assert not np.isnan(res.last_chunk_latency_s).any()
+    assert not np.isnan(res.last_chunk_latency_s).any() and not np.isnan(res.first_chunk_latency_s).any()
+    assert (res.first_chunk_latency_s <= res.last_chunk_latency_s).all() and (res.first_chunk_latency_s > 0).all()
     Wp, Wd, Wv = orc.PostnetWeights(ws, bs), orc.Weights(weights_fp32), orc.VocoderWeights(wv)
     worst = 0.0
     for i in range(n):

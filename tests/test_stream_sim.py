@@ -102,3 +102,53 @@ def test_per_step_join_batches_overlapping_requests():
     assert abs(res.first_chunk_latency_s[0] - 4e-3) < 1e-9
     both = [k for k, m in be.membership if m == [0, 1]]
     assert sum(both) == 8
+
+
+class LateBackend(ModelBackend):
+    """The modules behind the decoder take `t_late` seconds and run beside it: a chunk is handed out that long
+    after the segment that completed it (the fourth element of run's result)."""
+
+    def __init__(self, n_steps, chunk, t_step, t_late):
+        super().__init__(n_steps, chunk, t_step)
+        self.t_late = t_late
+        self.out = []            # (due time on the backend's own clock, index, last)
+        self.now = 0.0
+
+    def _due(self, until):
+        got = [(i, t, last) for t, i, last in self.out if t <= until]
+        self.out = [(t, i, last) for t, i, last in self.out if t > until]
+        return got
+
+    def run(self, k):
+        elapsed, chunks, fins = super().run(k)
+        start, end = self.now, self.now + elapsed
+        for rid in chunks:
+            s = self.live[rid]
+            self.out.append((end + self.t_late, s["index"], s["drained"] == s["total"]))
+        self.now = end
+        # deliveries are reported as seconds from the start of the segment that hears of them
+        got = [(i, max(0.0, t - start), last) for i, t, last in self._due(end)]
+        return elapsed, [], fins, got
+
+    def pending(self):
+        return bool(self.out)
+
+    def flush(self):
+        start = self.now
+        end = max(t for t, _, _ in self.out)
+        self.now = end
+        return end - start, [(i, t - start, last) for i, t, last in self._due(end)]
+
+
+def test_late_deliveries_are_counted_when_they_arrive():
+    """A backend whose later modules run beside the decoder: every chunk is handed out t_late after the segment
+    that completed it, also when the request has left the pool or the pool has run empty meanwhile."""
+    chunk, t_step, t_late = 4, 1e-3, 2.5e-3
+    n_steps = np.array([8, 5, 4])
+    arrivals = np.array([0.0, 0.0, 0.1])              # the third arrives long after the first two are through
+    be = LateBackend(n_steps, chunk, t_step, t_late)
+    res = stream.simulate(be, arrivals, n_steps, chunk, join_every=1, step_time_guess_s=t_step)
+    # first chunks complete after 4 steps; request 1's last (one frame) after 5, request 0's after 8; request 2 runs alone
+    np.testing.assert_allclose(res.first_chunk_latency_s, [4e-3 + t_late, 4e-3 + t_late, 4e-3 + t_late], rtol=0, atol=1e-9)
+    np.testing.assert_allclose(res.last_chunk_latency_s, [8e-3 + t_late, 5e-3 + t_late, 4e-3 + t_late], rtol=0, atol=1e-9)
+    assert not be.pending() and not be.live
