@@ -178,6 +178,14 @@ int tts_pool_frames(tts_pool *pool, int64_t id, int *out_frames, int *out_finish
 int tts_pool_size(const tts_pool *pool);
 int tts_pool_n_active(const tts_pool *pool);
 
+/* Slots the next step's kernels must cover (one past the highest running request's slot), and how many times a
+ * running request has been moved to a lower slot since creation.  The pool of Sec. 2.2.2 shrinks as requests leave;
+ * when the running requests would fit fewer 16-slot tiles than the kernels cover, and enough lower slots are free,
+ * the pool moves them down on the device before the next step.  Nothing a caller sees depends on the slot: ids,
+ * frames and states stay with the request, bit for bit.  Spans of 16 and fewer are left alone. */
+int tts_pool_span(const tts_pool *pool);
+long long tts_pool_moves(const tts_pool *pool);
+
 /* Wait until everything queued on the pool's stream has run.
  * Workgroups of one launch hand each other words (the projection's partial sums, the attention energies of a
  * request) and wait for them a bounded number of polls; should such a wait ever run out (the GPU so oversubscribed by
@@ -224,6 +232,12 @@ int tts_book_step(tts_book *b, int64_t *out_ids, int *out_n_active);
 /* frames the next drain would hand out (0 if the chunk is not ready) */
 int tts_book_drain(tts_book *b, int64_t id, int *out_first, int *out_frames, int *out_finished);
 int tts_book_retire(tts_book *b, int64_t id);
+/* slot of request `id` (-1: no such request) */
+int tts_book_slot(const tts_book *b, int64_t id);
+/* Packs the running requests into fewer 16-slot tiles (below one tile: a smaller power of two), not below `min_span`, if the free slots allow it
+ * (the pool does this before a step, with min_span 16).  Returns the number of moves carried out and writes the first
+ * `cap` of them as out_from[i] -> out_to[i]; 0 if there is nothing to gain or finished requests block the low slots. */
+int tts_book_compact(tts_book *b, int min_span, int *out_from, int *out_to, int cap);
 void tts_book_destroy(tts_book *b);
 
 #ifdef __cplusplus

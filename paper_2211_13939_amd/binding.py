@@ -33,10 +33,11 @@ EXPORTS = (
     "tts_pool_workspace_bytes", "tts_pool_create", "tts_pool_add_request", "tts_pool_step",
     "tts_pool_step_n", "tts_pool_drain_chunk", "tts_pool_get_stop_logits", "tts_pool_retire",
     "tts_pool_get_state", "tts_pool_set_state", "tts_pool_frames", "tts_pool_size", "tts_pool_n_active",
+    "tts_pool_span", "tts_pool_moves",
     "tts_pool_sync", "tts_pool_set_wait_polls", "tts_pool_timing", "tts_pool_elapsed_ms", "tts_pool_kernel_times", "tts_pool_destroy",
     "tts_last_error",
     "tts_book_create", "tts_book_add", "tts_book_step", "tts_book_drain", "tts_book_retire",
-    "tts_book_destroy",
+    "tts_book_slot", "tts_book_compact", "tts_book_destroy",
     "tts_pool_chunk_window",
     "tts_postnet_workspace_bytes", "tts_postnet_create", "tts_postnet_run", "tts_postnet_elapsed_ms",
     "tts_postnet_destroy",
@@ -124,6 +125,9 @@ def lib() -> C.CDLL:
     L.tts_pool_frames.argtypes = [vp, C.c_int64, _ip, _ip]
     L.tts_pool_size.argtypes = [vp]
     L.tts_pool_n_active.argtypes = [vp]
+    L.tts_pool_span.argtypes = [vp]
+    L.tts_pool_moves.restype = C.c_longlong
+    L.tts_pool_moves.argtypes = [vp]
     L.tts_pool_sync.argtypes = [vp]
     L.tts_pool_set_wait_polls.argtypes = [vp, C.c_int]
     L.tts_pool_timing.argtypes = [vp, C.c_int]
@@ -139,6 +143,8 @@ def lib() -> C.CDLL:
     L.tts_book_step.argtypes = [vp, _i64p, _ip]
     L.tts_book_drain.argtypes = [vp, C.c_int64, _ip, _ip, _ip]
     L.tts_book_retire.argtypes = [vp, C.c_int64]
+    L.tts_book_slot.argtypes = [vp, C.c_int64]
+    L.tts_book_compact.argtypes = [vp, C.c_int, _ip, _ip, C.c_int]
     L.tts_book_destroy.restype = None
     L.tts_book_destroy.argtypes = [vp]
     L.tts_pool_chunk_window.argtypes = [vp, C.c_int64, C.c_int, vp, _ip, _ip, _ip]
@@ -289,6 +295,12 @@ class Pool:
     def n_active(self) -> int:
         return lib().tts_pool_n_active(self._h)
 
+    def span(self) -> int:
+        return lib().tts_pool_span(self._h)
+
+    def moves(self) -> int:
+        return lib().tts_pool_moves(self._h)
+
     def sync(self) -> None:
         _check(lib().tts_pool_sync(self._h))
 
@@ -371,6 +383,15 @@ class Book:
 
     def retire(self, rid: int) -> None:
         _check(lib().tts_book_retire(self._h, rid))
+
+    def slot(self, rid: int) -> int:
+        return lib().tts_book_slot(self._h, rid)
+
+    def compact(self, min_span: int = 16):
+        src, dst = (C.c_int * self.max_pool)(), (C.c_int * self.max_pool)()
+        n = lib().tts_book_compact(self._h, min_span, src, dst, self.max_pool)
+        _check(min(n, 0))
+        return [(src[i], dst[i]) for i in range(n)]
 
     def close(self):
         if self._h:

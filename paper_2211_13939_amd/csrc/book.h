@@ -6,6 +6,7 @@
 #include <cstdint>
 #include <set>
 #include <unordered_map>
+#include <utility>
 #include <vector>
 
 namespace tts {
@@ -114,6 +115,56 @@ public:
         by_id_.erase(id);
         free_.insert(s);
         return 0;
+    }
+
+    // Slots the step kernels must cover: one past the highest running request's.
+    int span() const {
+        int sp = 0;
+        for (int sl : active_) sp = sl + 1 > sp ? sl + 1 : sp;
+        return sp;
+    }
+
+    // Span classes (what launch shapes are keyed by): whole tiles of 16 slots, powers of two within the first.
+    static int span_class(int n) {
+        if (n > 16) return (n + 15) / 16 * 16;
+        int b = 1;
+        while (b < n) b <<= 1;
+        return b;
+    }
+
+    // When requests have left, the running ones may sit far apart.  If they would fit a smaller span class (but not
+    // below `min_span`, under which a smaller launch saves nothing) and enough slots under it are free, the running
+    // requests above move into those free slots, lowest first: (from, to) pairs, in the order to carry them out.
+    // Finished requests that have not been retired keep their slots and may make this impossible: then no moves.
+    std::vector<std::pair<int, int>> plan_moves(int min_span) const {
+        std::vector<std::pair<int, int>> moves;
+        if (active_.empty()) return moves;
+        int target = span_class((int)active_.size());
+        if (target < min_span) target = min_span;
+        if (span_class(span()) <= target) return moves;
+        std::vector<int> high;
+        for (int sl : active_)
+            if (sl >= target) high.push_back(sl);
+        auto hole = free_.begin();
+        for (int from : high) {
+            if (hole == free_.end() || *hole >= target) return {};
+            moves.emplace_back(from, *hole++);
+        }
+        return moves;
+    }
+
+    // A running request changes slots (`to` must be free); its id, counters and place in the order of the running
+    // requests go along.
+    void move(int from, int to) {
+        SlotInfo& a = slots_[from];
+        slots_[to] = a;
+        by_id_[a.id] = to;
+        a = SlotInfo();
+        for (size_t i = 0; i < active_.size(); ++i)
+            if (active_[i] == from) active_[i] = to;
+        free_.erase(to);
+        free_.insert(from);
+        dirty_ = true;
     }
 
     const std::vector<int>& active() const { return active_; }

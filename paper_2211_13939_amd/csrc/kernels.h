@@ -40,6 +40,9 @@ hipError_t launch_step(const DevPtrs& d, const StepLaunch& cfg, int cur, hipStre
 
 hipError_t launch_set_live(const DevPtrs& d, const LiveArgs& args, hipStream_t s);
 hipError_t launch_slot_init(const DevPtrs& d, int wdtype, int slot, int L, int n_steps, hipStream_t s);
+// the whole per-slot state of `n` (<= MOVE_BATCH) running requests, each from its slot to a free one; the slots moved
+// from and the slots moved to are disjoint
+hipError_t launch_move_slots(const DevPtrs& d, int wdtype, int mdtype, const MoveArgs& mv, int n, hipStream_t s);
 // F_enc (fp32, device) -> slot memory, and processed memory PM = F W_mem^T
 hipError_t launch_join_memory(const DevPtrs& d, int mdtype, const float* F_dev, int slot, int L, hipStream_t s);
 // the gate pre-sums of one pool tile from activation half `nxt` (after a state overwrite between steps)

@@ -1393,6 +1393,69 @@ __global__ __launch_bounds__(256) void k_slot_init(DevPtrs d, int slot, int L, i
     }
 }
 
+// Running requests move from their slots to free ones (the host packs the pool into fewer slots when that shrinks
+// what the step kernels must span): everything the step carries per slot.  blockIdx.y = which move; no slot is both
+// a source and a destination within one launch.  The step's results do not depend on the slot a request sits in.
+template <typename XT, typename MT>
+__global__ __launch_bounds__(256) void k_move_slots(DevPtrs d, MoveArgs mv)
+{
+    constexpr int KB = Frag<XT>::KB;
+    const int from = mv.from[blockIdx.y], to = mv.to[blockIdx.y], L = mv.L[blockIdx.y], t = mv.t[blockIdx.y];
+    const int tid = blockIdx.x * 256 + threadIdx.x, nth = gridDim.x * 256;
+    const size_t ML = d.max_enc_len;
+    for (int b = 0; b < 2; ++b) {
+        XT* xa = reinterpret_cast<XT*>(d.xatt[b]);
+        XT* xd = reinterpret_cast<XT*>(d.xdec[b]);
+        for (int k = tid; k < K_ATT; k += nth) xa[xoff<XT>(K_ATT / KB, to, k)] = xa[xoff<XT>(K_ATT / KB, from, k)];
+        for (int k = tid; k < K_DEC; k += nth) xd[xoff<XT>(K_DEC / KB, to, k)] = xd[xoff<XT>(K_DEC / KB, from, k)];
+        for (int i = tid; i < L; i += nth) {
+            d.w_last[b][to * ML + i] = d.w_last[b][from * ML + i];
+            d.w_acc[b][to * ML + i] = d.w_acc[b][from * ML + i];
+        }
+    }
+    for (int i = tid; i < HID; i += nth) {
+        d.c_att[(size_t)to * HID + i] = d.c_att[(size_t)from * HID + i];
+        d.c_dec[(size_t)to * HID + i] = d.c_dec[(size_t)from * HID + i];
+    }
+    for (int i = tid; i < N_MEL; i += nth) d.m_last[(size_t)to * N_MEL + i] = d.m_last[(size_t)from * N_MEL + i];
+    // encoder memory, 16 bytes at a time (rows are whole multiples of that)
+    {
+        const uint4* fs = reinterpret_cast<const uint4*>(reinterpret_cast<const MT*>(d.Fmem) + (size_t)from * ML * ENC);
+        uint4* fd = reinterpret_cast<uint4*>(reinterpret_cast<MT*>(d.Fmem) + (size_t)to * ML * ENC);
+        const int nf = L * ENC * (int)sizeof(MT) / 16;
+        for (int i = tid; i < nf; i += nth) fd[i] = fs[i];
+        const uint4* ps = reinterpret_cast<const uint4*>(reinterpret_cast<const MT*>(d.PM) + (size_t)from * ML * ATT);
+        uint4* pd = reinterpret_cast<uint4*>(reinterpret_cast<MT*>(d.PM) + (size_t)to * ML * ATT);
+        const int np = L * ATT * (int)sizeof(MT) / 16;
+        for (int i = tid; i < np; i += nth) pd[i] = ps[i];
+    }
+    // the frames produced so far (some may not have been handed out yet)
+    {
+        const float4* ms = reinterpret_cast<const float4*>(d.mel_ring + (size_t)from * d.max_steps * N_MEL);
+        float4* md = reinterpret_cast<float4*>(d.mel_ring + (size_t)to * d.max_steps * N_MEL);
+        for (int i = tid; i < t * (N_MEL / 4); i += nth) md[i] = ms[i];
+        for (int i = tid; i < t; i += nth) d.stop_ring[(size_t)to * d.max_steps + i] = d.stop_ring[(size_t)from * d.max_steps + i];
+    }
+    // this slot's column of the gate pre-sums (thread = row tile)
+    if (d.pre_att && tid < HID / 4) {
+        const size_t o_from = ((size_t)(from >> 4) * (HID / 4) + tid) * 64 + (from & 15);
+        const size_t o_to = ((size_t)(to >> 4) * (HID / 4) + tid) * 64 + (to & 15);
+        floatx4* pa = reinterpret_cast<floatx4*>(d.pre_att);
+        floatx4* pdc = reinterpret_cast<floatx4*>(d.pre_dec);
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            pa[o_to + 16 * g] = pa[o_from + 16 * g];
+            if (pdc) pdc[o_to + 16 * g] = pdc[o_from + 16 * g];
+        }
+    }
+    if (tid == 0) {
+        d.L[to] = d.L[from];
+        d.t[to] = d.t[from];
+        d.n_steps[to] = d.n_steps[from];
+        d.done[to] = d.done[from];
+    }
+}
+
 // one workgroup per encoder position: store the row, PM[j] = W_mem F[j]
 template <typename MT>
 __global__ __launch_bounds__(ATT) void k_join_memory(DevPtrs d, const float* __restrict__ F, int slot)
@@ -1518,6 +1581,21 @@ hipError_t launch_slot_init(const DevPtrs& d, int wdtype, int slot, int L, int n
 {
     if (wdtype == 0) hipLaunchKernelGGL((k_slot_init<float>), dim3(1), dim3(256), 0, s, d, slot, L, n_steps);
     else hipLaunchKernelGGL((k_slot_init<bf16_t>), dim3(1), dim3(256), 0, s, d, slot, L, n_steps);
+    return hipGetLastError();
+}
+
+hipError_t launch_move_slots(const DevPtrs& d, int wdtype, int mdtype, const MoveArgs& mv, int n, hipStream_t s)
+{
+    if (n < 1 || n > MOVE_BATCH) return hipErrorInvalidValue;
+    for (int i = 0; i < n; ++i)
+        if (mv.from[i] == mv.to[i] || mv.L[i] < 1 || mv.L[i] > d.max_enc_len || mv.t[i] < 0 || mv.t[i] > d.max_steps)
+            return hipErrorInvalidValue;
+    const dim3 g(MOVE_WGS, n), b(256);
+    static_assert(MOVE_WGS * 256 >= HID / 4, "one thread per row tile of the pre-sums");
+    if (wdtype == 0 && mdtype == 0) hipLaunchKernelGGL((k_move_slots<float, float>), g, b, 0, s, d, mv);
+    else if (wdtype == 1 && mdtype == 1) hipLaunchKernelGGL((k_move_slots<bf16_t, bf16_t>), g, b, 0, s, d, mv);
+    else if (wdtype == 1 && mdtype == 0) hipLaunchKernelGGL((k_move_slots<bf16_t, float>), g, b, 0, s, d, mv);
+    else return hipErrorInvalidValue;
     return hipGetLastError();
 }
 

@@ -13,6 +13,7 @@
 #include <memory>
 #include <new>
 #include <string>
+#include <algorithm>
 #include <vector>
 
 #include "book.h"
@@ -223,6 +224,7 @@ struct tts_pool {
     hipStream_t stream = nullptr;
     std::unique_ptr<PoolBook> book;
     int parity = 0;               // activation buffer half the next step reads
+    long long n_moves = 0;        // requests moved to lower slots since creation
     int slot_span = 0;            // highest active slot + 1 (as last uploaded): what the per-slot grids must cover
     bool stop_enabled = false;
     bool timing = false;
@@ -474,17 +476,40 @@ static int lstm_rows_for(int n_blocks) { return n_blocks > 128 ? 4 : (n_blocks >
 // most steps captured into one graph
 static const int MAX_GRAPH_STEPS = 32;
 
-static int bucket_for(int n)
+// Span classes that launch shapes and graphs are keyed by: whole pool tiles, and powers of two within the first tile.
+static int bucket_for(int n) { return PoolBook::span_class(n); }
+
+// The step kernels cover every slot below the highest running one, so after requests have left the pool is packed into
+// fewer pool tiles when that is possible (Sec. 2.2.2 rebuilds its batch tensors every iteration; here a request's
+// state moves only when that shrinks the launch).  Launches over 16 slots and fewer take the same time.
+static const int COMPACT_MIN_SPAN = 16;
+static int compact(tts_pool* p)
 {
-    int b = 1;
-    while (b < n) b <<= 1;
-    return b;
+    const std::vector<std::pair<int, int>> moves = p->book->plan_moves(COMPACT_MIN_SPAN);
+    for (size_t i0 = 0; i0 < moves.size(); i0 += MOVE_BATCH) {
+        MoveArgs mv;
+        memset(&mv, 0, sizeof mv);
+        const int n = (int)std::min(moves.size() - i0, (size_t)MOVE_BATCH);
+        for (int i = 0; i < n; ++i) {
+            const SlotInfo& si = p->book->slot(moves[i0 + i].first);
+            mv.from[i] = moves[i0 + i].first;
+            mv.to[i] = moves[i0 + i].second;
+            mv.L[i] = si.L;
+            mv.t[i] = si.t;
+        }
+        HIP_TRY(launch_move_slots(p->d, p->cfg.weight_dtype, p->cfg.memory_dtype, mv, n, p->stream));
+        for (int i = 0; i < n; ++i) p->book->move(mv.from[i], mv.to[i]);
+        p->n_moves += n;
+    }
+    return TTS_OK;
 }
 
 // Tell the device which slots the next steps advance (only when the membership changed).
 static int push_membership(tts_pool* p)
 {
     if (!p->book->dirty()) return TTS_OK;
+    int rcc = compact(p);
+    if (rcc) return rcc;
     LiveArgs a;
     memset(&a, 0, sizeof a);
     int span = 0;
@@ -746,6 +771,8 @@ extern "C" int tts_pool_frames(tts_pool* p, int64_t id, int* out_frames, int* ou
 
 extern "C" int tts_pool_size(const tts_pool* p) { return p ? p->book->size() : 0; }
 extern "C" int tts_pool_n_active(const tts_pool* p) { return p ? (int)p->book->active().size() : 0; }
+extern "C" int tts_pool_span(const tts_pool* p) { return p ? p->book->span() : 0; }
+extern "C" long long tts_pool_moves(const tts_pool* p) { return p ? p->n_moves : 0; }
 
 extern "C" int tts_pool_sync(tts_pool* p)
 {
@@ -923,6 +950,20 @@ extern "C" int tts_book_drain(tts_book* b, int64_t id, int* out_first, int* out_
     if (out_frames) *out_frames = count;
     if (out_finished) *out_finished = fin;
     return TTS_OK;
+}
+
+extern "C" int tts_book_slot(const tts_book* b, int64_t id) { return b ? b->book.find(id) : -1; }
+
+extern "C" int tts_book_compact(tts_book* b, int min_span, int* out_from, int* out_to, int cap)
+{
+    if (!b || cap < 0 || (cap > 0 && (!out_from || !out_to))) return fail(TTS_E_INVAL, "null argument");
+    int n = 0;
+    for (const std::pair<int, int>& m : b->book.plan_moves(min_span)) {
+        if (n < cap) { out_from[n] = m.first; out_to[n] = m.second; }
+        b->book.move(m.first, m.second);
+        ++n;
+    }
+    return n;
 }
 
 extern "C" int tts_book_retire(tts_book* b, int64_t id)

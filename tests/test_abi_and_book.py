@@ -146,3 +146,56 @@ def test_encoder_config_validation_without_gpu():
         assert binding.encoder_workspace_bytes(c) == 0, field
     c = binding.make_encoder_config(max_tokens=600, max_len=300, vocab=(128, 0, 4, 4))
     assert binding.encoder_workspace_bytes(c) == 0
+
+
+def test_book_packs_running_requests_into_a_smaller_span():
+    """After requests leave, the running ones move into free low slots when that brings them into a smaller
+    power-of-two span; ids, frame counters and the order of the running requests go along."""
+    b = binding.Book(64, 100, 50, 8)
+    ids = [b.add(10, 50 if i % 3 == 0 else 3) for i in range(60)]
+    assert [b.slot(r) for r in ids] == list(range(60))
+    for _ in range(3):
+        b.step()
+    assert b.compact() == []                      # the finished requests still hold their slots
+    for i, r in enumerate(ids):
+        if i % 3:
+            assert b.drain(r) == (0, 3, True)
+            b.retire(r)
+    long_ids = ids[::3]                           # 20 requests in slots 0, 3, ..., 57
+    moves = b.compact()
+    # 20 requests fit the class of 32: those in slots 33..57 go to the lowest free slots, in order
+    assert moves == list(zip(range(33, 58, 3), [1, 2, 4, 5, 7, 8, 10, 11, 13]))
+    assert [b.slot(r) for r in long_ids] == list(range(0, 33, 3)) + [1, 2, 4, 5, 7, 8, 10, 11, 13]
+    assert b.compact() == []                      # nothing further to gain
+    assert b.step() == long_ids                   # same requests, same order
+    assert b.drain(long_ids[-1]) == (0, 0, False)  # 4 of 8 frames
+    for _ in range(4):
+        b.step()
+    assert b.drain(long_ids[-1]) == (0, 8, False)
+    # a new request takes the lowest free slot
+    assert b.slot(b.add(5, 5)) == 14
+    # 21 running: class 32 still; retire the nine that moved -> 12 running, class 16, everything above slot 15 moves
+    for r in long_ids[11:]:
+        b.retire(r)
+    assert b.compact() == list(zip([18, 21, 24, 27, 30], [1, 2, 4, 5, 7]))
+    assert max(b.slot(r) for r in long_ids[:11]) < 16
+    # spans of `min_span` and fewer are left alone
+    for r in long_ids[:4]:
+        b.retire(r)                               # slots 0, 3, 6, 9 free; 8 running, the highest in slot 15
+    assert b.compact() == []
+    assert b.compact(min_span=2) != []
+    b.close()
+
+
+def test_book_does_not_move_when_free_slots_do_not_suffice():
+    b = binding.Book(64, 100, 50, 8)
+    ids = [b.add(10, 50 if i >= 40 else 2) for i in range(64)]
+    b.step(); b.step()
+    for r in ids[:10]:
+        b.retire(r)                               # 24 running in slots 40..63, but only 10 free slots below 32
+    assert b.compact() == []
+    for r in ids[10:40]:
+        b.retire(r)
+    assert len(b.compact()) == 24
+    assert sorted(b.slot(r) for r in ids[40:]) == list(range(24))
+    b.close()

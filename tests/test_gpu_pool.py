@@ -434,3 +434,54 @@ def test_large_attention_vector_takes_the_two_pass_softmax(weights_fp32):
     err = max_err(gpu, ref)
     say(f"  max abs err {err:.3e}")
     assert err <= TOL_F32
+
+
+@pytest.mark.parametrize("bf16,max_pool,n_req", [(True, 64, 60), (False, 64, 44), (True, 160, 150), (False, 100, 90)])
+def test_requests_move_to_lower_slots_when_the_pool_shrinks(bf16, max_pool, n_req, weights_bf16, weights_fp32):
+    """Two of every three requests end after 6 steps and are retired; the others, scattered over all
+    tiles, are moved into the freed low slots before the next step (first into half the span or
+    less, later, after more of them left, further down) and carry on: their frames, those produced
+    before a move but handed out after it included, are bit for bit the frames of a pool in which
+    nobody leaves or moves, and their recurrent state reads back the same."""
+    weights = weights_bf16 if bf16 else weights_fp32
+    wl = synth.small_workload(n_req, 10, 120, 30, 30, seed=83, bf16=bf16)
+    say(f"case capacity {max_pool}, {'bf16' if bf16 else 'fp32'}: {n_req} requests, two of three leave after 6 steps")
+    stay = list(range(0, n_req, 3))
+    ref = gpu_decode(wl, weights, list(range(n_req)), 30, max_pool=max_pool, chunk_frames=8)
+    still = make_pool(wl, weights, max_pool=max_pool, max_steps=30, chunk_frames=8)
+    still_ids = [still.add_request(wl.encoder_outputs(i), 30) for i in range(n_req)]
+    still.step_n(10)
+    assert still.moves() == 0 and still.span() == n_req
+
+    pool = make_pool(wl, weights, max_pool=max_pool, max_steps=30, chunk_frames=8)
+    ids = [pool.add_request(wl.encoder_outputs(i), 30 if i in stay else 6) for i in range(n_req)]
+    pool.step_n(6)
+    for i, rid in enumerate(ids):
+        if i not in stay:
+            np.testing.assert_array_equal(_drain(pool, rid), ref[i, :6])
+            pool.retire(rid)
+    assert pool.moves() == 0 and pool.span() == stay[-1] + 1
+    pool.step_n(4)                                # the move happens here, with 6 frames waiting in each ring
+    small = 1 << (len(stay) - 1).bit_length()
+    assert pool.moves() > 0 and pool.span() <= small < n_req
+    got = {i: [pool.drain_chunk(ids[i])[0].copy()] for i in stay}      # frames 0..7
+    for name in ("m", "a", "w_last", "w_acc", "h_att", "c_att", "h_dec", "c_dec"):
+        for i in (stay[0], stay[-1]):
+            np.testing.assert_array_equal(pool.get_state(ids[i], name), still.get_state(still_ids[i], name))
+    still.close()
+    # a second round of leaving: only every fourth of the rest stays
+    moves = pool.moves()
+    for k, i in enumerate(stay):
+        if k % 4:
+            pool.retire(ids[i])
+    last = stay[::4]
+    pool.step_n(20)
+    if small > 16:
+        assert pool.moves() > moves and pool.span() <= max(16, small // 4)
+    for i in last:
+        got[i].append(_drain(pool, ids[i]))
+        np.testing.assert_array_equal(np.concatenate(got[i]), ref[i])
+    for i in stay:
+        if i not in last:
+            np.testing.assert_array_equal(got[i][0], ref[i, :8])
+    pool.close()
