@@ -78,7 +78,7 @@ def run_job(pool, wl, enc_dev, n_steps_total, pos=0):
     state = run_job.state
     while done < n_steps_total:
         if pos == 0:
-            state["ids"] = [pool.add_request(enc_dev[i], int(n[i])) for i in range(wl.n_requests)]
+            state["ids"] = pool.add_requests(enc_dev, [int(x) for x in n])
             state["next_fin"] = 0
         ids, k = state["ids"], state["next_fin"]
         seg = min(wl.chunk_frames, horizon - pos, n_steps_total - done)

@@ -122,6 +122,15 @@ int tts_pool_create(const tts_config *cfg, const tts_weights *weights,
 int tts_pool_add_request(tts_pool *pool, const float *enc_out, int L, int n_steps, int64_t *out_id);
 
 /*
+ * Add `n` requests at once: an iteration of the pool takes every request that is waiting (Sec. 2.2.2).  Same
+ * result, bit for bit, as `n` calls of tts_pool_add_request in this order (enc_out[i], L[i], n_steps[i] -> out_ids[i],
+ * each buffer HOST or DEVICE memory), but requests whose encoder outputs are in device memory are set up by one
+ * launch per 64 of them.  Arguments and room are checked first: on TTS_E_INVAL or TTS_E_FULL nothing was added.
+ */
+int tts_pool_add_requests(tts_pool *pool, int n, const float *const *enc_out, const int *L, const int *n_steps,
+                          int64_t *out_ids);
+
+/*
  * One decoder step: every unfinished request in the pool produces one more
  * mel frame (Eq. 2).  Asynchronous on the pool's stream.  *out_n_active (may
  * be NULL) receives the number of requests advanced; 0 on an empty pool, which

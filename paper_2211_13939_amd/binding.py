@@ -30,7 +30,7 @@ WEIGHT_FIELDS = ("prenet1", "prenet2", "att_w_ih", "att_w_hh", "att_b", "q_w", "
 
 # every symbol include/tts_pool.h declares
 EXPORTS = (
-    "tts_pool_workspace_bytes", "tts_pool_create", "tts_pool_add_request", "tts_pool_step",
+    "tts_pool_workspace_bytes", "tts_pool_create", "tts_pool_add_request", "tts_pool_add_requests", "tts_pool_step",
     "tts_pool_step_n", "tts_pool_drain_chunk", "tts_pool_get_stop_logits", "tts_pool_retire",
     "tts_pool_get_state", "tts_pool_set_state", "tts_pool_frames", "tts_pool_size", "tts_pool_n_active",
     "tts_pool_span", "tts_pool_moves",
@@ -115,6 +115,7 @@ def lib() -> C.CDLL:
     L.tts_pool_workspace_bytes.argtypes = [C.POINTER(TtsConfig)]
     L.tts_pool_create.argtypes = [C.POINTER(TtsConfig), C.POINTER(TtsWeights), vp, C.c_size_t, vp, C.POINTER(vp)]
     L.tts_pool_add_request.argtypes = [vp, vp, C.c_int, C.c_int, _i64p]
+    L.tts_pool_add_requests.argtypes = [vp, C.c_int, C.POINTER(vp), _ip, _ip, _i64p]
     L.tts_pool_step.argtypes = [vp, _ip]
     L.tts_pool_step_n.argtypes = [vp, C.c_int, _i64p]
     L.tts_pool_drain_chunk.argtypes = [vp, C.c_int64, _fp, _ip, _ip]
@@ -240,6 +241,25 @@ class Pool:
             ptr, L = a.data_ptr(), a.shape[0]
         _check(lib().tts_pool_add_request(self._h, C.c_void_p(ptr), int(L), int(n_steps), C.byref(rid)))
         return rid.value
+
+    def add_requests(self, enc_outs, n_steps) -> list:
+        """Several requests in one call; each enc_out as in add_request."""
+        n = len(enc_outs)
+        keep, ptrs, Ls = [], (C.c_void_p * max(n, 1))(), (C.c_int * max(n, 1))()
+        for i, e in enumerate(enc_outs):
+            if isinstance(e, np.ndarray):
+                a = np.ascontiguousarray(e, dtype=np.float32)
+                ptrs[i] = a.ctypes.data
+            else:
+                a = e.contiguous()
+                assert a.is_cuda and a.dtype == self._torch.float32
+                ptrs[i] = a.data_ptr()
+            Ls[i] = a.shape[0]
+            keep.append(a)
+        ns = (C.c_int * max(n, 1))(*[int(x) for x in n_steps])
+        ids = (C.c_int64 * max(n, 1))()
+        _check(lib().tts_pool_add_requests(self._h, n, ptrs, Ls, ns, ids))
+        return [ids[i] for i in range(n)]
 
     def add_request_raw(self, ptr: int, L: int, n_steps: int) -> int:
         rid = C.c_int64()

@@ -95,4 +95,12 @@ struct MoveArgs {
     int from[MOVE_BATCH], to[MOVE_BATCH], L[MOVE_BATCH], t[MOVE_BATCH];
 };
 
+// one launch's worth of joining requests (kernel argument): encoder outputs F[i] (fp32 [L][ENC], device) go to slot[i]
+constexpr int JOIN_BATCH = 64;
+constexpr int JOIN_POS = 8;      // encoder positions per workgroup
+struct JoinArgs {
+    const float* F[JOIN_BATCH];
+    int slot[JOIN_BATCH], L[JOIN_BATCH], n_steps[JOIN_BATCH];
+};
+
 }  // namespace tts

@@ -39,12 +39,11 @@ constexpr int N_STEP_KERNELS = 4;
 hipError_t launch_step(const DevPtrs& d, const StepLaunch& cfg, int cur, hipStream_t s, hipEvent_t* ev = nullptr);
 
 hipError_t launch_set_live(const DevPtrs& d, const LiveArgs& args, hipStream_t s);
-hipError_t launch_slot_init(const DevPtrs& d, int wdtype, int slot, int L, int n_steps, hipStream_t s);
 // the whole per-slot state of `n` (<= MOVE_BATCH) running requests, each from its slot to a free one; the slots moved
 // from and the slots moved to are disjoint
 hipError_t launch_move_slots(const DevPtrs& d, int wdtype, int mdtype, const MoveArgs& mv, int n, hipStream_t s);
-// F_enc (fp32, device) -> slot memory, and processed memory PM = F W_mem^T
-hipError_t launch_join_memory(const DevPtrs& d, int mdtype, const float* F_dev, int slot, int L, hipStream_t s);
+// `n` (<= JOIN_BATCH) requests join: state zeroed, F_enc (fp32, device) -> slot memory, processed memory PM = F W_mem^T
+hipError_t launch_join(const DevPtrs& d, int wdtype, int mdtype, const JoinArgs& ja, int n, hipStream_t s);
 // the gate pre-sums of one pool tile from activation half `nxt` (after a state overwrite between steps)
 hipError_t launch_presum_tile(const DevPtrs& d, int wdtype, int tile, int nxt, hipStream_t s);
 // p = Pre(m_last) into both activation buffers of one slot (after a state overwrite)

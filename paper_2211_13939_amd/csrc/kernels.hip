@@ -1351,12 +1351,11 @@ __global__ __launch_bounds__(MAX_POOL) void k_set_live(LiveArgs a, int* live)
     live[tid] = (a.bits[tid >> 5] >> (tid & 31)) & 1u;
 }
 
-// a joining request starts from all-zero state
+// a joining request starts from all-zero state (one workgroup of 256 threads)
 template <typename XT>
-__global__ __launch_bounds__(256) void k_slot_init(DevPtrs d, int slot, int L, int n_steps)
+__device__ __forceinline__ void slot_init(const DevPtrs& d, int slot, int L, int n_steps, int tid)
 {
     constexpr int KB = Frag<XT>::KB;
-    const int tid = threadIdx.x;
     const XT z = from_float<XT>(0.f);
     for (int b = 0; b < 2; ++b) {
         XT* xa = reinterpret_cast<XT*>(d.xatt[b]);
@@ -1456,22 +1455,42 @@ __global__ __launch_bounds__(256) void k_move_slots(DevPtrs d, MoveArgs mv)
     }
 }
 
-// one workgroup per encoder position: store the row, PM[j] = W_mem F[j]
-template <typename MT>
-__global__ __launch_bounds__(ATT) void k_join_memory(DevPtrs d, const float* __restrict__ F, int slot)
+// Requests join (blockIdx.y = which): workgroup 0 of a request zeroes its state, workgroup 1 + b takes encoder
+// positions 8 b .. 8 b + 7: stores the rows in the memory's type and forms PM[j] = W_mem F[j] in fp32 (thread = one
+// attention dimension of four positions, so that a column of W_mem^T is pulled once for eight positions).
+template <typename XT, typename MT>
+__global__ __launch_bounds__(256) void k_join(DevPtrs d, JoinArgs ja)
 {
-    const int j = blockIdx.x, tid = threadIdx.x;
-    __shared__ float s_f[ENC];
-    MT* Fm = reinterpret_cast<MT*>(d.Fmem) + ((size_t)slot * d.max_enc_len + j) * ENC;
-    for (int k = tid; k < ENC; k += ATT) {
-        const float x = F[(size_t)j * ENC + k];
-        s_f[k] = x;
-        Fm[k] = from_float<MT>(x);
+    const int r = blockIdx.y, tid = threadIdx.x;
+    const int slot = ja.slot[r], L = ja.L[r];
+    if (blockIdx.x == 0) {
+        slot_init<XT>(d, slot, L, ja.n_steps[r], tid);
+        return;
+    }
+    const int j0 = (blockIdx.x - 1) * JOIN_POS;
+    if (j0 >= L) return;
+    const int np = min(JOIN_POS, L - j0);
+    const float* __restrict__ F = ja.F[r] + (size_t)j0 * ENC;
+    __shared__ float s_f[JOIN_POS][ENC];
+    MT* Fm = reinterpret_cast<MT*>(d.Fmem) + ((size_t)slot * d.max_enc_len + j0) * ENC;
+    for (int i = tid; i < JOIN_POS * ENC; i += 256) {
+        const float x = i < np * ENC ? F[i] : 0.f;
+        s_f[i / ENC][i % ENC] = x;
+        if (i < np * ENC) Fm[i] = from_float<MT>(x);
     }
     __syncthreads();
-    float acc = 0.f;
-    for (int k = 0; k < ENC; ++k) acc += d.WmemT[k * ATT + tid] * s_f[k];
-    reinterpret_cast<MT*>(d.PM)[((size_t)slot * d.max_enc_len + j) * ATT + tid] = from_float<MT>(acc);
+    const int a = tid & (ATT - 1), h = tid / ATT;
+    static_assert(256 / ATT * 4 == JOIN_POS, "two halves of the workgroup, four positions each");
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int k = 0; k < ENC; ++k) {
+        const float w = d.WmemT[k * ATT + a];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) acc[q] += w * s_f[4 * h + q][k];
+    }
+    MT* pm = reinterpret_cast<MT*>(d.PM) + ((size_t)slot * d.max_enc_len + j0) * ATT;
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+        if (4 * h + q < np) pm[(4 * h + q) * ATT + a] = from_float<MT>(acc[q]);
 }
 
 // gather / scatter of one slot's piece of a slot-tiled activation array (state access, not on the step path)
@@ -1577,13 +1596,6 @@ hipError_t launch_set_live(const DevPtrs& d, const LiveArgs& args, hipStream_t s
     return hipGetLastError();
 }
 
-hipError_t launch_slot_init(const DevPtrs& d, int wdtype, int slot, int L, int n_steps, hipStream_t s)
-{
-    if (wdtype == 0) hipLaunchKernelGGL((k_slot_init<float>), dim3(1), dim3(256), 0, s, d, slot, L, n_steps);
-    else hipLaunchKernelGGL((k_slot_init<bf16_t>), dim3(1), dim3(256), 0, s, d, slot, L, n_steps);
-    return hipGetLastError();
-}
-
 hipError_t launch_move_slots(const DevPtrs& d, int wdtype, int mdtype, const MoveArgs& mv, int n, hipStream_t s)
 {
     if (n < 1 || n > MOVE_BATCH) return hipErrorInvalidValue;
@@ -1599,10 +1611,19 @@ hipError_t launch_move_slots(const DevPtrs& d, int wdtype, int mdtype, const Mov
     return hipGetLastError();
 }
 
-hipError_t launch_join_memory(const DevPtrs& d, int mdtype, const float* F_dev, int slot, int L, hipStream_t s)
+hipError_t launch_join(const DevPtrs& d, int wdtype, int mdtype, const JoinArgs& ja, int n, hipStream_t s)
 {
-    if (mdtype == 0) hipLaunchKernelGGL((k_join_memory<float>), dim3(L), dim3(ATT), 0, s, d, F_dev, slot);
-    else hipLaunchKernelGGL((k_join_memory<bf16_t>), dim3(L), dim3(ATT), 0, s, d, F_dev, slot);
+    if (n < 1 || n > JOIN_BATCH) return hipErrorInvalidValue;
+    int Lmax = 0;
+    for (int i = 0; i < n; ++i) {
+        if (!ja.F[i] || ja.L[i] < 1 || ja.L[i] > d.max_enc_len || ja.slot[i] < 0 || ja.slot[i] >= MAX_POOL) return hipErrorInvalidValue;
+        Lmax = ja.L[i] > Lmax ? ja.L[i] : Lmax;
+    }
+    const dim3 g(1 + (Lmax + JOIN_POS - 1) / JOIN_POS, n), b(256);
+    if (wdtype == 0 && mdtype == 0) hipLaunchKernelGGL((k_join<float, float>), g, b, 0, s, d, ja);
+    else if (wdtype == 1 && mdtype == 1) hipLaunchKernelGGL((k_join<bf16_t, bf16_t>), g, b, 0, s, d, ja);
+    else if (wdtype == 1 && mdtype == 0) hipLaunchKernelGGL((k_join<bf16_t, float>), g, b, 0, s, d, ja);
+    else return hipErrorInvalidValue;
     return hipGetLastError();
 }
 

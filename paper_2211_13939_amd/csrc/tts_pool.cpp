@@ -434,34 +434,61 @@ extern "C" void tts_pool_destroy(tts_pool* p)
     delete p;
 }
 
+static bool is_device_pointer(const void* ptr)
+{
+    hipPointerAttribute_t attr;
+    if (hipPointerGetAttributes(&attr, ptr) == hipSuccess) return attr.type == hipMemoryTypeDevice;
+    (void)hipGetLastError();
+    return false;
+}
+
+extern "C" int tts_pool_add_requests(tts_pool* p, int n, const float* const* enc_out, const int* L, const int* n_steps, int64_t* out_ids)
+{
+    if (!p || n < 0 || (n > 0 && (!enc_out || !L || !n_steps || !out_ids))) return fail(TTS_E_INVAL, "null argument");
+    for (int i = 0; i < n; ++i) {
+        if (!enc_out[i]) return fail(TTS_E_INVAL, "request %d: null encoder output", i);
+        if (L[i] < 1 || L[i] > p->cfg.max_enc_len) return fail(TTS_E_INVAL, "request %d: L = %d outside 1..%d", i, L[i], p->cfg.max_enc_len);
+        if (n_steps[i] < 1 || n_steps[i] > p->cfg.max_steps)
+            return fail(TTS_E_INVAL, "request %d: n_steps = %d outside 1..%d", i, n_steps[i], p->cfg.max_steps);
+    }
+    if (p->book->size() + n > p->cfg.max_pool)
+        return fail(TTS_E_FULL, "pool holds %d of max_pool = %d requests, %d more do not fit", p->book->size(), p->cfg.max_pool, n);
+
+    JoinArgs ja;
+    memset(&ja, 0, sizeof ja);
+    int nb = 0;
+    auto flush = [&]() -> int {
+        if (nb) HIP_TRY(launch_join(p->d, p->cfg.weight_dtype, p->cfg.memory_dtype, ja, nb, p->stream));
+        nb = 0;
+        return TTS_OK;
+    };
+    for (int i = 0; i < n; ++i) {
+        const bool on_device = is_device_pointer(enc_out[i]);
+        int slot;
+        int rc = p->book->add(L[i], n_steps[i], &out_ids[i], &slot);
+        if (rc) return fail(rc == -2 ? TTS_E_FULL : TTS_E_INVAL, "request rejected");
+        if (!on_device) {
+            // one staging buffer: what is queued goes first, then this request alone; the caller may free a host
+            // buffer on return, so the copy is finished before returning
+            if ((rc = flush())) return rc;
+            HIP_TRY(hipMemcpyAsync(p->d.stage, enc_out[i], (size_t)L[i] * ENC * 4, hipMemcpyHostToDevice, p->stream));
+            HIP_TRY(hipStreamSynchronize(p->stream));
+        }
+        ja.F[nb] = on_device ? enc_out[i] : p->d.stage;
+        ja.slot[nb] = slot;
+        ja.L[nb] = L[i];
+        ja.n_steps[nb] = n_steps[i];
+        ++nb;
+        if (!on_device || nb == JOIN_BATCH)
+            if ((rc = flush())) return rc;
+    }
+    return flush();
+}
+
 extern "C" int tts_pool_add_request(tts_pool* p, const float* enc_out, int L, int n_steps, int64_t* out_id)
 {
     if (!p || !enc_out || !out_id) return fail(TTS_E_INVAL, "null argument");
-    if (L < 1 || L > p->cfg.max_enc_len) return fail(TTS_E_INVAL, "L = %d outside 1..%d", L, p->cfg.max_enc_len);
-    if (n_steps < 1 || n_steps > p->cfg.max_steps)
-        return fail(TTS_E_INVAL, "n_steps = %d outside 1..%d", n_steps, p->cfg.max_steps);
-    if (p->book->size() >= p->cfg.max_pool) return fail(TTS_E_FULL, "pool holds max_pool = %d requests", p->cfg.max_pool);
-
-    hipPointerAttribute_t attr;
-    bool on_device = false;
-    if (hipPointerGetAttributes(&attr, enc_out) == hipSuccess) on_device = attr.type == hipMemoryTypeDevice;
-    else (void)hipGetLastError();
-
-    const float* F_dev = enc_out;
-    if (!on_device) {
-        // the caller may free a host buffer on return: finish the copy before returning
-        HIP_TRY(hipMemcpyAsync(p->d.stage, enc_out, (size_t)L * ENC * 4, hipMemcpyHostToDevice, p->stream));
-        HIP_TRY(hipStreamSynchronize(p->stream));
-        F_dev = p->d.stage;
-    }
-    int64_t id;
-    int slot;
-    int rc = p->book->add(L, n_steps, &id, &slot);
-    if (rc) return fail(rc == -2 ? TTS_E_FULL : TTS_E_INVAL, "request rejected");
-    HIP_TRY(launch_slot_init(p->d, p->cfg.weight_dtype, slot, L, n_steps, p->stream));
-    HIP_TRY(launch_join_memory(p->d, p->cfg.memory_dtype, F_dev, slot, L, p->stream));
-    *out_id = id;
-    return TTS_OK;
+    return tts_pool_add_requests(p, 1, &enc_out, &L, &n_steps, out_id);
 }
 
 // workgroups per request in the attention kernel: more when the pool alone cannot fill the chip

@@ -485,3 +485,45 @@ def test_requests_move_to_lower_slots_when_the_pool_shrinks(bf16, max_pool, n_re
         if i not in last:
             np.testing.assert_array_equal(got[i][0], ref[i, :8])
     pool.close()
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+def test_joining_together_equals_joining_one_by_one(bf16, weights_bf16, weights_fp32):
+    """tts_pool_add_requests: 70 requests at once (two launches; encoder outputs in device memory, every
+    seventh in host memory, lengths 1, 7, 8, 9 and the maximum among them) against the same requests
+    added one call at a time: identical frames and attention state.  Nothing is added when one of the
+    requests is invalid or the pool lacks room."""
+    import torch
+    weights = weights_bf16 if bf16 else weights_fp32
+    wl = synth.small_workload(70, 10, 200, 12, 12, seed=91, bf16=bf16)
+    wl.enc_len[:5] = [1, 7, 8, 9, 200]
+    say(f"case: 70 requests join in one call, {'bf16' if bf16 else 'fp32'}")
+    encs = [wl.encoder_outputs(i) for i in range(70)]
+    mixed = [e if i % 7 == 3 else torch.from_numpy(e).cuda() for i, e in enumerate(encs)]
+    kw = dict(max_pool=80, max_enc_len=200, max_steps=12, chunk_frames=12)
+    one = make_pool(wl, weights, **kw)
+    ids_one = [one.add_request(e, 12) for e in mixed]
+    many = make_pool(wl, weights, **kw)
+    with pytest.raises(binding.TtsError) as ei:
+        many.add_requests(mixed + mixed[:11], [12] * 81)
+    assert ei.value.code == binding.TTS_E_FULL and many.size() == 0
+    with pytest.raises(binding.TtsError) as ei:
+        many.add_requests(mixed[:3], [12, 13, 12])
+    assert ei.value.code == binding.TTS_E_INVAL and many.size() == 0
+    assert many.add_requests([], []) == []
+    ids_many = many.add_requests(mixed, [12] * 70)
+    assert many.size() == 70 and len(set(ids_many)) == 70
+    for pool in (one, many):
+        pool.step_n(12)
+    for a, b in zip(ids_one, ids_many):
+        np.testing.assert_array_equal(_drain(one, a), _drain(many, b))
+    for i in (0, 3, 4, 69):
+        np.testing.assert_array_equal(one.get_state(ids_one[i], "w_acc"), many.get_state(ids_many[i], "w_acc"))
+    ref, _, _ = oracle_decode(wl, weights, [0, 2, 3, 4, 66], 12, n_threads=5)
+    many2 = make_pool(wl, weights, **kw)
+    ids2 = many2.add_requests(mixed, [12] * 70)
+    many2.step_n(12)
+    for k, i in enumerate([0, 2, 3, 4, 66]):
+        assert np.abs(_drain(many2, ids2[i]) - ref[k]).max() <= (TOL_BF16 if bf16 else TOL_F32)
+    for pool in (one, many, many2):
+        pool.close()
