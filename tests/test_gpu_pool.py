@@ -396,27 +396,32 @@ def test_steps_beside_other_work_on_the_gpu(wl8, weights_fp32, solo_frames):
 
 
 def test_c3_shrinking_pool_full_job(weights_bf16):
-    """The whole c3 job as the benchmark runs it (requests retire at their own
-    end): every request produces exactly its frame count, sampled requests match
-    the oracle over their first 50 frames and stay finite to the end."""
+    """The whole c3 job as the benchmark runs it (all requests join in one call, requests retire at
+    their own end, the running ones are packed into fewer tiles as the pool shrinks): every request
+    produces exactly its frame count, sampled requests match the oracle over their first 50 frames
+    and, to their last frame, the bits of the same request decoded alone (which never moves)."""
     wl = synth.workload("c3")
     say("case c3: full job, 64 requests, pool shrinks")
     pool = make_pool(wl, weights_bf16)
-    ids = [pool.add_request(wl.encoder_outputs(i), int(wl.n_steps[i])) for i in range(64)]
+    ids = pool.add_requests([wl.encoder_outputs(i) for i in range(64)], [int(x) for x in wl.n_steps])
+    longest = int(np.argmax(wl.n_steps))
+    sample = sorted({3, 30, 59, longest})
     total = 0
     while pool.n_active():
         total += pool.step_n(40)
         for i, rid in enumerate(ids):
-            if rid is not None and pool.frames(rid)[1] and i not in (3, 30, 59):
+            if rid is not None and pool.frames(rid)[1] and i not in sample:
                 pool.retire(rid)
                 ids[i] = None
     assert total == int(wl.n_steps.sum())
-    sample = [3, 30, 59]
-    ref, _, _ = oracle_decode(wl, weights_bf16, sample, 50, n_threads=3)
+    assert pool.moves() > 0
+    ref, _, _ = oracle_decode(wl, weights_bf16, sample, 50, n_threads=4)
     for k, i in enumerate(sample):
         got = _drain(pool, ids[i])
         assert got.shape[0] == wl.n_steps[i] and np.isfinite(got).all()
         assert np.abs(got[:50] - ref[k]).max() <= TOL_BF16
+        alone = gpu_decode(wl, weights_bf16, [i], int(wl.n_steps[i]), max_pool=64)[0]
+        np.testing.assert_array_equal(got, alone)
     pool.close()
 
 
