@@ -90,7 +90,7 @@ struct LiveArgs {
 // one launch's worth of slot moves (kernel argument): request i goes from slot from[i] to slot to[i]; L = its encoder
 // length, t = frames it has produced so far (an upper bound is fine)
 constexpr int MOVE_BATCH = 32;
-constexpr int MOVE_WGS = 16;     // workgroups per move
+constexpr int MOVE_WGS = 32;     // workgroups per move
 struct MoveArgs {
     int from[MOVE_BATCH], to[MOVE_BATCH], L[MOVE_BATCH], t[MOVE_BATCH];
 };

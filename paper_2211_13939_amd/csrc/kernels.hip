@@ -1456,8 +1456,9 @@ __global__ __launch_bounds__(256) void k_move_slots(DevPtrs d, MoveArgs mv)
 }
 
 // Requests join (blockIdx.y = which): workgroup 0 of a request zeroes its state, workgroup 1 + b takes encoder
-// positions 8 b .. 8 b + 7: stores the rows in the memory's type and forms PM[j] = W_mem F[j] in fp32 (thread = one
-// attention dimension of four positions, so that a column of W_mem^T is pulled once for eight positions).
+// positions 8 b .. 8 b + 7: stores the rows in the memory's type and forms PM[j] = W_mem F[j] in fp32.  A thread
+// takes four attention dimensions and one eighth of K for all eight positions (a 16-byte piece of W_mem^T per k,
+// pulled once for eight positions); the eight partial sums of an entry are added in the order of K.
 template <typename XT, typename MT>
 __global__ __launch_bounds__(256) void k_join(DevPtrs d, JoinArgs ja)
 {
@@ -1471,7 +1472,10 @@ __global__ __launch_bounds__(256) void k_join(DevPtrs d, JoinArgs ja)
     if (j0 >= L) return;
     const int np = min(JOIN_POS, L - j0);
     const float* __restrict__ F = ja.F[r] + (size_t)j0 * ENC;
+    constexpr int KG = 8, KPG = ENC / KG;         // K groups, k per group
+    static_assert(256 == KG * (ATT / 4), "a thread = (K group, four attention dimensions)");
     __shared__ float s_f[JOIN_POS][ENC];
+    __shared__ float4 s_p[KG][JOIN_POS][ATT / 4];
     MT* Fm = reinterpret_cast<MT*>(d.Fmem) + ((size_t)slot * d.max_enc_len + j0) * ENC;
     for (int i = tid; i < JOIN_POS * ENC; i += 256) {
         const float x = i < np * ENC ? F[i] : 0.f;
@@ -1479,18 +1483,41 @@ __global__ __launch_bounds__(256) void k_join(DevPtrs d, JoinArgs ja)
         if (i < np * ENC) Fm[i] = from_float<MT>(x);
     }
     __syncthreads();
-    const int a = tid & (ATT - 1), h = tid / ATT;
-    static_assert(256 / ATT * 4 == JOIN_POS, "two halves of the workgroup, four positions each");
-    float acc[4] = {0.f, 0.f, 0.f, 0.f};
-    for (int k = 0; k < ENC; ++k) {
-        const float w = d.WmemT[k * ATT + a];
+    const int a4 = tid & (ATT / 4 - 1), kg = tid / (ATT / 4);
+    const float4* __restrict__ W4 = reinterpret_cast<const float4*>(d.WmemT) + (size_t)kg * KPG * (ATT / 4) + a4;
+    float4 acc[JOIN_POS];
 #pragma unroll
-        for (int q = 0; q < 4; ++q) acc[q] += w * s_f[4 * h + q][k];
+    for (int q = 0; q < JOIN_POS; ++q) acc[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll 8
+    for (int k = 0; k < KPG; ++k) {
+        const float4 w = W4[(size_t)k * (ATT / 4)];
+#pragma unroll
+        for (int q = 0; q < JOIN_POS; ++q) {
+            const float f = s_f[q][kg * KPG + k];
+            acc[q].x += w.x * f;
+            acc[q].y += w.y * f;
+            acc[q].z += w.z * f;
+            acc[q].w += w.w * f;
+        }
     }
-    MT* pm = reinterpret_cast<MT*>(d.PM) + ((size_t)slot * d.max_enc_len + j0) * ATT;
 #pragma unroll
-    for (int q = 0; q < 4; ++q)
-        if (4 * h + q < np) pm[(4 * h + q) * ATT + a] = from_float<MT>(acc[q]);
+    for (int q = 0; q < JOIN_POS; ++q) s_p[kg][q][a4] = acc[q];
+    __syncthreads();
+    // thread = (position q, attention dimensions 4 a4 .. 4 a4 + 3)
+    const int q = tid / (ATT / 4);
+    float4 t = s_p[0][q][a4];
+#pragma unroll
+    for (int g = 1; g < KG; ++g) {
+        const float4 u = s_p[g][q][a4];
+        t.x += u.x; t.y += u.y; t.z += u.z; t.w += u.w;
+    }
+    if (q < np) {
+        MT* pm = reinterpret_cast<MT*>(d.PM) + ((size_t)slot * d.max_enc_len + j0 + q) * ATT + 4 * a4;
+        pm[0] = from_float<MT>(t.x);
+        pm[1] = from_float<MT>(t.y);
+        pm[2] = from_float<MT>(t.z);
+        pm[3] = from_float<MT>(t.w);
+    }
 }
 
 // gather / scatter of one slot's piece of a slot-tiled activation array (state access, not on the step path)
