@@ -1392,66 +1392,105 @@ __device__ __forceinline__ void slot_init(const DevPtrs& d, int slot, int L, int
     }
 }
 
+// n 16-byte (or 4-byte) pieces from src to dst, four strided pieces per thread in flight
+template <typename V>
+__device__ __forceinline__ void copy_strided(V* __restrict__ dst, const V* __restrict__ src, int n, int tid, int nth)
+{
+    for (int i0 = tid; i0 < n; i0 += 4 * nth) {
+        V v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) v[u] = src[min(i0 + u * nth, n - 1)];
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (i0 + u * nth < n) dst[i0 + u * nth] = v[u];
+    }
+}
+
 // Running requests move from their slots to free ones (the host packs the pool into fewer slots when that shrinks
 // what the step kernels must span): everything the step carries per slot.  blockIdx.y = which move; no slot is both
 // a source and a destination within one launch.  The step's results do not depend on the slot a request sits in.
+// A thread first requests all its pieces of the small arrays, then stores them (a copy loop per array would be one
+// round trip to memory after the other).
 template <typename XT, typename MT>
 __global__ __launch_bounds__(256) void k_move_slots(DevPtrs d, MoveArgs mv)
 {
     constexpr int KB = Frag<XT>::KB;
     const int from = mv.from[blockIdx.y], to = mv.to[blockIdx.y], L = mv.L[blockIdx.y], t = mv.t[blockIdx.y];
-    const int tid = blockIdx.x * 256 + threadIdx.x, nth = gridDim.x * 256;
+    const int tid = blockIdx.x * 256 + threadIdx.x, nth = MOVE_WGS * 256;
+    static_assert(MOVE_WGS * 256 >= K_DEC && MOVE_WGS * 256 >= MAX_ENC_LEN && MOVE_WGS * 256 >= HID,
+                  "one piece of each small array per thread");
     const size_t ML = d.max_enc_len;
-    for (int b = 0; b < 2; ++b) {
-        XT* xa = reinterpret_cast<XT*>(d.xatt[b]);
-        XT* xd = reinterpret_cast<XT*>(d.xdec[b]);
-        for (int k = tid; k < K_ATT; k += nth) xa[xoff<XT>(K_ATT / KB, to, k)] = xa[xoff<XT>(K_ATT / KB, from, k)];
-        for (int k = tid; k < K_DEC; k += nth) xd[xoff<XT>(K_DEC / KB, to, k)] = xd[xoff<XT>(K_DEC / KB, from, k)];
-        for (int i = tid; i < L; i += nth) {
-            d.w_last[b][to * ML + i] = d.w_last[b][from * ML + i];
-            d.w_acc[b][to * ML + i] = d.w_acc[b][from * ML + i];
-        }
-    }
-    for (int i = tid; i < HID; i += nth) {
-        d.c_att[(size_t)to * HID + i] = d.c_att[(size_t)from * HID + i];
-        d.c_dec[(size_t)to * HID + i] = d.c_dec[(size_t)from * HID + i];
-    }
-    for (int i = tid; i < N_MEL; i += nth) d.m_last[(size_t)to * N_MEL + i] = d.m_last[(size_t)from * N_MEL + i];
-    // encoder memory, 16 bytes at a time (rows are whole multiples of that)
-    {
-        const uint4* fs = reinterpret_cast<const uint4*>(reinterpret_cast<const MT*>(d.Fmem) + (size_t)from * ML * ENC);
-        uint4* fd = reinterpret_cast<uint4*>(reinterpret_cast<MT*>(d.Fmem) + (size_t)to * ML * ENC);
-        const int nf = L * ENC * (int)sizeof(MT) / 16;
-        for (int i = tid; i < nf; i += nth) fd[i] = fs[i];
-        const uint4* ps = reinterpret_cast<const uint4*>(reinterpret_cast<const MT*>(d.PM) + (size_t)from * ML * ATT);
-        uint4* pd = reinterpret_cast<uint4*>(reinterpret_cast<MT*>(d.PM) + (size_t)to * ML * ATT);
-        const int np = L * ATT * (int)sizeof(MT) / 16;
-        for (int i = tid; i < np; i += nth) pd[i] = ps[i];
-    }
-    // the frames produced so far (some may not have been handed out yet)
-    {
-        const float4* ms = reinterpret_cast<const float4*>(d.mel_ring + (size_t)from * d.max_steps * N_MEL);
-        float4* md = reinterpret_cast<float4*>(d.mel_ring + (size_t)to * d.max_steps * N_MEL);
-        for (int i = tid; i < t * (N_MEL / 4); i += nth) md[i] = ms[i];
-        for (int i = tid; i < t; i += nth) d.stop_ring[(size_t)to * d.max_steps + i] = d.stop_ring[(size_t)from * d.max_steps + i];
-    }
-    // this slot's column of the gate pre-sums (thread = row tile)
-    if (d.pre_att && tid < HID / 4) {
-        const size_t o_from = ((size_t)(from >> 4) * (HID / 4) + tid) * 64 + (from & 15);
-        const size_t o_to = ((size_t)(to >> 4) * (HID / 4) + tid) * 64 + (to & 15);
-        floatx4* pa = reinterpret_cast<floatx4*>(d.pre_att);
-        floatx4* pdc = reinterpret_cast<floatx4*>(d.pre_dec);
+    // ---- small arrays: loads (clamped, unconditional) ...
+    XT xa[2], xd[2];
+    float wl[2], wa[2];
+    const int ka = min(tid, K_ATT - 1), kd = min(tid, K_DEC - 1), il = min(tid, L - 1);
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            pa[o_to + 16 * g] = pa[o_from + 16 * g];
-            if (pdc) pdc[o_to + 16 * g] = pdc[o_from + 16 * g];
+    for (int b = 0; b < 2; ++b) {
+        xa[b] = reinterpret_cast<const XT*>(d.xatt[b])[xoff<XT>(K_ATT / KB, from, ka)];
+        xd[b] = reinterpret_cast<const XT*>(d.xdec[b])[xoff<XT>(K_DEC / KB, from, kd)];
+        wl[b] = d.w_last[b][from * ML + il];
+        wa[b] = d.w_acc[b][from * ML + il];
+    }
+    const int ih = min(tid, HID - 1), im = min(tid, N_MEL - 1);
+    const float ca = d.c_att[(size_t)from * HID + ih], cd = d.c_dec[(size_t)from * HID + ih];
+    const float ml = d.m_last[(size_t)from * N_MEL + im];
+    // this slot's column of the gate pre-sums (thread = row tile)
+    const bool pre = d.pre_att && tid < HID / 4, pre_d = pre && d.pre_dec;
+    const size_t o_from = ((size_t)(from >> 4) * (HID / 4) + min(tid, HID / 4 - 1)) * 64 + (from & 15);
+    const size_t o_to = ((size_t)(to >> 4) * (HID / 4) + min(tid, HID / 4 - 1)) * 64 + (to & 15);
+    floatx4* pa = reinterpret_cast<floatx4*>(d.pre_att);
+    floatx4* pdc = reinterpret_cast<floatx4*>(d.pre_dec);
+    floatx4 va[4], vd[4];
+    if (pre) {
+#pragma unroll
+        for (int g = 0; g < 4; ++g) va[g] = pa[o_from + 16 * g];
+    }
+    if (pre_d) {
+#pragma unroll
+        for (int g = 0; g < 4; ++g) vd[g] = pdc[o_from + 16 * g];
+    }
+    const int sL = d.L[from], st = d.t[from], sn = d.n_steps[from], sd = d.done[from];
+    // ---- ... then stores
+#pragma unroll
+    for (int b = 0; b < 2; ++b) {
+        if (tid < K_ATT) reinterpret_cast<XT*>(d.xatt[b])[xoff<XT>(K_ATT / KB, to, tid)] = xa[b];
+        if (tid < K_DEC) reinterpret_cast<XT*>(d.xdec[b])[xoff<XT>(K_DEC / KB, to, tid)] = xd[b];
+        if (tid < L) {
+            d.w_last[b][to * ML + tid] = wl[b];
+            d.w_acc[b][to * ML + tid] = wa[b];
         }
+    }
+    if (tid < HID) {
+        d.c_att[(size_t)to * HID + tid] = ca;
+        d.c_dec[(size_t)to * HID + tid] = cd;
+    }
+    if (tid < N_MEL) d.m_last[(size_t)to * N_MEL + tid] = ml;
+    if (pre) {
+#pragma unroll
+        for (int g = 0; g < 4; ++g) pa[o_to + 16 * g] = va[g];
+    }
+    if (pre_d) {
+#pragma unroll
+        for (int g = 0; g < 4; ++g) pdc[o_to + 16 * g] = vd[g];
     }
     if (tid == 0) {
-        d.L[to] = d.L[from];
-        d.t[to] = d.t[from];
-        d.n_steps[to] = d.n_steps[from];
-        d.done[to] = d.done[from];
+        d.L[to] = sL;
+        d.t[to] = st;
+        d.n_steps[to] = sn;
+        d.done[to] = sd;
+    }
+    // ---- encoder memory and processed memory, 16 bytes at a time (rows are whole multiples of that), and the
+    // frames produced so far (some may not have been handed out yet)
+    copy_strided(reinterpret_cast<uint4*>(reinterpret_cast<MT*>(d.Fmem) + (size_t)to * ML * ENC),
+                 reinterpret_cast<const uint4*>(reinterpret_cast<const MT*>(d.Fmem) + (size_t)from * ML * ENC),
+                 L * ENC * (int)sizeof(MT) / 16, tid, nth);
+    copy_strided(reinterpret_cast<uint4*>(reinterpret_cast<MT*>(d.PM) + (size_t)to * ML * ATT),
+                 reinterpret_cast<const uint4*>(reinterpret_cast<const MT*>(d.PM) + (size_t)from * ML * ATT),
+                 L * ATT * (int)sizeof(MT) / 16, tid, nth);
+    if (t > 0) {
+        copy_strided(reinterpret_cast<float4*>(d.mel_ring + (size_t)to * d.max_steps * N_MEL),
+                     reinterpret_cast<const float4*>(d.mel_ring + (size_t)from * d.max_steps * N_MEL), t * (N_MEL / 4), tid, nth);
+        copy_strided(d.stop_ring + (size_t)to * d.max_steps, d.stop_ring + (size_t)from * d.max_steps, t, tid, nth);
     }
 }
 
@@ -1477,10 +1516,17 @@ __global__ __launch_bounds__(256) void k_join(DevPtrs d, JoinArgs ja)
     __shared__ float s_f[JOIN_POS][ENC];
     __shared__ float4 s_p[KG][JOIN_POS][ATT / 4];
     MT* Fm = reinterpret_cast<MT*>(d.Fmem) + ((size_t)slot * d.max_enc_len + j0) * ENC;
-    for (int i = tid; i < JOIN_POS * ENC; i += 256) {
-        const float x = i < np * ENC ? F[i] : 0.f;
-        s_f[i / ENC][i % ENC] = x;
-        if (i < np * ENC) Fm[i] = from_float<MT>(x);
+    // all of a thread's loads are requested before the first is used (clamped, not branched around)
+    constexpr int FPT = JOIN_POS * ENC / 256;
+    float fx[FPT];
+#pragma unroll
+    for (int u = 0; u < FPT; ++u) fx[u] = F[min(tid + u * 256, np * ENC - 1)];
+#pragma unroll
+    for (int u = 0; u < FPT; ++u) {
+        const int i = tid + u * 256;
+        const bool in = i < np * ENC;
+        s_f[i / ENC][i % ENC] = in ? fx[u] : 0.f;
+        if (in) Fm[i] = from_float<MT>(fx[u]);
     }
     __syncthreads();
     const int a4 = tid & (ATT / 4 - 1), kg = tid / (ATT / 4);
