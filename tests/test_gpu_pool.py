@@ -532,3 +532,40 @@ def test_joining_together_equals_joining_one_by_one(bf16, weights_bf16, weights_
         assert np.abs(_drain(many2, ids2[i]) - ref[k]).max() <= (TOL_BF16 if bf16 else TOL_F32)
     for pool in (one, many, many2):
         pool.close()
+
+
+def test_moves_with_a_stop_threshold():
+    """With a stop threshold a request may have ended on the device before the host knows (its frame
+    counter is then the host's upper bound, its done flag is set): moved or not, every request keeps
+    its frames, its frame count and its stop logits."""
+    say("case: slot moves in a pool with a stop threshold")
+    w = synth.make_weights()
+    w["stop_b"] = w["stop_b"].copy()
+    w["stop_b"][:] = 0.2
+    thr = 0.62
+    wl = synth.small_workload(40, 5, 90, 24, 24, seed=11)
+    kw = dict(max_pool=48, max_enc_len=90, max_steps=24, chunk_frames=24, stop_threshold=thr)
+    still, moved = make_pool(wl, w, **kw), make_pool(wl, w, **kw)
+    encs = [wl.encoder_outputs(i) for i in range(40)]
+    ids_s = still.add_requests(encs, [24] * 40)
+    ids_m = moved.add_requests(encs, [24] * 40)
+    leave = [i for i in range(32) if i % 2]
+    still.step_n(24)
+    moved.step_n(6)
+    for i in leave:
+        moved.retire(ids_m[i])
+    moved.step_n(18)
+    assert still.moves() == 0 and moved.moves() == 8 and moved.span() <= 32
+    n_early = 0
+    for i in range(40):
+        if i in leave:
+            continue
+        n_s, fin_s = still.frames(ids_s[i])
+        n_m, fin_m = moved.frames(ids_m[i])
+        assert (n_s, fin_s) == (n_m, fin_m) and fin_s
+        n_early += n_s < 24
+        np.testing.assert_array_equal(moved.stop_logits(ids_m[i], 0, n_m), still.stop_logits(ids_s[i], 0, n_s))
+        np.testing.assert_array_equal(_drain(moved, ids_m[i]), _drain(still, ids_s[i]))
+    assert n_early >= 1
+    still.close()
+    moved.close()
