@@ -236,8 +236,9 @@ class Pool:
             a = np.ascontiguousarray(enc_out, dtype=np.float32)
             ptr, L = a.ctypes.data, a.shape[0]
         else:
-            a = enc_out.contiguous()
-            assert a.is_cuda and a.dtype == self._torch.float32
+            # read by work queued on the pool's stream after this call returns: a temporary copy could be gone by then
+            a = enc_out
+            assert a.is_cuda and a.dtype == self._torch.float32 and a.is_contiguous()
             ptr, L = a.data_ptr(), a.shape[0]
         _check(lib().tts_pool_add_request(self._h, C.c_void_p(ptr), int(L), int(n_steps), C.byref(rid)))
         return rid.value
@@ -251,8 +252,8 @@ class Pool:
                 a = np.ascontiguousarray(e, dtype=np.float32)
                 ptrs[i] = a.ctypes.data
             else:
-                a = e.contiguous()
-                assert a.is_cuda and a.dtype == self._torch.float32
+                a = e
+                assert a.is_cuda and a.dtype == self._torch.float32 and a.is_contiguous()
                 ptrs[i] = a.data_ptr()
             Ls[i] = a.shape[0]
             keep.append(a)
