@@ -293,12 +293,13 @@ def test_small_and_large_capacity_pools_agree(wl8, weights_fp32, solo_frames):
 
 
 @pytest.mark.parametrize("bf16,max_pool,n_req", [(True, 32, 24), (True, 48, 40), (False, 48, 36), (False, 64, 52),
-                                                  (True, 96, 90), (True, 128, 120), (True, 160, 150), (True, 176, 170), (True, 208, 200)])
+                                                  (True, 80, 70), (True, 96, 90), (True, 112, 100), (True, 128, 120), (True, 160, 150),
+                                                  (True, 176, 170), (True, 208, 200)])
 def test_pools_of_several_tiles_with_gate_presums(bf16, max_pool, n_req, weights_bf16, weights_fp32):
     """Pools of two to four tiles: the pre-sum workgroups split by pool tiles (one group up to two
     tiles, two groups of 2 + 1 or 2 + 2 tiles above) and take one to three row tiles each.  bf16 pools of
     more tiles pre-sum the attention LSTM's late columns only, in groups of at most four tiles walked one
-    at a time (6 and 8 tiles: two groups; 10 and 11: three, with two idle workgroups per XCD; 13: four, the last of
+    at a time (5 to 8 tiles: two groups; 10 and 11: three, with two idle workgroups per XCD; 13: four, the last of
     one tile), and their
     projection runs as three or two workgroups per tile.  Against the oracle on a sample, and a request's
     bits do not depend on the pool's composition (alone in slot 0 vs among all, vs among 5 joining in
@@ -569,3 +570,20 @@ def test_moves_with_a_stop_threshold():
     assert n_early >= 1
     still.close()
     moved.close()
+
+
+@pytest.mark.parametrize("n_req", [20, 40, 70, 100, 140, 180, 230])
+def test_large_capacity_pool_at_partial_occupancy(n_req, weights_bf16):
+    """A pool of capacity 256 (bf16: pre-sums of the attention LSTM only, two projection workgroups per
+    tile) that holds fewer requests launches over the tiles they span (2, 3, 5, 7, 9, 12, 15 here): a
+    request's frames are those it produces alone in such a pool, and a sample matches the oracle."""
+    wl = synth.small_workload(n_req, 10, 120, 20, 20, seed=97, bf16=True)
+    say(f"case capacity 256, bf16: {n_req} requests, 20 steps")
+    full = gpu_decode(wl, weights_bf16, list(range(n_req)), 20, max_pool=256)
+    sample = [0, 17, n_req - 1]
+    ref, _, _ = oracle_decode(wl, weights_bf16, sample, 20, n_threads=3)
+    for k, i in enumerate(sample):
+        assert np.abs(full[i] - ref[k]).max() <= TOL_BF16
+    alone = gpu_decode(wl, weights_bf16, [17], 20, max_pool=256)[0]
+    np.testing.assert_array_equal(alone, full[17])
+    np.testing.assert_array_equal(gpu_decode(wl, weights_bf16, [n_req - 1], 20, max_pool=256)[0], full[n_req - 1])
