@@ -587,3 +587,49 @@ def test_large_capacity_pool_at_partial_occupancy(n_req, weights_bf16):
     alone = gpu_decode(wl, weights_bf16, [17], 20, max_pool=256)[0]
     np.testing.assert_array_equal(alone, full[17])
     np.testing.assert_array_equal(gpu_decode(wl, weights_bf16, [n_req - 1], 20, max_pool=256)[0], full[n_req - 1])
+
+
+@pytest.mark.parametrize("bf16,seed", [(True, 5), (False, 6)])
+def test_random_arrivals_and_departures(bf16, seed, weights_bf16, weights_fp32):
+    """150 requests arrive in random groups, run for 8 to 40 steps each and leave at their end, in a pool of
+    48 slots that is stepped 1 to 8 steps at a time and drained in chunks of 8: slots are reused, the pool is
+    packed again and again, and every request's frames are bit for bit those of a pool in which nobody leaves
+    or moves."""
+    weights = weights_bf16 if bf16 else weights_fp32
+    rng = np.random.default_rng(seed)
+    wl = synth.small_workload(150, 5, 60, 8, 40, seed=200 + seed, bf16=bf16)
+    say(f"case: random arrivals and departures, {'bf16' if bf16 else 'fp32'}")
+    kw = dict(max_pool=48, max_enc_len=60, max_steps=40, chunk_frames=8)
+    ref = {}
+    for b0 in range(0, 150, 48):
+        idx = list(range(b0, min(150, b0 + 48)))
+        out = gpu_decode(wl, weights, idx, 40, **kw)
+        for k, i in enumerate(idx):
+            ref[i] = out[k, : wl.n_steps[i]]
+    pool = make_pool(wl, weights, **kw)
+    nxt, live, got, moves_seen = 0, {}, {i: [] for i in range(150)}, 0
+    while nxt < 150 or live:
+        room = 48 - pool.size()
+        n_new = int(min(room, 150 - nxt, rng.integers(0, 12)))
+        if n_new:
+            idx = list(range(nxt, nxt + n_new))
+            for i, rid in zip(idx, pool.add_requests([wl.encoder_outputs(i) for i in idx], [int(wl.n_steps[i]) for i in idx])):
+                live[rid] = i
+            nxt += n_new
+        if not live:
+            continue
+        pool.step_n(int(rng.integers(1, 9)))
+        for rid in list(live):
+            while True:
+                frames, fin = pool.drain_chunk(rid)
+                if frames.shape[0]:
+                    got[live[rid]].append(frames.copy())
+                if fin or frames.shape[0] == 0:
+                    break
+            if fin:
+                pool.retire(rid)
+                del live[rid]
+    assert pool.moves() > 0 and pool.size() == 0
+    for i in range(150):
+        np.testing.assert_array_equal(np.concatenate(got[i]), ref[i])
+    pool.close()
