@@ -5,6 +5,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cstdarg>
 #include <cstdio>
 #include <cstdlib>
@@ -13,7 +14,6 @@
 #include <memory>
 #include <new>
 #include <string>
-#include <algorithm>
 #include <vector>
 
 #include "book.h"
