@@ -38,19 +38,6 @@ def build(verbose: bool = False) -> str:
     return OUT
 
 
-def build_machine_costs(verbose: bool = False) -> str:
-    """The stand-alone microbenchmark of kernel-boundary, synchronisation and streaming costs
-    (paper_2211_13939_amd/machine_costs; not loaded by anything)."""
-    out = os.path.join(HERE, "machine_costs")
-    cmd = [HIPCC, "-O3", "-std=c++17", "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang",
-           "-packed-fp32-ops", os.path.join(CSRC, "machine_costs.hip"), "-o", out]
-    if verbose:
-        print(" ".join(cmd), flush=True)
-    subprocess.run(cmd, check=True)
-    return out
-
-
 if __name__ == "__main__":
     print(build(verbose=True))
-    print(build_machine_costs(verbose=True))
     sys.exit(0)
