@@ -13,6 +13,12 @@ Two join policies:
                        2T for constant iteration time T, mean 1.5 T).
   join_every = 1       a request joins before the next decoder step.
 
+The non-incremental twin the paper compares with (Sec. 3.1) is here too, as a second loop over the same pool:
+`simulate_twin` builds a batch from the requests received so far, keeps that batch unchanged for the whole round
+(every request is decoded for as many steps as the round's longest needs, and is padded to the round's longest
+encoder length), hands each request its complete result when the round ends, and lets later arrivals queue for the
+next round.
+
 This module is host logic only; the backend does the work.
 """
 from __future__ import annotations
@@ -156,6 +162,102 @@ def simulate(backend: PoolBackend, arrival_s: Sequence[float], n_steps: Sequence
                 lcl[s["index"]] = clock - arrival_s[s["index"]]
             backend.retire(rid)
     return StreamResult(fcl, lcl, hist, n_seg, total_steps, busy, clock)
+
+
+class RoundBackend:
+    """What the non-incremental loop needs: `round(indices)` decodes the batch to its end and returns the elapsed
+    seconds (None: the loop times it)."""
+
+    def round(self, indices: Sequence[int]):
+        raise NotImplementedError
+
+
+@dataclass
+class TwinResult:
+    latency_s: np.ndarray            # per request: end of its round - arrival (the whole utterance is the response)
+    rounds: List[dict]               # per round: start, duration, indices, steps, padded_frames, useful_frames
+    busy_s: float
+    end_clock_s: float
+
+    def percentiles(self):
+        return {f"p{p}": float(np.percentile(self.latency_s, p)) for p in (50, 95, 99)}
+
+    def padding_waste(self) -> float:
+        """Share of the decoder frames computed that no request asked for."""
+        pad = sum(r["padded_frames"] for r in self.rounds)
+        use = sum(r["useful_frames"] for r in self.rounds)
+        return (pad - use) / max(1, pad)
+
+
+def simulate_twin(backend: RoundBackend, arrival_s: Sequence[float], n_steps: Sequence[int],
+                  max_batch: Optional[int] = None) -> TwinResult:
+    """The non-incremental twin (Sec. 3.1): the requests received so far form a batch whose size stays unchanged for
+    the whole inference round; requests that arrive during a round wait in the queue for the next one; a request's
+    response is its whole utterance, at the end of its round."""
+    arrival_s = np.asarray(arrival_s, np.float64)
+    n_steps = np.asarray(n_steps, np.int64)
+    n = arrival_s.shape[0]
+    order = np.argsort(arrival_s, kind="stable")
+    nxt, clock, busy = 0, 0.0, 0.0
+    lat = np.full(n, np.nan)
+    rounds: List[dict] = []
+    while nxt < n:
+        if arrival_s[order[nxt]] > clock:
+            clock = float(arrival_s[order[nxt]])          # idle until the next request is received
+        batch = []
+        while nxt < n and arrival_s[order[nxt]] <= clock and (max_batch is None or len(batch) < max_batch):
+            batch.append(int(order[nxt]))
+            nxt += 1
+        t0 = time.perf_counter()
+        elapsed = backend.round(batch)
+        dt = (time.perf_counter() - t0) if elapsed is None else float(elapsed)
+        steps = int(n_steps[batch].max())
+        rounds.append(dict(start=clock, duration=dt, indices=batch, steps=steps, padded_frames=steps * len(batch),
+                           useful_frames=int(n_steps[batch].sum())))
+        clock += dt
+        busy += dt
+        for i in batch:
+            lat[i] = clock - arrival_s[i]
+    return TwinResult(lat, rounds, busy, clock)
+
+
+class GpuTwinBackend(RoundBackend):
+    """A round on a binding.Pool: every request of the batch joins at once and is advanced for the round's longest
+    step count (the padding steps are real decoder steps: the pool's step kernels run on all of the batch until the
+    last request ends), then each utterance is copied to the host and the batch leaves.
+
+    pad_memory: the encoder outputs are also padded with zero rows to the round's longest, as a batch tensor would be
+    (the padded positions then take part in the attention like any other: this kernel set has no mask to give them
+    zero weight with, since its own pool never pads); the frames are then a timing vehicle only.  Without it every
+    request keeps its own length and its first n_i frames are exactly those of the incremental pool."""
+
+    def __init__(self, pool, enc, n_steps, pad_memory: bool = True, on_result=None):
+        self.pool, self.enc, self.n_steps, self.pad_memory, self.on_result = pool, enc, n_steps, pad_memory, on_result
+
+    def round(self, indices):
+        torch = self.pool._torch
+        steps = int(max(self.n_steps[i] for i in indices))
+        encs = [self.enc(i) for i in indices]
+        if self.pad_memory:
+            Lmax = max(int(e.shape[0]) for e in encs)
+            padded = []
+            for e in encs:
+                t = e if torch.is_tensor(e) else torch.from_numpy(np.ascontiguousarray(e, np.float32))
+                t = t.to(self.pool.device)
+                if int(t.shape[0]) < Lmax:
+                    with torch.cuda.stream(self.pool.stream):
+                        t = torch.cat([t, torch.zeros((Lmax - int(t.shape[0]), t.shape[1]), dtype=t.dtype, device=t.device)])
+                padded.append(t)
+            self.pool.stream.synchronize()
+            encs = padded
+        ids = self.pool.add_requests(encs, [steps] * len(indices))
+        self.pool.step_n(steps)
+        for i, rid in zip(indices, ids):
+            mel = self.pool.drain_all(rid)
+            if self.on_result is not None:
+                self.on_result(i, mel[: int(self.n_steps[i])])
+            self.pool.retire(rid)
+        return None
 
 
 def _steps_to_event(s: dict, chunk: int) -> int:

@@ -152,3 +152,48 @@ def test_late_deliveries_are_counted_when_they_arrive():
     np.testing.assert_allclose(res.first_chunk_latency_s, [4e-3 + t_late, 4e-3 + t_late, 4e-3 + t_late], rtol=0, atol=1e-9)
     np.testing.assert_allclose(res.last_chunk_latency_s, [8e-3 + t_late, 5e-3 + t_late, 4e-3 + t_late], rtol=0, atol=1e-9)
     assert not be.pending() and not be.live
+
+
+class ModelRoundBackend(stream.RoundBackend):
+    """A round takes (the longest request's steps) x t_step seconds whatever the batch holds."""
+
+    def __init__(self, n_steps, t_step):
+        self.n_steps, self.t_step = n_steps, t_step
+        self.batches = []
+
+    def round(self, indices):
+        self.batches.append(list(indices))
+        return max(int(self.n_steps[i]) for i in indices) * self.t_step
+
+
+def test_non_incremental_twin_two_rounds_closed_form():
+    """Sec. 3.1's non-incremental twin with a constant step time t: the batch is fixed for a round, a round lasts as
+    long as its longest request, arrivals during a round queue for the next one, and the response is the whole
+    utterance at the end of the round.  Requests 0, 1 are there at time 0 (100 and 40 steps); 2 and 3 arrive during
+    the first round (30 and 70 steps); 4 arrives long after everything is done (25 steps)."""
+    t = 1e-3
+    n_steps = np.array([100, 40, 30, 70, 25])
+    arrivals = np.array([0.0, 0.0, 10 * t, 50 * t, 500 * t])
+    be = ModelRoundBackend(n_steps, t)
+    res = stream.simulate_twin(be, arrivals, n_steps)
+    assert be.batches == [[0, 1], [2, 3], [4]]
+    want = np.array([100 * t, 100 * t, 170 * t - 10 * t, 170 * t - 50 * t, 25 * t])
+    np.testing.assert_allclose(res.latency_s, want, rtol=0, atol=1e-12)
+    assert [r["steps"] for r in res.rounds] == [100, 70, 25]
+    assert abs(res.rounds[1]["start"] - 100 * t) < 1e-12 and abs(res.rounds[2]["start"] - 500 * t) < 1e-12
+    # frames computed: 2 x 100 + 2 x 70 + 25; frames asked for: 265
+    assert abs(res.padding_waste() - (365 - 265) / 365) < 1e-12
+    assert abs(res.busy_s - 195 * t) < 1e-12 and abs(res.end_clock_s - 525 * t) < 1e-12
+
+
+def test_twin_batch_limit_and_mixed_lengths_wait_for_the_longest():
+    """With a batch limit the overflow waits a whole round; in a mixed batch the short request's latency is the long
+    one's (the padding the paper blames for Mixed being as slow as Long), while the incremental loop lets it go after
+    its own steps."""
+    t = 1e-3
+    n_steps = np.array([400, 40, 40])
+    arrivals = np.zeros(3)
+    res = stream.simulate_twin(ModelRoundBackend(n_steps, t), arrivals, n_steps, max_batch=2)
+    np.testing.assert_allclose(res.latency_s, [400 * t, 400 * t, 440 * t], atol=1e-12)
+    inc = stream.simulate(ModelBackend(n_steps, 40, t), arrivals, n_steps, 40, join_every=1)
+    np.testing.assert_allclose(inc.last_chunk_latency_s, [400 * t, 40 * t, 40 * t], atol=1e-12)
