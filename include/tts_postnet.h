@@ -81,6 +81,22 @@ int tts_postnet_create(const tts_postnet_config *cfg, const tts_postnet_weights 
 int tts_postnet_run(tts_postnet *pn, const float *d_mel, const int *win_len, const int *keep_from, int n,
                     float *d_out);
 
+/*
+ * The same call for callers that cannot allocate or be handed a workspace where they run: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Arguments, results (bit for bit) and errors are
+ * those of tts_postnet_run, but the scratch of the call -- the activations between the layers and the per-column
+ * tables -- lives in a static array inside the library instead of the arena: TTS_POSTNET_STATIC_BYTES bytes per GPU
+ * that runs it, held until the process ends.  The call allocates nothing (no hipMalloc, no hipFree, no allocating
+ * library routine) and records no events (tts_postnet_elapsed_ms does not see it).  A batch may carry at most
+ * TTS_POSTNET_STATIC_MAX_COLUMNS frames (context included) whatever max_columns says: more is TTS_E_INVAL.  Every
+ * call on a GPU, from any tts_postnet object, uses that GPU's one array: calls that overlap on one GPU (two streams,
+ * two threads) race; calls queued on one stream do not.  The device the object was created on must be current.
+ */
+#define TTS_POSTNET_STATIC_MAX_COLUMNS 4096
+#define TTS_POSTNET_STATIC_BYTES (2u * TTS_POSTNET_STATIC_MAX_COLUMNS * 512u * 4u + 2u * TTS_POSTNET_STATIC_MAX_COLUMNS * 4u)
+int tts_postnet_run_static(tts_postnet *pn, const float *d_mel, const int *win_len, const int *keep_from, int n,
+                           float *d_out);
+
 /* Device time of the last tts_postnet_run in milliseconds (HIP events on the stream); waits for the stream. */
 int tts_postnet_elapsed_ms(tts_postnet *pn, float *out_ms);
 

@@ -39,7 +39,7 @@ EXPORTS = (
     "tts_book_create", "tts_book_add", "tts_book_step", "tts_book_drain", "tts_book_retire",
     "tts_book_slot", "tts_book_compact", "tts_book_destroy",
     "tts_pool_chunk_window",
-    "tts_postnet_workspace_bytes", "tts_postnet_create", "tts_postnet_run", "tts_postnet_elapsed_ms",
+    "tts_postnet_workspace_bytes", "tts_postnet_create", "tts_postnet_run", "tts_postnet_run_static", "tts_postnet_elapsed_ms",
     "tts_postnet_destroy",
     "tts_vocoder_workspace_bytes", "tts_vocoder_create", "tts_vocoder_run", "tts_vocoder_elapsed_ms",
     "tts_vocoder_destroy",
@@ -89,6 +89,7 @@ class TtsEncoderWeights(C.Structure):
 VOCODER_HOP = 256
 VOCODER_FIRST, VOCODER_LAST = 1, 2
 POSTNET_CONTEXT = 10      # frames in front of a chunk that can influence it (2 per layer)
+TTS_POSTNET_STATIC_MAX_COLUMNS = 4096   # most frames one tts_postnet_run_static call may carry
 
 
 class TtsError(RuntimeError):
@@ -154,6 +155,7 @@ def lib() -> C.CDLL:
     L.tts_postnet_create.argtypes = [C.POINTER(TtsPostnetConfig), C.POINTER(TtsPostnetWeights), vp, C.c_size_t, vp,
                                      C.POINTER(vp)]
     L.tts_postnet_run.argtypes = [vp, vp, _ip, _ip, C.c_int, vp]
+    L.tts_postnet_run_static.argtypes = [vp, vp, _ip, _ip, C.c_int, vp]
     L.tts_postnet_elapsed_ms.argtypes = [vp, _fp]
     L.tts_postnet_destroy.restype = None
     L.tts_postnet_destroy.argtypes = [vp]
@@ -460,14 +462,17 @@ class Postnet:
                                             C.c_void_p(self.stream.cuda_stream), C.byref(h)))
         self._h = h
 
-    def run_device(self, d_mel, win_len, keep_from, d_out) -> None:
-        """d_mel / d_out: CUDA fp32 tensors (packed windows in, packed chunks out); queued on the stream."""
+    def run_device(self, d_mel, win_len, keep_from, d_out, static: bool = False) -> None:
+        """d_mel / d_out: CUDA fp32 tensors (packed windows in, packed chunks out); queued on the stream.
+        static: tts_postnet_run_static, the call that allocates nothing (its scratch is the library's static array)."""
         wl = np.ascontiguousarray(win_len, np.int32)
         kf = np.ascontiguousarray(keep_from, np.int32)
         assert d_mel.is_cuda and d_out.is_cuda and d_mel.is_contiguous() and d_out.is_contiguous()
         assert d_mel.numel() >= int(wl.sum()) * self.cfg.n_mel and d_out.numel() >= int((wl - kf).sum()) * self.cfg.n_mel
-        _check(lib().tts_postnet_run(self._h, C.c_void_p(d_mel.data_ptr()), wl.ctypes.data_as(_ip),
-                                     kf.ctypes.data_as(_ip), int(wl.shape[0]), C.c_void_p(d_out.data_ptr())))
+        fn = lib().tts_postnet_run_static if static else lib().tts_postnet_run
+        with self._torch.cuda.device(self.device):
+            _check(fn(self._h, C.c_void_p(d_mel.data_ptr()), wl.ctypes.data_as(_ip),
+                      kf.ctypes.data_as(_ip), int(wl.shape[0]), C.c_void_p(d_out.data_ptr())))
 
     def run(self, windows, keep_from) -> list:
         """windows: list of numpy [T_i, n_mel]; returns the post-processed chunks as numpy arrays."""

@@ -55,10 +55,44 @@ PnLayout layout_of(const tts_postnet_config& c)
 struct tts_postnet {
     tts_postnet_config cfg;
     PostnetPtrs d;
+    int device = -1;              // the device the arena (hence the weights) lives on
     hipStream_t stream = nullptr;
     hipEvent_t ev0 = nullptr, ev1 = nullptr;
     bool ev_valid = false;
 };
+
+// ---- scratch of the entry point that allocates nothing (tts_postnet_run_static): the activations between layers and
+// the per-column tables of one call, for up to TTS_POSTNET_STATIC_MAX_COLUMNS columns of fp32 activations.  One copy
+// per GPU, at its own address, held until the process ends; every call on a GPU uses it, so calls that overlap on one
+// GPU race.  The array's name is only a host-side handle: the address the kernels get is looked up once per device.
+namespace {
+constexpr size_t PN_STATIC_COLS = TTS_POSTNET_STATIC_MAX_COLUMNS;
+static_assert(PN_STATIC_COLS % 16 == 0, "whole column tiles");
+constexpr size_t PN_STATIC_ACT = PN_STATIC_COLS * PN_CHANNELS * 4;     // one activation buffer, fp32 (bf16 uses half of it)
+constexpr size_t PN_STATIC_TABLE = PN_STATIC_COLS * 4;
+constexpr size_t PN_STATIC_BYTES = 2 * PN_STATIC_ACT + 2 * PN_STATIC_TABLE;
+static_assert(PN_STATIC_BYTES == TTS_POSTNET_STATIC_BYTES, "the size the header states");
+constexpr int PN_MAX_DEVICES = 64;
+}  // namespace
+static __device__ __align__(256) unsigned char scratch[PN_STATIC_BYTES];
+static unsigned char* g_scratch[PN_MAX_DEVICES];   // per device: where that GPU's copy of `scratch` lives (null: not looked up yet)
+
+// the address of the current device's copy of `scratch` (looked up on the first call on that device)
+static int static_scratch(int device, unsigned char** out)
+{
+    if (device < 0 || device >= PN_MAX_DEVICES) return fail(TTS_E_UNSUPPORTED, "device %d: at most %d devices", device, PN_MAX_DEVICES);
+    if (!g_scratch[device]) {
+        int cur = -1;
+        HIP_TRY(hipGetDevice(&cur));
+        if (cur != device) return fail(TTS_E_INVAL, "device %d is current, the PostNet lives on device %d", cur, device);
+        void* ptr = nullptr;
+        HIP_TRY(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr) return fail(TTS_E_HIP, "no device address for the static scratch array");
+        g_scratch[device] = static_cast<unsigned char*>(ptr);
+    }
+    *out = g_scratch[device];
+    return TTS_OK;
+}
 
 extern "C" size_t tts_postnet_workspace_bytes(const tts_postnet_config* cfg)
 {
@@ -87,7 +121,15 @@ extern "C" int tts_postnet_create(const tts_postnet_config* cfg, const tts_postn
     tts_postnet* p = new (std::nothrow) tts_postnet();
     if (!p) return fail(TTS_E_INVAL, "out of host memory");
     p->cfg = *cfg;
+    p->device = attr.device;
     p->stream = (hipStream_t)hip_stream;
+    {
+        // set-up is the place to look the static scratch array up (tts_postnet_run_static may run where nothing but
+        // launches is allowed); if another device is current now, the first call on the arena's device does it
+        int cur = -1;
+        unsigned char* unused = nullptr;
+        if (hipGetDevice(&cur) == hipSuccess && cur == attr.device) rc = static_scratch(attr.device, &unused);
+    }
     char* base = (char*)dev_arena;
     const bool bf = cfg->weight_dtype == TTS_DTYPE_BF16;
     for (int l = 0; l < PN_LAYERS && rc == TTS_OK; ++l) {
@@ -119,8 +161,9 @@ extern "C" int tts_postnet_create(const tts_postnet_config* cfg, const tts_postn
     return TTS_OK;
 }
 
-extern "C" int tts_postnet_run(tts_postnet* p, const float* d_mel, const int* win_len, const int* keep_from, int n,
-                               float* d_out)
+// one dynamic batch with the scratch of `d` (the arena's, or the static array's); `timed`: HIP events around it
+static int run_batch(tts_postnet* p, const PostnetPtrs& d, int max_columns, bool timed, const float* d_mel, const int* win_len,
+                     const int* keep_from, int n, float* d_out)
 {
     if (!p || !d_mel || !win_len || !keep_from || !d_out) return fail(TTS_E_INVAL, "null argument");
     if (n < 1) return fail(TTS_E_INVAL, "n = %d windows", n);
@@ -131,11 +174,11 @@ extern "C" int tts_postnet_run(tts_postnet* p, const float* d_mel, const int* wi
             return fail(TTS_E_INVAL, "window %d: keep_from = %d outside [0, %d)", i, keep_from[i], win_len[i]);
         cols += win_len[i];
     }
-    if (cols > p->cfg.max_columns) return fail(TTS_E_INVAL, "%lld frames in one call, max_columns = %d", cols, p->cfg.max_columns);
+    if (cols > max_columns) return fail(TTS_E_INVAL, "%lld frames in one call, at most %d fit", cols, max_columns);
     const int n_col = (int)cols, n_pad = (n_col + 15) / 16 * 16;
     // the window list travels as kernel arguments, 256 windows at a time; the device expands it into the
     // per-column tables (position inside the window for the zero padding, output row of the column)
-    HIP_TRY(hipEventRecord(p->ev0, p->stream));
+    if (timed) HIP_TRY(hipEventRecord(p->ev0, p->stream));
     int c = 0, r = 0;
     for (int i0 = 0; i0 < n; i0 += PN_META_WINDOWS) {
         PnWindows w;
@@ -149,12 +192,39 @@ extern "C" int tts_postnet_run(tts_postnet* p, const float* d_mel, const int* wi
             c += win_len[i];
             r += win_len[i] - keep_from[i];
         }
-        HIP_TRY(launch_postnet_meta(p->d, w, n_col, n_pad, i0 == 0, p->stream));
+        HIP_TRY(launch_postnet_meta(d, w, n_col, n_pad, i0 == 0, p->stream));
     }
-    HIP_TRY(launch_postnet(p->d, p->cfg.weight_dtype, d_mel, n_col, d_out, p->stream));
-    HIP_TRY(hipEventRecord(p->ev1, p->stream));
-    p->ev_valid = true;
+    HIP_TRY(launch_postnet(d, p->cfg.weight_dtype, d_mel, n_col, d_out, p->stream));
+    if (timed) {
+        HIP_TRY(hipEventRecord(p->ev1, p->stream));
+        p->ev_valid = true;
+    }
     return TTS_OK;
+}
+
+extern "C" int tts_postnet_run(tts_postnet* p, const float* d_mel, const int* win_len, const int* keep_from, int n,
+                               float* d_out)
+{
+    if (!p) return fail(TTS_E_INVAL, "null argument");
+    return run_batch(p, p->d, p->cfg.max_columns, true, d_mel, win_len, keep_from, n, d_out);
+}
+
+extern "C" int tts_postnet_run_static(tts_postnet* p, const float* d_mel, const int* win_len, const int* keep_from, int n,
+                                      float* d_out)
+{
+    if (!p) return fail(TTS_E_INVAL, "null argument");
+    unsigned char* base = nullptr;
+    int rc = static_scratch(p->device, &base);
+    if (rc) return rc;
+    // the same kernels, their scratch in this GPU's copy of the static array instead of the arena.  A call writes every
+    // word of it that it reads (tables and activations of all its column tiles, padding columns included), so nothing
+    // has to start at zero and what the previous call left is never seen.
+    PostnetPtrs d = p->d;
+    d.act[0] = base;
+    d.act[1] = base + PN_STATIC_ACT;
+    d.cmeta = reinterpret_cast<int*>(base + 2 * PN_STATIC_ACT);
+    d.orow = reinterpret_cast<int*>(base + 2 * PN_STATIC_ACT + PN_STATIC_TABLE);
+    return run_batch(p, d, TTS_POSTNET_STATIC_MAX_COLUMNS, false, d_mel, win_len, keep_from, n, d_out);
 }
 
 extern "C" int tts_postnet_elapsed_ms(tts_postnet* p, float* out_ms)
