@@ -117,7 +117,7 @@ __global__ __launch_bounds__(PN_THREADS) void k_pn_conv(
         if constexpr (EPI != PN_EPI_LAST) {
             const float y0 = pn_act<EPI>(y[0]), y1 = pn_act<EPI>(y[1]), y2 = pn_act<EPI>(y[2]), y3 = pn_act<EPI>(y[3]);
             XT* dst = Xout + xoff<XT>(COUT / KB, col, ch);
-            if constexpr (sizeof(XT) == 2) *reinterpret_cast<uint2*>(dst) = make_uint2(pack_bf16x2(y0, y1), pack_bf16x2(y2, y3));
+            if constexpr (sizeof(XT) == 2) *reinterpret_cast<uint2*>(dst) = make_uint2(pack2<XT>(y0, y1), pack2<XT>(y2, y3));
             else *reinterpret_cast<float4*>(dst) = make_float4(y0, y1, y2, y3);
         } else {
             const int r = orow[col];
@@ -215,7 +215,7 @@ __global__ __launch_bounds__(PN_THREADS) void k_pn_conv_wide(
         if constexpr (EPI != PN_EPI_LAST) {
             const float y0 = pn_act<EPI>(y[0]), y1 = pn_act<EPI>(y[1]), y2 = pn_act<EPI>(y[2]), y3 = pn_act<EPI>(y[3]);
             XT* dst = Xout + xoff<XT>(COUT / KB, col, ch);
-            if constexpr (sizeof(XT) == 2) *reinterpret_cast<uint2*>(dst) = make_uint2(pack_bf16x2(y0, y1), pack_bf16x2(y2, y3));
+            if constexpr (sizeof(XT) == 2) *reinterpret_cast<uint2*>(dst) = make_uint2(pack2<XT>(y0, y1), pack2<XT>(y2, y3));
             else *reinterpret_cast<float4*>(dst) = make_float4(y0, y1, y2, y3);
         } else {
             const int r = orow[col];

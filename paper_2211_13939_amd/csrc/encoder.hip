@@ -362,7 +362,7 @@ hipError_t run_typed(const EncoderPtrs& d, const PnWindows& w, int n_col, float*
 hipError_t launch_encoder(const EncoderPtrs& d, int wdtype, const PnWindows& w, int n_col, float* out, hipStream_t s)
 {
     if (n_col < 1 || w.n < 1) return hipSuccess;
-    return wdtype == 0 ? run_typed<float>(d, w, n_col, out, s) : run_typed<bf16_t>(d, w, n_col, out, s);
+    return wdtype == 0 ? run_typed<float>(d, w, n_col, out, s) : run_typed<h16_t>(d, w, n_col, out, s);
 }
 
 }  // namespace tts

@@ -552,8 +552,8 @@ template <> struct LsaTile<float> {
     }
 };
 
-// bf16: v_mfma_f32_16x16x32_bf16, lane group g supplies 8 k values per step
-template <> struct LsaTile<bf16_t> {
+// two-byte operands: v_mfma_f32_16x16x32_f16, lane group g supplies 8 k values per step
+template <> struct LsaTile<h16_t> {
     uint4 kA[2][2];    // [mt][c]: filter 16 mt + jl, taps 8 g .. 8 g + 7 of channel c
     uint4 wA[8];       // [at]: W_loc row 32 (jl/4) + 4 at + jl%4, filters {4g..4g+3, 16+4g..16+4g+3}
     static constexpr int LDS_VECS = 12 * 64;   // the operands of all 64 lanes, as 16-byte pieces
@@ -579,16 +579,16 @@ template <> struct LsaTile<bf16_t> {
         for (int c = 0; c < 2; ++c) {
             const float* u = (c == 0 ? u0 : u1) + x0 + 8 * g;
             uint4 b;
-            b.x = pack_bf16x2(u[0], u[1]); b.y = pack_bf16x2(u[2], u[3]);
-            b.z = pack_bf16x2(u[4], u[5]); b.w = pack_bf16x2(u[6], u[7]);
-            loc0 = mfma_frag<bf16_t>(kA[0][c], b, loc0);
-            loc1 = mfma_frag<bf16_t>(kA[1][c], b, loc1);
+            b.x = pack2<h16_t>(u[0], u[1]); b.y = pack2<h16_t>(u[2], u[3]);
+            b.z = pack2<h16_t>(u[4], u[5]); b.w = pack2<h16_t>(u[6], u[7]);
+            loc0 = mfma_frag<h16_t>(kA[0][c], b, loc0);
+            loc1 = mfma_frag<h16_t>(kA[1][c], b, loc1);
         }
         uint4 bl;
-        bl.x = pack_bf16x2(loc0[0], loc0[1]); bl.y = pack_bf16x2(loc0[2], loc0[3]);
-        bl.z = pack_bf16x2(loc1[0], loc1[1]); bl.w = pack_bf16x2(loc1[2], loc1[3]);
+        bl.x = pack2<h16_t>(loc0[0], loc0[1]); bl.y = pack2<h16_t>(loc0[2], loc0[3]);
+        bl.z = pack2<h16_t>(loc1[0], loc1[1]); bl.w = pack2<h16_t>(loc1[2], loc1[3]);
 #pragma unroll
-        for (int at = 0; at < 8; ++at) pl[at] = mfma_frag<bf16_t>(wA[at], bl, q[at]);
+        for (int at = 0; at < 8; ++at) pl[at] = mfma_frag<h16_t>(wA[at], bl, q[at]);
     }
 };
 
@@ -998,7 +998,7 @@ constexpr int PROJ_ROWS = 96;
 constexpr int PROJ_MEL_LD = PROJ_ROWS + 4, PROJ_HID_LD = PRENET + 4;
 
 template <typename XT> struct PrenetK1 { static constexpr int value = 80; };
-template <> struct PrenetK1<bf16_t> { static constexpr int value = 96; };
+template <> struct PrenetK1<h16_t> { static constexpr int value = 96; };
 
 // B fragment (16 bytes of XT) from 16/sizeof(XT) consecutive fp32 values in LDS
 template <typename XT> __device__ __forceinline__ uint4 frag_from_f32(const float* p);
@@ -1006,9 +1006,9 @@ template <> __device__ __forceinline__ uint4 frag_from_f32<float>(const float* p
 {
     return make_uint4(__float_as_uint(p[0]), __float_as_uint(p[1]), __float_as_uint(p[2]), __float_as_uint(p[3]));
 }
-template <> __device__ __forceinline__ uint4 frag_from_f32<bf16_t>(const float* p)
+template <> __device__ __forceinline__ uint4 frag_from_f32<h16_t>(const float* p)
 {
-    return make_uint4(pack_bf16x2(p[0], p[1]), pack_bf16x2(p[2], p[3]), pack_bf16x2(p[4], p[5]), pack_bf16x2(p[6], p[7]));
+    return make_uint4(pack2<h16_t>(p[0], p[1]), pack2<h16_t>(p[2], p[3]), pack2<h16_t>(p[4], p[5]), pack2<h16_t>(p[6], p[7]));
 }
 
 struct ProjShared {
@@ -1238,7 +1238,7 @@ __device__ __forceinline__ void proj_tile(const DevPtrs& d, int cur, int tile, i
                     // four consecutive k inside one 16-byte piece: one store
                     XT* dst = xa + xoff<XT>(K_ATT / KB, sl, XA_P + 16 * mt + 4 * g);
                     const float p0 = fmaxf(acc[0], 0.f), p1 = fmaxf(acc[1], 0.f), p2 = fmaxf(acc[2], 0.f), p3 = fmaxf(acc[3], 0.f);
-                    if constexpr (sizeof(XT) == 2) *reinterpret_cast<uint2*>(dst) = make_uint2(pack_bf16x2(p0, p1), pack_bf16x2(p2, p3));
+                    if constexpr (sizeof(XT) == 2) *reinterpret_cast<uint2*>(dst) = make_uint2(pack2<XT>(p0, p1), pack2<XT>(p2, p3));
                     else *reinterpret_cast<float4*>(dst) = make_float4(p0, p1, p2, p3);
                 }
             }
@@ -1648,14 +1648,14 @@ hipError_t launch_step(const DevPtrs& d, const StepLaunch& cfg, int cur, hipStre
     if (cfg.pre_gates) {
         if (cfg.n_tiles > MAX_TILES || !d.pre_att || !d.qpart || (cfg.pre_gates == 2) != (d.pre_dec != nullptr)) return hipErrorInvalidValue;
         if (cfg.pre_gates == 1) {
-            if (cfg.wdtype == 1 && cfg.mdtype == 1) return step_typed<bf16_t, bf16_t, 1>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cfg.lstm_rows, cfg.proj_group, cur, s, ev);
-            if (cfg.wdtype == 1 && cfg.mdtype == 0) return step_typed<bf16_t, float, 1>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cfg.lstm_rows, cfg.proj_group, cur, s, ev);
+            if (cfg.wdtype == 1 && cfg.mdtype == 1) return step_typed<h16_t, bf16_t, 1>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cfg.lstm_rows, cfg.proj_group, cur, s, ev);
+            if (cfg.wdtype == 1 && cfg.mdtype == 0) return step_typed<h16_t, float, 1>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cfg.lstm_rows, cfg.proj_group, cur, s, ev);
             return hipErrorInvalidValue;
         }
         if (cfg.n_tiles > PRESUM_SMALL_TILES) return hipErrorInvalidValue;
         if (cfg.wdtype == 0 && cfg.mdtype == 0) return step_typed<float, float, 2>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cfg.lstm_rows, cfg.proj_group, cur, s, ev);
-        if (cfg.wdtype == 1 && cfg.mdtype == 1) return step_typed<bf16_t, bf16_t, 2>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cfg.lstm_rows, cfg.proj_group, cur, s, ev);
-        if (cfg.wdtype == 1 && cfg.mdtype == 0) return step_typed<bf16_t, float, 2>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cfg.lstm_rows, cfg.proj_group, cur, s, ev);
+        if (cfg.wdtype == 1 && cfg.mdtype == 1) return step_typed<h16_t, bf16_t, 2>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cfg.lstm_rows, cfg.proj_group, cur, s, ev);
+        if (cfg.wdtype == 1 && cfg.mdtype == 0) return step_typed<h16_t, float, 2>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cfg.lstm_rows, cfg.proj_group, cur, s, ev);
         return hipErrorInvalidValue;
     }
     // without pre-sums: fp32 pools of more than four tiles (the fp32 mode is the parity vehicle)
@@ -1678,8 +1678,8 @@ hipError_t launch_move_slots(const DevPtrs& d, int wdtype, int mdtype, const Mov
     const dim3 g(MOVE_WGS, n), b(256);
     static_assert(MOVE_WGS * 256 >= HID / 4, "one thread per row tile of the pre-sums");
     if (wdtype == 0 && mdtype == 0) hipLaunchKernelGGL((k_move_slots<float, float>), g, b, 0, s, d, mv);
-    else if (wdtype == 1 && mdtype == 1) hipLaunchKernelGGL((k_move_slots<bf16_t, bf16_t>), g, b, 0, s, d, mv);
-    else if (wdtype == 1 && mdtype == 0) hipLaunchKernelGGL((k_move_slots<bf16_t, float>), g, b, 0, s, d, mv);
+    else if (wdtype == 1 && mdtype == 1) hipLaunchKernelGGL((k_move_slots<h16_t, bf16_t>), g, b, 0, s, d, mv);
+    else if (wdtype == 1 && mdtype == 0) hipLaunchKernelGGL((k_move_slots<h16_t, float>), g, b, 0, s, d, mv);
     else return hipErrorInvalidValue;
     return hipGetLastError();
 }
@@ -1694,8 +1694,8 @@ hipError_t launch_join(const DevPtrs& d, int wdtype, int mdtype, const JoinArgs&
     }
     const dim3 g(1 + (Lmax + JOIN_POS - 1) / JOIN_POS, n), b(256);
     if (wdtype == 0 && mdtype == 0) hipLaunchKernelGGL((k_join<float, float>), g, b, 0, s, d, ja);
-    else if (wdtype == 1 && mdtype == 1) hipLaunchKernelGGL((k_join<bf16_t, bf16_t>), g, b, 0, s, d, ja);
-    else if (wdtype == 1 && mdtype == 0) hipLaunchKernelGGL((k_join<bf16_t, float>), g, b, 0, s, d, ja);
+    else if (wdtype == 1 && mdtype == 1) hipLaunchKernelGGL((k_join<h16_t, bf16_t>), g, b, 0, s, d, ja);
+    else if (wdtype == 1 && mdtype == 0) hipLaunchKernelGGL((k_join<h16_t, float>), g, b, 0, s, d, ja);
     else return hipErrorInvalidValue;
     return hipGetLastError();
 }
@@ -1704,14 +1704,14 @@ hipError_t launch_presum_tile(const DevPtrs& d, int wdtype, int tile, int nxt, h
 {
     if (!d.pre_att || tile < 0 || tile >= MAX_TILES) return hipErrorInvalidValue;
     if (wdtype == 0) hipLaunchKernelGGL((k_presum_tile<float>), dim3(HID / 4), dim3(LSTM_WAVES * 64), 0, s, d, nxt, tile);
-    else hipLaunchKernelGGL((k_presum_tile<bf16_t>), dim3(HID / 4), dim3(LSTM_WAVES * 64), 0, s, d, nxt, tile);
+    else hipLaunchKernelGGL((k_presum_tile<h16_t>), dim3(HID / 4), dim3(LSTM_WAVES * 64), 0, s, d, nxt, tile);
     return hipGetLastError();
 }
 
 hipError_t launch_prenet_slot(const DevPtrs& d, int wdtype, int slot, hipStream_t s)
 {
     if (wdtype == 0) hipLaunchKernelGGL((k_prenet_slot<float>), dim3(1), dim3(256), 0, s, d, slot);
-    else hipLaunchKernelGGL((k_prenet_slot<bf16_t>), dim3(1), dim3(256), 0, s, d, slot);
+    else hipLaunchKernelGGL((k_prenet_slot<h16_t>), dim3(1), dim3(256), 0, s, d, slot);
     return hipGetLastError();
 }
 
@@ -1720,7 +1720,7 @@ hipError_t launch_x_get(int wdtype, const void* X, int K, int slot, int off, int
     if (wdtype == 0)
         hipLaunchKernelGGL((k_x_get<float>), dim3(1), dim3(256), 0, s, reinterpret_cast<const float*>(X), K / Frag<float>::KB, slot, off, n, out);
     else
-        hipLaunchKernelGGL((k_x_get<bf16_t>), dim3(1), dim3(256), 0, s, reinterpret_cast<const bf16_t*>(X), K / Frag<bf16_t>::KB, slot, off, n, out);
+        hipLaunchKernelGGL((k_x_get<h16_t>), dim3(1), dim3(256), 0, s, reinterpret_cast<const h16_t*>(X), K / Frag<h16_t>::KB, slot, off, n, out);
     return hipGetLastError();
 }
 
@@ -1729,7 +1729,7 @@ hipError_t launch_x_set(int wdtype, void* X, int K, int slot, int off, int n, co
     if (wdtype == 0)
         hipLaunchKernelGGL((k_x_set<float>), dim3(1), dim3(256), 0, s, reinterpret_cast<float*>(X), K / Frag<float>::KB, slot, off, n, in);
     else
-        hipLaunchKernelGGL((k_x_set<bf16_t>), dim3(1), dim3(256), 0, s, reinterpret_cast<bf16_t*>(X), K / Frag<bf16_t>::KB, slot, off, n, in);
+        hipLaunchKernelGGL((k_x_set<h16_t>), dim3(1), dim3(256), 0, s, reinterpret_cast<h16_t*>(X), K / Frag<h16_t>::KB, slot, off, n, in);
     return hipGetLastError();
 }
 

@@ -1,4 +1,4 @@
-// Device helpers shared by the step kernels and the PostNet kernels: bf16 <-> fp32, fast sigmoid / tanh,
+// Device helpers shared by the step kernels and the PostNet kernels: bf16 / fp16 <-> fp32, fast sigmoid / tanh,
 // the MFMA fragment geometry and the fragment-order activation layout.  Device code only.
 #pragma once
 #include <hip/hip_runtime.h>
@@ -10,9 +10,16 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
 struct bf16_t { uint16_t bits; };
+// IEEE half precision: the two-byte MFMA operand type.  Weights given as bfloat16 values (8 significant bits) are exact
+// in it (11 significant bits) down to 2^-14, and activations rounded to it carry 2^-11 relative error where bfloat16
+// would carry 2^-8; v_mfma_f32_16x16x32_f16 runs at the rate of its bf16 twin.
+struct h16_t { uint16_t bits; };
+typedef _Float16 halfx8 __attribute__((ext_vector_type(8)));
+typedef _Float16 halfx2 __attribute__((ext_vector_type(2)));
 
 __device__ __forceinline__ float to_float(float x) { return x; }
 __device__ __forceinline__ float to_float(bf16_t x) { return __uint_as_float(((uint32_t)x.bits) << 16); }
+__device__ __forceinline__ float to_float(h16_t x) { return (float)__builtin_bit_cast(_Float16, x.bits); }
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
 
@@ -29,9 +36,18 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
     const floatx2 v = {lo, hi};
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
+// two floats -> one 32-bit word of two T (round to nearest even), `lo` in the low half
+template <typename T> __device__ __forceinline__ uint32_t pack2(float lo, float hi);
+template <> __device__ __forceinline__ uint32_t pack2<bf16_t>(float lo, float hi) { return pack_bf16x2(lo, hi); }
+template <> __device__ __forceinline__ uint32_t pack2<h16_t>(float lo, float hi)
+{
+    const floatx2 v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, halfx2));
+}
 template <typename T> __device__ __forceinline__ T from_float(float x);
 template <> __device__ __forceinline__ float from_float<float>(float x) { return x; }
 template <> __device__ __forceinline__ bf16_t from_float<bf16_t>(float x) { bf16_t r; r.bits = f2bf_bits(x); return r; }
+template <> __device__ __forceinline__ h16_t from_float<h16_t>(float x) { h16_t r; r.bits = __builtin_bit_cast(uint16_t, (_Float16)x); return r; }
 
 __device__ __forceinline__ float sigmoidf_(float x) { return __builtin_amdgcn_rcpf(1.0f + __expf(-x)); }
 // 1 - 2/(1+e^{2x}) with the hardware reciprocal (1 ulp): absolute error ~1e-7, saturates cleanly at +-1
@@ -75,6 +91,16 @@ template <> struct Vec16<bf16_t> {
     }
 };
 
+template <> struct Vec16<h16_t> {
+    static constexpr int N = 8;
+    __device__ static __forceinline__ void unpack(const uint4& u, float* f)
+    {
+        const halfx8 h = __builtin_bit_cast(halfx8, u);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) f[i] = (float)h[i];
+    }
+};
+
 // Fragment geometry for element type T: a fragment is 64 bytes of k per row / column.
 template <typename T> struct Frag {
     static constexpr int KB = 64 / (int)sizeof(T);    // k elements per fragment
@@ -103,6 +129,10 @@ template <typename T> __device__ __forceinline__ floatx4 mfma_frag(const uint4& 
 template <> __device__ __forceinline__ floatx4 mfma_frag<bf16_t>(const uint4& a, const uint4& b, floatx4 acc)
 {
     return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), acc, 0, 0, 0);
+}
+template <> __device__ __forceinline__ floatx4 mfma_frag<h16_t>(const uint4& a, const uint4& b, floatx4 acc)
+{
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(halfx8, a), __builtin_bit_cast(halfx8, b), acc, 0, 0, 0);
 }
 template <> __device__ __forceinline__ floatx4 mfma_frag<float>(const uint4& a, const uint4& b, floatx4 acc)
 {

@@ -65,7 +65,7 @@ hipError_t launch_postnet(const PostnetPtrs& d, int wdtype, const float* mel, in
 {
     const int n_ctiles = (n_col + 15) / 16;
     if (n_ctiles < 1) return hipSuccess;
-    return wdtype == 0 ? run_typed<float>(d, mel, n_col, n_ctiles, out, s) : run_typed<bf16_t>(d, mel, n_col, n_ctiles, out, s);
+    return wdtype == 0 ? run_typed<float>(d, mel, n_col, n_ctiles, out, s) : run_typed<h16_t>(d, mel, n_col, n_ctiles, out, s);
 }
 
 }  // namespace tts

@@ -59,6 +59,9 @@ static int check_config(const tts_config* c)
         return fail(TTS_E_INVAL, "memory_dtype must be 0 (fp32) or 1 (bf16)");
     if (c->memory_dtype == TTS_DTYPE_BF16 && c->weight_dtype != TTS_DTYPE_BF16)
         return fail(TTS_E_INVAL, "bf16 memory requires bf16 weights");
+    // the cumulative attention weights (at most one per frame and position) are a half-precision MFMA operand there
+    if (c->weight_dtype == TTS_DTYPE_BF16 && c->max_steps > 65504)
+        return fail(TTS_E_INVAL, "max_steps must be at most 65504 with bf16 weights");
     return TTS_OK;
 }
 

@@ -62,11 +62,11 @@ template <> __device__ __forceinline__ void lds_put4<float>(uint4* lds, int elem
 {
     *reinterpret_cast<float4*>(reinterpret_cast<float*>(lds) + elem) = v;
 }
-template <> __device__ __forceinline__ void lds_put4<bf16_t>(uint4* lds, int elem, float4 v)
+template <> __device__ __forceinline__ void lds_put4<h16_t>(uint4* lds, int elem, float4 v)
 {
     uint2 u;
-    u.x = pack_bf16x2(v.x, v.y);
-    u.y = pack_bf16x2(v.z, v.w);
+    u.x = pack2<h16_t>(v.x, v.y);
+    u.y = pack2<h16_t>(v.z, v.w);
     *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(lds) + elem) = u;
 }
 
@@ -526,7 +526,7 @@ hipError_t launch_vocoder_splice(const VocoderPtrs& d, const VocBatch& b, const 
 
 hipError_t launch_vocoder_generator(const VocoderPtrs& d, int wdtype, int n_windows, hipStream_t s)
 {
-    return wdtype == 0 ? generator_typed<float>(d, n_windows, s) : generator_typed<bf16_t>(d, n_windows, s);
+    return wdtype == 0 ? generator_typed<float>(d, n_windows, s) : generator_typed<h16_t>(d, n_windows, s);
 }
 
 hipError_t launch_vocoder_fade(const VocoderPtrs& d, const VocBatch& b, float* d_audio, hipStream_t s)

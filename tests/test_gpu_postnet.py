@@ -3,16 +3,15 @@ import numpy as np
 import pytest
 
 from paper_2211_13939_amd import binding, synth
-from tests.helpers import TOL_F32, make_pool, say
+from tests.helpers import TOL_BF16, TOL_F32, make_pool, say
 
 pytestmark = pytest.mark.gpu
 
 CTX = binding.POSTNET_CONTEXT
-# bf16 PostNet: the input and four layers of activations are rounded to bf16 (2^-9 relative each) and a
-# layer's gain with the synthetic N(0, 0.05^2) weights is about 2.5: the CPU emulation of exactly those
-# rounding points is 3.6e-2 away (max; rms 1e-2) from the exact stack on outputs of rms 2.2 and
-# magnitude up to 8.  The bound is relative to the largest output: 1 %.
-PN_TOL_BF16_REL = 1e-2
+# The bf16-weight PostNet multiplies IEEE-half operands: the input and four layers of activations are rounded to half
+# precision (2^-12 relative each) and a layer's gain with the synthetic N(0, 0.05^2) weights is about 2.5.  Every
+# comparison with the oracle, on N(0, 1) mel and on the decoder's own mel alike, is held to the absolute bf16 bar of
+# 2e-2 per mel bin (measured: 6e-3 on outputs of magnitude up to 11).
 
 
 def _oracle_chunks(W, utterances, cuts):
@@ -63,7 +62,7 @@ def test_ragged_batch_of_chunks_matches_oracle(bf16):
             worst = max(worst, float(np.abs(g - ref[i][k]).max()))
     scale = max(float(np.abs(c).max()) for r in ref for c in r)
     say(f"  max abs err {worst:.3e} (largest output {scale:.2f})")
-    assert worst <= (PN_TOL_BF16_REL * scale if bf16 else TOL_F32)
+    assert worst <= (TOL_BF16 if bf16 else TOL_F32)
     pn.close()
 
 
@@ -87,7 +86,7 @@ def test_large_batch_matches_oracle(bf16):
     worst = max(float(np.abs(g - r).max()) for g, r in zip(got, ref))
     scale = max(float(np.abs(r).max()) for r in ref)
     say(f"  max abs err {worst:.3e} (largest output {scale:.2f})")
-    assert worst <= (PN_TOL_BF16_REL * scale if bf16 else TOL_F32)
+    assert worst <= (TOL_BF16 if bf16 else TOL_F32)
 
 
 def test_very_large_batch_matches_oracle_and_small_batches():
@@ -113,30 +112,31 @@ def test_very_large_batch_matches_oracle_and_small_batches():
     worst = max(float(np.abs(g - r).max()) for g, r in zip(got, ref))
     between = max(float(np.abs(g - h).max()) for g, h in zip(got, small))
     say(f"  max abs err {worst:.3e} (largest output {scale:.2f}); against the other kernels {between:.3e}")
-    assert worst <= PN_TOL_BF16_REL * scale
-    assert between <= PN_TOL_BF16_REL * scale
+    assert worst <= TOL_BF16
+    assert between <= TOL_BF16
 
 
 def test_bf16_rounding_points():
-    """bf16 mode rounds the input mel and every tanh output to bf16 and accumulates in fp32.  The same
-    rounding points applied to the oracle's layers on the CPU must land within a few rounding flips of
-    the GPU (an activation next to a bf16 boundary may fall either way under fp32 accumulation)."""
+    """The two-byte mode takes the weights as bfloat16 values, rounds the input mel and every tanh output to IEEE half
+    (the MFMA operand type) and accumulates in fp32.  The same rounding points applied to the oracle's layers on the
+    CPU must land within a few rounding flips of the GPU (an activation next to a rounding boundary may fall either
+    way under fp32 accumulation)."""
     from oracle import oracle as orc
     ws, bs = synth.make_postnet_weights(bf16=True)
     mel = np.random.default_rng(21).standard_normal((53, 80)).astype(np.float32)
-    x = synth.round_to_bf16(mel).astype(np.float64)
+    x = mel.astype(np.float16).astype(np.float64)
     for l in range(5):
         y = orc.conv5(ws[l], bs[l], x, apply_tanh=(l < 4))
-        x = synth.round_to_bf16(y.astype(np.float32)).astype(np.float64) if l < 4 else y
+        x = y.astype(np.float32).astype(np.float16).astype(np.float64) if l < 4 else y
     emulated = mel + x
     exact = orc.postnet(orc.PostnetWeights(ws, bs), mel.astype(np.float64))
     pn = binding.Postnet(binding.make_postnet_config(max_columns=64, bf16=True), ws, bs)
     got = pn.run([mel], [0])[0]
     pn.close()
-    say(f"case postnet bf16 rounding points: gpu vs emulation {np.abs(got - emulated).max():.3e}, "
+    say(f"case postnet two-byte rounding points: gpu vs emulation {np.abs(got - emulated).max():.3e}, "
         f"emulation vs exact {np.abs(emulated - exact).max():.3e}, gpu vs exact {np.abs(got - exact).max():.3e}")
-    assert np.abs(got - emulated).max() <= 0.25 * np.abs(emulated - exact).max()
-    assert np.abs(got - exact).max() <= PN_TOL_BF16_REL * np.abs(exact).max()
+    assert np.abs(got - emulated).max() <= 0.5 * np.abs(emulated - exact).max()
+    assert np.abs(got - exact).max() <= TOL_BF16
 
 
 def test_window_without_full_context_is_rejected_or_exact_at_start():
@@ -220,6 +220,67 @@ def test_decoder_chunks_through_postnet_on_device(weights_fp32):
     say(f"  max abs err {worst:.3e}")
     assert done == [int(n) for n in wl.n_steps]
     assert worst <= 5 * TOL_F32      # decoder error (<= 1e-4) passes through five layers of gain
+    pn.close()
+    pool.close()
+
+
+def test_bf16_postnet_on_the_decoders_own_bf16_mel(weights_bf16):
+    """The bf16 module on the only input it ever receives: the bf16 decoder's chunks, handed over on the device
+    (tts_pool_chunk_window).  Two comparisons per chunk, both at the bf16 bar of 2e-2 absolute per mel bin:
+    the module alone (oracle PostNet applied to the very frames the GPU decoder produced) and the chain
+    (oracle decoder followed by the oracle PostNet on its own frames)."""
+    import torch
+    from oracle import oracle as orc
+    wl = synth.small_workload(3, 30, 120, 50, 96, seed=33, bf16=True)
+    chunk = 16
+    pool = make_pool(wl, weights_bf16, chunk_frames=chunk)
+    ws, bs = synth.make_postnet_weights(bf16=True)
+    pn = binding.Postnet(binding.make_postnet_config(max_columns=3 * (chunk + CTX), bf16=True), ws, bs, stream=pool.stream)
+    W = orc.PostnetWeights(ws, bs)
+    Wd = orc.Weights(weights_bf16)
+    ref_mel, _, frames, _ = orc.pool_decode(wl.dims, Wd, [wl.encoder_outputs(i) for i in range(3)],
+                                            [int(n) for n in wl.n_steps], int(wl.n_steps.max()), pm_round_bf16=True,
+                                            n_threads=3)
+    ids = [pool.add_request(wl.encoder_outputs(i), int(wl.n_steps[i])) for i in range(3)]
+    done = [0, 0, 0]
+    finished = [False] * 3
+    gpu_mel = [np.zeros((int(n), 80), np.float64) for n in wl.n_steps]
+    dev = pool.device
+    d_in = torch.empty((3 * (chunk + CTX), 80), dtype=torch.float32, device=dev)
+    d_out = torch.empty((3 * chunk, 80), dtype=torch.float32, device=dev)
+    worst_module = worst_chain = biggest = 0.0
+    say(f"case bf16 decoder -> bf16 postnet on device: L {wl.enc_len.tolist()}, steps {wl.n_steps.tolist()}, chunks of {chunk}")
+    while not all(finished):
+        pool.step_n(chunk)
+        lens, keeps, who, row = [], [], [], 0
+        for i, rid in enumerate(ids):
+            if finished[i]:
+                continue
+            c, n, fin = pool.chunk_window(rid, CTX, d_in[row:])
+            if n:
+                lens.append(c + n); keeps.append(c); who.append((i, n, row + c)); row += c + n
+            finished[i] = fin
+        if not lens:
+            continue
+        pn.run_device(d_in, lens, keeps, d_out)
+        pool.sync()
+        out = d_out.cpu().numpy()
+        win = d_in.cpu().numpy()
+        r = 0
+        for i, n, at in who:
+            s = done[i]
+            gpu_mel[i][s:s + n] = win[at:at + n]
+            want_module = orc.postnet_chunk(W, gpu_mel[i][: s + n], s)
+            want_chain = orc.postnet_chunk(W, ref_mel[i, : s + n], s)
+            worst_module = max(worst_module, float(np.abs(out[r:r + n] - want_module).max()))
+            worst_chain = max(worst_chain, float(np.abs(out[r:r + n] - want_chain).max()))
+            biggest = max(biggest, float(np.abs(want_chain).max()))
+            r += n
+            done[i] += n
+    say(f"  module alone: max abs err {worst_module:.3e}; decoder + module: {worst_chain:.3e}; largest output {biggest:.2f}")
+    assert done == [int(n) for n in wl.n_steps]
+    assert worst_module <= TOL_BF16
+    assert worst_chain <= TOL_BF16
     pn.close()
     pool.close()
 

@@ -17,13 +17,14 @@ def _mel(rng, n):
 
 
 def _emulate_bf16(w, mel):
-    """The generator with the bf16 path's rounding points written out with library routines (fp64 accumulate):
-    every convolution's input is rounded to bf16 after its activation; weights are bf16 values already."""
+    """The generator with the two-byte path's rounding points written out with library routines (fp64 accumulate):
+    every convolution's input is rounded to IEEE half (the MFMA operand type) after its activation; weights are bf16
+    values already, which that type holds exactly."""
     import torch
     import torch.nn.functional as F
 
     def r(x):
-        return torch.from_numpy(synth.round_to_bf16(x.numpy().astype(np.float32)).astype(np.float64))
+        return torch.from_numpy(x.numpy().astype(np.float32).astype(np.float16).astype(np.float64))
 
     t = lambda a: torch.from_numpy(np.ascontiguousarray(a, np.float64))
     x = F.conv1d(r(t(mel).T[None]), t(w["pre_w"]), t(w["pre_b"]), padding=3)
