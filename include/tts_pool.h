@@ -43,7 +43,8 @@ typedef enum {
     TTS_E_NOTFOUND = -3,  /* unknown or already retired request id */
     TTS_E_HIP = -4,       /* a HIP call failed; tts_last_error() carries its text */
     TTS_E_ARENA = -5,     /* device arena too small or misaligned */
-    TTS_E_UNSUPPORTED = -6 /* dimensions outside what the kernels are built for, or a device with fewer than 256 CUs */
+    TTS_E_UNSUPPORTED = -6, /* dimensions outside what the kernels are built for, or a device with fewer than 256 CUs */
+    TTS_E_LOST = -7       /* tts_pool_sync: requests were ended early by the device since the last call (see there) */
 } tts_status;
 
 enum { TTS_DTYPE_F32 = 0, TTS_DTYPE_BF16 = 1 };
@@ -149,7 +150,7 @@ int tts_pool_step_n(tts_pool *pool, int n, int64_t *out_frames);
  * frames exist and the request is unfinished, *out_frames = 0 and TTS_OK.  The
  * last chunk of a finished request may be short.  *out_finished = 1 once the
  * request is finished AND everything has been drained.  Waits for the stream.
- * TTS_E_HIP if a step's kernels could not finish their work (see tts_pool_sync).
+ * A request the device ended early (tts_pool_sync, tts_pool_lost) hands out the frames it has like any finished one.
  */
 int tts_pool_drain_chunk(tts_pool *pool, int64_t id, float *dst, int *out_frames, int *out_finished);
 
@@ -197,13 +198,21 @@ long long tts_pool_moves(const tts_pool *pool);
 
 /* Wait until everything queued on the pool's stream has run.
  * Workgroups of one launch hand each other words (the projection's partial sums, the attention energies of a
- * request) and wait for them a bounded number of polls; should such a wait ever run out (the GPU so oversubscribed by
- * other work that a partner is not scheduled for a quarter of a second), the kernels still finish, the frames
- * produced since are invalid, and this call and tts_pool_drain_chunk return TTS_E_HIP from then on. */
+ * request) and wait for them a bounded number of polls.  Should such a wait ever run out (the GPU so oversubscribed by
+ * other work that a partner is not scheduled for a quarter of a second), the kernels still finish and only the
+ * requests whose words were missing are affected: the device stores nothing more for them from that step on (the
+ * frames they have are valid and can be drained; they count as finished and hold their slots until retired), every
+ * other request in the pool goes on undisturbed.  The first tts_pool_sync after such an incident returns TTS_E_LOST
+ * with the ids in tts_last_error(); tts_pool_lost tells for one request.  Nothing else is needed to go on using the
+ * pool.  (A consumer on the device, tts_pool_chunk_window, can only know of steps that have already run: wait with
+ * this call before trusting chunks handed over from steps still in flight.) */
 int tts_pool_sync(tts_pool *pool);
 
+/* *out_lost = 1 if request `id` was ended early by the device because a step could not be completed for it. */
+int tts_pool_lost(tts_pool *pool, int64_t id, int *out_lost);
+
 /* The bound of those waits, in polls (default 2^18).  Waits for the stream.  0 makes every such wait give up at
- * once: the kernels run through as always, and the error path above can be exercised without anything hanging. */
+ * once: the kernels run through as always, and the path above can be exercised without anything hanging. */
 int tts_pool_set_wait_polls(tts_pool *pool, int polls);
 
 /* Device time of the kernels of the most recent tts_pool_step / step_n call,

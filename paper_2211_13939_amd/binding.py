@@ -17,7 +17,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libtts_pool.so")
 
 TTS_OK = 0
-TTS_E_INVAL, TTS_E_FULL, TTS_E_NOTFOUND, TTS_E_HIP, TTS_E_ARENA, TTS_E_UNSUPPORTED = -1, -2, -3, -4, -5, -6
+TTS_E_INVAL, TTS_E_FULL, TTS_E_NOTFOUND, TTS_E_HIP, TTS_E_ARENA, TTS_E_UNSUPPORTED, TTS_E_LOST = -1, -2, -3, -4, -5, -6, -7
 DTYPE_F32, DTYPE_BF16 = 0, 1
 STATE = dict(m=0, a=1, w_last=2, w_acc=3, h_att=4, c_att=5, h_dec=6, c_dec=7)
 
@@ -34,7 +34,7 @@ EXPORTS = (
     "tts_pool_step_n", "tts_pool_drain_chunk", "tts_pool_get_stop_logits", "tts_pool_retire",
     "tts_pool_get_state", "tts_pool_set_state", "tts_pool_frames", "tts_pool_size", "tts_pool_n_active",
     "tts_pool_span", "tts_pool_moves",
-    "tts_pool_sync", "tts_pool_set_wait_polls", "tts_pool_timing", "tts_pool_elapsed_ms", "tts_pool_kernel_times", "tts_pool_destroy",
+    "tts_pool_sync", "tts_pool_lost", "tts_pool_set_wait_polls", "tts_pool_timing", "tts_pool_elapsed_ms", "tts_pool_kernel_times", "tts_pool_destroy",
     "tts_last_error",
     "tts_book_create", "tts_book_add", "tts_book_step", "tts_book_drain", "tts_book_retire",
     "tts_book_slot", "tts_book_compact", "tts_book_destroy",
@@ -131,6 +131,7 @@ def lib() -> C.CDLL:
     L.tts_pool_moves.restype = C.c_longlong
     L.tts_pool_moves.argtypes = [vp]
     L.tts_pool_sync.argtypes = [vp]
+    L.tts_pool_lost.argtypes = [vp, C.c_int64, _ip]
     L.tts_pool_set_wait_polls.argtypes = [vp, C.c_int]
     L.tts_pool_timing.argtypes = [vp, C.c_int]
     L.tts_pool_elapsed_ms.argtypes = [vp, _fp]
@@ -323,6 +324,12 @@ class Pool:
 
     def moves(self) -> int:
         return lib().tts_pool_moves(self._h)
+
+    def lost(self, rid: int) -> bool:
+        """True if the device ended the request early because a step could not be completed for it."""
+        v = C.c_int()
+        _check(lib().tts_pool_lost(self._h, rid, C.byref(v)))
+        return bool(v.value)
 
     def sync(self) -> None:
         _check(lib().tts_pool_sync(self._h))

@@ -20,6 +20,7 @@ struct SlotInfo {
     int t = 0;        // frames produced (host mirror; an upper bound while a stop threshold may fire)
     int drained = 0;  // frames already handed out
     int parity = 0;   // which half of the double-buffered activations holds this request's newest state
+    bool lost = false; // ended by the device before its time: a step could not be completed for it
     SlotState state = SlotState::Free;
 };
 
@@ -90,6 +91,17 @@ public:
             si.state = SlotState::Finished;
             remove_active(slot);
         }
+    }
+
+    // A request the device froze after `t` frames (a step's kernels could not complete it): it ends there.
+    void lose(int slot, int t) {
+        SlotInfo& si = slots_[slot];
+        if (si.state == SlotState::Free) return;
+        if (t < si.t) si.t = t;
+        if (si.drained > si.t) si.drained = si.t;
+        si.lost = true;
+        if (si.state == SlotState::Active) remove_active(slot);
+        si.state = SlotState::Finished;
     }
 
     // What the next drain hands out: frames [first, first+count).  count = 0 if

@@ -49,7 +49,7 @@ struct DevPtrs {
     unsigned* proj_seq;   // [tiles][6]: steps each of a tile's projection workgroups has taken part in (zero at creation)
     unsigned long long* lsa_x; // [slots][max_enc_len] (step number << 32 | float bits): the energies the workgroups of a request hand each other
     unsigned* step_seq;   // [1] steps taken (zero at creation; advanced by the projection kernel)
-    int* fault;           // pinned host memory: set by a workgroup whose bounded wait for another's words ran out
+    int* fault;           // pinned host memory: set by a workgroup whose bounded wait for another's words ran out (with `failed` of the slots it froze)
     const void* lsa_kfrag; // location filters as per-lane MFMA A operands (layout depends on WT)
     const void* lsa_wfrag; // W_loc as per-lane MFMA A operands (layout depends on WT)
     const float* WmemT;   // [ENC][ATT] fp32 (join time only)
@@ -73,7 +73,8 @@ struct DevPtrs {
     int* L;               // [slots]
     int* t;               // [slots] frames produced
     int* n_steps;         // [slots]
-    int* done;            // [slots] reached its last frame (or tripped the stop threshold)
+    int* done;            // [slots] reached its last frame (or tripped the stop threshold, or failed)
+    int* failed;          // [slots] frozen by a workgroup whose bounded wait for its partners' words ran out (cleared when a request joins)
     int* live;            // [MAX_POOL] 1 = the slot's request is advanced by the next step (set by the host's membership upload)
     float* stage;         // [max_enc_len][ENC] fp32 staging for host-side encoder outputs
     int wait_polls;       // how often a workgroup polls another's words before it gives up and raises `fault` (DEFAULT_WAIT_POLLS)

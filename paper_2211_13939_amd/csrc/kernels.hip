@@ -607,12 +607,12 @@ __global__ __launch_bounds__(LSA_THREADS) void k_lsa(DevPtrs d, int cur, int n_s
     // A slot's S workgroups sit on one XCD (workgroup b runs on XCD b % 8): what they all read - the query's partial
     // products, the words they hand each other - then crosses into that XCD's L2 once.  Slots are dealt to the XCDs in
     // eights; the grid is padded to whole eights, and a workgroup past the last slot repeats the last slot's work
-    // (every read stays inside the arrays) and stores nothing but the same words as its twin.
+    // (every read stays inside the arrays), stores nothing and waits for nobody.
     const int xcd = blockIdx.x & 7, kx = blockIdx.x >> 3;
     const int slot_raw = (kx / S) * 8 + xcd, sp = kx % S;
     const int slot = min(slot_raw, n_slots - 1);
     const int live_w = d.live[slot], done_w = d.done[slot], L_w = d.L[slot];
-    const bool twin = slot_raw >= n_slots;       // computes what the last slot's workgroup computes, keeps it to itself
+    const bool twin = slot_raw >= n_slots;
     // the request's S workgroups share the energies (below): this step's number marks the words they exchange
     constexpr bool XCH = S > 1;
     unsigned seq = 0;
@@ -646,6 +646,7 @@ __global__ __launch_bounds__(LSA_THREADS) void k_lsa(DevPtrs d, int cur, int n_s
     __shared__ float s_u[2][LSA_UPAD];            // s_u[c][x] = u_c[x - 15]
     __shared__ float s_e[MAX_ENC_LEN];
     __shared__ float s_red[2 * LSA_WAVES];
+    __shared__ int s_fail;                        // a wait for another workgroup's words ran out
     __shared__ __attribute__((aligned(16))) float s_ctx[LSA_WAVES][ENC];
 
     constexpr int KB = Frag<XT>::KB;
@@ -696,7 +697,7 @@ __global__ __launch_bounds__(LSA_THREADS) void k_lsa(DevPtrs d, int cur, int n_s
         for (int i = 0; i < NV; ++i) pmv[i] = *reinterpret_cast<const uint4*>(pm + i * NPM);
     }
     __builtin_amdgcn_sched_barrier(0);            // everything above is in flight before anything below waits
-    const bool active = live_w && !done_w;
+    const bool active = live_w && !done_w && !twin;
     const int L = active ? L_w : 1;
     const int ntile = (L + 15) >> 4;
     if constexpr (QP) {
@@ -733,6 +734,7 @@ __global__ __launch_bounds__(LSA_THREADS) void k_lsa(DevPtrs d, int cur, int n_s
         }
     }
     if (tid < ATT) s_v[tid] = -2.0f * vreg;       // v . tanh(x) = sum(v) - 2 sum(v / (1 + e^{2x}))
+    if (tid == 0) s_fail = 0;
     if constexpr (TILE_LDS) {
         s_tile[tid] = tv0;
         if (tid < 256) s_tile[LSA_THREADS + tid] = tv1;
@@ -826,10 +828,11 @@ __global__ __launch_bounds__(LSA_THREADS) void k_lsa(DevPtrs d, int cur, int n_s
         if (fast_softmax) e = __expf(e - bound);
         if (g == 0 && j < L) {
             s_e[j] = e;
-            if constexpr (XCH)
-                __hip_atomic_store(&ex[j], ((unsigned long long)seq << 32) | __float_as_uint(e), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            else
+            if constexpr (XCH) {
+                if (!twin) __hip_atomic_store(&ex[j], ((unsigned long long)seq << 32) | __float_as_uint(e), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            } else {
                 psum += e;
+            }
         }
     }
 
@@ -861,14 +864,14 @@ __global__ __launch_bounds__(LSA_THREADS) void k_lsa(DevPtrs d, int cur, int n_s
         // the other workgroups' energies: every thread polls its own words until they carry this step's number
         // (bounded: the request's workgroups are resident together, S * slots <= 256 = one per CU)
         for (int x = tid; x < L; x += LSA_THREADS) {
-            if ((x >> 4) % S != sp) {
+            if (!twin && (x >> 4) % S != sp) {
                 unsigned long long w = 0;
                 bool in = false;
                 for (int spin = 0; spin < d.wait_polls && !in; ++spin) {
                     w = __hip_atomic_load(&ex[x], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     in = (unsigned)(w >> 32) == seq;
                 }
-                if (!in) *d.fault = 1;
+                if (!in) s_fail = 1;
                 s_e[x] = __uint_as_float((unsigned)w);
             }
         }
@@ -945,6 +948,17 @@ __global__ __launch_bounds__(LSA_THREADS) void k_lsa(DevPtrs d, int cur, int n_s
     }
     __syncthreads();
 
+    // A wait that ran out: the request cannot be advanced any further (its partners' energies never came).  It is
+    // frozen where it stands - marked done, so that every later kernel leaves it alone, and failed, so that the host
+    // can tell its owner - and nothing of this step is stored for it; every other request goes on.  (s_fail was last
+    // written before the barrier that follows the polling.)
+    const bool failed = XCH && s_fail != 0;
+    if (failed && tid == 0 && active) {
+        d.done[slot] = 1;
+        d.failed[slot] = 1;
+        *d.fault = 1;
+    }
+    const bool store = active && !failed;
     XT* xa = reinterpret_cast<XT*>(d.xatt[cur ^ 1]);
     XT* xd = reinterpret_cast<XT*>(d.xdec[cur]);
     for (int f = tid; f < FS; f += LSA_THREADS) {
@@ -961,7 +975,7 @@ __global__ __launch_bounds__(LSA_THREADS) void k_lsa(DevPtrs d, int cur, int n_s
         }
         const XT a = from_float<XT>(c * inv);
         const int k = sp * FS + f;
-        if (active && !twin) {
+        if (store) {
             xa[xoff<XT>(K_ATT / KB, slot, XA_A + k)] = a;
             xd[xoff<XT>(K_DEC / KB, slot, XD_A + k)] = a;
         }
@@ -971,7 +985,7 @@ __global__ __launch_bounds__(LSA_THREADS) void k_lsa(DevPtrs d, int cur, int n_s
     float* wa_out = d.w_acc[cur ^ 1] + (size_t)slot * d.max_enc_len;
     for (int x = sp + S * tid; x < L; x += S * LSA_THREADS) {
         const float w = s_e[x] * inv;
-        if (active && !twin) {
+        if (store) {
             wl_out[x] = w;
             wa_out[x] = s_u[1][x + LOC_PAD] + w;
         }
@@ -1127,6 +1141,7 @@ __device__ __forceinline__ void proj_tile(const DevPtrs& d, int cur, int tile, i
             sh.t[tid] = on ? my_t : 0;
             sh.cap[tid] = on ? my_cap : 0;
         }
+        if (tid == 0) *sh.ok = 1;
         // requested now that the projection fragments have left the registers
         if constexpr (!PRENET_FIRST) load_prenet_weights();
     }
@@ -1173,7 +1188,7 @@ __device__ __forceinline__ void proj_tile(const DevPtrs& d, int cur, int tile, i
                     }
                 }
             }
-            if (!all_in) *d.fault = 1;
+            if (!all_in) *sh.ok = 0;
 #pragma unroll
             for (int h = 0; h < G - 1; ++h)
 #pragma unroll
@@ -1187,6 +1202,18 @@ __device__ __forceinline__ void proj_tile(const DevPtrs& d, int cur, int tile, i
             sh.mel[idx & 15][idx >> 4] = v[it];
         }
         __syncthreads();
+        // A wait that ran out: the helpers' sums never came, so this tile's frames cannot be formed.  Its requests are
+        // frozen where they stand (done: every later kernel leaves them alone; failed: the host tells their owners) and
+        // nothing of this step is stored for them; the step counter below still advances for everyone else.
+        const bool gave_up = *sh.ok == 0;
+        __syncthreads();
+        if (gave_up && tid < 16 && sh.slot[tid] >= 0) {
+            d.done[sh.slot[tid]] = 1;
+            d.failed[sh.slot[tid]] = 1;
+            *d.fault = 1;
+            sh.slot[tid] = -1;
+        }
+        if (gave_up) __syncthreads();
         for (int idx = tid; idx < 16 * N_PROJ; idx += PROJ_THREADS) {
             const int r = idx / N_PROJ, o = idx - r * N_PROJ;
             const int sl = sh.slot[r];
@@ -1389,6 +1416,7 @@ __device__ __forceinline__ void slot_init(const DevPtrs& d, int slot, int L, int
         d.t[slot] = 0;
         d.n_steps[slot] = n_steps;
         d.done[slot] = 0;
+        d.failed[slot] = 0;
     }
 }
 
@@ -1449,7 +1477,7 @@ __global__ __launch_bounds__(256) void k_move_slots(DevPtrs d, MoveArgs mv)
 #pragma unroll
         for (int g = 0; g < 4; ++g) vd[g] = pdc[o_from + 16 * g];
     }
-    const int sL = d.L[from], st = d.t[from], sn = d.n_steps[from], sd = d.done[from];
+    const int sL = d.L[from], st = d.t[from], sn = d.n_steps[from], sd = d.done[from], sf = d.failed[from];
     // ---- ... then stores
 #pragma unroll
     for (int b = 0; b < 2; ++b) {
@@ -1478,6 +1506,8 @@ __global__ __launch_bounds__(256) void k_move_slots(DevPtrs d, MoveArgs mv)
         d.t[to] = st;
         d.n_steps[to] = sn;
         d.done[to] = sd;
+        d.failed[to] = sf;
+        d.failed[from] = 0;
     }
     // ---- encoder memory and processed memory, 16 bytes at a time (rows are whole multiples of that), and the
     // frames produced so far (some may not have been handed out yet)

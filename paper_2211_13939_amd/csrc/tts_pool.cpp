@@ -71,7 +71,7 @@ namespace {
 struct Layout {
     size_t Wa, Wd, ba, bd, Wq, Wq_epi, qpart, pre_att, pre_dec, proj_part, WmemT, lsa_kfrag, lsa_wfrag, v, Wmel, bmel, Wp1, Wp2;
     size_t xatt[2], xdec[2], c_att, c_dec, m_last, w_last[2], w_acc[2], Fmem, PM, mel_ring, stop_ring;
-    size_t L, t, n_steps, done, live, proj_seq, step_seq, lsa_x, stage;
+    size_t L, t, n_steps, done, failed, live, proj_seq, step_seq, lsa_x, stage;
     size_t total, proj_part_bytes;
 };
 
@@ -142,10 +142,11 @@ Layout make_layout(const tts_config& c)
     l.t = a.take(S * 4);
     l.n_steps = a.take(S * 4);
     l.done = a.take(S * 4);
+    l.failed = a.take(S * 4);
     l.live = a.take(MAX_POOL * 4);
     l.proj_seq = a.take((size_t)MAX_TILES * PROJ_GROUP * 4);     // zeroed at creation with the counters above
     l.step_seq = a.take(4);
-    l.lsa_x = a.take(S * ML * 8);                                       // zeroed too: no word carries a step's number yet
+    l.lsa_x = a.take(S * ML * 8);                        // zeroed too: no word carries a step's number yet
     l.stage = a.take(ML * ENC * 4);
     l.total = a.off;
     return l;
@@ -236,14 +237,42 @@ struct tts_pool {
     std::map<int, hipGraphExec_t> graphs;   // key = ((steps * 1024 + bucket) * 2 + parity
     std::vector<hipGraph_t> graph_defs;
     int* h_fault = nullptr;       // pinned, mapped: non-zero once a kernel's bounded wait has run out
+    int n_slots_padded = 0;       // slots the arena holds (max_pool rounded up to whole tiles)
+    std::vector<int64_t> lost_ids; // requests the device ended early that tts_pool_sync has not reported yet
 };
 
-// After a synchronisation that hands results to the caller: did every kernel finish its work?
-static int device_ok(const tts_pool* p)
+// After the stream has been waited for: did a workgroup's bounded wait run out since the last look?  The kernels froze
+// the requests concerned on the device (no frame was stored for them from that step on, every other request went on);
+// here the host's bookkeeping follows: each such request ends after the frames the device holds for it and is marked
+// lost, the device's marks and the status word are cleared.  The ids wait in `lost_ids` for the next tts_pool_sync.
+static int absorb_failures(tts_pool* p)
 {
-    if (p->h_fault && *p->h_fault)
-        return fail(TTS_E_HIP, "a workgroup gave up waiting for the words of its partners (projection sums or attention energies): frames since the last check are invalid");
+    if (!p->h_fault || !*p->h_fault) return TTS_OK;
+    const int n = p->n_slots_padded;
+    std::vector<int> failed(n), t(n);
+    HIP_TRY(hipMemcpyAsync(failed.data(), p->d.failed, (size_t)n * 4, hipMemcpyDeviceToHost, p->stream));
+    HIP_TRY(hipMemcpyAsync(t.data(), p->d.t, (size_t)n * 4, hipMemcpyDeviceToHost, p->stream));
+    HIP_TRY(hipMemsetAsync(p->d.failed, 0, (size_t)n * 4, p->stream));
+    HIP_TRY(hipStreamSynchronize(p->stream));
+    *p->h_fault = 0;
+    for (int sl = 0; sl < n && sl < p->cfg.max_pool; ++sl) {
+        if (!failed[sl] || p->book->slot(sl).state == SlotState::Free) continue;
+        p->book->lose(sl, t[sl]);
+        p->lost_ids.push_back(p->book->slot(sl).id);
+    }
     return TTS_OK;
+}
+
+// what tts_pool_sync says about the requests lost since it last said so
+static int report_lost(tts_pool* p)
+{
+    if (p->lost_ids.empty()) return TTS_OK;
+    std::string ids;
+    for (size_t i = 0; i < p->lost_ids.size() && i < 8; ++i) ids += (i ? ", " : "") + std::to_string((long long)p->lost_ids[i]);
+    const size_t n = p->lost_ids.size();
+    p->lost_ids.clear();
+    return fail(TTS_E_LOST, "%zu request(s) ended early (id %s%s): a workgroup gave up waiting for the words of its partners; "
+                "their frames so far are valid and can be drained, no further ones will come", n, ids.c_str(), n > 8 ? ", ..." : "");
 }
 
 static int upload_weights(tts_pool* p, const tts_weights* w, char* base, const Layout& l)
@@ -343,6 +372,7 @@ extern "C" int tts_pool_create(const tts_config* cfg, const tts_weights* w, void
     p->stream = (hipStream_t)hip_stream;
     p->stop_enabled = cfg->stop_threshold >= 0.f && cfg->stop_threshold <= 1.f;
     p->book.reset(new PoolBook(cfg->max_pool, cfg->max_enc_len, cfg->max_steps, cfg->chunk_frames));
+    p->n_slots_padded = (cfg->max_pool + 15) / 16 * 16;
 
     char* base = (char*)dev_arena;
     DevPtrs& d = p->d;
@@ -399,6 +429,7 @@ extern "C" int tts_pool_create(const tts_config* cfg, const tts_weights* w, void
     d.t = (int*)(base + l.t);
     d.n_steps = (int*)(base + l.n_steps);
     d.done = (int*)(base + l.done);
+    d.failed = (int*)(base + l.failed);
     d.live = (int*)(base + l.live);
     d.stage = (float*)(base + l.stage);
     d.wait_polls = DEFAULT_WAIT_POLLS;
@@ -738,7 +769,17 @@ extern "C" int tts_pool_drain_chunk(tts_pool* p, int64_t id, float* dst, int* ou
         const float* src = p->d.mel_ring + ((size_t)slot * p->cfg.max_steps + first) * N_MEL;
         HIP_TRY(hipMemcpyAsync(dst, src, (size_t)count * N_MEL * 4, hipMemcpyDeviceToHost, p->stream));
         HIP_TRY(hipStreamSynchronize(p->stream));
-        if ((rc = device_ok(p))) return rc;
+        if (*p->h_fault) {
+            // some request was frozen since the last look: if it is this one, the plan above counted frames that were
+            // never made; plan again from what the device holds (the copy above is then repeated for the right range)
+            if ((rc = absorb_failures(p))) return rc;
+            p->book->drain_plan(slot, &first, &count, &fin);
+            if (count > 0) {
+                src = p->d.mel_ring + ((size_t)slot * p->cfg.max_steps + first) * N_MEL;
+                HIP_TRY(hipMemcpyAsync(dst, src, (size_t)count * N_MEL * 4, hipMemcpyDeviceToHost, p->stream));
+                HIP_TRY(hipStreamSynchronize(p->stream));
+            }
+        }
         p->book->drain_commit(slot, count);
     }
     *out_frames = count;
@@ -755,6 +796,12 @@ extern "C" int tts_pool_chunk_window(tts_pool* p, int64_t id, int context, float
     if (slot < 0) return fail(TTS_E_NOTFOUND, "no request with id %lld", (long long)id);
     int rc = refresh_slot(p, slot);
     if (rc) return rc;
+    // a request frozen by steps that have already run must not hand out frames it never made (steps still in flight
+    // are the caller's to wait for: tts_pool_sync reports what they lost)
+    if (*p->h_fault) {
+        HIP_TRY(hipStreamSynchronize(p->stream));
+        if ((rc = absorb_failures(p))) return rc;
+    }
     int first, count, fin;
     p->book->drain_plan(slot, &first, &count, &fin);
     const int ctx = count > 0 ? (first < context ? first : context) : 0;
@@ -799,6 +846,10 @@ extern "C" int tts_pool_frames(tts_pool* p, int64_t id, int* out_frames, int* ou
     if (slot < 0) return fail(TTS_E_NOTFOUND, "no request with id %lld", (long long)id);
     int rc = refresh_slot(p, slot);
     if (rc) return rc;
+    if (*p->h_fault) {
+        HIP_TRY(hipStreamSynchronize(p->stream));
+        if ((rc = absorb_failures(p))) return rc;
+    }
     if (out_frames) *out_frames = p->book->slot(slot).t;
     if (out_finished) *out_finished = p->book->slot(slot).state == SlotState::Finished;
     return TTS_OK;
@@ -813,7 +864,22 @@ extern "C" int tts_pool_sync(tts_pool* p)
 {
     if (!p) return fail(TTS_E_INVAL, "pool is null");
     HIP_TRY(hipStreamSynchronize(p->stream));
-    return device_ok(p);
+    int rc = absorb_failures(p);
+    return rc ? rc : report_lost(p);
+}
+
+extern "C" int tts_pool_lost(tts_pool* p, int64_t id, int* out_lost)
+{
+    if (!p || !out_lost) return fail(TTS_E_INVAL, "null argument");
+    const int slot = p->book->find(id);
+    if (slot < 0) return fail(TTS_E_NOTFOUND, "no request with id %lld", (long long)id);
+    int rc = TTS_OK;
+    if (*p->h_fault) {
+        HIP_TRY(hipStreamSynchronize(p->stream));
+        if ((rc = absorb_failures(p))) return rc;
+    }
+    *out_lost = p->book->slot(slot).lost ? 1 : 0;
+    return TTS_OK;
 }
 
 extern "C" int tts_pool_set_wait_polls(tts_pool* p, int polls)

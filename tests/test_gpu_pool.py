@@ -351,28 +351,47 @@ def test_state_overwrite_refreshes_the_gate_presums(bf16, max_pool, weights_bf16
         pool.close()
 
 
-def test_wait_bound_zero_reports_an_error_and_nothing_hangs(wl8, weights_fp32, solo_frames):
+def test_wait_bound_zero_loses_only_the_step_in_flight_and_the_pool_goes_on(wl8, weights_fp32, solo_frames):
     """In pools of at most 64 slots workgroups wait, a bounded number of polls, for words other workgroups hand
-    them.  With the bound set to zero every such wait gives up at once: the kernels run through, sync and drain
-    report the error from then on; a pool with the default bound is not affected."""
+    them.  With the bound set to zero (forced from the host: every kernel still runs through) every such wait gives
+    up at once.  The requests whose words were missing are frozen at the frames they have -- nothing invalid is ever
+    stored -- and reported once; after that the same pool serves new requests with exactly the solo frames again."""
+    from paper_2211_13939_amd import binding
     from paper_2211_13939_amd.binding import TtsError
-    say("case: wait bound 0 (error path, forced from the host)")
+    say("case: wait bound 0 (give-up path, forced from the host), then the same pool again")
     pool = make_pool(wl8, weights_fp32, max_pool=8, max_enc_len=90, max_steps=24, chunk_frames=24)
-    rid = pool.add_request(wl8.encoder_outputs(1), 24)
+    rids = [pool.add_request(wl8.encoder_outputs(i), 24) for i in (1, 2)]
     pool.step_n(3)
     pool.sync()                      # fine so far
+    assert not pool.lost(rids[0])
     pool.set_wait_polls(0)
     pool.step_n(2)                   # returns: nothing hangs
+    with pytest.raises(TtsError) as info:
+        pool.sync()
+    assert info.value.code == binding.TTS_E_LOST and str(rids[0]) in str(info.value)
+    pool.sync()                      # said once; the pool is usable
+    for k, i in enumerate((1, 2)):
+        assert pool.lost(rids[k])
+        assert pool.frames(rids[k]) == (3, True)
+        got = _drain(pool, rids[k])  # the frames made before the give-up are valid and complete
+        np.testing.assert_array_equal(got, solo_frames[i][:3])
+        pool.retire(rids[k])
+    # with the bound still at zero a new request is lost at its first step, and says so
+    rid = pool.add_request(wl8.encoder_outputs(3), 24)
+    pool.step_n(4)
     with pytest.raises(TtsError):
         pool.sync()
-    with pytest.raises(TtsError):
-        pool.sync()                  # sticky
+    assert pool.lost(rid) and pool.frames(rid) == (0, True)
+    pool.retire(rid)
+    # the default bound again: the same pool, the same slots, the solo frames bit for bit
+    pool.set_wait_polls(1 << 18)
+    again = [pool.add_request(wl8.encoder_outputs(i), 24) for i in (1, 2, 3)]
+    pool.step_n(24)
+    pool.sync()
+    for k, i in enumerate((1, 2, 3)):
+        assert not pool.lost(again[k])
+        np.testing.assert_array_equal(_drain(pool, again[k]), solo_frames[i])
     pool.close()
-    other = make_pool(wl8, weights_fp32, max_pool=8, max_enc_len=90, max_steps=24, chunk_frames=24)
-    rid = other.add_request(wl8.encoder_outputs(1), 24)
-    other.step_n(24)
-    np.testing.assert_array_equal(_drain(other, rid), solo_frames[1])
-    other.close()
 
 
 def test_steps_beside_other_work_on_the_gpu(wl8, weights_fp32, solo_frames):
