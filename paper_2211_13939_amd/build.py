@@ -11,6 +11,9 @@ SOURCES = ["kernels.hip", "tts_pool.cpp", "postnet.hip", "postnet.cpp", "vocoder
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         # the first 16 dwords of a kernel's arguments arrive in scalar registers with the wave (gfx950 preloads them):
+         # the first loads of a kernel no longer wait for a cold read of the argument block
+         "-mllvm", "-amdgpu-kernarg-preload-count=16",
          "-Wall", "-Wno-unused-result"]
 
 

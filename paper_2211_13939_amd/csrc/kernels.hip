@@ -305,10 +305,21 @@ constexpr int PG_R = 3, PG_T = 2;
 constexpr int PG_CH = 2, PG_WIN = 4;
 typedef floatx4 (*PresumRed)[PG_R * PG_T][64];
 
+// What the projection kernel's launch requests first, as kernel arguments of their own (the leading 16 dwords of a
+// kernel's arguments arrive in scalar registers with the wave; the rest has to be read from memory first).
+struct ProjHot {
+    const uint4 *Wa, *Wd;           // the gate matrices
+    const void *xatt_nxt, *xdec_nxt; // the activation halves the next step reads
+    const void* xdec_cur;           // a of this step
+    const void* Wmel;
+    const int* live;
+    unsigned* proj_seq;
+};
+
 // DEC: the decoder LSTM's pre-sums too (pools of at most four tiles; larger pools keep all of its K in its own kernel
 // and have no buffer for them)
 template <typename XT, int NR, int NT, bool DEC>
-__device__ __forceinline__ void gate_presums_rt(const DevPtrs& d, int nxt, int r0, int t0, PresumRed red)
+__device__ __forceinline__ void gate_presums_rt(const DevPtrs& d, const ProjHot& hot, int r0, int t0, PresumRed red)
 {
     constexpr int NW = LSTM_WAVES, KB = Frag<XT>::KB;
     constexpr int NK_A = K_ATT / KB, NK_D = K_DEC / KB;
@@ -317,10 +328,10 @@ __device__ __forceinline__ void gate_presums_rt(const DevPtrs& d, int nxt, int r
     static_assert((NK_A / NW - F0_A) % PG_CH == 0 && (NK_D / NW - F0_D) % PG_CH == 0, "the late fragments split evenly into chunks");
     static_assert(NR * NT <= NW, "one wave adds up one (row tile, pool tile) sum");
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const uint4* __restrict__ Wa = d.Wa;
-    const uint4* __restrict__ Wd = d.Wd;
-    const uint4* __restrict__ xa = reinterpret_cast<const uint4*>(d.xatt[nxt]);
-    const uint4* __restrict__ xd = reinterpret_cast<const uint4*>(d.xdec[nxt]);
+    const uint4* __restrict__ Wa = hot.Wa;
+    const uint4* __restrict__ Wd = hot.Wd;
+    const uint4* __restrict__ xa = reinterpret_cast<const uint4*>(hot.xatt_nxt);
+    const uint4* __restrict__ xd = reinterpret_cast<const uint4*>(hot.xdec_nxt);
 
     uint4 a[PG_WIN][NR][PG_CH], b[PG_WIN][NT][PG_CH];
     floatx4 acc[NR][NT];
@@ -381,26 +392,26 @@ __device__ __forceinline__ void gate_presums_rt(const DevPtrs& d, int nxt, int r
 }
 
 template <typename XT, bool DEC>
-__device__ __forceinline__ void gate_presums_sel(const DevPtrs& d, int nxt, int r0, int nr, int t0, int nt, PresumRed red)
+__device__ __forceinline__ void gate_presums_sel(const DevPtrs& d, const ProjHot& hot, int r0, int nr, int t0, int nt, PresumRed red)
 {
     if (nt == 1) {
-        if (nr == 1) gate_presums_rt<XT, 1, 1, DEC>(d, nxt, r0, t0, red);
-        else if (nr == 2) gate_presums_rt<XT, 2, 1, DEC>(d, nxt, r0, t0, red);
-        else gate_presums_rt<XT, 3, 1, DEC>(d, nxt, r0, t0, red);
+        if (nr == 1) gate_presums_rt<XT, 1, 1, DEC>(d, hot, r0, t0, red);
+        else if (nr == 2) gate_presums_rt<XT, 2, 1, DEC>(d, hot, r0, t0, red);
+        else gate_presums_rt<XT, 3, 1, DEC>(d, hot, r0, t0, red);
     } else {
-        if (nr == 1) gate_presums_rt<XT, 1, 2, DEC>(d, nxt, r0, t0, red);
-        else if (nr == 2) gate_presums_rt<XT, 2, 2, DEC>(d, nxt, r0, t0, red);
-        else gate_presums_rt<XT, 3, 2, DEC>(d, nxt, r0, t0, red);
+        if (nr == 1) gate_presums_rt<XT, 1, 2, DEC>(d, hot, r0, t0, red);
+        else if (nr == 2) gate_presums_rt<XT, 2, 2, DEC>(d, hot, r0, t0, red);
+        else gate_presums_rt<XT, 3, 2, DEC>(d, hot, r0, t0, red);
     }
 }
 
 // The pre-sums of the next step, from the activation halves that step will read (cur ^ 1 of the step that is running),
 // for nr in 1 .. PG_R row tiles and nt in 1 .. PG_T pool tiles (the same for the whole workgroup).
 template <typename XT>
-__device__ __forceinline__ void gate_presums(const DevPtrs& d, int nxt, int r0, int nr, int t0, int nt, PresumRed red)
+__device__ __forceinline__ void gate_presums(const DevPtrs& d, const ProjHot& hot, int r0, int nr, int t0, int nt, PresumRed red)
 {
-    if (d.pre_dec) gate_presums_sel<XT, true>(d, nxt, r0, nr, t0, nt, red);
-    else gate_presums_sel<XT, false>(d, nxt, r0, nr, t0, nt, red);
+    if (d.pre_dec) gate_presums_sel<XT, true>(d, hot, r0, nr, t0, nt, red);
+    else gate_presums_sel<XT, false>(d, hot, r0, nr, t0, nt, red);
 }
 
 // Pools that span more than four tiles: a workgroup has up to PG_WALK_R row tiles and up to four pool tiles.  Its row
@@ -461,19 +472,19 @@ __device__ __forceinline__ void gate_presum_walk(const uint4* __restrict__ W, co
 }
 
 template <typename XT>
-__device__ __forceinline__ void gate_presums_walk(const DevPtrs& d, int nxt, int r0, int nr, int t0, int nt, WalkRed red)
+__device__ __forceinline__ void gate_presums_walk(const DevPtrs& d, const ProjHot& hot, int r0, int nr, int t0, int nt, WalkRed red)
 {
-    const uint4* xa = reinterpret_cast<const uint4*>(d.xatt[nxt]);
-    const uint4* xd = reinterpret_cast<const uint4*>(d.xdec[nxt]);
+    const uint4* xa = reinterpret_cast<const uint4*>(hot.xatt_nxt);
+    const uint4* xd = reinterpret_cast<const uint4*>(hot.xdec_nxt);
     floatx4* pa = reinterpret_cast<floatx4*>(d.pre_att);
     floatx4* pd = reinterpret_cast<floatx4*>(d.pre_dec);
     if constexpr (sizeof(XT) == 2) {
         switch (nr) {
-        case 1: gate_presum_walk<XT, K_ATT, 1>(d.Wa, xa, pa, r0, t0, nt, red); if (pd) gate_presum_walk<XT, K_DEC, 1>(d.Wd, xd, pd, r0, t0, nt, red); break;
-        case 2: gate_presum_walk<XT, K_ATT, 2>(d.Wa, xa, pa, r0, t0, nt, red); if (pd) gate_presum_walk<XT, K_DEC, 2>(d.Wd, xd, pd, r0, t0, nt, red); break;
-        case 3: gate_presum_walk<XT, K_ATT, 3>(d.Wa, xa, pa, r0, t0, nt, red); if (pd) gate_presum_walk<XT, K_DEC, 3>(d.Wd, xd, pd, r0, t0, nt, red); break;
-        case 4: gate_presum_walk<XT, K_ATT, 4>(d.Wa, xa, pa, r0, t0, nt, red); if (pd) gate_presum_walk<XT, K_DEC, 4>(d.Wd, xd, pd, r0, t0, nt, red); break;
-        default: gate_presum_walk<XT, K_ATT, 5>(d.Wa, xa, pa, r0, t0, nt, red); if (pd) gate_presum_walk<XT, K_DEC, 5>(d.Wd, xd, pd, r0, t0, nt, red); break;
+        case 1: gate_presum_walk<XT, K_ATT, 1>(hot.Wa, xa, pa, r0, t0, nt, red); if (pd) gate_presum_walk<XT, K_DEC, 1>(hot.Wd, xd, pd, r0, t0, nt, red); break;
+        case 2: gate_presum_walk<XT, K_ATT, 2>(hot.Wa, xa, pa, r0, t0, nt, red); if (pd) gate_presum_walk<XT, K_DEC, 2>(hot.Wd, xd, pd, r0, t0, nt, red); break;
+        case 3: gate_presum_walk<XT, K_ATT, 3>(hot.Wa, xa, pa, r0, t0, nt, red); if (pd) gate_presum_walk<XT, K_DEC, 3>(hot.Wd, xd, pd, r0, t0, nt, red); break;
+        case 4: gate_presum_walk<XT, K_ATT, 4>(hot.Wa, xa, pa, r0, t0, nt, red); if (pd) gate_presum_walk<XT, K_DEC, 4>(hot.Wd, xd, pd, r0, t0, nt, red); break;
+        default: gate_presum_walk<XT, K_ATT, 5>(hot.Wa, xa, pa, r0, t0, nt, red); if (pd) gate_presum_walk<XT, K_DEC, 5>(hot.Wd, xd, pd, r0, t0, nt, red); break;
         }
     }
 }
@@ -484,8 +495,9 @@ __global__ __launch_bounds__(LSTM_WAVES * 64) void k_presum_tile(DevPtrs d, int 
 {
     __shared__ floatx4 red[LSTM_WAVES][PG_R * PG_T][64];
     static_assert(PG_WALK_R <= PG_R * PG_T, "either form's reduction buffer");
-    if (d.pre_dec) gate_presums<XT>(d, nxt, blockIdx.x, 1, tile, 1, red);
-    else gate_presums_walk<XT>(d, nxt, blockIdx.x, 1, tile, 1, reinterpret_cast<WalkRed>(&red[0][0][0]));   // the attention LSTM's only
+    const ProjHot hot = {d.Wa, d.Wd, d.xatt[nxt], d.xdec[nxt], nullptr, d.Wmel, d.live, d.proj_seq};
+    if (d.pre_dec) gate_presums<XT>(d, hot, blockIdx.x, 1, tile, 1, red);
+    else gate_presums_walk<XT>(d, hot, blockIdx.x, 1, tile, 1, reinterpret_cast<WalkRed>(&red[0][0][0]));   // the attention LSTM's only
 }
 
 // ---------------------------------------------------------------------------
@@ -592,8 +604,11 @@ template <> struct LsaTile<h16_t> {
     }
 };
 
+// The first eight arguments repeat pointers that are also in `d_all`: the leading 16 dwords of a kernel's arguments
+// arrive in scalar registers with the wave, so the prologue's loads can go out before the argument block has been read.
 template <typename XT, typename MT, int S, bool QP>
-__global__ __launch_bounds__(LSA_THREADS) void k_lsa(DevPtrs d, int cur, int n_slots)
+__global__ __launch_bounds__(LSA_THREADS) void k_lsa(int* L_first, int* live_first, int* done_first, unsigned* seq_first, float* qpart_first,
+                                                    float* w_last_first, float* w_acc_first, void* PM_first, DevPtrs d, int cur, int n_slots)
 {
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int jl = lane & 15, g = lane >> 4;
@@ -611,12 +626,12 @@ __global__ __launch_bounds__(LSA_THREADS) void k_lsa(DevPtrs d, int cur, int n_s
     const int xcd = blockIdx.x & 7, kx = blockIdx.x >> 3;
     const int slot_raw = (kx / S) * 8 + xcd, sp = kx % S;
     const int slot = min(slot_raw, n_slots - 1);
-    const int live_w = d.live[slot], done_w = d.done[slot], L_w = d.L[slot];
+    const int live_w = live_first[slot], done_w = done_first[slot], L_w = L_first[slot];
     const bool twin = slot_raw >= n_slots;
     // the request's S workgroups share the energies (below): this step's number marks the words they exchange
     constexpr bool XCH = S > 1;
     unsigned seq = 0;
-    if constexpr (XCH) seq = d.step_seq[0] + 1u;
+    if constexpr (XCH) seq = seq_first[0] + 1u;
     // q = W_q h_att, one of two ways.
     // QP (pools with gate pre-sums): it arrives as QP_TALL rank-32 partial products written by this step's attention
     // LSTM.  Thread (a = tid % 128, quarter = tid / 128) adds up its quarter's pair sums P[2i] + P[2i+1] in
@@ -631,7 +646,7 @@ __global__ __launch_bounds__(LSA_THREADS) void k_lsa(DevPtrs d, int cur, int n_s
     uint4 qa[MG][QP ? 1 : NKW];
     const uint4* Wq = reinterpret_cast<const uint4*>(d.Wq) + (size_t)(wave * NKW) * 64 + lane;
     if constexpr (QP) {
-        const float* qp = d.qpart + ((size_t)slot * QP_TALL + (tid >> 7) * QN) * ATT + (tid & (ATT - 1));
+        const float* qp = qpart_first + ((size_t)slot * QP_TALL + (tid >> 7) * QN) * ATT + (tid & (ATT - 1));
 #pragma unroll
         for (int i = 0; i < QN; ++i) qv[i] = qp[(size_t)i * ATT];
     } else {
@@ -653,9 +668,9 @@ __global__ __launch_bounds__(LSA_THREADS) void k_lsa(DevPtrs d, int cur, int n_s
     constexpr int NPM = Vec16<MT>::N;
     constexpr int NV = 32 / NPM;                  // 16-byte pieces of a lane's 32 attention dims of PM[j]
     const int ML = d.max_enc_len;
-    const MT* PMs = reinterpret_cast<const MT*>(d.PM) + (size_t)slot * ML * ATT + 32 * g;
-    const float* wl = d.w_last[cur] + (size_t)slot * ML;
-    const float* wa = d.w_acc[cur] + (size_t)slot * ML;
+    const MT* PMs = reinterpret_cast<const MT*>(PM_first) + (size_t)slot * ML * ATT + 32 * g;
+    const float* wl = w_last_first + (size_t)slot * ML;
+    const float* wa = w_acc_first + (size_t)slot * ML;
 
     // ---- everything the prologue needs is requested before anything is consumed
     constexpr int UPT = (LSA_UPAD + LSA_THREADS - 1) / LSA_THREADS;
@@ -1034,7 +1049,7 @@ struct ProjShared {
 
 // One workgroup's part of a tile: workgroup `kp` of G contracts fragments [kp, kp + 1) * NK / G of K; kp = 0 leads.
 template <typename XT, int G, bool LEADER>
-__device__ __forceinline__ void proj_tile(const DevPtrs& d, int cur, int tile, int kp, const ProjShared& sh)
+__device__ __forceinline__ void proj_tile(const DevPtrs& d, const ProjHot& hot, int cur, int tile, int kp, const ProjShared& sh)
 {
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int jl = lane & 15, g = lane >> 4;
@@ -1059,8 +1074,8 @@ __device__ __forceinline__ void proj_tile(const DevPtrs& d, int cur, int tile, i
     float (*s_hid)[PROJ_HID_LD] = reinterpret_cast<float (*)[PROJ_HID_LD]>(sh.big);
     static_assert(16 * PROJ_HID_LD <= PROJ_WAVES * PROJ_ROWS * 16, "hid must fit the partial-sum buffer it aliases");
 
-    const uint4* xnew = reinterpret_cast<const uint4*>(d.xdec[cur ^ 1]);   // h_dec of this step
-    const uint4* xcur = reinterpret_cast<const uint4*>(d.xdec[cur]);       // a of this step
+    const uint4* xnew = reinterpret_cast<const uint4*>(hot.xdec_nxt);      // h_dec of this step
+    const uint4* xcur = reinterpret_cast<const uint4*>(hot.xdec_cur);      // a of this step
     const int ks0 = (kp * PROJ_WAVES + wave) * NKW;
     uint4 b[NKW];
 #pragma unroll
@@ -1071,7 +1086,7 @@ __device__ __forceinline__ void proj_tile(const DevPtrs& d, int cur, int tile, i
     }
     // this workgroup's sequence number: the steps it has taken part in
     unsigned my_seq = 0;
-    if constexpr (G > 1) my_seq = d.proj_seq[tile * G + kp];
+    if constexpr (G > 1) my_seq = hot.proj_seq[tile * G + kp];
     // slot bookkeeping of the 16 columns and this thread's biases of the reduction phase
     const int my_sl = tile * 16 + (tid & 15);
     int my_live = 0, my_done = 0, my_t = 0, my_cap = 0;
@@ -1081,12 +1096,12 @@ __device__ __forceinline__ void proj_tile(const DevPtrs& d, int cur, int tile, i
     unsigned step_no = 0;
     if constexpr (LEADER) {
         step_no = d.step_seq[0];
-        my_live = d.live[my_sl]; my_done = d.done[my_sl]; my_t = d.t[my_sl]; my_cap = d.n_steps[my_sl];
+        my_live = hot.live[my_sl]; my_done = d.done[my_sl]; my_t = d.t[my_sl]; my_cap = d.n_steps[my_sl];
 #pragma unroll
         for (int it = 0; it < RED_IT; ++it) bias_r[it] = d.bmel[min((tid + it * PROJ_THREADS) >> 4, N_PROJ - 1)];
     }
 
-    const uint4* W = reinterpret_cast<const uint4*>(d.Wmel) + lane;
+    const uint4* W = reinterpret_cast<const uint4*>(hot.Wmel) + lane;
     uint4 a[MH][NKW];
     auto load_proj_weights = [&](int m0) __attribute__((always_inline)) {
 #pragma unroll
@@ -1168,7 +1183,7 @@ __device__ __forceinline__ void proj_tile(const DevPtrs& d, int cur, int tile, i
         for (int it = 0; it < RED_IT; ++it)
             __hip_atomic_store(&mine[tid + it * PROJ_THREADS], ((unsigned long long)(my_seq + 1u) << 32) | __float_as_uint(v[it]),
                                __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (tid == 0) d.proj_seq[tile * G + kp] = my_seq + 1u;
+        if (tid == 0) hot.proj_seq[tile * G + kp] = my_seq + 1u;
         return;
     } else {
         if constexpr (G > 1) {
@@ -1193,7 +1208,7 @@ __device__ __forceinline__ void proj_tile(const DevPtrs& d, int cur, int tile, i
             for (int h = 0; h < G - 1; ++h)
 #pragma unroll
                 for (int it = 0; it < RED_IT; ++it) v[it] += __uint_as_float((unsigned)w[h][it]);
-            if (tid == 0) d.proj_seq[tile * G] = my_seq + 1u;
+            if (tid == 0) hot.proj_seq[tile * G] = my_seq + 1u;
         }
         // ... bias is in; hand the frame out
 #pragma unroll
@@ -1286,8 +1301,11 @@ __device__ __forceinline__ void proj_tile(const DevPtrs& d, int cur, int tile, i
 
 // G: workgroups per pool tile (fixed per pool: it sets the order in which the mel projection is summed)
 template <typename XT, bool PRE, int G>
-__global__ __launch_bounds__(PROJ_THREADS) void k_proj(DevPtrs d, int cur, int n_tiles)
+__global__ __launch_bounds__(PROJ_THREADS) void k_proj(const uint4* Wa_first, const uint4* Wd_first, const void* xatt_nxt_first, const void* xdec_nxt_first,
+                                                      const void* xdec_cur_first, const void* Wmel_first, const int* live_first, unsigned* proj_seq_first,
+                                                      DevPtrs d, int cur, int n_tiles)
 {
+    const ProjHot hot = {Wa_first, Wd_first, xatt_nxt_first, xdec_nxt_first, xdec_cur_first, Wmel_first, live_first, proj_seq_first};
     __shared__ __attribute__((aligned(16))) float s_big[PROJ_WAVES * PROJ_ROWS * 16];
     // row strides of 100 and 260 floats (an odd number of 16-byte pieces): the 16 columns of a
     // fragment read then fall into 16 different bank groups instead of one
@@ -1319,7 +1337,7 @@ __global__ __launch_bounds__(PROJ_THREADS) void k_proj(DevPtrs d, int cur, int n
                     else { k -= 16; t0 = per; nt = n_tiles - per; }
                 }
                 const int lo = rx0 + (rx1 - rx0) * k / Mc, hi = rx0 + (rx1 - rx0) * (k + 1) / Mc;
-                gate_presums<XT>(d, cur ^ 1, lo, hi - lo, t0, nt, reinterpret_cast<PresumRed>(s_big));
+                gate_presums<XT>(d, hot, lo, hi - lo, t0, nt, reinterpret_cast<PresumRed>(s_big));
             } else {
                 const int CG = (n_tiles + 3) / 4, Mc = 32 / CG;          // 2, 3 or 4 groups of 16, 10 or 8 workgroups
                 const int cg = i / Mc, k = i - cg * Mc;
@@ -1327,18 +1345,18 @@ __global__ __launch_bounds__(PROJ_THREADS) void k_proj(DevPtrs d, int cur, int n
                 const int per = (n_tiles + CG - 1) / CG, t0 = cg * per;
                 const int nt = min(per, n_tiles - t0);
                 const int lo = rx0 + (rx1 - rx0) * k / Mc, hi = rx0 + (rx1 - rx0) * (k + 1) / Mc;
-                if (nt > 0) gate_presums_walk<XT>(d, cur ^ 1, lo, hi - lo, t0, nt, reinterpret_cast<WalkRed>(s_big));
+                if (nt > 0) gate_presums_walk<XT>(d, hot, lo, hi - lo, t0, nt, reinterpret_cast<WalkRed>(s_big));
             }
             return;
         }
         if (i >= n_tiles * G) return;
-        if (i % G == 0) proj_tile<XT, G, true>(d, cur, i / G, 0, sh);
-        else proj_tile<XT, G, false>(d, cur, i / G, i % G, sh);
+        if (i % G == 0) proj_tile<XT, G, true>(d, hot, cur, i / G, 0, sh);
+        else proj_tile<XT, G, false>(d, hot, cur, i / G, i % G, sh);
     } else {
         // without pre-sums: the same workgroups per tile, wherever they land (n_tiles * G <= 96 workgroups)
         const int i = blockIdx.x;
-        if (i % G == 0) proj_tile<XT, G, true>(d, cur, i / G, 0, sh);
-        else proj_tile<XT, G, false>(d, cur, i / G, i % G, sh);
+        if (i % G == 0) proj_tile<XT, G, true>(d, hot, cur, i / G, 0, sh);
+        else proj_tile<XT, G, false>(d, hot, cur, i / G, i % G, sh);
     }
 }
 
@@ -1643,9 +1661,11 @@ static hipError_t step_typed(const DevPtrs& d, int n_req, int n_tiles, int lsa_s
     }
     mark(1);
     const int n_pad = (n_req + 7) / 8 * 8;      // slots are dealt to the XCDs in eights
-    if (lsa_split == 4) hipLaunchKernelGGL((k_lsa<XT, MT, 4, PRE>), dim3(n_pad * 4), dim3(LSA_THREADS), 0, s, d, cur, n_req);
-    else if (lsa_split == 2) hipLaunchKernelGGL((k_lsa<XT, MT, 2, PRE>), dim3(n_pad * 2), dim3(LSA_THREADS), 0, s, d, cur, n_req);
-    else hipLaunchKernelGGL((k_lsa<XT, MT, 1, PRE>), dim3(n_pad), dim3(LSA_THREADS), 0, s, d, cur, n_req);
+#define LSA_ARGS d.L, d.live, d.done, d.step_seq, d.qpart, d.w_last[cur], d.w_acc[cur], d.PM, d, cur, n_req
+    if (lsa_split == 4) hipLaunchKernelGGL((k_lsa<XT, MT, 4, PRE>), dim3(n_pad * 4), dim3(LSA_THREADS), 0, s, LSA_ARGS);
+    else if (lsa_split == 2) hipLaunchKernelGGL((k_lsa<XT, MT, 2, PRE>), dim3(n_pad * 2), dim3(LSA_THREADS), 0, s, LSA_ARGS);
+    else hipLaunchKernelGGL((k_lsa<XT, MT, 1, PRE>), dim3(n_pad), dim3(LSA_THREADS), 0, s, LSA_ARGS);
+#undef LSA_ARGS
     mark(2);
     // H_dec(t): consumed by this step's projection and the next step's decoder LSTM (same buffer)
     const uint4* xdec_in = reinterpret_cast<const uint4*>(d.xdec[cur]);
@@ -1664,9 +1684,11 @@ static hipError_t step_typed(const DevPtrs& d, int n_req, int n_tiles, int lsa_s
     mark(3);
     // with pre-sums the projection's launch fills the chip: XCD 0 runs the projection, the rest form the pre-sums
     const dim3 pg(PRE ? 256 : n_tiles * proj_group), pb(PROJ_THREADS);
-    if (proj_group == 6) hipLaunchKernelGGL((k_proj<XT, PRE, 6>), pg, pb, 0, s, d, cur, n_tiles);
-    else if (proj_group == 3) hipLaunchKernelGGL((k_proj<XT, PRE, 3>), pg, pb, 0, s, d, cur, n_tiles);
-    else if (proj_group == 2) hipLaunchKernelGGL((k_proj<XT, PRE, 2>), pg, pb, 0, s, d, cur, n_tiles);
+#define PROJ_ARGS d.Wa, d.Wd, (const void*)d.xatt[cur ^ 1], (const void*)d.xdec[cur ^ 1], (const void*)d.xdec[cur], d.Wmel, (const int*)d.live, d.proj_seq, d, cur, n_tiles
+    if (proj_group == 6) hipLaunchKernelGGL((k_proj<XT, PRE, 6>), pg, pb, 0, s, PROJ_ARGS);
+    else if (proj_group == 3) hipLaunchKernelGGL((k_proj<XT, PRE, 3>), pg, pb, 0, s, PROJ_ARGS);
+    else if (proj_group == 2) hipLaunchKernelGGL((k_proj<XT, PRE, 2>), pg, pb, 0, s, PROJ_ARGS);
+#undef PROJ_ARGS
     else return hipErrorInvalidValue;
     mark(4);
     return hipGetLastError();
