@@ -50,10 +50,9 @@ static_assert(XA_P == 0 && XD_HA == 0 && XD_A == HID, "the early parts lead the 
 
 template <typename XT, int K, bool PRE>
 __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm(
-    const uint4* __restrict__ Wfrag, const float* __restrict__ bias, const uint4* __restrict__ X,
-    float* __restrict__ c_state, XT* __restrict__ hout0, int nk0, int off0,
-    XT* __restrict__ hout1, int nk1, int off1,
-    int n_tiles, const int* __restrict__ live, const int* __restrict__ done, const floatx4* __restrict__ pre)
+    const uint4* __restrict__ Wfrag, const uint4* __restrict__ X, const float* __restrict__ bias, float* __restrict__ c_state,
+    const int* __restrict__ live, const int* __restrict__ done, const floatx4* __restrict__ pre, XT* __restrict__ hout0,
+    int nk0, int off0, XT* __restrict__ hout1, int nk1, int off1, int n_tiles)
 {
     constexpr int NW = LSTM_WAVES;
     constexpr int NK = K / Frag<XT>::KB;      // fragments per row tile / per pool tile
@@ -140,10 +139,9 @@ __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm(
 // repeated reads of the weights hit that XCD's L2.  The sums are taken in the same order as in k_lstm.
 template <typename XT, int K, int R, bool PRE = false>
 __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm_rc(
-    const uint4* __restrict__ Wfrag, const float* __restrict__ bias, const uint4* __restrict__ X,
-    float* __restrict__ c_state, XT* __restrict__ hout0, int nk0, int off0,
-    XT* __restrict__ hout1, int nk1, int off1,
-    int n_tiles, const int* __restrict__ live, const int* __restrict__ done, const floatx4* __restrict__ pre = nullptr)
+    const uint4* __restrict__ Wfrag, const uint4* __restrict__ X, const float* __restrict__ bias, float* __restrict__ c_state,
+    const int* __restrict__ live, const int* __restrict__ done, const floatx4* __restrict__ pre, XT* __restrict__ hout0,
+    int nk0, int off0, XT* __restrict__ hout1, int nk1, int off1, int n_tiles)
 {
     constexpr int NW = LSTM_WAVES;
     constexpr int NK = K / Frag<XT>::KB;
@@ -232,11 +230,9 @@ static_assert(QP_TALL == QUERY_PARTIALS, "the arena holds QUERY_PARTIALS partial
 
 template <typename XT>
 __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm_att_tall(
-    const uint4* __restrict__ Wfrag, const float* __restrict__ bias, const uint4* __restrict__ X,
-    float* __restrict__ c_state, XT* __restrict__ hout0, int nk0, int off0,
-    XT* __restrict__ hout1, int nk1, int off1,
-    const int* __restrict__ live, const int* __restrict__ done,
-    const float* __restrict__ wq_epi, float* __restrict__ qpart, const floatx4* __restrict__ pre)
+    const uint4* __restrict__ Wfrag, const uint4* __restrict__ X, const float* __restrict__ bias, float* __restrict__ c_state,
+    const int* __restrict__ live, const int* __restrict__ done, const floatx4* __restrict__ pre, const float* __restrict__ wq_epi,
+    XT* __restrict__ hout0, int nk0, int off0, XT* __restrict__ hout1, int nk1, int off1, float* __restrict__ qpart)
 {
     static_assert(TALL_RT == LSTM_WAVES, "one row tile per wave");
     constexpr int NK = K_ATT / Frag<XT>::KB;
@@ -1652,12 +1648,11 @@ static hipError_t step_typed(const DevPtrs& d, int n_req, int n_tiles, int lsa_s
     // With pre-sums: the tall kernel, which also hands the query over as partial products.  Without (fp32 pools of
     // more than four tiles): one row tile per workgroup, all of K.
     if constexpr (PRE) {
-        hipLaunchKernelGGL((k_lstm_att_tall<XT>), dim3(QP_TALL * n_tiles), lb, 0, s, d.Wa, d.ba, xatt_cur, d.c_att, xdec_cur, K_DEC / KB, XD_HA,
-                           xatt_nxt, K_ATT / KB, XA_H, d.live, d.done, d.Wq_epi, d.qpart, reinterpret_cast<const floatx4*>(d.pre_att));
+        hipLaunchKernelGGL((k_lstm_att_tall<XT>), dim3(QP_TALL * n_tiles), lb, 0, s, d.Wa, xatt_cur, d.ba, d.c_att, d.live, d.done,
+                           reinterpret_cast<const floatx4*>(d.pre_att), d.Wq_epi, xdec_cur, K_DEC / KB, XD_HA, xatt_nxt, K_ATT / KB, XA_H, d.qpart);
     } else {
-        hipLaunchKernelGGL((k_lstm<XT, K_ATT, false>), lg, lb, 0, s,
-                           d.Wa, d.ba, xatt_cur, d.c_att, xdec_cur, K_DEC / KB, XD_HA, xatt_nxt, K_ATT / KB, XA_H,
-                           n_tiles, d.live, d.done, nullptr);
+        hipLaunchKernelGGL((k_lstm<XT, K_ATT, false>), lg, lb, 0, s, d.Wa, xatt_cur, d.ba, d.c_att, d.live, d.done, (const floatx4*)nullptr,
+                           xdec_cur, K_DEC / KB, XD_HA, xatt_nxt, K_ATT / KB, XA_H, n_tiles);
     }
     mark(1);
     const int n_pad = (n_req + 7) / 8 * 8;      // slots are dealt to the XCDs in eights
@@ -1672,15 +1667,15 @@ static hipError_t step_typed(const DevPtrs& d, int n_req, int n_tiles, int lsa_s
     const floatx4* pre_dec = reinterpret_cast<const floatx4*>(d.pre_dec);
     if (rows == 4) {
         if constexpr (HAS_WIDE && !PRE_DEC)
-            hipLaunchKernelGGL((k_lstm_rc<XT, K_DEC, 4>), lg, lb, 0, s, d.Wd, d.bd, xdec_in, d.c_dec, xdec_nxt, K_DEC / KB, XD_HD,
-                               xdec_nxt, K_DEC / KB, XD_HD, n_tiles, d.live, d.done, pre_dec);
+            hipLaunchKernelGGL((k_lstm_rc<XT, K_DEC, 4>), lg, lb, 0, s, d.Wd, xdec_in, d.bd, d.c_dec, d.live, d.done, pre_dec,
+                               xdec_nxt, K_DEC / KB, XD_HD, xdec_nxt, K_DEC / KB, XD_HD, n_tiles);
     } else if (rows == 2) {
         if constexpr (HAS_WIDE)
-            hipLaunchKernelGGL((k_lstm_rc<XT, K_DEC, 2, PRE_DEC>), lg, lb, 0, s, d.Wd, d.bd, xdec_in, d.c_dec, xdec_nxt, K_DEC / KB, XD_HD,
-                               xdec_nxt, K_DEC / KB, XD_HD, n_tiles, d.live, d.done, pre_dec);
+            hipLaunchKernelGGL((k_lstm_rc<XT, K_DEC, 2, PRE_DEC>), lg, lb, 0, s, d.Wd, xdec_in, d.bd, d.c_dec, d.live, d.done, pre_dec,
+                               xdec_nxt, K_DEC / KB, XD_HD, xdec_nxt, K_DEC / KB, XD_HD, n_tiles);
     } else
-        hipLaunchKernelGGL((k_lstm<XT, K_DEC, PRE_DEC>), lg, lb, 0, s, d.Wd, d.bd, xdec_in, d.c_dec, xdec_nxt, K_DEC / KB, XD_HD,
-                           xdec_nxt, K_DEC / KB, XD_HD, n_tiles, d.live, d.done, pre_dec);
+        hipLaunchKernelGGL((k_lstm<XT, K_DEC, PRE_DEC>), lg, lb, 0, s, d.Wd, xdec_in, d.bd, d.c_dec, d.live, d.done, pre_dec,
+                           xdec_nxt, K_DEC / KB, XD_HD, xdec_nxt, K_DEC / KB, XD_HD, n_tiles);
     mark(3);
     // with pre-sums the projection's launch fills the chip: XCD 0 runs the projection, the rest form the pre-sums
     const dim3 pg(PRE ? 256 : n_tiles * proj_group), pb(PROJ_THREADS);
