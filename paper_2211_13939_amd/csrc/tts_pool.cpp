@@ -629,9 +629,16 @@ static int launch_steps(tts_pool* p, int n_active, int nsteps)
         hipError_t le = hipSuccess;
         for (int i = 0; i < nsteps && le == hipSuccess; ++i) le = launch_step(p->d, sl, p->parity ^ (i & 1), p->stream);
         hipError_t ce = hipStreamEndCapture(p->stream, &g);
-        if (le != hipSuccess) return fail(TTS_E_HIP, "capture of the step failed: %s", hipGetErrorString(le));
-        if (ce != hipSuccess) return fail(TTS_E_HIP, "hipStreamEndCapture: %s", hipGetErrorString(ce));
-        HIP_TRY(hipGraphInstantiate(&ge, g, nullptr, nullptr, 0));
+        if (le != hipSuccess || ce != hipSuccess) {
+            if (ce == hipSuccess && g) (void)hipGraphDestroy(g);
+            if (le != hipSuccess) return fail(TTS_E_HIP, "capture of the step failed: %s", hipGetErrorString(le));
+            return fail(TTS_E_HIP, "hipStreamEndCapture: %s", hipGetErrorString(ce));
+        }
+        const hipError_t ie = hipGraphInstantiate(&ge, g, nullptr, nullptr, 0);
+        if (ie != hipSuccess) {
+            (void)hipGraphDestroy(g);
+            return fail(TTS_E_HIP, "hipGraphInstantiate: %s", hipGetErrorString(ie));
+        }
         p->graph_defs.push_back(g);
         it = p->graphs.emplace(key, ge).first;
     }
