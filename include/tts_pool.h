@@ -75,8 +75,12 @@ typedef struct {
     int max_steps;     /* >= 1: most frames one request may produce (size of its mel ring) */
     int chunk_frames;  /* >= 1: frames handed out per drain ("configurable size of the chunk", Sec. 2.2.1) */
     int weight_dtype;  /* TTS_DTYPE_F32: fp32 weights and activations.
-                          TTS_DTYPE_BF16: weight matrices and the activations fed to them are
-                          bfloat16, accumulation and cell/softmax arithmetic fp32. */
+                          TTS_DTYPE_BF16: the weight matrices are bfloat16 VALUES (given values are rounded to
+                          bfloat16, ties to even, at upload); accumulation and cell / softmax arithmetic are fp32.
+                          On the device the matrices are held as IEEE half, which holds every bfloat16 value of
+                          magnitude >= 2^-14 exactly (smaller ones within 2^-25), and the activations multiplied
+                          with them are rounded to IEEE half: same bytes and MFMA rate as bfloat16 operands,
+                          8 x less operand rounding.  max_steps <= 65504 in this mode. */
     int memory_dtype;  /* storage of F_enc and of the processed memory F_enc W_mem^T.
                           TTS_DTYPE_BF16 requires weight_dtype == TTS_DTYPE_BF16. */
     int use_graph;     /* non-zero: each step is one hipGraph launch */

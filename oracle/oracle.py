@@ -1,8 +1,13 @@
-"""ctypes access to the plain-C oracle (oracle/tts_oracle.c).
+"""ctypes access to the plain-C oracle (oracle/*.c).
 
 TEST INFRASTRUCTURE: only tests/, the smoke check and the benchmark's
-cpu_baseline leg may import this.  Argument marshalling only; all arithmetic is
-in the C file.
+cpu_baseline leg may import this.  The arithmetic of the decoder step, the
+PostNet, the generator and the encoder is in the C files and this module only
+marshals their arguments; the one piece of the method written here is
+VocoderStream, the response rule of Eq. 3 / Eq. 4 (which samples a chunk's
+response carries, the equal-power fade against the previous tail, the
+write-back), plain numpy in double precision with its own pins in
+tests/test_vocoder_oracle.py.
 """
 from __future__ import annotations
 
