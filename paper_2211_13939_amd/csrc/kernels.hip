@@ -861,15 +861,19 @@ __global__ __launch_bounds__(LSA_THREADS) void k_lsa(int* L_first, int* live_fir
     constexpr int NP = NR / NA;                     // 32-position passes in flight
     constexpr int VPR = 8 * (int)sizeof(MT) / 16;   // 16-byte loads per row per lane
     const int xw = wave * 4 + (lane / LPR) * NA;    // this lane's first class
-    const MT* Fm = reinterpret_cast<const MT*>(d.Fmem) + (size_t)slot * d.max_enc_len * ENC + sp * FS + (lane % LPR) * 8;
+    // Rows are fetched through a buffer descriptor that ends at the request's last row: a row past the end comes back
+    // as zeros without a memory access, so all NR loads per lane can be issued whatever the length, at no traffic.
+    const MT* Fslot = reinterpret_cast<const MT*>(d.Fmem) + (size_t)slot * d.max_enc_len * ENC;
+    const __amdgpu_buffer_rsrc_t f_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<MT*>(Fslot), 0, L * ENC * (int)sizeof(MT), BUFFER_RSRC_RAW);
+    const int f_col = (sp * FS + (lane % LPR) * 8) * (int)sizeof(MT);     // this lane's columns inside a row, in bytes
     uint4 rows[NP][NA][VPR];
 #pragma unroll
     for (int pp = 0; pp < NP; ++pp)
 #pragma unroll
         for (int c = 0; c < NA; ++c) {
-            const MT* row = Fm + (size_t)min(pp * 32 + xw + c, L - 1) * ENC;
 #pragma unroll
-            for (int v = 0; v < VPR; ++v) rows[pp][c][v] = *reinterpret_cast<const uint4*>(row + v * NPM);
+            for (int v = 0; v < VPR; ++v)
+                rows[pp][c][v] = buffer_load16(f_rsrc, (pp * 32 + xw + c) * ENC * (int)sizeof(MT) + f_col + 16 * v);
         }
     if constexpr (XCH) {
         // the other workgroups' energies: every thread polls its own words until they carry this step's number
@@ -931,22 +935,29 @@ __global__ __launch_bounds__(LSA_THREADS) void k_lsa(int* L_first, int* live_fir
             for (int i = 0; i < 8; ++i) acc[c][i] = 0.f;
         for (int x0 = 0; x0 < L; x0 += 32 * NP) {
 #pragma unroll
-            for (int pp = 0; pp < NP; ++pp)
+            for (int pp = 0; pp < NP; ++pp) {
+                // a pass of 32 positions that lies wholly past the end adds exact zeros: skipped (the same for the whole
+                // workgroup; no load sits inside the branch)
+                if (x0 + pp * 32 < L) {
 #pragma unroll
-                for (int c = 0; c < NA; ++c) {
-                    const int x = x0 + pp * 32 + xw + c;
-                    const float w = x < L ? s_e[x] : 0.f;
-                    float fv[8];
+                    for (int c = 0; c < NA; ++c) {
+                        const int x = x0 + pp * 32 + xw + c;
+                        const float w = x < L ? s_e[x] : 0.f;
+                        float fv[8];
 #pragma unroll
-                    for (int v = 0; v < VPR; ++v) Vec16<MT>::unpack(rows[pp][c][v], fv + v * NPM);
+                        for (int v = 0; v < VPR; ++v) Vec16<MT>::unpack(rows[pp][c][v], fv + v * NPM);
 #pragma unroll
-                    for (int i = 0; i < 8; ++i) acc[c][i] = fmaf(w, fv[i], acc[c][i]);
-                    // refill this register row with the row NP passes ahead (unconditional: past
-                    // the end it re-reads the last row with weight zero)
-                    const MT* row = Fm + (size_t)min(x + 32 * NP, L - 1) * ENC;
-#pragma unroll
-                    for (int v = 0; v < VPR; ++v) rows[pp][c][v] = *reinterpret_cast<const uint4*>(row + v * NPM);
+                        for (int i = 0; i < 8; ++i) acc[c][i] = fmaf(w, fv[i], acc[c][i]);
+                    }
                 }
+                // refill these register rows with the rows NP passes ahead (unconditional: past the end the loads
+                // return zeros and move nothing)
+#pragma unroll
+                for (int c = 0; c < NA; ++c)
+#pragma unroll
+                    for (int v = 0; v < VPR; ++v)
+                        rows[pp][c][v] = buffer_load16(f_rsrc, (x0 + pp * 32 + xw + c + 32 * NP) * ENC * (int)sizeof(MT) + f_col + 16 * v);
+            }
         }
         // classes held by one lane are paired here: (c0 + c1) [+ (c2 + c3)]
 #pragma unroll

@@ -101,6 +101,17 @@ template <> struct Vec16<h16_t> {
     }
 };
 
+// 16 bytes through a raw buffer descriptor (byte offset `off` from its base): a load that starts at or past the
+// descriptor's size returns zeros and touches no memory (the hardware's range check), so ragged ends need neither
+// clamped addresses nor branches.  BUFFER_RSRC_RAW is the descriptor's last word for untyped 32-bit data on gfx9.
+constexpr int BUFFER_RSRC_RAW = 0x00020000;
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 buffer_load16(__amdgpu_buffer_rsrc_t rsrc, int off)
+{
+    const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(rsrc, off, 0, 0);
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+
 // Fragment geometry for element type T: a fragment is 64 bytes of k per row / column.
 template <typename T> struct Frag {
     static constexpr int KB = 64 / (int)sizeof(T);    // k elements per fragment
