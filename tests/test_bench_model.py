@@ -11,7 +11,7 @@ import bench  # noqa: E402
 from paper_2211_13939_amd import synth  # noqa: E402
 
 
-def test_step_bytes_is_the_formula_of_the_scope_table():
+def test_step_bytes_is_the_stated_formula():
     """weights once (18 173 504 elements), 33 092 bias bytes, 640 memory elements + 16 bytes of attention weights per
     position, the 4 688-float carried state read and written + one 320-byte frame per request."""
     # the 64-request job at its full pool: sum of its encoder lengths, two-byte weights and memory
@@ -19,7 +19,7 @@ def test_step_bytes_is_the_formula_of_the_scope_table():
     sum_L = int(wl.enc_len.sum())
     assert (wl.n_requests, sum_L) == (64, 9405)
     assert bench.step_bytes(64, sum_L, 2, 2) == 18_173_504 * 2 + 33_092 + sum_L * (640 * 2 + 16) + 64 * (2 * 4688 * 4 + 320) == 50_989_716
-    # the table's own rows (full pool, mean lengths): c1 72.8 MB, c2 75.8 MB, c4 120.7 MB
+    # full pools at mean lengths: c1 72.8 MB, c2 75.8 MB, c4 120.7 MB
     assert round(bench.step_bytes(1, 20, 4, 4) / 1e6, 1) == 72.8
     assert round(bench.step_bytes(16, 16 * 60, 4, 4) / 1e6, 1) == 75.8
     assert round(bench.step_bytes(256, 256 * 225, 2, 2) / 1e6, 1) == 120.7
