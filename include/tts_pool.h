@@ -106,7 +106,8 @@ size_t tts_pool_workspace_bytes(const tts_config *cfg);
  * Create a pool.  `dev_arena` is DEVICE memory of at least
  * tts_pool_workspace_bytes(cfg) bytes, 256-byte aligned, owned by the caller
  * and kept alive until tts_pool_destroy; the library allocates no device
- * memory itself.  `hip_stream` is a hipStream_t (NULL = the default stream) on
+ * memory itself (it allocates two small pieces of pinned host memory: a status
+ * word and a staging buffer of one chunk).  `hip_stream` is a hipStream_t (NULL = the default stream) on
  * which every kernel and copy of this pool is queued; it stays owned by the
  * caller.  Weights are uploaded and re-laid out here (synchronous).
  */

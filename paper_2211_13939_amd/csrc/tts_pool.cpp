@@ -237,6 +237,9 @@ struct tts_pool {
     std::map<int, hipGraphExec_t> graphs;   // key = ((steps * 1024 + bucket) * 2 + parity
     std::vector<hipGraph_t> graph_defs;
     int* h_fault = nullptr;       // pinned, mapped: non-zero once a kernel's bounded wait has run out
+    float* h_chunk = nullptr;     // pinned staging for one chunk on its way to the caller's (pageable) buffer: a copy from
+                                  // the device into pinned memory is a plain DMA, one into pageable memory is staged by the
+                                  // runtime at three times the cost
     int n_slots_padded = 0;       // slots the arena holds (max_pool rounded up to whole tiles)
     std::vector<int64_t> lost_ids; // requests the device ended early that tts_pool_sync has not reported yet
 };
@@ -402,6 +405,10 @@ extern "C" int tts_pool_create(const tts_config* cfg, const tts_weights* w, void
             return rc0;
         }
     }
+    if (hipHostMalloc(reinterpret_cast<void**>(&p->h_chunk), (size_t)cfg->chunk_frames * N_MEL * 4, hipHostMallocDefault) != hipSuccess) {
+        (void)hipGetLastError();
+        p->h_chunk = nullptr;     // drains then copy straight into the caller's buffer
+    }
     d.WmemT = (const float*)(base + l.WmemT);
     d.lsa_kfrag = base + l.lsa_kfrag;
     d.lsa_wfrag = base + l.lsa_wfrag;
@@ -465,6 +472,7 @@ extern "C" void tts_pool_destroy(tts_pool* p)
     if (p->ev0) (void)hipEventDestroy(p->ev0);
     if (p->ev1) (void)hipEventDestroy(p->ev1);
     if (p->h_fault) (void)hipHostFree(p->h_fault);
+    if (p->h_chunk) (void)hipHostFree(p->h_chunk);
     delete p;
 }
 
@@ -773,8 +781,9 @@ extern "C" int tts_pool_drain_chunk(tts_pool* p, int64_t id, float* dst, int* ou
     int first, count, fin;
     p->book->drain_plan(slot, &first, &count, &fin);
     if (count > 0) {
+        float* via = p->h_chunk ? p->h_chunk : dst;      // count <= chunk_frames: the staging buffer holds it
         const float* src = p->d.mel_ring + ((size_t)slot * p->cfg.max_steps + first) * N_MEL;
-        HIP_TRY(hipMemcpyAsync(dst, src, (size_t)count * N_MEL * 4, hipMemcpyDeviceToHost, p->stream));
+        HIP_TRY(hipMemcpyAsync(via, src, (size_t)count * N_MEL * 4, hipMemcpyDeviceToHost, p->stream));
         HIP_TRY(hipStreamSynchronize(p->stream));
         if (*p->h_fault) {
             // some request was frozen since the last look: if it is this one, the plan above counted frames that were
@@ -783,10 +792,11 @@ extern "C" int tts_pool_drain_chunk(tts_pool* p, int64_t id, float* dst, int* ou
             p->book->drain_plan(slot, &first, &count, &fin);
             if (count > 0) {
                 src = p->d.mel_ring + ((size_t)slot * p->cfg.max_steps + first) * N_MEL;
-                HIP_TRY(hipMemcpyAsync(dst, src, (size_t)count * N_MEL * 4, hipMemcpyDeviceToHost, p->stream));
+                HIP_TRY(hipMemcpyAsync(via, src, (size_t)count * N_MEL * 4, hipMemcpyDeviceToHost, p->stream));
                 HIP_TRY(hipStreamSynchronize(p->stream));
             }
         }
+        if (via != dst && count > 0) memcpy(dst, via, (size_t)count * N_MEL * 4);
         p->book->drain_commit(slot, count);
     }
     *out_frames = count;
