@@ -228,11 +228,13 @@ constexpr int TALL_RT = 8;                      // row tiles per workgroup
 constexpr int QP_TALL = HID / 4 / TALL_RT;      // partials per slot
 static_assert(QP_TALL == QUERY_PARTIALS, "the arena holds QUERY_PARTIALS partials per slot");
 
-template <typename XT>
+// TP: pool tiles per workgroup.  With more than eight pool tiles one tile per workgroup would be more workgroups than
+// compute units, each pulling the same 80 KB of weights; then a workgroup keeps its weights for two tiles.
+template <typename XT, int TP>
 __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm_att_tall(
     const uint4* __restrict__ Wfrag, const uint4* __restrict__ X, const float* __restrict__ bias, float* __restrict__ c_state,
     const int* __restrict__ live, const int* __restrict__ done, const floatx4* __restrict__ pre, const float* __restrict__ wq_epi,
-    XT* __restrict__ hout0, int nk0, int off0, XT* __restrict__ hout1, int nk1, int off1, float* __restrict__ qpart)
+    XT* __restrict__ hout0, int nk0, int off0, XT* __restrict__ hout1, int nk1, int off1, float* __restrict__ qpart, int n_tiles)
 {
     static_assert(TALL_RT == LSTM_WAVES, "one row tile per wave");
     constexpr int NK = K_ATT / Frag<XT>::KB;
@@ -240,54 +242,74 @@ __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm_att_tall(
     constexpr int BPW = NF / LSTM_WAVES;            // of the pool tile's, fetched per wave
     static_assert(NF % LSTM_WAVES == 0, "the activations' fragments split evenly over the waves");
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int rg = blockIdx.x % QP_TALL, tile = blockIdx.x / QP_TALL;
+    const int rg = blockIdx.x % QP_TALL, tile0 = (blockIdx.x / QP_TALL) * TP;
     const int rt = rg * TALL_RT + wave;
+    const int unit = rt * 4 + (lane >> 4);
 
+    // everything is requested at once, for all of the workgroup's tiles (a tile past the last repeats it and is dropped)
     uint4 a[NF];
 #pragma unroll
     for (int f = 0; f < NF; ++f) a[f] = Wfrag[xfrag(NK, rt, f, lane)];
-    uint4 bw[BPW];
+    uint4 bw[TP][BPW];
+    floatx4 pre4[TP];
+    int lv[TP], dn[TP];
+    float c_old[TP];
 #pragma unroll
-    for (int i = 0; i < BPW; ++i) bw[i] = X[xfrag(NK, tile, wave + i * LSTM_WAVES, lane)];
-    const int unit = rt * 4 + (lane >> 4), sl = tile * 16 + (lane & 15);
+    for (int j = 0; j < TP; ++j) {
+        const int tile = min(tile0 + j, n_tiles - 1), sl = tile * 16 + (lane & 15);
+#pragma unroll
+        for (int i = 0; i < BPW; ++i) bw[j][i] = X[xfrag(NK, tile, wave + i * LSTM_WAVES, lane)];
+        pre4[j] = pre[((size_t)tile * (HID / 4) + rt) * 64 + lane];
+        lv[j] = live[sl];
+        dn[j] = done[sl];
+        c_old[j] = c_state[(size_t)sl * HID + unit];
+    }
     const floatx4 bias4 = *reinterpret_cast<const floatx4*>(bias + unit * 4);
-    const floatx4 pre4 = pre[((size_t)tile * (HID / 4) + rt) * 64 + lane];
-    const int lv = live[sl], dn = done[sl];
-    const float c_old = c_state[(size_t)sl * HID + unit];
     // W_q[16 wave + lane % 16][32 rg + 4 s + lane / 16]: the A operands of the query partial's eight k steps
     float wq[TALL_RT];
 #pragma unroll
     for (int s = 0; s < TALL_RT; ++s) wq[s] = wq_epi[((size_t)(rg * TALL_RT + s) * 8 + wave) * 64 + lane];
     __builtin_amdgcn_sched_barrier(0);
 
-    __shared__ uint4 s_b[NF][64];
-    __shared__ float s_h[4 * TALL_RT][16];
+    __shared__ uint4 s_b[TP][NF][64];
+    __shared__ float s_h[TP][4 * TALL_RT][16];
 #pragma unroll
-    for (int i = 0; i < BPW; ++i) s_b[wave + i * LSTM_WAVES][lane] = bw[i];
+    for (int j = 0; j < TP; ++j)
+#pragma unroll
+        for (int i = 0; i < BPW; ++i) s_b[j][wave + i * LSTM_WAVES][lane] = bw[j][i];
     __syncthreads();
-    floatx4 g = {0.f, 0.f, 0.f, 0.f};
+    bool active[TP];
 #pragma unroll
-    for (int f = 0; f < NF; ++f) g = mfma_frag<XT>(a[f], s_b[f][lane], g);
-    g += bias4;
-    g += pre4;
-    const bool active = lv && !dn;
-    const float gi = sigmoidf_(g[0]), gf = sigmoidf_(g[1]);
-    const float gg = tanhf_(g[2]), go = sigmoidf_(g[3]);
-    const float c = gf * c_old + gi * gg;
-    const XT h = from_float<XT>(go * tanhf_(c));
-    if (active) {
-        c_state[(size_t)sl * HID + unit] = c;
-        hout0[xoff<XT>(nk0, sl, off0 + unit)] = h;
-        hout1[xoff<XT>(nk1, sl, off1 + unit)] = h;
+    for (int j = 0; j < TP; ++j) {
+        const int sl = (tile0 + j) * 16 + (lane & 15);
+        floatx4 g = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int f = 0; f < NF; ++f) g = mfma_frag<XT>(a[f], s_b[j][f][lane], g);
+        g += bias4;
+        g += pre4[j];
+        active[j] = lv[j] && !dn[j] && tile0 + j < n_tiles;
+        const float gi = sigmoidf_(g[0]), gf = sigmoidf_(g[1]);
+        const float gg = tanhf_(g[2]), go = sigmoidf_(g[3]);
+        const float c = gf * c_old[j] + gi * gg;
+        const XT h = from_float<XT>(go * tanhf_(c));
+        if (active[j]) {
+            c_state[(size_t)sl * HID + unit] = c;
+            hout0[xoff<XT>(nk0, sl, off0 + unit)] = h;
+            hout1[xoff<XT>(nk1, sl, off1 + unit)] = h;
+        }
+        s_h[j][4 * wave + (lane >> 4)][lane & 15] = active[j] ? to_float(h) : 0.f;
     }
-    s_h[4 * wave + (lane >> 4)][lane & 15] = active ? to_float(h) : 0.f;
     __syncthreads();
-    floatx4 part = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int s = 0; s < TALL_RT; ++s)
-        part = __builtin_amdgcn_mfma_f32_16x16x4f32(wq[s], s_h[4 * s + (lane >> 4)][lane & 15], part, 0, 0, 0);
-    if (active)
-        *reinterpret_cast<floatx4*>(qpart + ((size_t)sl * QP_TALL + rg) * ATT + 16 * wave + 4 * (lane >> 4)) = part;
+    for (int j = 0; j < TP; ++j) {
+        const int sl = (tile0 + j) * 16 + (lane & 15);
+        floatx4 part = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int s = 0; s < TALL_RT; ++s)
+            part = __builtin_amdgcn_mfma_f32_16x16x4f32(wq[s], s_h[j][4 * s + (lane >> 4)][lane & 15], part, 0, 0, 0);
+        if (active[j])
+            *reinterpret_cast<floatx4*>(qpart + ((size_t)sl * QP_TALL + rg) * ATT + 16 * wave + 4 * (lane >> 4)) = part;
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -1659,8 +1681,12 @@ static hipError_t step_typed(const DevPtrs& d, int n_req, int n_tiles, int lsa_s
     // With pre-sums: the tall kernel, which also hands the query over as partial products.  Without (fp32 pools of
     // more than four tiles): one row tile per workgroup, all of K.
     if constexpr (PRE) {
-        hipLaunchKernelGGL((k_lstm_att_tall<XT>), dim3(QP_TALL * n_tiles), lb, 0, s, d.Wa, xatt_cur, d.ba, d.c_att, d.live, d.done,
-                           reinterpret_cast<const floatx4*>(d.pre_att), d.Wq_epi, xdec_cur, K_DEC / KB, XD_HA, xatt_nxt, K_ATT / KB, XA_H, d.qpart);
+        if (n_tiles > 8)
+            hipLaunchKernelGGL((k_lstm_att_tall<XT, 2>), dim3(QP_TALL * ((n_tiles + 1) / 2)), lb, 0, s, d.Wa, xatt_cur, d.ba, d.c_att, d.live, d.done,
+                               reinterpret_cast<const floatx4*>(d.pre_att), d.Wq_epi, xdec_cur, K_DEC / KB, XD_HA, xatt_nxt, K_ATT / KB, XA_H, d.qpart, n_tiles);
+        else
+            hipLaunchKernelGGL((k_lstm_att_tall<XT, 1>), dim3(QP_TALL * n_tiles), lb, 0, s, d.Wa, xatt_cur, d.ba, d.c_att, d.live, d.done,
+                               reinterpret_cast<const floatx4*>(d.pre_att), d.Wq_epi, xdec_cur, K_DEC / KB, XD_HA, xatt_nxt, K_ATT / KB, XA_H, d.qpart, n_tiles);
     } else {
         hipLaunchKernelGGL((k_lstm<XT, K_ATT, false>), lg, lb, 0, s, d.Wa, xatt_cur, d.ba, d.c_att, d.live, d.done, (const floatx4*)nullptr,
                            xdec_cur, K_DEC / KB, XD_HA, xatt_nxt, K_ATT / KB, XA_H, n_tiles);
