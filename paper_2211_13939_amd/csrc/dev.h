@@ -44,6 +44,8 @@ struct DevPtrs {
     float* pre_att;       // [tiles][HID/4 row tiles][64 lanes][4]: the attention LSTM's gate sums over [A; H_att], MFMA accumulator layout,
                           // written by the projection kernel's launch for the next step (null: the LSTM kernels contract all of K)
     float* pre_dec;       // same for the decoder LSTM's sums over H_dec
+    float* pre_dec_b;     // same layout: the decoder LSTM's sums over H_att, formed inside the attention kernel's launch of the same step
+                          // (null: the decoder LSTM contracts H_att itself)
     unsigned long long* proj_part; // [tiles][5][96 * 16] (sequence number << 32 | float bits): partial sums of the projection's helper
                           // workgroups (pools with pre-sums), written and read within one kernel
     unsigned* proj_seq;   // [tiles][6]: steps each of a tile's projection workgroups has taken part in (zero at creation)

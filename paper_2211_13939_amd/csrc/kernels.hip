@@ -47,16 +47,20 @@ template <typename XT, int K> constexpr int lstm_main_frags()
     return (K == K_ATT ? PRENET : HID + ENC) / Frag<XT>::KB / LSTM_WAVES;
 }
 static_assert(XA_P == 0 && XD_HA == 0 && XD_A == HID, "the early parts lead the activation rows");
+// the leading fragments of a wave that hold H_att in the decoder LSTM's input
+template <typename XT> constexpr int lstm_hatt_frags() { return HID / Frag<XT>::KB / LSTM_WAVES; }
 
-template <typename XT, int K, bool PRE>
+template <typename XT, int K, bool PRE, bool HA = false>
 __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm(
     const uint4* __restrict__ Wfrag, const uint4* __restrict__ X, const float* __restrict__ bias, float* __restrict__ c_state,
-    const int* __restrict__ live, const int* __restrict__ done, const floatx4* __restrict__ pre, XT* __restrict__ hout0,
-    int nk0, int off0, XT* __restrict__ hout1, int nk1, int off1, int n_tiles)
+    const int* __restrict__ live, const int* __restrict__ done, const floatx4* __restrict__ pre, const floatx4* __restrict__ pre_b,
+    XT* __restrict__ hout0, int nk0, int off0, XT* __restrict__ hout1, int nk1, int off1, int n_tiles)
 {
     constexpr int NW = LSTM_WAVES;
     constexpr int NK = K / Frag<XT>::KB;      // fragments per row tile / per pool tile
-    constexpr int NF = PRE ? lstm_main_frags<XT, K>() : NK / NW;   // fragments per wave (the early ones only with PRE)
+    constexpr int F0 = HA ? lstm_hatt_frags<XT>() : 0;             // with HA the sums over H_att arrive in pre_b
+    constexpr int NF = (PRE ? lstm_main_frags<XT, K>() : NK / NW) - F0;   // fragments per wave (the early ones only with PRE)
+    static_assert(!HA || (PRE && K == K_DEC), "H_att leads the decoder LSTM's input");
     static_assert(NK % NW == 0, "K must split evenly over the waves");
     constexpr int TIF = sizeof(XT) == 2 ? 4 : 1;   // pool tiles whose activations are in flight together
 
@@ -69,7 +73,7 @@ __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm(
     // only HBM stream).  A tile without a running request is computed and dropped.
     uint4 a[NF];
 #pragma unroll
-    for (int f = 0; f < NF; ++f) a[f] = Wfrag[xfrag(NK, rt, wave + f * NW, lane)];
+    for (int f = 0; f < NF; ++f) a[f] = Wfrag[xfrag(NK, rt, wave + (F0 + f) * NW, lane)];
     // the first four waves also own the cell update of (pool tile in flight = wave, lane)
     const int unit = rt * 4 + (lane >> 4);
     floatx4 bias4 = {0.f, 0.f, 0.f, 0.f};
@@ -88,7 +92,9 @@ __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm(
         const int lv = live[sl], dn = done[sl];
         const float c_old = c_state[(size_t)sl * HID + unit];
         floatx4 pre4 = {0.f, 0.f, 0.f, 0.f};
+        floatx4 pre4b = {0.f, 0.f, 0.f, 0.f};
         if constexpr (PRE) pre4 = pre[((size_t)my_tile * (HID / 4) + rt) * 64 + lane];
+        if constexpr (HA) pre4b = pre_b[((size_t)my_tile * (HID / 4) + rt) * 64 + lane];
         __builtin_amdgcn_sched_barrier(0);   // issued here, looked at after the products
 #pragma unroll
         for (int t0 = 0; t0 < 4; t0 += TIF) {
@@ -98,7 +104,7 @@ __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm(
                 if (tg + t0 + t < n_tiles) {
                     const int tile = tg + t0 + t;
 #pragma unroll
-                    for (int f = 0; f < NF; ++f) b[t][f] = X[xfrag(NK, tile, wave + f * NW, lane)];
+                    for (int f = 0; f < NF; ++f) b[t][f] = X[xfrag(NK, tile, wave + (F0 + f) * NW, lane)];
                 }
             }
 #pragma unroll
@@ -118,6 +124,7 @@ __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm(
 #pragma unroll
             for (int w = 0; w < NW; ++w) g += red[w][wave][lane];
             if constexpr (PRE) g += pre4;
+            if constexpr (HA) g += pre4b;
             const float gi = sigmoidf_(g[0]), gf = sigmoidf_(g[1]);
             const float gg = tanhf_(g[2]), go = sigmoidf_(g[3]);
             const float c = gf * c_old + gi * gg;
@@ -137,15 +144,17 @@ __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm(
 // against 1 + tiles for the one-row-tile kernel.  R = 2 is the minimum at 4 tiles, R = 4 at 16.  The
 // workgroups that share rows sit on the same XCD (their blockIdx differ by a multiple of 64), so the
 // repeated reads of the weights hit that XCD's L2.  The sums are taken in the same order as in k_lstm.
-template <typename XT, int K, int R, bool PRE = false>
+template <typename XT, int K, int R, bool PRE = false, bool HA = false>
 __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm_rc(
     const uint4* __restrict__ Wfrag, const uint4* __restrict__ X, const float* __restrict__ bias, float* __restrict__ c_state,
-    const int* __restrict__ live, const int* __restrict__ done, const floatx4* __restrict__ pre, XT* __restrict__ hout0,
-    int nk0, int off0, XT* __restrict__ hout1, int nk1, int off1, int n_tiles)
+    const int* __restrict__ live, const int* __restrict__ done, const floatx4* __restrict__ pre, const floatx4* __restrict__ pre_b,
+    XT* __restrict__ hout0, int nk0, int off0, XT* __restrict__ hout1, int nk1, int off1, int n_tiles)
 {
     constexpr int NW = LSTM_WAVES;
     constexpr int NK = K / Frag<XT>::KB;
-    constexpr int NF = PRE ? lstm_main_frags<XT, K>() : NK / NW;
+    constexpr int F0 = HA ? lstm_hatt_frags<XT>() : 0;
+    constexpr int NF = (PRE ? lstm_main_frags<XT, K>() : NK / NW) - F0;
+    static_assert(!HA || (PRE && K == K_DEC), "H_att leads the decoder LSTM's input");
     constexpr int TP = 4 / R;                      // pool tiles per round: R x TP = 4 cell-update waves
     constexpr int NRG = HID / 4 / R;               // row groups
     static_assert(R == 2 || R == 4, "two or four row tiles per workgroup");
@@ -158,7 +167,7 @@ __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm_rc(
 #pragma unroll
     for (int r = 0; r < R; ++r)
 #pragma unroll
-        for (int f = 0; f < NF; ++f) a[r][f] = Wfrag[xfrag(NK, R * rg + r, wave + f * NW, lane)];
+        for (int f = 0; f < NF; ++f) a[r][f] = Wfrag[xfrag(NK, R * rg + r, wave + (F0 + f) * NW, lane)];
     const int per = (n_tiles + R - 1) / R;
     const int c0 = min(cg * per, n_tiles), c1 = min(c0 + per, n_tiles);
 
@@ -173,7 +182,9 @@ __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm_rc(
         const int lv = live[sl], dn = done[sl];
         const float c_old = c_state[(size_t)sl * HID + unit];
         floatx4 pre4 = {0.f, 0.f, 0.f, 0.f};
+        floatx4 pre4b = {0.f, 0.f, 0.f, 0.f};
         if constexpr (PRE) pre4 = pre[((size_t)min(tp + et, c1 - 1) * (HID / 4) + R * rg + er) * 64 + lane];
+        if constexpr (HA) pre4b = pre_b[((size_t)min(tp + et, c1 - 1) * (HID / 4) + R * rg + er) * 64 + lane];
         __builtin_amdgcn_sched_barrier(0);
         uint4 b[TP][NF];
 #pragma unroll
@@ -181,7 +192,7 @@ __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm_rc(
             if (tp + t < c1) {
                 const int tile = tp + t;
 #pragma unroll
-                for (int f = 0; f < NF; ++f) b[t][f] = X[xfrag(NK, tile, wave + f * NW, lane)];
+                for (int f = 0; f < NF; ++f) b[t][f] = X[xfrag(NK, tile, wave + (F0 + f) * NW, lane)];
             }
         }
 #pragma unroll
@@ -203,6 +214,7 @@ __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm_rc(
 #pragma unroll
             for (int w = 0; w < NW; ++w) g += red[w][wave][lane];
             if constexpr (PRE) g += pre4;
+            if constexpr (HA) g += pre4b;
             const float gi = sigmoidf_(g[0]), gf = sigmoidf_(g[1]);
             const float gg = tanhf_(g[2]), go = sigmoidf_(g[3]);
             const float c = gf * c_old + gi * gg;
@@ -622,12 +634,78 @@ template <> struct LsaTile<h16_t> {
     }
 };
 
+// The decoder LSTM's gate sums over H_att (K = HID of its 2560), formed inside the attention kernel's launch.  H_att(t) is
+// complete when that launch begins, and the attention itself is a chain of waits (exchange of energies, dependent round
+// trips) that leaves the load path of its compute units idle: workgroups j = 0 .. 255 behind the attention's own share a
+// CU with one of them each and contract two row tiles (2 (j % 128), + 1) with half of the pool tiles (j / 128), K split
+// over the waves as in k_lstm_rc; wave w chains its fragments w + 8 f in increasing f, the eight waves' sums are added
+// in wave order.  The sums land in pre_dec_b in accumulator layout and are read by the decoder LSTM of the same step.
+typedef floatx4 (*HattRed)[2][64];               // [wave][row tile][lane]: 16 KB
+template <typename XT>
+__device__ __forceinline__ void dec_hatt_presums(const uint4* __restrict__ Wd, const uint4* __restrict__ X, floatx4* __restrict__ out, int j, int n_tiles,
+                                                 HattRed red)
+{
+    constexpr int NW = LSTM_WAVES, R = 2, TP = 2;
+    constexpr int NK = K_DEC / Frag<XT>::KB;
+    constexpr int NF = lstm_hatt_frags<XT>();
+    constexpr int NRG = HID / 4 / R;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int rg = j % NRG, cg = j / NRG;
+    uint4 a[R][NF];
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int f = 0; f < NF; ++f) a[r][f] = Wd[xfrag(NK, R * rg + r, wave + f * NW, lane)];
+    const int per = (n_tiles + R - 1) / R;
+    const int c0 = min(cg * per, n_tiles), c1 = min(c0 + per, n_tiles);
+    for (int tp = c0; tp < c1; tp += TP) {
+        uint4 b[TP][NF];
+#pragma unroll
+        for (int t = 0; t < TP; ++t) {
+            const int tile = min(tp + t, c1 - 1);
+#pragma unroll
+            for (int f = 0; f < NF; ++f) b[t][f] = X[xfrag(NK, tile, wave + f * NW, lane)];
+        }
+#pragma unroll
+        for (int t = 0; t < TP; ++t) {
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int f = 0; f < NF; ++f) acc = mfma_frag<XT>(a[r][f], b[t][f], acc);
+                red[wave][r][lane] = acc;
+            }
+            __syncthreads();
+            if (wave < R && tp + t < c1) {
+                floatx4 g = red[0][wave][lane];
+#pragma unroll
+                for (int w = 1; w < NW; ++w) g += red[w][wave][lane];
+                out[((size_t)(tp + t) * (HID / 4) + R * rg + wave) * 64 + lane] = g;
+            }
+            __syncthreads();
+        }
+    }
+}
+constexpr int DEC_HATT_WGS = HID / 4 / 2;        // per half of the pool tiles
+
 // The first eight arguments repeat pointers that are also in `d_all`: the leading 16 dwords of a kernel's arguments
 // arrive in scalar registers with the wave, so the prologue's loads can go out before the argument block has been read.
-template <typename XT, typename MT, int S, bool QP>
-__global__ __launch_bounds__(LSA_THREADS) void k_lsa(int* L_first, int* live_first, int* done_first, unsigned* seq_first, float* qpart_first,
+// CO: the launch carries the workgroups of dec_hatt_presums behind the attention's own; two workgroups then share a CU
+// (four waves per SIMD: at most 128 registers).
+template <typename XT, typename MT, int S, bool QP, bool CO = false>
+__global__ __launch_bounds__(LSA_THREADS, CO ? 4 : 1) void k_lsa(int* L_first, int* live_first, int* done_first, unsigned* seq_first, float* qpart_first,
                                                     float* w_last_first, float* w_acc_first, void* PM_first, DevPtrs d, int cur, int n_slots)
 {
+    __shared__ __attribute__((aligned(16))) float s_ctx[LSA_WAVES][ENC];
+    if constexpr (CO) {
+        static_assert(sizeof(floatx4) * LSTM_WAVES * 2 * 64 <= sizeof(float) * LSA_WAVES * ENC && LSA_WAVES == LSTM_WAVES, "the pre-sums' reduction fits s_ctx");
+        const int n_lsa = (n_slots + 7) / 8 * 8 * S;
+        if ((int)blockIdx.x >= n_lsa) {
+            dec_hatt_presums<XT>(d.Wd, reinterpret_cast<const uint4*>(d.xdec[cur]), reinterpret_cast<floatx4*>(d.pre_dec_b),
+                                 blockIdx.x - n_lsa, (n_slots + 15) / 16, reinterpret_cast<HattRed>(&s_ctx[0][0]));
+            return;
+        }
+    }
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int jl = lane & 15, g = lane >> 4;
     // Workgroups are laid over the pool's SLOTS, not over a list of active requests: a list would
@@ -680,7 +758,6 @@ __global__ __launch_bounds__(LSA_THREADS) void k_lsa(int* L_first, int* live_fir
     __shared__ float s_e[MAX_ENC_LEN];
     __shared__ float s_red[2 * LSA_WAVES];
     __shared__ int s_fail;                        // a wait for another workgroup's words ran out
-    __shared__ __attribute__((aligned(16))) float s_ctx[LSA_WAVES][ENC];
 
     constexpr int KB = Frag<XT>::KB;
     constexpr int NPM = Vec16<MT>::N;
@@ -879,7 +956,7 @@ __global__ __launch_bounds__(LSA_THREADS) void k_lsa(int* L_first, int* live_fir
     constexpr int FS = ENC / S;                     // columns of this workgroup
     constexpr int LPR = 64 / S;                     // lanes per encoder row
     constexpr int NA = 4 / S;                       // position classes per lane
-    constexpr int NR = sizeof(MT) == 2 ? 16 : 8;    // rows in flight per lane
+    constexpr int NR = sizeof(MT) == 2 ? (CO ? 12 : 16) : 8;    // rows in flight per lane (CO: 128 registers)
     constexpr int NP = NR / NA;                     // 32-position passes in flight
     constexpr int VPR = 8 * (int)sizeof(MT) / 16;   // 16-byte loads per row per lane
     const int xw = wave * 4 + (lane / LPR) * NA;    // this lane's first class
@@ -1689,12 +1766,17 @@ static hipError_t step_typed(const DevPtrs& d, int n_req, int n_tiles, int lsa_s
                                reinterpret_cast<const floatx4*>(d.pre_att), d.Wq_epi, xdec_cur, K_DEC / KB, XD_HA, xatt_nxt, K_ATT / KB, XA_H, d.qpart, n_tiles);
     } else {
         hipLaunchKernelGGL((k_lstm<XT, K_ATT, false>), lg, lb, 0, s, d.Wa, xatt_cur, d.ba, d.c_att, d.live, d.done, (const floatx4*)nullptr,
-                           xdec_cur, K_DEC / KB, XD_HA, xatt_nxt, K_ATT / KB, XA_H, n_tiles);
+                           (const floatx4*)nullptr, xdec_cur, K_DEC / KB, XD_HA, xatt_nxt, K_ATT / KB, XA_H, n_tiles);
     }
     mark(1);
     const int n_pad = (n_req + 7) / 8 * 8;      // slots are dealt to the XCDs in eights
 #define LSA_ARGS d.L, d.live, d.done, d.step_seq, d.qpart, d.w_last[cur], d.w_acc[cur], d.PM, d, cur, n_req
-    if (lsa_split == 4) hipLaunchKernelGGL((k_lsa<XT, MT, 4, PRE>), dim3(n_pad * 4), dim3(LSA_THREADS), 0, s, LSA_ARGS);
+    // two-byte pools with both pre-sums: the decoder LSTM's sums over H_att ride in this launch
+    constexpr bool CO = PRE_DEC && sizeof(XT) == 2 && sizeof(MT) == 2;   // (the attention kernel for fp32 memory needs more than 128 registers)
+    if (CO != (d.pre_dec_b != nullptr)) return hipErrorInvalidValue;
+    const int n_co = CO ? DEC_HATT_WGS * (n_tiles > 1 ? 2 : 1) : 0;
+    if (lsa_split == 4) hipLaunchKernelGGL((k_lsa<XT, MT, 4, PRE, CO>), dim3(n_pad * 4 + n_co), dim3(LSA_THREADS), 0, s, LSA_ARGS);
+    else if (CO) return hipErrorInvalidValue;     // such pools span at most 64 slots: four workgroups per slot
     else if (lsa_split == 2) hipLaunchKernelGGL((k_lsa<XT, MT, 2, PRE>), dim3(n_pad * 2), dim3(LSA_THREADS), 0, s, LSA_ARGS);
     else hipLaunchKernelGGL((k_lsa<XT, MT, 1, PRE>), dim3(n_pad), dim3(LSA_THREADS), 0, s, LSA_ARGS);
 #undef LSA_ARGS
@@ -1702,16 +1784,17 @@ static hipError_t step_typed(const DevPtrs& d, int n_req, int n_tiles, int lsa_s
     // H_dec(t): consumed by this step's projection and the next step's decoder LSTM (same buffer)
     const uint4* xdec_in = reinterpret_cast<const uint4*>(d.xdec[cur]);
     const floatx4* pre_dec = reinterpret_cast<const floatx4*>(d.pre_dec);
+    const floatx4* pre_dec_b = reinterpret_cast<const floatx4*>(d.pre_dec_b);
     if (rows == 4) {
         if constexpr (HAS_WIDE && !PRE_DEC)
-            hipLaunchKernelGGL((k_lstm_rc<XT, K_DEC, 4>), lg, lb, 0, s, d.Wd, xdec_in, d.bd, d.c_dec, d.live, d.done, pre_dec,
+            hipLaunchKernelGGL((k_lstm_rc<XT, K_DEC, 4>), lg, lb, 0, s, d.Wd, xdec_in, d.bd, d.c_dec, d.live, d.done, pre_dec, pre_dec_b,
                                xdec_nxt, K_DEC / KB, XD_HD, xdec_nxt, K_DEC / KB, XD_HD, n_tiles);
     } else if (rows == 2) {
         if constexpr (HAS_WIDE)
-            hipLaunchKernelGGL((k_lstm_rc<XT, K_DEC, 2, PRE_DEC>), lg, lb, 0, s, d.Wd, xdec_in, d.bd, d.c_dec, d.live, d.done, pre_dec,
+            hipLaunchKernelGGL((k_lstm_rc<XT, K_DEC, 2, PRE_DEC, CO>), lg, lb, 0, s, d.Wd, xdec_in, d.bd, d.c_dec, d.live, d.done, pre_dec, pre_dec_b,
                                xdec_nxt, K_DEC / KB, XD_HD, xdec_nxt, K_DEC / KB, XD_HD, n_tiles);
     } else
-        hipLaunchKernelGGL((k_lstm<XT, K_DEC, PRE_DEC>), lg, lb, 0, s, d.Wd, xdec_in, d.bd, d.c_dec, d.live, d.done, pre_dec,
+        hipLaunchKernelGGL((k_lstm<XT, K_DEC, PRE_DEC, CO>), lg, lb, 0, s, d.Wd, xdec_in, d.bd, d.c_dec, d.live, d.done, pre_dec, pre_dec_b,
                            xdec_nxt, K_DEC / KB, XD_HD, xdec_nxt, K_DEC / KB, XD_HD, n_tiles);
     mark(3);
     // with pre-sums the projection's launch fills the chip: XCD 0 runs the projection, the rest form the pre-sums

@@ -69,7 +69,7 @@ static int check_config(const tts_config* c)
 namespace {
 
 struct Layout {
-    size_t Wa, Wd, ba, bd, Wq, Wq_epi, qpart, pre_att, pre_dec, proj_part, WmemT, lsa_kfrag, lsa_wfrag, v, Wmel, bmel, Wp1, Wp2;
+    size_t Wa, Wd, ba, bd, Wq, Wq_epi, qpart, pre_att, pre_dec, pre_dec_b, proj_part, WmemT, lsa_kfrag, lsa_wfrag, v, Wmel, bmel, Wp1, Wp2;
     size_t xatt[2], xdec[2], c_att, c_dec, m_last, w_last[2], w_acc[2], Fmem, PM, mel_ring, stop_ring;
     size_t L, t, n_steps, done, failed, live, proj_seq, step_seq, lsa_x, stage;
     size_t total, proj_part_bytes;
@@ -89,6 +89,9 @@ bool pre_gates_for(const tts_config& c)
 // the decoder LSTM's pre-sum too: only where the pre-sum workgroups still finish in the projection's shadow (beyond four
 // tiles it saved the decoder LSTM 1.8 us and kept the projection's launch 5 us longer)
 bool pre_dec_for(const tts_config& c) { return pre_gates_for(c) && (c.max_pool + 15) / 16 <= PRESUM_SMALL_TILES; }
+// and its sums over H_att formed beside the attention kernel, in the same launch: that kernel is a chain of waits that
+// leaves a CU's load path idle, and two of its workgroups fit a CU only with two-byte operands and memory
+bool pre_dec_hatt_for(const tts_config& c) { return pre_dec_for(c) && c.weight_dtype == TTS_DTYPE_BF16 && c.memory_dtype == TTS_DTYPE_BF16; }
 // workgroups per pool tile in the projection kernel: with pre-sums they must fit XCD 0 (32 CUs)
 int proj_group_for(const tts_config& c)
 {
@@ -125,6 +128,7 @@ Layout make_layout(const tts_config& c)
     l.qpart = a.take((pre_gates_for(c) ? S : 0) * (size_t)QUERY_PARTIALS * ATT * 4);
     l.pre_att = a.take((pre_gates_for(c) ? S / 16 : 0) * (size_t)(HID / 4) * 64 * 16);
     l.pre_dec = a.take((pre_dec_for(c) ? S / 16 : 0) * (size_t)(HID / 4) * 64 * 16);
+    l.pre_dec_b = a.take((pre_dec_hatt_for(c) ? S / 16 : 0) * (size_t)(HID / 4) * 64 * 16);
     l.proj_part_bytes = (S / 16) * (size_t)(PROJ_GROUP - 1) * 96 * 16 * 8;
     l.proj_part = a.take(l.proj_part_bytes);
     l.c_att = a.take(S * HID * 4);
@@ -388,6 +392,7 @@ extern "C" int tts_pool_create(const tts_config* cfg, const tts_weights* w, void
     d.qpart = pre_gates_for(*cfg) ? reinterpret_cast<float*>(base + l.qpart) : nullptr;
     d.pre_att = pre_gates_for(*cfg) ? reinterpret_cast<float*>(base + l.pre_att) : nullptr;
     d.pre_dec = pre_dec_for(*cfg) ? reinterpret_cast<float*>(base + l.pre_dec) : nullptr;
+    d.pre_dec_b = pre_dec_hatt_for(*cfg) ? reinterpret_cast<float*>(base + l.pre_dec_b) : nullptr;
     d.proj_part = reinterpret_cast<unsigned long long*>(base + l.proj_part);
     d.proj_seq = reinterpret_cast<unsigned*>(base + l.proj_seq);
     d.step_seq = reinterpret_cast<unsigned*>(base + l.step_seq);
