@@ -956,7 +956,9 @@ __global__ __launch_bounds__(LSA_THREADS, CO ? 4 : 1) void k_lsa(int* L_first, i
     constexpr int FS = ENC / S;                     // columns of this workgroup
     constexpr int LPR = 64 / S;                     // lanes per encoder row
     constexpr int NA = 4 / S;                       // position classes per lane
-    constexpr int NR = sizeof(MT) == 2 ? (CO ? 12 : 16) : 8;    // rows in flight per lane (CO: 128 registers)
+    // rows in flight per lane.  CO: the kernel has 128 registers.  S = 1 (pools of more than 128 slots): the kernel streams
+    // from HBM on every CU at once, and eight rows per lane in flight moved more bytes per second than sixteen or four.
+    constexpr int NR = sizeof(MT) == 2 ? (CO ? 12 : (S == 1 ? 8 : 16)) : 8;
     constexpr int NP = NR / NA;                     // 32-position passes in flight
     constexpr int VPR = 8 * (int)sizeof(MT) / 16;   // 16-byte loads per row per lane
     const int xw = wave * 4 + (lane / LPR) * NA;    // this lane's first class
