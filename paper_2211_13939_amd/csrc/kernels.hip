@@ -39,7 +39,8 @@ constexpr int LSTM_WAVES = 8;
 // with their columns of the gate matrices and store the sums in accumulator layout:
 //   pre[pool tile][row tile][lane] (floatx4) = sum over the late fragments of W[row tile] x[pool tile].
 // The LSTM kernels of the next step then contract only the early fragments -- Pre(M_last) (K = 256 of 1792) and
-// [H_att; A] (K = 1536 of 2560) -- and add pre in the cell update.  Wave w owns fragments w, w + 8, ...: the early part
+// [H_att; A] (K = 1536 of 2560) -- and add pre in the cell update.  With HA the decoder LSTM's leading fragments (H_att,
+// K = 1024) are summed too, beside the attention kernel in its launch (dec_hatt_presums), and arrive in pre_b.  Wave w owns fragments w, w + 8, ...: the early part
 // is the first lstm_main_frags() of them, for both matrices.
 template <typename XT, int K> constexpr int lstm_main_frags()
 {
