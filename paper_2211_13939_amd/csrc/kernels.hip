@@ -228,6 +228,102 @@ __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm_rc(
     }
 }
 
+// The same tile (R row tiles x up to C pool tiles per workgroup, all of K) as one stream over K: wave w walks its
+// fragments w, w + 8, ... once, each step fetching the R weight fragments and the C activation fragments of that k
+// and chaining them into R x C accumulators, with WIN steps of loads in flight.  Nothing waits for a whole matrix
+// slice or a whole pool tile any more: k_lstm_rc requests its weights in one burst and then pays one round trip to L2
+// per round of pool tiles; here the loads leave at the rate the products consume them.  Every (row tile, pool tile) sum
+// is formed as in k_lstm (wave w chains w + 8 f in increasing f; bias, then the eight waves' sums in wave order), so the
+// gates are the same bits.  The R x C sums are reduced through LDS eight at a time, one cell update per wave.
+template <typename XT, int K, int R, int C>
+__global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm_stream(
+    const uint4* __restrict__ Wfrag, const uint4* __restrict__ X, const float* __restrict__ bias, float* __restrict__ c_state,
+    const int* __restrict__ live, const int* __restrict__ done,
+    XT* __restrict__ hout0, int nk0, int off0, XT* __restrict__ hout1, int nk1, int off1, int n_tiles)
+{
+    constexpr int NW = LSTM_WAVES;
+    constexpr int NK = K / Frag<XT>::KB;
+    constexpr int NF = NK / NW;                    // k steps per wave
+    constexpr int NRG = HID / 4 / R;               // row groups; R groups of pool tiles
+    constexpr int WIN = 3;                         // k steps in flight
+    constexpr int PH = R * C / NW;                 // reduction phases of eight sums
+    static_assert(NK % NW == 0 && (R * C) % NW == 0 && WIN <= NF, "shape");
+
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int rg = blockIdx.x % NRG, cg = blockIdx.x / NRG;
+    const int per = (n_tiles + R - 1) / R;         // <= C (checked by the launcher)
+    const int c0 = min(cg * per, n_tiles), c1 = min(c0 + per, n_tiles);
+    if (c0 >= c1) return;                          // the whole workgroup: no pool tile in this group
+
+    // a pool tile past the group's last repeats it (the line is in L2 already) and is dropped
+    int tb[C];
+#pragma unroll
+    for (int t = 0; t < C; ++t) tb[t] = min(c0 + t, c1 - 1);
+
+    uint4 a[WIN][R], b[WIN][C];
+    auto issue = [&](int f) __attribute__((always_inline)) {
+#pragma unroll
+        for (int r = 0; r < R; ++r) a[f % WIN][r] = Wfrag[xfrag(NK, R * rg + r, wave + f * NW, lane)];
+#pragma unroll
+        for (int t = 0; t < C; ++t) b[f % WIN][t] = X[xfrag(NK, tb[t], wave + f * NW, lane)];
+    };
+#pragma unroll
+    for (int f = 0; f < WIN - 1; ++f) issue(f);
+
+    // the cell updates this wave owns: sum 8 p + wave of phase p = (row tile er[p], pool tile et[p])
+    int sl[PH], unit[PH], lv[PH], dn[PH];
+    float c_old[PH];
+    floatx4 bias4[PH];
+    bool mine[PH];
+#pragma unroll
+    for (int p = 0; p < PH; ++p) {
+        const int idx = NW * p + wave, er = idx / C, et = idx % C;
+        mine[p] = c0 + et < c1;
+        sl[p] = tb[et] * 16 + (lane & 15);
+        unit[p] = (R * rg + er) * 4 + (lane >> 4);
+        lv[p] = live[sl[p]];
+        dn[p] = done[sl[p]];
+        c_old[p] = c_state[(size_t)sl[p] * HID + unit[p]];
+        bias4[p] = *reinterpret_cast<const floatx4*>(bias + unit[p] * 4);
+    }
+
+    floatx4 acc[R][C];
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int t = 0; t < C; ++t) acc[r][t] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int f = 0; f < NF; ++f) {
+        if (f + WIN - 1 < NF) issue(f + WIN - 1);
+        __builtin_amdgcn_sched_barrier(0);         // the step ahead is requested before this one's products wait for theirs
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int t = 0; t < C; ++t) acc[r][t] = mfma_frag<XT>(a[f % WIN][r], b[f % WIN][t], acc[r][t]);
+    }
+
+    __shared__ floatx4 red[NW][NW][64];            // [wave][sum of the phase][lane]: 64 KB
+#pragma unroll
+    for (int p = 0; p < PH; ++p) {
+        if (p) __syncthreads();
+#pragma unroll
+        for (int j = 0; j < NW; ++j) red[wave][j][lane] = acc[(NW * p + j) / C][(NW * p + j) % C];
+        __syncthreads();
+        if (mine[p] && lv[p] && !dn[p]) {
+            floatx4 g = bias4[p];
+#pragma unroll
+            for (int w = 0; w < NW; ++w) g += red[w][wave][lane];
+            const float gi = sigmoidf_(g[0]), gf = sigmoidf_(g[1]);
+            const float gg = tanhf_(g[2]), go = sigmoidf_(g[3]);
+            const float c = gf * c_old[p] + gi * gg;
+            c_state[(size_t)sl[p] * HID + unit[p]] = c;
+            const XT h = from_float<XT>(go * tanhf_(c));
+            hout0[xoff<XT>(nk0, sl[p], off0 + unit[p])] = h;
+            hout1[xoff<XT>(nk1, sl[p], off1 + unit[p])] = h;
+        }
+    }
+}
+
 // ---------------------------------------------------------------------------
 // Attention LSTM of pools with gate pre-sums.  What is left of its gates is K = 256 (the prenet output), so the shape
 // of a workgroup's tile no longer matters for the bytes it pulls, and the tile is chosen for the attention query
@@ -1790,10 +1886,14 @@ static hipError_t step_typed(const DevPtrs& d, int n_req, int n_tiles, int lsa_s
     const floatx4* pre_dec_b = reinterpret_cast<const floatx4*>(d.pre_dec_b);
     if (rows == 4) {
         if constexpr (HAS_WIDE && !PRE_DEC)
-            hipLaunchKernelGGL((k_lstm_rc<XT, K_DEC, 4>), lg, lb, 0, s, d.Wd, xdec_in, d.bd, d.c_dec, d.live, d.done, pre_dec, pre_dec_b,
+            hipLaunchKernelGGL((k_lstm_stream<XT, K_DEC, 4, 4>), lg, lb, 0, s, d.Wd, xdec_in, d.bd, d.c_dec, d.live, d.done,
                                xdec_nxt, K_DEC / KB, XD_HD, xdec_nxt, K_DEC / KB, XD_HD, n_tiles);
     } else if (rows == 2) {
-        if constexpr (HAS_WIDE)
+        if constexpr (HAS_WIDE && !PRE_DEC) {
+            if (n_tiles > 8) return hipErrorInvalidValue;         // two groups of at most four pool tiles
+            hipLaunchKernelGGL((k_lstm_stream<XT, K_DEC, 2, 4>), lg, lb, 0, s, d.Wd, xdec_in, d.bd, d.c_dec, d.live, d.done,
+                               xdec_nxt, K_DEC / KB, XD_HD, xdec_nxt, K_DEC / KB, XD_HD, n_tiles);
+        } else if constexpr (HAS_WIDE)
             hipLaunchKernelGGL((k_lstm_rc<XT, K_DEC, 2, PRE_DEC, CO>), lg, lb, 0, s, d.Wd, xdec_in, d.bd, d.c_dec, d.live, d.done, pre_dec, pre_dec_b,
                                xdec_nxt, K_DEC / KB, XD_HD, xdec_nxt, K_DEC / KB, XD_HD, n_tiles);
     } else
