@@ -59,8 +59,9 @@ def step_flops(P, sum_L):
 def algorithmic_bytes(P, sum_L, s_w, s_m, pre_gates=None):
     """step_bytes split over the four kernels by where the bytes move (the sum is step_bytes exactly).  The split
     depends on `pre_gates`: 2 (pools of at most 64 slots): the gate matrices' columns for [A; H_att] (attention LSTM)
-    and H_dec (decoder LSTM) move in the projection kernel's launch, W_q in the attention LSTM's, and - two-byte pools -
-    the decoder LSTM's columns for H_att in the attention kernel's; 1 (larger
+    and H_dec (decoder LSTM) move in the projection kernel's launch, W_q in the attention LSTM's; in two-byte pools of that
+    size the decoder LSTM has no kernel of its own (its columns for H_att and H_dec move in the attention kernel's launch,
+    the rest and its state in the last kernel's, which holds it; "k_lstm_dec" is then 0); 1 (larger
     bf16 pools): the attention LSTM's only; 0 (larger fp32 pools): none.  Carried state is charged once, to the kernel
     that produces it (activations a later kernel reads again, gate pre-sums and query partials are traffic of the
     implementation, not of the algorithm)."""
@@ -68,20 +69,24 @@ def algorithmic_bytes(P, sum_L, s_w, s_m, pre_gates=None):
         pre_gates = 2 if P <= PRESUM_BOTH_MAX_POOL else (1 if s_w == 2 else 0)
     k_att_late = 512 + 1024 if pre_gates else 0
     k_dec_late = 1024 if pre_gates == 2 else 0
-    # two-byte pools with both pre-sums: the decoder LSTM's columns for H_att move in the attention kernel's launch
-    k_dec_hatt = 1024 if (pre_gates == 2 and s_w == 2 and s_m == 2) else 0
+    # two-byte pools with both pre-sums: the decoder LSTM is part of the last kernel's launch, and its columns for H_att
+    # and H_dec move in the attention kernel's
+    fused = pre_gates == 2 and s_w == 2 and s_m == 2
+    k_dec_hatt = 1024 if fused else 0
     w_q = 128 * 1024 * s_w
     lsa_w = (32 * 2 * 31 + 128 * 32 + 128) * s_w
     proj_w = (81 * 1536 + 80 * 256 + 256 * 256) * s_w + 81 * 4
+    dec_own = 4096 * (2560 - k_dec_late - k_dec_hatt) * s_w + 4096 * 4 + P * 4 * 1024 * 4
     return {
         # h_att and c_att read and written
         "k_lstm_att": 4096 * (1792 - k_att_late) * s_w + 4096 * 4 + (w_q if pre_gates else 0) + P * 4 * 1024 * 4,
         # PM + F_enc streamed, W_last / W_acc read and written, a read and written
-        "k_lsa": lsa_w + (0 if pre_gates else w_q) + sum_L * (640 * s_m + 16) + P * 2 * 512 * 4 + 4096 * k_dec_hatt * s_w,
+        "k_lsa": lsa_w + (0 if pre_gates else w_q) + sum_L * (640 * s_m + 16) + P * 2 * 512 * 4
+                 + 4096 * (k_dec_hatt + (k_dec_late if fused else 0)) * s_w,
         # h_dec and c_dec read and written
-        "k_lstm_dec": 4096 * (2560 - k_dec_late - k_dec_hatt) * s_w + 4096 * 4 + P * 4 * 1024 * 4,
+        "k_lstm_dec": 0 if fused else dec_own,
         # m_last read and written, the frame written to the ring
-        "k_proj": proj_w + 4096 * (k_att_late + k_dec_late) * s_w + P * (2 * 80 * 4 + 320),
+        "k_proj": proj_w + 4096 * (k_att_late + (0 if fused else k_dec_late)) * s_w + P * (2 * 80 * 4 + 320) + (dec_own if fused else 0),
     }
 
 
@@ -608,6 +613,7 @@ def main():
         # a launch is the kernel plus the gap in front of it: the event intervals (event cost subtracted) leave the
         # gaps out, so each kernel is charged an equal share of what the graph-launched step takes beyond their sum
         # (this is also how rocprofv3's kernel trace accounts: a kernel's start is the previous kernel's end)
+        kernel_us = {k: v for k, v in kernel_us.items() if v > 0.0}     # (no decoder-LSTM kernel in the fused form of the step)
         gap = max(0.0, (step_us - sum(kernel_us.values())) / len(kernel_us))
         launch_us = {k: v + gap for k, v in kernel_us.items()}
         dom = max(launch_us, key=launch_us.get)

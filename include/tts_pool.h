@@ -230,7 +230,9 @@ int tts_pool_elapsed_ms(tts_pool *pool, float *out_ms);
  * HIP event between consecutive kernels, and return the average device time of
  * each kernel of the step in microseconds in out_us (room for `cap` values;
  * *out_n_kernels receives how many there are: attention LSTM, attention,
- * decoder LSTM, projection + prenet).  The device cost of an event itself is
+ * decoder LSTM, projection + prenet; two-byte pools of at most 64 slots have
+ * no decoder-LSTM kernel - it is part of the last kernel's launch - and report
+ * 0 for it).  The device cost of an event itself is
  * measured with adjacent events and subtracted; if cap > *out_n_kernels it is
  * stored after the kernel times.  The intervals still contain the launch gap,
  * so they are upper bounds of the kernels' own durations.  The steps are real:

@@ -46,11 +46,14 @@ struct DevPtrs {
     float* pre_dec;       // same for the decoder LSTM's sums over H_dec
     float* pre_dec_b;     // same layout: the decoder LSTM's sums over H_att, formed inside the attention kernel's launch of the same step
                           // (null: the decoder LSTM contracts H_att itself)
-    unsigned long long* proj_part; // [tiles][5][96 * 16] (sequence number << 32 | float bits): partial sums of the projection's helper
+    unsigned long long* proj_part; // [tiles][5 (6 in the fused form)][96 * 16] (sequence number << 32 | float bits): partial sums of the projection's helper
                           // workgroups (pools with pre-sums), written and read within one kernel
     unsigned* proj_seq;   // [tiles][6]: steps each of a tile's projection workgroups has taken part in (zero at creation)
     unsigned long long* lsa_x; // [slots][max_enc_len] (step number << 32 | float bits): the energies the workgroups of a request hand each other
     unsigned* step_seq;   // [1] steps taken (zero at creation; advanced by the projection kernel)
+    unsigned long long* hdec_x; // [tiles][HID / 32 fragments][64 lanes][4] (sequence number << 32 | two halves): H_dec of the step as the
+                          // projection's B operand, handed from the decoder LSTM's part of the fused last kernel to the projection's
+                          // workgroups of the same launch (null: the decoder LSTM is a kernel of its own)
     int* fault;           // pinned host memory: set by a workgroup whose bounded wait for another's words ran out (with `failed` of the slots it froze)
     const void* lsa_kfrag; // location filters as per-lane MFMA A operands (layout depends on WT)
     const void* lsa_wfrag; // W_loc as per-lane MFMA A operands (layout depends on WT)

@@ -28,13 +28,15 @@ constexpr int PRESUM_SMALL_TILES = 4;
 // such a pool's attention LSTM writes this many partial products of the attention query per slot (d.qpart)
 constexpr int QUERY_PARTIALS = 32;
 // and its projection runs as this many workgroups per tile: d.proj_seq holds one sequence number for each, d.proj_part
-// the 96 x 16 partial sums of all but the first
+// the 96 x 16 partial sums of all but the first (of all of them, and one more sequence number for the tile's leader, in
+// the fused form of the last kernel: d.hdec_x)
 constexpr int PROJ_GROUP = 6;       // the largest group
 
 // One decoder step (paper Eq. 2) for every request whose slot is flagged in d.live.
 // `cur` selects which half of the double-buffered activations is read.
 // If `ev` is given it holds N_STEP_KERNELS + 1 events: ev[0] is recorded before the
 // first kernel and ev[i + 1] after kernel i (per-kernel device times).
+// (Pools with d.hdec_x launch three kernels - the decoder LSTM is part of the last one - and record ev[3] right after ev[2].)
 constexpr int N_STEP_KERNELS = 4;
 hipError_t launch_step(const DevPtrs& d, const StepLaunch& cfg, int cur, hipStream_t s, hipEvent_t* ev = nullptr);
 

@@ -7,6 +7,9 @@
 //   k_lstm<dec>   gates GEMM on MFMA + fused cell        (Eq. 2 line 3)
 //   k_proj        mel + stop projection, ring write, prenet of the new frame
 //                                                         (Eq. 2 line 5, Pre() of line 1)
+// Two-byte pools of at most 64 slots run three: what is left of the decoder LSTM
+// there (K = 512 of 2560, the rest arrives as gate pre-sums) is formed by the
+// workgroups of k_proj's launch before they turn to their own parts.
 //
 // Activations (the vectors multiplied by weight matrices) live in HBM in MFMA
 // B-operand order, tiled by pool slot: 16 slots form a tile, and a tile's
@@ -16,6 +19,7 @@
 // operand) alike, and building / splitting the dynamic batch is pure indexing.
 #include "kernels.h"
 #include "mfma.h"
+#include <type_traits>
 
 
 namespace tts {
@@ -738,13 +742,18 @@ template <> struct LsaTile<h16_t> {
 // over the waves as in k_lstm_rc; wave w chains its fragments w + 8 f in increasing f, the eight waves' sums are added
 // in wave order.  The sums land in pre_dec_b in accumulator layout and are read by the decoder LSTM of the same step.
 typedef floatx4 (*HattRed)[2][64];               // [wave][row tile][lane]: 16 KB
-template <typename XT>
-__device__ __forceinline__ void dec_hatt_presums(const uint4* __restrict__ Wd, const uint4* __restrict__ X, floatx4* __restrict__ out, int j, int n_tiles,
-                                                 HattRed red)
+// HD: the sums over H_dec of the step before (the trailing K = HID, into pre_dec) are formed here as well, after those
+// over H_att; that part's weights are requested before the first part's products.  (Pools whose last kernel holds the
+// decoder LSTM: its launch can no longer form them for the next step, H_dec being complete only when it ends.)
+template <typename XT, bool HD>
+__device__ __forceinline__ void dec_hatt_presums(const uint4* __restrict__ Wd, const uint4* __restrict__ X, floatx4* __restrict__ out,
+                                                 floatx4* __restrict__ out_hd, int j, int n_tiles, HattRed red)
 {
     constexpr int NW = LSTM_WAVES, R = 2, TP = 2;
     constexpr int NK = K_DEC / Frag<XT>::KB;
     constexpr int NF = lstm_hatt_frags<XT>();
+    constexpr int F_HD = lstm_main_frags<XT, K_DEC>();      // a wave's fragments that hold H_dec follow its early ones
+    static_assert(NK / NW - F_HD == NF, "H_dec is as long as H_att");
     constexpr int NRG = HID / 4 / R;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int rg = j % NRG, cg = j / NRG;
@@ -755,33 +764,48 @@ __device__ __forceinline__ void dec_hatt_presums(const uint4* __restrict__ Wd, c
         for (int f = 0; f < NF; ++f) a[r][f] = Wd[xfrag(NK, R * rg + r, wave + f * NW, lane)];
     const int per = (n_tiles + R - 1) / R;
     const int c0 = min(cg * per, n_tiles), c1 = min(c0 + per, n_tiles);
-    for (int tp = c0; tp < c1; tp += TP) {
+    static_assert(PRESUM_SMALL_TILES <= R * TP, "one round of pool tiles per workgroup");
+    if (c0 >= c1) return;
+    auto part = [&](int F0, floatx4* __restrict__ dst, bool prefetch) __attribute__((always_inline)) {
         uint4 b[TP][NF];
 #pragma unroll
         for (int t = 0; t < TP; ++t) {
-            const int tile = min(tp + t, c1 - 1);
+            const int tile = min(c0 + t, c1 - 1);
 #pragma unroll
-            for (int f = 0; f < NF; ++f) b[t][f] = X[xfrag(NK, tile, wave + f * NW, lane)];
+            for (int f = 0; f < NF; ++f) b[t][f] = X[xfrag(NK, tile, wave + (F0 + f) * NW, lane)];
+        }
+        floatx4 acc[TP][R];
+#pragma unroll
+        for (int t = 0; t < TP; ++t)
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                acc[t][r] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int f = 0; f < NF; ++f) acc[t][r] = mfma_frag<XT>(a[r][f], b[t][f], acc[t][r]);
+            }
+        if (prefetch) {
+            // the next part's weights: on their way during this part's reduction
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+#pragma unroll
+                for (int f = 0; f < NF; ++f) a[r][f] = Wd[xfrag(NK, R * rg + r, wave + (F_HD + f) * NW, lane)];
         }
 #pragma unroll
         for (int t = 0; t < TP; ++t) {
 #pragma unroll
-            for (int r = 0; r < R; ++r) {
-                floatx4 acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int f = 0; f < NF; ++f) acc = mfma_frag<XT>(a[r][f], b[t][f], acc);
-                red[wave][r][lane] = acc;
-            }
+            for (int r = 0; r < R; ++r) red[wave][r][lane] = acc[t][r];
             __syncthreads();
-            if (wave < R && tp + t < c1) {
+            if (wave < R && c0 + t < c1) {
                 floatx4 g = red[0][wave][lane];
 #pragma unroll
                 for (int w = 1; w < NW; ++w) g += red[w][wave][lane];
-                out[((size_t)(tp + t) * (HID / 4) + R * rg + wave) * 64 + lane] = g;
+                dst[((size_t)(c0 + t) * (HID / 4) + R * rg + wave) * 64 + lane] = g;
             }
             __syncthreads();
         }
-    }
+    };
+    part(0, out, HD);
+    if constexpr (HD) part(F_HD, out_hd, false);
 }
 constexpr int DEC_HATT_WGS = HID / 4 / 2;        // per half of the pool tiles
 
@@ -798,8 +822,9 @@ __global__ __launch_bounds__(LSA_THREADS, CO ? 4 : 1) void k_lsa(int* L_first, i
         static_assert(sizeof(floatx4) * LSTM_WAVES * 2 * 64 <= sizeof(float) * LSA_WAVES * ENC && LSA_WAVES == LSTM_WAVES, "the pre-sums' reduction fits s_ctx");
         const int n_lsa = (n_slots + 7) / 8 * 8 * S;
         if ((int)blockIdx.x >= n_lsa) {
-            dec_hatt_presums<XT>(d.Wd, reinterpret_cast<const uint4*>(d.xdec[cur]), reinterpret_cast<floatx4*>(d.pre_dec_b),
-                                 blockIdx.x - n_lsa, (n_slots + 15) / 16, reinterpret_cast<HattRed>(&s_ctx[0][0]));
+            dec_hatt_presums<XT, true>(d.Wd, reinterpret_cast<const uint4*>(d.xdec[cur]), reinterpret_cast<floatx4*>(d.pre_dec_b),
+                                       reinterpret_cast<floatx4*>(d.pre_dec), blockIdx.x - n_lsa, (n_slots + 15) / 16,
+                                       reinterpret_cast<HattRed>(&s_ctx[0][0]));
             return;
         }
     }
@@ -1230,6 +1255,8 @@ constexpr int PROJ_THREADS = 512;
 constexpr int PROJ_WAVES = PROJ_THREADS / 64;
 constexpr int PROJ_ROWS = 96;
 constexpr int PROJ_MEL_LD = PROJ_ROWS + 4, PROJ_HID_LD = PRENET + 4;
+constexpr int PROJ_GROUP_K = PROJ_GROUP;   // workgroups that split K of the projection in pools of at most five tiles
+constexpr int PROJ_WIN = 6;      // weight loads per wave in flight (the fused form)
 
 template <typename XT> struct PrenetK1 { static constexpr int value = 80; };
 template <> struct PrenetK1<h16_t> { static constexpr int value = 96; };
@@ -1244,6 +1271,110 @@ template <> __device__ __forceinline__ uint4 frag_from_f32<h16_t>(const float* p
 {
     return make_uint4(pack2<h16_t>(p[0], p[1]), pack2<h16_t>(p[2], p[3]), pack2<h16_t>(p[4], p[5]), pack2<h16_t>(p[6], p[7]));
 }
+
+// The decoder LSTM inside the projection kernel's launch (two-byte pools of at most four tiles, where what is left of its
+// gates is K = ENC: the sums over H_att and H_dec arrive as pre-sums).  Every one of the launch's 256 workgroups first
+// forms one of the 256 pieces k_lstm_rc<dec, 2> would (two row tiles x half of the pool tiles, the same sums in the same
+// order), stores H_dec where the next step reads it, and hands it to the projection's workgroups of the same launch as
+// 8-byte words: two halves beside the step's number, laid out as the projection's B operand (hdec_x).  The number is the
+// tile's leader's count of steps (the last of the tile's PROJ_GROUP_K + 1 counters), which the leader advances only after
+// all of the tile's words have been consumed.
+// A slot without a running request hands over zeros (its projection is dropped).  issue() requests, finish() consumes:
+// what a workgroup requests for its own part in between arrives behind the decoder LSTM's operands, not in front of them.
+typedef floatx4 (*DecRed)[4][64];                // [wave][sum][lane]: 32 KB
+template <typename XT>
+struct DecUnit {
+    static constexpr int NW = LSTM_WAVES, R = 2, TP = 2;
+    static constexpr int NK = K_DEC / Frag<XT>::KB;
+    static constexpr int F0 = lstm_hatt_frags<XT>();
+    static constexpr int NF = lstm_main_frags<XT, K_DEC>() - F0;
+    static constexpr int NRG = HID / 4 / R;
+    static_assert(sizeof(XT) == 2 && Frag<XT>::KB == 32, "two-byte operands: a row group's eight units are one 16-byte piece");
+    uint4 a[R][NF], b[TP][NF];
+    floatx4 pre4, pre4b, bias4;
+    float c_old;
+    int lv, dn, sl, unit, c0, c1, rg;
+    unsigned seq;
+    bool mine;
+
+    __device__ __forceinline__ void issue(const DevPtrs& d, const ProjHot& hot, int blk, int n_tiles)
+    {
+        const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+        const uint4* __restrict__ Wd = hot.Wd;
+        const uint4* __restrict__ X = reinterpret_cast<const uint4*>(hot.xdec_cur);
+        rg = blk % NRG;
+        const int cg = blk / NRG;
+        const int per = (n_tiles + R - 1) / R;
+        c0 = min(cg * per, n_tiles);
+        c1 = min(c0 + per, n_tiles);
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int f = 0; f < NF; ++f) a[r][f] = Wd[xfrag(NK, R * rg + r, wave + (F0 + f) * NW, lane)];
+#pragma unroll
+        for (int t = 0; t < TP; ++t) {
+            const int tile = max(min(c0 + t, c1 - 1), 0);
+#pragma unroll
+            for (int f = 0; f < NF; ++f) b[t][f] = X[xfrag(NK, tile, wave + (F0 + f) * NW, lane)];
+        }
+        // waves 0 .. 3 own a cell update: (pool tile c0 + wave / R, row tile wave % R); the others load the same words and drop them
+        const int er = wave % R, et = (wave / R) % TP;
+        const int tile_e = max(min(c0 + et, c1 - 1), 0);
+        mine = wave < 4 && c0 + et < c1;
+        sl = tile_e * 16 + (lane & 15);
+        unit = (R * rg + er) * 4 + (lane >> 4);
+        lv = hot.live[sl];
+        dn = d.done[sl];
+        c_old = d.c_dec[(size_t)sl * HID + unit];
+        pre4 = reinterpret_cast<const floatx4*>(d.pre_dec)[((size_t)tile_e * (HID / 4) + R * rg + er) * 64 + lane];
+        pre4b = reinterpret_cast<const floatx4*>(d.pre_dec_b)[((size_t)tile_e * (HID / 4) + R * rg + er) * 64 + lane];
+        bias4 = *reinterpret_cast<const floatx4*>(d.bd + unit * 4);
+        seq = hot.proj_seq[tile_e * (PROJ_GROUP_K + 1) + PROJ_GROUP_K] + 1u;
+    }
+
+    __device__ __forceinline__ void finish(const DevPtrs& d, const ProjHot& hot, DecRed red)
+    {
+        const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+        if (c0 >= c1) return;                     // the whole workgroup: no pool tile in its half
+#pragma unroll
+        for (int t = 0; t < TP; ++t)
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int f = 0; f < NF; ++f) acc = mfma_frag<XT>(a[r][f], b[t][f], acc);
+                red[wave][R * t + r][lane] = acc;
+            }
+        __syncthreads();
+        if (mine) {
+            floatx4 g = bias4;
+#pragma unroll
+            for (int w = 0; w < NW; ++w) g += red[w][wave][lane];
+            g += pre4;
+            g += pre4b;
+            const float gi = sigmoidf_(g[0]), gf = sigmoidf_(g[1]);
+            const float gg = tanhf_(g[2]), go = sigmoidf_(g[3]);
+            const float c = gf * c_old + gi * gg;
+            const bool on = lv && !dn;
+            XT h = from_float<XT>(go * tanhf_(c));
+            if (on) {
+                d.c_dec[(size_t)sl * HID + unit] = c;
+                reinterpret_cast<XT*>(const_cast<void*>(hot.xdec_nxt))[xoff<XT>(NK, sl, XD_HD + unit)] = h;
+            } else {
+                h.bits = 0;
+            }
+            // lanes l and l + 16 hold neighbouring units of one slot: the lower of the two stores both
+            const unsigned mineb = h.bits, theirs = (unsigned)__shfl_down((int)mineb, 16, 64);
+            const int q = lane >> 4;
+            if ((q & 1) == 0) {
+                const int er = wave % R;
+                const size_t w = ((((size_t)(sl >> 4) * (HID / 32) + rg / 4) * 64 + (rg % 4) * 16 + (lane & 15)) * 4) + er * 2 + (q >> 1);
+                __hip_atomic_store(&d.hdec_x[w], ((unsigned long long)seq << 32) | (theirs << 16) | mineb, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+        __syncthreads();
+    }
+};
 
 struct ProjShared {
     float* big;                          // PROJ_WAVES * PROJ_ROWS * 16 floats: partial sums, later hid
@@ -1504,8 +1635,249 @@ __device__ __forceinline__ void proj_tile(const DevPtrs& d, const ProjHot& hot, 
     }
 }
 
+// The fused form of a tile's workgroups (two-byte pools of at most four tiles; the launch holds the decoder LSTM too,
+// DecUnit).  Every workgroup first forms its piece of the decoder LSTM - other tiles' workgroups wait for it as well - and
+// only then requests its weights.  G workers contract one G-th of K of the projection each, as in the plain form, with
+// H_dec taken as words from hdec_x once every piece of a wave's K range is in, and hand their partial sums over as 8-byte
+// words; worker 0's start from the bias.  A further workgroup leads: it pulls nothing but the prenet's weights (with a
+// short window of loads per wave in flight: a wave that asks for all of them at once gets less than half the rate out of
+// the CU's load path), polls the G partial sums, adds them in worker order - the plain form's order, the frame is the
+// same bits - and finishes alone: prenet, then the books.  (All G + 1 workgroups adding the sums themselves and sharing
+// the prenet's second layer was tried: six times the polls, and a word took 3 us to be seen instead of 1.)
+constexpr int FUSED_GROUP = PROJ_GROUP_K + 1;    // workgroups per tile: the workers and the leader
+template <typename XT>
+__device__ __forceinline__ void proj_tile_fused(const DevPtrs& d, const ProjHot& hot, int cur, int tile, int kp, const ProjShared& sh, int n_tiles)
+{
+    constexpr int G = PROJ_GROUP_K;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int jl = lane & 15, g = lane >> 4;
+    constexpr int KB = Frag<XT>::KB;
+    constexpr int EPL = Frag<XT>::EPL;
+    constexpr int NKD = K_DEC / KB;
+    constexpr int NK = K_PROJ / KB;
+    static_assert(NK == G * PROJ_WAVES, "one fragment of K per wave");
+    constexpr int NM = PROJ_ROWS / 16;
+    constexpr int NK3 = PrenetK1<XT>::value / KB;
+    constexpr int NK4 = PRENET / KB;
+    constexpr int RED_IT = 16 * PROJ_ROWS / PROJ_THREADS;
+    static_assert(16 * PROJ_ROWS % PROJ_THREADS == 0, "the reduction phase splits evenly");
+    const bool leader = kp == G;
+
+    DecUnit<XT> dec;
+    dec.issue(d, hot, blockIdx.x, n_tiles);
+    if (tid == 0) *sh.ok = 1;
+    float (*s_part)[PROJ_ROWS][16] = reinterpret_cast<float (*)[PROJ_ROWS][16]>(sh.big);
+    float (*s_hid)[PROJ_HID_LD] = reinterpret_cast<float (*)[PROJ_HID_LD]>(sh.big);
+    static_assert(16 * PROJ_HID_LD <= PROJ_WAVES * PROJ_ROWS * 16, "hid must fit the partial-sum buffer it aliases");
+    // this workgroup's count of the steps it has taken part in: the number its words carry, and the one it expects
+    const unsigned my_seq = hot.proj_seq[tile * FUSED_GROUP + kp];
+
+    if (!leader) {
+        // ---- a worker: fragment ks of K = [h_dec; a] in wave `wave`
+        const uint4* xcur = reinterpret_cast<const uint4*>(hot.xdec_cur);
+        const int ks = kp * PROJ_WAVES + wave;
+        const bool from_h = ks < HID / KB;
+        uint4 b = xcur[xfrag(NKD, tile, XD_A / KB + max(ks - HID / KB, 0), lane)];
+        float bias_r[RED_IT];
+#pragma unroll
+        for (int it = 0; it < RED_IT; ++it) bias_r[it] = d.bmel[min((tid + it * PROJ_THREADS) >> 4, N_PROJ - 1)];
+        __builtin_amdgcn_sched_barrier(0);
+        dec.finish(d, hot, reinterpret_cast<DecRed>(sh.big));
+        __syncthreads();                                   // (a piece without pool tiles has no barrier of its own)
+        // (all six row tiles' fragments, the zero rows of the last included: a branch around a load would make the
+        // compiler wait for every load in flight where it rejoins)
+        const uint4* W = reinterpret_cast<const uint4*>(hot.Wmel) + lane;
+        uint4 a[NM];
+#pragma unroll
+        for (int m = 0; m < NM; ++m) a[m] = W[((size_t)m * NK + ks) * 64];
+        __builtin_amdgcn_sched_barrier(0);
+        // the wave's fragment of h_dec: every lane polls its four words (a bounded number of times)
+        bool all_in = !from_h;                             // a wave whose fragment lies in `a` waits for nobody
+        unsigned long long w[4];
+        const unsigned long long* hx = d.hdec_x + (((size_t)tile * (HID / KB) + min(ks, HID / KB - 1)) * 64 + lane) * 4;
+        for (int spin = 0; spin < d.wait_polls && !all_in; ++spin) {
+            all_in = true;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                w[i] = __hip_atomic_load(&hx[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                all_in = all_in && (unsigned)(w[i] >> 32) == my_seq + 1u;
+            }
+        }
+        if (!all_in) *sh.ok = 0;                           // looked at after the next barrier
+        if (from_h && all_in) b = make_uint4((unsigned)w[0], (unsigned)w[1], (unsigned)w[2], (unsigned)w[3]);
+        // the projection, one fragment of K per wave ...
+#pragma unroll
+        for (int m = 0; m < NM; ++m) {
+            const floatx4 acc = mfma_frag<XT>(a[m], b, floatx4{0.f, 0.f, 0.f, 0.f});
+#pragma unroll
+            for (int i = 0; i < 4; ++i) s_part[wave][16 * m + 4 * g + i][jl] = acc[i];
+        }
+        __syncthreads();
+        // ... reduced over the waves and handed over, each word with the step count beside it in one 8-byte store (a
+        // worker whose wait for h_dec ran out hands nothing over: the leader's wait then runs out as well)
+        if (*sh.ok) {
+            unsigned long long* mine = d.proj_part + (size_t)(tile * G + kp) * (16 * PROJ_ROWS);
+#pragma unroll
+            for (int it = 0; it < RED_IT; ++it) {
+                const int idx = tid + it * PROJ_THREADS;
+                const int o = idx >> 4, r = idx & 15;
+                float v = 0.f;
+                if (o < N_PROJ) {
+                    if (kp == 0) v = bias_r[it];
+#pragma unroll
+                    for (int wv = 0; wv < PROJ_WAVES; ++wv) v += s_part[wv][o][r];
+                }
+                __hip_atomic_store(&mine[idx], ((unsigned long long)(my_seq + 1u) << 32) | __float_as_uint(v), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+        if (tid == 0) hot.proj_seq[tile * FUSED_GROUP + kp] = my_seq + 1u;
+        return;
+    }
+
+    // ---- the leader
+    const int my_sl = tile * 16 + (tid & 15);
+    const int my_live = hot.live[my_sl], my_done = d.done[my_sl];
+    const int my_t = d.t[my_sl], my_cap = d.n_steps[my_sl];
+    const unsigned step_no = d.step_seq[0];
+    __builtin_amdgcn_sched_barrier(0);
+    dec.finish(d, hot, reinterpret_cast<DecRed>(sh.big));
+    if (tid < 16) {
+        const bool on = my_live && !my_done;
+        sh.slot[tid] = on ? my_sl : -1;
+        sh.t[tid] = on ? my_t : 0;
+        sh.cap[tid] = on ? my_cap : 0;
+    }
+    // weights of the two prenet layers for this wave's row tiles (w and w + 8)
+    const uint4* W1 = reinterpret_cast<const uint4*>(d.Wp1) + lane;
+    const uint4* W2 = reinterpret_cast<const uint4*>(d.Wp2) + lane;
+    uint4 a3[2][NK3], a4[2][NK4];
+#pragma unroll
+    for (int m = 0; m < 2; ++m) {
+        const int mt = wave + m * PROJ_WAVES;
+#pragma unroll
+        for (int f = 0; f < NK3; ++f) {
+            a3[m][f] = W1[((size_t)mt * NK3 + f) * 64];
+            vm_in_flight_at_most<PROJ_WIN>();
+        }
+#pragma unroll
+        for (int f = 0; f < NK4; ++f) {
+            a4[m][f] = W2[((size_t)mt * NK4 + f) * 64];
+            vm_in_flight_at_most<PROJ_WIN>();
+        }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    // the workers' sums as they arrive (every thread polls its own words), added in worker order
+    float v[RED_IT];
+    {
+        unsigned long long w[G][RED_IT];
+        bool all_in = false;
+        for (int spin = 0; spin < d.wait_polls && !all_in; ++spin) {
+            all_in = true;
+#pragma unroll
+            for (int h = 0; h < G; ++h) {
+                const unsigned long long* theirs = d.proj_part + (size_t)(tile * G + h) * (16 * PROJ_ROWS);
+#pragma unroll
+                for (int it = 0; it < RED_IT; ++it) {
+                    w[h][it] = __hip_atomic_load(&theirs[tid + it * PROJ_THREADS], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    all_in = all_in && (unsigned)(w[h][it] >> 32) == my_seq + 1u;
+                }
+            }
+        }
+        if (!all_in) *sh.ok = 0;
+#pragma unroll
+        for (int it = 0; it < RED_IT; ++it) {
+            v[it] = __uint_as_float((unsigned)w[0][it]);
+#pragma unroll
+            for (int h = 1; h < G; ++h) v[it] += __uint_as_float((unsigned)w[h][it]);
+        }
+        if (tid == 0) hot.proj_seq[tile * FUSED_GROUP + kp] = my_seq + 1u;
+    }
+#pragma unroll
+    for (int it = 0; it < RED_IT; ++it) {
+        const int idx = tid + it * PROJ_THREADS;
+        sh.mel[idx & 15][idx >> 4] = v[it];
+    }
+    __syncthreads();
+    // A wait that ran out: the workers' sums never came, so this tile's frames cannot be formed.  Its requests are
+    // frozen where they stand (done: every later kernel leaves them alone; failed: the host tells their owners) and
+    // nothing of this step is stored for them; the step counter below still advances for everyone else.
+    const bool gave_up = *sh.ok == 0;
+    __syncthreads();
+    if (gave_up && tid < 16 && sh.slot[tid] >= 0) {
+        d.done[sh.slot[tid]] = 1;
+        d.failed[sh.slot[tid]] = 1;
+        *d.fault = 1;
+        sh.slot[tid] = -1;
+    }
+    if (gave_up) __syncthreads();
+
+    // hid^T = relu(W_p1 mel^T); wave w owns row tiles w and w + 8
+    {
+        uint4 bm[NK3];
+#pragma unroll
+        for (int f = 0; f < NK3; ++f) bm[f] = frag_from_f32<XT>(&sh.mel[jl][f * KB + g * EPL]);
+        floatx4 acc[2];
+#pragma unroll
+        for (int m = 0; m < 2; ++m) {
+            acc[m] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int f = 0; f < NK3; ++f) acc[m] = mfma_frag<XT>(a3[m][f], bm[f], acc[m]);
+        }
+#pragma unroll
+        for (int m = 0; m < 2; ++m)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) s_hid[jl][16 * (wave + m * PROJ_WAVES) + 4 * g + i] = fmaxf(acc[m][i], 0.f);
+    }
+    __syncthreads();
+    // p^T = relu(W_p2 hid^T)
+    {
+        uint4 bh[NK4];
+#pragma unroll
+        for (int f = 0; f < NK4; ++f) bh[f] = frag_from_f32<XT>(&s_hid[jl][f * KB + g * EPL]);
+        const int sl = sh.slot[jl];
+        XT* xa = reinterpret_cast<XT*>(d.xatt[cur ^ 1]);
+#pragma unroll
+        for (int m = 0; m < 2; ++m) {
+            const int mt = wave + m * PROJ_WAVES;
+            floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int f = 0; f < NK4; ++f) acc = mfma_frag<XT>(a4[m][f], bh[f], acc);
+            if (sl >= 0) {
+                // four consecutive k inside one 16-byte piece: one store
+                XT* dst = xa + xoff<XT>(K_ATT / KB, sl, XA_P + 16 * mt + 4 * g);
+                const float p0 = fmaxf(acc[0], 0.f), p1 = fmaxf(acc[1], 0.f), p2 = fmaxf(acc[2], 0.f), p3 = fmaxf(acc[3], 0.f);
+                *reinterpret_cast<uint2*>(dst) = make_uint2(pack2<XT>(p0, p1), pack2<XT>(p2, p3));
+            }
+        }
+    }
+    // the books: the frame out, one step further
+    for (int idx = tid; idx < 16 * N_PROJ; idx += PROJ_THREADS) {
+        const int r = idx / N_PROJ, o = idx - r * N_PROJ;
+        const int sl = sh.slot[r];
+        if (sl >= 0) {
+            const float m = sh.mel[r][o];
+            if (o < N_MEL) {
+                d.mel_ring[((size_t)sl * d.max_steps + sh.t[r]) * N_MEL + o] = m;
+                d.m_last[(size_t)sl * N_MEL + o] = m;
+            } else {
+                d.stop_ring[(size_t)sl * d.max_steps + sh.t[r]] = m;
+            }
+        }
+    }
+    // the number the attention kernel's workgroups mark their exchanged words with
+    if (tile == 0 && tid == 0) d.step_seq[0] = step_no + 1u;
+    if (tid < 16 && sh.slot[tid] >= 0) {
+        const int sl = sh.slot[tid];
+        const int tn = sh.t[tid] + 1;
+        d.t[sl] = tn;
+        bool fin = tn >= sh.cap[tid];
+        if (d.stop_threshold >= 0.f && sigmoidf_(sh.mel[tid][N_MEL]) > d.stop_threshold) fin = true;
+        if (fin) d.done[sl] = 1;
+    }
+}
+
 // G: workgroups per pool tile (fixed per pool: it sets the order in which the mel projection is summed)
-template <typename XT, bool PRE, int G>
+template <typename XT, bool PRE, int G, bool FUSE = false>
 __global__ __launch_bounds__(PROJ_THREADS) void k_proj(const uint4* Wa_first, const uint4* Wd_first, const void* xatt_nxt_first, const void* xdec_nxt_first,
                                                       const void* xdec_cur_first, const void* Wmel_first, const int* live_first, unsigned* proj_seq_first,
                                                       DevPtrs d, int cur, int n_tiles)
@@ -1528,6 +1900,18 @@ __global__ __launch_bounds__(PROJ_THREADS) void k_proj(const uint4* Wa_first, co
         // fewest bytes through a CU), two or three row tiles each (one or two without the split).  Above: groups of at
         // most four tiles, two to five row tiles each, the tiles walked one at a time.
         const int x = blockIdx.x & 7, i = blockIdx.x >> 3;
+        static_assert(!FUSE || PRE, "the fused form is a form of the 256-workgroup launch");
+        if constexpr (FUSE) {
+            // Every workgroup forms its piece of the decoder LSTM first (the projection's own weave it into their start).
+            // The pre-sum workgroups request nothing of their own before the piece is done: with their first chunks
+            // on the way beside the pieces' operands, the pieces - which the projection waits for - finished 1.8 us later.
+            if (x != 0 || i >= n_tiles * FUSED_GROUP) {
+                DecUnit<XT> dec;
+                dec.issue(d, hot, blockIdx.x, n_tiles);
+                __builtin_amdgcn_sched_barrier(0);
+                dec.finish(d, hot, reinterpret_cast<DecRed>(s_big));
+            }
+        }
         if (x != 0) {
             static_assert(sizeof(floatx4) * LSTM_WAVES * PG_R * PG_T * 64 <= sizeof(s_big), "the reduction buffer aliases the partial sums");
             static_assert(sizeof(floatx4) * LSTM_WAVES * PG_WALK_R * 64 <= sizeof(s_big), "the reduction buffer aliases the partial sums");
@@ -1542,7 +1926,9 @@ __global__ __launch_bounds__(PROJ_THREADS) void k_proj(const uint4* Wa_first, co
                     else { k -= 16; t0 = per; nt = n_tiles - per; }
                 }
                 const int lo = rx0 + (rx1 - rx0) * k / Mc, hi = rx0 + (rx1 - rx0) * (k + 1) / Mc;
-                gate_presums<XT>(d, hot, lo, hi - lo, t0, nt, reinterpret_cast<PresumRed>(s_big));
+                // (fused: the decoder LSTM's sums over H_dec are formed beside the attention kernel of the next step)
+                if constexpr (FUSE) gate_presums_sel<XT, false>(d, hot, lo, hi - lo, t0, nt, reinterpret_cast<PresumRed>(s_big));
+                else gate_presums<XT>(d, hot, lo, hi - lo, t0, nt, reinterpret_cast<PresumRed>(s_big));
             } else {
                 const int CG = (n_tiles + 3) / 4, Mc = 32 / CG;          // 2, 3 or 4 groups of 16, 10 or 8 workgroups
                 const int cg = i / Mc, k = i - cg * Mc;
@@ -1552,6 +1938,11 @@ __global__ __launch_bounds__(PROJ_THREADS) void k_proj(const uint4* Wa_first, co
                 const int lo = rx0 + (rx1 - rx0) * k / Mc, hi = rx0 + (rx1 - rx0) * (k + 1) / Mc;
                 if (nt > 0) gate_presums_walk<XT>(d, hot, lo, hi - lo, t0, nt, reinterpret_cast<WalkRed>(s_big));
             }
+            return;
+        }
+        if constexpr (FUSE) {
+            static_assert(!FUSE || G == PROJ_GROUP_K, "the workers split K as the plain form's workgroups do");
+            if (i < n_tiles * FUSED_GROUP) proj_tile_fused<XT>(d, hot, cur, i / FUSED_GROUP, i % FUSED_GROUP, sh, n_tiles);
             return;
         }
         if (i >= n_tiles * G) return;
@@ -1872,7 +2263,7 @@ static hipError_t step_typed(const DevPtrs& d, int n_req, int n_tiles, int lsa_s
 #define LSA_ARGS d.L, d.live, d.done, d.step_seq, d.qpart, d.w_last[cur], d.w_acc[cur], d.PM, d, cur, n_req
     // two-byte pools with both pre-sums: the decoder LSTM's sums over H_att ride in this launch
     constexpr bool CO = PRE_DEC && sizeof(XT) == 2 && sizeof(MT) == 2;   // (the attention kernel for fp32 memory needs more than 128 registers)
-    if (CO != (d.pre_dec_b != nullptr)) return hipErrorInvalidValue;
+    if (CO != (d.pre_dec_b != nullptr) || CO != (d.hdec_x != nullptr)) return hipErrorInvalidValue;
     const int n_co = CO ? DEC_HATT_WGS * (n_tiles > 1 ? 2 : 1) : 0;
     if (lsa_split == 4) hipLaunchKernelGGL((k_lsa<XT, MT, 4, PRE, CO>), dim3(n_pad * 4 + n_co), dim3(LSA_THREADS), 0, s, LSA_ARGS);
     else if (CO) return hipErrorInvalidValue;     // such pools span at most 64 slots: four workgroups per slot
@@ -1884,7 +2275,10 @@ static hipError_t step_typed(const DevPtrs& d, int n_req, int n_tiles, int lsa_s
     const uint4* xdec_in = reinterpret_cast<const uint4*>(d.xdec[cur]);
     const floatx4* pre_dec = reinterpret_cast<const floatx4*>(d.pre_dec);
     const floatx4* pre_dec_b = reinterpret_cast<const floatx4*>(d.pre_dec_b);
-    if (rows == 4) {
+    if constexpr (CO) {
+        // the decoder LSTM is part of the last kernel's launch (below)
+        if (proj_group != 6) return hipErrorInvalidValue;
+    } else if (rows == 4) {
         if constexpr (HAS_WIDE && !PRE_DEC)
             hipLaunchKernelGGL((k_lstm_stream<XT, K_DEC, 4, 4>), lg, lb, 0, s, d.Wd, xdec_in, d.bd, d.c_dec, d.live, d.done,
                                xdec_nxt, K_DEC / KB, XD_HD, xdec_nxt, K_DEC / KB, XD_HD, n_tiles);
@@ -1903,7 +2297,7 @@ static hipError_t step_typed(const DevPtrs& d, int n_req, int n_tiles, int lsa_s
     // with pre-sums the projection's launch fills the chip: XCD 0 runs the projection, the rest form the pre-sums
     const dim3 pg(PRE ? 256 : n_tiles * proj_group), pb(PROJ_THREADS);
 #define PROJ_ARGS d.Wa, d.Wd, (const void*)d.xatt[cur ^ 1], (const void*)d.xdec[cur ^ 1], (const void*)d.xdec[cur], d.Wmel, (const int*)d.live, d.proj_seq, d, cur, n_tiles
-    if (proj_group == 6) hipLaunchKernelGGL((k_proj<XT, PRE, 6>), pg, pb, 0, s, PROJ_ARGS);
+    if (proj_group == 6) hipLaunchKernelGGL((k_proj<XT, PRE, 6, CO>), pg, pb, 0, s, PROJ_ARGS);
     else if (proj_group == 3) hipLaunchKernelGGL((k_proj<XT, PRE, 3>), pg, pb, 0, s, PROJ_ARGS);
     else if (proj_group == 2) hipLaunchKernelGGL((k_proj<XT, PRE, 2>), pg, pb, 0, s, PROJ_ARGS);
 #undef PROJ_ARGS

@@ -112,6 +112,19 @@ __device__ __forceinline__ uint4 buffer_load16(__amdgpu_buffer_rsrc_t rsrc, int 
     return make_uint4(v.x, v.y, v.z, v.w);
 }
 
+// Wait until at most N of this wave's vector-memory operations are still in flight.  Placed after each load of a long
+// run of loads it keeps a short rolling window in flight instead of the whole run: a workgroup that asks for everything
+// it needs at once gets 35-60 GB/s out of its compute unit's load path, one that keeps two to sixteen loads per wave in
+// flight 85-125 GB/s (measured on MI355X: one workgroup pulling 224 KB from HBM in 5.0 us against 1.8 us).
+template <int N> __device__ __forceinline__ void vm_in_flight_at_most()
+{
+    static_assert(N >= 0 && N < 64, "vmcnt is a six-bit counter");
+    // gfx9 s_waitcnt operand: vmcnt in bits [3:0] and [15:14]; expcnt [6:4] and lgkmcnt [11:8] left at "do not wait"
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | (0x7 << 4) | (0xF << 8));
+    asm volatile("" ::: "memory");
+}
+
 // Fragment geometry for element type T: a fragment is 64 bytes of k per row / column.
 template <typename T> struct Frag {
     static constexpr int KB = 64 / (int)sizeof(T);    // k elements per fragment
