@@ -156,6 +156,26 @@ def test_drain_chunks_and_errors(wl8, weights_fp32):
     pool.close()
 
 
+@pytest.fixture(scope="module")
+def wl8_bf16():
+    return synth.small_workload(8, 5, 90, 24, 24, seed=11, bf16=True)
+
+
+@pytest.fixture(scope="module")
+def solo_frames_bf16(wl8_bf16, weights_bf16):
+    """Every request of wl8_bf16 decoded alone in a two-byte pool of one (24 frames): the step of such pools is three
+    launches, with the decoder LSTM inside the last one."""
+    say("reference: 8 requests decoded alone, bf16")
+    return [gpu_decode(wl8_bf16, weights_bf16, [i], 24)[0] for i in range(8)]
+
+
+def _mode(request, bf16):
+    """(workload, weights, solo frames) of the fp32 or the two-byte flavour of the 8-request workload."""
+    if bf16:
+        return request.getfixturevalue("wl8_bf16"), request.getfixturevalue("weights_bf16"), request.getfixturevalue("solo_frames_bf16")
+    return request.getfixturevalue("wl8"), request.getfixturevalue("weights_fp32"), request.getfixturevalue("solo_frames")
+
+
 def test_snapshot_resume(wl8, weights_fp32, solo_frames):
     """The carried state set of Sec. 2.1.3 is complete: a fresh request restored
     from get_state continues on the same trajectory.  (Not bit-exact: restoring
@@ -319,13 +339,14 @@ def test_pools_of_several_tiles_with_gate_presums(bf16, max_pool, n_req, weights
     np.testing.assert_array_equal(few[4], full[0])
 
 
-@pytest.mark.parametrize("bf16,max_pool", [(False, 20), (True, 200)])
+@pytest.mark.parametrize("bf16,max_pool", [(False, 20), (True, 20), (True, 200)])
 def test_state_overwrite_refreshes_the_gate_presums(bf16, max_pool, weights_bf16, weights_fp32):
     """A request's H_att, A and H_dec are overwritten between steps with another request's: the
     pre-sums formed from the old state during the last projection must not reach the next step.
     Two pools run the same request; in the second its recurrent state is first replaced by
     garbage, then by the first pool's: the following frames are identical.  (Capacity 200, bf16: the
-    pool keeps pre-sums of the attention LSTM only.)"""
+    pool keeps pre-sums of the attention LSTM only.  Capacity 20, bf16: the decoder LSTM's pre-sums are formed inside
+    the step that uses them.)"""
     say(f"case: set_state between steps in a pool with gate pre-sums, capacity {max_pool}")
     wl8 = synth.small_workload(8, 5, 90, 24, 24, seed=11, bf16=bf16)
     weights_fp32 = weights_bf16 if bf16 else weights_fp32
@@ -351,11 +372,15 @@ def test_state_overwrite_refreshes_the_gate_presums(bf16, max_pool, weights_bf16
         pool.close()
 
 
-def test_wait_bound_zero_loses_only_the_step_in_flight_and_the_pool_goes_on(wl8, weights_fp32, solo_frames):
+@pytest.mark.parametrize("bf16", [False, True])
+def test_wait_bound_zero_loses_only_the_step_in_flight_and_the_pool_goes_on(bf16, request):
     """In pools of at most 64 slots workgroups wait, a bounded number of polls, for words other workgroups hand
     them.  With the bound set to zero (forced from the host: every kernel still runs through) every such wait gives
     up at once.  The requests whose words were missing are frozen at the frames they have -- nothing invalid is ever
-    stored -- and reported once; after that the same pool serves new requests with exactly the solo frames again."""
+    stored -- and reported once; after that the same pool serves new requests with exactly the solo frames again.
+    (Two-byte pools: the waits of the three-launch step too -- the projection's workers for the decoder LSTM's words,
+    their leader for the workers' sums.)"""
+    wl8, weights_fp32, solo_frames = _mode(request, bf16)
     from paper_2211_13939_amd import binding
     from paper_2211_13939_amd.binding import TtsError
     say("case: wait bound 0 (give-up path, forced from the host), then the same pool again")
@@ -394,10 +419,12 @@ def test_wait_bound_zero_loses_only_the_step_in_flight_and_the_pool_goes_on(wl8,
     pool.close()
 
 
-def test_steps_beside_other_work_on_the_gpu(wl8, weights_fp32, solo_frames):
+@pytest.mark.parametrize("bf16", [False, True])
+def test_steps_beside_other_work_on_the_gpu(bf16, request):
     """The kernels of a step wait for words of partner workgroups (bounded).  With another stream keeping the CUs
     busy a partner may start late: the frames must not change and no wait may run out."""
     import torch
+    wl8, weights_fp32, solo_frames = _mode(request, bf16)
     say("case: decoder steps while a second stream runs large matrix products")
     pool = make_pool(wl8, weights_fp32, max_pool=8, max_enc_len=90, max_steps=24, chunk_frames=24)
     rids = [pool.add_request(wl8.encoder_outputs(i), 24) for i in range(8)]
