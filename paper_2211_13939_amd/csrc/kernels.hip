@@ -1642,8 +1642,10 @@ __device__ __forceinline__ void proj_tile(const DevPtrs& d, const ProjHot& hot, 
 // words; worker 0's start from the bias.  A further workgroup leads: it pulls nothing but the prenet's weights (with a
 // short window of loads per wave in flight: a wave that asks for all of them at once gets less than half the rate out of
 // the CU's load path), polls the G partial sums, adds them in worker order - the plain form's order, the frame is the
-// same bits - and finishes alone: prenet, then the books.  (All G + 1 workgroups adding the sums themselves and sharing
-// the prenet's second layer was tried: six times the polls, and a word took 3 us to be seen instead of 1.)
+// same bits - and runs the prenet.  The last worker, whose fragments of K lie in `a` and which is therefore done early,
+// collects the sums as well and keeps the books meanwhile: frame and stop value into the rings, frame counters, end of a
+// request.  (All G + 1 workgroups adding the sums themselves and sharing the prenet's second layer was tried: six times
+// the polls, and a word took 3 us to be seen instead of 1.)
 constexpr int FUSED_GROUP = PROJ_GROUP_K + 1;    // workgroups per tile: the workers and the leader
 template <typename XT>
 __device__ __forceinline__ void proj_tile_fused(const DevPtrs& d, const ProjHot& hot, int cur, int tile, int kp, const ProjShared& sh, int n_tiles)
@@ -1672,6 +1674,54 @@ __device__ __forceinline__ void proj_tile_fused(const DevPtrs& d, const ProjHot&
     // this workgroup's count of the steps it has taken part in: the number its words carry, and the one it expects
     const unsigned my_seq = hot.proj_seq[tile * FUSED_GROUP + kp];
 
+    // slot bookkeeping of the 16 columns: the leader (which stores p) and the keeper of the books (the last worker) need it
+    const bool keeper = kp == G - 1;
+    const int my_sl = tile * 16 + (tid & 15);
+    const int my_live = hot.live[my_sl], my_done = d.done[my_sl];
+    const int my_t = d.t[my_sl], my_cap = d.n_steps[my_sl];
+    const unsigned step_no = d.step_seq[0];
+
+    // The workers' sums as they arrive (every thread polls its own words, a bounded number of times), added in worker
+    // order; then the frame into LDS.  A wait that ran out: the tile's frames cannot be formed; its requests are frozen
+    // where they stand (done: every later kernel leaves them alone; failed: the host tells their owners) and the
+    // workgroup stores nothing of this step for them.  Leader and keeper each do this for themselves.
+    auto collect_frame = [&]() __attribute__((always_inline)) {
+        float v[RED_IT];
+        unsigned long long w[G][RED_IT];
+        bool all_in = false;
+        for (int spin = 0; spin < d.wait_polls && !all_in; ++spin) {
+            all_in = true;
+#pragma unroll
+            for (int h = 0; h < G; ++h) {
+                const unsigned long long* theirs = d.proj_part + (size_t)(tile * G + h) * (16 * PROJ_ROWS);
+#pragma unroll
+                for (int it = 0; it < RED_IT; ++it) {
+                    w[h][it] = __hip_atomic_load(&theirs[tid + it * PROJ_THREADS], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    all_in = all_in && (unsigned)(w[h][it] >> 32) == my_seq + 1u;
+                }
+            }
+        }
+        if (!all_in) *sh.ok = 0;
+#pragma unroll
+        for (int it = 0; it < RED_IT; ++it) {
+            v[it] = __uint_as_float((unsigned)w[0][it]);
+#pragma unroll
+            for (int h = 1; h < G; ++h) v[it] += __uint_as_float((unsigned)w[h][it]);
+            const int idx = tid + it * PROJ_THREADS;
+            sh.mel[idx & 15][idx >> 4] = v[it];
+        }
+        __syncthreads();
+        const bool gave_up = *sh.ok == 0;
+        __syncthreads();
+        if (gave_up && tid < 16 && sh.slot[tid] >= 0) {
+            d.done[sh.slot[tid]] = 1;
+            d.failed[sh.slot[tid]] = 1;
+            *d.fault = 1;
+            sh.slot[tid] = -1;
+        }
+        if (gave_up) __syncthreads();
+    };
+
     if (!leader) {
         // ---- a worker: fragment ks of K = [h_dec; a] in wave `wave`
         const uint4* xcur = reinterpret_cast<const uint4*>(hot.xdec_cur);
@@ -1683,6 +1733,12 @@ __device__ __forceinline__ void proj_tile_fused(const DevPtrs& d, const ProjHot&
         for (int it = 0; it < RED_IT; ++it) bias_r[it] = d.bmel[min((tid + it * PROJ_THREADS) >> 4, N_PROJ - 1)];
         __builtin_amdgcn_sched_barrier(0);
         dec.finish(d, hot, reinterpret_cast<DecRed>(sh.big));
+        if (tid < 16) {
+            const bool on = my_live && !my_done;
+            sh.slot[tid] = on ? my_sl : -1;
+            sh.t[tid] = on ? my_t : 0;
+            sh.cap[tid] = on ? my_cap : 0;
+        }
         __syncthreads();                                   // (a piece without pool tiles has no barrier of its own)
         // (all six row tiles' fragments, the zero rows of the last included: a branch around a load would make the
         // compiler wait for every load in flight where it rejoins)
@@ -1714,7 +1770,7 @@ __device__ __forceinline__ void proj_tile_fused(const DevPtrs& d, const ProjHot&
         }
         __syncthreads();
         // ... reduced over the waves and handed over, each word with the step count beside it in one 8-byte store (a
-        // worker whose wait for h_dec ran out hands nothing over: the leader's wait then runs out as well)
+        // worker whose wait for h_dec ran out hands nothing over: the waits for its sums then run out as well)
         if (*sh.ok) {
             unsigned long long* mine = d.proj_part + (size_t)(tile * G + kp) * (16 * PROJ_ROWS);
 #pragma unroll
@@ -1731,14 +1787,38 @@ __device__ __forceinline__ void proj_tile_fused(const DevPtrs& d, const ProjHot&
             }
         }
         if (tid == 0) hot.proj_seq[tile * FUSED_GROUP + kp] = my_seq + 1u;
+        if (!keeper) return;
+
+        // ---- the keeper of the books (the last worker, whose fragments lie in `a`: it is done early): the frame out, one
+        // step further, while the leader runs the prenet
+        collect_frame();
+        for (int idx = tid; idx < 16 * N_PROJ; idx += PROJ_THREADS) {
+            const int r = idx / N_PROJ, o = idx - r * N_PROJ;
+            const int sl = sh.slot[r];
+            if (sl >= 0) {
+                const float m = sh.mel[r][o];
+                if (o < N_MEL) {
+                    d.mel_ring[((size_t)sl * d.max_steps + sh.t[r]) * N_MEL + o] = m;
+                    d.m_last[(size_t)sl * N_MEL + o] = m;
+                } else {
+                    d.stop_ring[(size_t)sl * d.max_steps + sh.t[r]] = m;
+                }
+            }
+        }
+        // the number the attention kernel's workgroups mark their exchanged words with
+        if (tile == 0 && tid == 0) d.step_seq[0] = step_no + 1u;
+        if (tid < 16 && sh.slot[tid] >= 0) {
+            const int sl = sh.slot[tid];
+            const int tn = sh.t[tid] + 1;
+            d.t[sl] = tn;
+            bool fin = tn >= sh.cap[tid];
+            if (d.stop_threshold >= 0.f && sigmoidf_(sh.mel[tid][N_MEL]) > d.stop_threshold) fin = true;
+            if (fin) d.done[sl] = 1;
+        }
         return;
     }
 
     // ---- the leader
-    const int my_sl = tile * 16 + (tid & 15);
-    const int my_live = hot.live[my_sl], my_done = d.done[my_sl];
-    const int my_t = d.t[my_sl], my_cap = d.n_steps[my_sl];
-    const unsigned step_no = d.step_seq[0];
     __builtin_amdgcn_sched_barrier(0);
     dec.finish(d, hot, reinterpret_cast<DecRed>(sh.big));
     if (tid < 16) {
@@ -1766,50 +1846,8 @@ __device__ __forceinline__ void proj_tile_fused(const DevPtrs& d, const ProjHot&
         }
     }
     __builtin_amdgcn_sched_barrier(0);
-    // the workers' sums as they arrive (every thread polls its own words), added in worker order
-    float v[RED_IT];
-    {
-        unsigned long long w[G][RED_IT];
-        bool all_in = false;
-        for (int spin = 0; spin < d.wait_polls && !all_in; ++spin) {
-            all_in = true;
-#pragma unroll
-            for (int h = 0; h < G; ++h) {
-                const unsigned long long* theirs = d.proj_part + (size_t)(tile * G + h) * (16 * PROJ_ROWS);
-#pragma unroll
-                for (int it = 0; it < RED_IT; ++it) {
-                    w[h][it] = __hip_atomic_load(&theirs[tid + it * PROJ_THREADS], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    all_in = all_in && (unsigned)(w[h][it] >> 32) == my_seq + 1u;
-                }
-            }
-        }
-        if (!all_in) *sh.ok = 0;
-#pragma unroll
-        for (int it = 0; it < RED_IT; ++it) {
-            v[it] = __uint_as_float((unsigned)w[0][it]);
-#pragma unroll
-            for (int h = 1; h < G; ++h) v[it] += __uint_as_float((unsigned)w[h][it]);
-        }
-        if (tid == 0) hot.proj_seq[tile * FUSED_GROUP + kp] = my_seq + 1u;
-    }
-#pragma unroll
-    for (int it = 0; it < RED_IT; ++it) {
-        const int idx = tid + it * PROJ_THREADS;
-        sh.mel[idx & 15][idx >> 4] = v[it];
-    }
-    __syncthreads();
-    // A wait that ran out: the workers' sums never came, so this tile's frames cannot be formed.  Its requests are
-    // frozen where they stand (done: every later kernel leaves them alone; failed: the host tells their owners) and
-    // nothing of this step is stored for them; the step counter below still advances for everyone else.
-    const bool gave_up = *sh.ok == 0;
-    __syncthreads();
-    if (gave_up && tid < 16 && sh.slot[tid] >= 0) {
-        d.done[sh.slot[tid]] = 1;
-        d.failed[sh.slot[tid]] = 1;
-        *d.fault = 1;
-        sh.slot[tid] = -1;
-    }
-    if (gave_up) __syncthreads();
+    collect_frame();
+    if (tid == 0) hot.proj_seq[tile * FUSED_GROUP + kp] = my_seq + 1u;
 
     // hid^T = relu(W_p1 mel^T); wave w owns row tiles w and w + 8
     {
@@ -1849,30 +1887,6 @@ __device__ __forceinline__ void proj_tile_fused(const DevPtrs& d, const ProjHot&
                 *reinterpret_cast<uint2*>(dst) = make_uint2(pack2<XT>(p0, p1), pack2<XT>(p2, p3));
             }
         }
-    }
-    // the books: the frame out, one step further
-    for (int idx = tid; idx < 16 * N_PROJ; idx += PROJ_THREADS) {
-        const int r = idx / N_PROJ, o = idx - r * N_PROJ;
-        const int sl = sh.slot[r];
-        if (sl >= 0) {
-            const float m = sh.mel[r][o];
-            if (o < N_MEL) {
-                d.mel_ring[((size_t)sl * d.max_steps + sh.t[r]) * N_MEL + o] = m;
-                d.m_last[(size_t)sl * N_MEL + o] = m;
-            } else {
-                d.stop_ring[(size_t)sl * d.max_steps + sh.t[r]] = m;
-            }
-        }
-    }
-    // the number the attention kernel's workgroups mark their exchanged words with
-    if (tile == 0 && tid == 0) d.step_seq[0] = step_no + 1u;
-    if (tid < 16 && sh.slot[tid] >= 0) {
-        const int sl = sh.slot[tid];
-        const int tn = sh.t[tid] + 1;
-        d.t[sl] = tn;
-        bool fin = tn >= sh.cap[tid];
-        if (d.stop_threshold >= 0.f && sigmoidf_(sh.mel[tid][N_MEL]) > d.stop_threshold) fin = true;
-        if (fin) d.done[sl] = 1;
     }
 }
 
