@@ -614,6 +614,14 @@ def main():
         # gaps out, so each kernel is charged an equal share of what the graph-launched step takes beyond their sum
         # (this is also how rocprofv3's kernel trace accounts: a kernel's start is the previous kernel's end)
         kernel_us = {k: v for k, v in kernel_us.items() if v > 0.0}     # (no decoder-LSTM kernel in the fused form of the step)
+        # Pools whose last launch also forms the next step's attention LSTM: a step inside a call is two launches (the
+        # attention kernel and the last one, which then moves the attention LSTM's bytes as well); only a call's first
+        # step has an attention-LSTM launch (k_lstm_att: that one launch) and only its last a plain last kernel.
+        first_step_us = {}
+        if "k_proj_last_step" in kernel_us:
+            first_step_us = {"k_lstm_att": kernel_us.pop("k_lstm_att", 0.0), "k_proj_last_step": kernel_us.pop("k_proj_last_step")}
+            per_kernel = dict(per_kernel)
+            per_kernel["k_proj"] += per_kernel.pop("k_lstm_att")
         gap = max(0.0, (step_us - sum(kernel_us.values())) / len(kernel_us))
         launch_us = {k: v + gap for k, v in kernel_us.items()}
         dom = max(launch_us, key=launch_us.get)
@@ -623,6 +631,7 @@ def main():
                            "traffic": traffic.get(dom) if traffic else None,
                            "launch_us": launch_us, "kernel_us": kernel_us, "launch_gap_us": gap,
                            "event_cost_us": event_cost_us, "algorithmic_bytes": per_kernel,
+                           "launches_per_step": len(kernel_us), "first_and_last_step_of_a_call_us": first_step_us or None,
                            "note": "kernel_us: HIP-event intervals around each kernel of 30 un-graphed full-pool steps "
                                    "queued back to back, minus the measured cost of an event; launch_us = kernel_us + an "
                                    "equal share of the graph-launched step time not covered by them (the launch gaps), the "

@@ -232,9 +232,16 @@ int tts_pool_elapsed_ms(tts_pool *pool, float *out_ms);
  * *out_n_kernels receives how many there are: attention LSTM, attention,
  * decoder LSTM, projection + prenet; two-byte pools of at most 64 slots have
  * no decoder-LSTM kernel - it is part of the last kernel's launch - and report
- * 0 for it).  The device cost of an event itself is
+ * 0 for it).  The n steps are launched as one call of n steps launches them:
+ * in those pools the last kernel of every step but the call's last also forms
+ * the next step's attention LSTM, so only the first step has an
+ * attention-LSTM kernel (that one launch is the figure reported) and the
+ * projection's figure is the average over the steps whose launch carried that
+ * extra part.  The device cost of an event itself is
  * measured with adjacent events and subtracted; if cap > *out_n_kernels it is
- * stored after the kernel times.  The intervals still contain the launch gap,
+ * stored after the kernel times, and if cap > *out_n_kernels + 1 the time of
+ * the last kernel without the extra part (the call's last step; 0 where no
+ * step differs) after that.  The intervals still contain the launch gap,
  * so they are upper bounds of the kernels' own durations.  The steps are real:
  * requests advance.  Waits for the stream. */
 int tts_pool_kernel_times(tts_pool *pool, int n, float *out_us, int cap, int *out_n_kernels);

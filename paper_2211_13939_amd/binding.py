@@ -351,6 +351,8 @@ class Pool:
         _check(lib().tts_pool_kernel_times(self._h, int(n_steps), buf, 8, C.byref(nk)))
         out = {self.KERNEL_NAMES[i]: float(buf[i]) for i in range(nk.value)}
         out["event_cost"] = float(buf[nk.value])
+        if buf[nk.value + 1] > 0:
+            out["k_proj_last_step"] = float(buf[nk.value + 1])
         return out
 
     def drain_all(self, rid: int) -> np.ndarray:

@@ -54,6 +54,14 @@ struct DevPtrs {
     unsigned long long* hdec_x; // [tiles][HID / 32 fragments][64 lanes][4] (sequence number << 32 | two halves): H_dec of the step as the
                           // projection's B operand, handed from the decoder LSTM's part of the fused last kernel to the projection's
                           // workgroups of the same launch (null: the decoder LSTM is a kernel of its own)
+    unsigned long long* p_x;    // [tiles][PRENET / 32 fragments][4][64 lanes] (bit 63: the slot takes no further step | sequence number << 32 |
+                          // two halves): the prenet output of the step as the attention LSTM's B operand, handed from a tile's leader to
+                          // the workgroups that form the NEXT step's attention LSTM inside the same launch (steps that are followed
+                          // by another step of the same call; null: the attention LSTM is always a kernel of its own)
+    unsigned long long* pre_x;  // [tiles][HID / 4 row tiles][4][64 lanes] (sequence number << 32 | float bits): the attention LSTM's
+                          // gate pre-sums, handed to those workgroups by the ones that form them
+    unsigned* wg_seq;     // [2]: launches of the fused last kernel so far, double buffered by the steps' parity (a launch reads one
+                          // and writes the other; zero at creation): the stamp of the words in p_x and pre_x
     int* fault;           // pinned host memory: set by a workgroup whose bounded wait for another's words ran out (with `failed` of the slots it froze)
     const void* lsa_kfrag; // location filters as per-lane MFMA A operands (layout depends on WT)
     const void* lsa_wfrag; // W_loc as per-lane MFMA A operands (layout depends on WT)

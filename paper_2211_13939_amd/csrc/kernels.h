@@ -13,6 +13,10 @@ struct StepLaunch {
     int lsa_split;  // workgroups per request in the attention kernel (1, 2 or 4; they split the context columns)
     int lstm_rows;  // row tiles per LSTM workgroup: 1 (all pool tiles each), 2 or 4 (1/2 or 1/4 of the pool tiles each)
     int proj_group; // workgroups per pool tile in the projection kernel: 6, 3 or 2 (fixed per pool; with pre_gates, n_tiles * proj_group <= 32)
+    int att_lead;   // 1: the step begins with the attention LSTM's own launch (always, except in pools with d.p_x for a step
+                    // whose predecessor in the same call formed it already); 0: it does not
+    int att_tail;   // 1 (pools with d.p_x only): the step's last launch also forms the attention LSTM of the next step, which then
+                    // has att_lead = 0.  The membership and the requests' states must not change between the two steps.
     int pre_gates;  // 2: the projection's launch also forms the next step's gate pre-sums (d.pre_att / d.pre_dec; fp32: n_tiles <= PRESUM_SMALL_TILES),
                     // 1: the attention LSTM's only (pools of more than PRESUM_SMALL_TILES tiles: d.pre_dec is null);
                     // either way the attention LSTM hands the query to the attention kernel as rank-32 partial products (d.qpart)

@@ -9,7 +9,9 @@
 //                                                         (Eq. 2 line 5, Pre() of line 1)
 // Two-byte pools of at most 64 slots run three: what is left of the decoder LSTM
 // there (K = 512 of 2560, the rest arrives as gate pre-sums) is formed by the
-// workgroups of k_proj's launch before they turn to their own parts.
+// workgroups of k_proj's launch before they turn to their own parts.  And two
+// for a step that follows another step of the same call: its attention LSTM
+// (K = 256 left) was formed at the end of that step's k_proj launch.
 //
 // Activations (the vectors multiplied by weight matrices) live in HBM in MFMA
 // B-operand order, tiled by pool slot: 16 slots form a tile, and a tile's
@@ -449,8 +451,10 @@ struct ProjHot {
 
 // DEC: the decoder LSTM's pre-sums too (pools of at most four tiles; larger pools keep all of its K in its own kernel
 // and have no buffer for them)
+// With `stamp` non-zero the attention LSTM's sums go to pre_x as 8-byte words that carry the stamp instead of to pre_att:
+// the next step's attention LSTM is then formed inside this launch (att_tail_unit) and polls them.
 template <typename XT, int NR, int NT, bool DEC>
-__device__ __forceinline__ void gate_presums_rt(const DevPtrs& d, const ProjHot& hot, int r0, int t0, PresumRed red)
+__device__ __forceinline__ void gate_presums_rt(const DevPtrs& d, const ProjHot& hot, int r0, int t0, PresumRed red, unsigned stamp)
 {
     constexpr int NW = LSTM_WAVES, KB = Frag<XT>::KB;
     constexpr int NK_A = K_ATT / KB, NK_D = K_DEC / KB;
@@ -487,7 +491,7 @@ __device__ __forceinline__ void gate_presums_rt(const DevPtrs& d, const ProjHot&
 #pragma unroll
             for (int t = 0; t < NT; ++t) acc[r][t] = floatx4{0.f, 0.f, 0.f, 0.f};
     };
-    auto finish = [&](float* out) __attribute__((always_inline)) {
+    auto finish = [&](float* out, bool as_words) __attribute__((always_inline)) {
 #pragma unroll
         for (int r = 0; r < NR; ++r)
 #pragma unroll
@@ -497,7 +501,15 @@ __device__ __forceinline__ void gate_presums_rt(const DevPtrs& d, const ProjHot&
             floatx4 g = red[0][wave][lane];
 #pragma unroll
             for (int w = 1; w < NW; ++w) g += red[w][wave][lane];
-            reinterpret_cast<floatx4*>(out)[((size_t)(t0 + wave % NT) * (HID / 4) + r0 + wave / NT) * 64 + lane] = g;
+            const size_t at = (size_t)(t0 + wave % NT) * (HID / 4) + r0 + wave / NT;
+            if (as_words) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    __hip_atomic_store(&d.pre_x[(at * 4 + i) * 64 + lane], ((unsigned long long)stamp << 32) | __float_as_uint(g[i]),
+                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            } else {
+                reinterpret_cast<floatx4*>(out)[at * 64 + lane] = g;
+            }
         }
         __syncthreads();
     };
@@ -515,24 +527,24 @@ __device__ __forceinline__ void gate_presums_rt(const DevPtrs& d, const ProjHot&
 #pragma unroll
                 for (int t = 0; t < NT; ++t) acc[r][t] = mfma_frag<XT>(a[i % PG_WIN][r][c], b[i % PG_WIN][t][c], acc[r][t]);
         if (i == NA - 1) {
-            finish(d.pre_att);
+            finish(d.pre_att, stamp != 0u);
             clear();
         }
     }
-    if constexpr (DEC) finish(d.pre_dec);
+    if constexpr (DEC) finish(d.pre_dec, false);
 }
 
 template <typename XT, bool DEC>
-__device__ __forceinline__ void gate_presums_sel(const DevPtrs& d, const ProjHot& hot, int r0, int nr, int t0, int nt, PresumRed red)
+__device__ __forceinline__ void gate_presums_sel(const DevPtrs& d, const ProjHot& hot, int r0, int nr, int t0, int nt, PresumRed red, unsigned stamp = 0u)
 {
     if (nt == 1) {
-        if (nr == 1) gate_presums_rt<XT, 1, 1, DEC>(d, hot, r0, t0, red);
-        else if (nr == 2) gate_presums_rt<XT, 2, 1, DEC>(d, hot, r0, t0, red);
-        else gate_presums_rt<XT, 3, 1, DEC>(d, hot, r0, t0, red);
+        if (nr == 1) gate_presums_rt<XT, 1, 1, DEC>(d, hot, r0, t0, red, stamp);
+        else if (nr == 2) gate_presums_rt<XT, 2, 1, DEC>(d, hot, r0, t0, red, stamp);
+        else gate_presums_rt<XT, 3, 1, DEC>(d, hot, r0, t0, red, stamp);
     } else {
-        if (nr == 1) gate_presums_rt<XT, 1, 2, DEC>(d, hot, r0, t0, red);
-        else if (nr == 2) gate_presums_rt<XT, 2, 2, DEC>(d, hot, r0, t0, red);
-        else gate_presums_rt<XT, 3, 2, DEC>(d, hot, r0, t0, red);
+        if (nr == 1) gate_presums_rt<XT, 1, 2, DEC>(d, hot, r0, t0, red, stamp);
+        else if (nr == 2) gate_presums_rt<XT, 2, 2, DEC>(d, hot, r0, t0, red, stamp);
+        else gate_presums_rt<XT, 3, 2, DEC>(d, hot, r0, t0, red, stamp);
     }
 }
 
@@ -1647,8 +1659,12 @@ __device__ __forceinline__ void proj_tile(const DevPtrs& d, const ProjHot& hot, 
 // request.  (All G + 1 workgroups adding the sums themselves and sharing the prenet's second layer was tried: six times
 // the polls, and a word took 3 us to be seen instead of 1.)
 constexpr int FUSED_GROUP = PROJ_GROUP_K + 1;    // workgroups per tile: the workers and the leader
+// row groups of the next step's attention LSTM per workgroup that forms them (two: half as many workgroups polling, but
+// twice the weights through each one's load path, which is what the tail of the launch then waits for: + 0.5 us)
+constexpr int TAIL_RG = 1;
 template <typename XT>
-__device__ __forceinline__ void proj_tile_fused(const DevPtrs& d, const ProjHot& hot, int cur, int tile, int kp, const ProjShared& sh, int n_tiles)
+__device__ __forceinline__ void proj_tile_fused(const DevPtrs& d, const ProjHot& hot, int cur, int tile, int kp, const ProjShared& sh, int n_tiles,
+                                                unsigned tail_stamp)
 {
     constexpr int G = PROJ_GROUP_K;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
@@ -1874,19 +1890,151 @@ __device__ __forceinline__ void proj_tile_fused(const DevPtrs& d, const ProjHot&
         for (int f = 0; f < NK4; ++f) bh[f] = frag_from_f32<XT>(&s_hid[jl][f * KB + g * EPL]);
         const int sl = sh.slot[jl];
         XT* xa = reinterpret_cast<XT*>(d.xatt[cur ^ 1]);
+        // handed over as words (tail_stamp != 0): does the slot take the next step?  The rule the keeper of the books applies.
+        bool goes_on = sl >= 0 && sh.t[jl] + 1 < sh.cap[jl];
+        if (d.stop_threshold >= 0.f && sigmoidf_(sh.mel[jl][N_MEL]) > d.stop_threshold) goes_on = false;
+        const unsigned long long mark = (unsigned long long)((goes_on ? 0u : 0x80000000u) | tail_stamp) << 32;
 #pragma unroll
         for (int m = 0; m < 2; ++m) {
             const int mt = wave + m * PROJ_WAVES;
             floatx4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int f = 0; f < NK4; ++f) acc = mfma_frag<XT>(a4[m][f], bh[f], acc);
-            if (sl >= 0) {
+            const float p0 = fmaxf(acc[0], 0.f), p1 = fmaxf(acc[1], 0.f), p2 = fmaxf(acc[2], 0.f), p3 = fmaxf(acc[3], 0.f);
+            const unsigned lo = sl >= 0 ? pack2<XT>(p0, p1) : 0u, hi = sl >= 0 ? pack2<XT>(p2, p3) : 0u;
+            if (tail_stamp != 0u) {
+                // rows 16 mt + 4 g .. + 3 of p = half of the 16-byte piece (mt % 2) * 2 + g / 2 of fragment mt / 2, column jl
+                const int piece = (mt & 1) * 2 + (g >> 1);
+                unsigned long long* px = d.p_x + (((size_t)tile * (PRENET / KB) + (mt >> 1)) * 4 + 2 * (g & 1)) * 64 + piece * 16 + jl;
+                __hip_atomic_store(px, mark | lo, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(px + 64, mark | hi, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            } else if (sl >= 0) {
                 // four consecutive k inside one 16-byte piece: one store
                 XT* dst = xa + xoff<XT>(K_ATT / KB, sl, XA_P + 16 * mt + 4 * g);
-                const float p0 = fmaxf(acc[0], 0.f), p1 = fmaxf(acc[1], 0.f), p2 = fmaxf(acc[2], 0.f), p3 = fmaxf(acc[3], 0.f);
-                *reinterpret_cast<uint2*>(dst) = make_uint2(pack2<XT>(p0, p1), pack2<XT>(p2, p3));
+                *reinterpret_cast<uint2*>(dst) = make_uint2(lo, hi);
             }
         }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// The attention LSTM of the NEXT step inside the last kernel's launch (steps followed by another step of the same
+// call): one of k_lstm_att_tall's units - 8 row tiles of one pool tile, one per wave - formed by a workgroup that has
+// finished its gate pre-sums.  The prenet output of the frame just produced arrives from the tile's leader as words
+// (p_x), the gate pre-sums from the workgroups that formed them (pre_x); every other operand is requested first.  Same
+// products and sums in the same order as the kernel, so the state is the same bits.  `cur` is the running step's
+// parity: the unit reads and writes what the next step's own kernel would (c_att, H_att into both activation halves,
+// the query partials).  A wait that runs out freezes the tile's requests as the projection's do.
+// ---------------------------------------------------------------------------
+template <typename XT, int RG>
+__device__ __forceinline__ void att_tail_unit(const DevPtrs& d, const ProjHot& hot, int cur, int tile, int rg0, unsigned stamp, float* lds)
+{
+    // RG row groups (rg0 .. rg0 + RG - 1) of 8 row tiles each: wave w owns row tile w of every one of them
+    constexpr int KB = Frag<XT>::KB;
+    constexpr int NK = K_ATT / KB;
+    constexpr int NF = PRENET / KB;
+    static_assert(NF == LSTM_WAVES && TALL_RT == LSTM_WAVES && PROJ_WAVES == LSTM_WAVES, "one fragment of p and one row tile per wave");
+    static_assert((NF * 64 * 4 + RG * 4 * TALL_RT * 16 + 1) * 4 <= (int)sizeof(float) * PROJ_WAVES * PROJ_ROWS * 16, "fits the launch's LDS");
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int sl = tile * 16 + (lane & 15);
+    const uint4* __restrict__ Wfrag = hot.Wa;
+
+    uint4 a[RG][NF];
+    float c_old[RG], wq[RG][TALL_RT];
+    floatx4 bias4[RG];
+    int unit[RG];
+#pragma unroll
+    for (int r = 0; r < RG; ++r) {
+        const int rt = (rg0 + r) * TALL_RT + wave;
+        unit[r] = rt * 4 + (lane >> 4);
+#pragma unroll
+        for (int f = 0; f < NF; ++f) a[r][f] = Wfrag[xfrag(NK, rt, f, lane)];
+    }
+    const int lv = hot.live[sl], dn = d.done[sl];
+#pragma unroll
+    for (int r = 0; r < RG; ++r) {
+        c_old[r] = d.c_att[(size_t)sl * HID + unit[r]];
+        bias4[r] = *reinterpret_cast<const floatx4*>(d.ba + unit[r] * 4);
+#pragma unroll
+        for (int s = 0; s < TALL_RT; ++s) wq[r][s] = d.Wq_epi[((size_t)((rg0 + r) * TALL_RT + s) * 8 + wave) * 64 + lane];
+    }
+    __builtin_amdgcn_sched_barrier(0);
+
+    uint4 (*s_b)[64] = reinterpret_cast<uint4 (*)[64]>(lds);                                   // [NF][64]
+    float (*s_h)[4 * TALL_RT][16] = reinterpret_cast<float (*)[4 * TALL_RT][16]>(lds + NF * 64 * 4);   // [RG][4 * TALL_RT][16]
+    int* s_ok = reinterpret_cast<int*>(lds + NF * 64 * 4 + RG * 4 * TALL_RT * 16);
+    if (threadIdx.x == 0) *s_ok = 1;
+    __syncthreads();
+
+    // The wave's row tiles of the pre-sums, long there; then its fragment of p: every lane polls its four words.
+    unsigned long long wp[RG][4], wb[4] = {0ull, 0ull, 0ull, 0ull};
+    bool all_in = false;
+    for (int spin = 0; spin < d.wait_polls && !all_in; ++spin) {
+        all_in = true;
+#pragma unroll
+        for (int r = 0; r < RG; ++r) {
+            const unsigned long long* qx = d.pre_x + (((size_t)tile * (HID / 4) + (rg0 + r) * TALL_RT + wave) * 4) * 64 + lane;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                wp[r][i] = __hip_atomic_load(&qx[i * 64], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                all_in = all_in && (unsigned)(wp[r][i] >> 32) == stamp;
+            }
+        }
+    }
+    const unsigned long long* px = d.p_x + (((size_t)tile * NF + wave) * 4) * 64 + lane;
+    bool p_in = false;
+    for (int spin = 0; spin < d.wait_polls && all_in && !p_in; ++spin) {
+        p_in = true;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            wb[i] = __hip_atomic_load(&px[i * 64], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            p_in = p_in && ((unsigned)(wb[i] >> 32) & 0x7fffffffu) == stamp;
+        }
+    }
+    if (!p_in) *s_ok = 0;
+    s_b[wave][lane] = make_uint4((unsigned)wb[0], (unsigned)wb[1], (unsigned)wb[2], (unsigned)wb[3]);
+    // (the words of lane l belong to column l % 16: the lane's own slot)
+    const bool goes_on = p_in && (wb[0] >> 63) == 0;
+    __syncthreads();
+    if (*s_ok == 0) {
+        if (threadIdx.x < 16 && lv && !dn) {
+            d.done[sl] = 1;
+            d.failed[sl] = 1;
+            *d.fault = 1;
+        }
+        return;
+    }
+    const bool active = lv && !dn && goes_on;
+#pragma unroll
+    for (int r = 0; r < RG; ++r) {
+        const floatx4 pre4 = {__uint_as_float((unsigned)wp[r][0]), __uint_as_float((unsigned)wp[r][1]), __uint_as_float((unsigned)wp[r][2]),
+                              __uint_as_float((unsigned)wp[r][3])};
+        floatx4 g4 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int f = 0; f < NF; ++f) g4 = mfma_frag<XT>(a[r][f], s_b[f][lane], g4);
+        g4 += bias4[r];
+        g4 += pre4;
+        const float gi = sigmoidf_(g4[0]), gf = sigmoidf_(g4[1]);
+        const float gg = tanhf_(g4[2]), go = sigmoidf_(g4[3]);
+        const float c = gf * c_old[r] + gi * gg;
+        const XT h = from_float<XT>(go * tanhf_(c));
+        if (active) {
+            // the next step's halves: its `cur` is this step's cur ^ 1
+            d.c_att[(size_t)sl * HID + unit[r]] = c;
+            reinterpret_cast<XT*>(d.xdec[cur ^ 1])[xoff<XT>(K_DEC / KB, sl, XD_HA + unit[r])] = h;
+            reinterpret_cast<XT*>(d.xatt[cur])[xoff<XT>(NK, sl, XA_H + unit[r])] = h;
+        }
+        s_h[r][4 * wave + (lane >> 4)][lane & 15] = active ? to_float(h) : 0.f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < RG; ++r) {
+        floatx4 part = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int s = 0; s < TALL_RT; ++s)
+            part = __builtin_amdgcn_mfma_f32_16x16x4f32(wq[r][s], s_h[r][4 * s + (lane >> 4)][lane & 15], part, 0, 0, 0);
+        if (active)
+            *reinterpret_cast<floatx4*>(d.qpart + ((size_t)sl * QP_TALL + rg0 + r) * ATT + 16 * wave + 4 * (lane >> 4)) = part;
     }
 }
 
@@ -1894,7 +2042,7 @@ __device__ __forceinline__ void proj_tile_fused(const DevPtrs& d, const ProjHot&
 template <typename XT, bool PRE, int G, bool FUSE = false>
 __global__ __launch_bounds__(PROJ_THREADS) void k_proj(const uint4* Wa_first, const uint4* Wd_first, const void* xatt_nxt_first, const void* xdec_nxt_first,
                                                       const void* xdec_cur_first, const void* Wmel_first, const int* live_first, unsigned* proj_seq_first,
-                                                      DevPtrs d, int cur, int n_tiles)
+                                                      DevPtrs d, int cur, int n_tiles, int tail)
 {
     const ProjHot hot = {Wa_first, Wd_first, xatt_nxt_first, xdec_nxt_first, xdec_cur_first, Wmel_first, live_first, proj_seq_first};
     __shared__ __attribute__((aligned(16))) float s_big[PROJ_WAVES * PROJ_ROWS * 16];
@@ -1903,6 +2051,16 @@ __global__ __launch_bounds__(PROJ_THREADS) void k_proj(const uint4* Wa_first, co
     __shared__ __attribute__((aligned(16))) float s_mel[16][PROJ_MEL_LD];
     __shared__ int s_slot[16], s_t[16], s_cap[16], s_ok;
     const ProjShared sh = {s_big, s_mel, s_slot, s_t, s_cap, &s_ok};
+
+    // tail: the launch also forms the next step's attention LSTM.  The words handed over for it carry a stamp: the number
+    // of launches of this kernel so far, kept as a pair of counters.  A launch reads the one of its parity and workgroup 0
+    // stores the next value into the other, which nobody reads before the next launch (the steps' parities alternate).
+    unsigned tail_stamp = 0u;
+    if constexpr (FUSE) {
+        const unsigned c = d.wg_seq[cur];
+        if (blockIdx.x == 0 && threadIdx.x == 0) d.wg_seq[cur ^ 1] = c + 1u;
+        if (tail) tail_stamp = c % 0x7ffffffeu + 1u;               // never zero, bit 31 free
+    }
 
     if constexpr (PRE) {
         // The launch has 256 workgroups, one per CU; workgroup b runs on XCD b % 8.  XCD 0 holds the projection's own
@@ -1941,8 +2099,13 @@ __global__ __launch_bounds__(PROJ_THREADS) void k_proj(const uint4* Wa_first, co
                 }
                 const int lo = rx0 + (rx1 - rx0) * k / Mc, hi = rx0 + (rx1 - rx0) * (k + 1) / Mc;
                 // (fused: the decoder LSTM's sums over H_dec are formed beside the attention kernel of the next step)
-                if constexpr (FUSE) gate_presums_sel<XT, false>(d, hot, lo, hi - lo, t0, nt, reinterpret_cast<PresumRed>(s_big));
-                else gate_presums<XT>(d, hot, lo, hi - lo, t0, nt, reinterpret_cast<PresumRed>(s_big));
+                if constexpr (FUSE) {
+                    gate_presums_sel<XT, false>(d, hot, lo, hi - lo, t0, nt, reinterpret_cast<PresumRed>(s_big), tail_stamp);
+                    // the next step's attention LSTM: unit c of 32 row groups x pool tiles, dealt over the seven XCDs
+                    const int c = i * 7 + (x - 1);
+                    constexpr int RG = TAIL_RG, per = QP_TALL / RG;
+                    if (tail_stamp != 0u && c < per * n_tiles) att_tail_unit<XT, RG>(d, hot, cur, c / per, c % per * RG, tail_stamp, s_big);
+                } else gate_presums<XT>(d, hot, lo, hi - lo, t0, nt, reinterpret_cast<PresumRed>(s_big));
             } else {
                 const int CG = (n_tiles + 3) / 4, Mc = 32 / CG;          // 2, 3 or 4 groups of 16, 10 or 8 workgroups
                 const int cg = i / Mc, k = i - cg * Mc;
@@ -1956,7 +2119,7 @@ __global__ __launch_bounds__(PROJ_THREADS) void k_proj(const uint4* Wa_first, co
         }
         if constexpr (FUSE) {
             static_assert(!FUSE || G == PROJ_GROUP_K, "the workers split K as the plain form's workgroups do");
-            if (i < n_tiles * FUSED_GROUP) proj_tile_fused<XT>(d, hot, cur, i / FUSED_GROUP, i % FUSED_GROUP, sh, n_tiles);
+            if (i < n_tiles * FUSED_GROUP) proj_tile_fused<XT>(d, hot, cur, i / FUSED_GROUP, i % FUSED_GROUP, sh, n_tiles, tail_stamp);
             return;
         }
         if (i >= n_tiles * G) return;
@@ -2241,7 +2404,8 @@ __global__ __launch_bounds__(256) void k_x_set(XT* X, int NK, int slot, int off,
 // ---------------------------------------------------------------------------
 // PM: 0 = no gate pre-sums, 1 = the attention LSTM's only (pools of more than four tiles), 2 = both LSTMs'
 template <typename XT, typename MT, int PM>
-static hipError_t step_typed(const DevPtrs& d, int n_req, int n_tiles, int lsa_split, int rows, int proj_group, int cur, hipStream_t s, hipEvent_t* ev)
+static hipError_t step_typed(const DevPtrs& d, int n_req, int n_tiles, int lsa_split, int rows, int proj_group, int att_lead, int att_tail, int cur,
+                             hipStream_t s, hipEvent_t* ev)
 {
     constexpr int KB = Frag<XT>::KB;
     auto mark = [&](int i) { if (ev) (void)hipEventRecord(ev[i], s); };
@@ -2261,7 +2425,12 @@ static hipError_t step_typed(const DevPtrs& d, int n_req, int n_tiles, int lsa_s
     // H_att(t): consumed by this step's decoder LSTM / attention and by the next step's attention LSTM.
     // With pre-sums: the tall kernel, which also hands the query over as partial products.  Without (fp32 pools of
     // more than four tiles): one row tile per workgroup, all of K.
-    if constexpr (PRE) {
+    constexpr bool CO = PRE_DEC && sizeof(XT) == 2 && sizeof(MT) == 2;   // (the attention kernel for fp32 memory needs more than 128 registers)
+    // only the fused last kernel can form the next step's attention LSTM, and only for a step that then runs without its own
+    if ((att_tail || !att_lead) && !(CO && d.p_x && d.pre_x && d.wg_seq)) return hipErrorInvalidValue;
+    if (!att_lead) {
+        // formed by the step before, inside its last launch
+    } else if constexpr (PRE) {
         if (n_tiles > 8)
             hipLaunchKernelGGL((k_lstm_att_tall<XT, 2>), dim3(QP_TALL * ((n_tiles + 1) / 2)), lb, 0, s, d.Wa, xatt_cur, d.ba, d.c_att, d.live, d.done,
                                reinterpret_cast<const floatx4*>(d.pre_att), d.Wq_epi, xdec_cur, K_DEC / KB, XD_HA, xatt_nxt, K_ATT / KB, XA_H, d.qpart, n_tiles);
@@ -2276,7 +2445,6 @@ static hipError_t step_typed(const DevPtrs& d, int n_req, int n_tiles, int lsa_s
     const int n_pad = (n_req + 7) / 8 * 8;      // slots are dealt to the XCDs in eights
 #define LSA_ARGS d.L, d.live, d.done, d.step_seq, d.qpart, d.w_last[cur], d.w_acc[cur], d.PM, d, cur, n_req
     // two-byte pools with both pre-sums: the decoder LSTM's sums over H_att ride in this launch
-    constexpr bool CO = PRE_DEC && sizeof(XT) == 2 && sizeof(MT) == 2;   // (the attention kernel for fp32 memory needs more than 128 registers)
     if (CO != (d.pre_dec_b != nullptr) || CO != (d.hdec_x != nullptr)) return hipErrorInvalidValue;
     const int n_co = CO ? DEC_HATT_WGS * (n_tiles > 1 ? 2 : 1) : 0;
     if (lsa_split == 4) hipLaunchKernelGGL((k_lsa<XT, MT, 4, PRE, CO>), dim3(n_pad * 4 + n_co), dim3(LSA_THREADS), 0, s, LSA_ARGS);
@@ -2310,7 +2478,7 @@ static hipError_t step_typed(const DevPtrs& d, int n_req, int n_tiles, int lsa_s
     mark(3);
     // with pre-sums the projection's launch fills the chip: XCD 0 runs the projection, the rest form the pre-sums
     const dim3 pg(PRE ? 256 : n_tiles * proj_group), pb(PROJ_THREADS);
-#define PROJ_ARGS d.Wa, d.Wd, (const void*)d.xatt[cur ^ 1], (const void*)d.xdec[cur ^ 1], (const void*)d.xdec[cur], d.Wmel, (const int*)d.live, d.proj_seq, d, cur, n_tiles
+#define PROJ_ARGS d.Wa, d.Wd, (const void*)d.xatt[cur ^ 1], (const void*)d.xdec[cur ^ 1], (const void*)d.xdec[cur], d.Wmel, (const int*)d.live, d.proj_seq, d, cur, n_tiles, att_tail
     if (proj_group == 6) hipLaunchKernelGGL((k_proj<XT, PRE, 6, CO>), pg, pb, 0, s, PROJ_ARGS);
     else if (proj_group == 3) hipLaunchKernelGGL((k_proj<XT, PRE, 3>), pg, pb, 0, s, PROJ_ARGS);
     else if (proj_group == 2) hipLaunchKernelGGL((k_proj<XT, PRE, 2>), pg, pb, 0, s, PROJ_ARGS);
@@ -2326,18 +2494,18 @@ hipError_t launch_step(const DevPtrs& d, const StepLaunch& cfg, int cur, hipStre
     if (cfg.pre_gates) {
         if (cfg.n_tiles > MAX_TILES || !d.pre_att || !d.qpart || (cfg.pre_gates == 2) != (d.pre_dec != nullptr)) return hipErrorInvalidValue;
         if (cfg.pre_gates == 1) {
-            if (cfg.wdtype == 1 && cfg.mdtype == 1) return step_typed<h16_t, bf16_t, 1>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cfg.lstm_rows, cfg.proj_group, cur, s, ev);
-            if (cfg.wdtype == 1 && cfg.mdtype == 0) return step_typed<h16_t, float, 1>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cfg.lstm_rows, cfg.proj_group, cur, s, ev);
+            if (cfg.wdtype == 1 && cfg.mdtype == 1) return step_typed<h16_t, bf16_t, 1>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cfg.lstm_rows, cfg.proj_group, cfg.att_lead, cfg.att_tail, cur, s, ev);
+            if (cfg.wdtype == 1 && cfg.mdtype == 0) return step_typed<h16_t, float, 1>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cfg.lstm_rows, cfg.proj_group, cfg.att_lead, cfg.att_tail, cur, s, ev);
             return hipErrorInvalidValue;
         }
         if (cfg.n_tiles > PRESUM_SMALL_TILES) return hipErrorInvalidValue;
-        if (cfg.wdtype == 0 && cfg.mdtype == 0) return step_typed<float, float, 2>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cfg.lstm_rows, cfg.proj_group, cur, s, ev);
-        if (cfg.wdtype == 1 && cfg.mdtype == 1) return step_typed<h16_t, bf16_t, 2>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cfg.lstm_rows, cfg.proj_group, cur, s, ev);
-        if (cfg.wdtype == 1 && cfg.mdtype == 0) return step_typed<h16_t, float, 2>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cfg.lstm_rows, cfg.proj_group, cur, s, ev);
+        if (cfg.wdtype == 0 && cfg.mdtype == 0) return step_typed<float, float, 2>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cfg.lstm_rows, cfg.proj_group, cfg.att_lead, cfg.att_tail, cur, s, ev);
+        if (cfg.wdtype == 1 && cfg.mdtype == 1) return step_typed<h16_t, bf16_t, 2>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cfg.lstm_rows, cfg.proj_group, cfg.att_lead, cfg.att_tail, cur, s, ev);
+        if (cfg.wdtype == 1 && cfg.mdtype == 0) return step_typed<h16_t, float, 2>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cfg.lstm_rows, cfg.proj_group, cfg.att_lead, cfg.att_tail, cur, s, ev);
         return hipErrorInvalidValue;
     }
     // without pre-sums: fp32 pools of more than four tiles (the fp32 mode is the parity vehicle)
-    if (cfg.wdtype == 0 && cfg.mdtype == 0) return step_typed<float, float, 0>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cfg.lstm_rows, cfg.proj_group, cur, s, ev);
+    if (cfg.wdtype == 0 && cfg.mdtype == 0) return step_typed<float, float, 0>(d, cfg.n_blocks, cfg.n_tiles, cfg.lsa_split, cfg.lstm_rows, cfg.proj_group, cfg.att_lead, cfg.att_tail, cur, s, ev);
     return hipErrorInvalidValue;
 }
 

@@ -71,7 +71,7 @@ namespace {
 struct Layout {
     size_t Wa, Wd, ba, bd, Wq, Wq_epi, qpart, pre_att, pre_dec, pre_dec_b, proj_part, WmemT, lsa_kfrag, lsa_wfrag, v, Wmel, bmel, Wp1, Wp2;
     size_t xatt[2], xdec[2], c_att, c_dec, m_last, w_last[2], w_acc[2], Fmem, PM, mel_ring, stop_ring;
-    size_t L, t, n_steps, done, failed, live, proj_seq, step_seq, lsa_x, hdec_x, stage;
+    size_t L, t, n_steps, done, failed, live, proj_seq, step_seq, lsa_x, hdec_x, p_x, pre_x, wg_seq, stage;
     size_t total, proj_part_bytes;
 };
 
@@ -152,6 +152,9 @@ Layout make_layout(const tts_config& c)
     l.step_seq = a.take(4);
     l.lsa_x = a.take(S * ML * 8);                        // zeroed too: no word carries a step's number yet
     l.hdec_x = a.take((pre_dec_hatt_for(c) ? S / 16 : 0) * (size_t)(HID / 32) * 64 * 4 * 8);   // likewise
+    l.p_x = a.take((pre_dec_hatt_for(c) ? S / 16 : 0) * (size_t)(PRENET / 32) * 64 * 4 * 8);
+    l.pre_x = a.take((pre_dec_hatt_for(c) ? S / 16 : 0) * (size_t)(HID / 4) * 64 * 4 * 8);
+    l.wg_seq = a.take(2 * 4);
     l.stage = a.take(ML * ENC * 4);
     l.total = a.off;
     return l;
@@ -399,6 +402,9 @@ extern "C" int tts_pool_create(const tts_config* cfg, const tts_weights* w, void
     d.step_seq = reinterpret_cast<unsigned*>(base + l.step_seq);
     d.lsa_x = reinterpret_cast<unsigned long long*>(base + l.lsa_x);
     d.hdec_x = pre_dec_hatt_for(*cfg) ? reinterpret_cast<unsigned long long*>(base + l.hdec_x) : nullptr;
+    d.p_x = pre_dec_hatt_for(*cfg) ? reinterpret_cast<unsigned long long*>(base + l.p_x) : nullptr;
+    d.pre_x = pre_dec_hatt_for(*cfg) ? reinterpret_cast<unsigned long long*>(base + l.pre_x) : nullptr;
+    d.wg_seq = reinterpret_cast<unsigned*>(base + l.wg_seq);
     // one pinned word the kernels can reach: a projection leader that gives up on its helpers says so here
     {
         hipError_t e = hipHostMalloc(reinterpret_cast<void**>(&p->h_fault), sizeof(int), hipHostMallocMapped);
@@ -551,6 +557,7 @@ static int lstm_rows_for(int n_blocks) { return n_blocks > 128 ? 4 : (n_blocks >
 
 // most steps captured into one graph
 static const int MAX_GRAPH_STEPS = 32;
+static const bool CHAIN_ATT_LSTM = true;
 // a whole chunk of at most this many steps is one graph of its own
 static const int MAX_CHUNK_GRAPH_STEPS = 64;
 
@@ -616,6 +623,19 @@ static void shape_for(const tts_pool* p, int span, StepLaunch* sl)
     sl->lstm_rows = lstm_rows_for(span);
     sl->pre_gates = !pre_gates_for(p->cfg) ? 0 : (pre_dec_for(p->cfg) ? 2 : 1);
     sl->proj_group = proj_group_for(p->cfg);
+    sl->att_lead = 1;
+    sl->att_tail = 0;
+}
+
+// Step i of `nsteps` consecutive steps of one call: in pools whose last launch can form the next step's attention LSTM
+// (d.p_x) every step but the last does, and every step but the first therefore has no attention-LSTM launch of its own.
+// Nothing can change between two steps of one call: joins, retirements and state accesses happen between calls, and the
+// first step of a call always launches its own attention LSTM.
+static void chain_steps(const tts_pool* p, StepLaunch* sl, int i, int nsteps)
+{
+    const bool chain = p->d.p_x != nullptr && CHAIN_ATT_LSTM;
+    sl->att_lead = !(chain && i > 0);
+    sl->att_tail = chain && i + 1 < nsteps;
 }
 
 // Queue `nsteps` consecutive steps for the current membership.  With graphs the
@@ -630,7 +650,10 @@ static int launch_steps(tts_pool* p, int n_active, int nsteps)
     (void)n_active;
     if (!p->cfg.use_graph) {
         shape_for(p, p->slot_span, &sl);
-        for (int i = 0; i < nsteps; ++i) HIP_TRY(launch_step(p->d, sl, p->parity ^ (i & 1), p->stream));
+        for (int i = 0; i < nsteps; ++i) {
+            chain_steps(p, &sl, i, nsteps);
+            HIP_TRY(launch_step(p->d, sl, p->parity ^ (i & 1), p->stream));
+        }
         return TTS_OK;
     }
     const int bucket = bucket_for(p->slot_span);
@@ -642,7 +665,10 @@ static int launch_steps(tts_pool* p, int n_active, int nsteps)
         hipGraphExec_t ge = nullptr;
         HIP_TRY(hipStreamBeginCapture(p->stream, hipStreamCaptureModeThreadLocal));
         hipError_t le = hipSuccess;
-        for (int i = 0; i < nsteps && le == hipSuccess; ++i) le = launch_step(p->d, sl, p->parity ^ (i & 1), p->stream);
+        for (int i = 0; i < nsteps && le == hipSuccess; ++i) {
+            chain_steps(p, &sl, i, nsteps);
+            le = launch_step(p->d, sl, p->parity ^ (i & 1), p->stream);
+        }
         hipError_t ce = hipStreamEndCapture(p->stream, &g);
         if (le != hipSuccess || ce != hipSuccess) {
             if (ce == hipSuccess && g) (void)hipGraphDestroy(g);
@@ -713,7 +739,9 @@ extern "C" int tts_pool_step_n(tts_pool* p, int n, int64_t* out_frames)
 // n un-graphed steps with an event between consecutive kernels, queued back to
 // back (one wait at the end); average device time of each kernel in
 // microseconds.  An event costs device time of its own: that cost is measured
-// with pairs of adjacent events and subtracted.
+// with pairs of adjacent events and subtracted.  The steps are launched as one
+// call of n steps launches them: the membership is uploaded once, and where a
+// step's last launch forms the next step's attention LSTM it does so here.
 extern "C" int tts_pool_kernel_times(tts_pool* p, int n, float* out_us, int cap, int* out_n_kernels)
 {
     if (!p || !out_us || n < 1 || n > 4096) return fail(TTS_E_INVAL, "bad argument");
@@ -725,14 +753,17 @@ extern "C" int tts_pool_kernel_times(tts_pool* p, int n, float* out_us, int cap,
     for (auto& e : ev)
         if (hipEventCreate(&e) != hipSuccess) { rc = fail(TTS_E_HIP, "hipEventCreate failed"); break; }
     int done = 0;
-    for (int i = 0; i < n && rc == TTS_OK; ++i) {
-        const int n_active = (int)p->book->active().size();
-        if (n_active == 0) break;
-        if ((rc = push_membership(p))) break;
-        StepLaunch sl;
-        sl.wdtype = p->cfg.weight_dtype;
-        sl.mdtype = p->cfg.memory_dtype;
+    StepLaunch sl;
+    sl.wdtype = p->cfg.weight_dtype;
+    sl.mdtype = p->cfg.memory_dtype;
+    if (rc == TTS_OK && !p->book->active().empty()) {
+        rc = push_membership(p);
         shape_for(p, p->slot_span, &sl);
+    }
+    for (int i = 0; i < n && rc == TTS_OK; ++i) {
+        // (a pool that empties on the way: the step before formed an attention LSTM in which no request took part)
+        if (p->book->active().empty()) break;
+        chain_steps(p, &sl, i, n);
         hipEvent_t* e = &ev[(size_t)i * per];
         hipError_t he = launch_step(p->d, sl, p->parity, p->stream, e);
         // an empty interval right after the step: the cost of the event itself
@@ -742,14 +773,25 @@ extern "C" int tts_pool_kernel_times(tts_pool* p, int n, float* out_us, int cap,
         p->book->step(p->parity);
         ++done;
     }
-    double acc[N_STEP_KERNELS + 1] = {0};
+    // per kernel: the steps that launched it.  The last kernel is averaged apart for the steps in which it also formed
+    // the next step's attention LSTM (all but the last, in pools that do this) and for those in which it did not.
+    const bool chained = n > 1 && p->d.p_x != nullptr && CHAIN_ATT_LSTM;
+    double acc[N_STEP_KERNELS + 1] = {0}, last_plain = 0;
+    int cnt[N_STEP_KERNELS + 1] = {0}, n_plain = 0;
     if (rc == TTS_OK && done > 0) {
         hipError_t he = hipStreamSynchronize(p->stream);
         for (int i = 0; i < done && he == hipSuccess; ++i)
             for (int k = 0; k <= N_STEP_KERNELS && he == hipSuccess; ++k) {
                 float ms = 0.f;
                 he = hipEventElapsedTime(&ms, ev[(size_t)i * per + k], ev[(size_t)i * per + k + 1]);
+                if (k == 0 && chained && i > 0) continue;                  // no attention-LSTM launch of its own
+                if (k == N_STEP_KERNELS - 1 && chained && i == n - 1) {    // the call's last step: nothing formed for a next one
+                    last_plain += ms;
+                    ++n_plain;
+                    continue;
+                }
                 acc[k] += ms;
+                ++cnt[k];
             }
         if (he != hipSuccess) rc = fail(TTS_E_HIP, "timed step: %s", hipGetErrorString(he));
     }
@@ -757,14 +799,19 @@ extern "C" int tts_pool_kernel_times(tts_pool* p, int n, float* out_us, int cap,
         if (e) (void)hipEventDestroy(e);
     if (rc) return rc;
     if (done == 0) return fail(TTS_E_INVAL, "the pool is empty");
-    const double ev_cost = acc[N_STEP_KERNELS] / done;
+    const double ev_cost = acc[N_STEP_KERNELS] / cnt[N_STEP_KERNELS];
     for (int k = 0; k < N_STEP_KERNELS; ++k) {
-        const double us = (acc[k] / done - ev_cost) * 1e3;
+        const double us = cnt[k] ? (acc[k] / cnt[k] - ev_cost) * 1e3 : 0.0;
         out_us[k] = (float)(us > 0 ? us : 0);
     }
     // a pool whose last kernel holds the decoder LSTM launches no kernel between its third and fourth event
     if (p->d.hdec_x) out_us[2] = 0.f;
     if (cap > N_STEP_KERNELS) out_us[N_STEP_KERNELS] = (float)(ev_cost * 1e3);
+    // the last kernel without the next step's attention LSTM (0: every timed step's was of one kind)
+    if (cap > N_STEP_KERNELS + 1) {
+        const double us = n_plain ? (last_plain / n_plain - ev_cost) * 1e3 : 0.0;
+        out_us[N_STEP_KERNELS + 1] = (float)(us > 0 ? us : 0);
+    }
     return TTS_OK;
 }
 

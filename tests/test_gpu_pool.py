@@ -679,3 +679,39 @@ def test_random_arrivals_and_departures(bf16, seed, weights_bf16, weights_fp32):
     for i in range(150):
         np.testing.assert_array_equal(np.concatenate(got[i]), ref[i])
     pool.close()
+
+
+@pytest.mark.parametrize("stop_threshold", [-1.0, 0.62])
+def test_steps_of_one_call_equal_one_call_per_step_to_the_state(stop_threshold):
+    """Two-byte pools of at most 64 slots form the attention LSTM of step t + 1 inside the last launch of step t when
+    both steps belong to one call; the first step of a call launches its own.  Both forms must leave the same bits:
+    frames, stop values and every piece of the carried state, also for requests that end inside a call (by their
+    frame count or by the stop threshold), whose state must stay where their last step left it."""
+    say(f"case: steps of one call vs one call per step, frames and state (stop threshold {stop_threshold})")
+    wl = synth.small_workload(20, 5, 90, 24, 24, seed=23, bf16=True)
+    w = synth.make_weights(bf16=True)
+    w["stop_b"] = w["stop_b"].copy()
+    w["stop_b"][:] = 0.2
+    n_steps = [3 + (5 * i) % 20 for i in range(20)]        # 3 .. 22 frames: most end inside the one call
+    pools, ids = [], []
+    for _ in range(2):
+        p = make_pool(wl, w, max_pool=20, max_enc_len=90, max_steps=24, chunk_frames=24, stop_threshold=stop_threshold)
+        ids.append([p.add_request(wl.encoder_outputs(i), n_steps[i]) for i in range(20)])
+        pools.append(p)
+    pools[0].step_n(24)
+    for _ in range(24):
+        pools[1].step()
+    for p in pools:
+        p.sync()
+    ended_early = 0
+    for a, b in zip(*ids):
+        fa, fb = pools[0].frames(a), pools[1].frames(b)
+        assert fa == fb and fa[1]
+        ended_early += fa[0] < 24
+        np.testing.assert_array_equal(pools[0].stop_logits(a, 0, fa[0]), pools[1].stop_logits(b, 0, fb[0]))
+        for name in ("m", "a", "w_last", "w_acc", "h_att", "c_att", "h_dec", "c_dec"):
+            np.testing.assert_array_equal(pools[0].get_state(a, name), pools[1].get_state(b, name), err_msg=name)
+        np.testing.assert_array_equal(_drain(pools[0], a), _drain(pools[1], b))
+    assert ended_early >= 15
+    for p in pools:
+        p.close()
