@@ -1703,26 +1703,37 @@ __device__ __forceinline__ void proj_tile_fused(const DevPtrs& d, const ProjHot&
     // workgroup stores nothing of this step for them.  Leader and keeper each do this for themselves.
     auto collect_frame = [&]() __attribute__((always_inline)) {
         float v[RED_IT];
-        unsigned long long w[G][RED_IT];
+        unsigned w[G][RED_IT];
+        // A word is a partial sum rounded to 20 bits of mantissa with the low four bits of the step count in the freed
+        // bits (sum_word): four bytes instead of eight.  Polls of words that another workgroup writes pass through the
+        // CU's load path at 25-30 GB/s, so a round of them takes as long as its bytes: 18 loads per thread of eight-byte
+        // words took 2.9 us.  The workers whose fragments lie in `a` wait for nobody and are done first: their words
+        // are asked for first and those of the workers that wait for h_dec last.
+        const unsigned phase = (my_seq + 1u) & 15u;
+        const unsigned* part32 = reinterpret_cast<const unsigned*>(d.proj_part);
         bool all_in = false;
         for (int spin = 0; spin < d.wait_polls && !all_in; ++spin) {
             all_in = true;
 #pragma unroll
-            for (int h = 0; h < G; ++h) {
-                const unsigned long long* theirs = d.proj_part + (size_t)(tile * G + h) * (16 * PROJ_ROWS);
+            for (int q = 0; q < G; ++q) {
+                constexpr int H_WORKERS = HID / KB / PROJ_WAVES;      // workers 0 .. H_WORKERS - 1 contract h_dec
+                const int h = (q + H_WORKERS) % G;
+                const unsigned* theirs = part32 + (size_t)(tile * G + h) * (16 * PROJ_ROWS);
 #pragma unroll
-                for (int it = 0; it < RED_IT; ++it) {
+                for (int it = 0; it < RED_IT; ++it)
                     w[h][it] = __hip_atomic_load(&theirs[tid + it * PROJ_THREADS], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    all_in = all_in && (unsigned)(w[h][it] >> 32) == my_seq + 1u;
-                }
             }
+#pragma unroll
+            for (int h = 0; h < G; ++h)
+#pragma unroll
+                for (int it = 0; it < RED_IT; ++it) all_in = all_in && (w[h][it] & 15u) == phase;
         }
         if (!all_in) *sh.ok = 0;
 #pragma unroll
         for (int it = 0; it < RED_IT; ++it) {
-            v[it] = __uint_as_float((unsigned)w[0][it]);
+            v[it] = __uint_as_float(w[0][it] & ~15u);
 #pragma unroll
-            for (int h = 1; h < G; ++h) v[it] += __uint_as_float((unsigned)w[h][it]);
+            for (int h = 1; h < G; ++h) v[it] += __uint_as_float(w[h][it] & ~15u);
             const int idx = tid + it * PROJ_THREADS;
             sh.mel[idx & 15][idx >> 4] = v[it];
         }
@@ -1788,7 +1799,7 @@ __device__ __forceinline__ void proj_tile_fused(const DevPtrs& d, const ProjHot&
         // ... reduced over the waves and handed over, each word with the step count beside it in one 8-byte store (a
         // worker whose wait for h_dec ran out hands nothing over: the waits for its sums then run out as well)
         if (*sh.ok) {
-            unsigned long long* mine = d.proj_part + (size_t)(tile * G + kp) * (16 * PROJ_ROWS);
+            unsigned* mine = reinterpret_cast<unsigned*>(d.proj_part) + (size_t)(tile * G + kp) * (16 * PROJ_ROWS);
 #pragma unroll
             for (int it = 0; it < RED_IT; ++it) {
                 const int idx = tid + it * PROJ_THREADS;
@@ -1799,7 +1810,10 @@ __device__ __forceinline__ void proj_tile_fused(const DevPtrs& d, const ProjHot&
 #pragma unroll
                     for (int wv = 0; wv < PROJ_WAVES; ++wv) v += s_part[wv][o][r];
                 }
-                __hip_atomic_store(&mine[idx], ((unsigned long long)(my_seq + 1u) << 32) | __float_as_uint(v), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                // sum_word: the magnitude rounded to the nearest multiple of 16 units in the last place, the count's
+                // low four bits in their stead (a worker that hands nothing over in a step falls one count behind what
+                // its readers expect, and stays recognisable for sixteen steps)
+                __hip_atomic_store(&mine[idx], ((__float_as_uint(v) + 8u) & ~15u) | ((my_seq + 1u) & 15u), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
         }
         if (tid == 0) hot.proj_seq[tile * FUSED_GROUP + kp] = my_seq + 1u;
@@ -1863,7 +1877,6 @@ __device__ __forceinline__ void proj_tile_fused(const DevPtrs& d, const ProjHot&
     }
     __builtin_amdgcn_sched_barrier(0);
     collect_frame();
-    if (tid == 0) hot.proj_seq[tile * FUSED_GROUP + kp] = my_seq + 1u;
 
     // hid^T = relu(W_p1 mel^T); wave w owns row tiles w and w + 8
     {
@@ -1894,13 +1907,20 @@ __device__ __forceinline__ void proj_tile_fused(const DevPtrs& d, const ProjHot&
         bool goes_on = sl >= 0 && sh.t[jl] + 1 < sh.cap[jl];
         if (d.stop_threshold >= 0.f && sigmoidf_(sh.mel[jl][N_MEL]) > d.stop_threshold) goes_on = false;
         const unsigned long long mark = (unsigned long long)((goes_on ? 0u : 0x80000000u) | tail_stamp) << 32;
+        // (both row tiles' products before the first store: the wait the compiler places in front of the second tile's
+        // weights counts every memory operation issued before it, the first tile's stores included)
+        floatx4 acc[2];
+#pragma unroll
+        for (int m = 0; m < 2; ++m) {
+            acc[m] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int f = 0; f < NK4; ++f) acc[m] = mfma_frag<XT>(a4[m][f], bh[f], acc[m]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int m = 0; m < 2; ++m) {
             const int mt = wave + m * PROJ_WAVES;
-            floatx4 acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int f = 0; f < NK4; ++f) acc = mfma_frag<XT>(a4[m][f], bh[f], acc);
-            const float p0 = fmaxf(acc[0], 0.f), p1 = fmaxf(acc[1], 0.f), p2 = fmaxf(acc[2], 0.f), p3 = fmaxf(acc[3], 0.f);
+            const float p0 = fmaxf(acc[m][0], 0.f), p1 = fmaxf(acc[m][1], 0.f), p2 = fmaxf(acc[m][2], 0.f), p3 = fmaxf(acc[m][3], 0.f);
             const unsigned lo = sl >= 0 ? pack2<XT>(p0, p1) : 0u, hi = sl >= 0 ? pack2<XT>(p2, p3) : 0u;
             if (tail_stamp != 0u) {
                 // rows 16 mt + 4 g .. + 3 of p = half of the 16-byte piece (mt % 2) * 2 + g / 2 of fragment mt / 2, column jl
@@ -1915,6 +1935,8 @@ __device__ __forceinline__ void proj_tile_fused(const DevPtrs& d, const ProjHot&
             }
         }
     }
+    // (last: a store in front of the prenet's products would be counted by the waits in front of their operands)
+    if (tid == 0) hot.proj_seq[tile * FUSED_GROUP + kp] = my_seq + 1u;
 }
 
 // ---------------------------------------------------------------------------
@@ -2005,6 +2027,8 @@ __device__ __forceinline__ void att_tail_unit(const DevPtrs& d, const ProjHot& h
         return;
     }
     const bool active = lv && !dn && goes_on;
+    float c_new[RG];
+    XT h_new[RG];
 #pragma unroll
     for (int r = 0; r < RG; ++r) {
         const floatx4 pre4 = {__uint_as_float((unsigned)wp[r][0]), __uint_as_float((unsigned)wp[r][1]), __uint_as_float((unsigned)wp[r][2]),
@@ -2016,25 +2040,31 @@ __device__ __forceinline__ void att_tail_unit(const DevPtrs& d, const ProjHot& h
         g4 += pre4;
         const float gi = sigmoidf_(g4[0]), gf = sigmoidf_(g4[1]);
         const float gg = tanhf_(g4[2]), go = sigmoidf_(g4[3]);
-        const float c = gf * c_old[r] + gi * gg;
-        const XT h = from_float<XT>(go * tanhf_(c));
-        if (active) {
-            // the next step's halves: its `cur` is this step's cur ^ 1
-            d.c_att[(size_t)sl * HID + unit[r]] = c;
-            reinterpret_cast<XT*>(d.xdec[cur ^ 1])[xoff<XT>(K_DEC / KB, sl, XD_HA + unit[r])] = h;
-            reinterpret_cast<XT*>(d.xatt[cur])[xoff<XT>(NK, sl, XA_H + unit[r])] = h;
-        }
-        s_h[r][4 * wave + (lane >> 4)][lane & 15] = active ? to_float(h) : 0.f;
+        c_new[r] = gf * c_old[r] + gi * gg;
+        h_new[r] = from_float<XT>(go * tanhf_(c_new[r]));
+        s_h[r][4 * wave + (lane >> 4)][lane & 15] = active ? to_float(h_new[r]) : 0.f;
     }
     __syncthreads();
+    // (every store after the last product: the wait the compiler places in front of a product's operands counts the
+    // stores issued before it, and an acknowledged store is half a microsecond away)
+    floatx4 part[RG];
 #pragma unroll
     for (int r = 0; r < RG; ++r) {
-        floatx4 part = {0.f, 0.f, 0.f, 0.f};
+        part[r] = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int s = 0; s < TALL_RT; ++s)
-            part = __builtin_amdgcn_mfma_f32_16x16x4f32(wq[r][s], s_h[r][4 * s + (lane >> 4)][lane & 15], part, 0, 0, 0);
-        if (active)
-            *reinterpret_cast<floatx4*>(d.qpart + ((size_t)sl * QP_TALL + rg0 + r) * ATT + 16 * wave + 4 * (lane >> 4)) = part;
+            part[r] = __builtin_amdgcn_mfma_f32_16x16x4f32(wq[r][s], s_h[r][4 * s + (lane >> 4)][lane & 15], part[r], 0, 0, 0);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    if (active) {
+#pragma unroll
+        for (int r = 0; r < RG; ++r) {
+            // the next step's halves: its `cur` is this step's cur ^ 1
+            d.c_att[(size_t)sl * HID + unit[r]] = c_new[r];
+            reinterpret_cast<XT*>(d.xdec[cur ^ 1])[xoff<XT>(K_DEC / KB, sl, XD_HA + unit[r])] = h_new[r];
+            reinterpret_cast<XT*>(d.xatt[cur])[xoff<XT>(NK, sl, XA_H + unit[r])] = h_new[r];
+            *reinterpret_cast<floatx4*>(d.qpart + ((size_t)sl * QP_TALL + rg0 + r) * ATT + 16 * wave + 4 * (lane >> 4)) = part[r];
+        }
     }
 }
 
