@@ -46,14 +46,15 @@ struct DevPtrs {
     float* pre_dec;       // same for the decoder LSTM's sums over H_dec
     float* pre_dec_b;     // same layout: the decoder LSTM's sums over H_att, formed inside the attention kernel's launch of the same step
                           // (null: the decoder LSTM contracts H_att itself)
-    unsigned long long* proj_part; // [tiles][5 (6 in the fused form)][96 * 16] (sequence number << 32 | float bits): partial sums of the projection's helper
-                          // workgroups (pools with pre-sums), written and read within one kernel
+    unsigned long long* proj_part; // [tiles][5][96 * 16] (sequence number << 32 | float bits): partial sums of the projection's helper
+                          // workgroups (pools with pre-sums), written and read within one kernel.  Fused form: [tiles][6][96 * 16]
+                          // 4-byte words in the same space (float bits, the low four mantissa bits replaced by the count's)
     unsigned* proj_seq;   // [tiles][6]: steps each of a tile's projection workgroups has taken part in (zero at creation)
     unsigned long long* lsa_x; // [slots][max_enc_len] (step number << 32 | float bits): the energies the workgroups of a request hand each other
     unsigned* step_seq;   // [1] steps taken (zero at creation; advanced by the projection kernel)
-    unsigned long long* hdec_x; // [tiles][HID / 32 fragments][64 lanes][4] (sequence number << 32 | two halves): H_dec of the step as the
-                          // projection's B operand, handed from the decoder LSTM's part of the fused last kernel to the projection's
-                          // workgroups of the same launch (null: the decoder LSTM is a kernel of its own)
+    unsigned long long* hdec_x; // [tiles][HID / 32 fragments][64 lanes][2] (four halves, bit 14 of each = a bit of the count): H_dec of the
+                          // step as the projection's B operand, handed from the decoder LSTM's part of the fused last kernel to the
+                          // projection's workgroups of the same launch (null: the decoder LSTM is a kernel of its own)
     unsigned long long* p_x;    // [tiles][PRENET / 32 fragments][4][64 lanes] (bit 63: the slot takes no further step | sequence number << 32 |
                           // two halves): the prenet output of the step as the attention LSTM's B operand, handed from a tile's leader to
                           // the workgroups that form the NEXT step's attention LSTM inside the same launch (steps that are followed

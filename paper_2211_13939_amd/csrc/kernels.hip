@@ -1288,9 +1288,12 @@ template <> __device__ __forceinline__ uint4 frag_from_f32<h16_t>(const float* p
 // gates is K = ENC: the sums over H_att and H_dec arrive as pre-sums).  Every one of the launch's 256 workgroups first
 // forms one of the 256 pieces k_lstm_rc<dec, 2> would (two row tiles x half of the pool tiles, the same sums in the same
 // order), stores H_dec where the next step reads it, and hands it to the projection's workgroups of the same launch as
-// 8-byte words: two halves beside the step's number, laid out as the projection's B operand (hdec_x).  The number is the
-// tile's leader's count of steps (the last of the tile's PROJ_GROUP_K + 1 counters), which the leader advances only after
-// all of the tile's words have been consumed.
+// 8-byte words of four halves, laid out as the projection's B operand (hdec_x); the exponent's top bit of each half, never
+// set for |h| <= 1, carries one of the low four bits of the step's number.  The number is the tile's leader's count of
+// steps (the last of the tile's PROJ_GROUP_K + 1 counters), which the leader advances only after all of the tile's
+// words have been consumed: a word of the step before carries the number before, one of sixteen steps ago cannot exist.
+// (Polls of another workgroup's words pass through a CU's load path at 25-30 GB/s: the denser the words, the shorter a
+// round of polls.)
 // A slot without a running request hands over zeros (its projection is dropped).  issue() requests, finish() consumes:
 // what a workgroup requests for its own part in between arrives behind the decoder LSTM's operands, not in front of them.
 typedef floatx4 (*DecRed)[4][64];                // [wave][sum][lane]: 32 KB
@@ -1375,13 +1378,18 @@ struct DecUnit {
             } else {
                 h.bits = 0;
             }
-            // lanes l and l + 16 hold neighbouring units of one slot: the lower of the two stores both
-            const unsigned mineb = h.bits, theirs = (unsigned)__shfl_down((int)mineb, 16, 64);
-            const int q = lane >> 4;
-            if ((q & 1) == 0) {
+            // lanes l, l + 16, l + 32, l + 48 hold the row tile's four units of one slot: the first stores all four as one
+            // 8-byte word.  |h| <= 1, so bit 14 of a half (the exponent's top bit) is free: the four of them carry the
+            // low four bits of the count.
+            const int mineb = (int)h.bits;
+            const unsigned long long u0 = (unsigned)mineb, u1 = (unsigned)__shfl(mineb, (lane & 15) + 16, 64);
+            const unsigned long long u2 = (unsigned)__shfl(mineb, (lane & 15) + 32, 64), u3 = (unsigned)__shfl(mineb, (lane & 15) + 48, 64);
+            if (lane < 16) {
                 const int er = wave % R;
-                const size_t w = ((((size_t)(sl >> 4) * (HID / 32) + rg / 4) * 64 + (rg % 4) * 16 + (lane & 15)) * 4) + er * 2 + (q >> 1);
-                __hip_atomic_store(&d.hdec_x[w], ((unsigned long long)seq << 32) | (theirs << 16) | mineb, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                const size_t w = (((size_t)(sl >> 4) * (HID / 32) + rg / 4) * 64 + (rg % 4) * 16 + lane) * 2 + er;
+                const unsigned long long mark = (unsigned long long)(seq & 1u) << 14 | (unsigned long long)(seq >> 1 & 1u) << 30 |
+                                                (unsigned long long)(seq >> 2 & 1u) << 46 | (unsigned long long)(seq >> 3 & 1u) << 62;
+                __hip_atomic_store(&d.hdec_x[w], u0 | u1 << 16 | u2 << 32 | u3 << 48 | mark, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
         }
         __syncthreads();
@@ -1650,11 +1658,10 @@ __device__ __forceinline__ void proj_tile(const DevPtrs& d, const ProjHot& hot, 
 // The fused form of a tile's workgroups (two-byte pools of at most four tiles; the launch holds the decoder LSTM too,
 // DecUnit).  Every workgroup first forms its piece of the decoder LSTM - other tiles' workgroups wait for it as well - and
 // only then requests its weights.  G workers contract one G-th of K of the projection each, as in the plain form, with
-// H_dec taken as words from hdec_x once every piece of a wave's K range is in, and hand their partial sums over as 8-byte
-// words; worker 0's start from the bias.  A further workgroup leads: it pulls nothing but the prenet's weights (with a
+// H_dec taken as words from hdec_x once every piece of a wave's K range is in, and hand their partial sums over as 4-byte
+// words (the count's low four bits in the mantissa's); worker 0's start from the bias.  A further workgroup leads: it pulls nothing but the prenet's weights (with a
 // short window of loads per wave in flight: a wave that asks for all of them at once gets less than half the rate out of
-// the CU's load path), polls the G partial sums, adds them in worker order - the plain form's order, the frame is the
-// same bits - and runs the prenet.  The last worker, whose fragments of K lie in `a` and which is therefore done early,
+// the CU's load path), polls the G partial sums, adds them in worker order - the plain form's order - and runs the prenet.  The last worker, whose fragments of K lie in `a` and which is therefore done early,
 // collects the sums as well and keeps the books meanwhile: frame and stop value into the rings, frame counters, end of a
 // request.  (All G + 1 workgroups adding the sums themselves and sharing the prenet's second layer was tried: six times
 // the polls, and a word took 3 us to be seen instead of 1.)
@@ -1719,15 +1726,24 @@ __device__ __forceinline__ void proj_tile_fused(const DevPtrs& d, const ProjHot&
                 constexpr int H_WORKERS = HID / KB / PROJ_WAVES;      // workers 0 .. H_WORKERS - 1 contract h_dec
                 const int h = (q + H_WORKERS) % G;
                 const unsigned* theirs = part32 + (size_t)(tile * G + h) * (16 * PROJ_ROWS);
+                // (a lane whose word lies in the zero rows beyond the stop row asks for the worker's first word instead: a
+                // wave of such lanes is one request, and no branch surrounds the load)
 #pragma unroll
-                for (int it = 0; it < RED_IT; ++it)
-                    w[h][it] = __hip_atomic_load(&theirs[tid + it * PROJ_THREADS], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                for (int it = 0; it < RED_IT; ++it) {
+                    const int idx = tid + it * PROJ_THREADS;
+                    w[h][it] = __hip_atomic_load(&theirs[(idx >> 4) < N_PROJ ? idx : 0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
             }
 #pragma unroll
             for (int h = 0; h < G; ++h)
 #pragma unroll
                 for (int it = 0; it < RED_IT; ++it) all_in = all_in && (w[h][it] & 15u) == phase;
         }
+#pragma unroll
+        for (int h = 0; h < G; ++h)
+#pragma unroll
+            for (int it = 0; it < RED_IT; ++it)
+                if (((tid + it * PROJ_THREADS) >> 4) >= N_PROJ) w[h][it] = 0u;
         if (!all_in) *sh.ok = 0;
 #pragma unroll
         for (int it = 0; it < RED_IT; ++it) {
@@ -1776,18 +1792,25 @@ __device__ __forceinline__ void proj_tile_fused(const DevPtrs& d, const ProjHot&
         __builtin_amdgcn_sched_barrier(0);
         // the wave's fragment of h_dec: every lane polls its four words (a bounded number of times)
         bool all_in = !from_h;                             // a wave whose fragment lies in `a` waits for nobody
-        unsigned long long w[4];
-        const unsigned long long* hx = d.hdec_x + (((size_t)tile * (HID / KB) + min(ks, HID / KB - 1)) * 64 + lane) * 4;
+        unsigned long long w[2];
+        const unsigned long long* hx = d.hdec_x + (((size_t)tile * (HID / KB) + min(ks, HID / KB - 1)) * 64 + lane) * 2;
+        constexpr unsigned long long MARK = 0x4000400040004000ull;
+        const unsigned cnt4 = (my_seq + 1u) & 15u;
+        const unsigned long long expect = (unsigned long long)(cnt4 & 1u) << 14 | (unsigned long long)(cnt4 >> 1 & 1u) << 30 |
+                                          (unsigned long long)(cnt4 >> 2 & 1u) << 46 | (unsigned long long)(cnt4 >> 3 & 1u) << 62;
         for (int spin = 0; spin < d.wait_polls && !all_in; ++spin) {
             all_in = true;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
+            for (int i = 0; i < 2; ++i) {
                 w[i] = __hip_atomic_load(&hx[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                all_in = all_in && (unsigned)(w[i] >> 32) == my_seq + 1u;
+                all_in = all_in && (w[i] & MARK) == expect;
             }
         }
         if (!all_in) *sh.ok = 0;                           // looked at after the next barrier
-        if (from_h && all_in) b = make_uint4((unsigned)w[0], (unsigned)w[1], (unsigned)w[2], (unsigned)w[3]);
+        if (from_h && all_in) {
+            const unsigned long long w0 = w[0] & ~MARK, w1 = w[1] & ~MARK;
+            b = make_uint4((unsigned)w0, (unsigned)(w0 >> 32), (unsigned)w1, (unsigned)(w1 >> 32));
+        }
         // the projection, one fragment of K per wave ...
 #pragma unroll
         for (int m = 0; m < NM; ++m) {
