@@ -681,22 +681,24 @@ def test_random_arrivals_and_departures(bf16, seed, weights_bf16, weights_fp32):
     pool.close()
 
 
-@pytest.mark.parametrize("stop_threshold", [-1.0, 0.62])
-def test_steps_of_one_call_equal_one_call_per_step_to_the_state(stop_threshold):
+@pytest.mark.parametrize("stop_threshold,n_req,max_pool", [(-1.0, 20, 20), (0.62, 20, 20), (-1.0, 90, 150), (0.62, 40, 256)])
+def test_steps_of_one_call_equal_one_call_per_step_to_the_state(stop_threshold, n_req, max_pool):
     """Two-byte pools of at most 64 slots form the attention LSTM of step t + 1 inside the last launch of step t when
     both steps belong to one call; the first step of a call launches its own.  Both forms must leave the same bits:
     frames, stop values and every piece of the carried state, also for requests that end inside a call (by their
-    frame count or by the stop threshold), whose state must stay where their last step left it."""
-    say(f"case: steps of one call vs one call per step, frames and state (stop threshold {stop_threshold})")
-    wl = synth.small_workload(20, 5, 90, 24, 24, seed=23, bf16=True)
+    frame count or by the stop threshold), whose state must stay where their last step left it.  (Capacities 150
+    and 256: larger pools, whose steps are the same four launches either way, at six and three tiles.)"""
+    say(f"case: steps of one call vs one call per step, frames and state (stop threshold {stop_threshold}, "
+        f"{n_req} requests, capacity {max_pool})")
+    wl = synth.small_workload(n_req, 5, 90, 24, 24, seed=23, bf16=True)
     w = synth.make_weights(bf16=True)
     w["stop_b"] = w["stop_b"].copy()
     w["stop_b"][:] = 0.2
-    n_steps = [3 + (5 * i) % 20 for i in range(20)]        # 3 .. 22 frames: most end inside the one call
+    n_steps = [3 + (5 * i) % 20 for i in range(n_req)]     # 3 .. 22 frames: most end inside the one call
     pools, ids = [], []
     for _ in range(2):
-        p = make_pool(wl, w, max_pool=20, max_enc_len=90, max_steps=24, chunk_frames=24, stop_threshold=stop_threshold)
-        ids.append([p.add_request(wl.encoder_outputs(i), n_steps[i]) for i in range(20)])
+        p = make_pool(wl, w, max_pool=max_pool, max_enc_len=90, max_steps=24, chunk_frames=24, stop_threshold=stop_threshold)
+        ids.append([p.add_request(wl.encoder_outputs(i), n_steps[i]) for i in range(n_req)])
         pools.append(p)
     pools[0].step_n(24)
     for _ in range(24):
@@ -712,6 +714,6 @@ def test_steps_of_one_call_equal_one_call_per_step_to_the_state(stop_threshold):
         for name in ("m", "a", "w_last", "w_acc", "h_att", "c_att", "h_dec", "c_dec"):
             np.testing.assert_array_equal(pools[0].get_state(a, name), pools[1].get_state(b, name), err_msg=name)
         np.testing.assert_array_equal(_drain(pools[0], a), _drain(pools[1], b))
-    assert ended_early >= 15
+    assert ended_early >= 3 * n_req // 4
     for p in pools:
         p.close()
