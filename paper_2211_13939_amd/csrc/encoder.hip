@@ -2,7 +2,7 @@
 //   k_enc_embed   E_all = sum of the four embedding rows of every token, stored as the first convolution's input
 //   (conv5_kernels.h: three kernel-5 convolutions with ReLU, "same" padding inside each request)
 //   k_enc_xproj   W_ih x + b for every token and both directions: the part of the LSTM that has no recurrence
-//   k_enc_lstm    the recurrence, one workgroup per direction and group of 16 requests
+//   k_enc_lstm    the recurrence, one workgroup per direction and group of 16 requests (k_enc_lstm_dot: a call of one request)
 //
 // The recurrence is a chain of L dependent steps of a 1024 x 256 matrix-vector product: latency, not bandwidth.
 // In bf16 the matrix of one direction (512 KB) is made resident in ONE compute unit -- six of its eight k fragments
@@ -206,6 +206,104 @@ __global__ __launch_bounds__(256) void k_enc_lstm(const uint4* __restrict__ Whh0
     }
 }
 
+// The recurrence for a call of ONE request (the usual case at join time) with two-byte weights, on the vector units.
+// 512 threads: a pair of threads is one hidden unit, the even one holding the rows of its input and forget gates, the odd
+// one those of the cell and output gates (512 halves a thread: 192 registers' worth and 64 LDS words, the same split of k
+// as above, straight from the fragment-ordered matrix; at two waves per SIMD a lane has 256 registers, all of them
+// operands of vector instructions).  A thread forms its two gate sums as chains of two-element dot products
+// (v_dot2_f32_f16, fp32 accumulation) over h, which every thread reads from LDS as a broadcast; the pair swaps sums and
+// both update the cell.  With one request in flight an MFMA's sixteen columns are 1/16 full - 32 cycles of the matrix
+// pipe for 512 useful products - while a dot-product instruction does 128 useful products in 4 cycles, and the gate sums
+// never pass through LDS.  (With two requests the compiler reads all of h ahead and spills the weights: those calls stay
+// on the MFMA kernel above.)
+// grid = (2 directions), 512 threads.  LDS: [16][512] uint4 of weights, h as halves [2 buffers][256].
+constexpr int ENC_DOT_THREADS = 2 * ENC_HID;
+constexpr int ENC_DOT_W_VECS = 16 * ENC_DOT_THREADS;
+constexpr int ENC_DOT_LDS_BYTES = ENC_DOT_W_VECS * 16 + 2 * ENC_HID * 2;
+
+__device__ __forceinline__ float dot8(uint4 w, uint4 h, float acc)
+{
+    acc = __builtin_amdgcn_fdot2(__builtin_bit_cast(halfx2, w.x), __builtin_bit_cast(halfx2, h.x), acc, false);
+    acc = __builtin_amdgcn_fdot2(__builtin_bit_cast(halfx2, w.y), __builtin_bit_cast(halfx2, h.y), acc, false);
+    acc = __builtin_amdgcn_fdot2(__builtin_bit_cast(halfx2, w.z), __builtin_bit_cast(halfx2, h.z), acc, false);
+    return __builtin_amdgcn_fdot2(__builtin_bit_cast(halfx2, w.w), __builtin_bit_cast(halfx2, h.w), acc, false);
+}
+
+__global__ __launch_bounds__(ENC_DOT_THREADS) void k_enc_lstm_dot(const uint4* __restrict__ Whh0, const uint4* __restrict__ Whh1,
+                                                                  const float* __restrict__ xproj, PnWindows w, int max_tokens, float* __restrict__ out)
+{
+    typedef h16_t XT;
+    constexpr int KB = Frag<XT>::KB, NK = ENC_HID / KB, KREG = 6, KLDS = NK - KREG;
+    static_assert(KB == 32 && NK == 8 && 2 * KLDS * 4 == 16, "k = 32 kf + 8 q + e: a lane's 16 bytes are 8 consecutive k");
+    extern __shared__ uint4 lds_enc[];
+    uint4* wl = lds_enc;                                                        // [(gate * KLDS + kl) * 4 + q][thread]
+    uint16_t* hs = reinterpret_cast<uint16_t*>(lds_enc + ENC_DOT_W_VECS);       // [buffer][unit]
+    const int tid = threadIdx.x, dir = blockIdx.x, unit = tid >> 1, half = tid & 1;
+    const int len = w.len[0], col0 = w.col0[0];
+    const uint4* Whh = dir ? Whh1 : Whh0;
+    // gate row 4 u + g lies in row tile u / 4 at row 4 (u % 4) + g; its k = 32 kf + 8 q .. + 7 in lane row + 16 q
+    const int rt = unit >> 2, r0 = 4 * (unit & 3) + 2 * half;
+    uint4 wr[2][KREG][4];
+#pragma unroll
+    for (int g = 0; g < 2; ++g)
+#pragma unroll
+        for (int kf = 0; kf < KREG; ++kf)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) wr[g][kf][q] = Whh[xfrag(NK, rt, kf, r0 + g + 16 * q)];
+#pragma unroll
+    for (int g = 0; g < 2; ++g)
+#pragma unroll
+        for (int kl = 0; kl < KLDS; ++kl)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) wl[((g * KLDS + kl) * 4 + q) * ENC_DOT_THREADS + tid] = Whh[xfrag(NK, rt, KREG + kl, r0 + g + 16 * q)];
+    hs[tid] = 0;                                                                // h = 0, both buffers
+
+    auto token = [&](int s) { return dir ? len - 1 - s : s; };
+    const float* xp = xproj + ((size_t)dir * max_tokens + col0) * ENC_GATES + 4 * unit;
+    floatx4 xnext = *reinterpret_cast<const floatx4*>(xp + (size_t)min(max(token(0), 0), len - 1) * ENC_GATES);
+    float c = 0.f;
+    __syncthreads();
+
+    for (int s = 0; s < len; ++s) {
+        const uint4* hr = reinterpret_cast<const uint4*>(hs + (s & 1) * ENC_HID);               // 32 pieces of 8 halves
+        uint16_t* hx = hs + ((s + 1) & 1) * ENC_HID;
+        asm volatile("" ::: "memory");                    // (the LDS-resident weights are read again every step, not kept in registers)
+        // two chains per gate sum (even and odd pieces of k), added at the end
+        float acc[2][2] = {{0.f, 0.f}, {0.f, 0.f}};
+#pragma unroll
+        for (int kf = 0; kf < NK; ++kf) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const uint4 hv = hr[kf * 4 + q];
+#pragma unroll
+                for (int g = 0; g < 2; ++g) {
+                    const uint4 wv = kf < KREG ? wr[g][kf < KREG ? kf : 0][q]
+                                               : wl[((g * KLDS + (kf >= KREG ? kf - KREG : 0)) * 4 + q) * ENC_DOT_THREADS + tid];
+                    acc[g][q & 1] = dot8(wv, hv, acc[g][q & 1]);
+                }
+            }
+            // a fragment of k at a time: few LDS words live at once
+            asm volatile("" ::: "memory");
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        // the pair swaps its sums: both threads hold all four gates
+        const float m0 = acc[0][0] + acc[0][1], m1 = acc[1][0] + acc[1][1];
+        const float o0 = __shfl_xor(m0, 1, 64), o1 = __shfl_xor(m1, 1, 64);
+        const int t = token(s);
+        const floatx4 gs = (half ? floatx4{o0, o1, m0, m1} : floatx4{m0, m1, o0, o1}) + xnext;
+        const float gi = sigmoidf_(gs[0]), gf = sigmoidf_(gs[1]), gg = tanhf_(gs[2]), go = sigmoidf_(gs[3]);
+        c = gf * c + gi * gg;
+        const float h = go * tanhf_(c);
+        if (half == 0) {
+            hx[unit] = from_float<XT>(h).bits;
+            out[(size_t)(col0 + t) * (2 * ENC_HID) + dir * ENC_HID + unit] = h;
+        }
+        const int tn = min(max(token(s + 1), 0), len - 1);             // next step's input projection, clamped to the request
+        xnext = *reinterpret_cast<const floatx4*>(xp + (size_t)tn * ENC_GATES);
+        __syncthreads();                                   // h is complete (the other buffer is free for the next step)
+    }
+}
+
 template <typename XT> struct EncLstmWideGeom {
     static constexpr int KB = Frag<XT>::KB, EPL = Frag<XT>::EPL;
     static constexpr int NK = ENC_HID / KB;                       // k fragments of W_hh
@@ -343,6 +441,20 @@ hipError_t run_typed(const EncoderPtrs& d, const PnWindows& w, int n_col, float*
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     // a call with a few requests (the usual case at join time) takes the kernel that compacts the cell update
+    if constexpr (sizeof(XT) == 2) {
+        if (w.n == 1) {
+            // one request, two-byte weights: the recurrence on the vector units
+            static bool dot_attr_set = false;
+            if (!dot_attr_set) {
+                e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_enc_lstm_dot), hipFuncAttributeMaxDynamicSharedMemorySize, ENC_DOT_LDS_BYTES);
+                if (e != hipSuccess) return e;
+                dot_attr_set = true;
+            }
+            hipLaunchKernelGGL(k_enc_lstm_dot, dim3(2), dim3(ENC_DOT_THREADS), ENC_DOT_LDS_BYTES, s, (const uint4*)d.w_hh[0], (const uint4*)d.w_hh[1], d.xproj, w,
+                               d.max_tokens, out);
+            return hipGetLastError();
+        }
+    }
     const bool compact = w.n <= ENC_COMPACT_UP_TO;
     const int lds = compact ? EncLstmGeom<XT>::LDS_BYTES : EncLstmWideGeom<XT>::LDS_BYTES;
     auto kern = compact ? k_enc_lstm<XT> : k_enc_lstm_wide<XT>;

@@ -30,6 +30,24 @@ def test_ragged_batch_matches_oracle(bf16):
     enc.close()
 
 
+@pytest.mark.parametrize("n_tokens", [1, 2, 33, 300])
+def test_a_call_of_one_request_matches_oracle_bf16(n_tokens):
+    """The usual call at join time: one request.  In the two-byte mode its recurrence runs on the vector units (a kernel
+    of its own); one token, two tokens and a request that feeds h back 300 times."""
+    from oracle import oracle as orc
+    w = synth.make_encoder_weights(bf16=True)
+    ids = synth.encoder_ids(n_tokens, 500 + n_tokens)
+    enc = binding.Encoder(binding.make_encoder_config(max_tokens=320, max_len=300, bf16=True), w)
+    say(f"case encoder: one request of {n_tokens} tokens, bf16")
+    got = enc.run([ids])[0]
+    want = orc.encoder(orc.EncoderWeights(w), ids)
+    assert got.shape == want.shape
+    err = float(np.abs(got - want).max())
+    say(f"  max abs err {err:.3e}")
+    assert err <= TOL_BF16
+    enc.close()
+
+
 def test_more_requests_than_mfma_columns_and_long_request():
     """20 requests (two groups of 16 columns in the recurrence) and one of 300 tokens, bf16."""
     from oracle import oracle as orc
@@ -50,14 +68,17 @@ def test_more_requests_than_mfma_columns_and_long_request():
 
 
 def test_result_does_not_depend_on_batch_composition():
-    """Bitwise, among calls that take the same recurrence kernel (calls of one or two requests take one that compacts
-    the cell update, larger calls the other; the two differ in summation order only)."""
+    """Bitwise, among calls that take the same recurrence kernel (a call of one request forms its gate sums on the vector
+    units, a call of two takes the kernel that compacts the cell update, larger calls the third; they differ in summation
+    order only)."""
     w = synth.make_encoder_weights(bf16=True)
     ids = [synth.encoder_ids(L, 300 + i) for i, L in enumerate((40, 9, 23, 61, 5, 33))]
     enc = binding.Encoder(binding.make_encoder_config(max_tokens=512, max_len=100, bf16=True), w)
     alone = enc.run([ids[2]])[0]
-    np.testing.assert_array_equal(alone, enc.run([ids[3], ids[2]])[1])
-    np.testing.assert_array_equal(alone, enc.run([ids[2], ids[0]])[0])
+    np.testing.assert_array_equal(alone, enc.run([ids[2]])[0])
+    pair = enc.run([ids[3], ids[2]])[1]
+    np.testing.assert_array_equal(pair, enc.run([ids[2], ids[0]])[0])
+    assert np.abs(alone - pair).max() <= 1e-3            # (the two kernels agree to rounding)
     four = enc.run([ids[0], ids[1], ids[2], ids[3]])[2]
     np.testing.assert_array_equal(four, enc.run(ids)[2])
     np.testing.assert_array_equal(four, enc.run([ids[2], ids[5], ids[4]])[0])
