@@ -1774,6 +1774,15 @@ __device__ __forceinline__ void proj_tile_fused(const DevPtrs& d, const ProjHot&
         float bias_r[RED_IT];
 #pragma unroll
         for (int it = 0; it < RED_IT; ++it) bias_r[it] = d.bmel[min((tid + it * PROJ_THREADS) >> 4, N_PROJ - 1)];
+        // The wave's fragments of the projection's weights are requested here, behind the piece's operands (they arrive in
+        // the order of the requests, so the piece is not held up) and before the piece is formed: requested after it, these
+        // 48 KB per workgroup were what a worker waited for, half a microsecond after its words of h_dec were in.
+        // (all six row tiles' fragments, the zero rows of the last included: a branch around a load would make the
+        // compiler wait for every load in flight where it rejoins)
+        const uint4* W = reinterpret_cast<const uint4*>(hot.Wmel) + lane;
+        uint4 a[NM];
+#pragma unroll
+        for (int m = 0; m < NM; ++m) a[m] = W[((size_t)m * NK + ks) * 64];
         __builtin_amdgcn_sched_barrier(0);
         dec.finish(d, hot, reinterpret_cast<DecRed>(sh.big));
         if (tid < 16) {
@@ -1783,13 +1792,6 @@ __device__ __forceinline__ void proj_tile_fused(const DevPtrs& d, const ProjHot&
             sh.cap[tid] = on ? my_cap : 0;
         }
         __syncthreads();                                   // (a piece without pool tiles has no barrier of its own)
-        // (all six row tiles' fragments, the zero rows of the last included: a branch around a load would make the
-        // compiler wait for every load in flight where it rejoins)
-        const uint4* W = reinterpret_cast<const uint4*>(hot.Wmel) + lane;
-        uint4 a[NM];
-#pragma unroll
-        for (int m = 0; m < NM; ++m) a[m] = W[((size_t)m * NK + ks) * 64];
-        __builtin_amdgcn_sched_barrier(0);
         // the wave's fragment of h_dec: every lane polls its four words (a bounded number of times)
         bool all_in = !from_h;                             // a wave whose fragment lies in `a` waits for nobody
         unsigned long long w[2];
