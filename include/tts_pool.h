@@ -146,7 +146,11 @@ int tts_pool_add_requests(tts_pool *pool, int n, const float *const *enc_out, co
 int tts_pool_step(tts_pool *pool, int *out_n_active);
 
 /* `n` consecutive steps (no joins in between); *out_frames (may be NULL)
- * receives the total number of frames produced. */
+ * receives the total number of frames produced.  Same frames and state, bit
+ * for bit, as n calls of tts_pool_step; the steps of one call are queued more
+ * tightly (one graph launch for up to a chunk of steps; in pools of at most 64
+ * slots with two-byte weights and memory a step that follows another step of
+ * the same call is two kernel launches instead of three). */
 int tts_pool_step_n(tts_pool *pool, int n, int64_t *out_frames);
 
 /*
