@@ -62,7 +62,7 @@ def algorithmic_bytes(P, sum_L, s_w, s_m, pre_gates=None):
     and H_dec (decoder LSTM) move in the projection kernel's launch, W_q in the attention LSTM's; in two-byte pools of that
     size the decoder LSTM has no kernel of its own (its columns for H_att and H_dec move in the attention kernel's launch,
     the rest and its state in the last kernel's, which holds it; "k_lstm_dec" is then 0); 1 (larger
-    bf16 pools): the attention LSTM's only; 0 (larger fp32 pools): none.  Carried state is charged once, to the kernel
+    bf16 pools): the attention LSTM's only, and the whole decoder LSTM moves in the last kernel's launch, which holds it; 0 (larger fp32 pools): none.  Carried state is charged once, to the kernel
     that produces it (activations a later kernel reads again, gate pre-sums and query partials are traffic of the
     implementation, not of the algorithm)."""
     if pre_gates is None:
@@ -72,6 +72,8 @@ def algorithmic_bytes(P, sum_L, s_w, s_m, pre_gates=None):
     # two-byte pools with both pre-sums: the decoder LSTM is part of the last kernel's launch, and its columns for H_att
     # and H_dec move in the attention kernel's
     fused = pre_gates == 2 and s_w == 2 and s_m == 2
+    # two-byte weights in larger pools: the decoder LSTM (all of its K) is the first part of the last kernel's launch
+    dec_in_last = fused or (pre_gates == 1 and s_w == 2)
     k_dec_hatt = 1024 if fused else 0
     w_q = 128 * 1024 * s_w
     lsa_w = (32 * 2 * 31 + 128 * 32 + 128) * s_w
@@ -84,9 +86,9 @@ def algorithmic_bytes(P, sum_L, s_w, s_m, pre_gates=None):
         "k_lsa": lsa_w + (0 if pre_gates else w_q) + sum_L * (640 * s_m + 16) + P * 2 * 512 * 4
                  + 4096 * (k_dec_hatt + (k_dec_late if fused else 0)) * s_w,
         # h_dec and c_dec read and written
-        "k_lstm_dec": 0 if fused else dec_own,
+        "k_lstm_dec": 0 if dec_in_last else dec_own,
         # m_last read and written, the frame written to the ring
-        "k_proj": proj_w + 4096 * (k_att_late + (0 if fused else k_dec_late)) * s_w + P * (2 * 80 * 4 + 320) + (dec_own if fused else 0),
+        "k_proj": proj_w + 4096 * (k_att_late + (0 if fused else k_dec_late)) * s_w + P * (2 * 80 * 4 + 320) + (dec_own if dec_in_last else 0),
     }
 
 
@@ -346,6 +348,10 @@ def config_bench(binding, synth, torch, name, use_graph):
         if "k_lstm_dec" in kernel_us and kernel_us["k_lstm_dec"] > 0:
             g = 2.0 * 4096 * 2560 * P       # the decoder LSTM's gate GEMM (pools of more than 64 slots contract all of its K there)
             row["k_lstm_dec_frac_of_bf16_mfma_peak"] = g / (kernel_us["k_lstm_dec"] * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS
+        elif P > PRESUM_BOTH_MAX_POOL and kernel_us.get("k_proj", 0) > 0:
+            # the decoder LSTM's gate GEMM and the attention LSTM's late columns both run in the last kernel's launch
+            g = 2.0 * 4096 * (2560 + 1536) * P + 2.0 * 81 * 1536 * P
+            row["k_proj_frac_of_bf16_mfma_peak"] = g / (kernel_us["k_proj"] * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS
     if note:
         row["note"] = note
     return row

@@ -234,9 +234,9 @@ int tts_pool_elapsed_ms(tts_pool *pool, float *out_ms);
  * HIP event between consecutive kernels, and return the average device time of
  * each kernel of the step in microseconds in out_us (room for `cap` values;
  * *out_n_kernels receives how many there are: attention LSTM, attention,
- * decoder LSTM, projection + prenet; two-byte pools of at most 64 slots have
- * no decoder-LSTM kernel - it is part of the last kernel's launch - and report
- * 0 for it).  The n steps are launched as one call of n steps launches them:
+ * decoder LSTM, projection + prenet; pools with two-byte weights have no
+ * decoder-LSTM kernel - it is part of the last kernel's launch (above 64
+ * slots: from 17 slots spanned) - and report 0 for it).  The n steps are launched as one call of n steps launches them:
  * in those pools the last kernel of every step but the call's last also forms
  * the next step's attention LSTM, so only the first step has an
  * attention-LSTM kernel (that one launch is the figure reported) and the

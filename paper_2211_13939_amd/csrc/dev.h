@@ -54,7 +54,8 @@ struct DevPtrs {
     unsigned* step_seq;   // [1] steps taken (zero at creation; advanced by the projection kernel)
     unsigned long long* hdec_x; // [tiles][HID / 32 fragments][64 lanes][2] (four halves, bit 14 of each = a bit of the count): H_dec of the
                           // step as the projection's B operand, handed from the decoder LSTM's part of the fused last kernel to the
-                          // projection's workgroups of the same launch (null: the decoder LSTM is a kernel of its own)
+                          // projection's workgroups of the same launch (two-byte pools of at most 64 slots; pools of more than 64
+                          // slots with two-byte weights from 17 slots spanned; null: the decoder LSTM is always a kernel of its own)
     unsigned long long* p_x;    // [tiles][PRENET / 32 fragments][4][64 lanes] (bit 63: the slot takes no further step | sequence number << 32 |
                           // two halves): the prenet output of the step as the attention LSTM's B operand, handed from a tile's leader to
                           // the workgroups that form the NEXT step's attention LSTM inside the same launch (steps that are followed

@@ -11,7 +11,10 @@
 // there (K = 512 of 2560, the rest arrives as gate pre-sums) is formed by the
 // workgroups of k_proj's launch before they turn to their own parts.  And two
 // for a step that follows another step of the same call: its attention LSTM
-// (K = 256 left) was formed at the end of that step's k_proj launch.
+// (K = 256 left) was formed at the end of that step's k_proj launch.  Pools of
+// more than 64 slots with two-byte weights run three as well from 17 slots
+// spanned: the decoder LSTM (all of its K, k_lstm_stream's tiles) is the first
+// part of k_proj's launch there.
 //
 // Activations (the vectors multiplied by weight matrices) live in HBM in MFMA
 // B-operand order, tiled by pool slot: 16 slots form a tile, and a tile's
@@ -241,11 +244,17 @@ __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm_rc(
 // per round of pool tiles; here the loads leave at the rate the products consume them.  Every (row tile, pool tile) sum
 // is formed as in k_lstm (wave w chains w + 8 f in increasing f; bias, then the eight waves' sums in wave order), so the
 // gates are the same bits.  The R x C sums are reduced through LDS eight at a time, one cell update per wave.
+// hx (may be null): H_dec is also handed, as 8-byte words of four halves whose exponent top bits carry the low four bits
+// of the tile's step count (proj_seq[tile * pg] + 1, as DecUnit does), to the projection's workgroups of the same launch:
+// the form in which this tile is the first thing every workgroup of the last kernel's launch does (pools of more than 64
+// slots with two-byte weights).  A slot without a running request hands over zeros.
+typedef floatx4 (*StreamRed)[LSTM_WAVES][64];      // [wave][sum of the phase][lane]: 64 KB
 template <typename XT, int K, int R, int C>
-__global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm_stream(
+__device__ __forceinline__ void lstm_stream_unit(
     const uint4* __restrict__ Wfrag, const uint4* __restrict__ X, const float* __restrict__ bias, float* __restrict__ c_state,
     const int* __restrict__ live, const int* __restrict__ done,
-    XT* __restrict__ hout0, int nk0, int off0, XT* __restrict__ hout1, int nk1, int off1, int n_tiles)
+    XT* __restrict__ hout0, int nk0, int off0, XT* __restrict__ hout1, int nk1, int off1, int n_tiles, int blk, StreamRed red,
+    unsigned long long* __restrict__ hx, const unsigned* __restrict__ proj_seq, int pg)
 {
     constexpr int NW = LSTM_WAVES;
     constexpr int NK = K / Frag<XT>::KB;
@@ -256,7 +265,7 @@ __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm_stream(
     static_assert(NK % NW == 0 && (R * C) % NW == 0 && WIN <= NF, "shape");
 
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int rg = blockIdx.x % NRG, cg = blockIdx.x / NRG;
+    const int rg = blk % NRG, cg = blk / NRG;
     const int per = (n_tiles + R - 1) / R;         // <= C (checked by the launcher)
     const int c0 = min(cg * per, n_tiles), c1 = min(c0 + per, n_tiles);
     if (c0 >= c1) return;                          // the whole workgroup: no pool tile in this group
@@ -280,6 +289,7 @@ __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm_stream(
     int sl[PH], unit[PH], lv[PH], dn[PH];
     float c_old[PH];
     floatx4 bias4[PH];
+    unsigned seq[PH];
     bool mine[PH];
 #pragma unroll
     for (int p = 0; p < PH; ++p) {
@@ -291,6 +301,7 @@ __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm_stream(
         dn[p] = done[sl[p]];
         c_old[p] = c_state[(size_t)sl[p] * HID + unit[p]];
         bias4[p] = *reinterpret_cast<const floatx4*>(bias + unit[p] * 4);
+        seq[p] = hx ? proj_seq[tb[et] * pg] + 1u : 0u;
     }
 
     floatx4 acc[R][C];
@@ -308,26 +319,54 @@ __global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm_stream(
             for (int t = 0; t < C; ++t) acc[r][t] = mfma_frag<XT>(a[f % WIN][r], b[f % WIN][t], acc[r][t]);
     }
 
-    __shared__ floatx4 red[NW][NW][64];            // [wave][sum of the phase][lane]: 64 KB
 #pragma unroll
     for (int p = 0; p < PH; ++p) {
         if (p) __syncthreads();
 #pragma unroll
         for (int j = 0; j < NW; ++j) red[wave][j][lane] = acc[(NW * p + j) / C][(NW * p + j) % C];
         __syncthreads();
-        if (mine[p] && lv[p] && !dn[p]) {
+        if (mine[p]) {                              // (the same for the whole wave)
             floatx4 g = bias4[p];
 #pragma unroll
             for (int w = 0; w < NW; ++w) g += red[w][wave][lane];
             const float gi = sigmoidf_(g[0]), gf = sigmoidf_(g[1]);
             const float gg = tanhf_(g[2]), go = sigmoidf_(g[3]);
             const float c = gf * c_old[p] + gi * gg;
-            c_state[(size_t)sl[p] * HID + unit[p]] = c;
-            const XT h = from_float<XT>(go * tanhf_(c));
-            hout0[xoff<XT>(nk0, sl[p], off0 + unit[p])] = h;
-            hout1[xoff<XT>(nk1, sl[p], off1 + unit[p])] = h;
+            const bool on = lv[p] && !dn[p];
+            XT h = from_float<XT>(go * tanhf_(c));
+            if (on) {
+                c_state[(size_t)sl[p] * HID + unit[p]] = c;
+                hout0[xoff<XT>(nk0, sl[p], off0 + unit[p])] = h;
+                hout1[xoff<XT>(nk1, sl[p], off1 + unit[p])] = h;
+            }
+            if constexpr (sizeof(XT) == 2) {
+                if (hx) {
+                    // lanes l, l + 16, l + 32, l + 48 hold the row tile's four units of one slot: the first stores all four
+                    const int mineb = on ? (int)h.bits : 0;
+                    const unsigned long long u0 = (unsigned)mineb, u1 = (unsigned)__shfl(mineb, (lane & 15) + 16, 64);
+                    const unsigned long long u2 = (unsigned)__shfl(mineb, (lane & 15) + 32, 64), u3 = (unsigned)__shfl(mineb, (lane & 15) + 48, 64);
+                    if (lane < 16) {
+                        const int rt = unit[p] >> 2;                       // row tile: two of them are a 16-byte piece, eight a fragment
+                        const size_t w = (((size_t)(sl[p] >> 4) * (HID / 32) + rt / 8) * 64 + (rt / 2 % 4) * 16 + lane) * 2 + (rt & 1);
+                        const unsigned sq = seq[p];
+                        const unsigned long long mark = (unsigned long long)(sq & 1u) << 14 | (unsigned long long)(sq >> 1 & 1u) << 30 |
+                                                        (unsigned long long)(sq >> 2 & 1u) << 46 | (unsigned long long)(sq >> 3 & 1u) << 62;
+                        __hip_atomic_store(&hx[w], u0 | u1 << 16 | u2 << 32 | u3 << 48 | mark, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    }
+                }
+            }
         }
     }
+}
+
+template <typename XT, int K, int R, int C>
+__global__ __launch_bounds__(LSTM_WAVES * 64) void k_lstm_stream(
+    const uint4* __restrict__ Wfrag, const uint4* __restrict__ X, const float* __restrict__ bias, float* __restrict__ c_state,
+    const int* __restrict__ live, const int* __restrict__ done,
+    XT* __restrict__ hout0, int nk0, int off0, XT* __restrict__ hout1, int nk1, int off1, int n_tiles)
+{
+    __shared__ floatx4 red[LSTM_WAVES][LSTM_WAVES][64];
+    lstm_stream_unit<XT, K, R, C>(Wfrag, X, bias, c_state, live, done, hout0, nk0, off0, hout1, nk1, off1, n_tiles, blockIdx.x, red, nullptr, nullptr, 0);
 }
 
 // ---------------------------------------------------------------------------
@@ -1405,7 +1444,7 @@ struct ProjShared {
 
 // One workgroup's part of a tile: workgroup `kp` of G contracts fragments [kp, kp + 1) * NK / G of K; kp = 0 leads.
 template <typename XT, int G, bool LEADER>
-__device__ __forceinline__ void proj_tile(const DevPtrs& d, const ProjHot& hot, int cur, int tile, int kp, const ProjShared& sh)
+__device__ __forceinline__ void proj_tile(const DevPtrs& d, const ProjHot& hot, int cur, int tile, int kp, const ProjShared& sh, bool hand = false)
 {
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int jl = lane & 15, g = lane >> 4;
@@ -1437,6 +1476,7 @@ __device__ __forceinline__ void proj_tile(const DevPtrs& d, const ProjHot& hot, 
 #pragma unroll
     for (int f = 0; f < NKW; ++f) {
         const int ks = ks0 + f;
+        // (hand: h_dec is formed inside this launch and arrives as words, below; the load is of the step before's and dropped)
         b[f] = ks < HID / KB ? xnew[xfrag(NKD, tile, XD_HD / KB + ks, lane)]
                              : xcur[xfrag(NKD, tile, XD_A / KB + ks - HID / KB, lane)];
     }
@@ -1491,6 +1531,38 @@ __device__ __forceinline__ void proj_tile(const DevPtrs& d, const ProjHot& hot, 
     // time between the MFMAs, each a full round trip
     __builtin_amdgcn_sched_barrier(0);
 
+    if constexpr (sizeof(XT) == 2) {
+        if (hand) {
+            // the wave's fragments of h_dec from the words the decoder LSTM's part of this launch hands over: every lane
+            // polls its two words per fragment (a bounded number of times); a fragment that lies in `a` waits for nobody
+            constexpr unsigned long long MARK = 0x4000400040004000ull;
+            const unsigned cnt4 = (my_seq + 1u) & 15u;
+            const unsigned long long expect = (unsigned long long)(cnt4 & 1u) << 14 | (unsigned long long)(cnt4 >> 1 & 1u) << 30 |
+                                              (unsigned long long)(cnt4 >> 2 & 1u) << 46 | (unsigned long long)(cnt4 >> 3 & 1u) << 62;
+            unsigned long long w[NKW][2];
+            bool all_in = false;
+            for (int spin = 0; spin < d.wait_polls && !all_in; ++spin) {
+                all_in = true;
+#pragma unroll
+                for (int f = 0; f < NKW; ++f) {
+                    const unsigned long long* hx = d.hdec_x + (((size_t)tile * (HID / KB) + min(ks0 + f, HID / KB - 1)) * 64 + lane) * 2;
+#pragma unroll
+                    for (int i = 0; i < 2; ++i) {
+                        w[f][i] = __hip_atomic_load(&hx[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        all_in = all_in && (ks0 + f >= HID / KB || (w[f][i] & MARK) == expect);
+                    }
+                }
+            }
+            if (!all_in) *sh.ok = 0;                       // looked at after the next barrier
+#pragma unroll
+            for (int f = 0; f < NKW; ++f)
+                if (ks0 + f < HID / KB) {
+                    const unsigned long long w0 = w[f][0] & ~MARK, w1 = w[f][1] & ~MARK;
+                    b[f] = all_in ? make_uint4((unsigned)w0, (unsigned)(w0 >> 32), (unsigned)w1, (unsigned)(w1 >> 32)) : make_uint4(0, 0, 0, 0);
+                }
+        }
+    }
+
     // ---- phase 1: projection of [h_dec; a], K split over the waves
 #pragma unroll
     for (int m0 = 0; m0 < NM; m0 += MH) {
@@ -1512,7 +1584,6 @@ __device__ __forceinline__ void proj_tile(const DevPtrs& d, const ProjHot& hot, 
             sh.t[tid] = on ? my_t : 0;
             sh.cap[tid] = on ? my_cap : 0;
         }
-        if (tid == 0) *sh.ok = 1;
         // requested now that the projection fragments have left the registers
         if constexpr (!PRENET_FIRST) load_prenet_weights();
     }
@@ -1534,11 +1605,14 @@ __device__ __forceinline__ void proj_tile(const DevPtrs& d, const ProjHot& hot, 
     if constexpr (!LEADER) {
         // ... a helper hands its sums over, each word with the sequence number beside it in one 8-byte store: the
         // leader knows a word is this step's from the number it carries, no flag and no fence are needed
+        // (a helper whose wait for h_dec ran out hands nothing over: the leader's wait for its sums then runs out as well)
         unsigned long long* mine = d.proj_part + (size_t)(tile * (G - 1) + kp - 1) * (16 * PROJ_ROWS);
+        if (*sh.ok) {
 #pragma unroll
-        for (int it = 0; it < RED_IT; ++it)
-            __hip_atomic_store(&mine[tid + it * PROJ_THREADS], ((unsigned long long)(my_seq + 1u) << 32) | __float_as_uint(v[it]),
-                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            for (int it = 0; it < RED_IT; ++it)
+                __hip_atomic_store(&mine[tid + it * PROJ_THREADS], ((unsigned long long)(my_seq + 1u) << 32) | __float_as_uint(v[it]),
+                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
         if (tid == 0) hot.proj_seq[tile * G + kp] = my_seq + 1u;
         return;
     } else {
@@ -2097,15 +2171,34 @@ __device__ __forceinline__ void att_tail_unit(const DevPtrs& d, const ProjHot& h
 template <typename XT, bool PRE, int G, bool FUSE = false>
 __global__ __launch_bounds__(PROJ_THREADS) void k_proj(const uint4* Wa_first, const uint4* Wd_first, const void* xatt_nxt_first, const void* xdec_nxt_first,
                                                       const void* xdec_cur_first, const void* Wmel_first, const int* live_first, unsigned* proj_seq_first,
-                                                      DevPtrs d, int cur, int n_tiles, int tail)
+                                                      DevPtrs d, int cur, int n_tiles, int tail, int dec_rows)
 {
     const ProjHot hot = {Wa_first, Wd_first, xatt_nxt_first, xdec_nxt_first, xdec_cur_first, Wmel_first, live_first, proj_seq_first};
-    __shared__ __attribute__((aligned(16))) float s_big[PROJ_WAVES * PROJ_ROWS * 16];
+    constexpr int BIG_FLOATS = PROJ_WAVES * PROJ_ROWS * 16 > LSTM_WAVES * LSTM_WAVES * 64 * 4 ? PROJ_WAVES * PROJ_ROWS * 16 : LSTM_WAVES * LSTM_WAVES * 64 * 4;
+    __shared__ __attribute__((aligned(16))) float s_big[BIG_FLOATS];   // (the decoder LSTM's reduction buffer is the larger use: 64 KB)
     // row strides of 100 and 260 floats (an odd number of 16-byte pieces): the 16 columns of a
     // fragment read then fall into 16 different bank groups instead of one
     __shared__ __attribute__((aligned(16))) float s_mel[16][PROJ_MEL_LD];
     __shared__ int s_slot[16], s_t[16], s_cap[16], s_ok;
     const ProjShared sh = {s_big, s_mel, s_slot, s_t, s_cap, &s_ok};
+    if (threadIdx.x == 0) s_ok = 1;
+
+    // dec_rows != 0 (pools of more than 64 slots with two-byte weights, from 17 slots spanned): the decoder LSTM is the first
+    // thing the launch's 256 workgroups do, each its k_lstm_stream tile, and the projection's workgroups take H_dec from the
+    // words those tiles hand over (d.hdec_x) instead of a kernel boundary: a boundary costs the gap, the next kernel's
+    // start-up and its first cold round trip, the hand-over one store-to-poll hop.
+    if constexpr (PRE && !FUSE && sizeof(XT) == 2) {
+        constexpr int KB = Frag<XT>::KB;
+        XT* xdec_nxt = reinterpret_cast<XT*>(const_cast<void*>(xdec_nxt_first));
+        const uint4* xdec_in = reinterpret_cast<const uint4*>(xdec_cur_first);
+        if (dec_rows == 4)
+            lstm_stream_unit<XT, K_DEC, 4, 4>(Wd_first, xdec_in, d.bd, d.c_dec, live_first, d.done, xdec_nxt, K_DEC / KB, XD_HD, xdec_nxt, K_DEC / KB, XD_HD,
+                                              n_tiles, blockIdx.x, reinterpret_cast<StreamRed>(s_big), d.hdec_x, proj_seq_first, G);
+        else if (dec_rows == 2)
+            lstm_stream_unit<XT, K_DEC, 2, 4>(Wd_first, xdec_in, d.bd, d.c_dec, live_first, d.done, xdec_nxt, K_DEC / KB, XD_HD, xdec_nxt, K_DEC / KB, XD_HD,
+                                              n_tiles, blockIdx.x, reinterpret_cast<StreamRed>(s_big), d.hdec_x, proj_seq_first, G);
+        if (dec_rows) __syncthreads();
+    }
 
     // tail: the launch also forms the next step's attention LSTM.  The words handed over for it carry a stamp: the number
     // of launches of this kernel so far, kept as a pair of counters.  A launch reads the one of its parity and workgroup 0
@@ -2178,8 +2271,8 @@ __global__ __launch_bounds__(PROJ_THREADS) void k_proj(const uint4* Wa_first, co
             return;
         }
         if (i >= n_tiles * G) return;
-        if (i % G == 0) proj_tile<XT, G, true>(d, hot, cur, i / G, 0, sh);
-        else proj_tile<XT, G, false>(d, hot, cur, i / G, i % G, sh);
+        if (i % G == 0) proj_tile<XT, G, true>(d, hot, cur, i / G, 0, sh, dec_rows != 0);
+        else proj_tile<XT, G, false>(d, hot, cur, i / G, i % G, sh, dec_rows != 0);
     } else {
         // without pre-sums: the same workgroups per tile, wherever they land (n_tiles * G <= 96 workgroups)
         const int i = blockIdx.x;
@@ -2500,7 +2593,7 @@ static hipError_t step_typed(const DevPtrs& d, int n_req, int n_tiles, int lsa_s
     const int n_pad = (n_req + 7) / 8 * 8;      // slots are dealt to the XCDs in eights
 #define LSA_ARGS d.L, d.live, d.done, d.step_seq, d.qpart, d.w_last[cur], d.w_acc[cur], d.PM, d, cur, n_req
     // two-byte pools with both pre-sums: the decoder LSTM's sums over H_att ride in this launch
-    if (CO != (d.pre_dec_b != nullptr) || CO != (d.hdec_x != nullptr)) return hipErrorInvalidValue;
+    if (CO != (d.pre_dec_b != nullptr) || (CO && !d.hdec_x)) return hipErrorInvalidValue;
     const int n_co = CO ? DEC_HATT_WGS * (n_tiles > 1 ? 2 : 1) : 0;
     if (lsa_split == 4) hipLaunchKernelGGL((k_lsa<XT, MT, 4, PRE, CO>), dim3(n_pad * 4 + n_co), dim3(LSA_THREADS), 0, s, LSA_ARGS);
     else if (CO) return hipErrorInvalidValue;     // such pools span at most 64 slots: four workgroups per slot
@@ -2512,9 +2605,14 @@ static hipError_t step_typed(const DevPtrs& d, int n_req, int n_tiles, int lsa_s
     const uint4* xdec_in = reinterpret_cast<const uint4*>(d.xdec[cur]);
     const floatx4* pre_dec = reinterpret_cast<const floatx4*>(d.pre_dec);
     const floatx4* pre_dec_b = reinterpret_cast<const floatx4*>(d.pre_dec_b);
+    // pools of more than 64 slots with two-byte weights: the decoder LSTM's stream tiles are the first part of the last launch
+    const int dec_rows = (PM == 1 && HAS_WIDE && d.hdec_x && (rows == 4 || rows == 2)) ? rows : 0;
+    if (dec_rows == 2 && n_tiles > 8) return hipErrorInvalidValue;          // two groups of at most four pool tiles
     if constexpr (CO) {
         // the decoder LSTM is part of the last kernel's launch (below)
         if (proj_group != 6) return hipErrorInvalidValue;
+    } else if (dec_rows) {
+        // (below)
     } else if (rows == 4) {
         if constexpr (HAS_WIDE && !PRE_DEC)
             hipLaunchKernelGGL((k_lstm_stream<XT, K_DEC, 4, 4>), lg, lb, 0, s, d.Wd, xdec_in, d.bd, d.c_dec, d.live, d.done,
@@ -2533,7 +2631,7 @@ static hipError_t step_typed(const DevPtrs& d, int n_req, int n_tiles, int lsa_s
     mark(3);
     // with pre-sums the projection's launch fills the chip: XCD 0 runs the projection, the rest form the pre-sums
     const dim3 pg(PRE ? 256 : n_tiles * proj_group), pb(PROJ_THREADS);
-#define PROJ_ARGS d.Wa, d.Wd, (const void*)d.xatt[cur ^ 1], (const void*)d.xdec[cur ^ 1], (const void*)d.xdec[cur], d.Wmel, (const int*)d.live, d.proj_seq, d, cur, n_tiles, att_tail
+#define PROJ_ARGS d.Wa, d.Wd, (const void*)d.xatt[cur ^ 1], (const void*)d.xdec[cur ^ 1], (const void*)d.xdec[cur], d.Wmel, (const int*)d.live, d.proj_seq, d, cur, n_tiles, att_tail, dec_rows
     if (proj_group == 6) hipLaunchKernelGGL((k_proj<XT, PRE, 6, CO>), pg, pb, 0, s, PROJ_ARGS);
     else if (proj_group == 3) hipLaunchKernelGGL((k_proj<XT, PRE, 3>), pg, pb, 0, s, PROJ_ARGS);
     else if (proj_group == 2) hipLaunchKernelGGL((k_proj<XT, PRE, 2>), pg, pb, 0, s, PROJ_ARGS);

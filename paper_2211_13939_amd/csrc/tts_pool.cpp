@@ -92,6 +92,9 @@ bool pre_dec_for(const tts_config& c) { return pre_gates_for(c) && (c.max_pool +
 // and its sums over H_att formed beside the attention kernel, in the same launch: that kernel is a chain of waits that
 // leaves a CU's load path idle, and two of its workgroups fit a CU only with two-byte operands and memory
 bool pre_dec_hatt_for(const tts_config& c) { return pre_dec_for(c) && c.weight_dtype == TTS_DTYPE_BF16 && c.memory_dtype == TTS_DTYPE_BF16; }
+// pools whose last kernel's launch holds the decoder LSTM and hands H_dec to the projection as words: those, and pools of
+// more than 64 slots with two-byte weights
+bool hdec_words_for(const tts_config& c) { return pre_dec_hatt_for(c) || (pre_gates_for(c) && !pre_dec_for(c) && c.weight_dtype == TTS_DTYPE_BF16); }
 // workgroups per pool tile in the projection kernel: with pre-sums they must fit XCD 0 (32 CUs)
 int proj_group_for(const tts_config& c)
 {
@@ -151,7 +154,7 @@ Layout make_layout(const tts_config& c)
     l.proj_seq = a.take((size_t)MAX_TILES * PROJ_GROUP * 4);     // zeroed at creation with the counters above
     l.step_seq = a.take(4);
     l.lsa_x = a.take(S * ML * 8);                        // zeroed too: no word carries a step's number yet
-    l.hdec_x = a.take((pre_dec_hatt_for(c) ? S / 16 : 0) * (size_t)(HID / 32) * 64 * 4 * 8);   // likewise
+    l.hdec_x = a.take((hdec_words_for(c) ? S / 16 : 0) * (size_t)(HID / 32) * 64 * 4 * 8);   // likewise
     l.p_x = a.take((pre_dec_hatt_for(c) ? S / 16 : 0) * (size_t)(PRENET / 32) * 64 * 4 * 8);
     l.pre_x = a.take((pre_dec_hatt_for(c) ? S / 16 : 0) * (size_t)(HID / 4) * 64 * 4 * 8);
     l.wg_seq = a.take(2 * 4);
@@ -401,7 +404,7 @@ extern "C" int tts_pool_create(const tts_config* cfg, const tts_weights* w, void
     d.proj_seq = reinterpret_cast<unsigned*>(base + l.proj_seq);
     d.step_seq = reinterpret_cast<unsigned*>(base + l.step_seq);
     d.lsa_x = reinterpret_cast<unsigned long long*>(base + l.lsa_x);
-    d.hdec_x = pre_dec_hatt_for(*cfg) ? reinterpret_cast<unsigned long long*>(base + l.hdec_x) : nullptr;
+    d.hdec_x = hdec_words_for(*cfg) ? reinterpret_cast<unsigned long long*>(base + l.hdec_x) : nullptr;
     d.p_x = pre_dec_hatt_for(*cfg) ? reinterpret_cast<unsigned long long*>(base + l.p_x) : nullptr;
     d.pre_x = pre_dec_hatt_for(*cfg) ? reinterpret_cast<unsigned long long*>(base + l.pre_x) : nullptr;
     d.wg_seq = reinterpret_cast<unsigned*>(base + l.wg_seq);
@@ -805,7 +808,8 @@ extern "C" int tts_pool_kernel_times(tts_pool* p, int n, float* out_us, int cap,
         out_us[k] = (float)(us > 0 ? us : 0);
     }
     // a pool whose last kernel holds the decoder LSTM launches no kernel between its third and fourth event
-    if (p->d.hdec_x) out_us[2] = 0.f;
+    // (pools of more than 64 slots: while they span more than 16 slots)
+    if (p->d.hdec_x && (p->d.pre_dec_b || lstm_rows_for(p->slot_span) > 1)) out_us[2] = 0.f;
     if (cap > N_STEP_KERNELS) out_us[N_STEP_KERNELS] = (float)(ev_cost * 1e3);
     // the last kernel without the next step's attention LSTM (0: every timed step's was of one kind)
     if (cap > N_STEP_KERNELS + 1) {

@@ -717,3 +717,47 @@ def test_steps_of_one_call_equal_one_call_per_step_to_the_state(stop_threshold, 
     assert ended_early >= 3 * n_req // 4
     for p in pools:
         p.close()
+
+
+def test_wait_bound_zero_in_a_pool_above_64_slots(weights_bf16):
+    """Pools of more than 64 slots with two-byte weights form the decoder LSTM inside the last kernel's launch once
+    they span more than 16 slots, and the projection's workgroups wait (a bounded number of polls) for the words it
+    hands them.  With the bound at zero, forced from the host, every such wait gives up at once and every kernel still
+    runs through: the requests are reported lost with the frames they had, and the same pool then decodes new requests
+    to the frames a pool of the same capacity yields with the default bound."""
+    from paper_2211_13939_amd import binding
+    from paper_2211_13939_amd.binding import TtsError
+    say("case: wait bound 0 in a capacity-100 pool of 20 requests (two tiles), then the same pool again")
+    wl = synth.small_workload(20, 5, 90, 12, 12, seed=31, bf16=True)
+
+    def decode(pool):
+        ids = [pool.add_request(wl.encoder_outputs(i), 12) for i in range(20)]
+        pool.step_n(12)
+        pool.sync()
+        out = [_drain(pool, rid) for rid in ids]
+        for rid in ids:
+            pool.retire(rid)
+        return out
+
+    ref_pool = make_pool(wl, weights_bf16, max_pool=100, max_enc_len=90, max_steps=12, chunk_frames=12)
+    want = decode(ref_pool)
+    ref_pool.close()
+    pool = make_pool(wl, weights_bf16, max_pool=100, max_enc_len=90, max_steps=12, chunk_frames=12)
+    ids = [pool.add_request(wl.encoder_outputs(i), 12) for i in range(20)]
+    pool.step_n(3)
+    pool.sync()
+    pool.set_wait_polls(0)
+    pool.step_n(2)                   # returns: nothing hangs
+    with pytest.raises(TtsError) as info:
+        pool.sync()
+    assert info.value.code == binding.TTS_E_LOST
+    pool.sync()                      # said once
+    for k, rid in enumerate(ids):
+        assert pool.lost(rid) and pool.frames(rid) == (3, True)
+        np.testing.assert_array_equal(_drain(pool, rid), want[k][:3])
+        pool.retire(rid)
+    pool.set_wait_polls(1 << 18)
+    got = decode(pool)
+    for a, b in zip(got, want):
+        np.testing.assert_array_equal(a, b)
+    pool.close()
