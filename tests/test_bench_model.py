@@ -34,6 +34,18 @@ def test_the_per_kernel_split_adds_up_to_the_step():
             assert sum(parts.values()) == bench.step_bytes(P, sum_L, s, s), (P, sum_L, s, pre)
 
 
+def test_the_decoder_lstm_is_charged_to_the_launch_that_holds_it():
+    """Two-byte pools have no decoder-LSTM kernel: its bytes move in the last kernel's launch (and, in pools of at most
+    64 slots, the columns for H_att and H_dec beside the attention); fp32 pools keep the kernel."""
+    small = bench.algorithmic_bytes(64, 9405, 2, 2)
+    large = bench.algorithmic_bytes(256, 58719, 2, 2)
+    fp32 = bench.algorithmic_bytes(16, 950, 4, 4)
+    assert small["k_lstm_dec"] == 0 and large["k_lstm_dec"] == 0 and fp32["k_lstm_dec"] > 0
+    w_dec = 4096 * 2560 * 2
+    assert large["k_proj"] > w_dec                                    # all of the decoder LSTM's weights
+    assert small["k_proj"] < w_dec and small["k_lsa"] > 4096 * 2048 * 2   # K = 512 of them there, K = 2048 beside the attention
+
+
 def test_job_bytes_integrate_the_membership_trace():
     """Request i is in the pool during steps 0 .. n_i - 1: the job's bytes are the per-step bytes summed over that trace."""
     wl = synth.small_workload(5, 10, 40, 3, 9, seed=5, bf16=True)

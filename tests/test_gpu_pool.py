@@ -761,3 +761,27 @@ def test_wait_bound_zero_in_a_pool_above_64_slots(weights_bf16):
     for a, b in zip(got, want):
         np.testing.assert_array_equal(a, b)
     pool.close()
+
+
+@pytest.mark.parametrize("max_pool,n_req", [(16, 10), (200, 120)])
+def test_kernel_times_follow_the_form_of_a_call(max_pool, n_req, weights_bf16):
+    """tts_pool_kernel_times launches its steps as one call launches them and reports per kernel: a pool of at most 64
+    slots has an attention-LSTM launch only in the call's first step and a last kernel that differs in the call's last
+    step; neither that pool nor one of more than 64 slots (two-byte weights) has a decoder-LSTM kernel.  The timed steps
+    are real steps: the frames equal those of a pool stepped without timing."""
+    say(f"case: kernel times, capacity {max_pool}, {n_req} requests")
+    wl = synth.small_workload(n_req, 5, 90, 12, 12, seed=41, bf16=True)
+    a = make_pool(wl, weights_bf16, max_pool=max_pool, max_enc_len=90, max_steps=12, chunk_frames=12)
+    b = make_pool(wl, weights_bf16, max_pool=max_pool, max_enc_len=90, max_steps=12, chunk_frames=12)
+    ia = [a.add_request(wl.encoder_outputs(i), 12) for i in range(n_req)]
+    ib = [b.add_request(wl.encoder_outputs(i), 12) for i in range(n_req)]
+    a.step_n(2)
+    us = a.kernel_times_us(8)
+    a.step_n(2)
+    b.step_n(12)
+    assert us["k_lstm_att"] > 0 and us["k_lsa"] > 0 and us["k_proj"] > 0 and us["k_lstm_dec"] == 0
+    assert ("k_proj_last_step" in us) == (max_pool <= 64)
+    for x, y in zip(ia, ib):
+        np.testing.assert_array_equal(_drain(a, x), _drain(b, y))
+    a.close()
+    b.close()
