@@ -785,3 +785,33 @@ def test_kernel_times_follow_the_form_of_a_call(max_pool, n_req, weights_bf16):
         np.testing.assert_array_equal(_drain(a, x), _drain(b, y))
     a.close()
     b.close()
+
+
+def test_steps_of_a_pool_above_64_slots_beside_other_work_on_the_gpu(weights_bf16):
+    """As test_steps_beside_other_work_on_the_gpu, for a pool whose last launch holds the decoder LSTM and whose
+    projection workgroups wait for its words: with another stream keeping the CUs busy the frames must not change
+    and no wait may run out."""
+    import torch
+    say("case: capacity-100 pool of 40 requests while a second stream runs large matrix products")
+    wl = synth.small_workload(40, 5, 90, 24, 24, seed=43, bf16=True)
+
+    def decode(busy):
+        pool = make_pool(wl, weights_bf16, max_pool=100, max_enc_len=90, max_steps=24, chunk_frames=24)
+        rids = [pool.add_request(wl.encoder_outputs(i), 24) for i in range(40)]
+        side = torch.cuda.Stream(device=pool.device)
+        if busy:
+            a = torch.randn(4096, 4096, device=pool.device)
+            with torch.cuda.stream(side):
+                for _ in range(40):
+                    a = (a @ a) * 1e-4
+        for _ in range(6):
+            pool.step_n(4)
+        pool.sync()                      # raises if a wait ran out
+        side.synchronize()
+        out = [_drain(pool, rid) for rid in rids]
+        pool.close()
+        return out
+
+    quiet, busy = decode(False), decode(True)
+    for a, b in zip(quiet, busy):
+        np.testing.assert_array_equal(a, b)
