@@ -2,7 +2,8 @@
 //   k_enc_embed   E_all = sum of the four embedding rows of every token, stored as the first convolution's input
 //   (conv5_kernels.h: three kernel-5 convolutions with ReLU, "same" padding inside each request)
 //   k_enc_xproj   W_ih x + b for every token and both directions: the part of the LSTM that has no recurrence
-//   k_enc_lstm    the recurrence, one workgroup per direction and group of 16 requests (k_enc_lstm_dot: a call of one request)
+//   k_enc_lstm    the recurrence, one workgroup per direction and group of 16 requests (fp32 weights);
+//                 k_enc_lstm_dot: two-byte weights, one workgroup per direction and request
 //
 // The recurrence is a chain of L dependent steps of a 1024 x 256 matrix-vector product: latency, not bandwidth.
 // In bf16 the matrix of one direction (512 KB) is made resident in ONE compute unit -- six of its eight k fragments
@@ -206,7 +207,11 @@ __global__ __launch_bounds__(256) void k_enc_lstm(const uint4* __restrict__ Whh0
     }
 }
 
-// The recurrence for a call of ONE request (the usual case at join time) with two-byte weights, on the vector units.
+// The recurrence with two-byte weights, on the vector units: one workgroup per direction and REQUEST (a call has at most
+// ENC_MAX_BATCH = 256 requests, so at most two workgroups per CU's worth of the chip, and the usual call at join time
+// has one).  A request's steps are a chain, and a chain is as fast alone on a CU as it gets: sixteen requests side by
+// side as the columns of one workgroup's MFMAs take 6 us per step, sixteen workgroups 1.9 us.  Every workgroup reads
+// the direction's 512 KB of W_hh once, from L2 after the first.  A request's result does not depend on its companions.
 // 512 threads: a pair of threads is one hidden unit, the even one holding the rows of its input and forget gates, the odd
 // one those of the cell and output gates (512 halves a thread: 192 registers' worth and 64 LDS words, the same split of k
 // as above, straight from the fragment-ordered matrix; at two waves per SIMD a lane has 256 registers, all of them
@@ -214,9 +219,8 @@ __global__ __launch_bounds__(256) void k_enc_lstm(const uint4* __restrict__ Whh0
 // (v_dot2_f32_f16, fp32 accumulation) over h, which every thread reads from LDS as a broadcast; the pair swaps sums and
 // both update the cell.  With one request in flight an MFMA's sixteen columns are 1/16 full - 32 cycles of the matrix
 // pipe for 512 useful products - while a dot-product instruction does 128 useful products in 4 cycles, and the gate sums
-// never pass through LDS.  (With two requests the compiler reads all of h ahead and spills the weights: those calls stay
-// on the MFMA kernel above.)
-// grid = (2 directions), 512 threads.  LDS: [16][512] uint4 of weights, h as halves [2 buffers][256].
+// never pass through LDS.
+// grid = (2 directions, requests), 512 threads.  LDS: [16][512] uint4 of weights, h as halves [2 buffers][256].
 constexpr int ENC_DOT_THREADS = 2 * ENC_HID;
 constexpr int ENC_DOT_W_VECS = 16 * ENC_DOT_THREADS;
 constexpr int ENC_DOT_LDS_BYTES = ENC_DOT_W_VECS * 16 + 2 * ENC_HID * 2;
@@ -238,8 +242,8 @@ __global__ __launch_bounds__(ENC_DOT_THREADS) void k_enc_lstm_dot(const uint4* _
     extern __shared__ uint4 lds_enc[];
     uint4* wl = lds_enc;                                                        // [(gate * KLDS + kl) * 4 + q][thread]
     uint16_t* hs = reinterpret_cast<uint16_t*>(lds_enc + ENC_DOT_W_VECS);       // [buffer][unit]
-    const int tid = threadIdx.x, dir = blockIdx.x, unit = tid >> 1, half = tid & 1;
-    const int len = w.len[0], col0 = w.col0[0];
+    const int tid = threadIdx.x, dir = blockIdx.x, req = blockIdx.y, unit = tid >> 1, half = tid & 1;
+    const int len = w.len[req], col0 = w.col0[req];
     const uint4* Whh = dir ? Whh1 : Whh0;
     // gate row 4 u + g lies in row tile u / 4 at row 4 (u % 4) + g; its k = 32 kf + 8 q .. + 7 in lane row + 16 q
     const int rt = unit >> 2, r0 = 4 * (unit & 3) + 2 * half;
@@ -440,32 +444,30 @@ hipError_t run_typed(const EncoderPtrs& d, const PnWindows& w, int n_col, float*
                        d.b[0], d.b[1], (const uint4*)x1, n_col, d.max_tokens, d.xproj);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
-    // a call with a few requests (the usual case at join time) takes the kernel that compacts the cell update
     if constexpr (sizeof(XT) == 2) {
-        if (w.n == 1) {
-            // one request, two-byte weights: the recurrence on the vector units
-            static bool dot_attr_set = false;
-            if (!dot_attr_set) {
-                e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_enc_lstm_dot), hipFuncAttributeMaxDynamicSharedMemorySize, ENC_DOT_LDS_BYTES);
-                if (e != hipSuccess) return e;
-                dot_attr_set = true;
-            }
-            hipLaunchKernelGGL(k_enc_lstm_dot, dim3(2), dim3(ENC_DOT_THREADS), ENC_DOT_LDS_BYTES, s, (const uint4*)d.w_hh[0], (const uint4*)d.w_hh[1], d.xproj, w,
-                               d.max_tokens, out);
-            return hipGetLastError();
+        // two-byte weights: the recurrence on the vector units, a workgroup per direction and request
+        static bool dot_attr_set = false;
+        if (!dot_attr_set) {
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_enc_lstm_dot), hipFuncAttributeMaxDynamicSharedMemorySize, ENC_DOT_LDS_BYTES);
+            if (e != hipSuccess) return e;
+            dot_attr_set = true;
         }
+        hipLaunchKernelGGL(k_enc_lstm_dot, dim3(2, w.n), dim3(ENC_DOT_THREADS), ENC_DOT_LDS_BYTES, s, (const uint4*)d.w_hh[0], (const uint4*)d.w_hh[1], d.xproj, w,
+                           d.max_tokens, out);
+    } else {
+        // fp32 weights: a call with a few requests takes the kernel that compacts the cell update
+        const bool compact = w.n <= ENC_COMPACT_UP_TO;
+        const int lds = compact ? EncLstmGeom<XT>::LDS_BYTES : EncLstmWideGeom<XT>::LDS_BYTES;
+        auto kern = compact ? k_enc_lstm<XT> : k_enc_lstm_wide<XT>;
+        static bool attr_set[2] = {false, false};   // dynamic LDS above 64 KB has to be allowed once per kernel
+        if (!attr_set[compact]) {
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+            if (e != hipSuccess) return e;
+            attr_set[compact] = true;
+        }
+        hipLaunchKernelGGL(kern, dim3(2, (w.n + 15) / 16), dim3(256), lds, s, (const uint4*)d.w_hh[0], (const uint4*)d.w_hh[1], d.xproj, w,
+                           d.max_tokens, out);
     }
-    const bool compact = w.n <= ENC_COMPACT_UP_TO;
-    const int lds = compact ? EncLstmGeom<XT>::LDS_BYTES : EncLstmWideGeom<XT>::LDS_BYTES;
-    auto kern = compact ? k_enc_lstm<XT> : k_enc_lstm_wide<XT>;
-    static bool attr_set[2] = {false, false};   // dynamic LDS above 64 KB has to be allowed once per kernel
-    if (!attr_set[compact]) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-        if (e != hipSuccess) return e;
-        attr_set[compact] = true;
-    }
-    hipLaunchKernelGGL(kern, dim3(2, (w.n + 15) / 16), dim3(256), lds, s, (const uint4*)d.w_hh[0], (const uint4*)d.w_hh[1], d.xproj, w,
-                       d.max_tokens, out);
     return hipGetLastError();
 }
 

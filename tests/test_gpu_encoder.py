@@ -32,8 +32,8 @@ def test_ragged_batch_matches_oracle(bf16):
 
 @pytest.mark.parametrize("n_tokens", [1, 2, 33, 300])
 def test_a_call_of_one_request_matches_oracle_bf16(n_tokens):
-    """The usual call at join time: one request.  In the two-byte mode its recurrence runs on the vector units (a kernel
-    of its own); one token, two tokens and a request that feeds h back 300 times."""
+    """The usual call at join time: one request (in the two-byte mode the recurrence runs on the vector units, a kernel of
+    its own): one token, two tokens and a request that feeds h back 300 times."""
     from oracle import oracle as orc
     w = synth.make_encoder_weights(bf16=True)
     ids = synth.encoder_ids(n_tokens, 500 + n_tokens)
@@ -49,7 +49,7 @@ def test_a_call_of_one_request_matches_oracle_bf16(n_tokens):
 
 
 def test_more_requests_than_mfma_columns_and_long_request():
-    """20 requests (two groups of 16 columns in the recurrence) and one of 300 tokens, bf16."""
+    """20 requests (more than the 16 columns of a column tile) and one of 300 tokens, bf16."""
     from oracle import oracle as orc
     w = synth.make_encoder_weights(bf16=True)
     W = orc.EncoderWeights(w)
@@ -67,22 +67,28 @@ def test_more_requests_than_mfma_columns_and_long_request():
     enc.close()
 
 
-def test_result_does_not_depend_on_batch_composition():
-    """Bitwise, among calls that take the same recurrence kernel (a call of one request forms its gate sums on the vector
-    units, a call of two takes the kernel that compacts the cell update, larger calls the third; they differ in summation
-    order only)."""
-    w = synth.make_encoder_weights(bf16=True)
+@pytest.mark.parametrize("bf16", [True, False])
+def test_result_does_not_depend_on_batch_composition(bf16):
+    """Bitwise.  In the two-byte mode every request has workgroups of its own in the recurrence, so a request's F_enc is
+    the same whatever the call holds beside it.  With fp32 weights it holds among calls that take the same recurrence
+    kernel (calls of up to two requests compact the cell update, larger calls do not; the two differ in summation order
+    only)."""
+    w = synth.make_encoder_weights(bf16=bf16)
     ids = [synth.encoder_ids(L, 300 + i) for i, L in enumerate((40, 9, 23, 61, 5, 33))]
-    enc = binding.Encoder(binding.make_encoder_config(max_tokens=512, max_len=100, bf16=True), w)
+    enc = binding.Encoder(binding.make_encoder_config(max_tokens=512, max_len=100, bf16=bf16), w)
+    say(f"case encoder batch composition, {'bf16' if bf16 else 'fp32'}")
     alone = enc.run([ids[2]])[0]
     np.testing.assert_array_equal(alone, enc.run([ids[2]])[0])
     pair = enc.run([ids[3], ids[2]])[1]
     np.testing.assert_array_equal(pair, enc.run([ids[2], ids[0]])[0])
-    assert np.abs(alone - pair).max() <= 1e-3            # (the two kernels agree to rounding)
+    np.testing.assert_array_equal(alone, pair)
     four = enc.run([ids[0], ids[1], ids[2], ids[3]])[2]
     np.testing.assert_array_equal(four, enc.run(ids)[2])
     np.testing.assert_array_equal(four, enc.run([ids[2], ids[5], ids[4]])[0])
-    assert np.abs(four - alone).max() <= 1e-2
+    if bf16:
+        np.testing.assert_array_equal(four, alone)
+    else:
+        assert np.abs(four - alone).max() <= 1e-5       # (the two kernels agree to rounding)
     enc.close()
 
 
