@@ -212,12 +212,13 @@ __global__ __launch_bounds__(256) void k_enc_lstm(const uint4* __restrict__ Whh0
 // has one).  A request's steps are a chain, and a chain is as fast alone on a CU as it gets: sixteen requests side by
 // side as the columns of one workgroup's MFMAs take 6 us per step, sixteen workgroups 1.9 us.  Every workgroup reads
 // the direction's 512 KB of W_hh once, from L2 after the first.  A request's result does not depend on its companions.
-// 512 threads: a pair of threads is one hidden unit, the even one holding the rows of its input and forget gates, the odd
-// one those of the cell and output gates (512 halves a thread: 192 registers' worth and 64 LDS words, the same split of k
-// as above, straight from the fragment-ordered matrix; at two waves per SIMD a lane has 256 registers, all of them
-// operands of vector instructions).  A thread forms its two gate sums as chains of two-element dot products
-// (v_dot2_f32_f16, fp32 accumulation) over h, which every thread reads from LDS as a broadcast; the pair swaps sums and
-// both update the cell.  With one request in flight an MFMA's sixteen columns are 1/16 full - 32 cycles of the matrix
+// 512 threads: a pair of threads is one hidden unit, each holding one half of k of the unit's four gate rows - the even
+// one the even pieces of eight consecutive k, the odd one the odd pieces - (512 halves a thread: 192 registers' worth and
+// 64 LDS words, the same split of k as above, straight from the fragment-ordered matrix; at two waves per SIMD a lane has
+// 256 registers, all of them operands of vector instructions).  A thread forms its half of the four gate sums as chains
+// of two-element dot products (v_dot2_f32_f16, fp32 accumulation) over its half of h, which it reads from LDS as a
+// broadcast (a wave reads two neighbouring pieces at a time: no bank is asked twice); the pair adds its halves and both
+// update the cell.  With one request in flight an MFMA's sixteen columns are 1/16 full - 32 cycles of the matrix
 // pipe for 512 useful products - while a dot-product instruction does 128 useful products in 4 cycles, and the gate sums
 // never pass through LDS.
 // grid = (2 directions, requests), 512 threads.  LDS: [16][512] uint4 of weights, h as halves [2 buffers][256].
@@ -240,26 +241,27 @@ __global__ __launch_bounds__(ENC_DOT_THREADS) void k_enc_lstm_dot(const uint4* _
     constexpr int KB = Frag<XT>::KB, NK = ENC_HID / KB, KREG = 6, KLDS = NK - KREG;
     static_assert(KB == 32 && NK == 8 && 2 * KLDS * 4 == 16, "k = 32 kf + 8 q + e: a lane's 16 bytes are 8 consecutive k");
     extern __shared__ uint4 lds_enc[];
-    uint4* wl = lds_enc;                                                        // [(gate * KLDS + kl) * 4 + q][thread]
+    uint4* wl = lds_enc;                                                        // [(gate * KLDS + kl) * 2 + p][thread]
     uint16_t* hs = reinterpret_cast<uint16_t*>(lds_enc + ENC_DOT_W_VECS);       // [buffer][unit]
     const int tid = threadIdx.x, dir = blockIdx.x, req = blockIdx.y, unit = tid >> 1, half = tid & 1;
     const int len = w.len[req], col0 = w.col0[req];
     const uint4* Whh = dir ? Whh1 : Whh0;
-    // gate row 4 u + g lies in row tile u / 4 at row 4 (u % 4) + g; its k = 32 kf + 8 q .. + 7 in lane row + 16 q
-    const int rt = unit >> 2, r0 = 4 * (unit & 3) + 2 * half;
-    uint4 wr[2][KREG][4];
+    // gate row 4 u + g lies in row tile u / 4 at row 4 (u % 4) + g; its k = 32 kf + 8 q .. + 7 in lane row + 16 q;
+    // this thread's pieces are q = half and half + 2
+    const int rt = unit >> 2, r0 = 4 * (unit & 3);
+    uint4 wr[4][KREG][2];
 #pragma unroll
-    for (int g = 0; g < 2; ++g)
+    for (int g = 0; g < 4; ++g)
 #pragma unroll
         for (int kf = 0; kf < KREG; ++kf)
 #pragma unroll
-            for (int q = 0; q < 4; ++q) wr[g][kf][q] = Whh[xfrag(NK, rt, kf, r0 + g + 16 * q)];
+            for (int p = 0; p < 2; ++p) wr[g][kf][p] = Whh[xfrag(NK, rt, kf, r0 + g + 16 * (half + 2 * p))];
 #pragma unroll
-    for (int g = 0; g < 2; ++g)
+    for (int g = 0; g < 4; ++g)
 #pragma unroll
         for (int kl = 0; kl < KLDS; ++kl)
 #pragma unroll
-            for (int q = 0; q < 4; ++q) wl[((g * KLDS + kl) * 4 + q) * ENC_DOT_THREADS + tid] = Whh[xfrag(NK, rt, KREG + kl, r0 + g + 16 * q)];
+            for (int p = 0; p < 2; ++p) wl[((g * KLDS + kl) * 2 + p) * ENC_DOT_THREADS + tid] = Whh[xfrag(NK, rt, KREG + kl, r0 + g + 16 * (half + 2 * p))];
     hs[tid] = 0;                                                                // h = 0, both buffers
 
     auto token = [&](int s) { return dir ? len - 1 - s : s; };
@@ -272,29 +274,38 @@ __global__ __launch_bounds__(ENC_DOT_THREADS) void k_enc_lstm_dot(const uint4* _
         const uint4* hr = reinterpret_cast<const uint4*>(hs + (s & 1) * ENC_HID);               // 32 pieces of 8 halves
         uint16_t* hx = hs + ((s + 1) & 1) * ENC_HID;
         asm volatile("" ::: "memory");                    // (the LDS-resident weights are read again every step, not kept in registers)
-        // two chains per gate sum (even and odd pieces of k), added at the end
-        float acc[2][2] = {{0.f, 0.f}, {0.f, 0.f}};
+        // one chain per gate over this thread's half of k, a piece of eight k at a time; the next piece's LDS words (h, and
+        // the weights that live there) are requested before the current piece's products, and no further ahead: few live
+        float acc[4] = {0.f, 0.f, 0.f, 0.f};
+        uint4 hv = hr[half], wv[4];
 #pragma unroll
-        for (int kf = 0; kf < NK; ++kf) {
+        for (int i = 0; i < 2 * NK; ++i) {
+            const int kf = i >> 1, p = i & 1;
+            uint4 hn = hv, wn[4];
+            if (i + 1 < 2 * NK) {
+                const int kn = (i + 1) >> 1, pn = (i + 1) & 1;
+                hn = hr[kn * 4 + half + 2 * pn];
+                if (kn >= KREG) {
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const uint4 hv = hr[kf * 4 + q];
-#pragma unroll
-                for (int g = 0; g < 2; ++g) {
-                    const uint4 wv = kf < KREG ? wr[g][kf < KREG ? kf : 0][q]
-                                               : wl[((g * KLDS + (kf >= KREG ? kf - KREG : 0)) * 4 + q) * ENC_DOT_THREADS + tid];
-                    acc[g][q & 1] = dot8(wv, hv, acc[g][q & 1]);
+                    for (int g = 0; g < 4; ++g) wn[g] = wl[((g * KLDS + (kn >= KREG ? kn - KREG : 0)) * 2 + pn) * ENC_DOT_THREADS + tid];
                 }
             }
-            // a fragment of k at a time: few LDS words live at once
+#pragma unroll
+            for (int g = 0; g < 4; ++g) acc[g] = dot8(kf < KREG ? wr[g][kf < KREG ? kf : 0][p] : wv[g], hv, acc[g]);
+            hv = hn;
+            if (i + 1 < 2 * NK && ((i + 1) >> 1) >= KREG) {
+#pragma unroll
+                for (int g = 0; g < 4; ++g) wv[g] = wn[g];
+            }
             asm volatile("" ::: "memory");
             __builtin_amdgcn_sched_barrier(0);
         }
-        // the pair swaps its sums: both threads hold all four gates
-        const float m0 = acc[0][0] + acc[0][1], m1 = acc[1][0] + acc[1][1];
-        const float o0 = __shfl_xor(m0, 1, 64), o1 = __shfl_xor(m1, 1, 64);
+        // the pair adds its halves: both threads hold all four gate sums, bit for bit the same
         const int t = token(s);
-        const floatx4 gs = (half ? floatx4{o0, o1, m0, m1} : floatx4{m0, m1, o0, o1}) + xnext;
+        floatx4 gs;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) gs[g] = acc[g] + __shfl_xor(acc[g], 1, 64);
+        gs += xnext;
         const float gi = sigmoidf_(gs[0]), gf = sigmoidf_(gs[1]), gg = tanhf_(gs[2]), go = sigmoidf_(gs[3]);
         c = gf * c + gi * gg;
         const float h = go * tanhf_(c);
