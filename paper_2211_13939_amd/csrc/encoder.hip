@@ -211,7 +211,8 @@ __global__ __launch_bounds__(256) void k_enc_lstm(const uint4* __restrict__ Whh0
 // ENC_MAX_BATCH = 256 requests, so at most two workgroups per CU's worth of the chip, and the usual call at join time
 // has one).  A request's steps are a chain, and a chain is as fast alone on a CU as it gets: sixteen requests side by
 // side as the columns of one workgroup's MFMAs take 6 us per step, sixteen workgroups 1.9 us.  Every workgroup reads
-// the direction's 512 KB of W_hh once, from L2 after the first.  A request's result does not depend on its companions.
+// the direction's 512 KB of W_hh once, from L2 after the first.  The recurrence of a request does not depend on its
+// companions in the call.
 // 512 threads: a pair of threads is one hidden unit, each holding one half of k of the unit's four gate rows - the even
 // one the even pieces of eight consecutive k, the odd one the odd pieces - (512 halves a thread: 192 registers' worth and
 // 64 LDS words, the same split of k as above, straight from the fragment-ordered matrix; at two waves per SIMD a lane has

@@ -69,10 +69,10 @@ def test_more_requests_than_mfma_columns_and_long_request():
 
 @pytest.mark.parametrize("bf16", [True, False])
 def test_result_does_not_depend_on_batch_composition(bf16):
-    """Bitwise.  In the two-byte mode every request has workgroups of its own in the recurrence, so a request's F_enc is
-    the same whatever the call holds beside it.  With fp32 weights it holds among calls that take the same recurrence
-    kernel (calls of up to two requests compact the cell update, larger calls do not; the two differ in summation order
-    only)."""
+    """Bitwise, among calls that take the same kernels (the convolutions have one kernel for calls below 24 column tiles
+    of tokens - all calls here - and one for larger calls, which differ in summation order only).  In the two-byte mode
+    every request has workgroups of its own in the recurrence; with fp32 weights calls of up to two requests compact the
+    cell update and larger calls do not, again a difference in summation order."""
     w = synth.make_encoder_weights(bf16=bf16)
     ids = [synth.encoder_ids(L, 300 + i) for i, L in enumerate((40, 9, 23, 61, 5, 33))]
     enc = binding.Encoder(binding.make_encoder_config(max_tokens=512, max_len=100, bf16=bf16), w)
@@ -215,3 +215,26 @@ def test_largest_batch_and_a_very_long_request():
     with pytest.raises(binding.TtsError):
         enc.run(ids + [ids[0]])                # 257 requests
     enc.close()
+
+
+def test_largest_batch_bf16():
+    """256 requests in one call in the two-byte mode: 512 workgroups of the recurrence, two per CU's worth of the chip."""
+    from oracle import oracle as orc
+    w = synth.make_encoder_weights(bf16=True)
+    W = orc.EncoderWeights(w)
+    rng = np.random.default_rng(31)
+    lens = [int(x) for x in rng.integers(1, 40, size=256)]
+    ids = [synth.encoder_ids(L, 1200 + i) for i, L in enumerate(lens)]
+    enc = binding.Encoder(binding.make_encoder_config(max_tokens=256 * 40, max_len=64, bf16=True), w)
+    say(f"case encoder largest batch, bf16: 256 requests, {sum(lens)} tokens")
+    got = enc.run(ids)
+    worst = 0.0
+    for k in (0, 1, 127, 128, 200, 255):
+        assert got[k].shape == (lens[k], 512)
+        worst = max(worst, float(np.abs(got[k] - orc.encoder(W, ids[k])).max()))
+    say(f"  max abs err {worst:.3e}, {enc.elapsed_ms() * 1e3:.0f} us")
+    assert worst <= TOL_BF16
+    # bit for bit what a smaller call gives that takes the same convolution kernel (from 24 column tiles up)
+    np.testing.assert_array_equal(got[200], enc.run(ids[150:])[50])
+    enc.close()
+
