@@ -224,10 +224,11 @@ template <typename XT, int C, int KS, int TP> struct VrGeom {
 
 // Positions per workgroup of the fused kernel.  Up to 32 channels the region's accumulators (x and one convolution's
 // output) and the operand buffer are small enough for two workgroups to share a CU: while one is in a convolution
-// (MFMA) the other can be preparing an operand (VALU).  Small batches take half of that: more workgroups, each with
-// a shorter chain.
-template <int C, bool SMALL> constexpr int vr_tp() { return (C >= 32 ? 256 : 512) / (SMALL ? 2 : 1); }
-constexpr int VR_SMALL_BELOW = 1024;             // workgroups of the large tiling below which the small one is used
+// (MFMA) the other can be preparing an operand (VALU).  Small batches take half of that, a request or two a quarter:
+// more workgroups, each with a shorter chain (and a larger share of halo: the sum of their work grows).
+template <int C, int LEVEL> constexpr int vr_tp() { return (C >= 32 ? 256 : 512) >> LEVEL; }
+constexpr int VR_SMALL_BELOW = 1024;             // workgroups of the large tiling below which the half tiles are used
+constexpr int VR_TINY_BELOW = 128;               // ... and the quarter tiles
 
 // acc[rt][ct] += W (rows rt, all k) * operand(columns of tile ct shifted by the taps)
 template <typename XT, int C, int KS, int NCOL, int PADR>
@@ -426,21 +427,29 @@ __global__ __launch_bounds__(VOC_HOP) void k_voc_fade(VocBatch b, const float* _
     if (i < emit) d_audio[(size_t)b.out_off[w] + i] = v;
 }
 
-// grid = (tiles of a window, windows, row groups).  SHORT: the layer runs at one position per frame, where a window
-// is a few dozen positions long.
+// grid = (tiles of a window, windows, row groups).  SHORT: tiles of 64 positions - for the layer that runs at one position
+// per frame, where a window is a few dozen positions long, and for every layer of a batch so small that the large tiles
+// would leave most of the chip idle (an output's sum does not depend on the tile it falls in).
+constexpr int VC_SHORT_BELOW = 512;              // workgroups of the large tiling below which the short one is used
 template <typename XT, int CIN, int ROWS, int COUT, int KS, int EPI, bool PRE_ACT, bool SRC3, int U, bool SHORT>
 void conv_launch(const VcArgs& a, const int* len, int rate, int window, int n_windows, hipStream_t s)
 {
     constexpr int TP = vc_tp<XT, CIN, ROWS, (KS - 1) / 2, SHORT>();
     constexpr int RT = ROWS / 16, RG = RT < 4 ? RT : 4;
     const dim3 grid((window * rate + TP - 1) / TP, n_windows, RT / RG);
+    if constexpr (!SHORT) {
+        if ((long)grid.x * grid.y * grid.z < VC_SHORT_BELOW) {
+            conv_launch<XT, CIN, ROWS, COUT, KS, EPI, PRE_ACT, SRC3, U, true>(a, len, rate, window, n_windows, s);
+            return;
+        }
+    }
     hipLaunchKernelGGL((k_vconv<XT, CIN, ROWS, COUT, KS, EPI, PRE_ACT, SRC3, U, SHORT>), grid, dim3(VC_THREADS), 0, s, a, len, rate, window);
 }
 
-template <typename XT, int C, bool SMALL>
+template <typename XT, int C, int LEVEL>
 hipError_t blocks_launch_tp(const VrArgs3& a, const int* len, int rate, int window, int n_windows, hipStream_t s)
 {
-    constexpr int TP = vr_tp<C, SMALL>();
+    constexpr int TP = vr_tp<C, LEVEL>();
     constexpr int L3 = VrGeom<XT, C, 3, TP>::BYTES, L7 = VrGeom<XT, C, 7, TP>::BYTES, L11 = VrGeom<XT, C, 11, TP>::BYTES;
     constexpr int LDS = L3 > L7 ? (L3 > L11 ? L3 : L11) : (L7 > L11 ? L7 : L11);      // the three kernels share a launch
     auto kern = k_vres<XT, C, TP>;
@@ -458,9 +467,10 @@ hipError_t blocks_launch_tp(const VrArgs3& a, const int* len, int rate, int wind
 template <typename XT, int C>
 hipError_t blocks_launch(const VrArgs3& a, const int* len, int rate, int window, int n_windows, hipStream_t s)
 {
-    const long wgs = (long)((window * rate + vr_tp<C, false>() - 1) / vr_tp<C, false>()) * n_windows * VOC_BLOCKS;
-    return wgs < VR_SMALL_BELOW ? blocks_launch_tp<XT, C, true>(a, len, rate, window, n_windows, s)
-                                : blocks_launch_tp<XT, C, false>(a, len, rate, window, n_windows, s);
+    const long wgs = (long)((window * rate + vr_tp<C, 0>() - 1) / vr_tp<C, 0>()) * n_windows * VOC_BLOCKS;
+    return wgs < VR_TINY_BELOW    ? blocks_launch_tp<XT, C, 2>(a, len, rate, window, n_windows, s)
+           : wgs < VR_SMALL_BELOW ? blocks_launch_tp<XT, C, 1>(a, len, rate, window, n_windows, s)
+                                  : blocks_launch_tp<XT, C, 0>(a, len, rate, window, n_windows, s);
 }
 
 template <typename XT, int S>
