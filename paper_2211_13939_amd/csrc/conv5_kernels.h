@@ -231,6 +231,9 @@ template <typename XT, int CIN, int COUT, int EPI>
 inline hipError_t conv_layer(bool wide, const void* W, const float* b, const void* xin, XT* xout, const int* cmeta, int n_ctiles,
                              const float* mel, int n_mel, const int* orow, float* out, hipStream_t s)
 {
+    // fewer row tiles than a wide workgroup has waves (the PostNet's last layer, 512 -> 80): the wide kernel would run on a
+    // few dozen workgroups with idle waves; the narrow one spreads the layer over the chip whatever the batch
+    if (COUT / 16 < PN_WAVES) wide = false;
     if (wide) {
         constexpr int LDS = (PN_WCT * 16 + 2 * PN_HALO) * (CIN * (int)sizeof(XT) + 16);
         auto kern = k_pn_conv_wide<XT, CIN, COUT, EPI>;
