@@ -6,12 +6,11 @@
 //                 k_enc_lstm_dot: two-byte weights, one workgroup per direction and request
 //
 // The recurrence is a chain of L dependent steps of a 1024 x 256 matrix-vector product: latency, not bandwidth.
-// In bf16 the matrix of one direction (512 KB) is made resident in ONE compute unit -- six of its eight k fragments
-// in the registers of the workgroup's four waves (384 of the 512 registers a lane may have at one wave per SIMD),
-// the other two in 128 KB of LDS -- so a step touches no memory beyond the precomputed input projections of the
-// requests in flight.  The hidden state goes round through 8 KB of LDS in B-fragment order; the 16 MFMA columns are
-// 16 requests.  Gate rows are stored unit-major / gate-minor, so the four gate sums of a unit are contiguous.
-// (fp32 matrices do not fit a compute unit: they stream from L2 every step.)
+// With two-byte weights the matrix of one direction (512 KB) is resident in ONE compute unit per request -- registers
+// and LDS of k_enc_lstm_dot's workgroup -- so a step touches no memory beyond the request's precomputed input projection.
+// fp32 matrices (1 MB) do not fit a compute unit: they stream from L2 every step through MFMAs whose 16 columns are 16
+// requests, the hidden state going round through LDS in B-fragment order.  Gate rows are stored unit-major / gate-minor,
+// so the four gate sums of a unit are contiguous.
 #include "encoder_kernels.h"
 
 #include "conv5_kernels.h"
@@ -58,18 +57,15 @@ __global__ __launch_bounds__(256) void k_enc_xproj(const uint4* __restrict__ W0,
 
 template <typename XT> struct EncLstmGeom {
     static constexpr int KB = Frag<XT>::KB, EPL = Frag<XT>::EPL;
-    static constexpr int NK = ENC_HID / KB;                       // k fragments of W_hh
-    static constexpr int KREG = sizeof(XT) == 2 ? 6 : 0;          // ... held in registers
-    static constexpr int KLDS = sizeof(XT) == 2 ? 2 : 0;          // ... held in LDS; the rest streams from L2
+    static constexpr int NK = ENC_HID / KB;                       // k fragments of W_hh (it streams from L2 every step)
     static constexpr int ROW_TILES = ENC_GATES / 16;              // 64
     static constexpr int TILES_PER_WAVE = ROW_TILES / 4;          // 16: a wave owns 64 units
     static constexpr int GCOLS = 2;                               // requests whose gate sums pass through LDS: the most a call may have
     static_assert(GCOLS >= ENC_COMPACT_UP_TO, "the compacting kernel serves calls of up to ENC_COMPACT_UP_TO requests");
-    static constexpr int W_VECS = KLDS * ROW_TILES * 64;
     static constexpr int H_VECS = NK * 64;                        // h of the 16 requests, B-fragment order
     static constexpr int C_VECS = ENC_HID * 16 / 4;               // the cell state of 256 units x 16 requests, fp32
     static constexpr int G_VECS = GCOLS * ENC_GATES / 4;          // W_hh h of GCOLS requests, fp32
-    static constexpr int LDS_BYTES = (W_VECS + H_VECS + C_VECS + G_VECS) * 16;
+    static constexpr int LDS_BYTES = (H_VECS + C_VECS + G_VECS) * 16;
 };
 
 // grid = (2 directions, 1), 256 threads; for calls of at most GCOLS requests.
@@ -84,10 +80,9 @@ __global__ __launch_bounds__(256) void k_enc_lstm(const uint4* __restrict__ Whh0
                                                   const float* __restrict__ xproj, PnWindows w, int max_tokens, float* __restrict__ out)
 {
     using G = EncLstmGeom<XT>;
-    constexpr int NK = G::NK, KREG = G::KREG, KLDS = G::KLDS, TPW = G::TILES_PER_WAVE, GCOLS = G::GCOLS;
+    constexpr int NK = G::NK, TPW = G::TILES_PER_WAVE, GCOLS = G::GCOLS;
     extern __shared__ uint4 lds_enc[];
-    uint4* wl = lds_enc;                                          // [KLDS][64 row tiles][64 lanes]
-    uint4* hb = lds_enc + G::W_VECS;                              // [NK][64 lanes]
+    uint4* hb = lds_enc;                                          // [NK][64 lanes]
     float* cl = reinterpret_cast<float*>(hb + G::H_VECS);         // [unit][request]
     float* gl = cl + ENC_HID * 16;                                // [GCOLS][gate row]
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n = lane & 15, g = lane >> 4;
@@ -105,17 +100,6 @@ __global__ __launch_bounds__(256) void k_enc_lstm(const uint4* __restrict__ Whh0
     }
     const uint4* Whh = dir ? Whh1 : Whh0;
 
-    uint4 wreg[TPW][KREG > 0 ? KREG : 1];
-    if constexpr (KREG > 0) {
-#pragma unroll
-        for (int i = 0; i < TPW; ++i)
-#pragma unroll
-            for (int kf = 0; kf < KREG; ++kf) wreg[i][kf] = Whh[xfrag(NK, TPW * wave + i, kf, lane)];
-    }
-    for (int idx = tid; idx < G::W_VECS; idx += 256) {
-        const int kl = idx / (G::ROW_TILES * 64), rem = idx - kl * (G::ROW_TILES * 64);
-        wl[idx] = Whh[xfrag(NK, rem >> 6, KREG + kl, rem & 63)];
-    }
     for (int idx = tid; idx < G::H_VECS + G::C_VECS; idx += 256) hb[idx] = make_uint4(0, 0, 0, 0);    // h = 0, c = 0
 
     // token of request j at step s: forwards from 0, backwards from the request's own last token
@@ -131,59 +115,22 @@ __global__ __launch_bounds__(256) void k_enc_lstm(const uint4* __restrict__ Whh0
     }
     __syncthreads();
 
-    // One step.  The row tiles are taken two at a time with all of h's fragments held in registers: while the pair's
-    // sixteen MFMAs run, the LDS-resident weight fragments of the next pair are on their way, and a finished pair's
-    // sums leave for the gate buffer at once, so only two tiles of accumulators are ever live.
     for (int s = 0; s < lmax; ++s) {
-        // ---- (1) W_hh h, (2) the sums of this call's (at most GCOLS) requests into LDS
+        // ---- (1) W_hh h: the matrix streams from L2, one k fragment of the wave's row tiles at a time;
+        //      (2) the sums of this call's (at most GCOLS) requests into LDS
         float* dst = gl + (n % GCOLS) * ENC_GATES + (TPW * wave) * 16 + 4 * g;
-        if constexpr (KREG + KLDS == NK) {
-            uint4 bv[NK];
+        floatx4 acc[TPW];
 #pragma unroll
-            for (int kf = 0; kf < NK; ++kf) bv[kf] = hb[kf * 64 + lane];
-            const uint4* wk = wl + (TPW * wave) * 64 + lane;           // [KLDS][row tile][lane], this wave's tiles
-            uint4 an[2][KLDS > 0 ? KLDS : 1];
-#pragma unroll
-            for (int e = 0; e < 2; ++e)
-#pragma unroll
-                for (int kl = 0; kl < KLDS; ++kl) an[e][kl] = wk[(kl * G::ROW_TILES + e) * 64];
-#pragma unroll
-            for (int i = 0; i < TPW; i += 2) {
-                uint4 ac[2][KLDS > 0 ? KLDS : 1];
-#pragma unroll
-                for (int e = 0; e < 2; ++e)
-#pragma unroll
-                    for (int kl = 0; kl < KLDS; ++kl) {
-                        ac[e][kl] = an[e][kl];
-                        if (i + 2 < TPW) an[e][kl] = wk[(kl * G::ROW_TILES + i + 2 + e) * 64];
-                    }
-                __builtin_amdgcn_sched_barrier(0);
-                floatx4 a0 = {0.f, 0.f, 0.f, 0.f}, a1 = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int kf = 0; kf < NK; ++kf) {
-                    a0 = mfma_frag<XT>(kf < KREG ? wreg[i][kf < KREG ? kf : 0] : ac[0][kf >= KREG ? kf - KREG : 0], bv[kf], a0);
-                    a1 = mfma_frag<XT>(kf < KREG ? wreg[i + 1][kf < KREG ? kf : 0] : ac[1][kf >= KREG ? kf - KREG : 0], bv[kf], a1);
-                }
-                if (n < GCOLS) {
-                    *reinterpret_cast<floatx4*>(dst + i * 16) = a0;
-                    *reinterpret_cast<floatx4*>(dst + (i + 1) * 16) = a1;
-                }
-            }
-        } else {
-            // nothing resident: the matrix streams from L2, one k fragment of the wave's row tiles at a time
-            floatx4 acc[TPW];
-#pragma unroll
-            for (int i = 0; i < TPW; ++i) acc[i] = floatx4{0.f, 0.f, 0.f, 0.f};
+        for (int i = 0; i < TPW; ++i) acc[i] = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll 1
-            for (int kf = 0; kf < NK; ++kf) {
-                const uint4 bv = hb[kf * 64 + lane];
+        for (int kf = 0; kf < NK; ++kf) {
+            const uint4 bv = hb[kf * 64 + lane];
 #pragma unroll
-                for (int i = 0; i < TPW; ++i) acc[i] = mfma_frag<XT>(Whh[xfrag(NK, TPW * wave + i, kf, lane)], bv, acc[i]);
-            }
-            if (n < GCOLS) {
+            for (int i = 0; i < TPW; ++i) acc[i] = mfma_frag<XT>(Whh[xfrag(NK, TPW * wave + i, kf, lane)], bv, acc[i]);
+        }
+        if (n < GCOLS) {
 #pragma unroll
-                for (int i = 0; i < TPW; ++i) *reinterpret_cast<floatx4*>(dst + i * 16) = acc[i];
-            }
+            for (int i = 0; i < TPW; ++i) *reinterpret_cast<floatx4*>(dst + i * 16) = acc[i];
         }
         __syncthreads();                                   // the sums are in LDS and every wave has read h
         // ---- (3) thread = hidden unit
@@ -322,15 +269,12 @@ __global__ __launch_bounds__(ENC_DOT_THREADS) void k_enc_lstm_dot(const uint4* _
 
 template <typename XT> struct EncLstmWideGeom {
     static constexpr int KB = Frag<XT>::KB, EPL = Frag<XT>::EPL;
-    static constexpr int NK = ENC_HID / KB;                       // k fragments of W_hh
-    static constexpr int KREG = sizeof(XT) == 2 ? 6 : 0;          // ... held in registers
-    static constexpr int KLDS = sizeof(XT) == 2 ? 2 : 0;          // ... held in LDS; the rest streams from L2
+    static constexpr int NK = ENC_HID / KB;                       // k fragments of W_hh (it streams from L2 every step)
     static constexpr int ROW_TILES = ENC_GATES / 16;              // 64
     static constexpr int TILES_PER_WAVE = ROW_TILES / 4;          // 16: a wave owns 64 units
-    static constexpr int W_VECS = KLDS * ROW_TILES * 64;
     static constexpr int H_VECS = NK * 64;                        // one copy of h; there are two (read one, write the other)
     static constexpr int C_VECS = ENC_HID * 16 / 4;              // the cell state of 256 units x 16 requests, fp32
-    static constexpr int LDS_BYTES = (W_VECS + 2 * H_VECS + C_VECS) * 16;
+    static constexpr int LDS_BYTES = (2 * H_VECS + C_VECS) * 16;
 };
 
 // The recurrence for well-filled groups (more than ENC_COMPACT_UP_TO requests in the call): the cell update runs where
@@ -342,10 +286,9 @@ __global__ __launch_bounds__(256) void k_enc_lstm_wide(const uint4* __restrict__
                                                   const float* __restrict__ xproj, PnWindows w, int max_tokens, float* __restrict__ out)
 {
     using G = EncLstmWideGeom<XT>;
-    constexpr int NK = G::NK, KREG = G::KREG, KLDS = G::KLDS, TPW = G::TILES_PER_WAVE;
+    constexpr int NK = G::NK, TPW = G::TILES_PER_WAVE;
     extern __shared__ uint4 lds_enc[];
-    uint4* wl = lds_enc;                     // [KLDS][64 row tiles][64 lanes]
-    uint4* hb = lds_enc + G::W_VECS;         // h of the 16 requests, B-fragment order, [NK][64 lanes]
+    uint4* hb = lds_enc;                     // h of the 16 requests, B-fragment order, [NK][64 lanes]
     float* cl = reinterpret_cast<float*>(hb + 2 * G::H_VECS); // cell state [unit][request]: only its owner lane touches an entry
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n = lane & 15, g = lane >> 4;
     const int dir = blockIdx.x, req = blockIdx.y * 16 + n;
@@ -356,17 +299,6 @@ __global__ __launch_bounds__(256) void k_enc_lstm_wide(const uint4* __restrict__
     for (int o = 1; o < 16; o <<= 1) lmax = max(lmax, __shfl_xor(lmax, o, 64));
     const uint4* Whh = dir ? Whh1 : Whh0;
 
-    uint4 wreg[TPW][KREG > 0 ? KREG : 1];
-    if constexpr (KREG > 0) {
-#pragma unroll
-        for (int i = 0; i < TPW; ++i)
-#pragma unroll
-            for (int kf = 0; kf < KREG; ++kf) wreg[i][kf] = Whh[xfrag(NK, TPW * wave + i, kf, lane)];
-    }
-    for (int idx = tid; idx < G::W_VECS; idx += 256) {
-        const int kl = idx / (G::ROW_TILES * 64), rem = idx - kl * (G::ROW_TILES * 64);
-        wl[idx] = Whh[xfrag(NK, rem >> 6, KREG + kl, rem & 63)];
-    }
     for (int idx = tid; idx < 2 * G::H_VECS; idx += 256) hb[idx] = make_uint4(0, 0, 0, 0);
 
     // token of this lane's request at step s: forwards from 0, backwards from its own last token; clamped so that
@@ -393,26 +325,13 @@ __global__ __launch_bounds__(256) void k_enc_lstm_wide(const uint4* __restrict__
         const int tn = token(s + 1);
 #pragma unroll
         for (int half = 0; half < 2; ++half) {
-            if constexpr (KREG + KLDS == NK) {
-#pragma unroll
-                for (int kf = 0; kf < NK; ++kf) {
-                    const uint4 bv = hr[kf * 64 + lane];
-#pragma unroll
-                    for (int j = 0; j < HALF; ++j) {
-                        const int i = half * HALF + j;
-                        const uint4 av = kf < KREG ? wreg[i][kf < KREG ? kf : 0] : wl[((kf - KREG) * G::ROW_TILES + TPW * wave + i) * 64 + lane];
-                        acc[i] = mfma_frag<XT>(av, bv, acc[i]);
-                    }
-                }
-            } else {
-                // nothing resident: the matrix streams from L2, one k fragment of the half's row tiles at a time
+            // the matrix streams from L2, one k fragment of the half's row tiles at a time
 #pragma unroll 1
-                for (int kf = 0; kf < NK; ++kf) {
-                    const uint4 bv = hr[kf * 64 + lane];
+            for (int kf = 0; kf < NK; ++kf) {
+                const uint4 bv = hr[kf * 64 + lane];
 #pragma unroll
-                    for (int j = 0; j < HALF; ++j)
-                        acc[half * HALF + j] = mfma_frag<XT>(Whh[xfrag(NK, TPW * wave + half * HALF + j, kf, lane)], bv, acc[half * HALF + j]);
-                }
+                for (int j = 0; j < HALF; ++j)
+                    acc[half * HALF + j] = mfma_frag<XT>(Whh[xfrag(NK, TPW * wave + half * HALF + j, kf, lane)], bv, acc[half * HALF + j]);
             }
 #pragma unroll
             for (int j = 0; j < HALF; ++j) {
