@@ -236,6 +236,11 @@ def test_full_size_batch_in_the_benchmarked_launch_shape(bf16):
     say(f"  max abs err {worst:.3e} on four sampled requests, {voc.elapsed_ms() * 1e3:.0f} us for the second round")
     assert worst <= (TOL_BF16 if bf16 else TOL_F32)
     voc.close()
+    # the same request alone takes the smallest tiles of every kernel: an output's sum does not depend on the tile it falls in
+    solo = binding.Vocoder(binding.make_vocoder_config(overlap=ov, max_chunk=chunk, max_requests=1, max_batch=1, bf16=bf16), w)
+    np.testing.assert_array_equal(solo.run([first[17]], [0], [FIRST])[0], r1[17])
+    np.testing.assert_array_equal(solo.run([second[17]], [0], [0])[0], r2[17])
+    solo.close()
 
 
 def test_largest_batch_of_short_chunks():
