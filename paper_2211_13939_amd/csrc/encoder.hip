@@ -186,10 +186,10 @@ __global__ __launch_bounds__(ENC_DOT_THREADS) void k_enc_lstm_dot(const uint4* _
                                                                   const float* __restrict__ xproj, PnWindows w, int max_tokens, float* __restrict__ out)
 {
     typedef h16_t XT;
-    constexpr int KB = Frag<XT>::KB, NK = ENC_HID / KB, KREG = 6, KLDS = NK - KREG;
-    static_assert(KB == 32 && NK == 8 && 2 * KLDS * 4 == 16, "k = 32 kf + 8 q + e: a lane's 16 bytes are 8 consecutive k");
+    constexpr int KB = Frag<XT>::KB, NK = ENC_HID / KB;
+    static_assert(KB == 32 && NK == 8, "k = 32 kf + 8 q + e: a lane's 16 bytes are 8 consecutive k");
     extern __shared__ uint4 lds_enc[];
-    uint4* wl = lds_enc;                                                        // [(gate * KLDS + kl) * 2 + p][thread]
+    uint4* wl = lds_enc;                                                        // [gate * 4 + piece / 4][thread]
     uint16_t* hs = reinterpret_cast<uint16_t*>(lds_enc + ENC_DOT_W_VECS);       // [buffer][unit]
     const int tid = threadIdx.x, dir = blockIdx.x, req = blockIdx.y, unit = tid >> 1, half = tid & 1;
     const int len = w.len[req], col0 = w.col0[req];
@@ -197,19 +197,19 @@ __global__ __launch_bounds__(ENC_DOT_THREADS) void k_enc_lstm_dot(const uint4* _
     // gate row 4 u + g lies in row tile u / 4 at row 4 (u % 4) + g; its k = 32 kf + 8 q .. + 7 in lane row + 16 q;
     // this thread's pieces are q = half and half + 2
     const int rt = unit >> 2, r0 = 4 * (unit & 3);
-    uint4 wr[4][KREG][2];
+    // of its 16 pieces (piece i: kf = i / 2, q = half + 2 (i % 2)) every fourth lives in LDS, the others in registers: the
+    // LDS reads are spread evenly over a step
+    constexpr int NP = 2 * NK, NP_LDS = NP / 4, NP_REG = NP - NP_LDS;
+    static_assert(NP_LDS * 4 * ENC_DOT_THREADS == ENC_DOT_W_VECS, "the LDS share of the weights");
+    uint4 wr[4][NP_REG];
 #pragma unroll
     for (int g = 0; g < 4; ++g)
 #pragma unroll
-        for (int kf = 0; kf < KREG; ++kf)
-#pragma unroll
-            for (int p = 0; p < 2; ++p) wr[g][kf][p] = Whh[xfrag(NK, rt, kf, r0 + g + 16 * (half + 2 * p))];
-#pragma unroll
-    for (int g = 0; g < 4; ++g)
-#pragma unroll
-        for (int kl = 0; kl < KLDS; ++kl)
-#pragma unroll
-            for (int p = 0; p < 2; ++p) wl[((g * KLDS + kl) * 2 + p) * ENC_DOT_THREADS + tid] = Whh[xfrag(NK, rt, KREG + kl, r0 + g + 16 * (half + 2 * p))];
+        for (int i = 0; i < NP; ++i) {
+            const uint4 v = Whh[xfrag(NK, rt, i >> 1, r0 + g + 16 * (half + 2 * (i & 1)))];
+            if ((i & 3) == 3) wl[(g * NP_LDS + (i >> 2)) * ENC_DOT_THREADS + tid] = v;
+            else wr[g][i - (i >> 2)] = v;
+        }
     hs[tid] = 0;                                                                // h = 0, both buffers
 
     auto token = [&](int s) { return dir ? len - 1 - s : s; };
@@ -227,21 +227,19 @@ __global__ __launch_bounds__(ENC_DOT_THREADS) void k_enc_lstm_dot(const uint4* _
         float acc[4] = {0.f, 0.f, 0.f, 0.f};
         uint4 hv = hr[half], wv[4];
 #pragma unroll
-        for (int i = 0; i < 2 * NK; ++i) {
-            const int kf = i >> 1, p = i & 1;
+        for (int i = 0; i < NP; ++i) {
             uint4 hn = hv, wn[4];
-            if (i + 1 < 2 * NK) {
-                const int kn = (i + 1) >> 1, pn = (i + 1) & 1;
-                hn = hr[kn * 4 + half + 2 * pn];
-                if (kn >= KREG) {
+            if (i + 1 < NP) {
+                hn = hr[((i + 1) >> 1) * 4 + half + 2 * ((i + 1) & 1)];
+                if (((i + 1) & 3) == 3) {
 #pragma unroll
-                    for (int g = 0; g < 4; ++g) wn[g] = wl[((g * KLDS + (kn >= KREG ? kn - KREG : 0)) * 2 + pn) * ENC_DOT_THREADS + tid];
+                    for (int g = 0; g < 4; ++g) wn[g] = wl[(g * NP_LDS + ((i + 1) >> 2)) * ENC_DOT_THREADS + tid];
                 }
             }
 #pragma unroll
-            for (int g = 0; g < 4; ++g) acc[g] = dot8(kf < KREG ? wr[g][kf < KREG ? kf : 0][p] : wv[g], hv, acc[g]);
+            for (int g = 0; g < 4; ++g) acc[g] = dot8((i & 3) == 3 ? wv[g] : wr[g][(i & 3) == 3 ? 0 : i - (i >> 2)], hv, acc[g]);
             hv = hn;
-            if (i + 1 < 2 * NK && ((i + 1) >> 1) >= KREG) {
+            if (i + 1 < NP && ((i + 1) & 3) == 3) {
 #pragma unroll
                 for (int g = 0; g < 4; ++g) wv[g] = wn[g];
             }
