@@ -255,7 +255,8 @@ inline hipError_t conv_layer(bool wide, const void* W, const float* b, const voi
     return hipGetLastError();
 }
 
-// batches of at least this many column tiles take the wide kernel
-constexpr int PN_WIDE_FROM = 24;
+// batches of at least this many column tiles take the wide kernel (measured with 50-column windows, two-byte mode: the narrow
+// kernel is the faster one up to 75 column tiles - 25 tiles 43 against 71 us per PostNet round -, the wide one from 100)
+constexpr int PN_WIDE_FROM = 80;
 
 }  // namespace tts

@@ -69,7 +69,7 @@ def test_more_requests_than_mfma_columns_and_long_request():
 
 @pytest.mark.parametrize("bf16", [True, False])
 def test_result_does_not_depend_on_batch_composition(bf16):
-    """Bitwise, among calls that take the same kernels (the convolutions have one kernel for calls below 24 column tiles
+    """Bitwise, among calls that take the same kernels (the convolutions have one kernel for calls below 80 column tiles
     of tokens - all calls here - and one for larger calls, which differ in summation order only).  In the two-byte mode
     every request has workgroups of its own in the recurrence; with fp32 weights calls of up to two requests compact the
     cell update and larger calls do not, again a difference in summation order."""
@@ -234,7 +234,7 @@ def test_largest_batch_bf16():
         worst = max(worst, float(np.abs(got[k] - orc.encoder(W, ids[k])).max()))
     say(f"  max abs err {worst:.3e}, {enc.elapsed_ms() * 1e3:.0f} us")
     assert worst <= TOL_BF16
-    # bit for bit what a smaller call gives that takes the same convolution kernel (from 24 column tiles up)
+    # bit for bit what a smaller call gives that takes the same convolution kernel (from 80 column tiles up)
     np.testing.assert_array_equal(got[200], enc.run(ids[150:])[50])
     enc.close()
 

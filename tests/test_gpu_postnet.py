@@ -68,19 +68,19 @@ def test_ragged_batch_of_chunks_matches_oracle(bf16):
 
 @pytest.mark.parametrize("bf16", [False, True])
 def test_large_batch_matches_oracle(bf16):
-    """A batch big enough for the large-batch kernel (27 column tiles): 8 windows of 50 frames (a 40-frame
+    """A batch big enough for the large-batch kernel (84 column tiles): 26 windows of 50 frames (a 40-frame
     chunk behind 10 frames of context) and one of 31.  A window is its own utterance as far as the oracle
     is concerned: the frames in front of it are zero."""
     from oracle import oracle as orc
     ws, bs = synth.make_postnet_weights(bf16=bf16)
     W = orc.PostnetWeights(ws, bs)
     rng = np.random.default_rng(77)
-    lens = [50] * 8 + [31]
-    keeps = [10] * 8 + [0]
+    lens = [50] * 26 + [31]
+    keeps = [10] * 26 + [0]
     wins = [rng.standard_normal((n, 80)).astype(np.float32) for n in lens]
     say(f"case postnet large batch: {sum(lens)} columns, {'bf16' if bf16 else 'fp32'}")
     ref = [orc.postnet_chunk(W, w.astype(np.float64), k) for w, k in zip(wins, keeps)]
-    pn = binding.Postnet(binding.make_postnet_config(max_columns=512, bf16=bf16), ws, bs)
+    pn = binding.Postnet(binding.make_postnet_config(max_columns=2048, bf16=bf16), ws, bs)
     got = pn.run(wins, keeps)
     pn.close()
     worst = max(float(np.abs(g - r).max()) for g, r in zip(got, ref))
@@ -157,7 +157,7 @@ def test_window_without_full_context_is_rejected_or_exact_at_start():
 
 def test_result_does_not_depend_on_batch_composition():
     """A chunk post-processed alone and in a batch of others: identical bits (every column only sees its own
-    window).  Holds among batches that take the same kernel (below 24 column tiles here)."""
+    window).  Holds among batches that take the same kernel (below 80 column tiles here)."""
     ws, bs = synth.make_postnet_weights(bf16=True)
     rng = np.random.default_rng(8)
     wins = [rng.standard_normal((n, 80)).astype(np.float32) for n in (26, 50, 11, 37, 18)]

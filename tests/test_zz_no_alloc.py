@@ -17,10 +17,10 @@ def test_static_scratch_call_equals_the_arena_call_twice_in_a_row(bf16):
     import torch
     ws, bs = synth.make_postnet_weights(bf16=bf16)
     rng = np.random.default_rng(77)
-    pn = binding.Postnet(binding.make_postnet_config(max_columns=1024, bf16=bf16), ws, bs)
+    pn = binding.Postnet(binding.make_postnet_config(max_columns=2048, bf16=bf16), ws, bs)
     dev = pn.device
-    # first a ragged batch that takes the wide kernels (more than 24 column tiles), then a small one (the narrow kernels)
-    for lens, keeps in (([50, 37, 1, 50, 64, 50, 50, 23, 50, 50, 50], [10, 10, 0, 10, 0, 10, 10, 3, 10, 10, 10]),
+    # first a ragged batch that takes the wide kernels (90 column tiles; from 80 up), then a small one (the narrow kernels)
+    for lens, keeps in (([50, 37, 1, 50, 64, 50, 50, 23, 50, 50, 50] * 3, [10, 10, 0, 10, 0, 10, 10, 3, 10, 10, 10] * 3),
                         ([26, 11, 5], [10, 0, 4])):
         mel = rng.standard_normal((sum(lens), 80)).astype(np.float32)
         n_out = sum(t - k for t, k in zip(lens, keeps))
